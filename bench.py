@@ -1,0 +1,171 @@
+#!/usr/bin/env python3
+"""Benchmark of the FLARE mixer on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--cfg 4] [--no-cpu-baseline]
+
+A step is one pass of the whole hot path -- flare_forward (encode partials, merge, decode)
+followed by flare_backward -- over one batch of the synthetic million-token mesh workload
+(B=1, H=8, d=16, N=1,000,000, M=256, bf16 storage, fp32 accumulation).  Inputs are resident in
+HBM before the timed region.  One JSON line is printed:
+  value        tokens/s of forward+backward (B*N tokens per step)
+  fwd          the same for the forward alone (its own timed loop of K steps)
+  roofline     the dominant kernel against the HBM roofline: algorithmic bytes per launch
+               divided by its mean duration, measured with HIP events on the launch stream
+  kernels      mean duration and algorithmic GB/s of every kernel of the step
+  cpu_baseline the fp64 CPU oracle timed on a bounded sample of the same workload
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
+
+# Rates of the softmax's exponentials on the vector ALUs (one v_exp_f32 per score and half):
+# 256 CUs x 4 SIMDs x 64 lanes / 8 cycles per wave instruction x 2.4 GHz.
+EXP_PEAK_GOPS = 256 * 4 * 64 / 8 * 2.4
+
+
+def algorithmic_bytes(kernel, B, H, N, M, d, elem):
+    """HBM bytes one launch of `kernel` must move: streamed token rows plus per-token statistics."""
+    row = d * elem
+    bhn = B * H * N
+    per_token = {
+        "encode_partial": 2 * row,              # k, v
+        "decode": 2 * row,                      # k in, y out
+        "bwd_token_stats": 2 * row + 8,         # k, dy in; lse_dec, delta out
+        "bwd_dz_partial": 2 * row + 4,          # k, dy, lse_dec in
+        "bwd_dq_partial": 3 * row + 8,          # k, v, dy, lse_dec, delta in
+        "bwd_dkdv": 5 * row + 8,                # k, v, dy in; dk, dv out
+        "bwd_pass_a": 2 * row + 8,
+        "bwd_pass_b": 5 * row + 8,
+    }
+    if kernel in per_token:
+        return bhn * per_token[kernel]
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--cfg", type=int, default=4, help="synthetic workload id (4 = the headline)")
+    ap.add_argument("--tokens", type=int, default=None, help="override N (for quick checks only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus %d is not supported "
+              "(see DESIGN.md, 'More than one GPU').  Run with --gpus 1." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2508_12594_amd import binding, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    binding.load()
+
+    over = {} if args.tokens is None else {"N": args.tokens}
+    inp = synth.make_inputs(args.cfg, with_dy=True, **over)
+    B, H, N, M, d = (inp[x] for x in "BHNMd")
+    dt = torch.float32 if inp["dtype"] == "f32" else torch.bfloat16
+    elem = 4 if inp["dtype"] == "f32" else 2
+    dev = {n: torch.from_numpy(inp[n]).to("cuda", dt).contiguous() for n in ("q", "k", "v", "dy")}
+    scale = inp["scale"]
+    code = binding.FLARE_F32 if inp["dtype"] == "f32" else binding.FLARE_BF16
+    fwd_b, bwd_b = binding.workspace_bytes(B, H, N, M, d, code)
+    ws = torch.empty(max(fwd_b, bwd_b, 256), dtype=torch.uint8, device="cuda")
+    y = torch.empty_like(dev["k"])
+    z = torch.empty((B, H, M, d), dtype=torch.float32, device="cuda")
+    lse = torch.empty((B, H, M), dtype=torch.float32, device="cuda")
+    dq = torch.empty((H, M, d), dtype=torch.float32, device="cuda")
+    dk = torch.empty_like(dev["k"])
+    dv = torch.empty_like(dev["k"])
+
+    def fwd():
+        binding.forward(dev["q"], dev["k"], dev["v"], scale, y=y, z=z, lse_enc=lse, workspace=ws)
+
+    def step():
+        fwd()
+        binding.backward(dev["q"], dev["k"], dev["v"], dev["dy"], z, lse, scale, dq_lat=dq, dk=dk, dv=dv,
+                         workspace=ws)
+
+    def timed(fn, steps):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    for _ in range(args.warmup):
+        step()
+    t_step = timed(step, args.steps)          # the headline: forward + backward
+    t_fwd = timed(fwd, args.steps)            # forward alone
+
+    # per-kernel durations: HIP events recorded by the library on the launch stream, same K steps
+    binding.profile_enable(True)
+    t_step_prof = timed(step, args.steps)
+    prof = binding.profile_read()
+    binding.profile_enable(False)
+
+    kernels = {}
+    for name, (ms, cnt) in prof.items():
+        mean_s = ms / cnt * 1e-3
+        ab = algorithmic_bytes(name, B, H, N, M, d, elem)
+        kernels[name] = {"mean_us": round(mean_s * 1e6, 2), "launches_per_step": cnt // args.steps,
+                         "algorithmic_GBps": (round(ab / mean_s / 1e9, 1) if ab else None)}
+    streaming = {n: v for n, v in kernels.items() if v["algorithmic_GBps"] is not None}
+    dom = max(streaming, key=lambda n: streaming[n]["mean_us"] * streaming[n]["launches_per_step"])
+    dom_bytes = algorithmic_bytes(dom, B, H, N, M, d, elem)
+    dom_s = kernels[dom]["mean_us"] * 1e-6
+    roofline = {"kernel": dom, "bound": "hbm", "achieved": round(dom_bytes / dom_s / 1e9, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(dom_bytes / dom_s / 1e9 / HBM_PEAK_GBS, 4),
+                "traffic": None, "bytes_per_launch": dom_bytes, "mean_us": kernels[dom]["mean_us"]}
+
+    tokens = B * N
+    fwd_bytes = 4 * B * H * N * d * elem       # k twice, v once, y once
+    fwd_flops = 8.0 * B * H * N * M * d
+    out = {
+        "metric": "FLARE fwd+bwd tokens/sec at N=%d, M=%d (one MI355X)" % (N, M),
+        "value": round(tokens / t_step, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(t_step * 1e3, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": inp["dtype"], "data": "synthetic",
+        "config": {"workload": synth.describe(args.cfg) + ("" if args.tokens is None else " [N overridden to %d]" % N),
+                   "step": "flare_forward + flare_backward", "B": B, "H": H, "N": N, "M": M, "d": d},
+        "fwd": {"tokens_per_s": round(tokens / t_fwd, 1), "ms": round(t_fwd * 1e3, 4),
+                "hbm_frac": round(fwd_bytes / t_fwd / 1e9 / HBM_PEAK_GBS, 4),
+                "mfma_frac": round(fwd_flops / t_fwd / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                "exp_frac": round(2.0 * B * H * N * M / t_fwd / 1e9 / EXP_PEAK_GOPS, 4)},
+        "ms_per_step_with_events": round(t_step_prof * 1e3, 4),
+        "roofline": roofline, "kernels": kernels,
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import flare_oracle
+        n_s = min(N, 65536)
+        sub = {n: inp[n][:1, :1, :n_s] for n in ("k", "v", "dy")}
+        q1 = inp["q"][:1]
+        t0 = time.perf_counter()
+        flare_oracle.forward(q1, sub["k"], sub["v"], scale)
+        flare_oracle.backward(q1, sub["k"], sub["v"], sub["dy"], scale)
+        t_cpu = time.perf_counter() - t0
+        out["cpu_baseline"] = {
+            "value": round(n_s / (t_cpu * H), 1), "unit": "tokens/s", "cores": flare_oracle.threads(),
+            "kind": "oracle",
+            "sample": "fp64 oracle forward+backward on head 0, first %d tokens, M=%d, d=%d (%.1f s); "
+                      "rate divided by H=%d heads" % (n_s, M, d, t_cpu, H)}
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,141 @@
+/*
+ * flare.h -- C ABI of libflare.so: FLARE's encode-decode token mixer on one MI355X (gfx950).
+ *
+ * The operator (paper Section 3.1, Eq. flare_encode and Eq. flare_decode; multi-head listing
+ * of the same section with shapes Q:[H M D], K,V:[B H N D] -> Y:[B H N D]):
+ *
+ *     S[m][n]  = scale * <q_lat[h][m][:], k[b][h][n][:]>          one score matrix per (b,h)
+ *     Z[m][:]  = sum_n softmax_n(S[m][.])[n] * v[b][h][n][:]       encode: softmax over N tokens
+ *     Y[n][:]  = sum_m softmax_m(S[.][n])[m] * Z[m][:]             decode: softmax over M latents
+ *
+ * `scale` is a MULTIPLIER on q.k and is the same in both halves (the paper's listing passes
+ * scale=1.0 to both attention calls; its Eq. sdpa writes a division by s, which coincides at
+ * s=1).  The latent queries are shared by all batch items.  The M x N weights are never
+ * written to memory.  There is no mask, dropout or bias.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller, contiguous with innermost
+ *     dimension d, and 16-byte aligned.  The library allocates and frees nothing on the hot
+ *     path, never synchronises the device, and only enqueues work on `stream` (a hipStream_t
+ *     passed as void*; NULL is the default stream).  Results are ready when the stream reaches
+ *     the point after the call.
+ *   - Outputs are overwritten, never accumulated into.
+ *   - `workspace` is caller-provided device scratch of at least the size that
+ *     flare_workspace_bytes reports for the same shape; its contents are undefined on return.
+ *     Two calls that share a workspace must be ordered on the same stream.
+ *   - Return value: FLARE_OK (0) or a negative flare_status.  Nothing is launched when an
+ *     argument check fails.  A launch failure reported by the HIP runtime gives FLARE_ELAUNCH.
+ *   - Supported shapes: B,H,N,M >= 1 with B*H <= 65535; d in {4, 8, 16, 32}; dtype f32 or bf16.
+ *     Shapes with dtype bf16, d in {16,32} and M a multiple of 32 up to 256 run on the
+ *     matrix-core kernels; everything else runs on the fp32 vector kernels.
+ *   - Results are bit-identical from run to run for the same inputs and shape (no float atomics;
+ *     every cross-block reduction is done in a fixed order).
+ *   - Non-finite inputs give undefined results.
+ */
+#ifndef FLARE_H
+#define FLARE_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FLARE_F32 = 0,   /* q_lat, k, v, y, dy, dk, dv are IEEE fp32 */
+    FLARE_BF16 = 1   /* ... are bfloat16; all accumulation and the saved statistics stay fp32 */
+} flare_dtype;
+
+typedef enum {
+    FLARE_OK = 0,
+    FLARE_EINVAL = -1,        /* null pointer, non-positive dimension, null shape */
+    FLARE_EUNSUPPORTED = -2,  /* d, dtype or B*H outside the supported set */
+    FLARE_EALIGN = -3,        /* a data pointer is not 16-byte aligned */
+    FLARE_EWORKSPACE = -4,    /* workspace is NULL or smaller than flare_workspace_bytes reports */
+    FLARE_ELAUNCH = -5        /* the HIP runtime rejected a launch or an event call */
+} flare_status;
+
+typedef struct {
+    int B;              /* batch items */
+    int H;              /* heads; head h uses its own slice of M latent queries */
+    int N;              /* tokens per batch item */
+    int M;              /* latent queries per head */
+    int d;              /* head dimension D = C / H */
+    flare_dtype dtype;  /* element type of q_lat, k, v, y, dy, dk, dv */
+} flare_shape;
+
+/* Library version: major*10000 + minor*100 + patch. */
+int flare_version(void);
+
+/* Static, NUL-terminated description of a flare_status value. */
+const char *flare_strerror(int status);
+
+/* Scratch bytes that flare_forward / flare_encode (fwd_bytes) and flare_backward (bwd_bytes)
+ * need for this shape.  Either output pointer may be NULL.  Host-only; touches no device. */
+int flare_workspace_bytes(const flare_shape *shape, size_t *fwd_bytes, size_t *bwd_bytes);
+
+/*
+ * Encode (Eq. flare_encode; Appendix E, per-latent form of z_m): split-N partial softmax
+ * reductions followed by a fixed-order merge.
+ *   q_lat [H][M][d] dtype, k, v [B][H][N][d] dtype                         (in)
+ *   z       [B][H][M][d] fp32: the latent sequence Z                        (out)
+ *   lse_enc [B][H][M]    fp32: log sum_n exp(S[m][n]), natural log          (out)
+ */
+int flare_encode(const flare_shape *shape, const void *q_lat, const void *k, const void *v,
+                 float *z, float *lse_enc, float scale,
+                 void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Decode (Eq. flare_decode; Appendix E, per-token form of y_n): per-token softmax over the M
+ * latents applied to Z.  Needs no workspace.
+ *   q_lat [H][M][d] dtype, k [B][H][N][d] dtype, z [B][H][M][d] fp32        (in)
+ *   y [B][H][N][d] dtype                                                    (out)
+ */
+int flare_decode(const flare_shape *shape, const void *q_lat, const void *k, const float *z,
+                 void *y, float scale, void *stream);
+
+/*
+ * Forward of the mixer = flare_encode then flare_decode on the same stream (listing in
+ * Section 3.1).  z and lse_enc are outputs the caller keeps for flare_backward.
+ */
+int flare_forward(const flare_shape *shape, const void *q_lat, const void *k, const void *v,
+                  void *y, float *z, float *lse_enc, float scale,
+                  void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Backward of the mixer.  The paper differentiates its two attention calls automatically
+ * (Appendix F, "Time and memory complexity": one forward and backward pass is what it
+ * times); the gradients follow from the softmax Jacobian.  With P = softmax_n(S) (M x N),
+ * R = softmax_m(S^T) (N x M), Z = P V, Y = R Z:
+ *     dZ = R^T dY,  delta_n = <dY_n, Y_n>,  eps_m = <dZ_m, Z_m>,  dV = P^T dZ,
+ *     dS[m][n] = P[m][n](<dZ_m, V_n> - eps_m) + R[n][m](<dY_n, Z_m> - delta_n),
+ *     dK_n = scale * sum_m dS[m][n] q_m,   dQ_m = scale * sum_n dS[m][n] k_n  summed over B.
+ *   q_lat, k, v as in the forward; dy [B][H][N][d] dtype                    (in)
+ *   z, lse_enc: what flare_forward wrote for the same inputs                (in)
+ *   y: unused, may be NULL (Y is recomputed from z)                         (in)
+ *   dq_lat [H][M][d] fp32 (summed over the batch), dk, dv [B][H][N][d] dtype (out)
+ */
+int flare_backward(const flare_shape *shape, const void *q_lat, const void *k, const void *v,
+                   const void *y, const void *dy, const float *z, const float *lse_enc,
+                   float *dq_lat, void *dk, void *dv, float scale,
+                   void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Per-kernel timing for measurement (not part of the operator).  While enabled, every kernel
+ * the library launches is bracketed by a pair of HIP events recorded on the launch stream.
+ * flare_profile_enable(1) creates the event pool (the only allocation this library makes) and
+ * clears the totals; flare_profile_enable(0) stops recording.  flare_profile_kernels() returns
+ * how many kernel ids exist; flare_profile_name(id) names one; flare_profile_read(id, ...)
+ * waits for the recorded events and returns the summed duration in milliseconds and the
+ * number of launches since enabling.  At most 8192 launches are recorded; later ones run
+ * untimed.  Not thread-safe.
+ */
+int flare_profile_enable(int on);
+int flare_profile_kernels(void);
+const char *flare_profile_name(int kernel_id);
+int flare_profile_read(int kernel_id, double *total_ms, int *launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLARE_H */

@@ -1,0 +1,220 @@
+"""Thin Python binding of libflare.so (see include/flare.h).
+
+Argument marshalling only: every step of the operator runs in the library's HIP kernels.
+torch is used for device memory and for the current stream, nothing else.  There is no
+fallback: if the library is missing or a call fails, an exception is raised.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libflare.so")
+
+FLARE_F32 = 0
+FLARE_BF16 = 1
+
+EXPORTS = [
+    "flare_version", "flare_strerror", "flare_workspace_bytes", "flare_encode", "flare_decode",
+    "flare_forward", "flare_backward", "flare_profile_enable", "flare_profile_kernels",
+    "flare_profile_name", "flare_profile_read",
+]
+
+
+class FlareShape(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int), ("H", ctypes.c_int), ("N", ctypes.c_int), ("M", ctypes.c_int),
+                ("d", ctypes.c_int), ("dtype", ctypes.c_int)]
+
+
+class FlareError(RuntimeError):
+    pass
+
+
+_lib = None
+
+
+def load():
+    """dlopen libflare.so (built by paper_2508_12594_amd.build); raises if it is not there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FlareError("libflare.so not found at %s: run `python -m paper_2508_12594_amd.build`" % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, fp, sp = ctypes.c_void_p, ctypes.c_void_p, ctypes.POINTER(FlareShape)
+    lib.flare_version.restype = ctypes.c_int
+    lib.flare_strerror.restype = ctypes.c_char_p
+    lib.flare_strerror.argtypes = [ctypes.c_int]
+    lib.flare_workspace_bytes.argtypes = [sp, ctypes.POINTER(ctypes.c_size_t), ctypes.POINTER(ctypes.c_size_t)]
+    lib.flare_encode.argtypes = [sp, vp, vp, vp, fp, fp, ctypes.c_float, vp, ctypes.c_size_t, vp]
+    lib.flare_decode.argtypes = [sp, vp, vp, fp, vp, ctypes.c_float, vp]
+    lib.flare_forward.argtypes = [sp, vp, vp, vp, vp, fp, fp, ctypes.c_float, vp, ctypes.c_size_t, vp]
+    lib.flare_backward.argtypes = [sp, vp, vp, vp, vp, vp, fp, fp, fp, vp, vp, ctypes.c_float, vp,
+                                   ctypes.c_size_t, vp]
+    lib.flare_profile_enable.argtypes = [ctypes.c_int]
+    lib.flare_profile_name.restype = ctypes.c_char_p
+    lib.flare_profile_name.argtypes = [ctypes.c_int]
+    lib.flare_profile_read.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
+    for name in ("flare_workspace_bytes", "flare_encode", "flare_decode", "flare_forward", "flare_backward",
+                 "flare_profile_enable", "flare_profile_kernels", "flare_profile_read"):
+        getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def strerror(code):
+    return load().flare_strerror(int(code)).decode()
+
+
+def _check(code, what):
+    if code != 0:
+        raise FlareError("%s failed: %d (%s)" % (what, code, strerror(code)))
+
+
+def version():
+    return int(load().flare_version())
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _dtype_code(t):
+    torch = _torch()
+    if t.dtype == torch.float32:
+        return FLARE_F32
+    if t.dtype == torch.bfloat16:
+        return FLARE_BF16
+    raise FlareError("dtype must be float32 or bfloat16, got %s" % t.dtype)
+
+
+def _shape_of(q, k):
+    if q.dim() != 3 or k.dim() != 4:
+        raise FlareError("expected q_lat[H,M,d] and k[B,H,N,d]")
+    H, M, d = q.shape
+    B, Hk, N, dk = k.shape
+    if Hk != H or dk != d or q.dtype != k.dtype:
+        raise FlareError("q_lat and k disagree on H, d or dtype")
+    return FlareShape(B, H, N, M, d, _dtype_code(k))
+
+
+def _dev(t, name, dtype=None, shape=None):
+    if not t.is_cuda or not t.is_contiguous():
+        raise FlareError("%s must be a contiguous device tensor" % name)
+    if dtype is not None and t.dtype != dtype:
+        raise FlareError("%s must have dtype %s" % (name, dtype))
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise FlareError("%s must have shape %s, got %s" % (name, tuple(shape), tuple(t.shape)))
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    torch = _torch()
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def workspace_bytes(B, H, N, M, d, dtype_code):
+    """(forward bytes, backward bytes) of scratch for this shape."""
+    shp = FlareShape(B, H, N, M, d, dtype_code)
+    f, b = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    _check(load().flare_workspace_bytes(ctypes.byref(shp), ctypes.byref(f), ctypes.byref(b)),
+           "flare_workspace_bytes")
+    return int(f.value), int(b.value)
+
+
+def _workspace(shp, which, workspace, device):
+    torch = _torch()
+    f, b = workspace_bytes(shp.B, shp.H, shp.N, shp.M, shp.d, shp.dtype)
+    need = f if which == "fwd" else b
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
+    if workspace.dtype != torch.uint8:
+        raise FlareError("workspace must be a uint8 tensor")
+    return workspace, ctypes.c_void_p(workspace.data_ptr()), ctypes.c_size_t(workspace.numel())
+
+
+def encode(q_lat, k, v, scale, z=None, lse_enc=None, workspace=None, stream=None):
+    """flare_encode: returns (z[B,H,M,d] fp32, lse_enc[B,H,M] fp32)."""
+    torch = _torch()
+    shp = _shape_of(q_lat, k)
+    if z is None:
+        z = torch.empty((shp.B, shp.H, shp.M, shp.d), dtype=torch.float32, device=k.device)
+    if lse_enc is None:
+        lse_enc = torch.empty((shp.B, shp.H, shp.M), dtype=torch.float32, device=k.device)
+    ws, ws_p, ws_n = _workspace(shp, "fwd", workspace, k.device)
+    _check(load().flare_encode(ctypes.byref(shp), _dev(q_lat, "q_lat"), _dev(k, "k"),
+                               _dev(v, "v", k.dtype, k.shape),
+                               _dev(z, "z", torch.float32, (shp.B, shp.H, shp.M, shp.d)),
+                               _dev(lse_enc, "lse_enc", torch.float32, (shp.B, shp.H, shp.M)),
+                               ctypes.c_float(scale), ws_p, ws_n, _stream(stream)), "flare_encode")
+    return z, lse_enc
+
+
+def decode(q_lat, k, z, scale, y=None, stream=None):
+    """flare_decode: returns y[B,H,N,d] in k's dtype."""
+    torch = _torch()
+    shp = _shape_of(q_lat, k)
+    if y is None:
+        y = torch.empty_like(k)
+    _check(load().flare_decode(ctypes.byref(shp), _dev(q_lat, "q_lat"), _dev(k, "k"),
+                               _dev(z, "z", torch.float32, (shp.B, shp.H, shp.M, shp.d)),
+                               _dev(y, "y", k.dtype, k.shape), ctypes.c_float(scale), _stream(stream)),
+           "flare_decode")
+    return y
+
+
+def forward(q_lat, k, v, scale, y=None, z=None, lse_enc=None, workspace=None, stream=None):
+    """flare_forward: returns (y, z, lse_enc)."""
+    torch = _torch()
+    shp = _shape_of(q_lat, k)
+    if y is None:
+        y = torch.empty_like(k)
+    if z is None:
+        z = torch.empty((shp.B, shp.H, shp.M, shp.d), dtype=torch.float32, device=k.device)
+    if lse_enc is None:
+        lse_enc = torch.empty((shp.B, shp.H, shp.M), dtype=torch.float32, device=k.device)
+    ws, ws_p, ws_n = _workspace(shp, "fwd", workspace, k.device)
+    _check(load().flare_forward(ctypes.byref(shp), _dev(q_lat, "q_lat"), _dev(k, "k"),
+                                _dev(v, "v", k.dtype, k.shape), _dev(y, "y", k.dtype, k.shape),
+                                _dev(z, "z", torch.float32, (shp.B, shp.H, shp.M, shp.d)),
+                                _dev(lse_enc, "lse_enc", torch.float32, (shp.B, shp.H, shp.M)),
+                                ctypes.c_float(scale), ws_p, ws_n, _stream(stream)), "flare_forward")
+    return y, z, lse_enc
+
+
+def backward(q_lat, k, v, dy, z, lse_enc, scale, dq_lat=None, dk=None, dv=None, workspace=None, stream=None):
+    """flare_backward: returns (dq_lat[H,M,d] fp32, dk, dv in k's dtype)."""
+    torch = _torch()
+    shp = _shape_of(q_lat, k)
+    if dq_lat is None:
+        dq_lat = torch.empty((shp.H, shp.M, shp.d), dtype=torch.float32, device=k.device)
+    if dk is None:
+        dk = torch.empty_like(k)
+    if dv is None:
+        dv = torch.empty_like(k)
+    ws, ws_p, ws_n = _workspace(shp, "bwd", workspace, k.device)
+    _check(load().flare_backward(ctypes.byref(shp), _dev(q_lat, "q_lat"), _dev(k, "k"),
+                                 _dev(v, "v", k.dtype, k.shape), None, _dev(dy, "dy", k.dtype, k.shape),
+                                 _dev(z, "z", torch.float32, (shp.B, shp.H, shp.M, shp.d)),
+                                 _dev(lse_enc, "lse_enc", torch.float32, (shp.B, shp.H, shp.M)),
+                                 _dev(dq_lat, "dq_lat", torch.float32, (shp.H, shp.M, shp.d)),
+                                 _dev(dk, "dk", k.dtype, k.shape), _dev(dv, "dv", k.dtype, k.shape),
+                                 ctypes.c_float(scale), ws_p, ws_n, _stream(stream)), "flare_backward")
+    return dq_lat, dk, dv
+
+
+def profile_enable(on):
+    _check(load().flare_profile_enable(1 if on else 0), "flare_profile_enable")
+
+
+def profile_read():
+    """{kernel name: (total ms, launches)} for kernels launched since profile_enable(True)."""
+    lib = load()
+    out = {}
+    for kid in range(lib.flare_profile_kernels()):
+        ms, cnt = ctypes.c_double(0), ctypes.c_int(0)
+        _check(lib.flare_profile_read(kid, ctypes.byref(ms), ctypes.byref(cnt)), "flare_profile_read")
+        if cnt.value:
+            out[lib.flare_profile_name(kid).decode()] = (float(ms.value), int(cnt.value))
+    return out

@@ -1,0 +1,60 @@
+// Internal declarations shared by the translation units of libflare.so.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "flare.h"
+
+namespace flare {
+
+// ---- kernel ids for the per-kernel timing hooks ------------------------------------------
+enum KernelId {
+    KID_ENCODE_PARTIAL = 0,
+    KID_ENCODE_MERGE,
+    KID_DECODE,
+    KID_BWD_TOKEN_STATS,
+    KID_BWD_DZ_PARTIAL,
+    KID_BWD_DZ_MERGE,
+    KID_BWD_DQ_PARTIAL,
+    KID_BWD_DQ_REDUCE,
+    KID_BWD_DKDV,
+    KID_COUNT
+};
+
+// Brackets one launch with events when timing is on (see flare_profile_enable).
+struct LaunchTimer {
+    LaunchTimer(int kid, hipStream_t stream);
+    ~LaunchTimer();
+    int slot;
+    hipStream_t stream;
+};
+
+// ---- how the token axis is split over workgroups -------------------------------------------
+struct Split {
+    int chunks;     // number of token chunks per (b,h)
+    int chunk_len;  // tokens per chunk (the last chunk may be shorter, never empty)
+};
+Split plan_split(int N, int BH, int min_len, int target_blocks);
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// ---- fp32 vector-ALU path (any M, d in {4,8,16,32}, f32 or bf16 storage) -------------------
+struct ValuPlan {
+    Split enc;          // split used by the encode partials
+    Split bwd;          // split used by the dZ and dQ partials
+    size_t fwd_bytes;   // workspace for encode
+    size_t bwd_bytes;   // workspace for backward
+};
+ValuPlan valu_plan(const flare_shape &s);
+
+int valu_encode(const flare_shape &s, const void *q, const void *k, const void *v, float *z,
+                float *lse_enc, float scale, void *ws, hipStream_t stream);
+int valu_decode(const flare_shape &s, const void *q, const void *k, const float *z, void *y,
+                float scale, hipStream_t stream);
+int valu_backward(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy,
+                  const float *z, const float *lse_enc, float *dq, void *dk, void *dv, float scale,
+                  void *ws, hipStream_t stream);
+
+}  // namespace flare

@@ -1,0 +1,628 @@
+// fp32 vector-ALU kernels of the FLARE mixer: the fp32 path, and the general path for
+// shapes the matrix-core kernels do not take (any M, d in {4,8,16,32}, f32 or bf16 storage).
+//
+// Two kernel shapes cover every step:
+//   * one thread per LATENT, streaming tokens (encode partials, dZ partials, dQ partials):
+//     the token rows k_n, v_n, dy_n have wave-uniform addresses, so they arrive through the
+//     scalar data path (reads only) and cost no vector memory traffic or LDS;
+//   * one thread per TOKEN, streaming latents (decode, token statistics, dK/dV): here
+//     q_m, z_m, dZ_m are the wave-uniform operands.
+// Scores are kept in log2 units, S2 = (scale*log2 e) * <q,k>, so that the softmax needs
+// one v_exp_f32 per score.  Every cross-block reduction goes through per-chunk partials
+// that are merged in a fixed order: results are bit-reproducible.
+//
+// Equations: Section 3.1, Eq. flare_encode / Eq. flare_decode; Appendix E per-latent and
+// per-token forms.  The backward follows the formulas in include/flare.h.
+#include "flare_internal.h"
+
+namespace flare {
+namespace {
+
+typedef uint16_t bf16_t;  // raw bfloat16 bits
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Load one row of D elements as floats.  `p` points at the first element of the row.
+template <int D>
+__device__ __forceinline__ void load_row(const float *__restrict__ p, float (&out)[D])
+{
+    const float4 *p4 = reinterpret_cast<const float4 *>(p);
+#pragma unroll
+    for (int i = 0; i < D / 4; ++i) {
+        float4 t = p4[i];
+        out[4 * i + 0] = t.x; out[4 * i + 1] = t.y; out[4 * i + 2] = t.z; out[4 * i + 3] = t.w;
+    }
+}
+template <int D>
+__device__ __forceinline__ void load_row(const bf16_t *__restrict__ p, float (&out)[D])
+{
+    if constexpr (D == 4) {
+        uint2 t = *reinterpret_cast<const uint2 *>(p);
+        out[0] = bf16_lo(t.x); out[1] = bf16_hi(t.x); out[2] = bf16_lo(t.y); out[3] = bf16_hi(t.y);
+    } else {
+        const uint4 *p4 = reinterpret_cast<const uint4 *>(p);
+#pragma unroll
+        for (int i = 0; i < D / 8; ++i) {
+            uint4 t = p4[i];
+            out[8 * i + 0] = bf16_lo(t.x); out[8 * i + 1] = bf16_hi(t.x);
+            out[8 * i + 2] = bf16_lo(t.y); out[8 * i + 3] = bf16_hi(t.y);
+            out[8 * i + 4] = bf16_lo(t.z); out[8 * i + 5] = bf16_hi(t.z);
+            out[8 * i + 6] = bf16_lo(t.w); out[8 * i + 7] = bf16_hi(t.w);
+        }
+    }
+}
+template <int D>
+__device__ __forceinline__ void store_row(float *__restrict__ p, const float (&in)[D])
+{
+    float4 *p4 = reinterpret_cast<float4 *>(p);
+#pragma unroll
+    for (int i = 0; i < D / 4; ++i) p4[i] = make_float4(in[4 * i], in[4 * i + 1], in[4 * i + 2], in[4 * i + 3]);
+}
+template <int D>
+__device__ __forceinline__ void store_row(bf16_t *__restrict__ p, const float (&in)[D])
+{
+    uint32_t w[D / 2];
+#pragma unroll
+    for (int i = 0; i < D / 2; ++i) w[i] = f32_to_bf16_rne(in[2 * i]) | (f32_to_bf16_rne(in[2 * i + 1]) << 16);
+    if constexpr (D == 4) {
+        *reinterpret_cast<uint2 *>(p) = make_uint2(w[0], w[1]);
+    } else {
+        uint4 *p4 = reinterpret_cast<uint4 *>(p);
+#pragma unroll
+        for (int i = 0; i < D / 8; ++i) p4[i] = make_uint4(w[4 * i], w[4 * i + 1], w[4 * i + 2], w[4 * i + 3]);
+    }
+}
+template <int D>
+__device__ __forceinline__ float dot(const float (&a)[D], const float (&b)[D])
+{
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < D; ++j) s = fmaf(a[j], b[j], s);
+    return s;
+}
+
+constexpr int kLatentBlock = 256;  // threads per block in the thread-per-latent kernels
+constexpr int kTokenBlock = 256;   // threads per block in the thread-per-token kernels
+constexpr int kGroup = 8;          // scores handled between two running-max updates
+
+// ---------------------------------------------------------------------------------------
+// Encode partials: thread = latent m, block = (chunk of tokens, b*h, block of latents).
+// Online softmax over the chunk's tokens; writes (running max, sum, unnormalised O) per chunk.
+// ---------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(kLatentBlock) void encode_partial_kernel(
+    const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v,
+    float *__restrict__ m_part, float *__restrict__ l_part, float *__restrict__ o_part,
+    int H, int N, int M, int chunk_len, int chunks, float c2)
+{
+    const int m = blockIdx.z * kLatentBlock + threadIdx.x;
+    if (m >= M) return;
+    const int bh = blockIdx.y, h = bh % H, chunk = blockIdx.x;
+    float qm[D];
+    load_row<D>(q + ((size_t)h * M + m) * D, qm);
+#pragma unroll
+    for (int j = 0; j < D; ++j) qm[j] *= c2;
+    const T *kb = k + (size_t)bh * N * D;
+    const T *vb = v + (size_t)bh * N * D;
+    const int n0 = chunk * chunk_len;
+    const int n1 = min(N, n0 + chunk_len);
+
+    float mr = -INFINITY, l = 0.f, o[D];
+#pragma unroll
+    for (int j = 0; j < D; ++j) o[j] = 0.f;
+
+    int n = n0;
+    for (; n + kGroup <= n1; n += kGroup) {
+        float s[kGroup];
+        float gm = mr;
+#pragma unroll
+        for (int t = 0; t < kGroup; ++t) {
+            float kr[D];
+            load_row<D>(kb + (size_t)(n + t) * D, kr);
+            s[t] = dot<D>(qm, kr);
+            gm = fmaxf(gm, s[t]);
+        }
+        const float al = fast_exp2(mr - gm);   // mr = -inf on the first group: exp2(-inf) = 0
+        mr = gm;
+        l *= al;
+#pragma unroll
+        for (int j = 0; j < D; ++j) o[j] *= al;
+#pragma unroll
+        for (int t = 0; t < kGroup; ++t) {
+            const float p = fast_exp2(s[t] - mr);
+            l += p;
+            float vr[D];
+            load_row<D>(vb + (size_t)(n + t) * D, vr);
+#pragma unroll
+            for (int j = 0; j < D; ++j) o[j] = fmaf(p, vr[j], o[j]);
+        }
+    }
+    for (; n < n1; ++n) {
+        float kr[D], vr[D];
+        load_row<D>(kb + (size_t)n * D, kr);
+        const float s = dot<D>(qm, kr);
+        const float gm = fmaxf(mr, s);
+        const float al = fast_exp2(mr - gm);
+        mr = gm;
+        const float p = fast_exp2(s - mr);
+        l = l * al + p;
+        load_row<D>(vb + (size_t)n * D, vr);
+#pragma unroll
+        for (int j = 0; j < D; ++j) o[j] = fmaf(p, vr[j], o[j] * al);
+    }
+    const size_t slot = ((size_t)bh * chunks + chunk) * M + m;
+    m_part[slot] = mr;
+    l_part[slot] = l;
+    store_row<D>(o_part + slot * D, o);
+}
+
+// Merge of the chunk partials in chunk order: thread = (b*h, m).
+template <int D>
+__global__ __launch_bounds__(256) void encode_merge_kernel(
+    const float *__restrict__ m_part, const float *__restrict__ l_part, const float *__restrict__ o_part,
+    float *__restrict__ z, float *__restrict__ lse_enc, int BH, int M, int chunks)
+{
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (size_t)BH * M) return;
+    const int bh = (int)(idx / M), m = (int)(idx % M);
+    float gm = -INFINITY;
+    for (int c = 0; c < chunks; ++c) gm = fmaxf(gm, m_part[((size_t)bh * chunks + c) * M + m]);
+    float l = 0.f, o[D];
+#pragma unroll
+    for (int j = 0; j < D; ++j) o[j] = 0.f;
+    for (int c = 0; c < chunks; ++c) {
+        const size_t slot = ((size_t)bh * chunks + c) * M + m;
+        const float w = fast_exp2(m_part[slot] - gm);
+        l = fmaf(l_part[slot], w, l);
+        float oc[D];
+        load_row<D>(o_part + slot * D, oc);
+#pragma unroll
+        for (int j = 0; j < D; ++j) o[j] = fmaf(oc[j], w, o[j]);
+    }
+    const float inv = 1.f / l;
+#pragma unroll
+    for (int j = 0; j < D; ++j) o[j] *= inv;
+    store_row<D>(z + idx * D, o);
+    lse_enc[idx] = (gm + log2f(l)) * kLn2;
+}
+
+// ---------------------------------------------------------------------------------------
+// Per-token pass over the latents.  MODE 0: decode, writes y.  MODE 1: backward statistics,
+// writes lse_dec2[n] = log2 sum_m 2^S2[m][n] and delta[n] = <dY_n, Y_n>.
+// ---------------------------------------------------------------------------------------
+template <typename T, int D, int MODE>
+__global__ __launch_bounds__(kTokenBlock) void token_pass_kernel(
+    const T *__restrict__ q, const T *__restrict__ k, const float *__restrict__ z,
+    T *__restrict__ y, const T *__restrict__ dy, float *__restrict__ lse_dec2, float *__restrict__ delta,
+    int H, int N, int M, float c2)
+{
+    const int n = blockIdx.x * kTokenBlock + threadIdx.x;
+    const int bh = blockIdx.y, h = bh % H;
+    const bool valid = n < N;
+    const size_t row = (size_t)bh * N + (valid ? n : N - 1);
+    float kn[D];
+    load_row<D>(k + row * D, kn);
+#pragma unroll
+    for (int j = 0; j < D; ++j) kn[j] *= c2;
+    const T *qh = q + (size_t)h * M * D;
+    const float *zb = z + (size_t)bh * M * D;
+
+    float mr = -INFINITY, l = 0.f, acc[D];
+#pragma unroll
+    for (int j = 0; j < D; ++j) acc[j] = 0.f;
+    int m = 0;
+    for (; m + kGroup <= M; m += kGroup) {
+        float s[kGroup];
+        float gm = mr;
+#pragma unroll
+        for (int t = 0; t < kGroup; ++t) {
+            float qr[D];
+            load_row<D>(qh + (size_t)(m + t) * D, qr);
+            s[t] = dot<D>(kn, qr);
+            gm = fmaxf(gm, s[t]);
+        }
+        const float al = fast_exp2(mr - gm);
+        mr = gm;
+        l *= al;
+#pragma unroll
+        for (int j = 0; j < D; ++j) acc[j] *= al;
+#pragma unroll
+        for (int t = 0; t < kGroup; ++t) {
+            const float p = fast_exp2(s[t] - mr);
+            l += p;
+            float zr[D];
+            load_row<D>(zb + (size_t)(m + t) * D, zr);
+#pragma unroll
+            for (int j = 0; j < D; ++j) acc[j] = fmaf(p, zr[j], acc[j]);
+        }
+    }
+    for (; m < M; ++m) {
+        float qr[D], zr[D];
+        load_row<D>(qh + (size_t)m * D, qr);
+        const float s = dot<D>(kn, qr);
+        const float gm = fmaxf(mr, s);
+        const float al = fast_exp2(mr - gm);
+        mr = gm;
+        const float p = fast_exp2(s - mr);
+        l = l * al + p;
+        load_row<D>(zb + (size_t)m * D, zr);
+#pragma unroll
+        for (int j = 0; j < D; ++j) acc[j] = fmaf(p, zr[j], acc[j] * al);
+    }
+    const float inv = 1.f / l;
+#pragma unroll
+    for (int j = 0; j < D; ++j) acc[j] *= inv;
+    if (!valid) return;
+    if constexpr (MODE == 0) {
+        store_row<D>(y + row * D, acc);
+    } else {
+        float g[D];
+        load_row<D>(dy + row * D, g);
+        lse_dec2[row] = mr + log2f(l);
+        delta[row] = dot<D>(g, acc);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// dZ partials: thread = latent m; dZ[m] += R[n][m] dY[n] over the chunk's tokens.
+// ---------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(kLatentBlock) void dz_partial_kernel(
+    const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ dy,
+    const float *__restrict__ lse_dec2, float *__restrict__ dz_part,
+    int H, int N, int M, int chunk_len, int chunks, float c2)
+{
+    const int m = blockIdx.z * kLatentBlock + threadIdx.x;
+    if (m >= M) return;
+    const int bh = blockIdx.y, h = bh % H, chunk = blockIdx.x;
+    float qm[D];
+    load_row<D>(q + ((size_t)h * M + m) * D, qm);
+#pragma unroll
+    for (int j = 0; j < D; ++j) qm[j] *= c2;
+    const T *kb = k + (size_t)bh * N * D;
+    const T *gb = dy + (size_t)bh * N * D;
+    const float *lb = lse_dec2 + (size_t)bh * N;
+    const int n0 = chunk * chunk_len;
+    const int n1 = min(N, n0 + chunk_len);
+    float acc[D];
+#pragma unroll
+    for (int j = 0; j < D; ++j) acc[j] = 0.f;
+    for (int n = n0; n < n1; ++n) {
+        float kr[D], g[D];
+        load_row<D>(kb + (size_t)n * D, kr);
+        const float r = fast_exp2(dot<D>(qm, kr) - lb[n]);
+        load_row<D>(gb + (size_t)n * D, g);
+#pragma unroll
+        for (int j = 0; j < D; ++j) acc[j] = fmaf(r, g[j], acc[j]);
+    }
+    store_row<D>(dz_part + (((size_t)bh * chunks + chunk) * M + m) * D, acc);
+}
+
+// dZ = sum of the chunk partials in chunk order; eps[m] = <dZ_m, Z_m>.  thread = (b*h, m).
+template <int D>
+__global__ __launch_bounds__(256) void dz_merge_kernel(
+    const float *__restrict__ dz_part, const float *__restrict__ z,
+    float *__restrict__ dz, float *__restrict__ eps, int BH, int M, int chunks)
+{
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (size_t)BH * M) return;
+    const int bh = (int)(idx / M), m = (int)(idx % M);
+    float acc[D], zr[D];
+#pragma unroll
+    for (int j = 0; j < D; ++j) acc[j] = 0.f;
+    for (int c = 0; c < chunks; ++c) {
+        float t[D];
+        load_row<D>(dz_part + (((size_t)bh * chunks + c) * M + m) * D, t);
+#pragma unroll
+        for (int j = 0; j < D; ++j) acc[j] += t[j];
+    }
+    load_row<D>(z + idx * D, zr);
+    store_row<D>(dz + idx * D, acc);
+    eps[idx] = dot<D>(acc, zr);
+}
+
+// ---------------------------------------------------------------------------------------
+// dQ partials: thread = latent m;  dQ[m] += dS[m][n] k[n] over the chunk's tokens, with
+// dS[m][n] = P[m][n](<dZ_m,V_n> - eps_m) + R[n][m](<dY_n,Z_m> - delta_n).
+// ---------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(kLatentBlock) void dq_partial_kernel(
+    const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v, const T *__restrict__ dy,
+    const float *__restrict__ z, const float *__restrict__ lse_enc, const float *__restrict__ dz,
+    const float *__restrict__ eps, const float *__restrict__ lse_dec2, const float *__restrict__ delta,
+    float *__restrict__ dq_part, int H, int N, int M, int chunk_len, int chunks, float c2)
+{
+    const int m = blockIdx.z * kLatentBlock + threadIdx.x;
+    if (m >= M) return;
+    const int bh = blockIdx.y, h = bh % H, chunk = blockIdx.x;
+    float qm[D], zm[D], dzm[D], acc[D];
+    load_row<D>(q + ((size_t)h * M + m) * D, qm);
+    load_row<D>(z + ((size_t)bh * M + m) * D, zm);
+    load_row<D>(dz + ((size_t)bh * M + m) * D, dzm);
+#pragma unroll
+    for (int j = 0; j < D; ++j) { qm[j] *= c2; acc[j] = 0.f; }
+    const float le2 = lse_enc[(size_t)bh * M + m] * kLog2e;
+    const float ep = eps[(size_t)bh * M + m];
+    const T *kb = k + (size_t)bh * N * D;
+    const T *vb = v + (size_t)bh * N * D;
+    const T *gb = dy + (size_t)bh * N * D;
+    const float *lb = lse_dec2 + (size_t)bh * N;
+    const float *db = delta + (size_t)bh * N;
+    const int n0 = chunk * chunk_len;
+    const int n1 = min(N, n0 + chunk_len);
+    for (int n = n0; n < n1; ++n) {
+        float kr[D], vr[D], g[D];
+        load_row<D>(kb + (size_t)n * D, kr);
+        load_row<D>(vb + (size_t)n * D, vr);
+        load_row<D>(gb + (size_t)n * D, g);
+        const float s2 = dot<D>(qm, kr);
+        const float p = fast_exp2(s2 - le2);
+        const float r = fast_exp2(s2 - lb[n]);
+        const float ds = p * (dot<D>(dzm, vr) - ep) + r * (dot<D>(zm, g) - db[n]);
+#pragma unroll
+        for (int j = 0; j < D; ++j) acc[j] = fmaf(ds, kr[j], acc[j]);
+    }
+    store_row<D>(dq_part + (((size_t)bh * chunks + chunk) * M + m) * D, acc);
+}
+
+// dq_lat[h][m] = scale * sum over batch items (in b order) and chunks (in chunk order).
+template <int D>
+__global__ __launch_bounds__(256) void dq_reduce_kernel(
+    const float *__restrict__ dq_part, float *__restrict__ dq, int B, int H, int M, int chunks, float scale)
+{
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;   // (h, m)
+    if (idx >= (size_t)H * M) return;
+    const int h = (int)(idx / M), m = (int)(idx % M);
+    float acc[D];
+#pragma unroll
+    for (int j = 0; j < D; ++j) acc[j] = 0.f;
+    for (int b = 0; b < B; ++b)
+        for (int c = 0; c < chunks; ++c) {
+            float t[D];
+            load_row<D>(dq_part + ((((size_t)b * H + h) * chunks + c) * M + m) * D, t);
+#pragma unroll
+            for (int j = 0; j < D; ++j) acc[j] += t[j];
+        }
+#pragma unroll
+    for (int j = 0; j < D; ++j) acc[j] *= scale;
+    store_row<D>(dq + idx * D, acc);
+}
+
+// ---------------------------------------------------------------------------------------
+// dK, dV: thread = token n;  dK_n = scale * sum_m dS[m][n] q_m,  dV_n = sum_m P[m][n] dZ_m.
+// ---------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(kTokenBlock) void dkdv_kernel(
+    const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v, const T *__restrict__ dy,
+    const float *__restrict__ z, const float *__restrict__ lse_enc, const float *__restrict__ dz,
+    const float *__restrict__ eps, const float *__restrict__ lse_dec2, const float *__restrict__ delta,
+    T *__restrict__ dk, T *__restrict__ dv, int H, int N, int M, float scale)
+{
+    const int n = blockIdx.x * kTokenBlock + threadIdx.x;
+    const int bh = blockIdx.y, h = bh % H;
+    const bool valid = n < N;
+    const size_t row = (size_t)bh * N + (valid ? n : N - 1);
+    const float c2 = scale * kLog2e;
+    float kn[D], vn[D], g[D], ak[D], av[D];
+    load_row<D>(k + row * D, kn);
+    load_row<D>(v + row * D, vn);
+    load_row<D>(dy + row * D, g);
+#pragma unroll
+    for (int j = 0; j < D; ++j) { kn[j] *= c2; ak[j] = 0.f; av[j] = 0.f; }
+    const float ld2 = lse_dec2[row];
+    const float dl = delta[row];
+    const T *qh = q + (size_t)h * M * D;
+    const float *zb = z + (size_t)bh * M * D;
+    const float *dzb = dz + (size_t)bh * M * D;
+    const float *leb = lse_enc + (size_t)bh * M;
+    const float *epb = eps + (size_t)bh * M;
+    for (int m = 0; m < M; ++m) {
+        float qr[D], zr[D], dzr[D];
+        load_row<D>(qh + (size_t)m * D, qr);
+        load_row<D>(zb + (size_t)m * D, zr);
+        load_row<D>(dzb + (size_t)m * D, dzr);
+        const float s2 = dot<D>(kn, qr);
+        const float p = fast_exp2(s2 - leb[m] * kLog2e);
+        const float r = fast_exp2(s2 - ld2);
+        const float ds = p * (dot<D>(dzr, vn) - epb[m]) + r * (dot<D>(zr, g) - dl);
+#pragma unroll
+        for (int j = 0; j < D; ++j) {
+            ak[j] = fmaf(ds, qr[j], ak[j]);
+            av[j] = fmaf(p, dzr[j], av[j]);
+        }
+    }
+    if (!valid) return;
+#pragma unroll
+    for (int j = 0; j < D; ++j) ak[j] *= scale;
+    store_row<D>(dk + row * D, ak);
+    store_row<D>(dv + row * D, av);
+}
+
+// ---- workspace carving --------------------------------------------------------------------
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct FwdWs { float *m_part, *l_part, *o_part; };
+struct BwdWs { float *lse_dec2, *delta, *part, *dz, *eps; };
+
+size_t fwd_layout(const flare_shape &s, const Split &sp, void *ws, FwdWs *out)
+{
+    const size_t slots = (size_t)s.B * s.H * sp.chunks * s.M;
+    size_t off = 0;
+    char *base = static_cast<char *>(ws);
+    if (out) out->m_part = reinterpret_cast<float *>(base + off);
+    off += align256(slots * 4);
+    if (out) out->l_part = reinterpret_cast<float *>(base + off);
+    off += align256(slots * 4);
+    if (out) out->o_part = reinterpret_cast<float *>(base + off);
+    off += align256(slots * s.d * 4);
+    return off;
+}
+size_t bwd_layout(const flare_shape &s, const Split &sp, void *ws, BwdWs *out)
+{
+    const size_t BH = (size_t)s.B * s.H;
+    size_t off = 0;
+    char *base = static_cast<char *>(ws);
+    if (out) out->lse_dec2 = reinterpret_cast<float *>(base + off);
+    off += align256(BH * s.N * 4);
+    if (out) out->delta = reinterpret_cast<float *>(base + off);
+    off += align256(BH * s.N * 4);
+    if (out) out->part = reinterpret_cast<float *>(base + off);
+    off += align256(BH * sp.chunks * s.M * s.d * 4);
+    if (out) out->dz = reinterpret_cast<float *>(base + off);
+    off += align256(BH * s.M * s.d * 4);
+    if (out) out->eps = reinterpret_cast<float *>(base + off);
+    off += align256(BH * s.M * 4);
+    return off;
+}
+
+inline int check_launch() { return hipGetLastError() == hipSuccess ? FLARE_OK : FLARE_ELAUNCH; }
+
+template <typename T, int D>
+int encode_impl(const flare_shape &s, const T *q, const T *k, const T *v, float *z, float *lse_enc,
+                float scale, void *ws, hipStream_t stream)
+{
+    const ValuPlan plan = valu_plan(s);
+    FwdWs w;
+    fwd_layout(s, plan.enc, ws, &w);
+    const int BH = s.B * s.H;
+    const int lat_blocks = (s.M + kLatentBlock - 1) / kLatentBlock;
+    {
+        LaunchTimer t(KID_ENCODE_PARTIAL, stream);
+        encode_partial_kernel<T, D><<<dim3(plan.enc.chunks, BH, lat_blocks), kLatentBlock, 0, stream>>>(
+            q, k, v, w.m_part, w.l_part, w.o_part, s.H, s.N, s.M, plan.enc.chunk_len, plan.enc.chunks,
+            scale * kLog2e);
+    }
+    if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
+    {
+        LaunchTimer t(KID_ENCODE_MERGE, stream);
+        const unsigned blocks = (unsigned)(((size_t)BH * s.M + 255) / 256);
+        encode_merge_kernel<D><<<blocks, 256, 0, stream>>>(w.m_part, w.l_part, w.o_part, z, lse_enc, BH, s.M,
+                                                          plan.enc.chunks);
+    }
+    return check_launch();
+}
+
+template <typename T, int D>
+int decode_impl(const flare_shape &s, const T *q, const T *k, const float *z, T *y, float scale,
+                hipStream_t stream)
+{
+    LaunchTimer t(KID_DECODE, stream);
+    token_pass_kernel<T, D, 0><<<dim3((s.N + kTokenBlock - 1) / kTokenBlock, s.B * s.H), kTokenBlock, 0, stream>>>(
+        q, k, z, y, nullptr, nullptr, nullptr, s.H, s.N, s.M, scale * kLog2e);
+    return check_launch();
+}
+
+template <typename T, int D>
+int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, const T *dy, const float *z,
+                  const float *lse_enc, float *dq, T *dk, T *dv, float scale, void *ws, hipStream_t stream)
+{
+    const ValuPlan plan = valu_plan(s);
+    BwdWs w;
+    bwd_layout(s, plan.bwd, ws, &w);
+    const int BH = s.B * s.H;
+    const float c2 = scale * kLog2e;
+    const int lat_blocks = (s.M + kLatentBlock - 1) / kLatentBlock;
+    const dim3 tok_grid((s.N + kTokenBlock - 1) / kTokenBlock, BH);
+    const dim3 lat_grid(plan.bwd.chunks, BH, lat_blocks);
+    const unsigned bhm_blocks = (unsigned)(((size_t)BH * s.M + 255) / 256);
+    {
+        LaunchTimer t(KID_BWD_TOKEN_STATS, stream);
+        token_pass_kernel<T, D, 1><<<tok_grid, kTokenBlock, 0, stream>>>(q, k, z, nullptr, dy, w.lse_dec2, w.delta,
+                                                                         s.H, s.N, s.M, c2);
+    }
+    if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
+    {
+        LaunchTimer t(KID_BWD_DZ_PARTIAL, stream);
+        dz_partial_kernel<T, D><<<lat_grid, kLatentBlock, 0, stream>>>(q, k, dy, w.lse_dec2, w.part, s.H, s.N, s.M,
+                                                                       plan.bwd.chunk_len, plan.bwd.chunks, c2);
+    }
+    if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
+    {
+        LaunchTimer t(KID_BWD_DZ_MERGE, stream);
+        dz_merge_kernel<D><<<bhm_blocks, 256, 0, stream>>>(w.part, z, w.dz, w.eps, BH, s.M, plan.bwd.chunks);
+    }
+    if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
+    {
+        LaunchTimer t(KID_BWD_DQ_PARTIAL, stream);
+        dq_partial_kernel<T, D><<<lat_grid, kLatentBlock, 0, stream>>>(q, k, v, dy, z, lse_enc, w.dz, w.eps,
+                                                                       w.lse_dec2, w.delta, w.part, s.H, s.N, s.M,
+                                                                       plan.bwd.chunk_len, plan.bwd.chunks, c2);
+    }
+    if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
+    {
+        LaunchTimer t(KID_BWD_DQ_REDUCE, stream);
+        const unsigned blocks = (unsigned)(((size_t)s.H * s.M + 255) / 256);
+        dq_reduce_kernel<D><<<blocks, 256, 0, stream>>>(w.part, dq, s.B, s.H, s.M, plan.bwd.chunks, scale);
+    }
+    if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
+    {
+        LaunchTimer t(KID_BWD_DKDV, stream);
+        dkdv_kernel<T, D><<<tok_grid, kTokenBlock, 0, stream>>>(q, k, v, dy, z, lse_enc, w.dz, w.eps, w.lse_dec2,
+                                                                w.delta, dk, dv, s.H, s.N, s.M, scale);
+    }
+    return check_launch();
+}
+
+// Dispatch on (dtype, d) to the template instances.
+#define FLARE_DISPATCH(s, CALL)                                                   \
+    do {                                                                          \
+        if ((s).dtype == FLARE_F32) {                                             \
+            typedef float T;                                                      \
+            switch ((s).d) {                                                      \
+                case 4: { constexpr int D = 4; return CALL; }                     \
+                case 8: { constexpr int D = 8; return CALL; }                     \
+                case 16: { constexpr int D = 16; return CALL; }                   \
+                case 32: { constexpr int D = 32; return CALL; }                   \
+            }                                                                     \
+        } else {                                                                  \
+            typedef bf16_t T;                                                     \
+            switch ((s).d) {                                                      \
+                case 4: { constexpr int D = 4; return CALL; }                     \
+                case 8: { constexpr int D = 8; return CALL; }                     \
+                case 16: { constexpr int D = 16; return CALL; }                   \
+                case 32: { constexpr int D = 32; return CALL; }                   \
+            }                                                                     \
+        }                                                                         \
+        return FLARE_EUNSUPPORTED;                                                \
+    } while (0)
+
+}  // namespace
+
+ValuPlan valu_plan(const flare_shape &s)
+{
+    ValuPlan p;
+    const int BH = s.B * s.H;
+    p.enc = plan_split(s.N, BH, 256, 2048);
+    p.bwd = plan_split(s.N, BH, 256, 2048);
+    p.fwd_bytes = fwd_layout(s, p.enc, nullptr, nullptr);
+    p.bwd_bytes = bwd_layout(s, p.bwd, nullptr, nullptr);
+    return p;
+}
+
+int valu_encode(const flare_shape &s, const void *q, const void *k, const void *v, float *z, float *lse_enc,
+                float scale, void *ws, hipStream_t stream)
+{
+    FLARE_DISPATCH(s, (encode_impl<T, D>(s, (const T *)q, (const T *)k, (const T *)v, z, lse_enc, scale, ws, stream)));
+}
+int valu_decode(const flare_shape &s, const void *q, const void *k, const float *z, void *y, float scale,
+                hipStream_t stream)
+{
+    FLARE_DISPATCH(s, (decode_impl<T, D>(s, (const T *)q, (const T *)k, z, (T *)y, scale, stream)));
+}
+int valu_backward(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy,
+                  const float *z, const float *lse_enc, float *dq, void *dk, void *dv, float scale, void *ws,
+                  hipStream_t stream)
+{
+    FLARE_DISPATCH(s, (backward_impl<T, D>(s, (const T *)q, (const T *)k, (const T *)v, (const T *)dy, z, lse_enc, dq,
+                                           (T *)dk, (T *)dv, scale, ws, stream)));
+}
+
+}  // namespace flare

@@ -1,0 +1,34 @@
+"""Helpers shared by the GPU parity tests (no method arithmetic here)."""
+import numpy as np
+
+# Tolerances on the max normwise relative error (per (b,h) slice, Frobenius norm):
+# fp32 path 1e-5; bf16 inputs with fp32 accumulation 2e-2.
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def slice_relerr(got, ref):
+    """max over leading-index slices [..., :, :] of ||got-ref||_F / ||ref||_F, in fp64."""
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    g = got.reshape(-1, got.shape[-2] * got.shape[-1])
+    r = ref.reshape(-1, ref.shape[-2] * ref.shape[-1])
+    num = np.linalg.norm(g - r, axis=1)
+    den = np.linalg.norm(r, axis=1)
+    return float(np.max(num / np.maximum(den, 1e-300)))
+
+
+def to_device(inp, names=("q", "k", "v", "dy")):
+    """numpy float32 arrays (already representable in the workload dtype) -> device tensors."""
+    import torch
+    dt = torch.float32 if inp["dtype"] == "f32" else torch.bfloat16
+    out = {}
+    for n in names:
+        if n in inp:
+            out[n] = torch.from_numpy(inp[n]).to(device="cuda", dtype=dt).contiguous()
+    return out
+
+
+def to_host(t):
+    import torch
+    return t.detach().to(torch.float32).cpu().numpy()

@@ -1,0 +1,63 @@
+"""The C-ABI library loads, exports every symbol include/flare.h declares, and rejects bad
+arguments on the host before anything is launched (no GPU needed, no compute calls)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2508_12594_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2508_12594_amd import build
+        build.build_library(verbose=False)
+    return binding.load()
+
+
+def test_header_symbols_are_exported(lib):
+    text = open(os.path.join(ROOT, "include", "flare.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = sorted(set(re.findall(r"\b(flare_[a-z_]+)\s*\(", text)))
+    assert declared == sorted(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_version_and_strerror(lib):
+    assert binding.version() >= 100
+    assert binding.strerror(0) == "success"
+    for code in (-1, -2, -3, -4, -5, -99):
+        assert len(binding.strerror(code)) > 0
+
+
+def test_workspace_bytes_and_shape_checks(lib):
+    f, b = binding.workspace_bytes(1, 8, 1000000, 256, 16, binding.FLARE_BF16)
+    assert 0 < f < 64 << 20 and b > 0
+    f1, _ = binding.workspace_bytes(1, 4, 1024, 64, 32, binding.FLARE_F32)
+    assert f1 > 0 and f1 % 256 == 0
+    bad = [(0, 1, 1, 1, 16, 0, -1), (1, 1, 1, 1, 5, 0, -2), (1, 1, 1, 1, 16, 7, -2), (70000, 1, 1, 1, 16, 0, -2)]
+    for B, H, N, M, d, dt, want in bad:
+        shp = binding.FlareShape(B, H, N, M, d, dt)
+        assert lib.flare_workspace_bytes(ctypes.byref(shp), None, None) == want
+    assert lib.flare_workspace_bytes(None, None, None) == -1
+
+
+def test_null_and_misaligned_pointers_are_rejected(lib):
+    shp = binding.FlareShape(1, 1, 8, 32, 16, binding.FLARE_F32)
+    p = ctypes.c_void_p(4096)        # never dereferenced: the checks fail first
+    odd = ctypes.c_void_p(4100)
+    assert lib.flare_forward(ctypes.byref(shp), None, p, p, p, p, p, ctypes.c_float(1), p, 1 << 20, None) == -1
+    assert lib.flare_forward(ctypes.byref(shp), p, p, p, None, p, p, ctypes.c_float(1), p, 1 << 20, None) == -1
+    assert lib.flare_forward(ctypes.byref(shp), p, odd, p, p, p, p, ctypes.c_float(1), p, 1 << 20, None) == -3
+    assert lib.flare_forward(ctypes.byref(shp), p, p, p, p, p, p, ctypes.c_float(1), p, 16, None) == -4
+    assert lib.flare_forward(ctypes.byref(shp), p, p, p, p, p, p, ctypes.c_float(1), None, 0, None) == -4
+    assert lib.flare_decode(ctypes.byref(shp), p, p, None, p, ctypes.c_float(1), None) == -1
+    assert lib.flare_backward(ctypes.byref(shp), p, p, p, None, None, p, p, p, p, p, ctypes.c_float(1), p,
+                              1 << 20, None) == -1
+    assert lib.flare_backward(ctypes.byref(shp), p, p, p, None, p, p, p, p, p, p, ctypes.c_float(1), p,
+                              16, None) == -4

@@ -1,0 +1,216 @@
+"""GPU parity: libflare.so (through its C ABI) against the fp64 CPU oracle, element by element,
+on the same seeded inputs.  Sizes here finish in seconds on the oracle yet span several
+tiles, several token chunks and ragged tails.  Full BASELINE sizes are in
+test_gpu_fullsize.py.
+
+Metric: max over (b,h) slices of ||T_gpu - T_ref||_F / ||T_ref||_F.  Bar: 1e-5 for the
+fp32 path, 2e-2 for bf16 inputs with fp32 accumulation.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2508_12594_amd import binding, synth
+from tests._util import TOL, slice_relerr, to_device, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print("[case] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+def _forward_case(oracle, inp, scale=None, tol=None):
+    import torch
+    scale = inp["scale"] if scale is None else scale
+    tol = TOL[inp["dtype"]] if tol is None else tol
+    dev = to_device(inp)
+    y, z, lse = binding.forward(dev["q"], dev["k"], dev["v"], scale)
+    torch.cuda.synchronize()
+    y_ref, z_ref, lse_ref = oracle.forward(inp["q"], inp["k"], inp["v"], scale)
+    e_y = slice_relerr(to_host(y), y_ref)
+    e_z = slice_relerr(to_host(z), z_ref)
+    e_l = float(np.max(np.abs(to_host(lse) - lse_ref)))
+    _say("   err y %.3e  z %.3e  lse(abs) %.3e  (tol %.0e)" % (e_y, e_z, e_l, tol))
+    assert e_y <= tol and e_z <= tol
+    assert e_l <= max(tol, 1e-4) * max(1.0, float(np.max(np.abs(lse_ref))))
+    return y, z, lse
+
+
+def _backward_case(oracle, inp, scale=None, tol=None, zero_dq_dk=False):
+    import torch
+    scale = inp["scale"] if scale is None else scale
+    tol = TOL[inp["dtype"]] if tol is None else tol
+    dev = to_device(inp)
+    y, z, lse = binding.forward(dev["q"], dev["k"], dev["v"], scale)
+    dq, dk, dv = binding.backward(dev["q"], dev["k"], dev["v"], dev["dy"], z, lse, scale)
+    torch.cuda.synchronize()
+    dq_ref, dk_ref, dv_ref = oracle.backward(inp["q"], inp["k"], inp["v"], inp["dy"], scale)
+    e_v = slice_relerr(to_host(dv), dv_ref)
+    if zero_dq_dk:
+        # the exact gradients vanish (e.g. N = 1: both softmaxes are constant in q and k), so
+        # measure dq and dk against the size of dv instead of against themselves
+        ref = float(np.linalg.norm(dv_ref))
+        assert float(np.linalg.norm(dq_ref)) <= 1e-12 * ref and float(np.linalg.norm(dk_ref)) <= 1e-12 * ref
+        e_q = float(np.linalg.norm(to_host(dq))) / ref
+        e_k = float(np.linalg.norm(to_host(dk))) / ref
+    else:
+        e_q = slice_relerr(to_host(dq), dq_ref)
+        e_k = slice_relerr(to_host(dk), dk_ref)
+    _say("   err dq %.3e  dk %.3e  dv %.3e  (tol %.0e)" % (e_q, e_k, e_v, tol))
+    assert e_q <= tol and e_k <= tol and e_v <= tol
+    return dq, dk, dv
+
+
+# ---- the five workloads, at sizes the oracle finishes in seconds -----------------------------
+FWD_CASES = [
+    # (cfg, overrides)
+    (1, dict()),                                # the fp32 workload at its full size
+    (1, dict(N=1000)),                          # ragged
+    (2, dict(B=2, N=3001)),                     # mesh, bf16, d=16, M=64
+    (3, dict(B=2, N=4096)),                     # bf16, d=32, M=128
+    (3, dict(B=1, N=777)),
+    (4, dict(N=10007)),                         # mesh, bf16, d=16, M=256, ragged
+    (5, dict(N=4099)),                          # bf16, d=32, M=256
+]
+
+
+@pytest.mark.parametrize("cfg,over", FWD_CASES)
+def test_forward_workloads(oracle, cfg, over):
+    _say("forward cfg%d %s" % (cfg, over))
+    inp = synth.make_inputs(cfg, with_dy=False, **over)
+    _forward_case(oracle, inp)
+
+
+def test_forward_scale_one(oracle):
+    """The paper's own setting: scale = 1 in both attention calls."""
+    for cfg, over in [(1, dict(N=515)), (2, dict(B=1, N=1030))]:
+        _say("forward scale=1 cfg%d %s" % (cfg, over))
+        inp = synth.make_inputs(cfg, with_dy=False, **over)
+        _forward_case(oracle, inp, scale=1.0)
+
+
+BWD_CASES = [
+    (1, dict()),
+    (1, dict(N=999, B=2)),
+    (2, dict(B=2, N=2050)),
+    (3, dict(B=3, N=1024)),
+    (4, dict(N=5003)),
+    (5, dict(N=3001)),
+]
+
+
+@pytest.mark.parametrize("cfg,over", BWD_CASES)
+def test_backward_workloads(oracle, cfg, over):
+    _say("backward cfg%d %s" % (cfg, over))
+    inp = synth.make_inputs(cfg, with_dy=True, **over)
+    _backward_case(oracle, inp)
+
+
+# ---- edge cases ---------------------------------------------------------------------------------
+EDGE_SHAPES = [
+    # B, H, N, M, d
+    (1, 1, 1, 32, 16),        # a single token: Y = v
+    (1, 2, 7, 32, 32),        # fewer tokens than one group
+    (2, 1, 63, 64, 16),
+    (1, 1, 65, 96, 16),       # M a multiple of 32 but not of 64
+    (1, 3, 257, 1, 16),       # one latent: Y_n = Z_1
+    (1, 1, 300, 33, 8),       # odd M, small d
+    (1, 2, 129, 300, 4),      # M above one latent block, d = 4
+    (1, 1, 40, 513, 32),      # three latent blocks
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", EDGE_SHAPES)
+def test_edge_shapes_forward_backward(oracle, shape, dtype):
+    B, H, N, M, d = shape
+    _say("edge %s %s" % (shape, dtype))
+    inp = synth.make_inputs(1, B=B, H=H, N=N, M=M, d=d, dtype=dtype, with_dy=True, seed=1234 + N + M)
+    y, _, _ = _forward_case(oracle, inp)
+    _backward_case(oracle, inp, zero_dq_dk=(N == 1))
+    if N == 1:
+        assert slice_relerr(to_host(y), inp["v"]) <= (1e-6 if dtype == "f32" else 4e-3)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_sharp_softmax_stress(oracle, dtype):
+    """Scores eight times larger: nearly one-hot softmaxes, the running max moves a lot."""
+    _say("stress gain 8 %s" % dtype)
+    inp = synth.make_inputs(1, B=1, H=2, N=2500, M=64, d=16, dtype=dtype, with_dy=True, score_gain=8.0)
+    _forward_case(oracle, inp)
+    _backward_case(oracle, inp, tol=TOL[dtype] * (3 if dtype == "f32" else 1))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_large_score_offsets(oracle, dtype):
+    """Scores far from zero (|S| ~ 100 and a per-latent spread of hundreds): nothing may overflow."""
+    _say("large offsets %s" % dtype)
+    inp = synth.make_inputs(1, B=1, H=1, N=1500, M=64, d=16, dtype=dtype, with_dy=False)
+    q, k = inp["q"].copy(), inp["k"].copy()
+    k[..., 0] = 4.0                                   # S[m][n] gets + scale * 4 * q[m][0]
+    q[..., 0] = np.linspace(-150.0, 150.0, q.shape[1], dtype=np.float32)[None, :]
+    if dtype == "bf16":
+        q, k = synth.bf16_round(q), synth.bf16_round(k)
+    inp["q"], inp["k"] = q, k
+    # a score of magnitude |S| carries about |S| * 2^-23 of fp32 rounding before the exponential
+    _forward_case(oracle, inp, tol=1e-4 if dtype == "f32" else None)
+
+
+def test_constant_v_gives_constant_y():
+    import torch
+    inp = synth.make_inputs(2, B=1, N=2000, with_dy=False)
+    dev = to_device(inp)
+    v = torch.full_like(dev["v"], 1.5)
+    y, z, _ = binding.forward(dev["q"], dev["k"], v, inp["scale"])
+    torch.cuda.synchronize()
+    assert float((y.float() - 1.5).abs().max()) <= 1.5 * 2 ** -7
+    assert float((z - 1.5).abs().max()) <= 1e-5
+
+
+@pytest.mark.parametrize("cfg,over", [(1, dict()), (2, dict(B=1, N=5000)), (5, dict(N=2048))])
+def test_bit_reproducible(cfg, over):
+    """Same inputs, same shape: identical bits on every run (fixed-order reductions)."""
+    import torch
+    inp = synth.make_inputs(cfg, with_dy=True, **over)
+    dev = to_device(inp)
+    outs = []
+    for _ in range(2):
+        y, z, lse = binding.forward(dev["q"], dev["k"], dev["v"], inp["scale"])
+        dq, dk, dv = binding.backward(dev["q"], dev["k"], dev["v"], dev["dy"], z, lse, inp["scale"])
+        torch.cuda.synchronize()
+        outs.append([t.clone() for t in (y, z, lse, dq, dk, dv)])
+    for a, b in zip(*outs):
+        assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
+
+
+def test_encode_decode_equal_forward():
+    import torch
+    inp = synth.make_inputs(3, B=1, N=1111, with_dy=False)
+    dev = to_device(inp)
+    y, z, lse = binding.forward(dev["q"], dev["k"], dev["v"], inp["scale"])
+    z2, lse2 = binding.encode(dev["q"], dev["k"], dev["v"], inp["scale"])
+    y2 = binding.decode(dev["q"], dev["k"], z2, inp["scale"])
+    torch.cuda.synchronize()
+    assert torch.equal(z, z2) and torch.equal(lse, lse2) and torch.equal(y.view(torch.uint8), y2.view(torch.uint8))
+
+
+def test_side_stream_and_caller_buffers():
+    """Runs on a caller-chosen stream with caller-owned outputs and workspace."""
+    import torch
+    inp = synth.make_inputs(1, with_dy=False)
+    dev = to_device(inp)
+    y0, z0, l0 = binding.forward(dev["q"], dev["k"], dev["v"], inp["scale"])
+    torch.cuda.synchronize()
+    f, _ = binding.workspace_bytes(inp["B"], inp["H"], inp["N"], inp["M"], inp["d"], binding.FLARE_F32)
+    ws = torch.empty(f, dtype=torch.uint8, device="cuda")
+    y, z, l = torch.empty_like(y0), torch.empty_like(z0), torch.empty_like(l0)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        binding.forward(dev["q"], dev["k"], dev["v"], inp["scale"], y=y, z=z, lse_enc=l, workspace=ws, stream=s)
+    s.synchronize()
+    assert torch.equal(y, y0) and torch.equal(z, z0) and torch.equal(l, l0)
+    with pytest.raises(binding.FlareError):
+        binding.forward(dev["q"], dev["k"], dev["v"], inp["scale"], workspace=ws[:64])
