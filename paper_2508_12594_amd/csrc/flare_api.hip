@@ -93,7 +93,7 @@ int flare_workspace_bytes(const flare_shape *shape, size_t *fwd_bytes, size_t *b
     const int rc = check_shape(shape);
     if (rc != FLARE_OK) return rc;
     const ValuPlan p = valu_plan(*shape);
-    if (fwd_bytes) *fwd_bytes = p.fwd_bytes;
+    if (fwd_bytes) *fwd_bytes = mfma_supported(*shape) ? mfma_fwd_bytes(*shape) : p.fwd_bytes;
     if (bwd_bytes) *bwd_bytes = p.bwd_bytes;
     return FLARE_OK;
 }
@@ -110,6 +110,8 @@ int flare_encode(const flare_shape *shape, const void *q_lat, const void *k, con
     size_t need = 0;
     flare_workspace_bytes(shape, &need, nullptr);
     if (!workspace || workspace_bytes < need) return FLARE_EWORKSPACE;
+    if (mfma_supported(*shape))
+        return mfma_encode(*shape, q_lat, k, v, z, lse_enc, scale, workspace, static_cast<hipStream_t>(stream));
     return valu_encode(*shape, q_lat, k, v, z, lse_enc, scale, workspace, static_cast<hipStream_t>(stream));
 }
 
@@ -120,6 +122,8 @@ int flare_decode(const flare_shape *shape, const void *q_lat, const void *k, con
     if (rc != FLARE_OK) return rc;
     if (!q_lat || !k || !z || !y) return FLARE_EINVAL;
     if (!aligned16(q_lat) || !aligned16(k) || !aligned16(z) || !aligned16(y)) return FLARE_EALIGN;
+    if (mfma_supported(*shape))
+        return mfma_decode(*shape, q_lat, k, z, y, scale, static_cast<hipStream_t>(stream));
     return valu_decode(*shape, q_lat, k, z, y, scale, static_cast<hipStream_t>(stream));
 }
 

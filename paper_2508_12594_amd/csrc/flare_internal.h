@@ -49,6 +49,14 @@ struct ValuPlan {
 };
 ValuPlan valu_plan(const flare_shape &s);
 
+// Carves the encode workspace for sp.chunks partial slots per (b,h); returns its size in bytes.
+// Any of the output pointers may be NULL (then ws is not touched).
+size_t valu_fwd_layout(const flare_shape &s, const Split &sp, void *ws, float **m_part, float **l_part,
+                       float **o_part);
+// Fixed-order merge of `parts` partial slots per (b,h) into z and lse_enc (shared by both paths).
+int launch_encode_merge(const flare_shape &s, const float *m_part, const float *l_part, const float *o_part,
+                        float *z, float *lse_enc, int parts, hipStream_t stream);
+
 int valu_encode(const flare_shape &s, const void *q, const void *k, const void *v, float *z,
                 float *lse_enc, float scale, void *ws, hipStream_t stream);
 int valu_decode(const flare_shape &s, const void *q, const void *k, const float *z, void *y,
@@ -56,5 +64,18 @@ int valu_decode(const flare_shape &s, const void *q, const void *k, const float 
 int valu_backward(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy,
                   const float *z, const float *lse_enc, float *dq, void *dk, void *dv, float scale,
                   void *ws, hipStream_t stream);
+
+// ---- bf16 matrix-core path (d in {16,32}; M = 32 or a multiple of 64 up to 256) --------------
+struct MfmaPlan {
+    Split enc;   // token chunks of the encode (one workgroup each)
+    int parts;   // partial slots per (b,h) = chunks * token groups per workgroup
+};
+bool mfma_supported(const flare_shape &s);
+MfmaPlan mfma_plan(const flare_shape &s);
+size_t mfma_fwd_bytes(const flare_shape &s);
+int mfma_encode(const flare_shape &s, const void *q, const void *k, const void *v, float *z,
+                float *lse_enc, float scale, void *ws, hipStream_t stream);
+int mfma_decode(const flare_shape &s, const void *q, const void *k, const float *z, void *y,
+                float scale, hipStream_t stream);
 
 }  // namespace flare

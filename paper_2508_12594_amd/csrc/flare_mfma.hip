@@ -1,0 +1,527 @@
+// Matrix-core (MFMA) kernels of the FLARE mixer for bf16 storage on gfx950.
+//
+// Both kernels are built from v_mfma_f32_32x32x16_bf16 and keep the M x N weights in
+// registers only.  The softmax work per score is one v_exp_f32, half a v_cvt_pk_bf16_f32 and
+// half a v_max3_f32: the score MFMA already delivers  S2 - stabiliser  because
+//   * q is pre-multiplied by scale*log2(e) and split into two bf16 terms (hi + lo), so the
+//     product is exact to ~2^-17 and the exponential is a bare 2^x;
+//   * the stabiliser enters through the MFMA's C operand (a register tuple holding -c).
+// The probabilities are rounded to bf16 once and feed the second MFMA straight from the
+// accumulator layout: the contraction index of the second product (tokens in the encode,
+// latents in the decode) is order-free, so the value operand is simply loaded in the
+// permuted order the accumulator layout dictates.  Row sums come out of the same MFMA from
+// a row of ones appended to the value operand, so numerator and denominator use identical
+// rounded weights.
+//
+// Register layouts of v_mfma_f32_32x32x16_bf16 (lane l, l32 = l % 32, hh = l / 32):
+//   A operand: row l32, contraction slots 8*hh .. 8*hh+7 (8 bf16 = 4 VGPRs)
+//   B operand: column l32, contraction slots 8*hh .. 8*hh+7
+//   C/D:       column l32, register r (0..15) holds row 8*(r/4) + 4*hh + r%4
+//
+// Equations: Section 3.1, Eq. flare_encode / Eq. flare_decode; Appendix E.
+#include "flare_internal.h"
+
+namespace flare {
+namespace {
+
+typedef uint16_t bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 w) { return __builtin_bit_cast(bf16x8, w); }
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+__device__ __forceinline__ uint32_t rne_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+// two fp32 -> packed bf16 (low half = a, high half = b), round to nearest even: one
+// v_cvt_pk_bf16_f32.  Left to the compiler (no inline asm) so that it keeps the wait state a
+// VALU read of a transcendental result needs.
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t cvt_pk_bf16(float a, float b)
+{
+    f32x2 v;
+    v[0] = a;
+    v[1] = b;
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x16 splat16(float x)
+{
+    f32x16 v;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) v[i] = x;
+    return v;
+}
+__device__ __forceinline__ float max16(const f32x16 &s, float m)
+{
+#pragma unroll
+    for (int i = 0; i < 16; i += 2) m = fmaxf(m, fmaxf(s[i], s[i + 1]));
+    return m;
+}
+// 16 accumulator values -> 16 packed bf16 probabilities 2^x (two B operands of 8)
+__device__ __forceinline__ void exp_pack(const f32x16 &dlt, bf16x8 &p0, bf16x8 &p1)
+{
+    u32x4 w0, w1;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        w0[i] = cvt_pk_bf16(fast_exp2(dlt[2 * i]), fast_exp2(dlt[2 * i + 1]));
+        w1[i] = cvt_pk_bf16(fast_exp2(dlt[8 + 2 * i]), fast_exp2(dlt[8 + 2 * i + 1]));
+    }
+    p0 = as_bf16x8(w0);
+    p1 = as_bf16x8(w1);
+}
+// Contraction slot (8*hh + i) of k-step s2 (0 or 1) of a 32-wide tile maps to this index within
+// the tile: the row that accumulator register 8*s2 + i holds.
+__device__ __forceinline__ int perm_index(int s2, int hh, int i) { return 16 * s2 + 8 * (i / 4) + 4 * hh + (i % 4); }
+
+// Latent-query operand for one 32-latent tile: row/column = latent, contraction over d.
+// Lane half hh covers d-indices (D/2)*hh + 8*s + i for k-step s.  The same mapping is used for
+// the key operand.  PRE: multiply by c2 and split into hi + lo bf16 terms; else raw bits (sign
+// flipped when c2 < 0 so that the kernel can work with |c2|).
+template <int D, bool PRE>
+__device__ __forceinline__ void load_q_operand(const bf16_t *__restrict__ q_row, int hh, float c2, bool flip,
+                                               bf16x8 (&hi)[D / 16], bf16x8 (&lo)[D / 16])
+{
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s) {
+        const u32x4 w = *reinterpret_cast<const u32x4 *>(q_row + (D / 2) * hh + 8 * s);
+        if constexpr (PRE) {
+            u32x4 wh, wl;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float a = bf16_lo(w[i]) * c2, b = bf16_hi(w[i]) * c2;
+                const uint32_t ah = rne_bf16(a), bh = rne_bf16(b);
+                const float ar = a - __uint_as_float(ah << 16), br = b - __uint_as_float(bh << 16);
+                wh[i] = ah | (bh << 16);
+                wl[i] = rne_bf16(ar) | (rne_bf16(br) << 16);
+            }
+            hi[s] = as_bf16x8(wh);
+            lo[s] = as_bf16x8(wl);
+        } else {
+            u32x4 wf = w;
+            if (flip) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) wf[i] = w[i] ^ 0x80008000u;
+            }
+            hi[s] = as_bf16x8(wf);
+            lo[s] = as_bf16x8(wf);
+        }
+    }
+}
+
+// ============================================================================================
+// Decode.  One wave owns 32 tokens at a time and all M latents:
+//   pass 1: scores from the hi terms only -> per-token maximum b (any value near the maximum
+//           is a valid stabiliser);
+//   pass 2: scores again with C = -b, 2^x, pack, and Y^T += Zaug^T . E with Zaug = [Z | 1].
+// Q (as A operand) and Z^T (as A operand, latents in the permuted order) live in registers
+// for the whole kernel; K streams from HBM straight into the B-operand layout; no LDS.
+// ============================================================================================
+template <int D, int MT, bool PRE>
+__global__ __launch_bounds__(256) void decode_mfma_kernel(
+    const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const float *__restrict__ z,
+    bf16_t *__restrict__ y, int H, int N, float c2)
+{
+    constexpr int KS = D / 16;   // k-steps of the score product
+    constexpr int HV = D / 16;   // 16-wide column groups of Z, each with its own ones row
+    constexpr int M = 32 * MT;
+    const int lane = threadIdx.x & 63, l32 = lane & 31, hh = lane >> 5;
+    const int wave = threadIdx.x >> 6;
+    const int bh = blockIdx.y, h = bh % H;
+    const bool flip = c2 < 0.f;
+    const float ac2 = PRE ? c2 : fabsf(c2);
+
+    bf16x8 qh[MT][KS], ql[MT][KS];
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+        load_q_operand<D, PRE>(q + ((size_t)h * M + 32 * t + l32) * D, hh, c2, flip, qh[t], ql[t]);
+
+    // Zaug^T operand: row l32 (< 16: column 16*hv + l32 of Z; 16: ones; else zero)
+    bf16x8 zt[HV][2 * MT];
+    {
+        const float *zb = z + (size_t)bh * M * D;
+#pragma unroll
+        for (int hv = 0; hv < HV; ++hv)
+#pragma unroll
+            for (int s = 0; s < 2 * MT; ++s) {
+                u32x4 w;
+#pragma unroll
+                for (int i = 0; i < 8; i += 2) {
+                    float a, b;
+                    if (l32 < 16) {
+                        a = zb[(size_t)(32 * (s / 2) + perm_index(s % 2, hh, i)) * D + 16 * hv + l32];
+                        b = zb[(size_t)(32 * (s / 2) + perm_index(s % 2, hh, i + 1)) * D + 16 * hv + l32];
+                    } else {
+                        a = b = (l32 == 16) ? 1.f : 0.f;
+                    }
+                    w[i / 2] = rne_bf16(a) | (rne_bf16(b) << 16);
+                }
+                zt[hv][s] = as_bf16x8(w);
+            }
+    }
+
+    const bf16_t *kb = k + (size_t)bh * N * D;
+    bf16_t *yb = y + (size_t)bh * N * D;
+    const int tiles = (N + 31) / 32;
+    const int stride = gridDim.x * 4;
+    for (int tile = blockIdx.x * 4 + wave; tile < tiles; tile += stride) {
+        const int n = tile * 32 + l32;
+        const int nld = min(n, N - 1);
+        bf16x8 kt[KS];
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+            kt[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(kb + (size_t)nld * D + (D / 2) * hh + 8 * s));
+
+        // pass 1: per-token maximum over the latents
+        float mx = -INFINITY;
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            f32x16 s = splat16(0.f);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) s = mfma(qh[t][ks], kt[ks], s);
+            mx = max16(s, mx);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float b2 = PRE ? mx : mx * ac2;
+        const f32x16 cneg = splat16(PRE ? -b2 : 0.f);
+
+        // pass 2
+        f32x16 acc[HV];
+#pragma unroll
+        for (int hv = 0; hv < HV; ++hv) acc[hv] = splat16(0.f);
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            f32x16 s = cneg;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) s = mfma(qh[t][ks], kt[ks], s);
+            if constexpr (PRE) {
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) s = mfma(ql[t][ks], kt[ks], s);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) s[i] = fmaf(s[i], ac2, -b2);
+            }
+            bf16x8 p0, p1;
+            exp_pack(s, p0, p1);
+#pragma unroll
+            for (int hv = 0; hv < HV; ++hv) {
+                acc[hv] = mfma(zt[hv][2 * t], p0, acc[hv]);
+                acc[hv] = mfma(zt[hv][2 * t + 1], p1, acc[hv]);
+            }
+        }
+        // row 16 (register 8 of the lower lane half) is the softmax denominator
+        const float den = __shfl(acc[0][8], l32);
+        const float inv = 1.f / den;
+        if (n < N) {
+#pragma unroll
+            for (int hv = 0; hv < HV; ++hv) {
+                u32x2 w0, w1;
+                w0[0] = cvt_pk_bf16(acc[hv][0] * inv, acc[hv][1] * inv);
+                w0[1] = cvt_pk_bf16(acc[hv][2] * inv, acc[hv][3] * inv);
+                w1[0] = cvt_pk_bf16(acc[hv][4] * inv, acc[hv][5] * inv);
+                w1[1] = cvt_pk_bf16(acc[hv][6] * inv, acc[hv][7] * inv);
+                *reinterpret_cast<u32x2 *>(yb + (size_t)n * D + 16 * hv + 4 * hh) = w0;
+                *reinterpret_cast<u32x2 *>(yb + (size_t)n * D + 16 * hv + 8 + 4 * hh) = w1;
+            }
+        }
+    }
+}
+
+// ============================================================================================
+// Encode partials.  A workgroup has 4 waves; wave w works on latent group w % G (NB tiles of 32
+// latents) and on every TG-th 32-token tile of the chunk starting at tile w / G.  Per tile:
+//   S2^T - c = K . Q'^T + C  (rows = tokens, columns = latents, C holds -c per latent),
+//   lazy online softmax: c moves only when a score exceeds it by more than kLazy (or on the
+//   first tile), then O and C are rescaled; 2^x, pack; O^T += Vaug^T . P^T, Vaug = [V | 1].
+// V^T is formed through a wave-private LDS tile (no workgroup barrier anywhere).
+// Output per wave: (c, row sums, unnormalised O) for its latents = one partial slot.
+// ============================================================================================
+constexpr float kLazy = 16.f;
+constexpr int kVtStride = 36;   // uint16 per LDS row: 32 tokens + 4 pad (72 B, conflict-free b64 reads)
+
+template <int D, int NB, bool PRE>
+__global__ __launch_bounds__(256) void encode_mfma_kernel(
+    const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
+    float *__restrict__ m_part, float *__restrict__ l_part, float *__restrict__ o_part,
+    int H, int N, int M, int chunk_len, int parts, int G, int TG, float c2)
+{
+    constexpr int KS = D / 16;
+    constexpr int HV = D / 16;
+    constexpr int ROWS = D + 2;   // V^T rows, then a row of ones, then a row of zeros
+    __shared__ __attribute__((aligned(16))) uint16_t vt_all[4][ROWS * kVtStride];
+
+    const int lane = threadIdx.x & 63, l32 = lane & 31, hh = lane >> 5;
+    const int wave = threadIdx.x >> 6;
+    const int g = wave % G, tg = wave / G;
+    const int bh = blockIdx.y, h = bh % H, chunk = blockIdx.x;
+    const bool flip = c2 < 0.f;
+    const float ac2 = PRE ? c2 : fabsf(c2);
+    uint16_t *vt = vt_all[wave];
+    if (tg >= TG) return;   // workgroups with G = 3 have one idle wave slot at most; no barriers are used
+
+    // constant rows of the value operand
+    if (lane < kVtStride) {
+        vt[D * kVtStride + lane] = 0x3f80;
+        vt[(D + 1) * kVtStride + lane] = 0;
+    }
+
+    const int lat0 = 32 * NB * g;
+    bf16x8 qh[NB][KS], ql[NB][KS];
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+        load_q_operand<D, PRE>(q + ((size_t)h * M + lat0 + 32 * b + l32) * D, hh, c2, flip, qh[b], ql[b]);
+
+    const bf16_t *kb = k + (size_t)bh * N * D;
+    const bf16_t *vb = v + (size_t)bh * N * D;
+    const int n0 = chunk * chunk_len;
+    const int n1 = min(N, n0 + chunk_len);
+    const int tiles = (n1 - n0 + 31) / 32;
+
+    float c[NB];
+    f32x16 cneg[NB], o[NB][HV];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        c[b] = 0.f;
+        cneg[b] = splat16(0.f);
+#pragma unroll
+        for (int hv = 0; hv < HV; ++hv) o[b][hv] = splat16(0.f);
+    }
+    bool first = true;
+
+    // row of the value operand this lane supplies for column group hv
+    int vrow[HV];
+#pragma unroll
+    for (int hv = 0; hv < HV; ++hv) vrow[hv] = (l32 < 16) ? 16 * hv + l32 : (l32 == 16 ? D : D + 1);
+
+    for (int it = tg; it < tiles; it += TG) {
+        const int tok0 = n0 + 32 * it;
+        // keys: A operand, row = token
+        const int nk = min(tok0 + l32, N - 1);
+        bf16x8 kt[KS];
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+            kt[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(kb + (size_t)nk * D + (D / 2) * hh + 8 * s));
+        // values: 32 tokens x D, 16 B pieces, written transposed into the wave's LDS tile
+        constexpr int PIECES = D / 8;          // 16-byte pieces per token row
+        constexpr int LOADS = PIECES / 2;      // pieces per lane (64 lanes cover 32 tokens x 2 pieces)
+        u32x4 vraw[LOADS];
+        const int vtok = lane >> 1;
+        const int nv = min(tok0 + vtok, N - 1);
+#pragma unroll
+        for (int j = 0; j < LOADS; ++j)
+            vraw[j] = *reinterpret_cast<const u32x4 *>(vb + (size_t)nv * D + 8 * ((lane & 1) * LOADS + j));
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // earlier reads of the tile are done
+#pragma unroll
+        for (int j = 0; j < LOADS; ++j) {
+            const int d0 = 8 * ((lane & 1) * LOADS + j);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                vt[(d0 + 2 * e) * kVtStride + vtok] = (uint16_t)(vraw[j][e] & 0xffffu);
+                vt[(d0 + 2 * e + 1) * kVtStride + vtok] = (uint16_t)(vraw[j][e] >> 16);
+            }
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the tile is written (same wave, in order)
+        bf16x8 va[HV][2];
+#pragma unroll
+        for (int hv = 0; hv < HV; ++hv)
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+                const uint16_t *row = vt + vrow[hv] * kVtStride + 16 * s2 + 4 * hh;
+                const u32x2 a = *reinterpret_cast<const u32x2 *>(row);
+                const u32x2 b = *reinterpret_cast<const u32x2 *>(row + 8);
+                u32x4 w;
+                w[0] = a[0]; w[1] = a[1]; w[2] = b[0]; w[3] = b[1];
+                va[hv][s2] = as_bf16x8(w);
+            }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+
+        const bool partial = tok0 + 32 > n1;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            f32x16 s = cneg[b];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) s = mfma(kt[ks], qh[b][ks], s);
+            if constexpr (PRE) {
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) s = mfma(kt[ks], ql[b][ks], s);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) s[i] = fmaf(s[i], ac2, -c[b]);
+            }
+            if (partial) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (tok0 + 8 * (r / 4) + 4 * hh + (r % 4) >= n1) s[r] = -INFINITY;
+            }
+            float mx = max16(s, -INFINITY);
+            mx = fmaxf(mx, __shfl_xor(mx, 32));   // both lane halves hold tokens of the same latent
+            if (first || __any(mx > kLazy)) {
+                const float shift = first ? mx : fmaxf(mx, 0.f);
+                if (!first) {
+                    const float f = fast_exp2(-shift);
+#pragma unroll
+                    for (int hv = 0; hv < HV; ++hv)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) o[b][hv][i] *= f;
+                }
+                c[b] += shift;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) s[i] -= shift;
+                if constexpr (PRE) cneg[b] = splat16(-c[b]);
+            }
+            bf16x8 p0, p1;
+            exp_pack(s, p0, p1);
+#pragma unroll
+            for (int hv = 0; hv < HV; ++hv) {
+                o[b][hv] = mfma(va[hv][0], p0, o[b][hv]);
+                o[b][hv] = mfma(va[hv][1], p1, o[b][hv]);
+            }
+        }
+        first = false;
+    }
+
+    // partial slot of this wave: (bh, chunk*TG + tg), latents lat0 .. lat0 + 32*NB
+    const size_t part = (size_t)bh * parts + (size_t)chunk * TG + tg;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        const size_t slot = part * M + lat0 + 32 * b + l32;
+        if (hh == 0) {
+            m_part[slot] = first ? -INFINITY : c[b];
+            l_part[slot] = o[b][0][8];
+        }
+#pragma unroll
+        for (int hv = 0; hv < HV; ++hv) {
+            float4 lo4 = make_float4(o[b][hv][0], o[b][hv][1], o[b][hv][2], o[b][hv][3]);
+            float4 hi4 = make_float4(o[b][hv][4], o[b][hv][5], o[b][hv][6], o[b][hv][7]);
+            *reinterpret_cast<float4 *>(o_part + slot * D + 16 * hv + 4 * hh) = lo4;
+            *reinterpret_cast<float4 *>(o_part + slot * D + 16 * hv + 8 + 4 * hh) = hi4;
+        }
+    }
+}
+
+inline int check_launch() { return hipGetLastError() == hipSuccess ? FLARE_OK : FLARE_ELAUNCH; }
+
+// latent-group geometry of the encode for a given M
+struct EncGeom { int NB, G, TG, threads; };
+EncGeom enc_geom(int M)
+{
+    EncGeom e;
+    if (M == 32) { e.NB = 1; e.G = 1; }
+    else { e.NB = 2; e.G = M / 64; }
+    e.TG = (e.G == 3) ? 1 : 4 / e.G;
+    e.threads = 64 * e.G * e.TG;
+    return e;
+}
+
+constexpr int kEncodeTargetBlocks = 768;   // three 4-wave workgroups per CU
+constexpr int kDecodeTargetBlocks = 768;
+
+}  // namespace
+
+bool mfma_supported(const flare_shape &s)
+{
+    if (s.dtype != FLARE_BF16) return false;
+    if (s.d != 16 && s.d != 32) return false;
+    if (s.M == 32) return true;
+    return s.M % 64 == 0 && s.M <= 256;
+}
+
+MfmaPlan mfma_plan(const flare_shape &s)
+{
+    MfmaPlan p;
+    const EncGeom e = enc_geom(s.M);
+    const int BH = s.B * s.H;
+    // each chunk gives every token group at least 8 tiles of 32 tokens
+    p.enc = plan_split(s.N, BH, 256 * e.TG, kEncodeTargetBlocks);
+    p.parts = p.enc.chunks * e.TG;
+    return p;
+}
+
+size_t mfma_fwd_bytes(const flare_shape &s)
+{
+    const MfmaPlan p = mfma_plan(s);
+    Split sp;
+    sp.chunks = p.parts;
+    sp.chunk_len = 0;
+    return valu_fwd_layout(s, sp, nullptr, nullptr, nullptr, nullptr);
+}
+
+int mfma_encode(const flare_shape &s, const void *q, const void *k, const void *v, float *z, float *lse_enc,
+                float scale, void *ws, hipStream_t stream)
+{
+    const MfmaPlan p = mfma_plan(s);
+    const EncGeom e = enc_geom(s.M);
+    Split sp;
+    sp.chunks = p.parts;
+    sp.chunk_len = 0;
+    float *m_part, *l_part, *o_part;
+    valu_fwd_layout(s, sp, ws, &m_part, &l_part, &o_part);
+    const int BH = s.B * s.H;
+    const float c2 = scale * kLog2e;
+    const dim3 grid(p.enc.chunks, BH);
+    const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *vv = (const bf16_t *)v;
+    {
+        LaunchTimer t(KID_ENCODE_PARTIAL, stream);
+#define FLARE_ENC(DD, NBB)                                                                                  \
+    encode_mfma_kernel<DD, NBB, true><<<grid, e.threads, 0, stream>>>(qq, kk, vv, m_part, l_part, o_part, s.H, \
+                                                                      s.N, s.M, p.enc.chunk_len, p.parts, e.G, e.TG, c2)
+        if (s.d == 16 && e.NB == 1) FLARE_ENC(16, 1);
+        else if (s.d == 16) FLARE_ENC(16, 2);
+        else if (e.NB == 1) FLARE_ENC(32, 1);
+        else FLARE_ENC(32, 2);
+#undef FLARE_ENC
+    }
+    if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
+    return launch_encode_merge(s, m_part, l_part, o_part, z, lse_enc, p.parts, stream);
+}
+
+int mfma_decode(const flare_shape &s, const void *q, const void *k, const float *z, void *y, float scale,
+                hipStream_t stream)
+{
+    const int BH = s.B * s.H;
+    const int tiles = (s.N + 31) / 32;
+    int blocks = (kDecodeTargetBlocks + BH - 1) / BH;
+    if (blocks > (tiles + 3) / 4) blocks = (tiles + 3) / 4;
+    const dim3 grid(blocks, BH);
+    const float c2 = scale * kLog2e;
+    const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k;
+    bf16_t *yy = (bf16_t *)y;
+    LaunchTimer t(KID_DECODE, stream);
+#define FLARE_DEC(DD, MTT, PREE) \
+    decode_mfma_kernel<DD, MTT, PREE><<<grid, 256, 0, stream>>>(qq, kk, z, yy, s.H, s.N, c2)
+    const int MT = s.M / 32;
+    if (s.d == 16) {
+        switch (MT) {
+            case 1: FLARE_DEC(16, 1, true); break;
+            case 2: FLARE_DEC(16, 2, true); break;
+            case 4: FLARE_DEC(16, 4, true); break;
+            case 6: FLARE_DEC(16, 6, true); break;
+            case 8: FLARE_DEC(16, 8, true); break;
+            default: return FLARE_EUNSUPPORTED;
+        }
+    } else {
+        switch (MT) {
+            case 1: FLARE_DEC(32, 1, true); break;
+            case 2: FLARE_DEC(32, 2, true); break;
+            case 4: FLARE_DEC(32, 4, true); break;
+            case 6: FLARE_DEC(32, 6, false); break;
+            case 8: FLARE_DEC(32, 8, false); break;
+            default: return FLARE_EUNSUPPORTED;
+        }
+    }
+#undef FLARE_DEC
+    return check_launch();
+}
+
+}  // namespace flare

@@ -449,22 +449,8 @@ __global__ __launch_bounds__(kTokenBlock) void dkdv_kernel(
 // ---- workspace carving --------------------------------------------------------------------
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-struct FwdWs { float *m_part, *l_part, *o_part; };
 struct BwdWs { float *lse_dec2, *delta, *part, *dz, *eps; };
 
-size_t fwd_layout(const flare_shape &s, const Split &sp, void *ws, FwdWs *out)
-{
-    const size_t slots = (size_t)s.B * s.H * sp.chunks * s.M;
-    size_t off = 0;
-    char *base = static_cast<char *>(ws);
-    if (out) out->m_part = reinterpret_cast<float *>(base + off);
-    off += align256(slots * 4);
-    if (out) out->l_part = reinterpret_cast<float *>(base + off);
-    off += align256(slots * 4);
-    if (out) out->o_part = reinterpret_cast<float *>(base + off);
-    off += align256(slots * s.d * 4);
-    return off;
-}
 size_t bwd_layout(const flare_shape &s, const Split &sp, void *ws, BwdWs *out)
 {
     const size_t BH = (size_t)s.B * s.H;
@@ -490,24 +476,17 @@ int encode_impl(const flare_shape &s, const T *q, const T *k, const T *v, float 
                 float scale, void *ws, hipStream_t stream)
 {
     const ValuPlan plan = valu_plan(s);
-    FwdWs w;
-    fwd_layout(s, plan.enc, ws, &w);
+    float *m_part, *l_part, *o_part;
+    valu_fwd_layout(s, plan.enc, ws, &m_part, &l_part, &o_part);
     const int BH = s.B * s.H;
     const int lat_blocks = (s.M + kLatentBlock - 1) / kLatentBlock;
     {
         LaunchTimer t(KID_ENCODE_PARTIAL, stream);
         encode_partial_kernel<T, D><<<dim3(plan.enc.chunks, BH, lat_blocks), kLatentBlock, 0, stream>>>(
-            q, k, v, w.m_part, w.l_part, w.o_part, s.H, s.N, s.M, plan.enc.chunk_len, plan.enc.chunks,
-            scale * kLog2e);
+            q, k, v, m_part, l_part, o_part, s.H, s.N, s.M, plan.enc.chunk_len, plan.enc.chunks, scale * kLog2e);
     }
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
-    {
-        LaunchTimer t(KID_ENCODE_MERGE, stream);
-        const unsigned blocks = (unsigned)(((size_t)BH * s.M + 255) / 256);
-        encode_merge_kernel<D><<<blocks, 256, 0, stream>>>(w.m_part, w.l_part, w.o_part, z, lse_enc, BH, s.M,
-                                                          plan.enc.chunks);
-    }
-    return check_launch();
+    return launch_encode_merge(s, m_part, l_part, o_part, z, lse_enc, plan.enc.chunks, stream);
 }
 
 template <typename T, int D>
@@ -596,13 +575,44 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
 
 }  // namespace
 
+size_t valu_fwd_layout(const flare_shape &s, const Split &sp, void *ws, float **m_part, float **l_part,
+                       float **o_part)
+{
+    const size_t slots = (size_t)s.B * s.H * sp.chunks * s.M;
+    size_t off = 0;
+    char *base = static_cast<char *>(ws);
+    if (m_part) *m_part = reinterpret_cast<float *>(base + off);
+    off += align256(slots * 4);
+    if (l_part) *l_part = reinterpret_cast<float *>(base + off);
+    off += align256(slots * 4);
+    if (o_part) *o_part = reinterpret_cast<float *>(base + off);
+    off += align256(slots * s.d * 4);
+    return off;
+}
+
+int launch_encode_merge(const flare_shape &s, const float *m_part, const float *l_part, const float *o_part,
+                        float *z, float *lse_enc, int parts, hipStream_t stream)
+{
+    const int BH = s.B * s.H;
+    const unsigned blocks = (unsigned)(((size_t)BH * s.M + 255) / 256);
+    LaunchTimer t(KID_ENCODE_MERGE, stream);
+    switch (s.d) {
+        case 4: encode_merge_kernel<4><<<blocks, 256, 0, stream>>>(m_part, l_part, o_part, z, lse_enc, BH, s.M, parts); break;
+        case 8: encode_merge_kernel<8><<<blocks, 256, 0, stream>>>(m_part, l_part, o_part, z, lse_enc, BH, s.M, parts); break;
+        case 16: encode_merge_kernel<16><<<blocks, 256, 0, stream>>>(m_part, l_part, o_part, z, lse_enc, BH, s.M, parts); break;
+        case 32: encode_merge_kernel<32><<<blocks, 256, 0, stream>>>(m_part, l_part, o_part, z, lse_enc, BH, s.M, parts); break;
+        default: return FLARE_EUNSUPPORTED;
+    }
+    return check_launch();
+}
+
 ValuPlan valu_plan(const flare_shape &s)
 {
     ValuPlan p;
     const int BH = s.B * s.H;
     p.enc = plan_split(s.N, BH, 256, 2048);
     p.bwd = plan_split(s.N, BH, 256, 2048);
-    p.fwd_bytes = fwd_layout(s, p.enc, nullptr, nullptr);
+    p.fwd_bytes = valu_fwd_layout(s, p.enc, nullptr, nullptr, nullptr, nullptr);
     p.bwd_bytes = bwd_layout(s, p.bwd, nullptr, nullptr);
     return p;
 }

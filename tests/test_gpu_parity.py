@@ -120,6 +120,10 @@ EDGE_SHAPES = [
     (1, 1, 300, 33, 8),       # odd M, small d
     (1, 2, 129, 300, 4),      # M above one latent block, d = 4
     (1, 1, 40, 513, 32),      # three latent blocks
+    (1, 2, 1000, 192, 16),    # three latent groups per workgroup on the matrix-core path
+    (2, 1, 100, 128, 32),
+    (1, 1, 33, 256, 32),      # one token past a 32-token tile
+    (1, 1, 31, 256, 16),
 ]
 
 
