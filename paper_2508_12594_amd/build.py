@@ -13,10 +13,13 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libflare.so")
-SOURCES = ["flare_api.hip", "flare_valu.hip", "flare_mfma.hip"]
+# source -> extra flags.  The matrix-core file never produces NaNs (masked scores are -inf and
+# are only ever compared, exponentiated or shifted by finite values), so it is compiled with
+# -fno-honor-nans: fmaxf chains then become v_max3_f32 without canonicalising moves.
+SOURCES = {"flare_api.hip": [], "flare_valu.hip": [], "flare_mfma.hip": ["-fno-honor-nans"]}
 
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-Wall", "-Wextra", "-Wno-unused-parameter",
     # keep the compiler from forming packed-fp32 VALU instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -24,14 +27,28 @@ FLAGS = [
 
 
 def build_library(verbose=True, extra_flags=()):
-    srcs = [os.path.join(CSRC, s) for s in SOURCES]
+    objdir = os.path.join(HERE, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    objs, procs = [], []
+    for src, flags in SOURCES.items():
+        obj = os.path.join(objdir, src.replace(".hip", ".%d.o" % os.getpid()))
+        cmd = ["hipcc"] + FLAGS + flags + list(extra_flags) + inc + ["-c", "-o", obj, os.path.join(CSRC, src)]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        procs.append((cmd, subprocess.Popen(cmd)))
+        objs.append(obj)
+    for cmd, proc in procs:
+        if proc.wait() != 0:
+            raise subprocess.CalledProcessError(proc.returncode, cmd)
     tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = ["hipcc"] + FLAGS + list(extra_flags) + ["-I", os.path.join(ROOT, "include"), "-I", CSRC,
-                                                   "-o", tmp] + srcs
+    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
     os.replace(tmp, LIB)
+    for obj in objs:
+        os.remove(obj)
     return LIB
 
 

@@ -66,7 +66,7 @@ __device__ __forceinline__ f32x16 splat16(float x)
 __device__ __forceinline__ float max16(const f32x16 &s, float m)
 {
 #pragma unroll
-    for (int i = 0; i < 16; i += 2) m = fmaxf(m, fmaxf(s[i], s[i + 1]));
+    for (int i = 0; i < 16; i += 2) m = fmaxf(fmaxf(m, s[i]), s[i + 1]);   // one v_max3_f32 per pair
     return m;
 }
 // 16 accumulator values -> 16 packed bf16 probabilities 2^x (two B operands of 8)
@@ -81,6 +81,10 @@ __device__ __forceinline__ void exp_pack(const f32x16 &dlt, bf16x8 &p0, bf16x8 &
     p0 = as_bf16x8(w0);
     p1 = as_bf16x8(w1);
 }
+// Nothing may be scheduled across this point: keeps the matrix-core work of the next tile issued
+// ahead of the vector work of the current one.
+__device__ __forceinline__ void sched_fence() { __builtin_amdgcn_sched_barrier(0); }
+
 // Contraction slot (8*hh + i) of k-step s2 (0 or 1) of a 32-wide tile maps to this index within
 // the tile: the row that accumulator register 8*s2 + i holds.
 __device__ __forceinline__ int perm_index(int s2, int hh, int i) { return 16 * s2 + 8 * (i / 4) + 4 * hh + (i % 4); }
@@ -128,8 +132,8 @@ __device__ __forceinline__ void load_q_operand(const bf16_t *__restrict__ q_row,
 // Q (as A operand) and Z^T (as A operand, latents in the permuted order) live in registers
 // for the whole kernel; K streams from HBM straight into the B-operand layout; no LDS.
 // ============================================================================================
-template <int D, int MT, bool PRE>
-__global__ __launch_bounds__(256) void decode_mfma_kernel(
+template <int D, int MT, bool PRE, int MINB>
+__global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const float *__restrict__ z,
     bf16_t *__restrict__ y, int H, int N, float c2)
 {
@@ -175,50 +179,76 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(
     bf16_t *yb = y + (size_t)bh * N * D;
     const int tiles = (N + 31) / 32;
     const int stride = gridDim.x * 4;
-    for (int tile = blockIdx.x * 4 + wave; tile < tiles; tile += stride) {
-        const int n = tile * 32 + l32;
-        const int nld = min(n, N - 1);
-        bf16x8 kt[KS];
+    int tile = blockIdx.x * 4 + wave;
+    bf16x8 kt[KS], ktn[KS];
+    if (tile < tiles) {
+        const int nld = min(tile * 32 + l32, N - 1);
 #pragma unroll
         for (int s = 0; s < KS; ++s)
             kt[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(kb + (size_t)nld * D + (D / 2) * hh + 8 * s));
+    }
+    for (; tile < tiles; tile += stride) {
+        const int n = tile * 32 + l32;
+        {   // prefetch the keys of this wave's next tile (the last tile is simply loaded again)
+            const int tn = (tile + stride < tiles) ? tile + stride : tile;
+            const int nld = min(tn * 32 + l32, N - 1);
+#pragma unroll
+            for (int s = 0; s < KS; ++s)
+                ktn[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(kb + (size_t)nld * D + (D / 2) * hh + 8 * s));
+        }
 
-        // pass 1: per-token maximum over the latents
+        // Scores of latent tile t against this token tile, on top of `init`.
+        auto qk_hi = [&](int t, f32x16 init) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) init = mfma(qh[t][ks], kt[ks], init);
+            return init;
+        };
+        auto qk_full = [&](int t, f32x16 init) {
+            init = qk_hi(t, init);
+            if constexpr (PRE) {
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) init = mfma(ql[t][ks], kt[ks], init);
+            }
+            return init;
+        };
+
+        // pass 1: per-token maximum over the latents (scores from the hi terms are close enough).
+        // The MFMA of tile t+1 is issued before the max over tile t.
         float mx = -INFINITY;
+        f32x16 s_cur = qk_hi(0, splat16(0.f)), s_next;
 #pragma unroll
         for (int t = 0; t < MT; ++t) {
-            f32x16 s = splat16(0.f);
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) s = mfma(qh[t][ks], kt[ks], s);
-            mx = max16(s, mx);
+            if (t + 1 < MT) s_next = qk_hi(t + 1, splat16(0.f));
+            sched_fence();
+            mx = max16(s_cur, mx);
+            s_cur = s_next;
         }
         mx = fmaxf(mx, __shfl_xor(mx, 32));
         const float b2 = PRE ? mx : mx * ac2;
         const f32x16 cneg = splat16(PRE ? -b2 : 0.f);
 
-        // pass 2
+        // pass 2: same pipeline; per latent tile 2^x, pack, and the value product
         f32x16 acc[HV];
 #pragma unroll
         for (int hv = 0; hv < HV; ++hv) acc[hv] = splat16(0.f);
+        s_cur = qk_full(0, cneg);
 #pragma unroll
         for (int t = 0; t < MT; ++t) {
-            f32x16 s = cneg;
+            if (t + 1 < MT) s_next = qk_full(t + 1, cneg);
+            sched_fence();
+            if constexpr (!PRE) {
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) s = mfma(qh[t][ks], kt[ks], s);
-            if constexpr (PRE) {
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) s = mfma(ql[t][ks], kt[ks], s);
-            } else {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) s[i] = fmaf(s[i], ac2, -b2);
+                for (int i = 0; i < 16; ++i) s_cur[i] = fmaf(s_cur[i], ac2, -b2);
             }
             bf16x8 p0, p1;
-            exp_pack(s, p0, p1);
+            exp_pack(s_cur, p0, p1);
 #pragma unroll
             for (int hv = 0; hv < HV; ++hv) {
                 acc[hv] = mfma(zt[hv][2 * t], p0, acc[hv]);
                 acc[hv] = mfma(zt[hv][2 * t + 1], p1, acc[hv]);
             }
+            sched_fence();
+            s_cur = s_next;
         }
         // row 16 (register 8 of the lower lane half) is the softmax denominator
         const float den = __shfl(acc[0][8], l32);
@@ -235,6 +265,8 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(
                 *reinterpret_cast<u32x2 *>(yb + (size_t)n * D + 16 * hv + 8 + 4 * hh) = w1;
             }
         }
+#pragma unroll
+        for (int s = 0; s < KS; ++s) kt[s] = ktn[s];
     }
 }
 
@@ -247,11 +279,11 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(
 // V^T is formed through a wave-private LDS tile (no workgroup barrier anywhere).
 // Output per wave: (c, row sums, unnormalised O) for its latents = one partial slot.
 // ============================================================================================
-constexpr float kLazy = 16.f;
+constexpr float kLazy = 16.f;   // the stabiliser moves when a score exceeds it by this much (log2 units)
 constexpr int kVtStride = 36;   // uint16 per LDS row: 32 tokens + 4 pad (72 B, conflict-free b64 reads)
 
-template <int D, int NB, bool PRE>
-__global__ __launch_bounds__(256) void encode_mfma_kernel(
+template <int D, int NB, bool PRE, int MINB>
+__global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     float *__restrict__ m_part, float *__restrict__ l_part, float *__restrict__ o_part,
     int H, int N, int M, int chunk_len, int parts, int G, int TG, float c2)
@@ -304,23 +336,48 @@ __global__ __launch_bounds__(256) void encode_mfma_kernel(
 #pragma unroll
     for (int hv = 0; hv < HV; ++hv) vrow[hv] = (l32 < 16) ? 16 * hv + l32 : (l32 == 16 ? D : D + 1);
 
-    for (int it = tg; it < tiles; it += TG) {
+    // keys: A operand, row = token.  values: 32 tokens x D in 16-byte pieces, two lanes per token.
+    constexpr int PIECES = D / 8;          // 16-byte pieces per token row
+    constexpr int LOADS = PIECES / 2;      // pieces per lane (64 lanes cover 32 tokens x 2 pieces)
+    const int vtok = lane >> 1;
+    bf16x8 kt[KS], ktn[KS];
+    u32x4 vraw[LOADS], vrawn[LOADS];
+    auto load_tile = [&](int it, bf16x8 (&kk)[KS], u32x4 (&vv)[LOADS]) {
         const int tok0 = n0 + 32 * it;
-        // keys: A operand, row = token
         const int nk = min(tok0 + l32, N - 1);
-        bf16x8 kt[KS];
-#pragma unroll
-        for (int s = 0; s < KS; ++s)
-            kt[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(kb + (size_t)nk * D + (D / 2) * hh + 8 * s));
-        // values: 32 tokens x D, 16 B pieces, written transposed into the wave's LDS tile
-        constexpr int PIECES = D / 8;          // 16-byte pieces per token row
-        constexpr int LOADS = PIECES / 2;      // pieces per lane (64 lanes cover 32 tokens x 2 pieces)
-        u32x4 vraw[LOADS];
-        const int vtok = lane >> 1;
         const int nv = min(tok0 + vtok, N - 1);
 #pragma unroll
+        for (int s = 0; s < KS; ++s)
+            kk[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(kb + (size_t)nk * D + (D / 2) * hh + 8 * s));
+#pragma unroll
         for (int j = 0; j < LOADS; ++j)
-            vraw[j] = *reinterpret_cast<const u32x4 *>(vb + (size_t)nv * D + 8 * ((lane & 1) * LOADS + j));
+            vv[j] = *reinterpret_cast<const u32x4 *>(vb + (size_t)nv * D + 8 * ((lane & 1) * LOADS + j));
+    };
+    // scores (minus the stabiliser) of latent tile b against the token tile held in kk
+    auto qk = [&](int b, const bf16x8 (&kk)[KS]) {
+        f32x16 r = cneg[b];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) r = mfma(kk[ks], qh[b][ks], r);
+        if constexpr (PRE) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) r = mfma(kk[ks], ql[b][ks], r);
+        }
+        return r;
+    };
+
+    // S[b]: scores of latent tile b for the token tile being processed.  S[0] of the next token
+    // tile is computed while the last latent tile of the current one is exponentiated.
+    f32x16 S[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) S[b] = splat16(0.f);
+    if (tg < tiles) {
+        load_tile(tg, kt, vraw);
+        S[0] = qk(0, kt);
+    }
+    for (int it = tg; it < tiles; it += TG) {
+        const int tok0 = n0 + 32 * it;
+        load_tile((it + TG < tiles) ? it + TG : it, ktn, vrawn);   // prefetch (or reload the last tile)
+        // write the values transposed into the wave's LDS tile
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // earlier reads of the tile are done
 #pragma unroll
         for (int j = 0; j < LOADS; ++j) {
@@ -346,27 +403,29 @@ __global__ __launch_bounds__(256) void encode_mfma_kernel(
             }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 
+        // register r of this lane holds token tok0 + 8*(r/4) + 4*hh + r%4: valid iff 8*(r/4) + r%4 < rem
+        const int rem = n1 - tok0 - 4 * hh;
         const bool partial = tok0 + 32 > n1;
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
-            f32x16 s = cneg[b];
+            // issue the next score product first: the next latent tile, or tile 0 of the next tokens
+            f32x16 nxt = (b + 1 < NB) ? qk(b + 1, kt) : qk(0, ktn);
+            sched_fence();
+            f32x16 sc = S[b];
+            if constexpr (!PRE) {
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) s = mfma(kt[ks], qh[b][ks], s);
-            if constexpr (PRE) {
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) s = mfma(kt[ks], ql[b][ks], s);
-            } else {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) s[i] = fmaf(s[i], ac2, -c[b]);
+                for (int i = 0; i < 16; ++i) sc[i] = fmaf(sc[i], ac2, -c[b]);
             }
             if (partial) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    if (tok0 + 8 * (r / 4) + 4 * hh + (r % 4) >= n1) s[r] = -INFINITY;
+                    if (8 * (r / 4) + (r % 4) >= rem) sc[r] = -INFINITY;
             }
-            float mx = max16(s, -INFINITY);
-            mx = fmaxf(mx, __shfl_xor(mx, 32));   // both lane halves hold tokens of the same latent
+            // lazy online softmax: the stabiliser moves only when a score exceeds it by more than
+            // kLazy (or on the first tile); otherwise 2^x is taken against the stale stabiliser
+            float mx = max16(sc, -INFINITY);
             if (first || __any(mx > kLazy)) {
+                mx = fmaxf(mx, __shfl_xor(mx, 32));   // both lane halves hold tokens of the same latent
                 const float shift = first ? mx : fmaxf(mx, 0.f);
                 if (!first) {
                     const float f = fast_exp2(-shift);
@@ -377,18 +436,30 @@ __global__ __launch_bounds__(256) void encode_mfma_kernel(
                 }
                 c[b] += shift;
 #pragma unroll
-                for (int i = 0; i < 16; ++i) s[i] -= shift;
-                if constexpr (PRE) cneg[b] = splat16(-c[b]);
+                for (int i = 0; i < 16; ++i) sc[i] -= shift;
+                if constexpr (PRE) {
+                    cneg[b] = splat16(-c[b]);
+                    if constexpr (NB == 1) {   // the product already in flight is for this same latent tile
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) nxt[i] -= shift;
+                    }
+                }
             }
             bf16x8 p0, p1;
-            exp_pack(s, p0, p1);
+            exp_pack(sc, p0, p1);
 #pragma unroll
             for (int hv = 0; hv < HV; ++hv) {
                 o[b][hv] = mfma(va[hv][0], p0, o[b][hv]);
                 o[b][hv] = mfma(va[hv][1], p1, o[b][hv]);
             }
+            sched_fence();
+            S[(b + 1) % NB] = nxt;
         }
         first = false;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) kt[s] = ktn[s];
+#pragma unroll
+        for (int j = 0; j < LOADS; ++j) vraw[j] = vrawn[j];
     }
 
     // partial slot of this wave: (bh, chunk*TG + tg), latents lat0 .. lat0 + 32*NB
@@ -413,19 +484,21 @@ __global__ __launch_bounds__(256) void encode_mfma_kernel(
 inline int check_launch() { return hipGetLastError() == hipSuccess ? FLARE_OK : FLARE_ELAUNCH; }
 
 // latent-group geometry of the encode for a given M
+// NB = 32-latent tiles per wave, G = latent groups (waves) per token tile, TG = token groups.
 struct EncGeom { int NB, G, TG, threads; };
-EncGeom enc_geom(int M)
+EncGeom enc_geom(int M, int /*d*/)
 {
     EncGeom e;
-    if (M == 32) { e.NB = 1; e.G = 1; }
-    else { e.NB = 2; e.G = M / 64; }
+    const int MB = M / 32;
+    e.NB = (MB == 1) ? 1 : 2;
+    e.G = MB / e.NB;
     e.TG = (e.G == 3) ? 1 : 4 / e.G;
     e.threads = 64 * e.G * e.TG;
     return e;
 }
 
-constexpr int kEncodeTargetBlocks = 768;   // three 4-wave workgroups per CU
-constexpr int kDecodeTargetBlocks = 768;
+constexpr int kEncodeTargetBlocks = 512;   // two 4-wave workgroups per CU
+constexpr int kDecodeTargetBlocks = 512;
 
 }  // namespace
 
@@ -440,7 +513,7 @@ bool mfma_supported(const flare_shape &s)
 MfmaPlan mfma_plan(const flare_shape &s)
 {
     MfmaPlan p;
-    const EncGeom e = enc_geom(s.M);
+    const EncGeom e = enc_geom(s.M, s.d);
     const int BH = s.B * s.H;
     // each chunk gives every token group at least 8 tiles of 32 tokens
     p.enc = plan_split(s.N, BH, 256 * e.TG, kEncodeTargetBlocks);
@@ -461,7 +534,7 @@ int mfma_encode(const flare_shape &s, const void *q, const void *k, const void *
                 float scale, void *ws, hipStream_t stream)
 {
     const MfmaPlan p = mfma_plan(s);
-    const EncGeom e = enc_geom(s.M);
+    const EncGeom e = enc_geom(s.M, s.d);
     Split sp;
     sp.chunks = p.parts;
     sp.chunk_len = 0;
@@ -473,9 +546,9 @@ int mfma_encode(const flare_shape &s, const void *q, const void *k, const void *
     const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *vv = (const bf16_t *)v;
     {
         LaunchTimer t(KID_ENCODE_PARTIAL, stream);
-#define FLARE_ENC(DD, NBB)                                                                                  \
-    encode_mfma_kernel<DD, NBB, true><<<grid, e.threads, 0, stream>>>(qq, kk, vv, m_part, l_part, o_part, s.H, \
-                                                                      s.N, s.M, p.enc.chunk_len, p.parts, e.G, e.TG, c2)
+#define FLARE_ENC(DD, NBB)                                                                                     \
+    encode_mfma_kernel<DD, NBB, true, 2><<<grid, e.threads, 0, stream>>>(qq, kk, vv, m_part, l_part, o_part, s.H, \
+                                                                         s.N, s.M, p.enc.chunk_len, p.parts, e.G, e.TG, c2)
         if (s.d == 16 && e.NB == 1) FLARE_ENC(16, 1);
         else if (s.d == 16) FLARE_ENC(16, 2);
         else if (e.NB == 1) FLARE_ENC(32, 1);
@@ -498,25 +571,25 @@ int mfma_decode(const flare_shape &s, const void *q, const void *k, const float 
     const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k;
     bf16_t *yy = (bf16_t *)y;
     LaunchTimer t(KID_DECODE, stream);
-#define FLARE_DEC(DD, MTT, PREE) \
-    decode_mfma_kernel<DD, MTT, PREE><<<grid, 256, 0, stream>>>(qq, kk, z, yy, s.H, s.N, c2)
+#define FLARE_DEC(DD, MTT, PREE, MINB) \
+    decode_mfma_kernel<DD, MTT, PREE, MINB><<<grid, 256, 0, stream>>>(qq, kk, z, yy, s.H, s.N, c2)
     const int MT = s.M / 32;
     if (s.d == 16) {
         switch (MT) {
-            case 1: FLARE_DEC(16, 1, true); break;
-            case 2: FLARE_DEC(16, 2, true); break;
-            case 4: FLARE_DEC(16, 4, true); break;
-            case 6: FLARE_DEC(16, 6, true); break;
-            case 8: FLARE_DEC(16, 8, true); break;
+            case 1: FLARE_DEC(16, 1, true, 2); break;
+            case 2: FLARE_DEC(16, 2, true, 2); break;
+            case 4: FLARE_DEC(16, 4, true, 2); break;
+            case 6: FLARE_DEC(16, 6, true, 2); break;
+            case 8: FLARE_DEC(16, 8, true, 2); break;
             default: return FLARE_EUNSUPPORTED;
         }
     } else {
         switch (MT) {
-            case 1: FLARE_DEC(32, 1, true); break;
-            case 2: FLARE_DEC(32, 2, true); break;
-            case 4: FLARE_DEC(32, 4, true); break;
-            case 6: FLARE_DEC(32, 6, false); break;
-            case 8: FLARE_DEC(32, 8, false); break;
+            case 1: FLARE_DEC(32, 1, true, 2); break;
+            case 2: FLARE_DEC(32, 2, true, 2); break;
+            case 4: FLARE_DEC(32, 4, true, 2); break;
+            case 6: FLARE_DEC(32, 6, false, 1); break;
+            case 8: FLARE_DEC(32, 8, false, 1); break;
             default: return FLARE_EUNSUPPORTED;
         }
     }
