@@ -2,10 +2,13 @@
 //
 // Both kernels are built from v_mfma_f32_32x32x16_bf16 and keep the M x N weights in
 // registers only.  The softmax work per score is one v_exp_f32, half a v_cvt_pk_bf16_f32 and
-// half a v_max3_f32: the score MFMA already delivers  S2 - stabiliser  because
+// half a v_max3_f32: the score MFMAs already deliver  S2 - stabiliser  because
 //   * q is pre-multiplied by scale*log2(e) and split into two bf16 terms (hi + lo), so the
 //     product is exact to ~2^-17 and the exponential is a bare 2^x;
-//   * the stabiliser enters through the MFMA's C operand (a register tuple holding -c).
+//   * the stabiliser rides in the contraction: slot 0 of the lo product carries
+//     (1) x (-stabiliser) instead of q_lo[0] x k[0], a term of relative size 2^-9 of one of the
+//     d products.  The stabiliser is therefore kept bf16-representable; any value near the
+//     maximum is a valid stabiliser.
 // The probabilities are rounded to bf16 once and feed the second MFMA straight from the
 // accumulator layout: the contraction index of the second product (tokens in the encode,
 // latents in the decode) is order-free, so the value operand is simply loaded in the
@@ -124,13 +127,27 @@ __device__ __forceinline__ void load_q_operand(const bf16_t *__restrict__ q_row,
     }
 }
 
+// Replace contraction slot 0 (low half of word 0) of an operand; `keep` and `bits` are per-lane
+// constants so that only the lower lane half (which owns slot 0) is changed.
+__device__ __forceinline__ bf16x8 with_slot0(bf16x8 x, uint32_t keep, uint32_t bits)
+{
+    u32x4 w = __builtin_bit_cast(u32x4, x);
+    w[0] = (w[0] & keep) | bits;
+    return as_bf16x8(w);
+}
+__device__ __forceinline__ float bf16_round(float x) { return __uint_as_float(rne_bf16(x) << 16); }
+__device__ __forceinline__ void compiler_fence() { asm volatile("" ::: "memory"); }
+
 // ============================================================================================
 // Decode.  One wave owns 32 tokens at a time and all M latents:
-//   pass 1: scores from the hi terms only -> per-token maximum b (any value near the maximum
-//           is a valid stabiliser);
-//   pass 2: scores again with C = -b, 2^x, pack, and Y^T += Zaug^T . E with Zaug = [Z | 1].
+//   pass 1: scores from the hi terms only -> per-token maximum, rounded to bf16 = stabiliser b;
+//   pass 2: full scores minus b (b sits in slot 0 of the key operand of the lo product), 2^x,
+//           pack, and Y^T += Zaug^T . E with Zaug = [Z | 1].
 // Q (as A operand) and Z^T (as A operand, latents in the permuted order) live in registers
 // for the whole kernel; K streams from HBM straight into the B-operand layout; no LDS.
+// Each pass issues the MFMAs of latent tile t+1 before the vector work on tile t.
+// PRE = false (shapes whose operands would not fit otherwise): raw q, no lo term, and
+// 2^(|c2| s - b) formed with one v_fma_f32 per score.
 // ============================================================================================
 template <int D, int MT, bool PRE, int MINB>
 __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
@@ -145,11 +162,14 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
     const int bh = blockIdx.y, h = bh % H;
     const bool flip = c2 < 0.f;
     const float ac2 = PRE ? c2 : fabsf(c2);
+    const uint32_t keep0 = hh == 0 ? 0xffff0000u : 0xffffffffu;
 
     bf16x8 qh[MT][KS], ql[MT][KS];
 #pragma unroll
-    for (int t = 0; t < MT; ++t)
+    for (int t = 0; t < MT; ++t) {
         load_q_operand<D, PRE>(q + ((size_t)h * M + 32 * t + l32) * D, hh, c2, flip, qh[t], ql[t]);
+        if constexpr (PRE) ql[t][0] = with_slot0(ql[t][0], keep0, hh == 0 ? 0x3f80u : 0u);   // slot 0 := 1.0
+    }
 
     // Zaug^T operand: row l32 (< 16: column 16*hv + l32 of Z; 16: ones; else zero)
     bf16x8 zt[HV][2 * MT];
@@ -196,45 +216,57 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
             for (int s = 0; s < KS; ++s)
                 ktn[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(kb + (size_t)nld * D + (D / 2) * hh + 8 * s));
         }
-
-        // Scores of latent tile t against this token tile, on top of `init`.
-        auto qk_hi = [&](int t, f32x16 init) {
+        auto qk_hi = [&](int t) {
+            f32x16 r = splat16(0.f);
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) init = mfma(qh[t][ks], kt[ks], init);
-            return init;
-        };
-        auto qk_full = [&](int t, f32x16 init) {
-            init = qk_hi(t, init);
-            if constexpr (PRE) {
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) init = mfma(ql[t][ks], kt[ks], init);
-            }
-            return init;
+            for (int ks = 0; ks < KS; ++ks) r = mfma(qh[t][ks], kt[ks], r);
+            return r;
         };
 
-        // pass 1: per-token maximum over the latents (scores from the hi terms are close enough).
-        // The MFMA of tile t+1 is issued before the max over tile t.
+        // pass 1: per-token maximum over the latents
         float mx = -INFINITY;
-        f32x16 s_cur = qk_hi(0, splat16(0.f)), s_next;
+        f32x16 s_cur = qk_hi(0), s_next;
 #pragma unroll
         for (int t = 0; t < MT; ++t) {
-            if (t + 1 < MT) s_next = qk_hi(t + 1, splat16(0.f));
+            if (t + 1 < MT) s_next = qk_hi(t + 1);
             sched_fence();
             mx = max16(s_cur, mx);
             s_cur = s_next;
         }
         mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float b2 = PRE ? mx : mx * ac2;
-        const f32x16 cneg = splat16(PRE ? -b2 : 0.f);
+        // stabiliser: bf16(max) in slot 0 of the key operand (PRE), or folded into the fma
+        const uint32_t bbits = rne_bf16(-mx);
+        const bf16x8 kta0 = with_slot0(kt[0], keep0, hh == 0 ? bbits : 0u);
+        const float b2 = mx * ac2;
+        // The hi products are recomputed in pass 2 rather than kept (8 tiles x 16 registers would
+        // not fit); an opaque copy of the keys stops the compiler from merging the two passes.
+        bf16x8 kt2[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            u32x4 w = __builtin_bit_cast(u32x4, kt[ks]);
+            asm volatile("" : "+v"(w));
+            kt2[ks] = as_bf16x8(w);
+        }
+        auto qk_full = [&](int t) {
+            f32x16 r = splat16(0.f);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) r = mfma(qh[t][ks], kt2[ks], r);
+            if constexpr (PRE) {
+                r = mfma(ql[t][0], kta0, r);
+#pragma unroll
+                for (int ks = 1; ks < KS; ++ks) r = mfma(ql[t][ks], kt[ks], r);
+            }
+            return r;
+        };
 
-        // pass 2: same pipeline; per latent tile 2^x, pack, and the value product
+        // pass 2: per latent tile 2^x, pack, and the value product
         f32x16 acc[HV];
 #pragma unroll
         for (int hv = 0; hv < HV; ++hv) acc[hv] = splat16(0.f);
-        s_cur = qk_full(0, cneg);
+        s_cur = qk_full(0);
 #pragma unroll
         for (int t = 0; t < MT; ++t) {
-            if (t + 1 < MT) s_next = qk_full(t + 1, cneg);
+            if (t + 1 < MT) s_next = qk_full(t + 1);
             sched_fence();
             if constexpr (!PRE) {
 #pragma unroll
@@ -271,18 +303,22 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
 }
 
 // ============================================================================================
-// Encode partials.  A workgroup has 4 waves; wave w works on latent group w % G (NB tiles of 32
-// latents) and on every TG-th 32-token tile of the chunk starting at tile w / G.  Per tile:
-//   S2^T - c = K . Q'^T + C  (rows = tokens, columns = latents, C holds -c per latent),
+// Encode partials.  A workgroup has up to 4 waves; wave w works on latent group w % G (NB tiles
+// of 32 latents) and on every TG-th 32-token tile of the chunk, starting at tile w / G.  Per tile
+// and latent tile:
+//   S2^T - c = K . Q'^T  (rows = tokens, columns = latents; -c rides in slot 0 of the lo product),
 //   lazy online softmax: c moves only when a score exceeds it by more than kLazy (or on the
-//   first tile), then O and C are rescaled; 2^x, pack; O^T += Vaug^T . P^T, Vaug = [V | 1].
-// V^T is formed through a wave-private LDS tile (no workgroup barrier anywhere).
+//   first tile), then O is rescaled; 2^x, pack; O^T += Vaug^T . P^T, Vaug = [V | 1].
+// V^T is formed through a wave-private, double-buffered LDS tile (no workgroup barrier
+// anywhere): the values of tile j+1 are written while tile j is computed and read back at its
+// end.  Keys are prefetched one tile ahead, values two.  The MFMAs of the next latent tile (or
+// of the next token tile) are issued before the vector work on the current one.
 // Output per wave: (c, row sums, unnormalised O) for its latents = one partial slot.
 // ============================================================================================
 constexpr float kLazy = 16.f;   // the stabiliser moves when a score exceeds it by this much (log2 units)
 constexpr int kVtStride = 36;   // uint16 per LDS row: 32 tokens + 4 pad (72 B, conflict-free b64 reads)
 
-template <int D, int NB, bool PRE, int MINB>
+template <int D, int NB, int MINB>
 __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     float *__restrict__ m_part, float *__restrict__ l_part, float *__restrict__ o_part,
@@ -290,46 +326,48 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
 {
     constexpr int KS = D / 16;
     constexpr int HV = D / 16;
-    constexpr int ROWS = D + 2;   // V^T rows, then a row of ones, then a row of zeros
-    __shared__ __attribute__((aligned(16))) uint16_t vt_all[4][ROWS * kVtStride];
+    constexpr int ROWS = D + 2;                 // V^T rows, then a row of ones, then a row of zeros
+    constexpr int BUF = ROWS * kVtStride;       // uint16 per buffer
+    __shared__ __attribute__((aligned(16))) uint16_t vt_all[4][2 * BUF];
 
     const int lane = threadIdx.x & 63, l32 = lane & 31, hh = lane >> 5;
     const int wave = threadIdx.x >> 6;
     const int g = wave % G, tg = wave / G;
     const int bh = blockIdx.y, h = bh % H, chunk = blockIdx.x;
-    const bool flip = c2 < 0.f;
-    const float ac2 = PRE ? c2 : fabsf(c2);
+    const uint32_t keep0 = hh == 0 ? 0xffff0000u : 0xffffffffu;
     uint16_t *vt = vt_all[wave];
-    if (tg >= TG) return;   // workgroups with G = 3 have one idle wave slot at most; no barriers are used
 
-    // constant rows of the value operand
+    // constant rows of the value operand, in both buffers
     if (lane < kVtStride) {
         vt[D * kVtStride + lane] = 0x3f80;
         vt[(D + 1) * kVtStride + lane] = 0;
+        vt[BUF + D * kVtStride + lane] = 0x3f80;
+        vt[BUF + (D + 1) * kVtStride + lane] = 0;
     }
 
     const int lat0 = 32 * NB * g;
     bf16x8 qh[NB][KS], ql[NB][KS];
 #pragma unroll
-    for (int b = 0; b < NB; ++b)
-        load_q_operand<D, PRE>(q + ((size_t)h * M + lat0 + 32 * b + l32) * D, hh, c2, flip, qh[b], ql[b]);
+    for (int b = 0; b < NB; ++b) {
+        load_q_operand<D, true>(q + ((size_t)h * M + lat0 + 32 * b + l32) * D, hh, c2, false, qh[b], ql[b]);
+        ql[b][0] = with_slot0(ql[b][0], keep0, 0u);   // slot 0 := -c = 0
+    }
 
     const bf16_t *kb = k + (size_t)bh * N * D;
     const bf16_t *vb = v + (size_t)bh * N * D;
     const int n0 = chunk * chunk_len;
     const int n1 = min(N, n0 + chunk_len);
     const int tiles = (n1 - n0 + 31) / 32;
+    const int cnt = (tiles > tg) ? (tiles - tg + TG - 1) / TG : 0;   // tiles of this wave
 
     float c[NB];
-    f32x16 cneg[NB], o[NB][HV];
+    f32x16 o[NB][HV];
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         c[b] = 0.f;
-        cneg[b] = splat16(0.f);
 #pragma unroll
         for (int hv = 0; hv < HV; ++hv) o[b][hv] = splat16(0.f);
     }
-    bool first = true;
 
     // row of the value operand this lane supplies for column group hv
     int vrow[HV];
@@ -340,135 +378,148 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     constexpr int PIECES = D / 8;          // 16-byte pieces per token row
     constexpr int LOADS = PIECES / 2;      // pieces per lane (64 lanes cover 32 tokens x 2 pieces)
     const int vtok = lane >> 1;
-    bf16x8 kt[KS], ktn[KS];
-    u32x4 vraw[LOADS], vrawn[LOADS];
-    auto load_tile = [&](int it, bf16x8 (&kk)[KS], u32x4 (&vv)[LOADS]) {
-        const int tok0 = n0 + 32 * it;
-        const int nk = min(tok0 + l32, N - 1);
-        const int nv = min(tok0 + vtok, N - 1);
+    auto tile_tok0 = [&](int j) { return n0 + 32 * (tg + min(j, cnt - 1) * TG); };   // j-th tile of this wave
+    auto load_k = [&](int j, bf16x8 (&kk)[KS]) {
+        const int nk = min(tile_tok0(j) + l32, N - 1);
 #pragma unroll
         for (int s = 0; s < KS; ++s)
             kk[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(kb + (size_t)nk * D + (D / 2) * hh + 8 * s));
-#pragma unroll
-        for (int j = 0; j < LOADS; ++j)
-            vv[j] = *reinterpret_cast<const u32x4 *>(vb + (size_t)nv * D + 8 * ((lane & 1) * LOADS + j));
     };
-    // scores (minus the stabiliser) of latent tile b against the token tile held in kk
-    auto qk = [&](int b, const bf16x8 (&kk)[KS]) {
-        f32x16 r = cneg[b];
+    auto load_v = [&](int j, u32x4 (&vv)[LOADS]) {
+        const int nv = min(tile_tok0(j) + vtok, N - 1);
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) r = mfma(kk[ks], qh[b][ks], r);
-        if constexpr (PRE) {
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) r = mfma(kk[ks], ql[b][ks], r);
-        }
-        return r;
+        for (int i = 0; i < LOADS; ++i)
+            vv[i] = *reinterpret_cast<const u32x4 *>(vb + (size_t)nv * D + 8 * ((lane & 1) * LOADS + i));
     };
-
-    // S[b]: scores of latent tile b for the token tile being processed.  S[0] of the next token
-    // tile is computed while the last latent tile of the current one is exponentiated.
-    f32x16 S[NB];
+    auto write_vt = [&](const u32x4 (&vv)[LOADS], uint16_t *buf) {   // transposed: row = column of V
 #pragma unroll
-    for (int b = 0; b < NB; ++b) S[b] = splat16(0.f);
-    if (tg < tiles) {
-        load_tile(tg, kt, vraw);
-        S[0] = qk(0, kt);
-    }
-    for (int it = tg; it < tiles; it += TG) {
-        const int tok0 = n0 + 32 * it;
-        load_tile((it + TG < tiles) ? it + TG : it, ktn, vrawn);   // prefetch (or reload the last tile)
-        // write the values transposed into the wave's LDS tile
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // earlier reads of the tile are done
-#pragma unroll
-        for (int j = 0; j < LOADS; ++j) {
-            const int d0 = 8 * ((lane & 1) * LOADS + j);
+        for (int i = 0; i < LOADS; ++i) {
+            const int d0 = 8 * ((lane & 1) * LOADS + i);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                vt[(d0 + 2 * e) * kVtStride + vtok] = (uint16_t)(vraw[j][e] & 0xffffu);
-                vt[(d0 + 2 * e + 1) * kVtStride + vtok] = (uint16_t)(vraw[j][e] >> 16);
+                buf[(d0 + 2 * e) * kVtStride + vtok] = (uint16_t)(vv[i][e] & 0xffffu);
+                buf[(d0 + 2 * e + 1) * kVtStride + vtok] = (uint16_t)(vv[i][e] >> 16);
             }
         }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the tile is written (same wave, in order)
-        bf16x8 va[HV][2];
+    };
+    auto read_va = [&](const uint16_t *buf, bf16x8 (&va)[HV][2]) {
 #pragma unroll
         for (int hv = 0; hv < HV; ++hv)
 #pragma unroll
             for (int s2 = 0; s2 < 2; ++s2) {
-                const uint16_t *row = vt + vrow[hv] * kVtStride + 16 * s2 + 4 * hh;
+                const uint16_t *row = buf + vrow[hv] * kVtStride + 16 * s2 + 4 * hh;
                 const u32x2 a = *reinterpret_cast<const u32x2 *>(row);
                 const u32x2 b = *reinterpret_cast<const u32x2 *>(row + 8);
                 u32x4 w;
                 w[0] = a[0]; w[1] = a[1]; w[2] = b[0]; w[3] = b[1];
                 va[hv][s2] = as_bf16x8(w);
             }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    };
+    // scores minus the stabiliser of latent tile b against the token tile (kk, kk0a = kk[0] with slot 0 := 1)
+    auto qk = [&](int b, const bf16x8 (&kk)[KS], bf16x8 kk0a) {
+        f32x16 r = splat16(0.f);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) r = mfma(kk[ks], qh[b][ks], r);
+        r = mfma(kk0a, ql[b][0], r);
+#pragma unroll
+        for (int ks = 1; ks < KS; ++ks) r = mfma(kk[ks], ql[b][ks], r);
+        return r;
+    };
+    const uint32_t one0 = hh == 0 ? 0x3f80u : 0u;
 
-        // register r of this lane holds token tok0 + 8*(r/4) + 4*hh + r%4: valid iff 8*(r/4) + r%4 < rem
-        const int rem = n1 - tok0 - 4 * hh;
-        const bool partial = tok0 + 32 > n1;
+    if (cnt > 0) {
+        bf16x8 kt[KS], ktn[KS], va[HV][2];
+        u32x4 vr1[LOADS], vr2[LOADS];
+        f32x16 S[NB];
+        bool first = true;
+
+        // prologue: tile 0 fully staged, tile 1's values in flight
+        load_k(0, kt);
+        load_v(0, vr1);
+        compiler_fence();
+        write_vt(vr1, vt);
+        compiler_fence();
+        read_va(vt, va);
+        load_v(1, vr1);
 #pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            // issue the next score product first: the next latent tile, or tile 0 of the next tokens
-            f32x16 nxt = (b + 1 < NB) ? qk(b + 1, kt) : qk(0, ktn);
-            sched_fence();
-            f32x16 sc = S[b];
-            if constexpr (!PRE) {
+        for (int b = 0; b < NB; ++b) S[b] = splat16(0.f);
+        S[0] = qk(0, kt, with_slot0(kt[0], keep0, one0));
+
+        for (int j = 0; j < cnt; ++j) {
+            const int tok0 = tile_tok0(j);
+            uint16_t *buf_next = vt + ((j + 1) & 1) * BUF;
+            load_k(j + 1, ktn);
+            load_v(j + 2, vr2);
+            compiler_fence();
+            write_vt(vr1, buf_next);          // values of tile j+1
+            compiler_fence();
+            const bf16x8 kt0a = with_slot0(kt[0], keep0, one0);
+
+            // register r of this lane holds token tok0 + 8*(r/4) + 4*hh + r%4: valid iff 8*(r/4) + r%4 < rem
+            const int rem = n1 - tok0 - 4 * hh;
+            const bool partial = tok0 + 32 > n1;
 #pragma unroll
-                for (int i = 0; i < 16; ++i) sc[i] = fmaf(sc[i], ac2, -c[b]);
-            }
-            if (partial) {
+            for (int b = 0; b < NB; ++b) {
+                // issue the next score product first: the next latent tile, or tile 0 of the next tokens
+                f32x16 nxt;
+                if (b + 1 < NB) nxt = qk(b + 1, kt, kt0a);
+                else nxt = qk(0, ktn, with_slot0(ktn[0], keep0, one0));
+                sched_fence();
+                f32x16 sc = S[b];
+                if (partial) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    if (8 * (r / 4) + (r % 4) >= rem) sc[r] = -INFINITY;
-            }
-            // lazy online softmax: the stabiliser moves only when a score exceeds it by more than
-            // kLazy (or on the first tile); otherwise 2^x is taken against the stale stabiliser
-            float mx = max16(sc, -INFINITY);
-            if (first || __any(mx > kLazy)) {
-                mx = fmaxf(mx, __shfl_xor(mx, 32));   // both lane halves hold tokens of the same latent
-                const float shift = first ? mx : fmaxf(mx, 0.f);
-                if (!first) {
-                    const float f = fast_exp2(-shift);
-#pragma unroll
-                    for (int hv = 0; hv < HV; ++hv)
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) o[b][hv][i] *= f;
+                    for (int r = 0; r < 16; ++r)
+                        if (8 * (r / 4) + (r % 4) >= rem) sc[r] = -INFINITY;
                 }
-                c[b] += shift;
+                float mx = max16(sc, -INFINITY);
+                if (first || __any(mx > kLazy)) {
+                    mx = fmaxf(mx, __shfl_xor(mx, 32));   // both lane halves hold tokens of the same latent
+                    const float cn = bf16_round(c[b] + (first ? mx : fmaxf(mx, 0.f)));
+                    const float shift = cn - c[b];
+                    if (!first) {
+                        const float f = fast_exp2(-shift);
 #pragma unroll
-                for (int i = 0; i < 16; ++i) sc[i] -= shift;
-                if constexpr (PRE) {
-                    cneg[b] = splat16(-c[b]);
+                        for (int hv = 0; hv < HV; ++hv)
+#pragma unroll
+                            for (int i = 0; i < 16; ++i) o[b][hv][i] *= f;
+                    }
+                    c[b] = cn;
+                    ql[b][0] = with_slot0(ql[b][0], keep0, hh == 0 ? rne_bf16(-cn) : 0u);
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) sc[i] -= shift;
                     if constexpr (NB == 1) {   // the product already in flight is for this same latent tile
 #pragma unroll
                         for (int i = 0; i < 16; ++i) nxt[i] -= shift;
                     }
                 }
-            }
-            bf16x8 p0, p1;
-            exp_pack(sc, p0, p1);
+                bf16x8 p0, p1;
+                exp_pack(sc, p0, p1);
 #pragma unroll
-            for (int hv = 0; hv < HV; ++hv) {
-                o[b][hv] = mfma(va[hv][0], p0, o[b][hv]);
-                o[b][hv] = mfma(va[hv][1], p1, o[b][hv]);
+                for (int hv = 0; hv < HV; ++hv) {
+                    o[b][hv] = mfma(va[hv][0], p0, o[b][hv]);
+                    o[b][hv] = mfma(va[hv][1], p1, o[b][hv]);
+                }
+                sched_fence();
+                S[(b + 1) % NB] = nxt;
             }
-            sched_fence();
-            S[(b + 1) % NB] = nxt;
+            first = false;
+            compiler_fence();
+            read_va(buf_next, va);            // value operand of tile j+1 (written at the top of this iteration)
+#pragma unroll
+            for (int s = 0; s < KS; ++s) kt[s] = ktn[s];
+#pragma unroll
+            for (int i = 0; i < LOADS; ++i) vr1[i] = vr2[i];
         }
-        first = false;
-#pragma unroll
-        for (int s = 0; s < KS; ++s) kt[s] = ktn[s];
-#pragma unroll
-        for (int j = 0; j < LOADS; ++j) vraw[j] = vrawn[j];
     }
 
     // partial slot of this wave: (bh, chunk*TG + tg), latents lat0 .. lat0 + 32*NB
+    if (tg >= TG) return;
     const size_t part = (size_t)bh * parts + (size_t)chunk * TG + tg;
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         const size_t slot = part * M + lat0 + 32 * b + l32;
         if (hh == 0) {
-            m_part[slot] = first ? -INFINITY : c[b];
+            m_part[slot] = (cnt > 0) ? c[b] : -INFINITY;
             l_part[slot] = o[b][0][8];
         }
 #pragma unroll
@@ -486,11 +537,13 @@ inline int check_launch() { return hipGetLastError() == hipSuccess ? FLARE_OK : 
 // latent-group geometry of the encode for a given M
 // NB = 32-latent tiles per wave, G = latent groups (waves) per token tile, TG = token groups.
 struct EncGeom { int NB, G, TG, threads; };
-EncGeom enc_geom(int M, int /*d*/)
+EncGeom enc_geom(int M, int d)
 {
     EncGeom e;
     const int MB = M / 32;
-    e.NB = (MB == 1) ? 1 : 2;
+    if (MB == 1) e.NB = 1;
+    else if (d == 16 && MB % 4 == 0) e.NB = 4;
+    else e.NB = 2;
     e.G = MB / e.NB;
     e.TG = (e.G == 3) ? 1 : 4 / e.G;
     e.threads = 64 * e.G * e.TG;
@@ -546,11 +599,12 @@ int mfma_encode(const flare_shape &s, const void *q, const void *k, const void *
     const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *vv = (const bf16_t *)v;
     {
         LaunchTimer t(KID_ENCODE_PARTIAL, stream);
-#define FLARE_ENC(DD, NBB)                                                                                     \
-    encode_mfma_kernel<DD, NBB, true, 2><<<grid, e.threads, 0, stream>>>(qq, kk, vv, m_part, l_part, o_part, s.H, \
-                                                                         s.N, s.M, p.enc.chunk_len, p.parts, e.G, e.TG, c2)
+#define FLARE_ENC(DD, NBB)                                                                               \
+    encode_mfma_kernel<DD, NBB, 2><<<grid, e.threads, 0, stream>>>(qq, kk, vv, m_part, l_part, o_part, s.H, \
+                                                                   s.N, s.M, p.enc.chunk_len, p.parts, e.G, e.TG, c2)
         if (s.d == 16 && e.NB == 1) FLARE_ENC(16, 1);
-        else if (s.d == 16) FLARE_ENC(16, 2);
+        else if (s.d == 16 && e.NB == 2) FLARE_ENC(16, 2);
+        else if (s.d == 16) FLARE_ENC(16, 4);
         else if (e.NB == 1) FLARE_ENC(32, 1);
         else FLARE_ENC(32, 2);
 #undef FLARE_ENC
