@@ -77,5 +77,9 @@ int mfma_encode(const flare_shape &s, const void *q, const void *k, const void *
                 float *lse_enc, float scale, void *ws, hipStream_t stream);
 int mfma_decode(const flare_shape &s, const void *q, const void *k, const float *z, void *y,
                 float scale, hipStream_t stream);
+int mfma_token_stats(const flare_shape &s, const void *q, const void *k, const float *z, const void *dy,
+                     float *lse_dec2, float *delta, float scale, hipStream_t stream);
+int mfma_dz_partial(const flare_shape &s, const void *q, const void *k, const void *dy, const float *lse_dec2,
+                    float *dz_part, float scale, hipStream_t stream);
 
 }  // namespace flare

@@ -127,6 +127,22 @@ __device__ __forceinline__ void load_q_operand(const bf16_t *__restrict__ q_row,
     }
 }
 
+// Replace contraction slots 0..3 (words 0 and 1) of an operand in the lower lane half.
+__device__ __forceinline__ bf16x8 with_slots(bf16x8 x, bool lower_half, uint32_t w0, uint32_t w1)
+{
+    u32x4 w = __builtin_bit_cast(u32x4, x);
+    w[0] = lower_half ? w0 : w[0];
+    w[1] = lower_half ? w1 : w[1];
+    return __builtin_bit_cast(bf16x8, w);
+}
+// x as a hi + lo pair of bf16 values packed in one word (hi in the low half)
+__device__ __forceinline__ uint32_t split_bf16_pair(float x)
+{
+    const uint32_t hi = (__float_as_uint(x) + 0x7fffu + ((__float_as_uint(x) >> 16) & 1u)) >> 16;
+    const float r = x - __uint_as_float(hi << 16);
+    const uint32_t lo = (__float_as_uint(r) + 0x7fffu + ((__float_as_uint(r) >> 16) & 1u)) >> 16;
+    return hi | (lo << 16);
+}
 // Replace contraction slot 0 (low half of word 0) of an operand; `keep` and `bits` are per-lane
 // constants so that only the lower lane half (which owns slot 0) is changed.
 __device__ __forceinline__ bf16x8 with_slot0(bf16x8 x, uint32_t keep, uint32_t bits)
@@ -149,10 +165,13 @@ __device__ __forceinline__ void compiler_fence() { asm volatile("" ::: "memory")
 // PRE = false (shapes whose operands would not fit otherwise): raw q, no lo term, and
 // 2^(|c2| s - b) formed with one v_fma_f32 per score.
 // ============================================================================================
-template <int D, int MT, bool PRE, int MINB>
+// MODE 0 writes y.  MODE 1 (first step of the backward) writes per token
+//   lse_dec2[n] = log2 sum_m 2^S2[m][n]   and   delta[n] = <dY_n, Y_n>   (Y_n kept in fp32).
+template <int D, int MT, bool PRE, int MINB, int MODE>
 __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const float *__restrict__ z,
-    bf16_t *__restrict__ y, int H, int N, float c2)
+    bf16_t *__restrict__ y, const bf16_t *__restrict__ dy, float *__restrict__ lse_dec2,
+    float *__restrict__ delta, int H, int N, float c2)
 {
     constexpr int KS = D / 16;   // k-steps of the score product
     constexpr int HV = D / 16;   // 16-wide column groups of Z, each with its own ones row
@@ -285,7 +304,30 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
         // row 16 (register 8 of the lower lane half) is the softmax denominator
         const float den = __shfl(acc[0][8], l32);
         const float inv = 1.f / den;
-        if (n < N) {
+        if constexpr (MODE == 1) {
+            const size_t row = (size_t)bh * N + min(n, N - 1);
+            float part = 0.f;
+#pragma unroll
+            for (int hv = 0; hv < HV; ++hv) {
+                const u32x2 g0 = *reinterpret_cast<const u32x2 *>(dy + row * D + 16 * hv + 4 * hh);
+                const u32x2 g1 = *reinterpret_cast<const u32x2 *>(dy + row * D + 16 * hv + 8 + 4 * hh);
+                part = fmaf(acc[hv][0] * inv, bf16_lo(g0[0]), part);
+                part = fmaf(acc[hv][1] * inv, bf16_hi(g0[0]), part);
+                part = fmaf(acc[hv][2] * inv, bf16_lo(g0[1]), part);
+                part = fmaf(acc[hv][3] * inv, bf16_hi(g0[1]), part);
+                part = fmaf(acc[hv][4] * inv, bf16_lo(g1[0]), part);
+                part = fmaf(acc[hv][5] * inv, bf16_hi(g1[0]), part);
+                part = fmaf(acc[hv][6] * inv, bf16_lo(g1[1]), part);
+                part = fmaf(acc[hv][7] * inv, bf16_hi(g1[1]), part);
+            }
+            part += __shfl_xor(part, 32);
+            // the stabiliser that was actually subtracted: -bf16(-mx), or b2 on the fma path
+            const float used = PRE ? -__uint_as_float(bbits << 16) : b2;
+            if (n < N && hh == 0) {
+                lse_dec2[row] = used + log2f(den);
+                delta[row] = part;
+            }
+        } else if (n < N) {
 #pragma unroll
             for (int hv = 0; hv < HV; ++hv) {
                 u32x2 w0, w1;
@@ -318,9 +360,14 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
 constexpr float kLazy = 16.f;   // the stabiliser moves when a score exceeds it by this much (log2 units)
 constexpr int kVtStride = 36;   // uint16 per LDS row: 32 tokens + 4 pad (72 B, conflict-free b64 reads)
 
-template <int D, int NB, int MINB>
+// MODE 1 (second step of the backward) reuses the same machinery for dZ = R^T dY: the values are
+// dY, the weights are R^T[n][m] = 2^(S2 - lse_dec2[n]) with the per-token -lse_dec2 carried as a
+// hi + lo bf16 pair in slots 2,3 of the key operand of the lo product (against 1,1 on the query
+// side), and there is no softmax state: only the unnormalised sums are written.
+template <int D, int NB, int MINB, int MODE>
 __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
+    const float *__restrict__ lse_dec2,
     float *__restrict__ m_part, float *__restrict__ l_part, float *__restrict__ o_part,
     int H, int N, int M, int chunk_len, int parts, int G, int TG, float c2)
 {
@@ -350,7 +397,11 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         load_q_operand<D, true>(q + ((size_t)h * M + lat0 + 32 * b + l32) * D, hh, c2, false, qh[b], ql[b]);
-        ql[b][0] = with_slot0(ql[b][0], keep0, 0u);   // slot 0 := -c = 0
+        if constexpr (MODE == 0) {
+            ql[b][0] = with_slot0(ql[b][0], keep0, 0u);   // slot 0 := -c = 0
+        } else {
+            ql[b][0] = with_slots(ql[b][0], hh == 0, 0u, 0x3f803f80u);   // slots 0,1 := 0; slots 2,3 := 1
+        }
     }
 
     const bf16_t *kb = k + (size_t)bh * N * D;
@@ -426,6 +477,20 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         return r;
     };
     const uint32_t one0 = hh == 0 ? 0x3f80u : 0u;
+    const float *lb = (MODE == 1) ? lse_dec2 + (size_t)bh * N : nullptr;
+    // key operand of the lo product: slot 0 := 1 (MODE 0), or slots 2,3 := -lse_dec2 of this lane's token
+    auto k_aug = [&](bf16x8 k0, float neg_lse) {
+        if constexpr (MODE == 0) return with_slot0(k0, keep0, one0);
+        else {
+            u32x4 w = __builtin_bit_cast(u32x4, k0);
+            w[1] = hh == 0 ? split_bf16_pair(neg_lse) : w[1];
+            return as_bf16x8(w);
+        }
+    };
+    auto load_lse = [&](int j) {
+        if constexpr (MODE == 1) return -lb[min(tile_tok0(j) + l32, N - 1)];
+        else return 0.f;
+    };
 
     if (cnt > 0) {
         bf16x8 kt[KS], ktn[KS], va[HV][2];
@@ -434,6 +499,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         bool first = true;
 
         // prologue: tile 0 fully staged, tile 1's values in flight
+        float nl = load_lse(0), nln = 0.f;
         load_k(0, kt);
         load_v(0, vr1);
         compiler_fence();
@@ -443,17 +509,18 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         load_v(1, vr1);
 #pragma unroll
         for (int b = 0; b < NB; ++b) S[b] = splat16(0.f);
-        S[0] = qk(0, kt, with_slot0(kt[0], keep0, one0));
+        S[0] = qk(0, kt, k_aug(kt[0], nl));
 
         for (int j = 0; j < cnt; ++j) {
             const int tok0 = tile_tok0(j);
             uint16_t *buf_next = vt + ((j + 1) & 1) * BUF;
+            nln = load_lse(j + 1);
             load_k(j + 1, ktn);
             load_v(j + 2, vr2);
             compiler_fence();
             write_vt(vr1, buf_next);          // values of tile j+1
             compiler_fence();
-            const bf16x8 kt0a = with_slot0(kt[0], keep0, one0);
+            const bf16x8 kt0a = k_aug(kt[0], nl);
 
             // register r of this lane holds token tok0 + 8*(r/4) + 4*hh + r%4: valid iff 8*(r/4) + r%4 < rem
             const int rem = n1 - tok0 - 4 * hh;
@@ -463,7 +530,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
                 // issue the next score product first: the next latent tile, or tile 0 of the next tokens
                 f32x16 nxt;
                 if (b + 1 < NB) nxt = qk(b + 1, kt, kt0a);
-                else nxt = qk(0, ktn, with_slot0(ktn[0], keep0, one0));
+                else nxt = qk(0, ktn, k_aug(ktn[0], nln));
                 sched_fence();
                 f32x16 sc = S[b];
                 if (partial) {
@@ -471,8 +538,8 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
                     for (int r = 0; r < 16; ++r)
                         if (8 * (r / 4) + (r % 4) >= rem) sc[r] = -INFINITY;
                 }
-                float mx = max16(sc, -INFINITY);
-                if (first || __any(mx > kLazy)) {
+                float mx = (MODE == 0) ? max16(sc, -INFINITY) : 0.f;
+                if (MODE == 0 && (first || __any(mx > kLazy))) {
                     mx = fmaxf(mx, __shfl_xor(mx, 32));   // both lane halves hold tokens of the same latent
                     const float cn = bf16_round(c[b] + (first ? mx : fmaxf(mx, 0.f)));
                     const float shift = cn - c[b];
@@ -503,6 +570,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
                 S[(b + 1) % NB] = nxt;
             }
             first = false;
+            nl = nln;
             compiler_fence();
             read_va(buf_next, va);            // value operand of tile j+1 (written at the top of this iteration)
 #pragma unroll
@@ -518,7 +586,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         const size_t slot = part * M + lat0 + 32 * b + l32;
-        if (hh == 0) {
+        if (MODE == 0 && hh == 0) {
             m_part[slot] = (cnt > 0) ? c[b] : -INFINITY;
             l_part[slot] = o[b][0][8];
         }
@@ -599,9 +667,10 @@ int mfma_encode(const flare_shape &s, const void *q, const void *k, const void *
     const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *vv = (const bf16_t *)v;
     {
         LaunchTimer t(KID_ENCODE_PARTIAL, stream);
-#define FLARE_ENC(DD, NBB)                                                                               \
-    encode_mfma_kernel<DD, NBB, 2><<<grid, e.threads, 0, stream>>>(qq, kk, vv, m_part, l_part, o_part, s.H, \
-                                                                   s.N, s.M, p.enc.chunk_len, p.parts, e.G, e.TG, c2)
+#define FLARE_ENC(DD, NBB)                                                                                   \
+    encode_mfma_kernel<DD, NBB, 2, 0><<<grid, e.threads, 0, stream>>>(qq, kk, vv, nullptr, m_part, l_part, o_part, \
+                                                                      s.H, s.N, s.M, p.enc.chunk_len, p.parts, e.G, \
+                                                                      e.TG, c2)
         if (s.d == 16 && e.NB == 1) FLARE_ENC(16, 1);
         else if (s.d == 16 && e.NB == 2) FLARE_ENC(16, 2);
         else if (s.d == 16) FLARE_ENC(16, 4);
@@ -613,8 +682,33 @@ int mfma_encode(const flare_shape &s, const void *q, const void *k, const void *
     return launch_encode_merge(s, m_part, l_part, o_part, z, lse_enc, p.parts, stream);
 }
 
-int mfma_decode(const flare_shape &s, const void *q, const void *k, const float *z, void *y, float scale,
-                hipStream_t stream)
+// dZ partials of the backward (the encode machinery with values dY and weights R^T)
+int mfma_dz_partial(const flare_shape &s, const void *q, const void *k, const void *dy, const float *lse_dec2,
+                    float *dz_part, float scale, hipStream_t stream)
+{
+    const MfmaPlan p = mfma_plan(s);
+    const EncGeom e = enc_geom(s.M, s.d);
+    const int BH = s.B * s.H;
+    const float c2 = scale * kLog2e;
+    const dim3 grid(p.enc.chunks, BH);
+    const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *gg = (const bf16_t *)dy;
+    LaunchTimer t(KID_BWD_DZ_PARTIAL, stream);
+#define FLARE_DZ(DD, NBB)                                                                                      \
+    encode_mfma_kernel<DD, NBB, 2, 1><<<grid, e.threads, 0, stream>>>(qq, kk, gg, lse_dec2, nullptr, nullptr, dz_part, \
+                                                                      s.H, s.N, s.M, p.enc.chunk_len, p.parts, e.G,  \
+                                                                      e.TG, c2)
+    if (s.d == 16 && e.NB == 1) FLARE_DZ(16, 1);
+    else if (s.d == 16 && e.NB == 2) FLARE_DZ(16, 2);
+    else if (s.d == 16) FLARE_DZ(16, 4);
+    else if (e.NB == 1) FLARE_DZ(32, 1);
+    else FLARE_DZ(32, 2);
+#undef FLARE_DZ
+    return check_launch();
+}
+
+template <int MODE>
+static int launch_decode_family(const flare_shape &s, const void *q, const void *k, const float *z, void *y,
+                                const void *dy, float *lse_dec2, float *delta, float scale, hipStream_t stream)
 {
     const int BH = s.B * s.H;
     const int tiles = (s.N + 31) / 32;
@@ -622,11 +716,12 @@ int mfma_decode(const flare_shape &s, const void *q, const void *k, const float 
     if (blocks > (tiles + 3) / 4) blocks = (tiles + 3) / 4;
     const dim3 grid(blocks, BH);
     const float c2 = scale * kLog2e;
-    const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k;
+    const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *gg = (const bf16_t *)dy;
     bf16_t *yy = (bf16_t *)y;
-    LaunchTimer t(KID_DECODE, stream);
-#define FLARE_DEC(DD, MTT, PREE, MINB) \
-    decode_mfma_kernel<DD, MTT, PREE, MINB><<<grid, 256, 0, stream>>>(qq, kk, z, yy, s.H, s.N, c2)
+    LaunchTimer t(MODE == 0 ? KID_DECODE : KID_BWD_TOKEN_STATS, stream);
+#define FLARE_DEC(DD, MTT, PREE, MINB)                                                                          \
+    decode_mfma_kernel<DD, MTT, PREE, MINB, MODE><<<grid, 256, 0, stream>>>(qq, kk, z, yy, gg, lse_dec2, delta, s.H, \
+                                                                            s.N, c2)
     const int MT = s.M / 32;
     if (s.d == 16) {
         switch (MT) {
@@ -649,6 +744,18 @@ int mfma_decode(const flare_shape &s, const void *q, const void *k, const float 
     }
 #undef FLARE_DEC
     return check_launch();
+}
+
+int mfma_decode(const flare_shape &s, const void *q, const void *k, const float *z, void *y, float scale,
+                hipStream_t stream)
+{
+    return launch_decode_family<0>(s, q, k, z, y, nullptr, nullptr, nullptr, scale, stream);
+}
+
+int mfma_token_stats(const flare_shape &s, const void *q, const void *k, const float *z, const void *dy,
+                     float *lse_dec2, float *delta, float scale, hipStream_t stream)
+{
+    return launch_decode_family<1>(s, q, k, z, nullptr, dy, lse_dec2, delta, scale, stream);
 }
 
 }  // namespace flare

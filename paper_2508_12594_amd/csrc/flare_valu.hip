@@ -164,32 +164,59 @@ __global__ __launch_bounds__(kLatentBlock) void encode_partial_kernel(
     store_row<D>(o_part + slot * D, o);
 }
 
-// Merge of the chunk partials in chunk order: thread = (b*h, m).
+// Merge of the partial slots of one (b*h, m): a workgroup takes 16 latents; the 16 threads of a
+// latent each fold the slots p = j, j+16, ... in order and a fixed xor-shuffle tree folds the 16
+// results, so the association order depends on the slot count only (bit-reproducible).
+// A slot with m = -inf is empty and contributes nothing.
 template <int D>
 __global__ __launch_bounds__(256) void encode_merge_kernel(
     const float *__restrict__ m_part, const float *__restrict__ l_part, const float *__restrict__ o_part,
-    float *__restrict__ z, float *__restrict__ lse_enc, int BH, int M, int chunks)
+    float *__restrict__ z, float *__restrict__ lse_enc, int BH, int M, int parts)
 {
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (size_t)BH * M) return;
-    const int bh = (int)(idx / M), m = (int)(idx % M);
-    float gm = -INFINITY;
-    for (int c = 0; c < chunks; ++c) gm = fmaxf(gm, m_part[((size_t)bh * chunks + c) * M + m]);
-    float l = 0.f, o[D];
+    const int j = threadIdx.x & 15;
+    const int m = blockIdx.x * 16 + (threadIdx.x >> 4);
+    const int bh = blockIdx.y;
+    const bool live = m < M;
+    const int mm = live ? m : M - 1;
+    float gm = -INFINITY, l = 0.f, o[D];
 #pragma unroll
-    for (int j = 0; j < D; ++j) o[j] = 0.f;
-    for (int c = 0; c < chunks; ++c) {
-        const size_t slot = ((size_t)bh * chunks + c) * M + m;
-        const float w = fast_exp2(m_part[slot] - gm);
-        l = fmaf(l_part[slot], w, l);
+    for (int i = 0; i < D; ++i) o[i] = 0.f;
+    for (int p = j; p < parts; p += 16) {
+        const size_t slot = ((size_t)bh * parts + p) * M + mm;
+        const float mp = m_part[slot];
+        if (mp == -INFINITY) continue;
+        const float ng = fmaxf(gm, mp);
+        const float wa = fast_exp2(gm - ng);          // gm = -inf on the first live slot: weight 0
+        const float wb = fast_exp2(mp - ng);
         float oc[D];
         load_row<D>(o_part + slot * D, oc);
+        l = l * wa + l_part[slot] * wb;
 #pragma unroll
-        for (int j = 0; j < D; ++j) o[j] = fmaf(oc[j], w, o[j]);
+        for (int i = 0; i < D; ++i) o[i] = o[i] * wa + oc[i] * wb;
+        gm = ng;
     }
+#pragma unroll
+    for (int off = 1; off < 16; off <<= 1) {
+        const float gm2 = __shfl_xor(gm, off);
+        const float l2 = __shfl_xor(l, off);
+        const float ng = fmaxf(gm, gm2);
+        const float wa = (gm == -INFINITY) ? 0.f : fast_exp2(gm - ng);
+        const float wb = (gm2 == -INFINITY) ? 0.f : fast_exp2(gm2 - ng);
+        // both lanes of a pair must form the same sum: order the operands by lane parity
+        const bool low = (j & off) == 0;
+        l = low ? (l * wa + l2 * wb) : (l2 * wb + l * wa);
+#pragma unroll
+        for (int i = 0; i < D; ++i) {
+            const float o2 = __shfl_xor(o[i], off);
+            o[i] = low ? (o[i] * wa + o2 * wb) : (o2 * wb + o[i] * wa);
+        }
+        gm = ng;
+    }
+    if (!live || j != 0) return;
     const float inv = 1.f / l;
 #pragma unroll
-    for (int j = 0; j < D; ++j) o[j] *= inv;
+    for (int i = 0; i < D; ++i) o[i] *= inv;
+    const size_t idx = (size_t)bh * M + m;
     store_row<D>(z + idx * D, o);
     lse_enc[idx] = (gm + log2f(l)) * kLn2;
 }
@@ -451,7 +478,8 @@ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct BwdWs { float *lse_dec2, *delta, *part, *dz, *eps; };
 
-size_t bwd_layout(const flare_shape &s, const Split &sp, void *ws, BwdWs *out)
+// `slots` = partial slots per (b,h) the shared partial buffer must hold
+size_t bwd_layout(const flare_shape &s, int slots, void *ws, BwdWs *out)
 {
     const size_t BH = (size_t)s.B * s.H;
     size_t off = 0;
@@ -461,7 +489,7 @@ size_t bwd_layout(const flare_shape &s, const Split &sp, void *ws, BwdWs *out)
     if (out) out->delta = reinterpret_cast<float *>(base + off);
     off += align256(BH * s.N * 4);
     if (out) out->part = reinterpret_cast<float *>(base + off);
-    off += align256(BH * sp.chunks * s.M * s.d * 4);
+    off += align256(BH * slots * s.M * s.d * 4);
     if (out) out->dz = reinterpret_cast<float *>(base + off);
     off += align256(BH * s.M * s.d * 4);
     if (out) out->eps = reinterpret_cast<float *>(base + off);
@@ -470,6 +498,12 @@ size_t bwd_layout(const flare_shape &s, const Split &sp, void *ws, BwdWs *out)
 }
 
 inline int check_launch() { return hipGetLastError() == hipSuccess ? FLARE_OK : FLARE_ELAUNCH; }
+
+inline int bwd_slots(const flare_shape &s, const ValuPlan &plan)
+{
+    const int mf = mfma_supported(s) ? mfma_plan(s).parts : 0;
+    return plan.bwd.chunks > mf ? plan.bwd.chunks : mf;
+}
 
 template <typename T, int D>
 int encode_impl(const flare_shape &s, const T *q, const T *k, const T *v, float *z, float *lse_enc,
@@ -504,29 +538,39 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
                   const float *lse_enc, float *dq, T *dk, T *dv, float scale, void *ws, hipStream_t stream)
 {
     const ValuPlan plan = valu_plan(s);
+    const bool mf = mfma_supported(s);          // matrix-core kernels where they exist
+    const int dz_parts = mf ? mfma_plan(s).parts : plan.bwd.chunks;
     BwdWs w;
-    bwd_layout(s, plan.bwd, ws, &w);
+    bwd_layout(s, bwd_slots(s, plan), ws, &w);
     const int BH = s.B * s.H;
     const float c2 = scale * kLog2e;
     const int lat_blocks = (s.M + kLatentBlock - 1) / kLatentBlock;
     const dim3 tok_grid((s.N + kTokenBlock - 1) / kTokenBlock, BH);
     const dim3 lat_grid(plan.bwd.chunks, BH, lat_blocks);
     const unsigned bhm_blocks = (unsigned)(((size_t)BH * s.M + 255) / 256);
-    {
-        LaunchTimer t(KID_BWD_TOKEN_STATS, stream);
-        token_pass_kernel<T, D, 1><<<tok_grid, kTokenBlock, 0, stream>>>(q, k, z, nullptr, dy, w.lse_dec2, w.delta,
-                                                                         s.H, s.N, s.M, c2);
+    if (mf) {
+        int rc = mfma_token_stats(s, q, k, z, dy, w.lse_dec2, w.delta, scale, stream);
+        if (rc != FLARE_OK) return rc;
+        rc = mfma_dz_partial(s, q, k, dy, w.lse_dec2, w.part, scale, stream);
+        if (rc != FLARE_OK) return rc;
+    } else {
+        {
+            LaunchTimer t(KID_BWD_TOKEN_STATS, stream);
+            token_pass_kernel<T, D, 1><<<tok_grid, kTokenBlock, 0, stream>>>(q, k, z, nullptr, dy, w.lse_dec2,
+                                                                             w.delta, s.H, s.N, s.M, c2);
+        }
+        if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
+        {
+            LaunchTimer t(KID_BWD_DZ_PARTIAL, stream);
+            dz_partial_kernel<T, D><<<lat_grid, kLatentBlock, 0, stream>>>(q, k, dy, w.lse_dec2, w.part, s.H, s.N,
+                                                                           s.M, plan.bwd.chunk_len, plan.bwd.chunks,
+                                                                           c2);
+        }
+        if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     }
-    if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
-    {
-        LaunchTimer t(KID_BWD_DZ_PARTIAL, stream);
-        dz_partial_kernel<T, D><<<lat_grid, kLatentBlock, 0, stream>>>(q, k, dy, w.lse_dec2, w.part, s.H, s.N, s.M,
-                                                                       plan.bwd.chunk_len, plan.bwd.chunks, c2);
-    }
-    if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     {
         LaunchTimer t(KID_BWD_DZ_MERGE, stream);
-        dz_merge_kernel<D><<<bhm_blocks, 256, 0, stream>>>(w.part, z, w.dz, w.eps, BH, s.M, plan.bwd.chunks);
+        dz_merge_kernel<D><<<bhm_blocks, 256, 0, stream>>>(w.part, z, w.dz, w.eps, BH, s.M, dz_parts);
     }
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     {
@@ -594,7 +638,7 @@ int launch_encode_merge(const flare_shape &s, const float *m_part, const float *
                         float *z, float *lse_enc, int parts, hipStream_t stream)
 {
     const int BH = s.B * s.H;
-    const unsigned blocks = (unsigned)(((size_t)BH * s.M + 255) / 256);
+    const dim3 blocks((s.M + 15) / 16, BH);
     LaunchTimer t(KID_ENCODE_MERGE, stream);
     switch (s.d) {
         case 4: encode_merge_kernel<4><<<blocks, 256, 0, stream>>>(m_part, l_part, o_part, z, lse_enc, BH, s.M, parts); break;
@@ -613,7 +657,7 @@ ValuPlan valu_plan(const flare_shape &s)
     p.enc = plan_split(s.N, BH, 256, 2048);
     p.bwd = plan_split(s.N, BH, 256, 2048);
     p.fwd_bytes = valu_fwd_layout(s, p.enc, nullptr, nullptr, nullptr, nullptr);
-    p.bwd_bytes = bwd_layout(s, p.bwd, nullptr, nullptr);
+    p.bwd_bytes = bwd_layout(s, bwd_slots(s, p), nullptr, nullptr);
     return p;
 }
 
