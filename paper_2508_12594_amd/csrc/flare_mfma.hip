@@ -600,6 +600,232 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     }
 }
 
+// ============================================================================================
+// Backward, dQ partials (latent-major, same wave geometry as the encode).  For its NB latent tiles
+// a wave keeps, as B operands (column = latent, contraction over d): q' hi and lo, dZ and Z in
+// bf16.  Per 32-token tile it streams K, V and dY as A operands (row = token) and forms, all on
+// the matrix cores,
+//     S2 - lse_enc2[m]   (-lse_enc2 as a hi+lo pair in slots 0,1 of the lo query operand, x 1,1)
+//     S2 - lse_dec2[n]   (-lse_dec2 in slots 2,3 of the lo key operand, x 1,1)
+//     a[n][m] = <V_n, dZ_m> - eps[m]      (-eps rides in one more, otherwise empty, k-step)
+//     c[n][m] = <dY_n, Z_m> - delta[n]    (-delta likewise)
+// then dS^T = 2^(..) a + 2^(..) c in fp32, rounds it to bf16 and accumulates
+//     dQ^T[dd][m] += K^T[dd][n] dS^T[n][m]
+// with K^T read back from a wave-private, double-buffered LDS tile.  Masked tokens have both
+// exponents at -inf, so their dS is exactly zero.
+// ============================================================================================
+template <int D, int NB, int MINB>
+__global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
+    const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
+    const bf16_t *__restrict__ dy, const float *__restrict__ z, const float *__restrict__ lse_enc,
+    const float *__restrict__ dz, const float *__restrict__ eps, const float *__restrict__ lse_dec2,
+    const float *__restrict__ delta, float *__restrict__ dq_part,
+    int H, int N, int M, int chunk_len, int parts, int G, int TG, float c2)
+{
+    constexpr int KS = D / 16;
+    constexpr int HV = D / 16;
+    constexpr int ROWS = D + 1;                 // K^T rows, then a row of zeros
+    constexpr int BUF = ROWS * kVtStride;
+    __shared__ __attribute__((aligned(16))) uint16_t kt_all[4][2 * BUF];
+
+    const int lane = threadIdx.x & 63, l32 = lane & 31, hh = lane >> 5;
+    const int wave = threadIdx.x >> 6;
+    const int g = wave % G, tg = wave / G;
+    const int bh = blockIdx.y, h = bh % H, chunk = blockIdx.x;
+    const bool lower = hh == 0;
+    uint16_t *lds = kt_all[wave];
+    if (lane < kVtStride) {
+        lds[D * kVtStride + lane] = 0;
+        lds[BUF + D * kVtStride + lane] = 0;
+    }
+
+    // ---- per-latent operands ----
+    const int lat0 = 32 * NB * g;
+    bf16x8 qh[NB][KS], ql[NB][KS], dzb[NB][KS], zb[NB][KS], dz_aug[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        const int m = lat0 + 32 * b + l32;
+        load_q_operand<D, true>(q + ((size_t)h * M + m) * D, hh, c2, false, qh[b], ql[b]);
+        const float le2 = lse_enc[(size_t)bh * M + m] * kLog2e;
+        ql[b][0] = with_slots(ql[b][0], lower, split_bf16_pair(-le2), 0x3f803f80u);
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const float *zr = z + ((size_t)bh * M + m) * D + (D / 2) * hh + 8 * s;
+            const float *dr = dz + ((size_t)bh * M + m) * D + (D / 2) * hh + 8 * s;
+            u32x4 wz, wd;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                wz[i] = rne_bf16(zr[2 * i]) | (rne_bf16(zr[2 * i + 1]) << 16);
+                wd[i] = rne_bf16(dr[2 * i]) | (rne_bf16(dr[2 * i + 1]) << 16);
+            }
+            zb[b][s] = as_bf16x8(wz);
+            dzb[b][s] = as_bf16x8(wd);
+        }
+        u32x4 we;
+        we[0] = lower ? split_bf16_pair(-eps[(size_t)bh * M + m]) : 0u;
+        we[1] = 0u; we[2] = 0u; we[3] = 0u;
+        dz_aug[b] = as_bf16x8(we);
+    }
+    u32x4 w11;
+    w11[0] = lower ? 0x3f803f80u : 0u;
+    w11[1] = 0u; w11[2] = 0u; w11[3] = 0u;
+    const bf16x8 ones_aug = as_bf16x8(w11);      // slots 0,1 = 1 in the lower lane half, else 0
+
+    const bf16_t *kb = k + (size_t)bh * N * D;
+    const bf16_t *vb = v + (size_t)bh * N * D;
+    const bf16_t *gb = dy + (size_t)bh * N * D;
+    const float *lb = lse_dec2 + (size_t)bh * N;
+    const float *db = delta + (size_t)bh * N;
+    const int n0 = chunk * chunk_len;
+    const int n1 = min(N, n0 + chunk_len);
+    const int tiles = (n1 - n0 + 31) / 32;
+    const int cnt = (tiles > tg) ? (tiles - tg + TG - 1) / TG : 0;
+
+    f32x16 acc[NB][HV];
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int hv = 0; hv < HV; ++hv) acc[b][hv] = splat16(0.f);
+
+    int krow[HV];
+#pragma unroll
+    for (int hv = 0; hv < HV; ++hv) krow[hv] = (l32 < 16) ? 16 * hv + l32 : D;
+
+    auto tile_tok0 = [&](int j) { return n0 + 32 * (tg + min(j, cnt - 1) * TG); };
+    auto load_rows = [&](const bf16_t *base, int j, bf16x8 (&t)[KS]) {   // A operand: row = token
+        const int n = min(tile_tok0(j) + l32, N - 1);
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+            t[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(base + (size_t)n * D + (D / 2) * hh + 8 * s));
+    };
+    auto write_kt = [&](const bf16x8 (&t)[KS], uint16_t *buf) {   // transposed: row = d-index, column = token
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const u32x4 w = __builtin_bit_cast(u32x4, t[s]);
+            const int d0 = (D / 2) * hh + 8 * s;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                buf[(d0 + 2 * e) * kVtStride + l32] = (uint16_t)(w[e] & 0xffffu);
+                buf[(d0 + 2 * e + 1) * kVtStride + l32] = (uint16_t)(w[e] >> 16);
+            }
+        }
+    };
+    auto read_kT = [&](const uint16_t *buf, bf16x8 (&kT)[HV][2]) {
+#pragma unroll
+        for (int hv = 0; hv < HV; ++hv)
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+                const uint16_t *row = buf + krow[hv] * kVtStride + 16 * s2 + 4 * hh;
+                const u32x2 a = *reinterpret_cast<const u32x2 *>(row);
+                const u32x2 b = *reinterpret_cast<const u32x2 *>(row + 8);
+                u32x4 w;
+                w[0] = a[0]; w[1] = a[1]; w[2] = b[0]; w[3] = b[1];
+                kT[hv][s2] = as_bf16x8(w);
+            }
+    };
+
+    if (cnt > 0) {
+        bf16x8 kt[KS], ktn[KS], ktnn[KS], vt[KS], vtn[KS], gt[KS], gtn[KS], kT[HV][2];
+        float nld, nldn, dl, dln;
+        load_rows(kb, 0, kt);
+        load_rows(kb, 1, ktn);
+        load_rows(vb, 0, vt);
+        load_rows(gb, 0, gt);
+        nld = -lb[min(tile_tok0(0) + l32, N - 1)];
+        dl = db[min(tile_tok0(0) + l32, N - 1)];
+        compiler_fence();
+        write_kt(kt, lds);
+        compiler_fence();
+        read_kT(lds, kT);
+
+        for (int j = 0; j < cnt; ++j) {
+            const int tok0 = tile_tok0(j);
+            uint16_t *buf_next = lds + ((j + 1) & 1) * BUF;
+            load_rows(kb, j + 2, ktnn);
+            load_rows(vb, j + 1, vtn);
+            load_rows(gb, j + 1, gtn);
+            nldn = -lb[min(tile_tok0(j + 1) + l32, N - 1)];
+            dln = db[min(tile_tok0(j + 1) + l32, N - 1)];
+            compiler_fence();
+            write_kt(ktn, buf_next);
+            compiler_fence();
+
+            // token-side operands of the lo and of the correction k-steps
+            u32x4 wa = __builtin_bit_cast(u32x4, kt[0]), wb = wa;
+            wa[0] = lower ? 0x3f803f80u : wa[0];                 // slots 0,1 := 1   (picks -lse_enc2)
+            wa[1] = lower ? 0u : wa[1];                          // slots 2,3 := 0
+            wb[0] = lower ? 0u : wb[0];                          // slots 0,1 := 0
+            wb[1] = lower ? split_bf16_pair(nld) : wb[1];        // slots 2,3 := -lse_dec2[n]
+            const bf16x8 kt_a = as_bf16x8(wa), kt_b = as_bf16x8(wb);
+            u32x4 wg;
+            wg[0] = lower ? split_bf16_pair(-dl) : 0u;
+            wg[1] = 0u; wg[2] = 0u; wg[3] = 0u;
+            const bf16x8 g_aug = as_bf16x8(wg);
+
+            const int rem = n1 - tok0 - 4 * hh;
+            const bool partial = tok0 + 32 > n1;
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                f32x16 x = splat16(0.f);
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) x = mfma(kt[ks], qh[b][ks], x);
+                f32x16 s1 = mfma(kt_a, ql[b][0], x);
+                f32x16 s2 = mfma(kt_b, ql[b][0], x);
+#pragma unroll
+                for (int ks = 1; ks < KS; ++ks) {
+                    s1 = mfma(kt[ks], ql[b][ks], s1);
+                    s2 = mfma(kt[ks], ql[b][ks], s2);
+                }
+                f32x16 av = mfma(ones_aug, dz_aug[b], splat16(0.f));
+                f32x16 cv = mfma(g_aug, ones_aug, splat16(0.f));
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    av = mfma(vt[ks], dzb[b][ks], av);
+                    cv = mfma(gt[ks], zb[b][ks], cv);
+                }
+                if (partial) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (8 * (r / 4) + (r % 4) >= rem) { s1[r] = -INFINITY; s2[r] = -INFINITY; }
+                }
+                f32x16 ds;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) ds[i] = fmaf(fast_exp2(s2[i]), cv[i], fast_exp2(s1[i]) * av[i]);
+                u32x4 w0, w1;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    w0[i] = cvt_pk_bf16(ds[2 * i], ds[2 * i + 1]);
+                    w1[i] = cvt_pk_bf16(ds[8 + 2 * i], ds[8 + 2 * i + 1]);
+                }
+#pragma unroll
+                for (int hv = 0; hv < HV; ++hv) {
+                    acc[b][hv] = mfma(kT[hv][0], as_bf16x8(w0), acc[b][hv]);
+                    acc[b][hv] = mfma(kT[hv][1], as_bf16x8(w1), acc[b][hv]);
+                }
+            }
+            compiler_fence();
+            read_kT(buf_next, kT);
+#pragma unroll
+            for (int s = 0; s < KS; ++s) { kt[s] = ktn[s]; ktn[s] = ktnn[s]; vt[s] = vtn[s]; gt[s] = gtn[s]; }
+            nld = nldn;
+            dl = dln;
+        }
+    }
+
+    const size_t part = (size_t)bh * parts + (size_t)chunk * TG + tg;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        const size_t slot = part * M + lat0 + 32 * b + l32;
+#pragma unroll
+        for (int hv = 0; hv < HV; ++hv) {
+            float4 lo4 = make_float4(acc[b][hv][0], acc[b][hv][1], acc[b][hv][2], acc[b][hv][3]);
+            float4 hi4 = make_float4(acc[b][hv][4], acc[b][hv][5], acc[b][hv][6], acc[b][hv][7]);
+            *reinterpret_cast<float4 *>(dq_part + slot * D + 16 * hv + 4 * hh) = lo4;
+            *reinterpret_cast<float4 *>(dq_part + slot * D + 16 * hv + 8 + 4 * hh) = hi4;
+        }
+    }
+}
+
 inline int check_launch() { return hipGetLastError() == hipSuccess ? FLARE_OK : FLARE_ELAUNCH; }
 
 // latent-group geometry of the encode for a given M
@@ -704,6 +930,49 @@ int mfma_dz_partial(const flare_shape &s, const void *q, const void *k, const vo
     else FLARE_DZ(32, 2);
 #undef FLARE_DZ
     return check_launch();
+}
+
+// dQ partials of the backward; slot layout as the encode partials: [(b*h) * parts + part][M][d]
+int mfma_dq_partial(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy,
+                    const float *z, const float *lse_enc, const float *dz, const float *eps,
+                    const float *lse_dec2, const float *delta, float *dq_part, float scale, hipStream_t stream)
+{
+    const MfmaPlan p = mfma_plan(s);
+    EncGeom e = enc_geom(s.M, s.d);
+    if (e.NB == 4) {   // this kernel keeps more operands per latent tile: two tiles per wave at most
+        e.NB = 2;
+        e.G = s.M / 64;
+        e.TG = (e.G == 3) ? 1 : 4 / e.G;
+        e.threads = 64 * e.G * e.TG;
+    }
+    const int BH = s.B * s.H;
+    const float c2 = scale * kLog2e;
+    const int parts = p.enc.chunks * e.TG;
+    const dim3 grid(p.enc.chunks, BH);
+    const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *vv = (const bf16_t *)v, *gg = (const bf16_t *)dy;
+    LaunchTimer t(KID_BWD_DQ_PARTIAL, stream);
+#define FLARE_DQ(DD, NBB, MINB)                                                                                 \
+    bwd_dq_mfma_kernel<DD, NBB, MINB><<<grid, e.threads, 0, stream>>>(qq, kk, vv, gg, z, lse_enc, dz, eps, lse_dec2, \
+                                                                      delta, dq_part, s.H, s.N, s.M,                \
+                                                                      p.enc.chunk_len, parts, e.G, e.TG, c2)
+    if (s.d == 16 && e.NB == 1) FLARE_DQ(16, 1, 2);
+    else if (s.d == 16) FLARE_DQ(16, 2, 2);
+    else if (e.NB == 1) FLARE_DQ(32, 1, 2);
+    else FLARE_DQ(32, 2, 1);
+#undef FLARE_DQ
+    return check_launch();
+}
+
+// partial slots per (b,h) that mfma_dq_partial writes
+int mfma_dq_parts(const flare_shape &s)
+{
+    const MfmaPlan p = mfma_plan(s);
+    EncGeom e = enc_geom(s.M, s.d);
+    if (e.NB == 4) {
+        e.G = s.M / 64;
+        e.TG = (e.G == 3) ? 1 : 4 / e.G;
+    }
+    return p.enc.chunks * e.TG;
 }
 
 template <int MODE>

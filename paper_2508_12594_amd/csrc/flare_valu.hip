@@ -501,7 +501,11 @@ inline int check_launch() { return hipGetLastError() == hipSuccess ? FLARE_OK : 
 
 inline int bwd_slots(const flare_shape &s, const ValuPlan &plan)
 {
-    const int mf = mfma_supported(s) ? mfma_plan(s).parts : 0;
+    int mf = 0;
+    if (mfma_supported(s)) {
+        mf = mfma_plan(s).parts;
+        if (mfma_dq_parts(s) > mf) mf = mfma_dq_parts(s);
+    }
     return plan.bwd.chunks > mf ? plan.bwd.chunks : mf;
 }
 
@@ -573,7 +577,13 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
         dz_merge_kernel<D><<<bhm_blocks, 256, 0, stream>>>(w.part, z, w.dz, w.eps, BH, s.M, dz_parts);
     }
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
-    {
+    int dq_parts = plan.bwd.chunks;
+    if (mf) {
+        dq_parts = mfma_dq_parts(s);
+        const int rc = mfma_dq_partial(s, q, k, v, dy, z, lse_enc, w.dz, w.eps, w.lse_dec2, w.delta, w.part, scale,
+                                       stream);
+        if (rc != FLARE_OK) return rc;
+    } else {
         LaunchTimer t(KID_BWD_DQ_PARTIAL, stream);
         dq_partial_kernel<T, D><<<lat_grid, kLatentBlock, 0, stream>>>(q, k, v, dy, z, lse_enc, w.dz, w.eps,
                                                                        w.lse_dec2, w.delta, w.part, s.H, s.N, s.M,
@@ -583,7 +593,7 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     {
         LaunchTimer t(KID_BWD_DQ_REDUCE, stream);
         const unsigned blocks = (unsigned)(((size_t)s.H * s.M + 255) / 256);
-        dq_reduce_kernel<D><<<blocks, 256, 0, stream>>>(w.part, dq, s.B, s.H, s.M, plan.bwd.chunks, scale);
+        dq_reduce_kernel<D><<<blocks, 256, 0, stream>>>(w.part, dq, s.B, s.H, s.M, dq_parts, scale);
     }
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     {
