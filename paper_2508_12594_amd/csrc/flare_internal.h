@@ -79,6 +79,10 @@ int mfma_decode(const flare_shape &s, const void *q, const void *k, const float 
                 float scale, hipStream_t stream);
 int mfma_token_stats(const flare_shape &s, const void *q, const void *k, const float *z, const void *dy,
                      float *lse_dec2, float *delta, float scale, hipStream_t stream);
+bool mfma_dkdv_supported(const flare_shape &s);
+int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy, const float *z,
+              const float *lse_enc, const float *dz, const float *eps, const float *lse_dec2, const float *delta,
+              void *dk, void *dv, float scale, hipStream_t stream);
 int mfma_dq_parts(const flare_shape &s);
 int mfma_dq_partial(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy,
                     const float *z, const float *lse_enc, const float *dz, const float *eps,

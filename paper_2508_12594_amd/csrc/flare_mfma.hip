@@ -826,6 +826,228 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
     }
 }
 
+// ============================================================================================
+// Backward, dK and dV (token-major, like the decode: one wave owns 32 tokens at a time and walks
+// over all latent tiles).  Everything that depends on the latents only is prepared once per
+// workgroup as MFMA-ready operand images in LDS (one (b,h) per workgroup, 8 waves share it):
+//   A-type images (row = latent, contraction over d): q' hi, q' lo (slots 0,1 = -lse_enc2 pair,
+//     slots 2,3 = 1,1), dZ hi (and lo), Z hi (and lo);
+//   row images (row = output column, contraction over the 32 latents in accumulator order):
+//     RW1 = [dZ^T ; -(eps q)^T]   and   RW2 = [q^T ; 0].
+// Per token tile and latent tile:  P = 2^(S2 - lse_enc2[m]), R = 2^(S2 - lse_dec2[n]),
+//   a = <dZ_m, V_n>,  c = <Z_m, dY_n> - delta[n],  dS' = P a + R c  (fp32), then
+//   acc1 += RW1 . P   (rows 0-15: dV^T, rows 16-31: -(sum_m P eps_m q_m)^T)
+//   acc2 += RW2 . dS' (rows 0-15: (sum_m dS' q_m)^T)
+// and at the end  dV = acc1[0:16],  dK = scale * (acc2[0:16] + acc1[16:32]).
+// LO2: also carry lo terms of dZ and Z (more accurate a and c; needs more LDS).
+// ============================================================================================
+template <int D, int MT, bool LO2>
+__global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
+    const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
+    const bf16_t *__restrict__ dy, const float *__restrict__ z, const float *__restrict__ lse_enc,
+    const float *__restrict__ dz, const float *__restrict__ eps, const float *__restrict__ lse_dec2,
+    const float *__restrict__ delta, bf16_t *__restrict__ dk, bf16_t *__restrict__ dv,
+    int H, int N, float c2, float scale)
+{
+    constexpr int KS = D / 16;
+    constexpr int HV = D / 16;
+    constexpr int M = 32 * MT;
+    constexpr int NA = (LO2 ? 6 : 4) * KS;      // A-type images per latent tile
+    constexpr int NR = 4 * HV;                  // row images per latent tile (RW1, RW2) x 2 k-steps
+    constexpr int PER_TILE = NA + NR;
+    extern __shared__ __attribute__((aligned(16))) u32x4 img[];   // [MT][PER_TILE][64 lanes]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
+    const int wave = tid >> 6;
+    const int bh = blockIdx.y, h = bh % H;
+    const bool lower = hh == 0;
+
+    // ---- build the operand images ----
+    {
+        const bf16_t *qh_ = q + (size_t)h * M * D;
+        const float *zb = z + (size_t)bh * M * D;
+        const float *dzb = dz + (size_t)bh * M * D;
+        const float *eb = eps + (size_t)bh * M;
+        const float *leb = lse_enc + (size_t)bh * M;
+        for (int idx = tid; idx < MT * PER_TILE * 64; idx += 512) {
+            const int ln = idx & 63, sid = (idx >> 6) % PER_TILE, t = (idx >> 6) / PER_TILE;
+            const int r32 = ln & 31, hf = ln >> 5;
+            u32x4 w;
+            if (sid < NA) {
+                const int kind = sid / KS, ks = sid % KS;          // 0 qh, 1 ql, 2 dzh, 3 zh, 4 dzl, 5 zl
+                const int m = 32 * t + r32;
+                const int d0 = (D / 2) * hf + 8 * ks;
+                float x[8];
+                if (kind <= 1) {
+                    const u32x4 raw = *reinterpret_cast<const u32x4 *>(qh_ + (size_t)m * D + d0);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) { x[2 * i] = bf16_lo(raw[i]) * c2; x[2 * i + 1] = bf16_hi(raw[i]) * c2; }
+                } else {
+                    const float *src = ((kind == 2 || kind == 4) ? dzb : zb) + (size_t)m * D + d0;
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) x[i] = src[i];
+                }
+                const bool want_lo = (kind == 1 || kind >= 4);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    uint32_t a = rne_bf16(x[2 * i]), b = rne_bf16(x[2 * i + 1]);
+                    if (want_lo) {
+                        a = rne_bf16(x[2 * i] - __uint_as_float(a << 16));
+                        b = rne_bf16(x[2 * i + 1] - __uint_as_float(b << 16));
+                    }
+                    w[i] = a | (b << 16);
+                }
+                if (kind == 1 && ks == 0 && hf == 0) {
+                    w[0] = split_bf16_pair(-leb[m] * kLog2e);
+                    w[1] = 0x3f803f80u;
+                }
+            } else {
+                const int rsid = sid - NA;                          // (which, hv, s2)
+                const int which = rsid / (2 * HV), hv = (rsid / 2) % HV, s2 = rsid % 2;
+                const int dd = 16 * hv + (r32 & 15);
+#pragma unroll
+                for (int i = 0; i < 8; i += 2) {
+                    float a, b;
+                    const int m0 = 32 * t + perm_index(s2, hf, i), m1 = 32 * t + perm_index(s2, hf, i + 1);
+                    const float q0 = __uint_as_float((uint32_t)qh_[(size_t)m0 * D + dd] << 16);
+                    const float q1 = __uint_as_float((uint32_t)qh_[(size_t)m1 * D + dd] << 16);
+                    if (which == 0) {
+                        a = (r32 < 16) ? dzb[(size_t)m0 * D + dd] : -eb[m0] * q0;
+                        b = (r32 < 16) ? dzb[(size_t)m1 * D + dd] : -eb[m1] * q1;
+                    } else {
+                        a = (r32 < 16) ? q0 : 0.f;
+                        b = (r32 < 16) ? q1 : 0.f;
+                    }
+                    w[i / 2] = rne_bf16(a) | (rne_bf16(b) << 16);
+                }
+            }
+            img[idx] = w;
+        }
+    }
+    __syncthreads();
+
+    u32x4 w11;
+    w11[0] = lower ? 0x3f803f80u : 0u;
+    w11[1] = 0u; w11[2] = 0u; w11[3] = 0u;
+    const bf16x8 ones_aug = as_bf16x8(w11);
+
+    const bf16_t *kb = k + (size_t)bh * N * D;
+    const bf16_t *vb = v + (size_t)bh * N * D;
+    const bf16_t *gb = dy + (size_t)bh * N * D;
+    const float *lb = lse_dec2 + (size_t)bh * N;
+    const float *db = delta + (size_t)bh * N;
+    const int tiles = (N + 31) / 32;
+    const int stride = gridDim.x * 8;
+    auto load_cols = [&](const bf16_t *base, int tile, bf16x8 (&t)[KS]) {   // B operand: column = token
+        const int n = min(tile * 32 + l32, N - 1);
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+            t[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(base + (size_t)n * D + (D / 2) * hh + 8 * s));
+    };
+    auto image = [&](int t, int sid) { return as_bf16x8(img[(t * PER_TILE + sid) * 64 + lane]); };
+
+    int tile = blockIdx.x * 8 + wave;
+    bf16x8 kt[KS], vt[KS], gt[KS], ktn[KS], vtn[KS], gtn[KS];
+    if (tile < tiles) {
+        load_cols(kb, tile, kt);
+        load_cols(vb, tile, vt);
+        load_cols(gb, tile, gt);
+    }
+    for (; tile < tiles; tile += stride) {
+        const int n = tile * 32 + l32;
+        const int tn = (tile + stride < tiles) ? tile + stride : tile;
+        load_cols(kb, tn, ktn);
+        load_cols(vb, tn, vtn);
+        load_cols(gb, tn, gtn);
+        const size_t row = (size_t)min(n, N - 1);
+        const float nld = -lb[row], dl = db[row];
+
+        u32x4 wa = __builtin_bit_cast(u32x4, kt[0]), wb = wa;
+        wa[0] = lower ? 0x3f803f80u : wa[0];
+        wa[1] = lower ? 0u : wa[1];
+        wb[0] = lower ? 0u : wb[0];
+        wb[1] = lower ? split_bf16_pair(nld) : wb[1];
+        const bf16x8 kt_a = as_bf16x8(wa), kt_b = as_bf16x8(wb);
+        u32x4 wg;
+        wg[0] = lower ? split_bf16_pair(-dl) : 0u;
+        wg[1] = 0u; wg[2] = 0u; wg[3] = 0u;
+        const bf16x8 g_aug = as_bf16x8(wg);
+
+        f32x16 acc1[HV], acc2[HV];
+#pragma unroll
+        for (int hv = 0; hv < HV; ++hv) { acc1[hv] = splat16(0.f); acc2[hv] = splat16(0.f); }
+
+#pragma unroll 1
+        for (int t = 0; t < MT; ++t) {
+            f32x16 x = splat16(0.f);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) x = mfma(image(t, 0 * KS + ks), kt[ks], x);
+            const bf16x8 ql0 = image(t, 1 * KS);
+            f32x16 s1 = mfma(ql0, kt_a, x);
+            f32x16 s2 = mfma(ql0, kt_b, x);
+#pragma unroll
+            for (int ks = 1; ks < KS; ++ks) {
+                const bf16x8 qlk = image(t, 1 * KS + ks);
+                s1 = mfma(qlk, kt[ks], s1);
+                s2 = mfma(qlk, kt[ks], s2);
+            }
+            f32x16 av = splat16(0.f);
+            f32x16 cv = mfma(ones_aug, g_aug, splat16(0.f));
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                av = mfma(image(t, 2 * KS + ks), vt[ks], av);
+                cv = mfma(image(t, 3 * KS + ks), gt[ks], cv);
+                if constexpr (LO2) {
+                    av = mfma(image(t, 4 * KS + ks), vt[ks], av);
+                    cv = mfma(image(t, 5 * KS + ks), gt[ks], cv);
+                }
+            }
+            u32x4 p0, p1, d0, d1;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float pa = fast_exp2(s1[2 * i]), pb = fast_exp2(s1[2 * i + 1]);
+                const float pc = fast_exp2(s1[8 + 2 * i]), pd = fast_exp2(s1[8 + 2 * i + 1]);
+                p0[i] = cvt_pk_bf16(pa, pb);
+                p1[i] = cvt_pk_bf16(pc, pd);
+                d0[i] = cvt_pk_bf16(fmaf(fast_exp2(s2[2 * i]), cv[2 * i], pa * av[2 * i]),
+                                    fmaf(fast_exp2(s2[2 * i + 1]), cv[2 * i + 1], pb * av[2 * i + 1]));
+                d1[i] = cvt_pk_bf16(fmaf(fast_exp2(s2[8 + 2 * i]), cv[8 + 2 * i], pc * av[8 + 2 * i]),
+                                    fmaf(fast_exp2(s2[8 + 2 * i + 1]), cv[8 + 2 * i + 1], pd * av[8 + 2 * i + 1]));
+            }
+#pragma unroll
+            for (int hv = 0; hv < HV; ++hv) {
+                acc1[hv] = mfma(image(t, NA + (0 * HV + hv) * 2 + 0), as_bf16x8(p0), acc1[hv]);
+                acc1[hv] = mfma(image(t, NA + (0 * HV + hv) * 2 + 1), as_bf16x8(p1), acc1[hv]);
+                acc2[hv] = mfma(image(t, NA + (1 * HV + hv) * 2 + 0), as_bf16x8(d0), acc2[hv]);
+                acc2[hv] = mfma(image(t, NA + (1 * HV + hv) * 2 + 1), as_bf16x8(d1), acc2[hv]);
+            }
+        }
+        if (n < N) {
+            bf16_t *dkr = dk + ((size_t)bh * N + n) * D;
+            bf16_t *dvr = dv + ((size_t)bh * N + n) * D;
+#pragma unroll
+            for (int hv = 0; hv < HV; ++hv) {
+                u32x2 w0, w1;
+                w0[0] = cvt_pk_bf16(acc1[hv][0], acc1[hv][1]);
+                w0[1] = cvt_pk_bf16(acc1[hv][2], acc1[hv][3]);
+                w1[0] = cvt_pk_bf16(acc1[hv][4], acc1[hv][5]);
+                w1[1] = cvt_pk_bf16(acc1[hv][6], acc1[hv][7]);
+                *reinterpret_cast<u32x2 *>(dvr + 16 * hv + 4 * hh) = w0;
+                *reinterpret_cast<u32x2 *>(dvr + 16 * hv + 8 + 4 * hh) = w1;
+                w0[0] = cvt_pk_bf16(scale * (acc2[hv][0] + acc1[hv][8]), scale * (acc2[hv][1] + acc1[hv][9]));
+                w0[1] = cvt_pk_bf16(scale * (acc2[hv][2] + acc1[hv][10]), scale * (acc2[hv][3] + acc1[hv][11]));
+                w1[0] = cvt_pk_bf16(scale * (acc2[hv][4] + acc1[hv][12]), scale * (acc2[hv][5] + acc1[hv][13]));
+                w1[1] = cvt_pk_bf16(scale * (acc2[hv][6] + acc1[hv][14]), scale * (acc2[hv][7] + acc1[hv][15]));
+                *reinterpret_cast<u32x2 *>(dkr + 16 * hv + 4 * hh) = w0;
+                *reinterpret_cast<u32x2 *>(dkr + 16 * hv + 8 + 4 * hh) = w1;
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < KS; ++s) { kt[s] = ktn[s]; vt[s] = vtn[s]; gt[s] = gtn[s]; }
+    }
+}
+
 inline int check_launch() { return hipGetLastError() == hipSuccess ? FLARE_OK : FLARE_ELAUNCH; }
 
 // latent-group geometry of the encode for a given M
@@ -960,6 +1182,61 @@ int mfma_dq_partial(const flare_shape &s, const void *q, const void *k, const vo
     else if (e.NB == 1) FLARE_DQ(32, 1, 2);
     else FLARE_DQ(32, 2, 1);
 #undef FLARE_DQ
+    return check_launch();
+}
+
+// dK and dV of the backward.  One workgroup of 8 waves per (b,h) slice and block of token tiles;
+// the operand images need (4 or 6)*KS + 4*HV KiB of LDS per latent tile.
+bool mfma_dkdv_supported(const flare_shape &s)
+{
+    if (!mfma_supported(s)) return false;
+    const int MT = s.M / 32;
+    return MT == 1 || MT == 2 || MT == 4 || MT == 8;
+}
+
+int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy, const float *z,
+              const float *lse_enc, const float *dz, const float *eps, const float *lse_dec2, const float *delta,
+              void *dk, void *dv, float scale, hipStream_t stream)
+{
+    const int BH = s.B * s.H;
+    const int tiles = (s.N + 31) / 32;
+    int blocks = (256 + BH - 1) / BH;                 // one 8-wave workgroup per CU
+    if (blocks > (tiles + 7) / 8) blocks = (tiles + 7) / 8;
+    const dim3 grid(blocks, BH);
+    const float c2 = scale * kLog2e;
+    const int MT = s.M / 32;
+    const bool lo2 = (s.d == 16);
+    const int KS = s.d / 16, HV = s.d / 16;
+    const size_t lds = (size_t)MT * ((lo2 ? 6 : 4) * KS + 4 * HV) * 1024;
+    const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *vv = (const bf16_t *)v, *gg = (const bf16_t *)dy;
+    LaunchTimer t(KID_BWD_DKDV, stream);
+#define FLARE_DKDV(DD, MTT, LO)                                                                                  \
+    do {                                                                                                         \
+        auto kern = bwd_dkdv_mfma_kernel<DD, MTT, LO>;                                                           \
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                (int)lds) != hipSuccess)                                                         \
+            return FLARE_ELAUNCH;                                                                                \
+        kern<<<grid, 512, lds, stream>>>(qq, kk, vv, gg, z, lse_enc, dz, eps, lse_dec2, delta, (bf16_t *)dk,      \
+                                         (bf16_t *)dv, s.H, s.N, c2, scale);                                     \
+    } while (0)
+    if (s.d == 16) {
+        switch (MT) {
+            case 1: FLARE_DKDV(16, 1, true); break;
+            case 2: FLARE_DKDV(16, 2, true); break;
+            case 4: FLARE_DKDV(16, 4, true); break;
+            case 8: FLARE_DKDV(16, 8, true); break;
+            default: return FLARE_EUNSUPPORTED;
+        }
+    } else {
+        switch (MT) {
+            case 1: FLARE_DKDV(32, 1, false); break;
+            case 2: FLARE_DKDV(32, 2, false); break;
+            case 4: FLARE_DKDV(32, 4, false); break;
+            case 8: FLARE_DKDV(32, 8, false); break;
+            default: return FLARE_EUNSUPPORTED;
+        }
+    }
+#undef FLARE_DKDV
     return check_launch();
 }
 

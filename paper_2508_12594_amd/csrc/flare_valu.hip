@@ -596,6 +596,8 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
         dq_reduce_kernel<D><<<blocks, 256, 0, stream>>>(w.part, dq, s.B, s.H, s.M, dq_parts, scale);
     }
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
+    if (mf && mfma_dkdv_supported(s))
+        return mfma_dkdv(s, q, k, v, dy, z, lse_enc, w.dz, w.eps, w.lse_dec2, w.delta, dk, dv, scale, stream);
     {
         LaunchTimer t(KID_BWD_DKDV, stream);
         dkdv_kernel<T, D><<<tok_grid, kTokenBlock, 0, stream>>>(q, k, v, dy, z, lse_enc, w.dz, w.eps, w.lse_dec2,
