@@ -152,7 +152,7 @@ def main():
 
     if not args.no_cpu_baseline:
         from oracle import flare_oracle
-        n_s = min(N, 65536)
+        n_s = min(N, 1 << 20)
         sub = {n: inp[n][:1, :1, :n_s] for n in ("k", "v", "dy")}
         q1 = inp["q"][:1]
         t0 = time.perf_counter()

@@ -127,14 +127,6 @@ __device__ __forceinline__ void load_q_operand(const bf16_t *__restrict__ q_row,
     }
 }
 
-// Replace contraction slots 0..3 (words 0 and 1) of an operand in the lower lane half.
-__device__ __forceinline__ bf16x8 with_slots(bf16x8 x, bool lower_half, uint32_t w0, uint32_t w1)
-{
-    u32x4 w = __builtin_bit_cast(u32x4, x);
-    w[0] = lower_half ? w0 : w[0];
-    w[1] = lower_half ? w1 : w[1];
-    return __builtin_bit_cast(bf16x8, w);
-}
 // x as a hi + lo pair of bf16 values packed in one word (hi in the low half)
 __device__ __forceinline__ uint32_t split_bf16_pair(float x)
 {
@@ -362,8 +354,8 @@ constexpr int kVtStride = 36;   // uint16 per LDS row: 32 tokens + 4 pad (72 B, 
 
 // MODE 1 (second step of the backward) reuses the same machinery for dZ = R^T dY: the values are
 // dY, the weights are R^T[n][m] = 2^(S2 - lse_dec2[n]) with the per-token -lse_dec2 carried as a
-// hi + lo bf16 pair in slots 2,3 of the key operand of the lo product (against 1,1 on the query
-// side), and there is no softmax state: only the unnormalised sums are written.
+// hi + lo bf16 pair in one more k-step (token side: slots 2,3; query side: 1,1), and there is no
+// softmax state: only the unnormalised sums are written.
 template <int D, int NB, int MINB, int MODE>
 __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
@@ -397,11 +389,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         load_q_operand<D, true>(q + ((size_t)h * M + lat0 + 32 * b + l32) * D, hh, c2, false, qh[b], ql[b]);
-        if constexpr (MODE == 0) {
-            ql[b][0] = with_slot0(ql[b][0], keep0, 0u);   // slot 0 := -c = 0
-        } else {
-            ql[b][0] = with_slots(ql[b][0], hh == 0, 0u, 0x3f803f80u);   // slots 0,1 := 0; slots 2,3 := 1
-        }
+        if constexpr (MODE == 0) ql[b][0] = with_slot0(ql[b][0], keep0, 0u);   // slot 0 := -c = 0
     }
 
     const bf16_t *kb = k + (size_t)bh * N * D;
@@ -466,24 +454,34 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
                 va[hv][s2] = as_bf16x8(w);
             }
     };
+    u32x4 w23;
+    w23[0] = 0u; w23[1] = hh == 0 ? 0x3f803f80u : 0u; w23[2] = 0u; w23[3] = 0u;
+    const bf16x8 ones23 = as_bf16x8(w23);      // query side of the correction k-step: slots 2,3 = 1
     // scores minus the stabiliser of latent tile b against the token tile (kk, kk0a = kk[0] with slot 0 := 1)
     auto qk = [&](int b, const bf16x8 (&kk)[KS], bf16x8 kk0a) {
         f32x16 r = splat16(0.f);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) r = mfma(kk[ks], qh[b][ks], r);
-        r = mfma(kk0a, ql[b][0], r);
+        if constexpr (MODE == 0) {
+            r = mfma(kk0a, ql[b][0], r);
+        } else {
+            r = mfma(kk[0], ql[b][0], r);
+            r = mfma(kk0a, ones23, r);
+        }
 #pragma unroll
         for (int ks = 1; ks < KS; ++ks) r = mfma(kk[ks], ql[b][ks], r);
         return r;
     };
     const uint32_t one0 = hh == 0 ? 0x3f80u : 0u;
     const float *lb = (MODE == 1) ? lse_dec2 + (size_t)bh * N : nullptr;
-    // key operand of the lo product: slot 0 := 1 (MODE 0), or slots 2,3 := -lse_dec2 of this lane's token
+    // MODE 0: key operand of the lo product with slot 0 := 1.  MODE 1: key operand of a separate
+    // correction k-step, zero except slots 2,3 := -lse_dec2 of this lane's token (hi + lo pair).
     auto k_aug = [&](bf16x8 k0, float neg_lse) {
         if constexpr (MODE == 0) return with_slot0(k0, keep0, one0);
         else {
-            u32x4 w = __builtin_bit_cast(u32x4, k0);
-            w[1] = hh == 0 ? split_bf16_pair(neg_lse) : w[1];
+            u32x4 w;
+            w[0] = 0u; w[2] = 0u; w[3] = 0u;
+            w[1] = hh == 0 ? split_bf16_pair(neg_lse) : 0u;
             return as_bf16x8(w);
         }
     };
@@ -603,10 +601,10 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
 // ============================================================================================
 // Backward, dQ partials (latent-major, same wave geometry as the encode).  For its NB latent tiles
 // a wave keeps, as B operands (column = latent, contraction over d): q' hi and lo, dZ and Z in
-// bf16.  Per 32-token tile it streams K, V and dY as A operands (row = token) and forms, all on
-// the matrix cores,
-//     S2 - lse_enc2[m]   (-lse_enc2 as a hi+lo pair in slots 0,1 of the lo query operand, x 1,1)
-//     S2 - lse_dec2[n]   (-lse_dec2 in slots 2,3 of the lo key operand, x 1,1)
+// bf16 (hi and, at d = 16, lo).  Per 32-token tile it streams K, V and dY as A operands
+// (row = token) and forms, all on the matrix cores,
+//     S2 - lse_enc2[m]   (one more k-step: -lse_enc2 as a hi+lo pair in slots 0,1, against 1,1)
+//     S2 - lse_dec2[n]   (likewise -lse_dec2 in slots 2,3 of the token-side operand)
 //     a[n][m] = <V_n, dZ_m> - eps[m]      (-eps rides in one more, otherwise empty, k-step)
 //     c[n][m] = <dY_n, Z_m> - delta[n]    (-delta likewise)
 // then dS^T = 2^(..) a + 2^(..) c in fp32, rounds it to bf16 and accumulates
@@ -641,25 +639,38 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
 
     // ---- per-latent operands ----
     const int lat0 = 32 * NB * g;
-    bf16x8 qh[NB][KS], ql[NB][KS], dzb[NB][KS], zb[NB][KS], dz_aug[NB];
+    constexpr bool LO2 = (D == 16);             // carry lo terms of dZ and Z as well
+    bf16x8 qh[NB][KS], ql[NB][KS], q_aug[NB], dzb[NB][KS], zb[NB][KS], dzl[NB][KS], zl[NB][KS], dz_aug[NB];
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         const int m = lat0 + 32 * b + l32;
         load_q_operand<D, true>(q + ((size_t)h * M + m) * D, hh, c2, false, qh[b], ql[b]);
         const float le2 = lse_enc[(size_t)bh * M + m] * kLog2e;
-        ql[b][0] = with_slots(ql[b][0], lower, split_bf16_pair(-le2), 0x3f803f80u);
+        u32x4 wq;
+        wq[0] = lower ? split_bf16_pair(-le2) : 0u;     // slots 0,1 := -lse_enc2 (hi + lo)
+        wq[1] = lower ? 0x3f803f80u : 0u;               // slots 2,3 := 1
+        wq[2] = 0u; wq[3] = 0u;
+        q_aug[b] = as_bf16x8(wq);
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             const float *zr = z + ((size_t)bh * M + m) * D + (D / 2) * hh + 8 * s;
             const float *dr = dz + ((size_t)bh * M + m) * D + (D / 2) * hh + 8 * s;
-            u32x4 wz, wd;
+            u32x4 wz, wd, wzl, wdl;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                wz[i] = rne_bf16(zr[2 * i]) | (rne_bf16(zr[2 * i + 1]) << 16);
-                wd[i] = rne_bf16(dr[2 * i]) | (rne_bf16(dr[2 * i + 1]) << 16);
+                const uint32_t z0 = rne_bf16(zr[2 * i]), z1 = rne_bf16(zr[2 * i + 1]);
+                const uint32_t d0 = rne_bf16(dr[2 * i]), d1 = rne_bf16(dr[2 * i + 1]);
+                wz[i] = z0 | (z1 << 16);
+                wd[i] = d0 | (d1 << 16);
+                wzl[i] = rne_bf16(zr[2 * i] - __uint_as_float(z0 << 16)) |
+                         (rne_bf16(zr[2 * i + 1] - __uint_as_float(z1 << 16)) << 16);
+                wdl[i] = rne_bf16(dr[2 * i] - __uint_as_float(d0 << 16)) |
+                         (rne_bf16(dr[2 * i + 1] - __uint_as_float(d1 << 16)) << 16);
             }
             zb[b][s] = as_bf16x8(wz);
             dzb[b][s] = as_bf16x8(wd);
+            zl[b][s] = as_bf16x8(wzl);
+            dzl[b][s] = as_bf16x8(wdl);
         }
         u32x4 we;
         we[0] = lower ? split_bf16_pair(-eps[(size_t)bh * M + m]) : 0u;
@@ -750,13 +761,11 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
             write_kt(ktn, buf_next);
             compiler_fence();
 
-            // token-side operands of the lo and of the correction k-steps
-            u32x4 wa = __builtin_bit_cast(u32x4, kt[0]), wb = wa;
-            wa[0] = lower ? 0x3f803f80u : wa[0];                 // slots 0,1 := 1   (picks -lse_enc2)
-            wa[1] = lower ? 0u : wa[1];                          // slots 2,3 := 0
-            wb[0] = lower ? 0u : wb[0];                          // slots 0,1 := 0
-            wb[1] = lower ? split_bf16_pair(nld) : wb[1];        // slots 2,3 := -lse_dec2[n]
-            const bf16x8 kt_a = as_bf16x8(wa), kt_b = as_bf16x8(wb);
+            // token-side operands of the correction k-steps (zero outside the named slots)
+            u32x4 wb;
+            wb[0] = 0u; wb[2] = 0u; wb[3] = 0u;
+            wb[1] = lower ? split_bf16_pair(nld) : 0u;           // slots 2,3 := -lse_dec2[n]
+            const bf16x8 kt_a = ones_aug, kt_b = as_bf16x8(wb);  // slots 0,1 := 1 picks -lse_enc2
             u32x4 wg;
             wg[0] = lower ? split_bf16_pair(-dl) : 0u;
             wg[1] = 0u; wg[2] = 0u; wg[3] = 0u;
@@ -769,19 +778,20 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
                 f32x16 x = splat16(0.f);
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) x = mfma(kt[ks], qh[b][ks], x);
-                f32x16 s1 = mfma(kt_a, ql[b][0], x);
-                f32x16 s2 = mfma(kt_b, ql[b][0], x);
 #pragma unroll
-                for (int ks = 1; ks < KS; ++ks) {
-                    s1 = mfma(kt[ks], ql[b][ks], s1);
-                    s2 = mfma(kt[ks], ql[b][ks], s2);
-                }
+                for (int ks = 0; ks < KS; ++ks) x = mfma(kt[ks], ql[b][ks], x);
+                f32x16 s1 = mfma(kt_a, q_aug[b], x);
+                f32x16 s2 = mfma(kt_b, q_aug[b], x);
                 f32x16 av = mfma(ones_aug, dz_aug[b], splat16(0.f));
                 f32x16 cv = mfma(g_aug, ones_aug, splat16(0.f));
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
                     av = mfma(vt[ks], dzb[b][ks], av);
                     cv = mfma(gt[ks], zb[b][ks], cv);
+                    if constexpr (LO2) {
+                        av = mfma(vt[ks], dzl[b][ks], av);
+                        cv = mfma(gt[ks], zl[b][ks], cv);
+                    }
                 }
                 if (partial) {
 #pragma unroll
@@ -830,8 +840,8 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
 // Backward, dK and dV (token-major, like the decode: one wave owns 32 tokens at a time and walks
 // over all latent tiles).  Everything that depends on the latents only is prepared once per
 // workgroup as MFMA-ready operand images in LDS (one (b,h) per workgroup, 8 waves share it):
-//   A-type images (row = latent, contraction over d): q' hi, q' lo (slots 0,1 = -lse_enc2 pair,
-//     slots 2,3 = 1,1), dZ hi (and lo), Z hi (and lo);
+//   A-type images (row = latent, contraction over d): q' hi, q' lo, dZ hi (and lo), Z hi (and
+//     lo), and a correction operand (slots 0,1 = -lse_enc2 as a hi+lo pair, slots 2,3 = 1,1);
 //   row images (row = output column, contraction over the 32 latents in accumulator order):
 //     RW1 = [dZ^T ; -(eps q)^T]   and   RW2 = [q^T ; 0].
 // Per token tile and latent tile:  P = 2^(S2 - lse_enc2[m]), R = 2^(S2 - lse_dec2[n]),
@@ -852,7 +862,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     constexpr int KS = D / 16;
     constexpr int HV = D / 16;
     constexpr int M = 32 * MT;
-    constexpr int NA = (LO2 ? 6 : 4) * KS;      // A-type images per latent tile
+    constexpr int NA = (LO2 ? 6 : 4) * KS + 1;  // A-type images per latent tile (the last one: corrections)
     constexpr int NR = 4 * HV;                  // row images per latent tile (RW1, RW2) x 2 k-steps
     constexpr int PER_TILE = NA + NR;
     extern __shared__ __attribute__((aligned(16))) u32x4 img[];   // [MT][PER_TILE][64 lanes]
@@ -874,7 +884,12 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
             const int ln = idx & 63, sid = (idx >> 6) % PER_TILE, t = (idx >> 6) / PER_TILE;
             const int r32 = ln & 31, hf = ln >> 5;
             u32x4 w;
-            if (sid < NA) {
+            if (sid == NA - 1) {
+                // correction operand: slots 0,1 = -lse_enc2 (hi + lo pair), slots 2,3 = 1, else zero
+                w[0] = hf == 0 ? split_bf16_pair(-leb[32 * t + r32] * kLog2e) : 0u;
+                w[1] = hf == 0 ? 0x3f803f80u : 0u;
+                w[2] = 0u; w[3] = 0u;
+            } else if (sid < NA) {
                 const int kind = sid / KS, ks = sid % KS;          // 0 qh, 1 ql, 2 dzh, 3 zh, 4 dzl, 5 zl
                 const int m = 32 * t + r32;
                 const int d0 = (D / 2) * hf + 8 * ks;
@@ -897,10 +912,6 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                         b = rne_bf16(x[2 * i + 1] - __uint_as_float(b << 16));
                     }
                     w[i] = a | (b << 16);
-                }
-                if (kind == 1 && ks == 0 && hf == 0) {
-                    w[0] = split_bf16_pair(-leb[m] * kLog2e);
-                    w[1] = 0x3f803f80u;
                 }
             } else {
                 const int rsid = sid - NA;                          // (which, hv, s2)
@@ -963,12 +974,10 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
         const size_t row = (size_t)min(n, N - 1);
         const float nld = -lb[row], dl = db[row];
 
-        u32x4 wa = __builtin_bit_cast(u32x4, kt[0]), wb = wa;
-        wa[0] = lower ? 0x3f803f80u : wa[0];
-        wa[1] = lower ? 0u : wa[1];
-        wb[0] = lower ? 0u : wb[0];
-        wb[1] = lower ? split_bf16_pair(nld) : wb[1];
-        const bf16x8 kt_a = as_bf16x8(wa), kt_b = as_bf16x8(wb);
+        u32x4 wb;
+        wb[0] = 0u; wb[2] = 0u; wb[3] = 0u;
+        wb[1] = lower ? split_bf16_pair(nld) : 0u;           // slots 2,3 := -lse_dec2[n]
+        const bf16x8 kt_a = ones_aug, kt_b = as_bf16x8(wb);  // slots 0,1 := 1 picks -lse_enc2
         u32x4 wg;
         wg[0] = lower ? split_bf16_pair(-dl) : 0u;
         wg[1] = 0u; wg[2] = 0u; wg[3] = 0u;
@@ -983,15 +992,11 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
             f32x16 x = splat16(0.f);
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) x = mfma(image(t, 0 * KS + ks), kt[ks], x);
-            const bf16x8 ql0 = image(t, 1 * KS);
-            f32x16 s1 = mfma(ql0, kt_a, x);
-            f32x16 s2 = mfma(ql0, kt_b, x);
 #pragma unroll
-            for (int ks = 1; ks < KS; ++ks) {
-                const bf16x8 qlk = image(t, 1 * KS + ks);
-                s1 = mfma(qlk, kt[ks], s1);
-                s2 = mfma(qlk, kt[ks], s2);
-            }
+            for (int ks = 0; ks < KS; ++ks) x = mfma(image(t, 1 * KS + ks), kt[ks], x);
+            const bf16x8 qa = image(t, NA - 1);
+            f32x16 s1 = mfma(qa, kt_a, x);
+            f32x16 s2 = mfma(qa, kt_b, x);
             f32x16 av = splat16(0.f);
             f32x16 cv = mfma(ones_aug, g_aug, splat16(0.f));
 #pragma unroll
@@ -1186,7 +1191,7 @@ int mfma_dq_partial(const flare_shape &s, const void *q, const void *k, const vo
 }
 
 // dK and dV of the backward.  One workgroup of 8 waves per (b,h) slice and block of token tiles;
-// the operand images need (4 or 6)*KS + 4*HV KiB of LDS per latent tile.
+// the operand images need (4 or 6)*KS + 1 + 4*HV KiB of LDS per latent tile.
 bool mfma_dkdv_supported(const flare_shape &s)
 {
     if (!mfma_supported(s)) return false;
@@ -1207,7 +1212,7 @@ int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v,
     const int MT = s.M / 32;
     const bool lo2 = (s.d == 16);
     const int KS = s.d / 16, HV = s.d / 16;
-    const size_t lds = (size_t)MT * ((lo2 ? 6 : 4) * KS + 4 * HV) * 1024;
+    const size_t lds = (size_t)MT * ((lo2 ? 6 : 4) * KS + 1 + 4 * HV) * 1024;
     const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *vv = (const bf16_t *)v, *gg = (const bf16_t *)dy;
     LaunchTimer t(KID_BWD_DKDV, stream);
 #define FLARE_DKDV(DD, MTT, LO)                                                                                  \
