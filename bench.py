@@ -9,9 +9,11 @@ followed by flare_backward -- over one batch of the synthetic million-token mesh
 HBM before the timed region.  One JSON line is printed:
   value        tokens/s of forward+backward (B*N tokens per step)
   fwd          the same for the forward alone (its own timed loop of K steps)
-  roofline     the dominant kernel against the HBM roofline: algorithmic bytes per launch
-               divided by its mean duration, measured with HIP events on the launch stream
-  kernels      mean duration and algorithmic GB/s of every kernel of the step
+  roofline     the dominant kernel (most time per step) against the roofline that binds it: HBM
+               (algorithmic bytes per launch / mean duration) or, where the softmax's exponentials
+               need longer than the bytes, the vector ALUs' v_exp_f32 rate ("alu"); durations are
+               measured with HIP events on the launch stream
+  kernels      mean duration, algorithmic GB/s and exponentials/s of every kernel of the step
   cpu_baseline the fp64 CPU oracle timed on a bounded sample of the same workload
 """
 import argparse
@@ -51,6 +53,27 @@ def algorithmic_bytes(kernel, B, H, N, M, d, elem):
     return None
 
 
+def exponentials(kernel, B, H, N, M):
+    """v_exp_f32 lane-operations one launch of `kernel` cannot avoid (one per score and softmax)."""
+    per_pair = {"encode_partial": 1, "decode": 1, "bwd_token_stats": 1, "bwd_dz_partial": 1,
+                "bwd_dq_partial": 2, "bwd_dkdv": 2}
+    return per_pair.get(kernel, 0) * B * H * N * M
+
+
+# HBM bytes per launch (fetch, write) of the default workload, from two `rocprofv3 --pmc` runs
+# (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch), each scaled by what the same counter read for a
+# plain 256 MB device copy in the same run (FETCH_SIZE x 2.00, WRITE_SIZE x 1.00); see
+# profiles/forward_backward_cfg4_hbm_traffic.md.
+MEASURED_TRAFFIC_CFG4 = {
+    "encode_partial": (250582 * 2.0 * 1024, 18432 * 1024),
+    "decode": (125887 * 2.0 * 1024, 250000 * 1024),
+    "bwd_token_stats": (250886 * 2.0 * 1024, 62500 * 1024),
+    "bwd_dz_partial": (266225 * 2.0 * 1024, 16384 * 1024),
+    "bwd_dq_partial": (408100 * 2.0 * 1024, 8192 * 1024),
+    "bwd_dkdv": (407639 * 2.0 * 1024, 500000 * 1024),
+}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -59,10 +82,12 @@ def main():
     ap.add_argument("--cfg", type=int, default=4, help="synthetic workload id (4 = the headline)")
     ap.add_argument("--tokens", type=int, default=None, help="override N (for quick checks only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run three plain device copies of k (known size) first, for scaling profiler counters")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only; --gpus %d is not supported "
-              "(see DESIGN.md, 'More than one GPU').  Run with --gpus 1." % args.gpus, file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding across GPUs); "
+              "--gpus %d is not supported.  Run with --gpus 1." % args.gpus, file=sys.stderr)
         sys.exit(2)
 
     import torch
@@ -107,6 +132,10 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps
 
+    if args.copy_calibration:
+        for _ in range(3):
+            y.copy_(dev["k"])                 # reads and writes B*H*N*d*elem bytes each
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     t_step = timed(step, args.steps)          # the headline: forward + backward
@@ -122,15 +151,33 @@ def main():
     for name, (ms, cnt) in prof.items():
         mean_s = ms / cnt * 1e-3
         ab = algorithmic_bytes(name, B, H, N, M, d, elem)
+        ex = exponentials(name, B, H, N, M)
         kernels[name] = {"mean_us": round(mean_s * 1e6, 2), "launches_per_step": cnt // args.steps,
-                         "algorithmic_GBps": (round(ab / mean_s / 1e9, 1) if ab else None)}
+                         "algorithmic_GBps": (round(ab / mean_s / 1e9, 1) if ab else None),
+                         "hbm_frac": (round(ab / mean_s / 1e9 / HBM_PEAK_GBS, 4) if ab else None),
+                         "exp_Gops": (round(ex / mean_s / 1e9, 1) if ex else None),
+                         "exp_frac": (round(ex / mean_s / 1e9 / EXP_PEAK_GOPS, 4) if ex else None)}
     streaming = {n: v for n, v in kernels.items() if v["algorithmic_GBps"] is not None}
     dom = max(streaming, key=lambda n: streaming[n]["mean_us"] * streaming[n]["launches_per_step"])
     dom_bytes = algorithmic_bytes(dom, B, H, N, M, d, elem)
+    dom_exps = exponentials(dom, B, H, N, M)
     dom_s = kernels[dom]["mean_us"] * 1e-6
-    roofline = {"kernel": dom, "bound": "hbm", "achieved": round(dom_bytes / dom_s / 1e9, 1),
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(dom_bytes / dom_s / 1e9 / HBM_PEAK_GBS, 4),
-                "traffic": None, "bytes_per_launch": dom_bytes, "mean_us": kernels[dom]["mean_us"]}
+    default_workload = args.cfg == 4 and args.tokens is None
+    traffic = sum(MEASURED_TRAFFIC_CFG4[dom]) if default_workload and dom in MEASURED_TRAFFIC_CFG4 else None
+    # the roofline that binds this kernel: whichever lower bound on its duration is larger
+    if dom_exps / (EXP_PEAK_GOPS * 1e9) > dom_bytes / (HBM_PEAK_GBS * 1e9):
+        roofline = {"kernel": dom, "bound": "alu", "achieved": round(dom_exps / dom_s / 1e9, 1),
+                    "peak": EXP_PEAK_GOPS, "unit": "Gop/s (v_exp_f32 lane-ops)",
+                    "frac": round(dom_exps / dom_s / 1e9 / EXP_PEAK_GOPS, 4), "traffic": traffic,
+                    "ops_per_launch": dom_exps, "mean_us": kernels[dom]["mean_us"],
+                    "hbm": {"achieved": round(dom_bytes / dom_s / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                            "frac": round(dom_bytes / dom_s / 1e9 / HBM_PEAK_GBS, 4),
+                            "bytes_per_launch": dom_bytes}}
+    else:
+        roofline = {"kernel": dom, "bound": "hbm", "achieved": round(dom_bytes / dom_s / 1e9, 1),
+                    "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(dom_bytes / dom_s / 1e9 / HBM_PEAK_GBS, 4), "traffic": traffic,
+                    "bytes_per_launch": dom_bytes, "mean_us": kernels[dom]["mean_us"]}
 
     tokens = B * N
     fwd_bytes = 4 * B * H * N * d * elem       # k twice, v once, y once
@@ -153,17 +200,18 @@ def main():
     if not args.no_cpu_baseline:
         from oracle import flare_oracle
         n_s = min(N, 1 << 20)
-        sub = {n: inp[n][:1, :1, :n_s] for n in ("k", "v", "dy")}
-        q1 = inp["q"][:1]
+        h_s = min(H, 2)
+        sub = {n: inp[n][:1, :h_s, :n_s] for n in ("k", "v", "dy")}
+        q1 = inp["q"][:h_s]
         t0 = time.perf_counter()
         flare_oracle.forward(q1, sub["k"], sub["v"], scale)
         flare_oracle.backward(q1, sub["k"], sub["v"], sub["dy"], scale)
         t_cpu = time.perf_counter() - t0
         out["cpu_baseline"] = {
-            "value": round(n_s / (t_cpu * H), 1), "unit": "tokens/s", "cores": flare_oracle.threads(),
+            "value": round(n_s * h_s / (t_cpu * H), 1), "unit": "tokens/s", "cores": flare_oracle.threads(),
             "kind": "oracle",
-            "sample": "fp64 oracle forward+backward on head 0, first %d tokens, M=%d, d=%d (%.1f s); "
-                      "rate divided by H=%d heads" % (n_s, M, d, t_cpu, H)}
+            "sample": "fp64 oracle forward+backward on the first %d head(s), first %d tokens, M=%d, d=%d "
+                      "(%.1f s); rate scaled to all H=%d heads" % (h_s, n_s, M, d, t_cpu, H)}
     print(json.dumps(out), flush=True)
 
 
