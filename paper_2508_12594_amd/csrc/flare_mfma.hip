@@ -865,6 +865,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     constexpr int NA = (LO2 ? 6 : 4) * KS + 1;  // A-type images per latent tile (the last one: corrections)
     constexpr int NR = 4 * HV;                  // row images per latent tile (RW1, RW2) x 2 k-steps
     constexpr int PER_TILE = NA + NR;
+    constexpr bool PREFETCH = (D == 16);        // registers allow a second image set at d = 16 only
     extern __shared__ __attribute__((aligned(16))) u32x4 img[];   // [MT][PER_TILE][64 lanes]
 
     const int tid = threadIdx.x;
@@ -987,25 +988,28 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
 #pragma unroll
         for (int hv = 0; hv < HV; ++hv) { acc1[hv] = splat16(0.f); acc2[hv] = splat16(0.f); }
 
-#pragma unroll 1
-        for (int t = 0; t < MT; ++t) {
+        // one latent tile t: `im` holds its NA A-type images; the row images are read here, early
+        // enough to arrive while the scores are exponentiated
+        auto tile_step = [&](int t, const bf16x8 (&im)[NA]) {
+            bf16x8 rw[NR];
+#pragma unroll
+            for (int r = 0; r < NR; ++r) rw[r] = image(t, NA + r);
             f32x16 x = splat16(0.f);
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) x = mfma(image(t, 0 * KS + ks), kt[ks], x);
+            for (int ks = 0; ks < KS; ++ks) x = mfma(im[0 * KS + ks], kt[ks], x);
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) x = mfma(image(t, 1 * KS + ks), kt[ks], x);
-            const bf16x8 qa = image(t, NA - 1);
-            f32x16 s1 = mfma(qa, kt_a, x);
-            f32x16 s2 = mfma(qa, kt_b, x);
+            for (int ks = 0; ks < KS; ++ks) x = mfma(im[1 * KS + ks], kt[ks], x);
+            f32x16 s1 = mfma(im[NA - 1], kt_a, x);
+            f32x16 s2 = mfma(im[NA - 1], kt_b, x);
             f32x16 av = splat16(0.f);
             f32x16 cv = mfma(ones_aug, g_aug, splat16(0.f));
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                av = mfma(image(t, 2 * KS + ks), vt[ks], av);
-                cv = mfma(image(t, 3 * KS + ks), gt[ks], cv);
+                av = mfma(im[2 * KS + ks], vt[ks], av);
+                cv = mfma(im[3 * KS + ks], gt[ks], cv);
                 if constexpr (LO2) {
-                    av = mfma(image(t, 4 * KS + ks), vt[ks], av);
-                    cv = mfma(image(t, 5 * KS + ks), gt[ks], cv);
+                    av = mfma(im[4 * KS + ks], vt[ks], av);
+                    cv = mfma(im[5 * KS + ks], gt[ks], cv);
                 }
             }
             u32x4 p0, p1, d0, d1;
@@ -1022,10 +1026,34 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
             }
 #pragma unroll
             for (int hv = 0; hv < HV; ++hv) {
-                acc1[hv] = mfma(image(t, NA + (0 * HV + hv) * 2 + 0), as_bf16x8(p0), acc1[hv]);
-                acc1[hv] = mfma(image(t, NA + (0 * HV + hv) * 2 + 1), as_bf16x8(p1), acc1[hv]);
-                acc2[hv] = mfma(image(t, NA + (1 * HV + hv) * 2 + 0), as_bf16x8(d0), acc2[hv]);
-                acc2[hv] = mfma(image(t, NA + (1 * HV + hv) * 2 + 1), as_bf16x8(d1), acc2[hv]);
+                acc1[hv] = mfma(rw[(0 * HV + hv) * 2 + 0], as_bf16x8(p0), acc1[hv]);
+                acc1[hv] = mfma(rw[(0 * HV + hv) * 2 + 1], as_bf16x8(p1), acc1[hv]);
+                acc2[hv] = mfma(rw[(1 * HV + hv) * 2 + 0], as_bf16x8(d0), acc2[hv]);
+                acc2[hv] = mfma(rw[(1 * HV + hv) * 2 + 1], as_bf16x8(d1), acc2[hv]);
+            }
+        };
+        auto load_images = [&](int t, bf16x8 (&im)[NA]) {
+#pragma unroll
+            for (int sid = 0; sid < NA; ++sid) im[sid] = image(t, sid);
+        };
+        if constexpr (PREFETCH && MT > 1) {
+            // two sets of A-type images in registers: the next latent tile's are read from LDS
+            // while the current tile is computed
+            bf16x8 imA[NA], imB[NA];
+            load_images(0, imA);
+#pragma unroll 1
+            for (int t = 0; t < MT; t += 2) {
+                load_images(t + 1, imB);
+                tile_step(t, imA);
+                if (t + 2 < MT) load_images(t + 2, imA);
+                tile_step(t + 1, imB);
+            }
+        } else {
+#pragma unroll 1
+            for (int t = 0; t < MT; ++t) {
+                bf16x8 im[NA];
+                load_images(t, im);
+                tile_step(t, im);
             }
         }
         if (n < N) {

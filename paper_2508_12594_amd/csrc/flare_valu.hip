@@ -333,24 +333,51 @@ __global__ __launch_bounds__(kLatentBlock) void dz_partial_kernel(
     store_row<D>(dz_part + (((size_t)bh * chunks + chunk) * M + m) * D, acc);
 }
 
-// dZ = sum of the chunk partials in chunk order; eps[m] = <dZ_m, Z_m>.  thread = (b*h, m).
+// Fixed-order sum of partial slots, shared by dZ and dQ.  A workgroup takes 16 rows (latents); the
+// 16 threads of a row each add the slots j, j+16, ... in order and a fixed xor-shuffle tree adds
+// the 16 results, so the association order depends on the slot count only.
+// Slot s of output row (outer, m) lives at  part[((s / inner) * stride_o + outer) * inner + s % inner][m]
+// with stride_o = outer count:  dZ: outer = b*h, one group of `inner` slots;  dQ: outer = h, the
+// slots of all batch items b (groups of `inner` partials each), i.e. the batch sum in b order.
+template <int D>
+__device__ __forceinline__ void sum_slots(const float *__restrict__ part, int outer, int n_outer, int groups,
+                                          int inner, int M, int m, int j, float (&acc)[D])
+{
+#pragma unroll
+    for (int i = 0; i < D; ++i) acc[i] = 0.f;
+    const int total = groups * inner;
+    for (int s = j; s < total; s += 16) {
+        const size_t slot = ((size_t)(s / inner) * n_outer + outer) * inner + (s % inner);
+        float t[D];
+        load_row<D>(part + (slot * M + m) * D, t);
+#pragma unroll
+        for (int i = 0; i < D; ++i) acc[i] += t[i];
+    }
+#pragma unroll
+    for (int off = 1; off < 16; off <<= 1) {
+        const bool low = (j & off) == 0;
+#pragma unroll
+        for (int i = 0; i < D; ++i) {
+            const float o = __shfl_xor(acc[i], off);
+            acc[i] = low ? (acc[i] + o) : (o + acc[i]);
+        }
+    }
+}
+
+// dZ[b*h][m] = sum of its partial slots; eps[m] = <dZ_m, Z_m>.
 template <int D>
 __global__ __launch_bounds__(256) void dz_merge_kernel(
     const float *__restrict__ dz_part, const float *__restrict__ z,
-    float *__restrict__ dz, float *__restrict__ eps, int BH, int M, int chunks)
+    float *__restrict__ dz, float *__restrict__ eps, int BH, int M, int parts)
 {
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (size_t)BH * M) return;
-    const int bh = (int)(idx / M), m = (int)(idx % M);
+    const int j = threadIdx.x & 15;
+    const int m = blockIdx.x * 16 + (threadIdx.x >> 4);
+    const int bh = blockIdx.y;
+    const bool live = m < M;
     float acc[D], zr[D];
-#pragma unroll
-    for (int j = 0; j < D; ++j) acc[j] = 0.f;
-    for (int c = 0; c < chunks; ++c) {
-        float t[D];
-        load_row<D>(dz_part + (((size_t)bh * chunks + c) * M + m) * D, t);
-#pragma unroll
-        for (int j = 0; j < D; ++j) acc[j] += t[j];
-    }
+    sum_slots<D>(dz_part, bh, BH, 1, parts, M, live ? m : M - 1, j, acc);
+    if (!live || j != 0) return;
+    const size_t idx = (size_t)bh * M + m;
     load_row<D>(z + idx * D, zr);
     store_row<D>(dz + idx * D, acc);
     eps[idx] = dot<D>(acc, zr);
@@ -400,27 +427,21 @@ __global__ __launch_bounds__(kLatentBlock) void dq_partial_kernel(
     store_row<D>(dq_part + (((size_t)bh * chunks + chunk) * M + m) * D, acc);
 }
 
-// dq_lat[h][m] = scale * sum over batch items (in b order) and chunks (in chunk order).
+// dq_lat[h][m] = scale * sum over batch items and partial slots (fixed order, see sum_slots).
 template <int D>
 __global__ __launch_bounds__(256) void dq_reduce_kernel(
-    const float *__restrict__ dq_part, float *__restrict__ dq, int B, int H, int M, int chunks, float scale)
+    const float *__restrict__ dq_part, float *__restrict__ dq, int B, int H, int M, int parts, float scale)
 {
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;   // (h, m)
-    if (idx >= (size_t)H * M) return;
-    const int h = (int)(idx / M), m = (int)(idx % M);
+    const int j = threadIdx.x & 15;
+    const int m = blockIdx.x * 16 + (threadIdx.x >> 4);
+    const int h = blockIdx.y;
+    const bool live = m < M;
     float acc[D];
+    sum_slots<D>(dq_part, h, H, B, parts, M, live ? m : M - 1, j, acc);
+    if (!live || j != 0) return;
 #pragma unroll
-    for (int j = 0; j < D; ++j) acc[j] = 0.f;
-    for (int b = 0; b < B; ++b)
-        for (int c = 0; c < chunks; ++c) {
-            float t[D];
-            load_row<D>(dq_part + ((((size_t)b * H + h) * chunks + c) * M + m) * D, t);
-#pragma unroll
-            for (int j = 0; j < D; ++j) acc[j] += t[j];
-        }
-#pragma unroll
-    for (int j = 0; j < D; ++j) acc[j] *= scale;
-    store_row<D>(dq + idx * D, acc);
+    for (int i = 0; i < D; ++i) acc[i] *= scale;
+    store_row<D>(dq + ((size_t)h * M + m) * D, acc);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -551,7 +572,6 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     const int lat_blocks = (s.M + kLatentBlock - 1) / kLatentBlock;
     const dim3 tok_grid((s.N + kTokenBlock - 1) / kTokenBlock, BH);
     const dim3 lat_grid(plan.bwd.chunks, BH, lat_blocks);
-    const unsigned bhm_blocks = (unsigned)(((size_t)BH * s.M + 255) / 256);
     if (mf) {
         int rc = mfma_token_stats(s, q, k, z, dy, w.lse_dec2, w.delta, scale, stream);
         if (rc != FLARE_OK) return rc;
@@ -574,7 +594,7 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     }
     {
         LaunchTimer t(KID_BWD_DZ_MERGE, stream);
-        dz_merge_kernel<D><<<bhm_blocks, 256, 0, stream>>>(w.part, z, w.dz, w.eps, BH, s.M, dz_parts);
+        dz_merge_kernel<D><<<dim3((s.M + 15) / 16, BH), 256, 0, stream>>>(w.part, z, w.dz, w.eps, BH, s.M, dz_parts);
     }
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     int dq_parts = plan.bwd.chunks;
@@ -592,8 +612,7 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     {
         LaunchTimer t(KID_BWD_DQ_REDUCE, stream);
-        const unsigned blocks = (unsigned)(((size_t)s.H * s.M + 255) / 256);
-        dq_reduce_kernel<D><<<blocks, 256, 0, stream>>>(w.part, dq, s.B, s.H, s.M, dq_parts, scale);
+        dq_reduce_kernel<D><<<dim3((s.M + 15) / 16, s.H), 256, 0, stream>>>(w.part, dq, s.B, s.H, s.M, dq_parts, scale);
     }
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     if (mf && mfma_dkdv_supported(s))
