@@ -42,6 +42,7 @@ def algorithmic_bytes(kernel, B, H, N, M, d, elem):
         "encode_partial": 2 * row,              # k, v
         "decode": 2 * row,                      # k in, y out
         "bwd_token_stats": 2 * row + 8,         # k, dy in; lse_dec, delta out
+        "bwd_prep": 2 * row + 12,               # y, dy, lse_dec in; lse_dec2, delta out
         "bwd_dz_partial": 2 * row + 4,          # k, dy, lse_dec in
         "bwd_dq_partial": 3 * row + 8,          # k, v, dy, lse_dec, delta in
         "bwd_dkdv": 5 * row + 8,                # k, v, dy in; dk, dv out
@@ -67,7 +68,6 @@ def exponentials(kernel, B, H, N, M):
 MEASURED_TRAFFIC_CFG4 = {
     "encode_partial": (250582 * 2.0 * 1024, 18432 * 1024),
     "decode": (125887 * 2.0 * 1024, 250000 * 1024),
-    "bwd_token_stats": (250886 * 2.0 * 1024, 62500 * 1024),
     "bwd_dz_partial": (266225 * 2.0 * 1024, 16384 * 1024),
     "bwd_dq_partial": (408100 * 2.0 * 1024, 8192 * 1024),
     "bwd_dkdv": (407639 * 2.0 * 1024, 500000 * 1024),
@@ -115,17 +115,18 @@ def main():
     y = torch.empty_like(dev["k"])
     z = torch.empty((B, H, M, d), dtype=torch.float32, device="cuda")
     lse = torch.empty((B, H, M), dtype=torch.float32, device="cuda")
+    lse_dec = torch.empty((B, H, N), dtype=torch.float32, device="cuda")
     dq = torch.empty((H, M, d), dtype=torch.float32, device="cuda")
     dk = torch.empty_like(dev["k"])
     dv = torch.empty_like(dev["k"])
 
     def fwd():
-        binding.forward(dev["q"], dev["k"], dev["v"], scale, y=y, z=z, lse_enc=lse, workspace=ws)
+        binding.forward(dev["q"], dev["k"], dev["v"], scale, y=y, z=z, lse_enc=lse, lse_dec=lse_dec, workspace=ws)
 
-    def step():
+    def step():   # a training step: the forward saves z, lse_enc, lse_dec and y for the backward
         fwd()
-        binding.backward(dev["q"], dev["k"], dev["v"], dev["dy"], z, lse, scale, dq_lat=dq, dk=dk, dv=dv,
-                         workspace=ws)
+        binding.backward(dev["q"], dev["k"], dev["v"], dev["dy"], z, lse, scale, y=y, lse_dec=lse_dec,
+                         dq_lat=dq, dk=dk, dv=dv, workspace=ws)
 
     def timed(fn, steps):
         torch.cuda.synchronize()

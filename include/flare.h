@@ -26,7 +26,7 @@
  *   - Return value: FLARE_OK (0) or a negative flare_status.  Nothing is launched when an
  *     argument check fails.  A launch failure reported by the HIP runtime gives FLARE_ELAUNCH.
  *   - Supported shapes: B,H,N,M >= 1 with B*H <= 65535; d in {4, 8, 16, 32}; dtype f32 or bf16.
- *     Shapes with dtype bf16, d in {16,32} and M a multiple of 32 up to 256 run on the
+ *     Shapes with dtype bf16, d in {16,32} and M = 32 or a multiple of 64 up to 256 run on the
  *     matrix-core kernels; everything else runs on the fp32 vector kernels.
  *   - Results are bit-identical from run to run for the same inputs and shape (no float atomics;
  *     every cross-block reduction is done in a fixed order).
@@ -90,16 +90,18 @@ int flare_encode(const flare_shape *shape, const void *q_lat, const void *k, con
  * latents applied to Z.  Needs no workspace.
  *   q_lat [H][M][d] dtype, k [B][H][N][d] dtype, z [B][H][M][d] fp32        (in)
  *   y [B][H][N][d] dtype                                                    (out)
+ *   lse_dec [B][H][N] fp32: log sum_m exp(S[m][n]), natural log; may be NULL (out, optional)
  */
 int flare_decode(const flare_shape *shape, const void *q_lat, const void *k, const float *z,
-                 void *y, float scale, void *stream);
+                 void *y, float *lse_dec, float scale, void *stream);
 
 /*
  * Forward of the mixer = flare_encode then flare_decode on the same stream (listing in
- * Section 3.1).  z and lse_enc are outputs the caller keeps for flare_backward.
+ * Section 3.1).  z and lse_enc are outputs the caller keeps for flare_backward; lse_dec (may be
+ * NULL) is a third one that saves the backward one pass over the scores.
  */
 int flare_forward(const flare_shape *shape, const void *q_lat, const void *k, const void *v,
-                  void *y, float *z, float *lse_enc, float scale,
+                  void *y, float *z, float *lse_enc, float *lse_dec, float scale,
                   void *workspace, size_t workspace_bytes, void *stream);
 
 /*
@@ -112,12 +114,14 @@ int flare_forward(const flare_shape *shape, const void *q_lat, const void *k, co
  *     dK_n = scale * sum_m dS[m][n] q_m,   dQ_m = scale * sum_n dS[m][n] k_n  summed over B.
  *   q_lat, k, v as in the forward; dy [B][H][N][d] dtype                    (in)
  *   z, lse_enc: what flare_forward wrote for the same inputs                (in)
- *   y: unused, may be NULL (Y is recomputed from z)                         (in)
+ *   y, lse_dec: what flare_forward wrote, or NULL.  When both are given, delta_n is taken from
+ *     the stored y and the decode normaliser from lse_dec; when either is NULL both are
+ *     recomputed from z (one more pass over the scores, Y in fp32)          (in, optional)
  *   dq_lat [H][M][d] fp32 (summed over the batch), dk, dv [B][H][N][d] dtype (out)
  */
 int flare_backward(const flare_shape *shape, const void *q_lat, const void *k, const void *v,
-                   const void *y, const void *dy, const float *z, const float *lse_enc,
-                   float *dq_lat, void *dk, void *dv, float scale,
+                   const void *y, const float *lse_dec, const void *dy, const float *z,
+                   const float *lse_enc, float *dq_lat, void *dk, void *dv, float scale,
                    void *workspace, size_t workspace_bytes, void *stream);
 
 /*

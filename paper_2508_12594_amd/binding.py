@@ -46,9 +46,9 @@ def load():
     lib.flare_strerror.argtypes = [ctypes.c_int]
     lib.flare_workspace_bytes.argtypes = [sp, ctypes.POINTER(ctypes.c_size_t), ctypes.POINTER(ctypes.c_size_t)]
     lib.flare_encode.argtypes = [sp, vp, vp, vp, fp, fp, ctypes.c_float, vp, ctypes.c_size_t, vp]
-    lib.flare_decode.argtypes = [sp, vp, vp, fp, vp, ctypes.c_float, vp]
-    lib.flare_forward.argtypes = [sp, vp, vp, vp, vp, fp, fp, ctypes.c_float, vp, ctypes.c_size_t, vp]
-    lib.flare_backward.argtypes = [sp, vp, vp, vp, vp, vp, fp, fp, fp, vp, vp, ctypes.c_float, vp,
+    lib.flare_decode.argtypes = [sp, vp, vp, fp, vp, fp, ctypes.c_float, vp]
+    lib.flare_forward.argtypes = [sp, vp, vp, vp, vp, fp, fp, fp, ctypes.c_float, vp, ctypes.c_size_t, vp]
+    lib.flare_backward.argtypes = [sp, vp, vp, vp, vp, fp, vp, fp, fp, fp, vp, vp, ctypes.c_float, vp,
                                    ctypes.c_size_t, vp]
     lib.flare_profile_enable.argtypes = [ctypes.c_int]
     lib.flare_profile_name.restype = ctypes.c_char_p
@@ -151,21 +151,29 @@ def encode(q_lat, k, v, scale, z=None, lse_enc=None, workspace=None, stream=None
     return z, lse_enc
 
 
-def decode(q_lat, k, z, scale, y=None, stream=None):
-    """flare_decode: returns y[B,H,N,d] in k's dtype."""
+def _opt_lse_dec(lse_dec, shp):
+    torch = _torch()
+    if lse_dec is None:
+        return None
+    return _dev(lse_dec, "lse_dec", torch.float32, (shp.B, shp.H, shp.N))
+
+
+def decode(q_lat, k, z, scale, y=None, lse_dec=None, stream=None):
+    """flare_decode: returns y[B,H,N,d] in k's dtype; fills lse_dec[B,H,N] (fp32) when given."""
     torch = _torch()
     shp = _shape_of(q_lat, k)
     if y is None:
         y = torch.empty_like(k)
     _check(load().flare_decode(ctypes.byref(shp), _dev(q_lat, "q_lat"), _dev(k, "k"),
                                _dev(z, "z", torch.float32, (shp.B, shp.H, shp.M, shp.d)),
-                               _dev(y, "y", k.dtype, k.shape), ctypes.c_float(scale), _stream(stream)),
+                               _dev(y, "y", k.dtype, k.shape), _opt_lse_dec(lse_dec, shp),
+                               ctypes.c_float(scale), _stream(stream)),
            "flare_decode")
     return y
 
 
-def forward(q_lat, k, v, scale, y=None, z=None, lse_enc=None, workspace=None, stream=None):
-    """flare_forward: returns (y, z, lse_enc)."""
+def forward(q_lat, k, v, scale, y=None, z=None, lse_enc=None, lse_dec=None, workspace=None, stream=None):
+    """flare_forward: returns (y, z, lse_enc); fills lse_dec[B,H,N] (fp32) when given."""
     torch = _torch()
     shp = _shape_of(q_lat, k)
     if y is None:
@@ -179,12 +187,16 @@ def forward(q_lat, k, v, scale, y=None, z=None, lse_enc=None, workspace=None, st
                                 _dev(v, "v", k.dtype, k.shape), _dev(y, "y", k.dtype, k.shape),
                                 _dev(z, "z", torch.float32, (shp.B, shp.H, shp.M, shp.d)),
                                 _dev(lse_enc, "lse_enc", torch.float32, (shp.B, shp.H, shp.M)),
+                                _opt_lse_dec(lse_dec, shp),
                                 ctypes.c_float(scale), ws_p, ws_n, _stream(stream)), "flare_forward")
     return y, z, lse_enc
 
 
-def backward(q_lat, k, v, dy, z, lse_enc, scale, dq_lat=None, dk=None, dv=None, workspace=None, stream=None):
-    """flare_backward: returns (dq_lat[H,M,d] fp32, dk, dv in k's dtype)."""
+def backward(q_lat, k, v, dy, z, lse_enc, scale, y=None, lse_dec=None, dq_lat=None, dk=None, dv=None,
+             workspace=None, stream=None):
+    """flare_backward: returns (dq_lat[H,M,d] fp32, dk, dv in k's dtype).
+
+    Pass the forward's y and lse_dec to reuse them; without both, they are recomputed from z."""
     torch = _torch()
     shp = _shape_of(q_lat, k)
     if dq_lat is None:
@@ -195,7 +207,9 @@ def backward(q_lat, k, v, dy, z, lse_enc, scale, dq_lat=None, dk=None, dv=None, 
         dv = torch.empty_like(k)
     ws, ws_p, ws_n = _workspace(shp, "bwd", workspace, k.device)
     _check(load().flare_backward(ctypes.byref(shp), _dev(q_lat, "q_lat"), _dev(k, "k"),
-                                 _dev(v, "v", k.dtype, k.shape), None, _dev(dy, "dy", k.dtype, k.shape),
+                                 _dev(v, "v", k.dtype, k.shape),
+                                 None if y is None else _dev(y, "y", k.dtype, k.shape),
+                                 _opt_lse_dec(lse_dec, shp), _dev(dy, "dy", k.dtype, k.shape),
                                  _dev(z, "z", torch.float32, (shp.B, shp.H, shp.M, shp.d)),
                                  _dev(lse_enc, "lse_enc", torch.float32, (shp.B, shp.H, shp.M)),
                                  _dev(dq_lat, "dq_lat", torch.float32, (shp.H, shp.M, shp.d)),

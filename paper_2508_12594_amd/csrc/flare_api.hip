@@ -36,7 +36,7 @@ struct ProfileState {
 };
 ProfileState g_prof;
 const char *const kKernelNames[KID_COUNT] = {
-    "encode_partial", "encode_merge", "decode", "bwd_token_stats", "bwd_dz_partial",
+    "encode_partial", "encode_merge", "decode", "bwd_token_stats", "bwd_prep", "bwd_dz_partial",
     "bwd_dz_merge", "bwd_dq_partial", "bwd_dq_reduce", "bwd_dkdv"};
 }  // namespace
 
@@ -116,43 +116,45 @@ int flare_encode(const flare_shape *shape, const void *q_lat, const void *k, con
 }
 
 int flare_decode(const flare_shape *shape, const void *q_lat, const void *k, const float *z, void *y,
-                 float scale, void *stream)
+                 float *lse_dec, float scale, void *stream)
 {
     int rc = check_shape(shape);
     if (rc != FLARE_OK) return rc;
     if (!q_lat || !k || !z || !y) return FLARE_EINVAL;
-    if (!aligned16(q_lat) || !aligned16(k) || !aligned16(z) || !aligned16(y)) return FLARE_EALIGN;
+    if (!aligned16(q_lat) || !aligned16(k) || !aligned16(z) || !aligned16(y) || !aligned16(lse_dec))
+        return FLARE_EALIGN;
     if (mfma_supported(*shape))
-        return mfma_decode(*shape, q_lat, k, z, y, scale, static_cast<hipStream_t>(stream));
-    return valu_decode(*shape, q_lat, k, z, y, scale, static_cast<hipStream_t>(stream));
+        return mfma_decode(*shape, q_lat, k, z, y, lse_dec, scale, static_cast<hipStream_t>(stream));
+    return valu_decode(*shape, q_lat, k, z, y, lse_dec, scale, static_cast<hipStream_t>(stream));
 }
 
 int flare_forward(const flare_shape *shape, const void *q_lat, const void *k, const void *v, void *y,
-                  float *z, float *lse_enc, float scale, void *workspace, size_t workspace_bytes,
-                  void *stream)
+                  float *z, float *lse_enc, float *lse_dec, float scale, void *workspace,
+                  size_t workspace_bytes, void *stream)
 {
     if (!y) return FLARE_EINVAL;
-    if (!aligned16(y)) return FLARE_EALIGN;
+    if (!aligned16(y) || !aligned16(lse_dec)) return FLARE_EALIGN;
     int rc = flare_encode(shape, q_lat, k, v, z, lse_enc, scale, workspace, workspace_bytes, stream);
     if (rc != FLARE_OK) return rc;
-    return flare_decode(shape, q_lat, k, z, y, scale, stream);
+    return flare_decode(shape, q_lat, k, z, y, lse_dec, scale, stream);
 }
 
 int flare_backward(const flare_shape *shape, const void *q_lat, const void *k, const void *v,
-                   const void *y, const void *dy, const float *z, const float *lse_enc, float *dq_lat,
-                   void *dk, void *dv, float scale, void *workspace, size_t workspace_bytes, void *stream)
+                   const void *y, const float *lse_dec, const void *dy, const float *z,
+                   const float *lse_enc, float *dq_lat, void *dk, void *dv, float scale, void *workspace,
+                   size_t workspace_bytes, void *stream)
 {
-    (void)y;
     int rc = check_shape(shape);
     if (rc != FLARE_OK) return rc;
     if (!q_lat || !k || !v || !dy || !z || !lse_enc || !dq_lat || !dk || !dv) return FLARE_EINVAL;
     if (!aligned16(q_lat) || !aligned16(k) || !aligned16(v) || !aligned16(dy) || !aligned16(z) ||
-        !aligned16(lse_enc) || !aligned16(dq_lat) || !aligned16(dk) || !aligned16(dv) || !aligned16(workspace))
+        !aligned16(lse_enc) || !aligned16(dq_lat) || !aligned16(dk) || !aligned16(dv) || !aligned16(workspace) ||
+        !aligned16(y) || !aligned16(lse_dec))
         return FLARE_EALIGN;
     size_t need = 0;
     flare_workspace_bytes(shape, nullptr, &need);
     if (!workspace || workspace_bytes < need) return FLARE_EWORKSPACE;
-    return valu_backward(*shape, q_lat, k, v, dy, z, lse_enc, dq_lat, dk, dv, scale, workspace,
+    return valu_backward(*shape, q_lat, k, v, y, lse_dec, dy, z, lse_enc, dq_lat, dk, dv, scale, workspace,
                          static_cast<hipStream_t>(stream));
 }
 

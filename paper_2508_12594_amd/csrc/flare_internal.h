@@ -14,6 +14,7 @@ enum KernelId {
     KID_ENCODE_MERGE,
     KID_DECODE,
     KID_BWD_TOKEN_STATS,
+    KID_BWD_PREP,
     KID_BWD_DZ_PARTIAL,
     KID_BWD_DZ_MERGE,
     KID_BWD_DQ_PARTIAL,
@@ -60,10 +61,12 @@ int launch_encode_merge(const flare_shape &s, const float *m_part, const float *
 int valu_encode(const flare_shape &s, const void *q, const void *k, const void *v, float *z,
                 float *lse_enc, float scale, void *ws, hipStream_t stream);
 int valu_decode(const flare_shape &s, const void *q, const void *k, const float *z, void *y,
-                float scale, hipStream_t stream);
-int valu_backward(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy,
-                  const float *z, const float *lse_enc, float *dq, void *dk, void *dv, float scale,
-                  void *ws, hipStream_t stream);
+                float *lse_dec, float scale, hipStream_t stream);
+// The whole backward; uses the matrix-core kernels where the shape allows.  y and lse_dec may be
+// NULL (then the token statistics are recomputed).
+int valu_backward(const flare_shape &s, const void *q, const void *k, const void *v, const void *y,
+                  const float *lse_dec, const void *dy, const float *z, const float *lse_enc, float *dq,
+                  void *dk, void *dv, float scale, void *ws, hipStream_t stream);
 
 // ---- bf16 matrix-core path (d in {16,32}; M = 32 or a multiple of 64 up to 256) --------------
 struct MfmaPlan {
@@ -76,7 +79,7 @@ size_t mfma_fwd_bytes(const flare_shape &s);
 int mfma_encode(const flare_shape &s, const void *q, const void *k, const void *v, float *z,
                 float *lse_enc, float scale, void *ws, hipStream_t stream);
 int mfma_decode(const flare_shape &s, const void *q, const void *k, const float *z, void *y,
-                float scale, hipStream_t stream);
+                float *lse_dec, float scale, hipStream_t stream);
 int mfma_token_stats(const flare_shape &s, const void *q, const void *k, const float *z, const void *dy,
                      float *lse_dec2, float *delta, float scale, hipStream_t stream);
 bool mfma_dkdv_supported(const flare_shape &s);

@@ -157,7 +157,8 @@ __device__ __forceinline__ void compiler_fence() { asm volatile("" ::: "memory")
 // PRE = false (shapes whose operands would not fit otherwise): raw q, no lo term, and
 // 2^(|c2| s - b) formed with one v_fma_f32 per score.
 // ============================================================================================
-// MODE 0 writes y.  MODE 1 (first step of the backward) writes per token
+// MODE 0 writes y and, when lse_dec2 is not NULL, log sum_m exp(S[m][n]) (natural log) there.
+// MODE 1 (first step of the backward when nothing was saved) writes per token
 //   lse_dec2[n] = log2 sum_m 2^S2[m][n]   and   delta[n] = <dY_n, Y_n>   (Y_n kept in fp32).
 template <int D, int MT, bool PRE, int MINB, int MODE>
 __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
@@ -320,6 +321,10 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
                 delta[row] = part;
             }
         } else if (n < N) {
+            if (lse_dec2 && hh == 0) {   // optional saved statistic of the forward, natural log
+                const float used = PRE ? -__uint_as_float(bbits << 16) : b2;
+                lse_dec2[(size_t)bh * N + n] = (used + log2f(den)) * kLn2;
+            }
 #pragma unroll
             for (int hv = 0; hv < HV; ++hv) {
                 u32x2 w0, w1;
@@ -1325,10 +1330,10 @@ static int launch_decode_family(const flare_shape &s, const void *q, const void 
     return check_launch();
 }
 
-int mfma_decode(const flare_shape &s, const void *q, const void *k, const float *z, void *y, float scale,
-                hipStream_t stream)
+int mfma_decode(const flare_shape &s, const void *q, const void *k, const float *z, void *y, float *lse_dec,
+                float scale, hipStream_t stream)
 {
-    return launch_decode_family<0>(s, q, k, z, y, nullptr, nullptr, nullptr, scale, stream);
+    return launch_decode_family<0>(s, q, k, z, y, nullptr, lse_dec, nullptr, scale, stream);
 }
 
 int mfma_token_stats(const flare_shape &s, const void *q, const void *k, const float *z, const void *dy,

@@ -290,12 +290,29 @@ __global__ __launch_bounds__(kTokenBlock) void token_pass_kernel(
     if (!valid) return;
     if constexpr (MODE == 0) {
         store_row<D>(y + row * D, acc);
+        if (lse_dec2) lse_dec2[row] = (mr + log2f(l)) * kLn2;   // optional saved statistic, natural log
     } else {
         float g[D];
         load_row<D>(dy + row * D, g);
         lse_dec2[row] = mr + log2f(l);
         delta[row] = dot<D>(g, acc);
     }
+}
+
+// Token statistics of the backward from what the forward saved: delta[n] = <dY_n, Y_n> with the
+// stored Y, lse_dec2[n] = lse_dec[n] * log2(e).  thread = token; purely HBM-bound.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void bwd_prep_kernel(
+    const T *__restrict__ y, const T *__restrict__ dy, const float *__restrict__ lse_dec,
+    float *__restrict__ lse_dec2, float *__restrict__ delta, size_t rows)
+{
+    const size_t row = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (row >= rows) return;
+    float a[D], g[D];
+    load_row<D>(y + row * D, a);
+    load_row<D>(dy + row * D, g);
+    delta[row] = dot<D>(a, g);
+    lse_dec2[row] = lse_dec[row] * kLog2e;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -549,18 +566,19 @@ int encode_impl(const flare_shape &s, const T *q, const T *k, const T *v, float 
 }
 
 template <typename T, int D>
-int decode_impl(const flare_shape &s, const T *q, const T *k, const float *z, T *y, float scale,
+int decode_impl(const flare_shape &s, const T *q, const T *k, const float *z, T *y, float *lse_dec, float scale,
                 hipStream_t stream)
 {
     LaunchTimer t(KID_DECODE, stream);
     token_pass_kernel<T, D, 0><<<dim3((s.N + kTokenBlock - 1) / kTokenBlock, s.B * s.H), kTokenBlock, 0, stream>>>(
-        q, k, z, y, nullptr, nullptr, nullptr, s.H, s.N, s.M, scale * kLog2e);
+        q, k, z, y, nullptr, lse_dec, nullptr, s.H, s.N, s.M, scale * kLog2e);
     return check_launch();
 }
 
 template <typename T, int D>
-int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, const T *dy, const float *z,
-                  const float *lse_enc, float *dq, T *dk, T *dv, float scale, void *ws, hipStream_t stream)
+int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, const T *y, const float *lse_dec,
+                  const T *dy, const float *z, const float *lse_enc, float *dq, T *dk, T *dv, float scale, void *ws,
+                  hipStream_t stream)
 {
     const ValuPlan plan = valu_plan(s);
     const bool mf = mfma_supported(s);          // matrix-core kernels where they exist
@@ -572,18 +590,25 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     const int lat_blocks = (s.M + kLatentBlock - 1) / kLatentBlock;
     const dim3 tok_grid((s.N + kTokenBlock - 1) / kTokenBlock, BH);
     const dim3 lat_grid(plan.bwd.chunks, BH, lat_blocks);
-    if (mf) {
-        int rc = mfma_token_stats(s, q, k, z, dy, w.lse_dec2, w.delta, scale, stream);
-        if (rc != FLARE_OK) return rc;
-        rc = mfma_dz_partial(s, q, k, dy, w.lse_dec2, w.part, scale, stream);
+    // token statistics: from what the forward saved, or recomputed
+    if (y && lse_dec) {
+        const size_t rows = (size_t)BH * s.N;
+        LaunchTimer t(KID_BWD_PREP, stream);
+        bwd_prep_kernel<T, D><<<(unsigned)((rows + 255) / 256), 256, 0, stream>>>(y, dy, lse_dec, w.lse_dec2, w.delta,
+                                                                                  rows);
+    } else if (mf) {
+        const int rc = mfma_token_stats(s, q, k, z, dy, w.lse_dec2, w.delta, scale, stream);
         if (rc != FLARE_OK) return rc;
     } else {
-        {
-            LaunchTimer t(KID_BWD_TOKEN_STATS, stream);
-            token_pass_kernel<T, D, 1><<<tok_grid, kTokenBlock, 0, stream>>>(q, k, z, nullptr, dy, w.lse_dec2,
-                                                                             w.delta, s.H, s.N, s.M, c2);
-        }
-        if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
+        LaunchTimer t(KID_BWD_TOKEN_STATS, stream);
+        token_pass_kernel<T, D, 1><<<tok_grid, kTokenBlock, 0, stream>>>(q, k, z, nullptr, dy, w.lse_dec2, w.delta,
+                                                                         s.H, s.N, s.M, c2);
+    }
+    if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
+    if (mf) {
+        const int rc = mfma_dz_partial(s, q, k, dy, w.lse_dec2, w.part, scale, stream);
+        if (rc != FLARE_OK) return rc;
+    } else {
         {
             LaunchTimer t(KID_BWD_DZ_PARTIAL, stream);
             dz_partial_kernel<T, D><<<lat_grid, kLatentBlock, 0, stream>>>(q, k, dy, w.lse_dec2, w.part, s.H, s.N,
@@ -697,17 +722,17 @@ int valu_encode(const flare_shape &s, const void *q, const void *k, const void *
 {
     FLARE_DISPATCH(s, (encode_impl<T, D>(s, (const T *)q, (const T *)k, (const T *)v, z, lse_enc, scale, ws, stream)));
 }
-int valu_decode(const flare_shape &s, const void *q, const void *k, const float *z, void *y, float scale,
-                hipStream_t stream)
+int valu_decode(const flare_shape &s, const void *q, const void *k, const float *z, void *y, float *lse_dec,
+                float scale, hipStream_t stream)
 {
-    FLARE_DISPATCH(s, (decode_impl<T, D>(s, (const T *)q, (const T *)k, z, (T *)y, scale, stream)));
+    FLARE_DISPATCH(s, (decode_impl<T, D>(s, (const T *)q, (const T *)k, z, (T *)y, lse_dec, scale, stream)));
 }
-int valu_backward(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy,
-                  const float *z, const float *lse_enc, float *dq, void *dk, void *dv, float scale, void *ws,
-                  hipStream_t stream)
+int valu_backward(const flare_shape &s, const void *q, const void *k, const void *v, const void *y,
+                  const float *lse_dec, const void *dy, const float *z, const float *lse_enc, float *dq, void *dk,
+                  void *dv, float scale, void *ws, hipStream_t stream)
 {
-    FLARE_DISPATCH(s, (backward_impl<T, D>(s, (const T *)q, (const T *)k, (const T *)v, (const T *)dy, z, lse_enc, dq,
-                                           (T *)dk, (T *)dv, scale, ws, stream)));
+    FLARE_DISPATCH(s, (backward_impl<T, D>(s, (const T *)q, (const T *)k, (const T *)v, (const T *)y, lse_dec,
+                                           (const T *)dy, z, lse_enc, dq, (T *)dk, (T *)dv, scale, ws, stream)));
 }
 
 }  // namespace flare

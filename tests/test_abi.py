@@ -51,13 +51,15 @@ def test_null_and_misaligned_pointers_are_rejected(lib):
     shp = binding.FlareShape(1, 1, 8, 32, 16, binding.FLARE_F32)
     p = ctypes.c_void_p(4096)        # never dereferenced: the checks fail first
     odd = ctypes.c_void_p(4100)
-    assert lib.flare_forward(ctypes.byref(shp), None, p, p, p, p, p, ctypes.c_float(1), p, 1 << 20, None) == -1
-    assert lib.flare_forward(ctypes.byref(shp), p, p, p, None, p, p, ctypes.c_float(1), p, 1 << 20, None) == -1
-    assert lib.flare_forward(ctypes.byref(shp), p, odd, p, p, p, p, ctypes.c_float(1), p, 1 << 20, None) == -3
-    assert lib.flare_forward(ctypes.byref(shp), p, p, p, p, p, p, ctypes.c_float(1), p, 16, None) == -4
-    assert lib.flare_forward(ctypes.byref(shp), p, p, p, p, p, p, ctypes.c_float(1), None, 0, None) == -4
-    assert lib.flare_decode(ctypes.byref(shp), p, p, None, p, ctypes.c_float(1), None) == -1
-    assert lib.flare_backward(ctypes.byref(shp), p, p, p, None, None, p, p, p, p, p, ctypes.c_float(1), p,
+    one = ctypes.c_float(1)
+    assert lib.flare_forward(ctypes.byref(shp), None, p, p, p, p, p, None, one, p, 1 << 20, None) == -1
+    assert lib.flare_forward(ctypes.byref(shp), p, p, p, None, p, p, None, one, p, 1 << 20, None) == -1
+    assert lib.flare_forward(ctypes.byref(shp), p, odd, p, p, p, p, None, one, p, 1 << 20, None) == -3
+    assert lib.flare_forward(ctypes.byref(shp), p, p, p, p, p, p, odd, one, p, 1 << 20, None) == -3
+    assert lib.flare_forward(ctypes.byref(shp), p, p, p, p, p, p, None, one, p, 16, None) == -4
+    assert lib.flare_forward(ctypes.byref(shp), p, p, p, p, p, p, None, one, None, 0, None) == -4
+    assert lib.flare_decode(ctypes.byref(shp), p, p, None, p, None, one, None) == -1
+    assert lib.flare_backward(ctypes.byref(shp), p, p, p, None, None, None, p, p, p, p, p, one, p,
                               1 << 20, None) == -1
-    assert lib.flare_backward(ctypes.byref(shp), p, p, p, None, p, p, p, p, p, p, ctypes.c_float(1), p,
+    assert lib.flare_backward(ctypes.byref(shp), p, p, p, None, None, p, p, p, p, p, p, one, p,
                               16, None) == -4

@@ -81,8 +81,9 @@ def test_forward_backward_262k(oracle):
     inp = synth.make_inputs(5, with_dy=True)
     N, scale, tol = inp["N"], inp["scale"], TOL["bf16"]
     dev = to_device(inp)
-    y, z, lse = binding.forward(dev["q"], dev["k"], dev["v"], scale)
-    dq, dk, dv = binding.backward(dev["q"], dev["k"], dev["v"], dev["dy"], z, lse, scale)
+    lse_dec = torch.empty(dev["k"].shape[:3], dtype=torch.float32, device="cuda")
+    y, z, lse = binding.forward(dev["q"], dev["k"], dev["v"], scale, lse_dec=lse_dec)
+    dq, dk, dv = binding.backward(dev["q"], dev["k"], dev["v"], dev["dy"], z, lse, scale, y=y, lse_dec=lse_dec)
     torch.cuda.synchronize()
     y_h, z_h, dq_h, dk_h, dv_h = (to_host(t) for t in (y, z, dq, dk, dv))
     for t in (y_h, z_h, dq_h, dk_h, dv_h):
@@ -103,6 +104,34 @@ def test_forward_backward_262k(oracle):
                     dv=slice_relerr(dv_h[:, h:h + 1, tok], dv_ref))
         _say("   head %d: " % h + "  ".join("%s %.3e" % kv for kv in errs.items()) + "  (tol %.0e)" % tol)
         assert max(errs.values()) <= tol
+
+
+@pytest.mark.parametrize("saved", [True, False])
+def test_forward_backward_million_tokens(oracle, saved):
+    """The step bench.py times: config 4 (N = 1,000,000, M = 256, d = 16) forward + backward, with the
+    forward's y and lse_dec handed to the backward (saved) or recomputed."""
+    import torch
+    _say("full forward+backward cfg4 saved=%s" % saved)
+    inp = synth.make_inputs(4, with_dy=True)
+    N, scale, tol = inp["N"], inp["scale"], TOL["bf16"]
+    dev = to_device(inp)
+    lse_dec = torch.empty(dev["k"].shape[:3], dtype=torch.float32, device="cuda") if saved else None
+    y, z, lse = binding.forward(dev["q"], dev["k"], dev["v"], scale, lse_dec=lse_dec)
+    dq, dk, dv = binding.backward(dev["q"], dev["k"], dev["v"], dev["dy"], z, lse, scale,
+                                  y=y if saved else None, lse_dec=lse_dec)
+    torch.cuda.synchronize()
+    dq_h, dk_h, dv_h = (to_host(t) for t in (dq, dk, dv))
+    for t in (dq_h, dk_h, dv_h):
+        assert np.isfinite(t).all()
+    tok = _sample_tokens(N, 2048, 6)
+    h = 3
+    sl = (slice(None), slice(h, h + 1))
+    dq_ref, dk_ref, dv_ref = oracle.backward(inp["q"][h:h + 1], inp["k"][sl], inp["v"][sl], inp["dy"][sl], scale,
+                                             tok=tok)
+    errs = dict(dq=slice_relerr(dq_h[h:h + 1], dq_ref), dk=slice_relerr(dk_h[:, h:h + 1, tok], dk_ref),
+                dv=slice_relerr(dv_h[:, h:h + 1, tok], dv_ref))
+    _say("   head %d: " % h + "  ".join("%s %.3e" % kv for kv in errs.items()) + "  (tol %.0e)" % tol)
+    assert max(errs.values()) <= tol
 
 
 def test_backward_full_small_workloads(oracle):

@@ -39,13 +39,16 @@ def _forward_case(oracle, inp, scale=None, tol=None):
     return y, z, lse
 
 
-def _backward_case(oracle, inp, scale=None, tol=None, zero_dq_dk=False):
+def _backward_case(oracle, inp, scale=None, tol=None, zero_dq_dk=False, saved=False):
+    """saved=True hands the forward's y and lse_dec to the backward (no recomputation)."""
     import torch
     scale = inp["scale"] if scale is None else scale
     tol = TOL[inp["dtype"]] if tol is None else tol
     dev = to_device(inp)
-    y, z, lse = binding.forward(dev["q"], dev["k"], dev["v"], scale)
-    dq, dk, dv = binding.backward(dev["q"], dev["k"], dev["v"], dev["dy"], z, lse, scale)
+    lse_dec = torch.empty(dev["k"].shape[:3], dtype=torch.float32, device="cuda") if saved else None
+    y, z, lse = binding.forward(dev["q"], dev["k"], dev["v"], scale, lse_dec=lse_dec)
+    dq, dk, dv = binding.backward(dev["q"], dev["k"], dev["v"], dev["dy"], z, lse, scale,
+                                  y=y if saved else None, lse_dec=lse_dec)
     torch.cuda.synchronize()
     dq_ref, dk_ref, dv_ref = oracle.backward(inp["q"], inp["k"], inp["v"], inp["dy"], scale)
     e_v = slice_relerr(to_host(dv), dv_ref)
@@ -102,11 +105,29 @@ BWD_CASES = [
 ]
 
 
+@pytest.mark.parametrize("saved", [False, True])
 @pytest.mark.parametrize("cfg,over", BWD_CASES)
-def test_backward_workloads(oracle, cfg, over):
-    _say("backward cfg%d %s" % (cfg, over))
+def test_backward_workloads(oracle, cfg, over, saved):
+    _say("backward cfg%d %s saved=%s" % (cfg, over, saved))
     inp = synth.make_inputs(cfg, with_dy=True, **over)
-    _backward_case(oracle, inp)
+    _backward_case(oracle, inp, saved=saved)
+
+
+@pytest.mark.parametrize("cfg,over", [(1, dict(N=700)), (4, dict(N=3000)), (3, dict(B=2, N=900))])
+def test_saved_lse_dec_matches_oracle(oracle, cfg, over):
+    """lse_dec[n] = log sum_m exp(S[m][n]) as written by the forward."""
+    import torch
+    inp = synth.make_inputs(cfg, with_dy=False, **over)
+    dev = to_device(inp)
+    lse_dec = torch.empty(dev["k"].shape[:3], dtype=torch.float32, device="cuda")
+    binding.forward(dev["q"], dev["k"], dev["v"], inp["scale"], lse_dec=lse_dec)
+    torch.cuda.synchronize()
+    s = inp["scale"] * np.einsum("hmd,bhnd->bhmn", inp["q"].astype(np.float64), inp["k"].astype(np.float64))
+    mx = s.max(axis=2, keepdims=True)
+    ref = (mx + np.log(np.exp(s - mx).sum(axis=2, keepdims=True)))[:, :, 0]
+    err = float(np.max(np.abs(to_host(lse_dec) - ref)))
+    _say("   lse_dec abs err %.3e" % err)
+    assert err <= (1e-5 if inp["dtype"] == "f32" else 1e-2)
 
 
 # ---- edge cases ---------------------------------------------------------------------------------
@@ -135,6 +156,7 @@ def test_edge_shapes_forward_backward(oracle, shape, dtype):
     inp = synth.make_inputs(1, B=B, H=H, N=N, M=M, d=d, dtype=dtype, with_dy=True, seed=1234 + N + M)
     y, _, _ = _forward_case(oracle, inp)
     _backward_case(oracle, inp, zero_dq_dk=(N == 1))
+    _backward_case(oracle, inp, zero_dq_dk=(N == 1), saved=True)
     if N == 1:
         assert slice_relerr(to_host(y), inp["v"]) <= (1e-6 if dtype == "f32" else 4e-3)
 
