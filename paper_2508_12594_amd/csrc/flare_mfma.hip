@@ -870,7 +870,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     constexpr int NA = (LO2 ? 6 : 4) * KS + 1;  // A-type images per latent tile (the last one: corrections)
     constexpr int NR = 4 * HV;                  // row images per latent tile (RW1, RW2) x 2 k-steps
     constexpr int PER_TILE = NA + NR;
-    constexpr bool PREFETCH = (D == 16);        // registers allow a second image set at d = 16 only
+    constexpr bool PIPE = (D == 16);            // look one latent tile ahead where registers allow
     extern __shared__ __attribute__((aligned(16))) u32x4 img[];   // [MT][PER_TILE][64 lanes]
 
     const int tid = threadIdx.x;
@@ -993,41 +993,52 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
 #pragma unroll
         for (int hv = 0; hv < HV; ++hv) { acc1[hv] = splat16(0.f); acc2[hv] = splat16(0.f); }
 
-        // one latent tile t: `im` holds its NA A-type images; the row images are read here, early
-        // enough to arrive while the scores are exponentiated
-        auto tile_step = [&](int t, const bf16x8 (&im)[NA]) {
-            bf16x8 rw[NR];
-#pragma unroll
-            for (int r = 0; r < NR; ++r) rw[r] = image(t, NA + r);
+        // Score products of latent tile t (minus lse_enc2 / minus lse_dec2): 2*KS + 2 MFMAs.
+        auto scores = [&](int t, f32x16 &s1, f32x16 &s2) {
             f32x16 x = splat16(0.f);
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) x = mfma(im[0 * KS + ks], kt[ks], x);
+            for (int ks = 0; ks < KS; ++ks) x = mfma(image(t, 0 * KS + ks), kt[ks], x);
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) x = mfma(im[1 * KS + ks], kt[ks], x);
-            f32x16 s1 = mfma(im[NA - 1], kt_a, x);
-            f32x16 s2 = mfma(im[NA - 1], kt_b, x);
+            for (int ks = 0; ks < KS; ++ks) x = mfma(image(t, 1 * KS + ks), kt[ks], x);
+            const bf16x8 qa = image(t, NA - 1);
+            s1 = mfma(qa, kt_a, x);
+            s2 = mfma(qa, kt_b, x);
+        };
+        // One latent tile, software-pipelined: the a and c products of tile t and the score products
+        // of tile t+1 are issued first and run on the matrix cores while the vector ALUs
+        // exponentiate the scores of tile t (s1, s2, computed one step earlier).
+        auto tile_step = [&](int t, f32x16 &s1, f32x16 &s2, f32x16 &s1n, f32x16 &s2n) {
+            if constexpr (!PIPE) scores(t, s1, s2);   // not enough registers at d = 32: no look-ahead
             f32x16 av = splat16(0.f);
             f32x16 cv = mfma(ones_aug, g_aug, splat16(0.f));
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                av = mfma(im[2 * KS + ks], vt[ks], av);
-                cv = mfma(im[3 * KS + ks], gt[ks], cv);
+                av = mfma(image(t, 2 * KS + ks), vt[ks], av);
+                cv = mfma(image(t, 3 * KS + ks), gt[ks], cv);
                 if constexpr (LO2) {
-                    av = mfma(im[4 * KS + ks], vt[ks], av);
-                    cv = mfma(im[5 * KS + ks], gt[ks], cv);
+                    av = mfma(image(t, 4 * KS + ks), vt[ks], av);
+                    cv = mfma(image(t, 5 * KS + ks), gt[ks], cv);
                 }
             }
+            if constexpr (PIPE) {
+                if (t + 1 < MT) scores(t + 1, s1n, s2n);
+            }
+            bf16x8 rw[NR];
+#pragma unroll
+            for (int r = 0; r < NR; ++r) rw[r] = image(t, NA + r);
+            sched_fence();
+            f32x16 pv, rv;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) { pv[i] = fast_exp2(s1[i]); rv[i] = fast_exp2(s2[i]); }
             u32x4 p0, p1, d0, d1;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const float pa = fast_exp2(s1[2 * i]), pb = fast_exp2(s1[2 * i + 1]);
-                const float pc = fast_exp2(s1[8 + 2 * i]), pd = fast_exp2(s1[8 + 2 * i + 1]);
-                p0[i] = cvt_pk_bf16(pa, pb);
-                p1[i] = cvt_pk_bf16(pc, pd);
-                d0[i] = cvt_pk_bf16(fmaf(fast_exp2(s2[2 * i]), cv[2 * i], pa * av[2 * i]),
-                                    fmaf(fast_exp2(s2[2 * i + 1]), cv[2 * i + 1], pb * av[2 * i + 1]));
-                d1[i] = cvt_pk_bf16(fmaf(fast_exp2(s2[8 + 2 * i]), cv[8 + 2 * i], pc * av[8 + 2 * i]),
-                                    fmaf(fast_exp2(s2[8 + 2 * i + 1]), cv[8 + 2 * i + 1], pd * av[8 + 2 * i + 1]));
+                p0[i] = cvt_pk_bf16(pv[2 * i], pv[2 * i + 1]);
+                p1[i] = cvt_pk_bf16(pv[8 + 2 * i], pv[8 + 2 * i + 1]);
+                d0[i] = cvt_pk_bf16(fmaf(rv[2 * i], cv[2 * i], pv[2 * i] * av[2 * i]),
+                                    fmaf(rv[2 * i + 1], cv[2 * i + 1], pv[2 * i + 1] * av[2 * i + 1]));
+                d1[i] = cvt_pk_bf16(fmaf(rv[8 + 2 * i], cv[8 + 2 * i], pv[8 + 2 * i] * av[8 + 2 * i]),
+                                    fmaf(rv[8 + 2 * i + 1], cv[8 + 2 * i + 1], pv[8 + 2 * i + 1] * av[8 + 2 * i + 1]));
             }
 #pragma unroll
             for (int hv = 0; hv < HV; ++hv) {
@@ -1036,29 +1047,19 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                 acc2[hv] = mfma(rw[(1 * HV + hv) * 2 + 0], as_bf16x8(d0), acc2[hv]);
                 acc2[hv] = mfma(rw[(1 * HV + hv) * 2 + 1], as_bf16x8(d1), acc2[hv]);
             }
+            sched_fence();
         };
-        auto load_images = [&](int t, bf16x8 (&im)[NA]) {
-#pragma unroll
-            for (int sid = 0; sid < NA; ++sid) im[sid] = image(t, sid);
-        };
-        if constexpr (PREFETCH && MT > 1) {
-            // two sets of A-type images in registers: the next latent tile's are read from LDS
-            // while the current tile is computed
-            bf16x8 imA[NA], imB[NA];
-            load_images(0, imA);
+        {
+            f32x16 sa1 = splat16(0.f), sa2 = splat16(0.f), sb1 = splat16(0.f), sb2 = splat16(0.f);
+            if constexpr (PIPE) scores(0, sa1, sa2);
+            if constexpr (MT == 1) {
+                tile_step(0, sa1, sa2, sb1, sb2);
+            } else {
 #pragma unroll 1
-            for (int t = 0; t < MT; t += 2) {
-                load_images(t + 1, imB);
-                tile_step(t, imA);
-                if (t + 2 < MT) load_images(t + 2, imA);
-                tile_step(t + 1, imB);
-            }
-        } else {
-#pragma unroll 1
-            for (int t = 0; t < MT; ++t) {
-                bf16x8 im[NA];
-                load_images(t, im);
-                tile_step(t, im);
+                for (int t = 0; t < MT; t += 2) {
+                    tile_step(t, sa1, sa2, sb1, sb2);
+                    tile_step(t + 1, sb1, sb2, sa1, sa2);
+                }
             }
         }
         if (n < N) {
