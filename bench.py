@@ -82,6 +82,8 @@ def main():
     ap.add_argument("--cfg", type=int, default=4, help="synthetic workload id (4 = the headline)")
     ap.add_argument("--tokens", type=int, default=None, help="override N (for quick checks only)")
     ap.add_argument("--latents", type=int, default=None, help="override M (for quick checks only)")
+    ap.add_argument("--layout", choices=["bhnd", "bnhd"], default="bhnd",
+                    help="memory order of k, v, y, dy, dk, dv: [B,H,N,d] (default) or [B,N,H,d]")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run three plain device copies of k (known size) first, for scaling profiler counters")
@@ -108,6 +110,10 @@ def main():
     dt = torch.float32 if inp["dtype"] == "f32" else torch.bfloat16
     elem = 4 if inp["dtype"] == "f32" else 2
     dev = {n: torch.from_numpy(inp[n]).to("cuda", dt).contiguous() for n in ("q", "k", "v", "dy")}
+    if args.layout == "bnhd":
+        for n in ("k", "v", "dy"):
+            dev[n] = dev[n].permute(0, 2, 1, 3).contiguous()
+    lay = args.layout
     scale = inp["scale"]
     code = binding.FLARE_F32 if inp["dtype"] == "f32" else binding.FLARE_BF16
     fwd_b, bwd_b = binding.workspace_bytes(B, H, N, M, d, code)
@@ -121,12 +127,13 @@ def main():
     dv = torch.empty_like(dev["k"])
 
     def fwd():
-        binding.forward(dev["q"], dev["k"], dev["v"], scale, y=y, z=z, lse_enc=lse, lse_dec=lse_dec, workspace=ws)
+        binding.forward(dev["q"], dev["k"], dev["v"], scale, y=y, z=z, lse_enc=lse, lse_dec=lse_dec, workspace=ws,
+                        layout=lay)
 
     def step():   # a training step: the forward saves z, lse_enc, lse_dec and y for the backward
         fwd()
         binding.backward(dev["q"], dev["k"], dev["v"], dev["dy"], z, lse, scale, y=y, lse_dec=lse_dec,
-                         dq_lat=dq, dk=dk, dv=dv, workspace=ws)
+                         dq_lat=dq, dk=dk, dv=dv, workspace=ws, layout=lay)
 
     def timed(fn, steps):
         torch.cuda.synchronize()
@@ -193,7 +200,8 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": inp["dtype"], "data": "synthetic",
         "config": {"workload": synth.describe(args.cfg) + ("" if args.tokens is None else " [N overridden to %d]" % N)
                    + ("" if args.latents is None else " [M overridden to %d]" % M),
-                   "step": "flare_forward + flare_backward", "B": B, "H": H, "N": N, "M": M, "d": d},
+                   "step": "flare_forward + flare_backward", "B": B, "H": H, "N": N, "M": M, "d": d,
+                   "layout": "[B,H,N,d]" if lay == "bhnd" else "[B,N,H,d]"},
         "fwd": {"tokens_per_s": round(tokens / t_fwd, 1), "ms": round(t_fwd * 1e3, 4),
                 "hbm_frac": round(fwd_bytes / t_fwd / 1e9 / HBM_PEAK_GBS, 4),
                 "mfma_frac": round(fwd_flops / t_fwd / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),

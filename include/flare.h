@@ -25,7 +25,9 @@
  *     Two calls that share a workspace must be ordered on the same stream.
  *   - Return value: FLARE_OK (0) or a negative flare_status.  Nothing is launched when an
  *     argument check fails.  A launch failure reported by the HIP runtime gives FLARE_ELAUNCH.
- *   - Supported shapes: B,H,N,M >= 1 with B*H <= 65535; d in {4, 8, 16, 32}; dtype f32 or bf16.
+ *   - Supported shapes: B,H,N,M >= 1 with B*H <= 65535; d in {4, 8, 16, 32}; dtype f32 or bf16;
+ *     either flare_layout for the token tensors (every "[B][H][N][d]" below reads [B][N][H][d]
+ *     when shape->layout is FLARE_BNHD; the per-token statistic lse_dec is [B][H][N] always).
  *     Shapes with dtype bf16, d in {16,32} and M = 32 or a multiple of 64 up to 256 run on the
  *     matrix-core kernels; everything else runs on the fp32 vector kernels.
  *   - Results are bit-identical from run to run for the same inputs and shape (no float atomics;
@@ -49,11 +51,17 @@ typedef enum {
 typedef enum {
     FLARE_OK = 0,
     FLARE_EINVAL = -1,        /* null pointer, non-positive dimension, null shape */
-    FLARE_EUNSUPPORTED = -2,  /* d, dtype or B*H outside the supported set */
+    FLARE_EUNSUPPORTED = -2,  /* d, dtype, layout or B*H outside the supported set */
     FLARE_EALIGN = -3,        /* a data pointer is not 16-byte aligned */
     FLARE_EWORKSPACE = -4,    /* workspace is NULL or smaller than flare_workspace_bytes reports */
     FLARE_ELAUNCH = -5        /* the HIP runtime rejected a launch or an event call */
 } flare_status;
+
+typedef enum {
+    FLARE_BHND = 0,  /* token tensors are [B][H][N][d]: one contiguous [N][d] slab per head */
+    FLARE_BNHD = 1   /* token tensors are [B][N][H][d] = [B][N][C] with C = H*d, the layout the block's
+                        linear projections produce (listing in Section 3.1 before its head split) */
+} flare_layout;
 
 typedef struct {
     int B;              /* batch items */
@@ -62,6 +70,8 @@ typedef struct {
     int M;              /* latent queries per head */
     int d;              /* head dimension D = C / H */
     flare_dtype dtype;  /* element type of q_lat, k, v, y, dy, dk, dv */
+    flare_layout layout; /* memory order of the token tensors k, v, y, dy, dk, dv (0 = [B][H][N][d]);
+                            q_lat, z, lse_enc, lse_dec and dq_lat do not depend on it */
 } flare_shape;
 
 /* Library version: major*10000 + minor*100 + patch. */

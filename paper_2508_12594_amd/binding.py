@@ -12,6 +12,9 @@ LIB_PATH = os.path.join(_HERE, "libflare.so")
 
 FLARE_F32 = 0
 FLARE_BF16 = 1
+FLARE_BHND = 0   # token tensors [B,H,N,d]
+FLARE_BNHD = 1   # token tensors [B,N,H,d] (= [B,N,C], C = H*d)
+LAYOUTS = {"bhnd": FLARE_BHND, "bnhd": FLARE_BNHD}
 
 EXPORTS = [
     "flare_version", "flare_strerror", "flare_workspace_bytes", "flare_encode", "flare_decode",
@@ -22,7 +25,7 @@ EXPORTS = [
 
 class FlareShape(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int), ("H", ctypes.c_int), ("N", ctypes.c_int), ("M", ctypes.c_int),
-                ("d", ctypes.c_int), ("dtype", ctypes.c_int)]
+                ("d", ctypes.c_int), ("dtype", ctypes.c_int), ("layout", ctypes.c_int)]
 
 
 class FlareError(RuntimeError):
@@ -88,14 +91,19 @@ def _dtype_code(t):
     raise FlareError("dtype must be float32 or bfloat16, got %s" % t.dtype)
 
 
-def _shape_of(q, k):
+def _shape_of(q, k, layout="bhnd"):
+    if layout not in LAYOUTS:
+        raise FlareError("layout must be 'bhnd' or 'bnhd'")
     if q.dim() != 3 or k.dim() != 4:
-        raise FlareError("expected q_lat[H,M,d] and k[B,H,N,d]")
+        raise FlareError("expected q_lat[H,M,d] and k[B,H,N,d] (layout 'bhnd') or k[B,N,H,d] (layout 'bnhd')")
     H, M, d = q.shape
-    B, Hk, N, dk = k.shape
+    if layout == "bhnd":
+        B, Hk, N, dk = k.shape
+    else:
+        B, N, Hk, dk = k.shape
     if Hk != H or dk != d or q.dtype != k.dtype:
         raise FlareError("q_lat and k disagree on H, d or dtype")
-    return FlareShape(B, H, N, M, d, _dtype_code(k))
+    return FlareShape(B, H, N, M, d, _dtype_code(k), LAYOUTS[layout])
 
 
 def _dev(t, name, dtype=None, shape=None):
@@ -115,8 +123,8 @@ def _stream(stream):
 
 
 def workspace_bytes(B, H, N, M, d, dtype_code):
-    """(forward bytes, backward bytes) of scratch for this shape."""
-    shp = FlareShape(B, H, N, M, d, dtype_code)
+    """(forward bytes, backward bytes) of scratch for this shape (the same for both layouts)."""
+    shp = FlareShape(B, H, N, M, d, dtype_code, FLARE_BHND)
     f, b = ctypes.c_size_t(0), ctypes.c_size_t(0)
     _check(load().flare_workspace_bytes(ctypes.byref(shp), ctypes.byref(f), ctypes.byref(b)),
            "flare_workspace_bytes")
@@ -134,10 +142,10 @@ def _workspace(shp, which, workspace, device):
     return workspace, ctypes.c_void_p(workspace.data_ptr()), ctypes.c_size_t(workspace.numel())
 
 
-def encode(q_lat, k, v, scale, z=None, lse_enc=None, workspace=None, stream=None):
+def encode(q_lat, k, v, scale, z=None, lse_enc=None, workspace=None, stream=None, layout="bhnd"):
     """flare_encode: returns (z[B,H,M,d] fp32, lse_enc[B,H,M] fp32)."""
     torch = _torch()
-    shp = _shape_of(q_lat, k)
+    shp = _shape_of(q_lat, k, layout)
     if z is None:
         z = torch.empty((shp.B, shp.H, shp.M, shp.d), dtype=torch.float32, device=k.device)
     if lse_enc is None:
@@ -158,10 +166,10 @@ def _opt_lse_dec(lse_dec, shp):
     return _dev(lse_dec, "lse_dec", torch.float32, (shp.B, shp.H, shp.N))
 
 
-def decode(q_lat, k, z, scale, y=None, lse_dec=None, stream=None):
-    """flare_decode: returns y[B,H,N,d] in k's dtype; fills lse_dec[B,H,N] (fp32) when given."""
+def decode(q_lat, k, z, scale, y=None, lse_dec=None, stream=None, layout="bhnd"):
+    """flare_decode: returns y (k's shape and dtype); fills lse_dec[B,H,N] (fp32) when given."""
     torch = _torch()
-    shp = _shape_of(q_lat, k)
+    shp = _shape_of(q_lat, k, layout)
     if y is None:
         y = torch.empty_like(k)
     _check(load().flare_decode(ctypes.byref(shp), _dev(q_lat, "q_lat"), _dev(k, "k"),
@@ -172,10 +180,13 @@ def decode(q_lat, k, z, scale, y=None, lse_dec=None, stream=None):
     return y
 
 
-def forward(q_lat, k, v, scale, y=None, z=None, lse_enc=None, lse_dec=None, workspace=None, stream=None):
-    """flare_forward: returns (y, z, lse_enc); fills lse_dec[B,H,N] (fp32) when given."""
+def forward(q_lat, k, v, scale, y=None, z=None, lse_enc=None, lse_dec=None, workspace=None, stream=None,
+            layout="bhnd"):
+    """flare_forward: returns (y, z, lse_enc); fills lse_dec[B,H,N] (fp32) when given.
+
+    layout 'bhnd': k, v, y are [B,H,N,d]; 'bnhd': they are [B,N,H,d]."""
     torch = _torch()
-    shp = _shape_of(q_lat, k)
+    shp = _shape_of(q_lat, k, layout)
     if y is None:
         y = torch.empty_like(k)
     if z is None:
@@ -193,12 +204,12 @@ def forward(q_lat, k, v, scale, y=None, z=None, lse_enc=None, lse_dec=None, work
 
 
 def backward(q_lat, k, v, dy, z, lse_enc, scale, y=None, lse_dec=None, dq_lat=None, dk=None, dv=None,
-             workspace=None, stream=None):
+             workspace=None, stream=None, layout="bhnd"):
     """flare_backward: returns (dq_lat[H,M,d] fp32, dk, dv in k's dtype).
 
     Pass the forward's y and lse_dec to reuse them; without both, they are recomputed from z."""
     torch = _torch()
-    shp = _shape_of(q_lat, k)
+    shp = _shape_of(q_lat, k, layout)
     if dq_lat is None:
         dq_lat = torch.empty((shp.H, shp.M, shp.d), dtype=torch.float32, device=k.device)
     if dk is None:

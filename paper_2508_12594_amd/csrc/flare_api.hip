@@ -61,6 +61,7 @@ int check_shape(const flare_shape *s)
     if (!s) return FLARE_EINVAL;
     if (s->B < 1 || s->H < 1 || s->N < 1 || s->M < 1 || s->d < 1) return FLARE_EINVAL;
     if (s->dtype != FLARE_F32 && s->dtype != FLARE_BF16) return FLARE_EUNSUPPORTED;
+    if (s->layout != FLARE_BHND && s->layout != FLARE_BNHD) return FLARE_EUNSUPPORTED;
     if (s->d != 4 && s->d != 8 && s->d != 16 && s->d != 32) return FLARE_EUNSUPPORTED;
     if ((long long)s->B * s->H > 65535) return FLARE_EUNSUPPORTED;
     return FLARE_OK;
@@ -80,7 +81,7 @@ const char *flare_strerror(int status)
     switch (status) {
         case FLARE_OK: return "success";
         case FLARE_EINVAL: return "invalid argument (null pointer or non-positive dimension)";
-        case FLARE_EUNSUPPORTED: return "unsupported shape or dtype";
+        case FLARE_EUNSUPPORTED: return "unsupported shape, dtype or layout";
         case FLARE_EALIGN: return "pointer is not 16-byte aligned";
         case FLARE_EWORKSPACE: return "workspace missing or too small";
         case FLARE_ELAUNCH: return "HIP runtime rejected a launch";

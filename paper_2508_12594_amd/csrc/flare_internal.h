@@ -38,6 +38,22 @@ struct Split {
 };
 Split plan_split(int N, int BH, int min_len, int target_blocks);
 
+// ---- where a row of a token tensor (k, v, y, dy, dk, dv) lives --------------------------------
+// Element (b, h, n, j) is at b*sb + h*sh + n*sn + j (in elements), for either layout of flare.h.
+struct TokStride {
+    long long sb, sh, sn;
+};
+inline TokStride tok_stride(const flare_shape &s)
+{
+    const long long H = s.H, N = s.N, d = s.d;
+    if (s.layout == FLARE_BNHD) return TokStride{N * H * d, d, H * d};
+    return TokStride{H * N * d, N * d, d};
+}
+__device__ __forceinline__ size_t tok_base(const TokStride &t, int bh, int H)
+{
+    return (size_t)(bh / H) * (size_t)t.sb + (size_t)(bh % H) * (size_t)t.sh;
+}
+
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 

@@ -164,7 +164,7 @@ template <int D, int MT, bool PRE, int MINB, int MODE>
 __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const float *__restrict__ z,
     bf16_t *__restrict__ y, const bf16_t *__restrict__ dy, float *__restrict__ lse_dec2,
-    float *__restrict__ delta, int H, int N, float c2)
+    float *__restrict__ delta, TokStride ts, int H, int N, float c2)
 {
     constexpr int KS = D / 16;   // k-steps of the score product
     constexpr int HV = D / 16;   // 16-wide column groups of Z, each with its own ones row
@@ -207,8 +207,8 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
             }
     }
 
-    const bf16_t *kb = k + (size_t)bh * N * D;
-    bf16_t *yb = y + (size_t)bh * N * D;
+    const bf16_t *kb = k + tok_base(ts, bh, H);
+    bf16_t *yb = y + tok_base(ts, bh, H);
     const int tiles = (N + 31) / 32;
     const int stride = gridDim.x * 4;
     int tile = blockIdx.x * 4 + wave;
@@ -217,7 +217,7 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
         const int nld = min(tile * 32 + l32, N - 1);
 #pragma unroll
         for (int s = 0; s < KS; ++s)
-            kt[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(kb + (size_t)nld * D + (D / 2) * hh + 8 * s));
+            kt[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(kb + (size_t)nld * ts.sn + (D / 2) * hh + 8 * s));
     }
     for (; tile < tiles; tile += stride) {
         const int n = tile * 32 + l32;
@@ -226,7 +226,7 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
             const int nld = min(tn * 32 + l32, N - 1);
 #pragma unroll
             for (int s = 0; s < KS; ++s)
-                ktn[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(kb + (size_t)nld * D + (D / 2) * hh + 8 * s));
+                ktn[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(kb + (size_t)nld * ts.sn + (D / 2) * hh + 8 * s));
         }
         auto qk_hi = [&](int t) {
             f32x16 r = splat16(0.f);
@@ -299,11 +299,12 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
         const float inv = 1.f / den;
         if constexpr (MODE == 1) {
             const size_t row = (size_t)bh * N + min(n, N - 1);
+            const bf16_t *gr = dy + tok_base(ts, bh, H) + (size_t)min(n, N - 1) * ts.sn;
             float part = 0.f;
 #pragma unroll
             for (int hv = 0; hv < HV; ++hv) {
-                const u32x2 g0 = *reinterpret_cast<const u32x2 *>(dy + row * D + 16 * hv + 4 * hh);
-                const u32x2 g1 = *reinterpret_cast<const u32x2 *>(dy + row * D + 16 * hv + 8 + 4 * hh);
+                const u32x2 g0 = *reinterpret_cast<const u32x2 *>(gr + 16 * hv + 4 * hh);
+                const u32x2 g1 = *reinterpret_cast<const u32x2 *>(gr + 16 * hv + 8 + 4 * hh);
                 part = fmaf(acc[hv][0] * inv, bf16_lo(g0[0]), part);
                 part = fmaf(acc[hv][1] * inv, bf16_hi(g0[0]), part);
                 part = fmaf(acc[hv][2] * inv, bf16_lo(g0[1]), part);
@@ -332,8 +333,8 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
                 w0[1] = cvt_pk_bf16(acc[hv][2] * inv, acc[hv][3] * inv);
                 w1[0] = cvt_pk_bf16(acc[hv][4] * inv, acc[hv][5] * inv);
                 w1[1] = cvt_pk_bf16(acc[hv][6] * inv, acc[hv][7] * inv);
-                *reinterpret_cast<u32x2 *>(yb + (size_t)n * D + 16 * hv + 4 * hh) = w0;
-                *reinterpret_cast<u32x2 *>(yb + (size_t)n * D + 16 * hv + 8 + 4 * hh) = w1;
+                *reinterpret_cast<u32x2 *>(yb + (size_t)n * ts.sn + 16 * hv + 4 * hh) = w0;
+                *reinterpret_cast<u32x2 *>(yb + (size_t)n * ts.sn + 16 * hv + 8 + 4 * hh) = w1;
             }
         }
 #pragma unroll
@@ -366,7 +367,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const float *__restrict__ lse_dec2,
     float *__restrict__ m_part, float *__restrict__ l_part, float *__restrict__ o_part,
-    int H, int N, int M, int chunk_len, int parts, int G, int TG, float c2)
+    TokStride ts, int H, int N, int M, int chunk_len, int parts, int G, int TG, float c2)
 {
     constexpr int KS = D / 16;
     constexpr int HV = D / 16;
@@ -397,8 +398,8 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         if constexpr (MODE == 0) ql[b][0] = with_slot0(ql[b][0], keep0, 0u);   // slot 0 := -c = 0
     }
 
-    const bf16_t *kb = k + (size_t)bh * N * D;
-    const bf16_t *vb = v + (size_t)bh * N * D;
+    const bf16_t *kb = k + tok_base(ts, bh, H);
+    const bf16_t *vb = v + tok_base(ts, bh, H);
     const int n0 = chunk * chunk_len;
     const int n1 = min(N, n0 + chunk_len);
     const int tiles = (n1 - n0 + 31) / 32;
@@ -427,13 +428,13 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         const int nk = min(tile_tok0(j) + l32, N - 1);
 #pragma unroll
         for (int s = 0; s < KS; ++s)
-            kk[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(kb + (size_t)nk * D + (D / 2) * hh + 8 * s));
+            kk[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(kb + (size_t)nk * ts.sn + (D / 2) * hh + 8 * s));
     };
     auto load_v = [&](int j, u32x4 (&vv)[LOADS]) {
         const int nv = min(tile_tok0(j) + vtok, N - 1);
 #pragma unroll
         for (int i = 0; i < LOADS; ++i)
-            vv[i] = *reinterpret_cast<const u32x4 *>(vb + (size_t)nv * D + 8 * ((lane & 1) * LOADS + i));
+            vv[i] = *reinterpret_cast<const u32x4 *>(vb + (size_t)nv * ts.sn + 8 * ((lane & 1) * LOADS + i));
     };
     auto write_vt = [&](const u32x4 (&vv)[LOADS], uint16_t *buf) {   // transposed: row = column of V
 #pragma unroll
@@ -623,7 +624,7 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
     const bf16_t *__restrict__ dy, const float *__restrict__ z, const float *__restrict__ lse_enc,
     const float *__restrict__ dz, const float *__restrict__ eps, const float *__restrict__ lse_dec2,
     const float *__restrict__ delta, float *__restrict__ dq_part,
-    int H, int N, int M, int chunk_len, int parts, int G, int TG, float c2)
+    TokStride ts, int H, int N, int M, int chunk_len, int parts, int G, int TG, float c2)
 {
     constexpr int KS = D / 16;
     constexpr int HV = D / 16;
@@ -687,9 +688,9 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
     w11[1] = 0u; w11[2] = 0u; w11[3] = 0u;
     const bf16x8 ones_aug = as_bf16x8(w11);      // slots 0,1 = 1 in the lower lane half, else 0
 
-    const bf16_t *kb = k + (size_t)bh * N * D;
-    const bf16_t *vb = v + (size_t)bh * N * D;
-    const bf16_t *gb = dy + (size_t)bh * N * D;
+    const bf16_t *kb = k + tok_base(ts, bh, H);
+    const bf16_t *vb = v + tok_base(ts, bh, H);
+    const bf16_t *gb = dy + tok_base(ts, bh, H);
     const float *lb = lse_dec2 + (size_t)bh * N;
     const float *db = delta + (size_t)bh * N;
     const int n0 = chunk * chunk_len;
@@ -712,7 +713,7 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
         const int n = min(tile_tok0(j) + l32, N - 1);
 #pragma unroll
         for (int s = 0; s < KS; ++s)
-            t[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(base + (size_t)n * D + (D / 2) * hh + 8 * s));
+            t[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(base + (size_t)n * ts.sn + (D / 2) * hh + 8 * s));
     };
     auto write_kt = [&](const bf16x8 (&t)[KS], uint16_t *buf) {   // transposed: row = d-index, column = token
 #pragma unroll
@@ -862,7 +863,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     const bf16_t *__restrict__ dy, const float *__restrict__ z, const float *__restrict__ lse_enc,
     const float *__restrict__ dz, const float *__restrict__ eps, const float *__restrict__ lse_dec2,
     const float *__restrict__ delta, bf16_t *__restrict__ dk, bf16_t *__restrict__ dv,
-    int H, int N, float c2, float scale)
+    TokStride ts, int H, int N, float c2, float scale)
 {
     constexpr int KS = D / 16;
     constexpr int HV = D / 16;
@@ -949,9 +950,9 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     w11[1] = 0u; w11[2] = 0u; w11[3] = 0u;
     const bf16x8 ones_aug = as_bf16x8(w11);
 
-    const bf16_t *kb = k + (size_t)bh * N * D;
-    const bf16_t *vb = v + (size_t)bh * N * D;
-    const bf16_t *gb = dy + (size_t)bh * N * D;
+    const bf16_t *kb = k + tok_base(ts, bh, H);
+    const bf16_t *vb = v + tok_base(ts, bh, H);
+    const bf16_t *gb = dy + tok_base(ts, bh, H);
     const float *lb = lse_dec2 + (size_t)bh * N;
     const float *db = delta + (size_t)bh * N;
     const int tiles = (N + 31) / 32;
@@ -960,7 +961,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
         const int n = min(tile * 32 + l32, N - 1);
 #pragma unroll
         for (int s = 0; s < KS; ++s)
-            t[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(base + (size_t)n * D + (D / 2) * hh + 8 * s));
+            t[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(base + (size_t)n * ts.sn + (D / 2) * hh + 8 * s));
     };
     auto image = [&](int t, int sid) { return as_bf16x8(img[(t * PER_TILE + sid) * 64 + lane]); };
 
@@ -1063,8 +1064,8 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
             }
         }
         if (n < N) {
-            bf16_t *dkr = dk + ((size_t)bh * N + n) * D;
-            bf16_t *dvr = dv + ((size_t)bh * N + n) * D;
+            bf16_t *dkr = dk + tok_base(ts, bh, H) + (size_t)n * ts.sn;
+            bf16_t *dvr = dv + tok_base(ts, bh, H) + (size_t)n * ts.sn;
 #pragma unroll
             for (int hv = 0; hv < HV; ++hv) {
                 u32x2 w0, w1;
@@ -1156,7 +1157,7 @@ int mfma_encode(const flare_shape &s, const void *q, const void *k, const void *
         LaunchTimer t(KID_ENCODE_PARTIAL, stream);
 #define FLARE_ENC(DD, NBB)                                                                                   \
     encode_mfma_kernel<DD, NBB, 2, 0><<<grid, e.threads, 0, stream>>>(qq, kk, vv, nullptr, m_part, l_part, o_part, \
-                                                                      s.H, s.N, s.M, p.enc.chunk_len, p.parts, e.G, \
+                                                                      tok_stride(s), s.H, s.N, s.M, p.enc.chunk_len, p.parts, e.G, \
                                                                       e.TG, c2)
         if (s.d == 16 && e.NB == 1) FLARE_ENC(16, 1);
         else if (s.d == 16 && e.NB == 2) FLARE_ENC(16, 2);
@@ -1182,7 +1183,7 @@ int mfma_dz_partial(const flare_shape &s, const void *q, const void *k, const vo
     LaunchTimer t(KID_BWD_DZ_PARTIAL, stream);
 #define FLARE_DZ(DD, NBB)                                                                                      \
     encode_mfma_kernel<DD, NBB, 2, 1><<<grid, e.threads, 0, stream>>>(qq, kk, gg, lse_dec2, nullptr, nullptr, dz_part, \
-                                                                      s.H, s.N, s.M, p.enc.chunk_len, p.parts, e.G,  \
+                                                                      tok_stride(s), s.H, s.N, s.M, p.enc.chunk_len, p.parts, e.G,  \
                                                                       e.TG, c2)
     if (s.d == 16 && e.NB == 1) FLARE_DZ(16, 1);
     else if (s.d == 16 && e.NB == 2) FLARE_DZ(16, 2);
@@ -1214,7 +1215,7 @@ int mfma_dq_partial(const flare_shape &s, const void *q, const void *k, const vo
     LaunchTimer t(KID_BWD_DQ_PARTIAL, stream);
 #define FLARE_DQ(DD, NBB, MINB)                                                                                 \
     bwd_dq_mfma_kernel<DD, NBB, MINB><<<grid, e.threads, 0, stream>>>(qq, kk, vv, gg, z, lse_enc, dz, eps, lse_dec2, \
-                                                                      delta, dq_part, s.H, s.N, s.M,                \
+                                                                      delta, dq_part, tok_stride(s), s.H, s.N, s.M, \
                                                                       p.enc.chunk_len, parts, e.G, e.TG, c2)
     if (s.d == 16 && e.NB == 1) FLARE_DQ(16, 1, 2);
     else if (s.d == 16) FLARE_DQ(16, 2, 2);
@@ -1256,7 +1257,7 @@ int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v,
                                 (int)lds) != hipSuccess)                                                         \
             return FLARE_ELAUNCH;                                                                                \
         kern<<<grid, 512, lds, stream>>>(qq, kk, vv, gg, z, lse_enc, dz, eps, lse_dec2, delta, (bf16_t *)dk,      \
-                                         (bf16_t *)dv, s.H, s.N, c2, scale);                                     \
+                                         (bf16_t *)dv, tok_stride(s), s.H, s.N, c2, scale);                      \
     } while (0)
     if (s.d == 16) {
         switch (MT) {
@@ -1305,8 +1306,8 @@ static int launch_decode_family(const flare_shape &s, const void *q, const void 
     bf16_t *yy = (bf16_t *)y;
     LaunchTimer t(MODE == 0 ? KID_DECODE : KID_BWD_TOKEN_STATS, stream);
 #define FLARE_DEC(DD, MTT, PREE, MINB)                                                                          \
-    decode_mfma_kernel<DD, MTT, PREE, MINB, MODE><<<grid, 256, 0, stream>>>(qq, kk, z, yy, gg, lse_dec2, delta, s.H, \
-                                                                            s.N, c2)
+    decode_mfma_kernel<DD, MTT, PREE, MINB, MODE><<<grid, 256, 0, stream>>>(qq, kk, z, yy, gg, lse_dec2, delta,      \
+                                                                            tok_stride(s), s.H, s.N, c2)
     const int MT = s.M / 32;
     if (s.d == 16) {
         switch (MT) {

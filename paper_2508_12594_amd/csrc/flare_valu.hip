@@ -101,7 +101,7 @@ template <typename T, int D>
 __global__ __launch_bounds__(kLatentBlock) void encode_partial_kernel(
     const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v,
     float *__restrict__ m_part, float *__restrict__ l_part, float *__restrict__ o_part,
-    int H, int N, int M, int chunk_len, int chunks, float c2)
+    TokStride ts, int H, int N, int M, int chunk_len, int chunks, float c2)
 {
     const int m = blockIdx.z * kLatentBlock + threadIdx.x;
     if (m >= M) return;
@@ -110,8 +110,8 @@ __global__ __launch_bounds__(kLatentBlock) void encode_partial_kernel(
     load_row<D>(q + ((size_t)h * M + m) * D, qm);
 #pragma unroll
     for (int j = 0; j < D; ++j) qm[j] *= c2;
-    const T *kb = k + (size_t)bh * N * D;
-    const T *vb = v + (size_t)bh * N * D;
+    const T *kb = k + tok_base(ts, bh, H);
+    const T *vb = v + tok_base(ts, bh, H);
     const int n0 = chunk * chunk_len;
     const int n1 = min(N, n0 + chunk_len);
 
@@ -126,7 +126,7 @@ __global__ __launch_bounds__(kLatentBlock) void encode_partial_kernel(
 #pragma unroll
         for (int t = 0; t < kGroup; ++t) {
             float kr[D];
-            load_row<D>(kb + (size_t)(n + t) * D, kr);
+            load_row<D>(kb + (size_t)(n + t) * ts.sn, kr);
             s[t] = dot<D>(qm, kr);
             gm = fmaxf(gm, s[t]);
         }
@@ -140,21 +140,21 @@ __global__ __launch_bounds__(kLatentBlock) void encode_partial_kernel(
             const float p = fast_exp2(s[t] - mr);
             l += p;
             float vr[D];
-            load_row<D>(vb + (size_t)(n + t) * D, vr);
+            load_row<D>(vb + (size_t)(n + t) * ts.sn, vr);
 #pragma unroll
             for (int j = 0; j < D; ++j) o[j] = fmaf(p, vr[j], o[j]);
         }
     }
     for (; n < n1; ++n) {
         float kr[D], vr[D];
-        load_row<D>(kb + (size_t)n * D, kr);
+        load_row<D>(kb + (size_t)n * ts.sn, kr);
         const float s = dot<D>(qm, kr);
         const float gm = fmaxf(mr, s);
         const float al = fast_exp2(mr - gm);
         mr = gm;
         const float p = fast_exp2(s - mr);
         l = l * al + p;
-        load_row<D>(vb + (size_t)n * D, vr);
+        load_row<D>(vb + (size_t)n * ts.sn, vr);
 #pragma unroll
         for (int j = 0; j < D; ++j) o[j] = fmaf(p, vr[j], o[j] * al);
     }
@@ -229,14 +229,15 @@ template <typename T, int D, int MODE>
 __global__ __launch_bounds__(kTokenBlock) void token_pass_kernel(
     const T *__restrict__ q, const T *__restrict__ k, const float *__restrict__ z,
     T *__restrict__ y, const T *__restrict__ dy, float *__restrict__ lse_dec2, float *__restrict__ delta,
-    int H, int N, int M, float c2)
+    TokStride ts, int H, int N, int M, float c2)
 {
     const int n = blockIdx.x * kTokenBlock + threadIdx.x;
     const int bh = blockIdx.y, h = bh % H;
     const bool valid = n < N;
-    const size_t row = (size_t)bh * N + (valid ? n : N - 1);
+    const size_t row = (size_t)bh * N + (valid ? n : N - 1);                     // index of the per-token scalars
+    const size_t trow = tok_base(ts, bh, H) + (size_t)(valid ? n : N - 1) * ts.sn;  // first element of the token's row
     float kn[D];
-    load_row<D>(k + row * D, kn);
+    load_row<D>(k + trow, kn);
 #pragma unroll
     for (int j = 0; j < D; ++j) kn[j] *= c2;
     const T *qh = q + (size_t)h * M * D;
@@ -289,28 +290,35 @@ __global__ __launch_bounds__(kTokenBlock) void token_pass_kernel(
     for (int j = 0; j < D; ++j) acc[j] *= inv;
     if (!valid) return;
     if constexpr (MODE == 0) {
-        store_row<D>(y + row * D, acc);
+        store_row<D>(y + trow, acc);
         if (lse_dec2) lse_dec2[row] = (mr + log2f(l)) * kLn2;   // optional saved statistic, natural log
     } else {
         float g[D];
-        load_row<D>(dy + row * D, g);
+        load_row<D>(dy + trow, g);
         lse_dec2[row] = mr + log2f(l);
         delta[row] = dot<D>(g, acc);
     }
 }
 
 // Token statistics of the backward from what the forward saved: delta[n] = <dY_n, Y_n> with the
-// stored Y, lse_dec2[n] = lse_dec[n] * log2(e).  thread = token; purely HBM-bound.
+// stored Y, lse_dec2[n] = lse_dec[n] * log2(e).  thread = one token row of one head, numbered in
+// the memory order of the token tensors so that a wave reads consecutive rows; purely HBM-bound.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void bwd_prep_kernel(
     const T *__restrict__ y, const T *__restrict__ dy, const float *__restrict__ lse_dec,
-    float *__restrict__ lse_dec2, float *__restrict__ delta, size_t rows)
+    float *__restrict__ lse_dec2, float *__restrict__ delta, bool head_fastest, int H, int N, size_t rows)
 {
-    const size_t row = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (row >= rows) return;
+    const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= rows) return;
+    const size_t trow = t * D;     // both layouts are dense: row t of the tensor as it lies in memory
+    size_t row = t;                // index into the [B][H][N] statistics
+    if (head_fastest) {            // t = (b*N + n)*H + h
+        const size_t bn = t / H, h = t % H, b = bn / N, n = bn % N;
+        row = (b * H + h) * N + n;
+    }
     float a[D], g[D];
-    load_row<D>(y + row * D, a);
-    load_row<D>(dy + row * D, g);
+    load_row<D>(y + trow, a);
+    load_row<D>(dy + trow, g);
     delta[row] = dot<D>(a, g);
     lse_dec2[row] = lse_dec[row] * kLog2e;
 }
@@ -322,7 +330,7 @@ template <typename T, int D>
 __global__ __launch_bounds__(kLatentBlock) void dz_partial_kernel(
     const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ dy,
     const float *__restrict__ lse_dec2, float *__restrict__ dz_part,
-    int H, int N, int M, int chunk_len, int chunks, float c2)
+    TokStride ts, int H, int N, int M, int chunk_len, int chunks, float c2)
 {
     const int m = blockIdx.z * kLatentBlock + threadIdx.x;
     if (m >= M) return;
@@ -331,8 +339,8 @@ __global__ __launch_bounds__(kLatentBlock) void dz_partial_kernel(
     load_row<D>(q + ((size_t)h * M + m) * D, qm);
 #pragma unroll
     for (int j = 0; j < D; ++j) qm[j] *= c2;
-    const T *kb = k + (size_t)bh * N * D;
-    const T *gb = dy + (size_t)bh * N * D;
+    const T *kb = k + tok_base(ts, bh, H);
+    const T *gb = dy + tok_base(ts, bh, H);
     const float *lb = lse_dec2 + (size_t)bh * N;
     const int n0 = chunk * chunk_len;
     const int n1 = min(N, n0 + chunk_len);
@@ -341,9 +349,9 @@ __global__ __launch_bounds__(kLatentBlock) void dz_partial_kernel(
     for (int j = 0; j < D; ++j) acc[j] = 0.f;
     for (int n = n0; n < n1; ++n) {
         float kr[D], g[D];
-        load_row<D>(kb + (size_t)n * D, kr);
+        load_row<D>(kb + (size_t)n * ts.sn, kr);
         const float r = fast_exp2(dot<D>(qm, kr) - lb[n]);
-        load_row<D>(gb + (size_t)n * D, g);
+        load_row<D>(gb + (size_t)n * ts.sn, g);
 #pragma unroll
         for (int j = 0; j < D; ++j) acc[j] = fmaf(r, g[j], acc[j]);
     }
@@ -409,7 +417,7 @@ __global__ __launch_bounds__(kLatentBlock) void dq_partial_kernel(
     const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v, const T *__restrict__ dy,
     const float *__restrict__ z, const float *__restrict__ lse_enc, const float *__restrict__ dz,
     const float *__restrict__ eps, const float *__restrict__ lse_dec2, const float *__restrict__ delta,
-    float *__restrict__ dq_part, int H, int N, int M, int chunk_len, int chunks, float c2)
+    float *__restrict__ dq_part, TokStride ts, int H, int N, int M, int chunk_len, int chunks, float c2)
 {
     const int m = blockIdx.z * kLatentBlock + threadIdx.x;
     if (m >= M) return;
@@ -422,18 +430,18 @@ __global__ __launch_bounds__(kLatentBlock) void dq_partial_kernel(
     for (int j = 0; j < D; ++j) { qm[j] *= c2; acc[j] = 0.f; }
     const float le2 = lse_enc[(size_t)bh * M + m] * kLog2e;
     const float ep = eps[(size_t)bh * M + m];
-    const T *kb = k + (size_t)bh * N * D;
-    const T *vb = v + (size_t)bh * N * D;
-    const T *gb = dy + (size_t)bh * N * D;
+    const T *kb = k + tok_base(ts, bh, H);
+    const T *vb = v + tok_base(ts, bh, H);
+    const T *gb = dy + tok_base(ts, bh, H);
     const float *lb = lse_dec2 + (size_t)bh * N;
     const float *db = delta + (size_t)bh * N;
     const int n0 = chunk * chunk_len;
     const int n1 = min(N, n0 + chunk_len);
     for (int n = n0; n < n1; ++n) {
         float kr[D], vr[D], g[D];
-        load_row<D>(kb + (size_t)n * D, kr);
-        load_row<D>(vb + (size_t)n * D, vr);
-        load_row<D>(gb + (size_t)n * D, g);
+        load_row<D>(kb + (size_t)n * ts.sn, kr);
+        load_row<D>(vb + (size_t)n * ts.sn, vr);
+        load_row<D>(gb + (size_t)n * ts.sn, g);
         const float s2 = dot<D>(qm, kr);
         const float p = fast_exp2(s2 - le2);
         const float r = fast_exp2(s2 - lb[n]);
@@ -469,17 +477,18 @@ __global__ __launch_bounds__(kTokenBlock) void dkdv_kernel(
     const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v, const T *__restrict__ dy,
     const float *__restrict__ z, const float *__restrict__ lse_enc, const float *__restrict__ dz,
     const float *__restrict__ eps, const float *__restrict__ lse_dec2, const float *__restrict__ delta,
-    T *__restrict__ dk, T *__restrict__ dv, int H, int N, int M, float scale)
+    T *__restrict__ dk, T *__restrict__ dv, TokStride ts, int H, int N, int M, float scale)
 {
     const int n = blockIdx.x * kTokenBlock + threadIdx.x;
     const int bh = blockIdx.y, h = bh % H;
     const bool valid = n < N;
     const size_t row = (size_t)bh * N + (valid ? n : N - 1);
+    const size_t trow = tok_base(ts, bh, H) + (size_t)(valid ? n : N - 1) * ts.sn;
     const float c2 = scale * kLog2e;
     float kn[D], vn[D], g[D], ak[D], av[D];
-    load_row<D>(k + row * D, kn);
-    load_row<D>(v + row * D, vn);
-    load_row<D>(dy + row * D, g);
+    load_row<D>(k + trow, kn);
+    load_row<D>(v + trow, vn);
+    load_row<D>(dy + trow, g);
 #pragma unroll
     for (int j = 0; j < D; ++j) { kn[j] *= c2; ak[j] = 0.f; av[j] = 0.f; }
     const float ld2 = lse_dec2[row];
@@ -507,8 +516,8 @@ __global__ __launch_bounds__(kTokenBlock) void dkdv_kernel(
     if (!valid) return;
 #pragma unroll
     for (int j = 0; j < D; ++j) ak[j] *= scale;
-    store_row<D>(dk + row * D, ak);
-    store_row<D>(dv + row * D, av);
+    store_row<D>(dk + trow, ak);
+    store_row<D>(dv + trow, av);
 }
 
 // ---- workspace carving --------------------------------------------------------------------
@@ -559,7 +568,7 @@ int encode_impl(const flare_shape &s, const T *q, const T *k, const T *v, float 
     {
         LaunchTimer t(KID_ENCODE_PARTIAL, stream);
         encode_partial_kernel<T, D><<<dim3(plan.enc.chunks, BH, lat_blocks), kLatentBlock, 0, stream>>>(
-            q, k, v, m_part, l_part, o_part, s.H, s.N, s.M, plan.enc.chunk_len, plan.enc.chunks, scale * kLog2e);
+            q, k, v, m_part, l_part, o_part, tok_stride(s), s.H, s.N, s.M, plan.enc.chunk_len, plan.enc.chunks, scale * kLog2e);
     }
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     return launch_encode_merge(s, m_part, l_part, o_part, z, lse_enc, plan.enc.chunks, stream);
@@ -571,7 +580,7 @@ int decode_impl(const flare_shape &s, const T *q, const T *k, const float *z, T 
 {
     LaunchTimer t(KID_DECODE, stream);
     token_pass_kernel<T, D, 0><<<dim3((s.N + kTokenBlock - 1) / kTokenBlock, s.B * s.H), kTokenBlock, 0, stream>>>(
-        q, k, z, y, nullptr, lse_dec, nullptr, s.H, s.N, s.M, scale * kLog2e);
+        q, k, z, y, nullptr, lse_dec, nullptr, tok_stride(s), s.H, s.N, s.M, scale * kLog2e);
     return check_launch();
 }
 
@@ -587,22 +596,23 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     bwd_layout(s, bwd_slots(s, plan), ws, &w);
     const int BH = s.B * s.H;
     const float c2 = scale * kLog2e;
+    const TokStride ts = tok_stride(s);
     const int lat_blocks = (s.M + kLatentBlock - 1) / kLatentBlock;
     const dim3 tok_grid((s.N + kTokenBlock - 1) / kTokenBlock, BH);
     const dim3 lat_grid(plan.bwd.chunks, BH, lat_blocks);
     // token statistics: from what the forward saved, or recomputed
     if (y && lse_dec) {
-        const size_t rows = (size_t)BH * s.N;
         LaunchTimer t(KID_BWD_PREP, stream);
-        bwd_prep_kernel<T, D><<<(unsigned)((rows + 255) / 256), 256, 0, stream>>>(y, dy, lse_dec, w.lse_dec2, w.delta,
-                                                                                  rows);
+        const size_t rows = (size_t)BH * s.N;
+        bwd_prep_kernel<T, D><<<(unsigned)((rows + 255) / 256), 256, 0, stream>>>(
+            y, dy, lse_dec, w.lse_dec2, w.delta, s.layout == FLARE_BNHD, s.H, s.N, rows);
     } else if (mf) {
         const int rc = mfma_token_stats(s, q, k, z, dy, w.lse_dec2, w.delta, scale, stream);
         if (rc != FLARE_OK) return rc;
     } else {
         LaunchTimer t(KID_BWD_TOKEN_STATS, stream);
         token_pass_kernel<T, D, 1><<<tok_grid, kTokenBlock, 0, stream>>>(q, k, z, nullptr, dy, w.lse_dec2, w.delta,
-                                                                         s.H, s.N, s.M, c2);
+                                                                         ts, s.H, s.N, s.M, c2);
     }
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     if (mf) {
@@ -611,8 +621,8 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     } else {
         {
             LaunchTimer t(KID_BWD_DZ_PARTIAL, stream);
-            dz_partial_kernel<T, D><<<lat_grid, kLatentBlock, 0, stream>>>(q, k, dy, w.lse_dec2, w.part, s.H, s.N,
-                                                                           s.M, plan.bwd.chunk_len, plan.bwd.chunks,
+            dz_partial_kernel<T, D><<<lat_grid, kLatentBlock, 0, stream>>>(q, k, dy, w.lse_dec2, w.part, ts, s.H,
+                                                                           s.N, s.M, plan.bwd.chunk_len, plan.bwd.chunks,
                                                                            c2);
         }
         if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
@@ -631,7 +641,7 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     } else {
         LaunchTimer t(KID_BWD_DQ_PARTIAL, stream);
         dq_partial_kernel<T, D><<<lat_grid, kLatentBlock, 0, stream>>>(q, k, v, dy, z, lse_enc, w.dz, w.eps,
-                                                                       w.lse_dec2, w.delta, w.part, s.H, s.N, s.M,
+                                                                       w.lse_dec2, w.delta, w.part, ts, s.H, s.N, s.M,
                                                                        plan.bwd.chunk_len, plan.bwd.chunks, c2);
     }
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
@@ -645,7 +655,7 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     {
         LaunchTimer t(KID_BWD_DKDV, stream);
         dkdv_kernel<T, D><<<tok_grid, kTokenBlock, 0, stream>>>(q, k, v, dy, z, lse_enc, w.dz, w.eps, w.lse_dec2,
-                                                                w.delta, dk, dv, s.H, s.N, s.M, scale);
+                                                                w.delta, dk, dv, ts, s.H, s.N, s.M, scale);
     }
     return check_launch();
 }
