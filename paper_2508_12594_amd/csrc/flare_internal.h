@@ -99,14 +99,19 @@ int mfma_decode(const flare_shape &s, const void *q, const void *k, const float 
 int mfma_token_stats(const flare_shape &s, const void *q, const void *k, const float *z, const void *dy,
                      float *lse_dec2, float *delta, float scale, hipStream_t stream);
 bool mfma_dkdv_supported(const flare_shape &s);
+// In the three backward launchers below the per-token decode statistic is read as
+// ld_mul * lse_dec2[n]: pass the workspace array with ld_mul = 1, or the forward's natural-log
+// lse_dec with ld_mul = log2(e).
 int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy, const float *z,
               const float *lse_enc, const float *dz, const float *eps, const float *lse_dec2, const float *delta,
-              void *dk, void *dv, float scale, hipStream_t stream);
+              float ld_mul, void *dk, void *dv, float scale, hipStream_t stream);
 int mfma_dq_parts(const flare_shape &s);
 int mfma_dq_partial(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy,
                     const float *z, const float *lse_enc, const float *dz, const float *eps,
-                    const float *lse_dec2, const float *delta, float *dq_part, float scale, hipStream_t stream);
+                    const float *lse_dec2, const float *delta, float ld_mul, float *dq_part, float scale,
+                    hipStream_t stream);
+// y and delta_out may be NULL; when given, delta_out[b][h][n] = <dY_n, Y_n> is written as a by-product.
 int mfma_dz_partial(const flare_shape &s, const void *q, const void *k, const void *dy, const float *lse_dec2,
-                    float *dz_part, float scale, hipStream_t stream);
+                    float ld_mul, const void *y, float *delta_out, float *dz_part, float scale, hipStream_t stream);
 
 }  // namespace flare

@@ -361,11 +361,15 @@ constexpr int kVtStride = 36;   // uint16 per LDS row: 32 tokens + 4 pad (72 B, 
 // MODE 1 (second step of the backward) reuses the same machinery for dZ = R^T dY: the values are
 // dY, the weights are R^T[n][m] = 2^(S2 - lse_dec2[n]) with the per-token -lse_dec2 carried as a
 // hi + lo bf16 pair in one more k-step (token side: slots 2,3; query side: 1,1), and there is no
-// softmax state: only the unnormalised sums are written.
+// softmax state: only the unnormalised sums are written.  lse_dec2 is read as ld_mul * lse_dec2[n]
+// (ld_mul = log2 e when the array holds the forward's natural-log statistic).  When y_tok is given,
+// every wave also forms delta[n] = <dY_n, Y_n> from the rows it streams anyway (no branch in the
+// loop), and the waves of latent group 0 store it to delta_out for the two kernels that follow.
 template <int D, int NB, int MINB, int MODE>
 __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
-    const float *__restrict__ lse_dec2,
+    const float *__restrict__ lse_dec2, float ld_mul, const bf16_t *__restrict__ y_tok,
+    float *__restrict__ delta_out,
     float *__restrict__ m_part, float *__restrict__ l_part, float *__restrict__ o_part,
     TokStride ts, int H, int N, int M, int chunk_len, int parts, int G, int TG, float c2)
 {
@@ -492,13 +496,36 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         }
     };
     auto load_lse = [&](int j) {
-        if constexpr (MODE == 1) return -lb[min(tile_tok0(j) + l32, N - 1)];
+        if constexpr (MODE == 1) return -lb[min(tile_tok0(j) + l32, N - 1)] * ld_mul;
         else return 0.f;
+    };
+    // delta of the wave's j-th tile (j < cnt) from its dY and Y rows: two lanes per token
+    const bool do_delta = (MODE == 1) && y_tok != nullptr;
+    const bf16_t *yb = (MODE == 1 && y_tok != nullptr) ? y_tok + tok_base(ts, bh, H) : vb;
+    auto load_y = [&](int j, u32x4 (&yy)[LOADS]) {
+        const int nv = min(tile_tok0(j) + vtok, N - 1);
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i)
+            yy[i] = *reinterpret_cast<const u32x4 *>(yb + (size_t)nv * ts.sn + 8 * ((lane & 1) * LOADS + i));
+    };
+    auto put_delta = [&](int j, const u32x4 (&gv)[LOADS], const u32x4 (&yy)[LOADS]) {
+        float part = 0.f;
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                part = fmaf(bf16_lo(gv[i][e]), bf16_lo(yy[i][e]), part);
+                part = fmaf(bf16_hi(gv[i][e]), bf16_hi(yy[i][e]), part);
+            }
+        // the other half of the row is in the neighbouring lane: quad_perm [1,0,3,2]
+        part += __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(part), 0xB1, 0xf, 0xf, true));
+        const int n = n0 + 32 * (tg + j * TG) + vtok;
+        if (do_delta && j < cnt && g == 0 && (lane & 1) == 0 && n < n1) delta_out[(size_t)bh * N + n] = part;
     };
 
     if (cnt > 0) {
         bf16x8 kt[KS], ktn[KS], va[HV][2];
-        u32x4 vr1[LOADS], vr2[LOADS];
+        u32x4 vr1[LOADS], vr2[LOADS], yr1[LOADS], yr2[LOADS];
         f32x16 S[NB];
         bool first = true;
 
@@ -506,6 +533,11 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         float nl = load_lse(0), nln = 0.f;
         load_k(0, kt);
         load_v(0, vr1);
+        if (do_delta) {
+            load_y(0, yr1);
+            put_delta(0, vr1, yr1);
+            load_y(1, yr1);
+        }
         compiler_fence();
         write_vt(vr1, vt);
         compiler_fence();
@@ -521,6 +553,11 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
             nln = load_lse(j + 1);
             load_k(j + 1, ktn);
             load_v(j + 2, vr2);
+            if constexpr (MODE == 1) {
+                // (when y_tok is NULL, yb aliases the dY rows: the loads stay in bounds, nothing is stored)
+                load_y(j + 2, yr2);
+                put_delta(j + 1, vr1, yr1);   // vr1, yr1: rows of tile j+1 (nothing stored past the last tile)
+            }
             compiler_fence();
             write_vt(vr1, buf_next);          // values of tile j+1
             compiler_fence();
@@ -581,6 +618,10 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
             for (int s = 0; s < KS; ++s) kt[s] = ktn[s];
 #pragma unroll
             for (int i = 0; i < LOADS; ++i) vr1[i] = vr2[i];
+            if (do_delta) {
+#pragma unroll
+                for (int i = 0; i < LOADS; ++i) yr1[i] = yr2[i];
+            }
         }
     }
 
@@ -623,7 +664,7 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const bf16_t *__restrict__ dy, const float *__restrict__ z, const float *__restrict__ lse_enc,
     const float *__restrict__ dz, const float *__restrict__ eps, const float *__restrict__ lse_dec2,
-    const float *__restrict__ delta, float *__restrict__ dq_part,
+    const float *__restrict__ delta, float ld_mul, float *__restrict__ dq_part,
     TokStride ts, int H, int N, int M, int chunk_len, int parts, int G, int TG, float c2)
 {
     constexpr int KS = D / 16;
@@ -748,7 +789,7 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
         load_rows(kb, 1, ktn);
         load_rows(vb, 0, vt);
         load_rows(gb, 0, gt);
-        nld = -lb[min(tile_tok0(0) + l32, N - 1)];
+        nld = -lb[min(tile_tok0(0) + l32, N - 1)] * ld_mul;
         dl = db[min(tile_tok0(0) + l32, N - 1)];
         compiler_fence();
         write_kt(kt, lds);
@@ -761,7 +802,7 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
             load_rows(kb, j + 2, ktnn);
             load_rows(vb, j + 1, vtn);
             load_rows(gb, j + 1, gtn);
-            nldn = -lb[min(tile_tok0(j + 1) + l32, N - 1)];
+            nldn = -lb[min(tile_tok0(j + 1) + l32, N - 1)] * ld_mul;
             dln = db[min(tile_tok0(j + 1) + l32, N - 1)];
             compiler_fence();
             write_kt(ktn, buf_next);
@@ -862,7 +903,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const bf16_t *__restrict__ dy, const float *__restrict__ z, const float *__restrict__ lse_enc,
     const float *__restrict__ dz, const float *__restrict__ eps, const float *__restrict__ lse_dec2,
-    const float *__restrict__ delta, bf16_t *__restrict__ dk, bf16_t *__restrict__ dv,
+    const float *__restrict__ delta, float ld_mul, bf16_t *__restrict__ dk, bf16_t *__restrict__ dv,
     TokStride ts, int H, int N, float c2, float scale)
 {
     constexpr int KS = D / 16;
@@ -979,7 +1020,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
         load_cols(vb, tn, vtn);
         load_cols(gb, tn, gtn);
         const size_t row = (size_t)min(n, N - 1);
-        const float nld = -lb[row], dl = db[row];
+        const float nld = -lb[row] * ld_mul, dl = db[row];
 
         u32x4 wb;
         wb[0] = 0u; wb[2] = 0u; wb[3] = 0u;
@@ -1156,7 +1197,7 @@ int mfma_encode(const flare_shape &s, const void *q, const void *k, const void *
     {
         LaunchTimer t(KID_ENCODE_PARTIAL, stream);
 #define FLARE_ENC(DD, NBB)                                                                                   \
-    encode_mfma_kernel<DD, NBB, 2, 0><<<grid, e.threads, 0, stream>>>(qq, kk, vv, nullptr, m_part, l_part, o_part, \
+    encode_mfma_kernel<DD, NBB, 2, 0><<<grid, e.threads, 0, stream>>>(qq, kk, vv, nullptr, 1.f, nullptr, nullptr, m_part, l_part, o_part, \
                                                                       tok_stride(s), s.H, s.N, s.M, p.enc.chunk_len, p.parts, e.G, \
                                                                       e.TG, c2)
         if (s.d == 16 && e.NB == 1) FLARE_ENC(16, 1);
@@ -1172,7 +1213,7 @@ int mfma_encode(const flare_shape &s, const void *q, const void *k, const void *
 
 // dZ partials of the backward (the encode machinery with values dY and weights R^T)
 int mfma_dz_partial(const flare_shape &s, const void *q, const void *k, const void *dy, const float *lse_dec2,
-                    float *dz_part, float scale, hipStream_t stream)
+                    float ld_mul, const void *y, float *delta_out, float *dz_part, float scale, hipStream_t stream)
 {
     const MfmaPlan p = mfma_plan(s);
     const EncGeom e = enc_geom(s.M, s.d);
@@ -1182,7 +1223,7 @@ int mfma_dz_partial(const flare_shape &s, const void *q, const void *k, const vo
     const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *gg = (const bf16_t *)dy;
     LaunchTimer t(KID_BWD_DZ_PARTIAL, stream);
 #define FLARE_DZ(DD, NBB)                                                                                      \
-    encode_mfma_kernel<DD, NBB, 2, 1><<<grid, e.threads, 0, stream>>>(qq, kk, gg, lse_dec2, nullptr, nullptr, dz_part, \
+    encode_mfma_kernel<DD, NBB, 2, 1><<<grid, e.threads, 0, stream>>>(qq, kk, gg, lse_dec2, ld_mul, (const bf16_t *)y, delta_out, nullptr, nullptr, dz_part, \
                                                                       tok_stride(s), s.H, s.N, s.M, p.enc.chunk_len, p.parts, e.G,  \
                                                                       e.TG, c2)
     if (s.d == 16 && e.NB == 1) FLARE_DZ(16, 1);
@@ -1197,7 +1238,8 @@ int mfma_dz_partial(const flare_shape &s, const void *q, const void *k, const vo
 // dQ partials of the backward; slot layout as the encode partials: [(b*h) * parts + part][M][d]
 int mfma_dq_partial(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy,
                     const float *z, const float *lse_enc, const float *dz, const float *eps,
-                    const float *lse_dec2, const float *delta, float *dq_part, float scale, hipStream_t stream)
+                    const float *lse_dec2, const float *delta, float ld_mul, float *dq_part, float scale,
+                    hipStream_t stream)
 {
     const MfmaPlan p = mfma_plan(s);
     EncGeom e = enc_geom(s.M, s.d);
@@ -1215,7 +1257,7 @@ int mfma_dq_partial(const flare_shape &s, const void *q, const void *k, const vo
     LaunchTimer t(KID_BWD_DQ_PARTIAL, stream);
 #define FLARE_DQ(DD, NBB, MINB)                                                                                 \
     bwd_dq_mfma_kernel<DD, NBB, MINB><<<grid, e.threads, 0, stream>>>(qq, kk, vv, gg, z, lse_enc, dz, eps, lse_dec2, \
-                                                                      delta, dq_part, tok_stride(s), s.H, s.N, s.M, \
+                                                                      delta, ld_mul, dq_part, tok_stride(s), s.H, s.N, s.M, \
                                                                       p.enc.chunk_len, parts, e.G, e.TG, c2)
     if (s.d == 16 && e.NB == 1) FLARE_DQ(16, 1, 2);
     else if (s.d == 16) FLARE_DQ(16, 2, 2);
@@ -1236,7 +1278,7 @@ bool mfma_dkdv_supported(const flare_shape &s)
 
 int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy, const float *z,
               const float *lse_enc, const float *dz, const float *eps, const float *lse_dec2, const float *delta,
-              void *dk, void *dv, float scale, hipStream_t stream)
+              float ld_mul, void *dk, void *dv, float scale, hipStream_t stream)
 {
     const int BH = s.B * s.H;
     const int tiles = (s.N + 31) / 32;
@@ -1256,7 +1298,7 @@ int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v,
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
                                 (int)lds) != hipSuccess)                                                         \
             return FLARE_ELAUNCH;                                                                                \
-        kern<<<grid, 512, lds, stream>>>(qq, kk, vv, gg, z, lse_enc, dz, eps, lse_dec2, delta, (bf16_t *)dk,      \
+        kern<<<grid, 512, lds, stream>>>(qq, kk, vv, gg, z, lse_enc, dz, eps, lse_dec2, delta, ld_mul, (bf16_t *)dk, \
                                          (bf16_t *)dv, tok_stride(s), s.H, s.N, c2, scale);                      \
     } while (0)
     if (s.d == 16) {

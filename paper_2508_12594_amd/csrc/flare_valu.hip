@@ -600,8 +600,15 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     const int lat_blocks = (s.M + kLatentBlock - 1) / kLatentBlock;
     const dim3 tok_grid((s.N + kTokenBlock - 1) / kTokenBlock, BH);
     const dim3 lat_grid(plan.bwd.chunks, BH, lat_blocks);
-    // token statistics: from what the forward saved, or recomputed
-    if (y && lse_dec) {
+    // token statistics: from what the forward saved, or recomputed.  On the matrix-core path the
+    // saved ones need no pass of their own: the dZ kernel forms delta while it streams dY, and every
+    // kernel reads lse_dec itself, scaled to log2 units.
+    const bool saved = y && lse_dec;
+    const bool fused = saved && mf && mfma_dkdv_supported(s);   // every later kernel is a matrix-core one
+    const float *ld = fused ? lse_dec : w.lse_dec2;
+    const float ld_mul = fused ? kLog2e : 1.f;
+    if (fused) {
+    } else if (saved) {
         LaunchTimer t(KID_BWD_PREP, stream);
         const size_t rows = (size_t)BH * s.N;
         bwd_prep_kernel<T, D><<<(unsigned)((rows + 255) / 256), 256, 0, stream>>>(
@@ -616,7 +623,8 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     }
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     if (mf) {
-        const int rc = mfma_dz_partial(s, q, k, dy, w.lse_dec2, w.part, scale, stream);
+        const int rc = mfma_dz_partial(s, q, k, dy, ld, ld_mul, fused ? y : nullptr, fused ? w.delta : nullptr,
+                                       w.part, scale, stream);
         if (rc != FLARE_OK) return rc;
     } else {
         {
@@ -635,7 +643,7 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     int dq_parts = plan.bwd.chunks;
     if (mf) {
         dq_parts = mfma_dq_parts(s);
-        const int rc = mfma_dq_partial(s, q, k, v, dy, z, lse_enc, w.dz, w.eps, w.lse_dec2, w.delta, w.part, scale,
+        const int rc = mfma_dq_partial(s, q, k, v, dy, z, lse_enc, w.dz, w.eps, ld, w.delta, ld_mul, w.part, scale,
                                        stream);
         if (rc != FLARE_OK) return rc;
     } else {
@@ -651,7 +659,7 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     }
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     if (mf && mfma_dkdv_supported(s))
-        return mfma_dkdv(s, q, k, v, dy, z, lse_enc, w.dz, w.eps, w.lse_dec2, w.delta, dk, dv, scale, stream);
+        return mfma_dkdv(s, q, k, v, dy, z, lse_enc, w.dz, w.eps, ld, w.delta, ld_mul, dk, dv, scale, stream);
     {
         LaunchTimer t(KID_BWD_DKDV, stream);
         dkdv_kernel<T, D><<<tok_grid, kTokenBlock, 0, stream>>>(q, k, v, dy, z, lse_enc, w.dz, w.eps, w.lse_dec2,
