@@ -37,7 +37,8 @@ struct ProfileState {
 ProfileState g_prof;
 const char *const kKernelNames[KID_COUNT] = {
     "encode_partial", "encode_merge", "decode", "bwd_token_stats", "bwd_prep", "bwd_dz_partial",
-    "bwd_dz_merge", "bwd_dq_partial", "bwd_dq_reduce", "bwd_dkdv"};
+    "bwd_dz_merge", "bwd_dq_partial", "bwd_dq_reduce", "bwd_dkdv", "bwd_plan", "bwd_dq_partial_2exp",
+    "bwd_dkdv_2exp"};
 }  // namespace
 
 LaunchTimer::LaunchTimer(int kid, hipStream_t s) : slot(-1), stream(s)

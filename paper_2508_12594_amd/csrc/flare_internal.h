@@ -20,6 +20,9 @@ enum KernelId {
     KID_BWD_DQ_PARTIAL,
     KID_BWD_DQ_REDUCE,
     KID_BWD_DKDV,
+    KID_BWD_PLAN,
+    KID_BWD_DQ_PARTIAL_2EXP,
+    KID_BWD_DKDV_2EXP,
     KID_COUNT
 };
 
@@ -99,19 +102,25 @@ int mfma_decode(const flare_shape &s, const void *q, const void *k, const float 
 int mfma_token_stats(const flare_shape &s, const void *q, const void *k, const float *z, const void *dy,
                      float *lse_dec2, float *delta, float scale, hipStream_t stream);
 bool mfma_dkdv_supported(const flare_shape &s);
-// In the three backward launchers below the per-token decode statistic is read as
+// In the backward launchers below the per-token decode statistic is read as
 // ld_mul * lse_dec2[n]: pass the workspace array with ld_mul = 1, or the forward's natural-log
 // lse_dec with ld_mul = log2(e).
 int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy, const float *z,
               const float *lse_enc, const float *dz, const float *eps, const float *lse_dec2, const float *delta,
-              float ld_mul, void *dk, void *dv, float scale, hipStream_t stream);
+              float ld_mul, const int *plan, bool one_exp, void *dk, void *dv, float scale, hipStream_t stream);
 int mfma_dq_parts(const flare_shape &s);
 int mfma_dq_partial(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy,
                     const float *z, const float *lse_enc, const float *dz, const float *eps,
-                    const float *lse_dec2, const float *delta, float ld_mul, float *dq_part, float scale,
-                    hipStream_t stream);
+                    const float *lse_dec2, const float *delta, float ld_mul, const int *plan, bool one_exp,
+                    float *dq_part, float scale, hipStream_t stream);
 // y and delta_out may be NULL; when given, delta_out[b][h][n] = <dY_n, Y_n> is written as a by-product.
 int mfma_dz_partial(const flare_shape &s, const void *q, const void *k, const void *dy, const float *lse_dec2,
-                    float ld_mul, const void *y, float *delta_out, float *dz_part, float scale, hipStream_t stream);
+                    float ld_mul, const void *y, float *delta_out, float *ld_range, float *dz_part, float scale,
+                    hipStream_t stream);
+// The dQ and dK/dV kernels exist in two variants, one and two exponentials per score.  Both are
+// launched; each leaves at once the (b,h) slices that plan[b*h] (1 = one exponential) gives to the
+// other.  ld_range[b*h][part] = (min, max) of lse_dec2 as mfma_dz_partial recorded it.
+int mfma_bwd_plan(const flare_shape &s, const float *ld_range, const float *lse_enc, int *plan, bool force_two,
+                  hipStream_t stream);
 
 }  // namespace flare

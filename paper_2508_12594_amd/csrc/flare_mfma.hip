@@ -148,9 +148,10 @@ __device__ __forceinline__ void compiler_fence() { asm volatile("" ::: "memory")
 
 // ============================================================================================
 // Decode.  One wave owns 32 tokens at a time and all M latents:
-//   pass 1: scores from the hi terms only -> per-token maximum, rounded to bf16 = stabiliser b;
-//   pass 2: full scores minus b (b sits in slot 0 of the key operand of the lo product), 2^x,
-//           pack, and Y^T += Zaug^T . E with Zaug = [Z | 1].
+//   pass 1: scores from the hi terms only -> per-token maximum = stabiliser b;
+//   pass 2: full scores minus b (-b is the C operand the score products of all latent tiles
+//           start from: one 16-register splat per token tile), 2^x, pack, and
+//           Y^T += Zaug^T . E with Zaug = [Z | 1].
 // Q (as A operand) and Z^T (as A operand, latents in the permuted order) live in registers
 // for the whole kernel; K streams from HBM straight into the B-operand layout; no LDS.
 // Each pass issues the MFMAs of latent tile t+1 before the vector work on tile t.
@@ -174,14 +175,11 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
     const int bh = blockIdx.y, h = bh % H;
     const bool flip = c2 < 0.f;
     const float ac2 = PRE ? c2 : fabsf(c2);
-    const uint32_t keep0 = hh == 0 ? 0xffff0000u : 0xffffffffu;
 
     bf16x8 qh[MT][KS], ql[MT][KS];
 #pragma unroll
-    for (int t = 0; t < MT; ++t) {
+    for (int t = 0; t < MT; ++t)
         load_q_operand<D, PRE>(q + ((size_t)h * M + 32 * t + l32) * D, hh, c2, flip, qh[t], ql[t]);
-        if constexpr (PRE) ql[t][0] = with_slot0(ql[t][0], keep0, hh == 0 ? 0x3f80u : 0u);   // slot 0 := 1.0
-    }
 
     // Zaug^T operand: row l32 (< 16: column 16*hv + l32 of Z; 16: ones; else zero)
     bf16x8 zt[HV][2 * MT];
@@ -246,9 +244,8 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
             s_cur = s_next;
         }
         mx = fmaxf(mx, __shfl_xor(mx, 32));
-        // stabiliser: bf16(max) in slot 0 of the key operand (PRE), or folded into the fma
-        const uint32_t bbits = rne_bf16(-mx);
-        const bf16x8 kta0 = with_slot0(kt[0], keep0, hh == 0 ? bbits : 0u);
+        // stabiliser: -max as the starting value of the score accumulators (PRE), or folded into the fma
+        const f32x16 cinit = splat16(PRE ? -mx : 0.f);
         const float b2 = mx * ac2;
         // The hi products are recomputed in pass 2 rather than kept (8 tiles x 16 registers would
         // not fit); an opaque copy of the keys stops the compiler from merging the two passes.
@@ -260,13 +257,12 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
             kt2[ks] = as_bf16x8(w);
         }
         auto qk_full = [&](int t) {
-            f32x16 r = splat16(0.f);
+            f32x16 r = cinit;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) r = mfma(qh[t][ks], kt2[ks], r);
             if constexpr (PRE) {
-                r = mfma(ql[t][0], kta0, r);
 #pragma unroll
-                for (int ks = 1; ks < KS; ++ks) r = mfma(ql[t][ks], kt[ks], r);
+                for (int ks = 0; ks < KS; ++ks) r = mfma(ql[t][ks], kt[ks], r);
             }
             return r;
         };
@@ -315,15 +311,15 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
                 part = fmaf(acc[hv][7] * inv, bf16_hi(g1[1]), part);
             }
             part += __shfl_xor(part, 32);
-            // the stabiliser that was actually subtracted: -bf16(-mx), or b2 on the fma path
-            const float used = PRE ? -__uint_as_float(bbits << 16) : b2;
+            // the stabiliser that was actually subtracted
+            const float used = PRE ? mx : b2;
             if (n < N && hh == 0) {
                 lse_dec2[row] = used + log2f(den);
                 delta[row] = part;
             }
         } else if (n < N) {
             if (lse_dec2 && hh == 0) {   // optional saved statistic of the forward, natural log
-                const float used = PRE ? -__uint_as_float(bbits << 16) : b2;
+                const float used = PRE ? mx : b2;
                 lse_dec2[(size_t)bh * N + n] = (used + log2f(den)) * kLn2;
             }
 #pragma unroll
@@ -346,7 +342,8 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
 // Encode partials.  A workgroup has up to 4 waves; wave w works on latent group w % G (NB tiles
 // of 32 latents) and on every TG-th 32-token tile of the chunk, starting at tile w / G.  Per tile
 // and latent tile:
-//   S2^T - c = K . Q'^T  (rows = tokens, columns = latents; -c rides in slot 0 of the lo product),
+//   S2^T - c = K . Q'^T  (rows = tokens, columns = latents; -c rides in a k-step of its own:
+//   key side 1 in slot 0, query side -c in slot 0, so that every lo term of q' stays in),
 //   lazy online softmax: c moves only when a score exceeds it by more than kLazy (or on the
 //   first tile), then O is rescaled; 2^x, pack; O^T += Vaug^T . P^T, Vaug = [V | 1].
 // V^T is formed through a wave-private, double-buffered LDS tile (no workgroup barrier
@@ -365,11 +362,13 @@ constexpr int kVtStride = 36;   // uint16 per LDS row: 32 tokens + 4 pad (72 B, 
 // (ld_mul = log2 e when the array holds the forward's natural-log statistic).  When y_tok is given,
 // every wave also forms delta[n] = <dY_n, Y_n> from the rows it streams anyway (no branch in the
 // loop), and the waves of latent group 0 store it to delta_out for the two kernels that follow.
+// Those waves also record the smallest and largest lse_dec2 they met, ld_range[part] = (min, max),
+// from which bwd_plan_kernel decides which variant of the next two kernels may run.
 template <int D, int NB, int MINB, int MODE>
 __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const float *__restrict__ lse_dec2, float ld_mul, const bf16_t *__restrict__ y_tok,
-    float *__restrict__ delta_out,
+    float *__restrict__ delta_out, float *__restrict__ ld_range,
     float *__restrict__ m_part, float *__restrict__ l_part, float *__restrict__ o_part,
     TokStride ts, int H, int N, int M, int chunk_len, int parts, int G, int TG, float c2)
 {
@@ -399,8 +398,12 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         load_q_operand<D, true>(q + ((size_t)h * M + lat0 + 32 * b + l32) * D, hh, c2, false, qh[b], ql[b]);
-        if constexpr (MODE == 0) ql[b][0] = with_slot0(ql[b][0], keep0, 0u);   // slot 0 := -c = 0
     }
+    u32x4 wzero;
+    wzero[0] = 0u; wzero[1] = 0u; wzero[2] = 0u; wzero[3] = 0u;
+    bf16x8 caug[MODE == 0 ? NB : 1];             // query side of the stabiliser k-step: slot 0 := -c
+#pragma unroll
+    for (int b = 0; b < (MODE == 0 ? NB : 1); ++b) caug[b] = as_bf16x8(wzero);
 
     const bf16_t *kb = k + tok_base(ts, bh, H);
     const bf16_t *vb = v + tok_base(ts, bh, H);
@@ -410,6 +413,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     const int cnt = (tiles > tg) ? (tiles - tg + TG - 1) / TG : 0;   // tiles of this wave
 
     float c[NB];
+    float nl_min = INFINITY, nl_max = -INFINITY;   // range of -lse_dec2 over this wave's tokens (MODE 1)
     f32x16 o[NB][HV];
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
@@ -467,27 +471,22 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     u32x4 w23;
     w23[0] = 0u; w23[1] = hh == 0 ? 0x3f803f80u : 0u; w23[2] = 0u; w23[3] = 0u;
     const bf16x8 ones23 = as_bf16x8(w23);      // query side of the correction k-step: slots 2,3 = 1
-    // scores minus the stabiliser of latent tile b against the token tile (kk, kk0a = kk[0] with slot 0 := 1)
+    // scores minus the stabiliser of latent tile b against the token tile (kk; kk0a = key side of the correction k-step)
     auto qk = [&](int b, const bf16x8 (&kk)[KS], bf16x8 kk0a) {
         f32x16 r = splat16(0.f);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) r = mfma(kk[ks], qh[b][ks], r);
-        if constexpr (MODE == 0) {
-            r = mfma(kk0a, ql[b][0], r);
-        } else {
-            r = mfma(kk[0], ql[b][0], r);
-            r = mfma(kk0a, ones23, r);
-        }
 #pragma unroll
-        for (int ks = 1; ks < KS; ++ks) r = mfma(kk[ks], ql[b][ks], r);
+        for (int ks = 0; ks < KS; ++ks) r = mfma(kk[ks], ql[b][ks], r);
+        r = mfma(kk0a, MODE == 0 ? caug[MODE == 0 ? b : 0] : ones23, r);
         return r;
     };
     const uint32_t one0 = hh == 0 ? 0x3f80u : 0u;
     const float *lb = (MODE == 1) ? lse_dec2 + (size_t)bh * N : nullptr;
-    // MODE 0: key operand of the lo product with slot 0 := 1.  MODE 1: key operand of a separate
-    // correction k-step, zero except slots 2,3 := -lse_dec2 of this lane's token (hi + lo pair).
+    // Key operand of the correction k-step.  MODE 0: slot 0 := 1, else zero.  MODE 1: zero except
+    // slots 2,3 := -lse_dec2 of this lane's token (hi + lo pair).
     auto k_aug = [&](bf16x8 k0, float neg_lse) {
-        if constexpr (MODE == 0) return with_slot0(k0, keep0, one0);
+        if constexpr (MODE == 0) return with_slot0(as_bf16x8(wzero), keep0, one0);
         else {
             u32x4 w;
             w[0] = 0u; w[2] = 0u; w[3] = 0u;
@@ -592,7 +591,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
                             for (int i = 0; i < 16; ++i) o[b][hv][i] *= f;
                     }
                     c[b] = cn;
-                    ql[b][0] = with_slot0(ql[b][0], keep0, hh == 0 ? rne_bf16(-cn) : 0u);
+                    caug[b] = with_slot0(caug[b], keep0, hh == 0 ? rne_bf16(-cn) : 0u);
 #pragma unroll
                     for (int i = 0; i < 16; ++i) sc[i] -= shift;
                     if constexpr (NB == 1) {   // the product already in flight is for this same latent tile
@@ -611,6 +610,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
                 S[(b + 1) % NB] = nxt;
             }
             first = false;
+            if constexpr (MODE == 1) { nl_min = fminf(nl_min, nl); nl_max = fmaxf(nl_max, nl); }
             nl = nln;
             compiler_fence();
             read_va(buf_next, va);            // value operand of tile j+1 (written at the top of this iteration)
@@ -628,6 +628,17 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     // partial slot of this wave: (bh, chunk*TG + tg), latents lat0 .. lat0 + 32*NB
     if (tg >= TG) return;
     const size_t part = (size_t)bh * parts + (size_t)chunk * TG + tg;
+    if (MODE == 1 && ld_range != nullptr && g == 0) {
+#pragma unroll
+        for (int off = 1; off < 32; off <<= 1) {   // both lane halves hold the same tokens
+            nl_min = fminf(nl_min, __shfl_xor(nl_min, off));
+            nl_max = fmaxf(nl_max, __shfl_xor(nl_max, off));
+        }
+        if (lane == 0) {   // a wave without tiles leaves (+inf, -inf): neutral
+            ld_range[2 * part] = -nl_max;
+            ld_range[2 * part + 1] = -nl_min;
+        }
+    }
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         const size_t slot = part * M + lat0 + 32 * b + l32;
@@ -658,13 +669,21 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
 //     dQ^T[dd][m] += K^T[dd][n] dS^T[n][m]
 // with K^T read back from a wave-private, double-buffered LDS tile.  Masked tokens have both
 // exponents at -inf, so their dS is exactly zero.
+//
+// ONE = true is the variant with one exponential per score.  With kappa = max_m lse_enc2[m],
+//     R[n][m] = P[m][n] * u[m] * w[n],   u[m] = 2^(lse_enc2[m] - kappa),  w[n] = 2^(kappa - lse_dec2[n]),
+// so dS^T = P * (a + w[n] * u[m] c): u is folded into the Z operand (and multiplies delta in the
+// correction k-step), w[n] is a per-row factor that goes from the token's lane to the rows of
+// the accumulator layout through 128 bytes of LDS.  It is exact as long as u, w and P stay in
+// fp32 range wherever R matters, which bwd_plan_kernel guarantees per (b,h) (plan[bh] = 1);
+// otherwise the ONE = false variant runs.  Each variant returns at once when the plan names the other.
 // ============================================================================================
-template <int D, int NB, int MINB>
+template <int D, int NB, int MINB, bool ONE>
 __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const bf16_t *__restrict__ dy, const float *__restrict__ z, const float *__restrict__ lse_enc,
     const float *__restrict__ dz, const float *__restrict__ eps, const float *__restrict__ lse_dec2,
-    const float *__restrict__ delta, float ld_mul, float *__restrict__ dq_part,
+    const float *__restrict__ delta, float ld_mul, const int *__restrict__ plan, float *__restrict__ dq_part,
     TokStride ts, int H, int N, int M, int chunk_len, int parts, int G, int TG, float c2)
 {
     constexpr int KS = D / 16;
@@ -672,13 +691,23 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
     constexpr int ROWS = D + 1;                 // K^T rows, then a row of zeros
     constexpr int BUF = ROWS * kVtStride;
     __shared__ __attribute__((aligned(16))) uint16_t kt_all[4][2 * BUF];
+    __shared__ __attribute__((aligned(16))) float wl_all[ONE ? 4 : 1][2][32];   // w[n] of a token tile
 
     const int lane = threadIdx.x & 63, l32 = lane & 31, hh = lane >> 5;
     const int wave = threadIdx.x >> 6;
     const int g = wave % G, tg = wave / G;
     const int bh = blockIdx.y, h = bh % H, chunk = blockIdx.x;
+    if ((plan[bh] != 0) != ONE) return;         // the other variant owns this (b,h)
     const bool lower = hh == 0;
     uint16_t *lds = kt_all[wave];
+    float (*wl)[32] = wl_all[ONE ? wave : 0];
+    float kap = 0.f;
+    if constexpr (ONE) {
+        kap = -INFINITY;
+        for (int m = lane; m < M; m += 64) kap = fmaxf(kap, lse_enc[(size_t)bh * M + m] * kLog2e);
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) kap = fmaxf(kap, __shfl_xor(kap, off));
+    }
     if (lane < kVtStride) {
         lds[D * kVtStride + lane] = 0;
         lds[BUF + D * kVtStride + lane] = 0;
@@ -688,11 +717,21 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
     const int lat0 = 32 * NB * g;
     constexpr bool LO2 = (D == 16);             // carry lo terms of dZ and Z as well
     bf16x8 qh[NB][KS], ql[NB][KS], q_aug[NB], dzb[NB][KS], zb[NB][KS], dzl[NB][KS], zl[NB][KS], dz_aug[NB];
+    bf16x8 u_aug[ONE ? NB : 1];
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         const int m = lat0 + 32 * b + l32;
         load_q_operand<D, true>(q + ((size_t)h * M + m) * D, hh, c2, false, qh[b], ql[b]);
         const float le2 = lse_enc[(size_t)bh * M + m] * kLog2e;
+        const float um = ONE ? fast_exp2(le2 - kap) : 1.f;   // folded into Z
+        if constexpr (ONE) {
+            const uint32_t us = split_bf16_pair(um);          // slots 0,1,2 := u hi, u hi, u lo
+            u32x4 wu;
+            wu[0] = lower ? ((us & 0xffffu) | (us << 16)) : 0u;
+            wu[1] = lower ? (us >> 16) : 0u;
+            wu[2] = 0u; wu[3] = 0u;
+            u_aug[b] = as_bf16x8(wu);
+        }
         u32x4 wq;
         wq[0] = lower ? split_bf16_pair(-le2) : 0u;     // slots 0,1 := -lse_enc2 (hi + lo)
         wq[1] = lower ? 0x3f803f80u : 0u;               // slots 2,3 := 1
@@ -705,12 +744,13 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
             u32x4 wz, wd, wzl, wdl;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const uint32_t z0 = rne_bf16(zr[2 * i]), z1 = rne_bf16(zr[2 * i + 1]);
+                const float za = zr[2 * i] * um, zc = zr[2 * i + 1] * um;
+                const uint32_t z0 = rne_bf16(za), z1 = rne_bf16(zc);
                 const uint32_t d0 = rne_bf16(dr[2 * i]), d1 = rne_bf16(dr[2 * i + 1]);
                 wz[i] = z0 | (z1 << 16);
                 wd[i] = d0 | (d1 << 16);
-                wzl[i] = rne_bf16(zr[2 * i] - __uint_as_float(z0 << 16)) |
-                         (rne_bf16(zr[2 * i + 1] - __uint_as_float(z1 << 16)) << 16);
+                wzl[i] = rne_bf16(za - __uint_as_float(z0 << 16)) |
+                         (rne_bf16(zc - __uint_as_float(z1 << 16)) << 16);
                 wdl[i] = rne_bf16(dr[2 * i] - __uint_as_float(d0 << 16)) |
                          (rne_bf16(dr[2 * i + 1] - __uint_as_float(d1 << 16)) << 16);
             }
@@ -782,9 +822,19 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
             }
     };
 
+    // w[n] of a tile: written by the token's lane, read back as the 16 rows of this lane's registers
+    auto read_w = [&](const float *buf, float (&wr)[16]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float4 t = *reinterpret_cast<const float4 *>(buf + 8 * i + 4 * hh);
+            wr[4 * i] = t.x; wr[4 * i + 1] = t.y; wr[4 * i + 2] = t.z; wr[4 * i + 3] = t.w;
+        }
+    };
+
     if (cnt > 0) {
         bf16x8 kt[KS], ktn[KS], ktnn[KS], vt[KS], vtn[KS], gt[KS], gtn[KS], kT[HV][2];
         float nld, nldn, dl, dln;
+        float wrow[ONE ? 16 : 1];
         load_rows(kb, 0, kt);
         load_rows(kb, 1, ktn);
         load_rows(vb, 0, vt);
@@ -793,8 +843,10 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
         dl = db[min(tile_tok0(0) + l32, N - 1)];
         compiler_fence();
         write_kt(kt, lds);
+        if constexpr (ONE) wl[0][l32] = fast_exp2(kap + nld);
         compiler_fence();
         read_kT(lds, kT);
+        if constexpr (ONE) read_w(wl[0], wrow);
 
         for (int j = 0; j < cnt; ++j) {
             const int tok0 = tile_tok0(j);
@@ -806,6 +858,7 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
             dln = db[min(tile_tok0(j + 1) + l32, N - 1)];
             compiler_fence();
             write_kt(ktn, buf_next);
+            if constexpr (ONE) wl[(j + 1) & 1][l32] = fast_exp2(kap + nldn);
             compiler_fence();
 
             // token-side operands of the correction k-steps (zero outside the named slots)
@@ -814,8 +867,10 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
             wb[1] = lower ? split_bf16_pair(nld) : 0u;           // slots 2,3 := -lse_dec2[n]
             const bf16x8 kt_a = ones_aug, kt_b = as_bf16x8(wb);  // slots 0,1 := 1 picks -lse_enc2
             u32x4 wg;
-            wg[0] = lower ? split_bf16_pair(-dl) : 0u;
-            wg[1] = 0u; wg[2] = 0u; wg[3] = 0u;
+            const uint32_t ds_ = split_bf16_pair(-dl);
+            wg[0] = lower ? ds_ : 0u;
+            wg[1] = (ONE && lower) ? (ds_ & 0xffffu) : 0u;       // ONE: slots 0,1,2 := -delta hi, lo, hi
+            wg[2] = 0u; wg[3] = 0u;
             const bf16x8 g_aug = as_bf16x8(wg);
 
             const int rem = n1 - tok0 - 4 * hh;
@@ -828,9 +883,10 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) x = mfma(kt[ks], ql[b][ks], x);
                 f32x16 s1 = mfma(kt_a, q_aug[b], x);
-                f32x16 s2 = mfma(kt_b, q_aug[b], x);
+                f32x16 s2 = s1;
+                if constexpr (!ONE) s2 = mfma(kt_b, q_aug[b], x);
                 f32x16 av = mfma(ones_aug, dz_aug[b], splat16(0.f));
-                f32x16 cv = mfma(g_aug, ones_aug, splat16(0.f));
+                f32x16 cv = mfma(g_aug, ONE ? u_aug[ONE ? b : 0] : ones_aug, splat16(0.f));
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
                     av = mfma(vt[ks], dzb[b][ks], av);
@@ -846,8 +902,13 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
                         if (8 * (r / 4) + (r % 4) >= rem) { s1[r] = -INFINITY; s2[r] = -INFINITY; }
                 }
                 f32x16 ds;
+                if constexpr (ONE) {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) ds[i] = fmaf(fast_exp2(s2[i]), cv[i], fast_exp2(s1[i]) * av[i]);
+                    for (int i = 0; i < 16; ++i) ds[i] = fast_exp2(s1[i]) * fmaf(cv[i], wrow[i], av[i]);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) ds[i] = fmaf(fast_exp2(s2[i]), cv[i], fast_exp2(s1[i]) * av[i]);
+                }
                 u32x4 w0, w1;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
@@ -862,6 +923,7 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
             }
             compiler_fence();
             read_kT(buf_next, kT);
+            if constexpr (ONE) read_w(wl[(j + 1) & 1], wrow);
 #pragma unroll
             for (int s = 0; s < KS; ++s) { kt[s] = ktn[s]; ktn[s] = ktnn[s]; vt[s] = vtn[s]; gt[s] = gtn[s]; }
             nld = nldn;
@@ -897,14 +959,17 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
 //   acc2 += RW2 . dS' (rows 0-15: (sum_m dS' q_m)^T)
 // and at the end  dV = acc1[0:16],  dK = scale * (acc2[0:16] + acc1[16:32]).
 // LO2: also carry lo terms of dZ and Z (more accurate a and c; needs more LDS).
+// ONE: one exponential per score, as in the dQ kernel: R = P u[m] w[n]; u is folded into the Z images
+// (and into slots 4-6 of the correction image, against -delta in the token operand), w[n] is a
+// per-lane scalar here, and dS' = P (a + w c).  Runs only where plan[bh] = 1.
 // ============================================================================================
-template <int D, int MT, bool LO2>
+template <int D, int MT, bool LO2, bool ONE>
 __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const bf16_t *__restrict__ dy, const float *__restrict__ z, const float *__restrict__ lse_enc,
     const float *__restrict__ dz, const float *__restrict__ eps, const float *__restrict__ lse_dec2,
-    const float *__restrict__ delta, float ld_mul, bf16_t *__restrict__ dk, bf16_t *__restrict__ dv,
-    TokStride ts, int H, int N, float c2, float scale)
+    const float *__restrict__ delta, float ld_mul, const int *__restrict__ plan, bf16_t *__restrict__ dk,
+    bf16_t *__restrict__ dv, TokStride ts, int H, int N, float c2, float scale)
 {
     constexpr int KS = D / 16;
     constexpr int HV = D / 16;
@@ -920,6 +985,14 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     const int wave = tid >> 6;
     const int bh = blockIdx.y, h = bh % H;
     const bool lower = hh == 0;
+    if ((plan[bh] != 0) != ONE) return;         // the other variant owns this (b,h); uniform over the workgroup
+    float kap = 0.f;
+    if constexpr (ONE) {
+        kap = -INFINITY;
+        for (int m = lane; m < M; m += 64) kap = fmaxf(kap, lse_enc[(size_t)bh * M + m] * kLog2e);
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) kap = fmaxf(kap, __shfl_xor(kap, off));
+    }
 
     // ---- build the operand images ----
     {
@@ -934,9 +1007,15 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
             u32x4 w;
             if (sid == NA - 1) {
                 // correction operand: slots 0,1 = -lse_enc2 (hi + lo pair), slots 2,3 = 1, else zero
-                w[0] = hf == 0 ? split_bf16_pair(-leb[32 * t + r32] * kLog2e) : 0u;
+                const float le2 = leb[32 * t + r32] * kLog2e;
+                w[0] = hf == 0 ? split_bf16_pair(-le2) : 0u;
                 w[1] = hf == 0 ? 0x3f803f80u : 0u;
                 w[2] = 0u; w[3] = 0u;
+                if constexpr (ONE) {   // slots 4,5,6 := u hi, u hi, u lo
+                    const uint32_t us = split_bf16_pair(fast_exp2(le2 - kap));
+                    w[2] = hf == 0 ? ((us & 0xffffu) | (us << 16)) : 0u;
+                    w[3] = hf == 0 ? (us >> 16) : 0u;
+                }
             } else if (sid < NA) {
                 const int kind = sid / KS, ks = sid % KS;          // 0 qh, 1 ql, 2 dzh, 3 zh, 4 dzl, 5 zl
                 const int m = 32 * t + r32;
@@ -947,9 +1026,11 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
 #pragma unroll
                     for (int i = 0; i < 4; ++i) { x[2 * i] = bf16_lo(raw[i]) * c2; x[2 * i + 1] = bf16_hi(raw[i]) * c2; }
                 } else {
-                    const float *src = ((kind == 2 || kind == 4) ? dzb : zb) + (size_t)m * D + d0;
+                    const bool is_z = (kind == 3 || kind == 5);
+                    const float *src = (is_z ? zb : dzb) + (size_t)m * D + d0;
+                    const float um = (ONE && is_z) ? fast_exp2(leb[m] * kLog2e - kap) : 1.f;
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) x[i] = src[i];
+                    for (int i = 0; i < 8; ++i) x[i] = src[i] * um;
                 }
                 const bool want_lo = (kind == 1 || kind >= 4);
 #pragma unroll
@@ -1021,14 +1102,18 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
         load_cols(gb, tn, gtn);
         const size_t row = (size_t)min(n, N - 1);
         const float nld = -lb[row] * ld_mul, dl = db[row];
+        const float wn = ONE ? fast_exp2(kap + nld) : 0.f;
 
         u32x4 wb;
         wb[0] = 0u; wb[2] = 0u; wb[3] = 0u;
         wb[1] = lower ? split_bf16_pair(nld) : 0u;           // slots 2,3 := -lse_dec2[n]
         const bf16x8 kt_a = ones_aug, kt_b = as_bf16x8(wb);  // slots 0,1 := 1 picks -lse_enc2
         u32x4 wg;
-        wg[0] = lower ? split_bf16_pair(-dl) : 0u;
-        wg[1] = 0u; wg[2] = 0u; wg[3] = 0u;
+        const uint32_t ds_ = split_bf16_pair(-dl);
+        wg[0] = (!ONE && lower) ? ds_ : 0u;                  // two exponentials: slots 0,1 := -delta (hi, lo)
+        wg[1] = 0u;
+        wg[2] = (ONE && lower) ? ds_ : 0u;                   // one: slots 4,5,6 := -delta hi, lo, hi
+        wg[3] = (ONE && lower) ? (ds_ & 0xffffu) : 0u;
         const bf16x8 g_aug = as_bf16x8(wg);
 
         f32x16 acc1[HV], acc2[HV];
@@ -1044,7 +1129,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
             for (int ks = 0; ks < KS; ++ks) x = mfma(image(t, 1 * KS + ks), kt[ks], x);
             const bf16x8 qa = image(t, NA - 1);
             s1 = mfma(qa, kt_a, x);
-            s2 = mfma(qa, kt_b, x);
+            if constexpr (!ONE) s2 = mfma(qa, kt_b, x);
         };
         // One latent tile, software-pipelined: the a and c products of tile t and the score products
         // of tile t+1 are issued first and run on the matrix cores while the vector ALUs
@@ -1052,7 +1137,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
         auto tile_step = [&](int t, f32x16 &s1, f32x16 &s2, f32x16 &s1n, f32x16 &s2n) {
             if constexpr (!PIPE) scores(t, s1, s2);   // not enough registers at d = 32: no look-ahead
             f32x16 av = splat16(0.f);
-            f32x16 cv = mfma(ones_aug, g_aug, splat16(0.f));
+            f32x16 cv = mfma(ONE ? image(t, NA - 1) : ones_aug, g_aug, splat16(0.f));
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 av = mfma(image(t, 2 * KS + ks), vt[ks], av);
@@ -1071,16 +1156,18 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
             sched_fence();
             f32x16 pv, rv;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) { pv[i] = fast_exp2(s1[i]); rv[i] = fast_exp2(s2[i]); }
+            for (int i = 0; i < 16; ++i) {
+                pv[i] = fast_exp2(s1[i]);
+                if constexpr (ONE) rv[i] = pv[i] * fmaf(cv[i], wn, av[i]);     // dS' = P (a + w[n] u[m] c)
+                else rv[i] = fmaf(fast_exp2(s2[i]), cv[i], pv[i] * av[i]);     // dS' = P a + R c
+            }
             u32x4 p0, p1, d0, d1;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 p0[i] = cvt_pk_bf16(pv[2 * i], pv[2 * i + 1]);
                 p1[i] = cvt_pk_bf16(pv[8 + 2 * i], pv[8 + 2 * i + 1]);
-                d0[i] = cvt_pk_bf16(fmaf(rv[2 * i], cv[2 * i], pv[2 * i] * av[2 * i]),
-                                    fmaf(rv[2 * i + 1], cv[2 * i + 1], pv[2 * i + 1] * av[2 * i + 1]));
-                d1[i] = cvt_pk_bf16(fmaf(rv[8 + 2 * i], cv[8 + 2 * i], pv[8 + 2 * i] * av[8 + 2 * i]),
-                                    fmaf(rv[8 + 2 * i + 1], cv[8 + 2 * i + 1], pv[8 + 2 * i + 1] * av[8 + 2 * i + 1]));
+                d0[i] = cvt_pk_bf16(rv[2 * i], rv[2 * i + 1]);
+                d1[i] = cvt_pk_bf16(rv[8 + 2 * i], rv[8 + 2 * i + 1]);
             }
 #pragma unroll
             for (int hv = 0; hv < HV; ++hv) {
@@ -1197,7 +1284,7 @@ int mfma_encode(const flare_shape &s, const void *q, const void *k, const void *
     {
         LaunchTimer t(KID_ENCODE_PARTIAL, stream);
 #define FLARE_ENC(DD, NBB)                                                                                   \
-    encode_mfma_kernel<DD, NBB, 2, 0><<<grid, e.threads, 0, stream>>>(qq, kk, vv, nullptr, 1.f, nullptr, nullptr, m_part, l_part, o_part, \
+    encode_mfma_kernel<DD, NBB, 2, 0><<<grid, e.threads, 0, stream>>>(qq, kk, vv, nullptr, 1.f, nullptr, nullptr, nullptr, m_part, l_part, o_part, \
                                                                       tok_stride(s), s.H, s.N, s.M, p.enc.chunk_len, p.parts, e.G, \
                                                                       e.TG, c2)
         if (s.d == 16 && e.NB == 1) FLARE_ENC(16, 1);
@@ -1213,7 +1300,8 @@ int mfma_encode(const flare_shape &s, const void *q, const void *k, const void *
 
 // dZ partials of the backward (the encode machinery with values dY and weights R^T)
 int mfma_dz_partial(const flare_shape &s, const void *q, const void *k, const void *dy, const float *lse_dec2,
-                    float ld_mul, const void *y, float *delta_out, float *dz_part, float scale, hipStream_t stream)
+                    float ld_mul, const void *y, float *delta_out, float *ld_range, float *dz_part, float scale,
+                    hipStream_t stream)
 {
     const MfmaPlan p = mfma_plan(s);
     const EncGeom e = enc_geom(s.M, s.d);
@@ -1223,7 +1311,7 @@ int mfma_dz_partial(const flare_shape &s, const void *q, const void *k, const vo
     const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *gg = (const bf16_t *)dy;
     LaunchTimer t(KID_BWD_DZ_PARTIAL, stream);
 #define FLARE_DZ(DD, NBB)                                                                                      \
-    encode_mfma_kernel<DD, NBB, 2, 1><<<grid, e.threads, 0, stream>>>(qq, kk, gg, lse_dec2, ld_mul, (const bf16_t *)y, delta_out, nullptr, nullptr, dz_part, \
+    encode_mfma_kernel<DD, NBB, 2, 1><<<grid, e.threads, 0, stream>>>(qq, kk, gg, lse_dec2, ld_mul, (const bf16_t *)y, delta_out, ld_range, nullptr, nullptr, dz_part, \
                                                                       tok_stride(s), s.H, s.N, s.M, p.enc.chunk_len, p.parts, e.G,  \
                                                                       e.TG, c2)
     if (s.d == 16 && e.NB == 1) FLARE_DZ(16, 1);
@@ -1238,8 +1326,8 @@ int mfma_dz_partial(const flare_shape &s, const void *q, const void *k, const vo
 // dQ partials of the backward; slot layout as the encode partials: [(b*h) * parts + part][M][d]
 int mfma_dq_partial(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy,
                     const float *z, const float *lse_enc, const float *dz, const float *eps,
-                    const float *lse_dec2, const float *delta, float ld_mul, float *dq_part, float scale,
-                    hipStream_t stream)
+                    const float *lse_dec2, const float *delta, float ld_mul, const int *plan, bool one_exp,
+                    float *dq_part, float scale, hipStream_t stream)
 {
     const MfmaPlan p = mfma_plan(s);
     EncGeom e = enc_geom(s.M, s.d);
@@ -1254,11 +1342,18 @@ int mfma_dq_partial(const flare_shape &s, const void *q, const void *k, const vo
     const int parts = p.enc.chunks * e.TG;
     const dim3 grid(p.enc.chunks, BH);
     const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *vv = (const bf16_t *)v, *gg = (const bf16_t *)dy;
-    LaunchTimer t(KID_BWD_DQ_PARTIAL, stream);
-#define FLARE_DQ(DD, NBB, MINB)                                                                                 \
-    bwd_dq_mfma_kernel<DD, NBB, MINB><<<grid, e.threads, 0, stream>>>(qq, kk, vv, gg, z, lse_enc, dz, eps, lse_dec2, \
-                                                                      delta, ld_mul, dq_part, tok_stride(s), s.H, s.N, s.M, \
-                                                                      p.enc.chunk_len, parts, e.G, e.TG, c2)
+    LaunchTimer t(one_exp ? KID_BWD_DQ_PARTIAL : KID_BWD_DQ_PARTIAL_2EXP, stream);
+#define FLARE_DQ(DD, NBB, MINB)                                                                                  \
+    do {                                                                                                         \
+        if (one_exp)                                                                                             \
+            bwd_dq_mfma_kernel<DD, NBB, MINB, true><<<grid, e.threads, 0, stream>>>(                             \
+                qq, kk, vv, gg, z, lse_enc, dz, eps, lse_dec2, delta, ld_mul, plan, dq_part, tok_stride(s), s.H, \
+                s.N, s.M, p.enc.chunk_len, parts, e.G, e.TG, c2);                                                \
+        else                                                                                                     \
+            bwd_dq_mfma_kernel<DD, NBB, MINB, false><<<grid, e.threads, 0, stream>>>(                            \
+                qq, kk, vv, gg, z, lse_enc, dz, eps, lse_dec2, delta, ld_mul, plan, dq_part, tok_stride(s), s.H, \
+                s.N, s.M, p.enc.chunk_len, parts, e.G, e.TG, c2);                                                \
+    } while (0)
     if (s.d == 16 && e.NB == 1) FLARE_DQ(16, 1, 2);
     else if (s.d == 16) FLARE_DQ(16, 2, 2);
     else if (e.NB == 1) FLARE_DQ(32, 1, 2);
@@ -1278,7 +1373,7 @@ bool mfma_dkdv_supported(const flare_shape &s)
 
 int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy, const float *z,
               const float *lse_enc, const float *dz, const float *eps, const float *lse_dec2, const float *delta,
-              float ld_mul, void *dk, void *dv, float scale, hipStream_t stream)
+              float ld_mul, const int *plan, bool one_exp, void *dk, void *dv, float scale, hipStream_t stream)
 {
     const int BH = s.B * s.H;
     const int tiles = (s.N + 31) / 32;
@@ -1291,15 +1386,15 @@ int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v,
     const int KS = s.d / 16, HV = s.d / 16;
     const size_t lds = (size_t)MT * ((lo2 ? 6 : 4) * KS + 1 + 4 * HV) * 1024;
     const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *vv = (const bf16_t *)v, *gg = (const bf16_t *)dy;
-    LaunchTimer t(KID_BWD_DKDV, stream);
+    LaunchTimer t(one_exp ? KID_BWD_DKDV : KID_BWD_DKDV_2EXP, stream);
 #define FLARE_DKDV(DD, MTT, LO)                                                                                  \
     do {                                                                                                         \
-        auto kern = bwd_dkdv_mfma_kernel<DD, MTT, LO>;                                                           \
+        auto kern = one_exp ? bwd_dkdv_mfma_kernel<DD, MTT, LO, true> : bwd_dkdv_mfma_kernel<DD, MTT, LO, false>; \
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
                                 (int)lds) != hipSuccess)                                                         \
             return FLARE_ELAUNCH;                                                                                \
-        kern<<<grid, 512, lds, stream>>>(qq, kk, vv, gg, z, lse_enc, dz, eps, lse_dec2, delta, ld_mul, (bf16_t *)dk, \
-                                         (bf16_t *)dv, tok_stride(s), s.H, s.N, c2, scale);                      \
+        kern<<<grid, 512, lds, stream>>>(qq, kk, vv, gg, z, lse_enc, dz, eps, lse_dec2, delta, ld_mul, plan,     \
+                                         (bf16_t *)dk, (bf16_t *)dv, tok_stride(s), s.H, s.N, c2, scale);        \
     } while (0)
     if (s.d == 16) {
         switch (MT) {
@@ -1319,6 +1414,63 @@ int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v,
         }
     }
 #undef FLARE_DKDV
+    return check_launch();
+}
+
+// Which variant of the dQ and dK/dV kernels may run for a (b,h): plan[bh] = 1 (one exponential per
+// score) iff, with kappa = max_m lse_enc2[m], every u[m] = 2^(lse_enc2[m] - kappa) >= 2^-kPlanSpan and
+// every w[n] = 2^(kappa - lse_dec2[n]) lies in [2^-kPlanSpan, 2^kPlanSpan].  Then wherever
+// R = P u w is above 2^-(126 - 2 kPlanSpan), P is a normal fp32 number and nothing is lost; anything
+// else (wide score ranges, non-finite statistics) takes the two-exponential kernels.
+constexpr float kPlanSpan = 50.f;
+namespace {
+__global__ __launch_bounds__(256) void bwd_plan_kernel(const float *__restrict__ ld_range,
+                                                       const float *__restrict__ lse_enc, int *__restrict__ plan,
+                                                       int parts, int M, int force_two)
+{
+    __shared__ float red[4][4];
+    const int bh = blockIdx.x, tid = threadIdx.x;
+    float le_min = INFINITY, le_max = -INFINITY, ld_min = INFINITY, ld_max = -INFINITY;
+    for (int m = tid; m < M; m += 256) {
+        const float v = lse_enc[(size_t)bh * M + m] * kLog2e;
+        le_min = fminf(le_min, v);
+        le_max = fmaxf(le_max, v);
+    }
+    for (int p = tid; p < parts; p += 256) {
+        ld_min = fminf(ld_min, ld_range[2 * ((size_t)bh * parts + p)]);
+        ld_max = fmaxf(ld_max, ld_range[2 * ((size_t)bh * parts + p) + 1]);
+    }
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        le_min = fminf(le_min, __shfl_xor(le_min, off));
+        le_max = fmaxf(le_max, __shfl_xor(le_max, off));
+        ld_min = fminf(ld_min, __shfl_xor(ld_min, off));
+        ld_max = fmaxf(ld_max, __shfl_xor(ld_max, off));
+    }
+    if ((tid & 63) == 0) {
+        red[tid >> 6][0] = le_min; red[tid >> 6][1] = le_max;
+        red[tid >> 6][2] = ld_min; red[tid >> 6][3] = ld_max;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < 4; ++w) {
+            le_min = fminf(le_min, red[w][0]); le_max = fmaxf(le_max, red[w][1]);
+            ld_min = fminf(ld_min, red[w][2]); ld_max = fmaxf(ld_max, red[w][3]);
+        }
+        // written so that a NaN anywhere makes the test fail
+        const bool ok = (le_max - le_min <= kPlanSpan) && (le_max - ld_min <= kPlanSpan) &&
+                        (ld_max - le_max <= kPlanSpan) && fabsf(le_max) < 1e30f;
+        plan[bh] = (ok && !force_two) ? 1 : 0;
+    }
+}
+}  // namespace
+
+int mfma_bwd_plan(const flare_shape &s, const float *ld_range, const float *lse_enc, int *plan, bool force_two,
+                  hipStream_t stream)
+{
+    LaunchTimer t(KID_BWD_PLAN, stream);
+    bwd_plan_kernel<<<s.B * s.H, 256, 0, stream>>>(ld_range, lse_enc, plan, mfma_plan(s).parts, s.M,
+                                                   force_two ? 1 : 0);
     return check_launch();
 }
 

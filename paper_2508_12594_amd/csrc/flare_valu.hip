@@ -13,6 +13,8 @@
 //
 // Equations: Section 3.1, Eq. flare_encode / Eq. flare_decode; Appendix E per-latent and
 // per-token forms.  The backward follows the formulas in include/flare.h.
+#include <stdlib.h>
+
 #include "flare_internal.h"
 
 namespace flare {
@@ -523,7 +525,7 @@ __global__ __launch_bounds__(kTokenBlock) void dkdv_kernel(
 // ---- workspace carving --------------------------------------------------------------------
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-struct BwdWs { float *lse_dec2, *delta, *part, *dz, *eps; };
+struct BwdWs { float *lse_dec2, *delta, *part, *dz, *eps, *ld_range; int *plan; };
 
 // `slots` = partial slots per (b,h) the shared partial buffer must hold
 size_t bwd_layout(const flare_shape &s, int slots, void *ws, BwdWs *out)
@@ -541,10 +543,22 @@ size_t bwd_layout(const flare_shape &s, int slots, void *ws, BwdWs *out)
     off += align256(BH * s.M * s.d * 4);
     if (out) out->eps = reinterpret_cast<float *>(base + off);
     off += align256(BH * s.M * 4);
+    if (out) out->ld_range = reinterpret_cast<float *>(base + off);
+    off += align256(BH * slots * 2 * 4);
+    if (out) out->plan = reinterpret_cast<int *>(base + off);
+    off += align256(BH * 4);
     return off;
 }
 
 inline int check_launch() { return hipGetLastError() == hipSuccess ? FLARE_OK : FLARE_ELAUNCH; }
+
+// FLARE_BWD_TWO_EXP=1 in the environment sends every (b,h) to the two-exponential kernels (a
+// switch for tests and measurements; read at every call).
+inline bool force_two_exp()
+{
+    const char *e = getenv("FLARE_BWD_TWO_EXP");
+    return e != nullptr && e[0] != '\0' && e[0] != '0';
+}
 
 inline int bwd_slots(const flare_shape &s, const ValuPlan &plan)
 {
@@ -623,8 +637,10 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     }
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     if (mf) {
-        const int rc = mfma_dz_partial(s, q, k, dy, ld, ld_mul, fused ? y : nullptr, fused ? w.delta : nullptr,
-                                       w.part, scale, stream);
+        int rc = mfma_dz_partial(s, q, k, dy, ld, ld_mul, fused ? y : nullptr, fused ? w.delta : nullptr,
+                                 w.ld_range, w.part, scale, stream);
+        if (rc != FLARE_OK) return rc;
+        rc = mfma_bwd_plan(s, w.ld_range, lse_enc, w.plan, force_two_exp(), stream);
         if (rc != FLARE_OK) return rc;
     } else {
         {
@@ -643,9 +659,11 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     int dq_parts = plan.bwd.chunks;
     if (mf) {
         dq_parts = mfma_dq_parts(s);
-        const int rc = mfma_dq_partial(s, q, k, v, dy, z, lse_enc, w.dz, w.eps, ld, w.delta, ld_mul, w.part, scale,
-                                       stream);
-        if (rc != FLARE_OK) return rc;
+        for (int one = 1; one >= 0; --one) {   // each (b,h) slice is computed by exactly one of the two
+            const int rc = mfma_dq_partial(s, q, k, v, dy, z, lse_enc, w.dz, w.eps, ld, w.delta, ld_mul, w.plan,
+                                           one != 0, w.part, scale, stream);
+            if (rc != FLARE_OK) return rc;
+        }
     } else {
         LaunchTimer t(KID_BWD_DQ_PARTIAL, stream);
         dq_partial_kernel<T, D><<<lat_grid, kLatentBlock, 0, stream>>>(q, k, v, dy, z, lse_enc, w.dz, w.eps,
@@ -658,8 +676,14 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
         dq_reduce_kernel<D><<<dim3((s.M + 15) / 16, s.H), 256, 0, stream>>>(w.part, dq, s.B, s.H, s.M, dq_parts, scale);
     }
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
-    if (mf && mfma_dkdv_supported(s))
-        return mfma_dkdv(s, q, k, v, dy, z, lse_enc, w.dz, w.eps, ld, w.delta, ld_mul, dk, dv, scale, stream);
+    if (mf && mfma_dkdv_supported(s)) {
+        for (int one = 1; one >= 0; --one) {
+            const int rc = mfma_dkdv(s, q, k, v, dy, z, lse_enc, w.dz, w.eps, ld, w.delta, ld_mul, w.plan, one != 0,
+                                     dk, dv, scale, stream);
+            if (rc != FLARE_OK) return rc;
+        }
+        return FLARE_OK;
+    }
     {
         LaunchTimer t(KID_BWD_DKDV, stream);
         dkdv_kernel<T, D><<<tok_grid, kTokenBlock, 0, stream>>>(q, k, v, dy, z, lse_enc, w.dz, w.eps, w.lse_dec2,
