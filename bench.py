@@ -43,9 +43,11 @@ def algorithmic_bytes(kernel, B, H, N, M, d, elem):
         "decode": 2 * row,                      # k in, y out
         "bwd_token_stats": 2 * row + 8,         # k, dy in; lse_dec, delta out
         "bwd_prep": 2 * row + 12,               # y, dy, lse_dec in; lse_dec2, delta out
-        "bwd_dz_partial": 2 * row + 4,          # k, dy, lse_dec in
+        "bwd_dz_partial": 3 * row + 8,          # k, dy, y, lse_dec in; delta out (saved-statistics path)
         "bwd_dq_partial": 3 * row + 8,          # k, v, dy, lse_dec, delta in
         "bwd_dkdv": 5 * row + 8,                # k, v, dy in; dk, dv out
+        "bwd_dq_partial_2exp": 3 * row + 8,
+        "bwd_dkdv_2exp": 5 * row + 8,
         "bwd_pass_a": 2 * row + 8,
         "bwd_pass_b": 5 * row + 8,
     }
@@ -55,9 +57,12 @@ def algorithmic_bytes(kernel, B, H, N, M, d, elem):
 
 
 def exponentials(kernel, B, H, N, M):
-    """v_exp_f32 lane-operations one launch of `kernel` cannot avoid (one per score and softmax)."""
+    """v_exp_f32 lane-operations one launch of `kernel` cannot avoid: one per score.  (The last two
+    backward kernels need both softmax weights of a score, but the second follows from the first by
+    a multiplication, R = P * 2^(lse_enc2[m] - lse_dec2[n]); their two-exponential fall-backs are
+    priced at two.)"""
     per_pair = {"encode_partial": 1, "decode": 1, "bwd_token_stats": 1, "bwd_dz_partial": 1,
-                "bwd_dq_partial": 2, "bwd_dkdv": 2}
+                "bwd_dq_partial": 1, "bwd_dkdv": 1, "bwd_dq_partial_2exp": 2, "bwd_dkdv_2exp": 2}
     return per_pair.get(kernel, 0) * B * H * N * M
 
 
@@ -66,11 +71,11 @@ def exponentials(kernel, B, H, N, M):
 # plain 256 MB device copy in the same run (FETCH_SIZE x 2.00, WRITE_SIZE x 1.00); see
 # profiles/forward_backward_cfg4_hbm_traffic.md.
 MEASURED_TRAFFIC_CFG4 = {
-    "encode_partial": (250582 * 2.0 * 1024, 18432 * 1024),
-    "decode": (125887 * 2.0 * 1024, 250000 * 1024),
-    "bwd_dz_partial": (266225 * 2.0 * 1024, 16384 * 1024),
-    "bwd_dq_partial": (408100 * 2.0 * 1024, 8192 * 1024),
-    "bwd_dkdv": (407639 * 2.0 * 1024, 500000 * 1024),
+    "encode_partial": (250585 * 2.0 * 1024, 18432 * 1024),
+    "decode": (125889 * 2.0 * 1024, 281250 * 1024),
+    "bwd_dz_partial": (391527 * 2.0 * 1024, 47712 * 1024),
+    "bwd_dq_partial": (408103 * 2.0 * 1024, 8192 * 1024),
+    "bwd_dkdv": (407652 * 2.0 * 1024, 500000 * 1024),
 }
 
 
