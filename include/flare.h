@@ -25,7 +25,8 @@
  *     Two calls that share a workspace must be ordered on the same stream.
  *   - Return value: FLARE_OK (0) or a negative flare_status.  Nothing is launched when an
  *     argument check fails.  A launch failure reported by the HIP runtime gives FLARE_ELAUNCH.
- *   - Supported shapes: B,H,N,M >= 1 with B*H <= 65535; d in {4, 8, 16, 32}; dtype f32 or bf16;
+ *   - Supported shapes: B,H,N,M >= 1 with B*H <= 65535, N < 2^24 and N times the token stride in
+ *     elements (d, or H*d for FLARE_BNHD) below 2^32; d in {4, 8, 16, 32}; dtype f32 or bf16;
  *     either flare_layout for the token tensors (every "[B][H][N][d]" below reads [B][N][H][d]
  *     when shape->layout is FLARE_BNHD; the per-token statistic lse_dec is [B][H][N] always).
  *     Shapes with dtype bf16, d in {16,32} and M = 32 or a multiple of 64 up to 256 run on the

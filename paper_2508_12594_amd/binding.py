@@ -40,9 +40,10 @@ def load():
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(LIB_PATH):
-        raise FlareError("libflare.so not found at %s: run `python -m paper_2508_12594_amd.build`" % LIB_PATH)
-    lib = ctypes.CDLL(LIB_PATH)
+    path = os.environ.get("FLARE_LIB_PATH") or LIB_PATH    # another build of the library, for A/B timing
+    if not os.path.exists(path):
+        raise FlareError("libflare.so not found at %s: run `python -m paper_2508_12594_amd.build`" % path)
+    lib = ctypes.CDLL(path)
     vp, fp, sp = ctypes.c_void_p, ctypes.c_void_p, ctypes.POINTER(FlareShape)
     lib.flare_version.restype = ctypes.c_int
     lib.flare_strerror.restype = ctypes.c_char_p

@@ -65,6 +65,9 @@ int check_shape(const flare_shape *s)
     if (s->layout != FLARE_BHND && s->layout != FLARE_BNHD) return FLARE_EUNSUPPORTED;
     if (s->d != 4 && s->d != 8 && s->d != 16 && s->d != 32) return FLARE_EUNSUPPORTED;
     if ((long long)s->B * s->H > 65535) return FLARE_EUNSUPPORTED;
+    // token rows are addressed with a 24-bit multiply (tok_off)
+    const long long sn = (s->layout == FLARE_BNHD) ? (long long)s->H * s->d : s->d;
+    if (s->N >= (1 << 24) || sn >= (1 << 24) || (long long)s->N * sn >= (1LL << 32)) return FLARE_EUNSUPPORTED;
     return FLARE_OK;
 }
 

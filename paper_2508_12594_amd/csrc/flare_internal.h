@@ -56,6 +56,12 @@ __device__ __forceinline__ size_t tok_base(const TokStride &t, int bh, int H)
 {
     return (size_t)(bh / H) * (size_t)t.sb + (size_t)(bh % H) * (size_t)t.sh;
 }
+// Offset of token n's row inside its (b,h) slice.  A full-rate 24-bit multiply: the entry points
+// admit only shapes with N < 2^24 and N * sn < 2^32 (see check_shape).
+__device__ __forceinline__ size_t tok_off(const TokStride &t, int n)
+{
+    return (size_t)__umul24((unsigned)n, (unsigned)t.sn);
+}
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;

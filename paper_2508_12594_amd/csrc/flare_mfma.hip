@@ -215,7 +215,7 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
         const int nld = min(tile * 32 + l32, N - 1);
 #pragma unroll
         for (int s = 0; s < KS; ++s)
-            kt[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(kb + (size_t)nld * ts.sn + (D / 2) * hh + 8 * s));
+            kt[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(kb + tok_off(ts, nld) + (D / 2) * hh + 8 * s));
     }
     for (; tile < tiles; tile += stride) {
         const int n = tile * 32 + l32;
@@ -224,7 +224,7 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
             const int nld = min(tn * 32 + l32, N - 1);
 #pragma unroll
             for (int s = 0; s < KS; ++s)
-                ktn[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(kb + (size_t)nld * ts.sn + (D / 2) * hh + 8 * s));
+                ktn[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(kb + tok_off(ts, nld) + (D / 2) * hh + 8 * s));
         }
         auto qk_hi = [&](int t) {
             f32x16 r = splat16(0.f);
@@ -295,7 +295,7 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
         const float inv = 1.f / den;
         if constexpr (MODE == 1) {
             const size_t row = (size_t)bh * N + min(n, N - 1);
-            const bf16_t *gr = dy + tok_base(ts, bh, H) + (size_t)min(n, N - 1) * ts.sn;
+            const bf16_t *gr = dy + tok_base(ts, bh, H) + tok_off(ts, min(n, N - 1));
             float part = 0.f;
 #pragma unroll
             for (int hv = 0; hv < HV; ++hv) {
@@ -329,8 +329,8 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
                 w0[1] = cvt_pk_bf16(acc[hv][2] * inv, acc[hv][3] * inv);
                 w1[0] = cvt_pk_bf16(acc[hv][4] * inv, acc[hv][5] * inv);
                 w1[1] = cvt_pk_bf16(acc[hv][6] * inv, acc[hv][7] * inv);
-                *reinterpret_cast<u32x2 *>(yb + (size_t)n * ts.sn + 16 * hv + 4 * hh) = w0;
-                *reinterpret_cast<u32x2 *>(yb + (size_t)n * ts.sn + 16 * hv + 8 + 4 * hh) = w1;
+                *reinterpret_cast<u32x2 *>(yb + tok_off(ts, n) + 16 * hv + 4 * hh) = w0;
+                *reinterpret_cast<u32x2 *>(yb + tok_off(ts, n) + 16 * hv + 8 + 4 * hh) = w1;
             }
         }
 #pragma unroll
@@ -436,13 +436,13 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         const int nk = min(tile_tok0(j) + l32, N - 1);
 #pragma unroll
         for (int s = 0; s < KS; ++s)
-            kk[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(kb + (size_t)nk * ts.sn + (D / 2) * hh + 8 * s));
+            kk[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(kb + tok_off(ts, nk) + (D / 2) * hh + 8 * s));
     };
     auto load_v = [&](int j, u32x4 (&vv)[LOADS]) {
         const int nv = min(tile_tok0(j) + vtok, N - 1);
 #pragma unroll
         for (int i = 0; i < LOADS; ++i)
-            vv[i] = *reinterpret_cast<const u32x4 *>(vb + (size_t)nv * ts.sn + 8 * ((lane & 1) * LOADS + i));
+            vv[i] = *reinterpret_cast<const u32x4 *>(vb + tok_off(ts, nv) + 8 * ((lane & 1) * LOADS + i));
     };
     auto write_vt = [&](const u32x4 (&vv)[LOADS], uint16_t *buf) {   // transposed: row = column of V
 #pragma unroll
@@ -505,7 +505,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         const int nv = min(tile_tok0(j) + vtok, N - 1);
 #pragma unroll
         for (int i = 0; i < LOADS; ++i)
-            yy[i] = *reinterpret_cast<const u32x4 *>(yb + (size_t)nv * ts.sn + 8 * ((lane & 1) * LOADS + i));
+            yy[i] = *reinterpret_cast<const u32x4 *>(yb + tok_off(ts, nv) + 8 * ((lane & 1) * LOADS + i));
     };
     auto put_delta = [&](int j, const u32x4 (&gv)[LOADS], const u32x4 (&yy)[LOADS]) {
         float part = 0.f;
@@ -794,7 +794,7 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
         const int n = min(tile_tok0(j) + l32, N - 1);
 #pragma unroll
         for (int s = 0; s < KS; ++s)
-            t[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(base + (size_t)n * ts.sn + (D / 2) * hh + 8 * s));
+            t[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(base + tok_off(ts, n) + (D / 2) * hh + 8 * s));
     };
     auto write_kt = [&](const bf16x8 (&t)[KS], uint16_t *buf) {   // transposed: row = d-index, column = token
 #pragma unroll
@@ -1083,7 +1083,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
         const int n = min(tile * 32 + l32, N - 1);
 #pragma unroll
         for (int s = 0; s < KS; ++s)
-            t[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(base + (size_t)n * ts.sn + (D / 2) * hh + 8 * s));
+            t[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(base + tok_off(ts, n) + (D / 2) * hh + 8 * s));
     };
     auto image = [&](int t, int sid) { return as_bf16x8(img[(t * PER_TILE + sid) * 64 + lane]); };
 
@@ -1192,8 +1192,8 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
             }
         }
         if (n < N) {
-            bf16_t *dkr = dk + tok_base(ts, bh, H) + (size_t)n * ts.sn;
-            bf16_t *dvr = dv + tok_base(ts, bh, H) + (size_t)n * ts.sn;
+            bf16_t *dkr = dk + tok_base(ts, bh, H) + tok_off(ts, n);
+            bf16_t *dvr = dv + tok_base(ts, bh, H) + tok_off(ts, n);
 #pragma unroll
             for (int hv = 0; hv < HV; ++hv) {
                 u32x2 w0, w1;

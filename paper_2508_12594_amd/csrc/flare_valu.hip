@@ -128,7 +128,7 @@ __global__ __launch_bounds__(kLatentBlock) void encode_partial_kernel(
 #pragma unroll
         for (int t = 0; t < kGroup; ++t) {
             float kr[D];
-            load_row<D>(kb + (size_t)(n + t) * ts.sn, kr);
+            load_row<D>(kb + tok_off(ts, (n + t)), kr);
             s[t] = dot<D>(qm, kr);
             gm = fmaxf(gm, s[t]);
         }
@@ -142,21 +142,21 @@ __global__ __launch_bounds__(kLatentBlock) void encode_partial_kernel(
             const float p = fast_exp2(s[t] - mr);
             l += p;
             float vr[D];
-            load_row<D>(vb + (size_t)(n + t) * ts.sn, vr);
+            load_row<D>(vb + tok_off(ts, (n + t)), vr);
 #pragma unroll
             for (int j = 0; j < D; ++j) o[j] = fmaf(p, vr[j], o[j]);
         }
     }
     for (; n < n1; ++n) {
         float kr[D], vr[D];
-        load_row<D>(kb + (size_t)n * ts.sn, kr);
+        load_row<D>(kb + tok_off(ts, n), kr);
         const float s = dot<D>(qm, kr);
         const float gm = fmaxf(mr, s);
         const float al = fast_exp2(mr - gm);
         mr = gm;
         const float p = fast_exp2(s - mr);
         l = l * al + p;
-        load_row<D>(vb + (size_t)n * ts.sn, vr);
+        load_row<D>(vb + tok_off(ts, n), vr);
 #pragma unroll
         for (int j = 0; j < D; ++j) o[j] = fmaf(p, vr[j], o[j] * al);
     }
@@ -237,7 +237,7 @@ __global__ __launch_bounds__(kTokenBlock) void token_pass_kernel(
     const int bh = blockIdx.y, h = bh % H;
     const bool valid = n < N;
     const size_t row = (size_t)bh * N + (valid ? n : N - 1);                     // index of the per-token scalars
-    const size_t trow = tok_base(ts, bh, H) + (size_t)(valid ? n : N - 1) * ts.sn;  // first element of the token's row
+    const size_t trow = tok_base(ts, bh, H) + tok_off(ts, (valid ? n : N - 1));  // first element of the token's row
     float kn[D];
     load_row<D>(k + trow, kn);
 #pragma unroll
@@ -351,9 +351,9 @@ __global__ __launch_bounds__(kLatentBlock) void dz_partial_kernel(
     for (int j = 0; j < D; ++j) acc[j] = 0.f;
     for (int n = n0; n < n1; ++n) {
         float kr[D], g[D];
-        load_row<D>(kb + (size_t)n * ts.sn, kr);
+        load_row<D>(kb + tok_off(ts, n), kr);
         const float r = fast_exp2(dot<D>(qm, kr) - lb[n]);
-        load_row<D>(gb + (size_t)n * ts.sn, g);
+        load_row<D>(gb + tok_off(ts, n), g);
 #pragma unroll
         for (int j = 0; j < D; ++j) acc[j] = fmaf(r, g[j], acc[j]);
     }
@@ -441,9 +441,9 @@ __global__ __launch_bounds__(kLatentBlock) void dq_partial_kernel(
     const int n1 = min(N, n0 + chunk_len);
     for (int n = n0; n < n1; ++n) {
         float kr[D], vr[D], g[D];
-        load_row<D>(kb + (size_t)n * ts.sn, kr);
-        load_row<D>(vb + (size_t)n * ts.sn, vr);
-        load_row<D>(gb + (size_t)n * ts.sn, g);
+        load_row<D>(kb + tok_off(ts, n), kr);
+        load_row<D>(vb + tok_off(ts, n), vr);
+        load_row<D>(gb + tok_off(ts, n), g);
         const float s2 = dot<D>(qm, kr);
         const float p = fast_exp2(s2 - le2);
         const float r = fast_exp2(s2 - lb[n]);
@@ -485,7 +485,7 @@ __global__ __launch_bounds__(kTokenBlock) void dkdv_kernel(
     const int bh = blockIdx.y, h = bh % H;
     const bool valid = n < N;
     const size_t row = (size_t)bh * N + (valid ? n : N - 1);
-    const size_t trow = tok_base(ts, bh, H) + (size_t)(valid ? n : N - 1) * ts.sn;
+    const size_t trow = tok_base(ts, bh, H) + tok_off(ts, (valid ? n : N - 1));
     const float c2 = scale * kLog2e;
     float kn[D], vn[D], g[D], ak[D], av[D];
     load_row<D>(k + trow, kn);
