@@ -87,6 +87,7 @@ def main():
     ap.add_argument("--cfg", type=int, default=4, help="synthetic workload id (4 = the headline)")
     ap.add_argument("--tokens", type=int, default=None, help="override N (for quick checks only)")
     ap.add_argument("--latents", type=int, default=None, help="override M (for quick checks only)")
+    ap.add_argument("--head-dim", type=int, default=None, help="override d (for quick checks only)")
     ap.add_argument("--layout", choices=["bhnd", "bnhd"], default="bhnd",
                     help="memory order of k, v, y, dy, dk, dv: [B,H,N,d] (default) or [B,N,H,d]")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -110,6 +111,8 @@ def main():
     over = {} if args.tokens is None else {"N": args.tokens}
     if args.latents is not None:
         over["M"] = args.latents
+    if args.head_dim is not None:
+        over["d"] = args.head_dim
     inp = synth.make_inputs(args.cfg, with_dy=True, **over)
     B, H, N, M, d = (inp[x] for x in "BHNMd")
     dt = torch.float32 if inp["dtype"] == "f32" else torch.bfloat16
@@ -178,7 +181,7 @@ def main():
     dom_bytes = algorithmic_bytes(dom, B, H, N, M, d, elem)
     dom_exps = exponentials(dom, B, H, N, M)
     dom_s = kernels[dom]["mean_us"] * 1e-6
-    default_workload = args.cfg == 4 and args.tokens is None and args.latents is None
+    default_workload = args.cfg == 4 and args.tokens is None and args.latents is None and args.head_dim is None
     traffic = sum(MEASURED_TRAFFIC_CFG4[dom]) if default_workload and dom in MEASURED_TRAFFIC_CFG4 else None
     # the roofline that binds this kernel: whichever lower bound on its duration is larger
     if dom_exps / (EXP_PEAK_GOPS * 1e9) > dom_bytes / (HBM_PEAK_GBS * 1e9):
@@ -204,7 +207,8 @@ def main():
         "warmup": args.warmup, "ms_per_step": round(t_step * 1e3, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": inp["dtype"], "data": "synthetic",
         "config": {"workload": synth.describe(args.cfg) + ("" if args.tokens is None else " [N overridden to %d]" % N)
-                   + ("" if args.latents is None else " [M overridden to %d]" % M),
+                   + ("" if args.latents is None else " [M overridden to %d]" % M)
+                   + ("" if args.head_dim is None else " [d overridden to %d]" % d),
                    "step": "flare_forward + flare_backward", "B": B, "H": H, "N": N, "M": M, "d": d,
                    "layout": "[B,H,N,d]" if lay == "bhnd" else "[B,N,H,d]"},
         "fwd": {"tokens_per_s": round(tokens / t_fwd, 1), "ms": round(t_fwd * 1e3, 4),

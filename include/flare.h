@@ -127,7 +127,9 @@ int flare_forward(const flare_shape *shape, const void *q_lat, const void *k, co
  *   z, lse_enc: what flare_forward wrote for the same inputs                (in)
  *   y, lse_dec: what flare_forward wrote, or NULL.  When both are given, delta_n is taken from
  *     the stored y and the decode normaliser from lse_dec; when either is NULL both are
- *     recomputed from z (one more pass over the scores, Y in fp32)          (in, optional)
+ *     recomputed from z (one more pass over the scores, Y in fp32).  With bf16 storage and
+ *     d < 16 they are recomputed in either case: delta from a bf16-rounded y of so few
+ *     elements would not meet the accuracy of the rest                      (in, optional)
  *   dq_lat [H][M][d] fp32 (summed over the batch), dk, dv [B][H][N][d] dtype (out)
  */
 int flare_backward(const flare_shape *shape, const void *q_lat, const void *k, const void *v,

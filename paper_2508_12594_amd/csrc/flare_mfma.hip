@@ -92,17 +92,58 @@ __device__ __forceinline__ void sched_fence() { __builtin_amdgcn_sched_barrier(0
 // the tile: the row that accumulator register 8*s2 + i holds.
 __device__ __forceinline__ int perm_index(int s2, int hh, int i) { return 16 * s2 + 8 * (i / 4) + 4 * hh + (i % 4); }
 
+// Head dimensions below 16 run with the contraction padded to 16: DR is the real d (the row length
+// in memory), D = max(DR, 16) what the matrix cores see; the padding slots are zero in every
+// operand.  The helpers below move 8 (bf16, fp32) or 4 (outputs) consecutive elements of a
+// DR-element row and give zeros / skip the store beyond its end.
+constexpr int padded_dim(int dr) { return dr < 16 ? 16 : dr; }
+template <int DR>
+__device__ __forceinline__ u32x4 row8_bf16(const bf16_t *__restrict__ row, int e0)   // e0: a multiple of 8
+{
+    u32x4 w;
+    w[0] = 0u; w[1] = 0u; w[2] = 0u; w[3] = 0u;
+    if constexpr (DR >= 16) {
+        w = *reinterpret_cast<const u32x4 *>(row + e0);
+    } else if constexpr (DR == 8) {
+        if (e0 == 0) w = *reinterpret_cast<const u32x4 *>(row);
+    } else {
+        if (e0 == 0) {
+            const u32x2 t = *reinterpret_cast<const u32x2 *>(row);
+            w[0] = t[0]; w[1] = t[1];
+        }
+    }
+    return w;
+}
+template <int DR>
+__device__ __forceinline__ void row8_f32(const float *__restrict__ row, int e0, float (&x)[8])
+{
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = 0.f;
+    if (DR >= 16 || e0 == 0) {
+#pragma unroll
+        for (int i = 0; i < (DR >= 8 ? 8 : DR); ++i) x[i] = row[e0 + i];
+    }
+}
+// Accumulator rows of one 16-wide column group: registers 0-3 hold columns 4*hh .. 4*hh+3, registers
+// 4-7 columns 8 + 4*hh ... of group hv.  true iff that quartet lies inside a DR-element row.
+template <int DR>
+__device__ __forceinline__ bool quartet_inside(int hv, int hh, int upper)
+{
+    return 16 * hv + 8 * upper + 4 * hh < DR;
+}
+
 // Latent-query operand for one 32-latent tile: row/column = latent, contraction over d.
 // Lane half hh covers d-indices (D/2)*hh + 8*s + i for k-step s.  The same mapping is used for
 // the key operand.  PRE: multiply by c2 and split into hi + lo bf16 terms; else raw bits (sign
 // flipped when c2 < 0 so that the kernel can work with |c2|).
-template <int D, bool PRE>
+template <int DR, bool PRE>
 __device__ __forceinline__ void load_q_operand(const bf16_t *__restrict__ q_row, int hh, float c2, bool flip,
-                                               bf16x8 (&hi)[D / 16], bf16x8 (&lo)[D / 16])
+                                               bf16x8 (&hi)[padded_dim(DR) / 16], bf16x8 (&lo)[padded_dim(DR) / 16])
 {
+    constexpr int D = padded_dim(DR);
 #pragma unroll
     for (int s = 0; s < D / 16; ++s) {
-        const u32x4 w = *reinterpret_cast<const u32x4 *>(q_row + (D / 2) * hh + 8 * s);
+        const u32x4 w = row8_bf16<DR>(q_row, (D / 2) * hh + 8 * s);
         if constexpr (PRE) {
             u32x4 wh, wl;
 #pragma unroll
@@ -161,12 +202,13 @@ __device__ __forceinline__ void compiler_fence() { asm volatile("" ::: "memory")
 // MODE 0 writes y and, when lse_dec2 is not NULL, log sum_m exp(S[m][n]) (natural log) there.
 // MODE 1 (first step of the backward when nothing was saved) writes per token
 //   lse_dec2[n] = log2 sum_m 2^S2[m][n]   and   delta[n] = <dY_n, Y_n>   (Y_n kept in fp32).
-template <int D, int MT, bool PRE, int MINB, int MODE>
+template <int DR, int MT, bool PRE, int MINB, int MODE>
 __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const float *__restrict__ z,
     bf16_t *__restrict__ y, const bf16_t *__restrict__ dy, float *__restrict__ lse_dec2,
     float *__restrict__ delta, TokStride ts, int H, int N, float c2)
 {
+    constexpr int D = padded_dim(DR);
     constexpr int KS = D / 16;   // k-steps of the score product
     constexpr int HV = D / 16;   // 16-wide column groups of Z, each with its own ones row
     constexpr int M = 32 * MT;
@@ -179,12 +221,12 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
     bf16x8 qh[MT][KS], ql[MT][KS];
 #pragma unroll
     for (int t = 0; t < MT; ++t)
-        load_q_operand<D, PRE>(q + ((size_t)h * M + 32 * t + l32) * D, hh, c2, flip, qh[t], ql[t]);
+        load_q_operand<DR, PRE>(q + ((size_t)h * M + 32 * t + l32) * DR, hh, c2, flip, qh[t], ql[t]);
 
     // Zaug^T operand: row l32 (< 16: column 16*hv + l32 of Z; 16: ones; else zero)
     bf16x8 zt[HV][2 * MT];
     {
-        const float *zb = z + (size_t)bh * M * D;
+        const float *zb = z + (size_t)bh * M * DR;
 #pragma unroll
         for (int hv = 0; hv < HV; ++hv)
 #pragma unroll
@@ -193,9 +235,9 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
 #pragma unroll
                 for (int i = 0; i < 8; i += 2) {
                     float a, b;
-                    if (l32 < 16) {
-                        a = zb[(size_t)(32 * (s / 2) + perm_index(s % 2, hh, i)) * D + 16 * hv + l32];
-                        b = zb[(size_t)(32 * (s / 2) + perm_index(s % 2, hh, i + 1)) * D + 16 * hv + l32];
+                    if (l32 < 16 && 16 * hv + l32 < DR) {
+                        a = zb[(size_t)(32 * (s / 2) + perm_index(s % 2, hh, i)) * DR + 16 * hv + l32];
+                        b = zb[(size_t)(32 * (s / 2) + perm_index(s % 2, hh, i + 1)) * DR + 16 * hv + l32];
                     } else {
                         a = b = (l32 == 16) ? 1.f : 0.f;
                     }
@@ -215,7 +257,7 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
         const int nld = min(tile * 32 + l32, N - 1);
 #pragma unroll
         for (int s = 0; s < KS; ++s)
-            kt[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(kb + tok_off(ts, nld) + (D / 2) * hh + 8 * s));
+            kt[s] = as_bf16x8(row8_bf16<DR>(kb + tok_off(ts, nld), (D / 2) * hh + 8 * s));
     }
     for (; tile < tiles; tile += stride) {
         const int n = tile * 32 + l32;
@@ -224,7 +266,7 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
             const int nld = min(tn * 32 + l32, N - 1);
 #pragma unroll
             for (int s = 0; s < KS; ++s)
-                ktn[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(kb + tok_off(ts, nld) + (D / 2) * hh + 8 * s));
+                ktn[s] = as_bf16x8(row8_bf16<DR>(kb + tok_off(ts, nld), (D / 2) * hh + 8 * s));
         }
         auto qk_hi = [&](int t) {
             f32x16 r = splat16(0.f);
@@ -299,8 +341,10 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
             float part = 0.f;
 #pragma unroll
             for (int hv = 0; hv < HV; ++hv) {
-                const u32x2 g0 = *reinterpret_cast<const u32x2 *>(gr + 16 * hv + 4 * hh);
-                const u32x2 g1 = *reinterpret_cast<const u32x2 *>(gr + 16 * hv + 8 + 4 * hh);
+                u32x2 g0, g1;
+                g0[0] = 0u; g0[1] = 0u; g1[0] = 0u; g1[1] = 0u;
+                if (quartet_inside<DR>(hv, hh, 0)) g0 = *reinterpret_cast<const u32x2 *>(gr + 16 * hv + 4 * hh);
+                if (quartet_inside<DR>(hv, hh, 1)) g1 = *reinterpret_cast<const u32x2 *>(gr + 16 * hv + 8 + 4 * hh);
                 part = fmaf(acc[hv][0] * inv, bf16_lo(g0[0]), part);
                 part = fmaf(acc[hv][1] * inv, bf16_hi(g0[0]), part);
                 part = fmaf(acc[hv][2] * inv, bf16_lo(g0[1]), part);
@@ -329,8 +373,9 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
                 w0[1] = cvt_pk_bf16(acc[hv][2] * inv, acc[hv][3] * inv);
                 w1[0] = cvt_pk_bf16(acc[hv][4] * inv, acc[hv][5] * inv);
                 w1[1] = cvt_pk_bf16(acc[hv][6] * inv, acc[hv][7] * inv);
-                *reinterpret_cast<u32x2 *>(yb + tok_off(ts, n) + 16 * hv + 4 * hh) = w0;
-                *reinterpret_cast<u32x2 *>(yb + tok_off(ts, n) + 16 * hv + 8 + 4 * hh) = w1;
+                if (quartet_inside<DR>(hv, hh, 0)) *reinterpret_cast<u32x2 *>(yb + tok_off(ts, n) + 16 * hv + 4 * hh) = w0;
+                if (quartet_inside<DR>(hv, hh, 1))
+                    *reinterpret_cast<u32x2 *>(yb + tok_off(ts, n) + 16 * hv + 8 + 4 * hh) = w1;
             }
         }
 #pragma unroll
@@ -364,7 +409,7 @@ constexpr int kVtStride = 36;   // uint16 per LDS row: 32 tokens + 4 pad (72 B, 
 // loop), and the waves of latent group 0 store it to delta_out for the two kernels that follow.
 // Those waves also record the smallest and largest lse_dec2 they met, ld_range[part] = (min, max),
 // from which bwd_plan_kernel decides which variant of the next two kernels may run.
-template <int D, int NB, int MINB, int MODE>
+template <int DR, int NB, int MINB, int MODE>
 __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const float *__restrict__ lse_dec2, float ld_mul, const bf16_t *__restrict__ y_tok,
@@ -372,6 +417,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     float *__restrict__ m_part, float *__restrict__ l_part, float *__restrict__ o_part,
     TokStride ts, int H, int N, int M, int chunk_len, int parts, int G, int TG, float c2)
 {
+    constexpr int D = padded_dim(DR);
     constexpr int KS = D / 16;
     constexpr int HV = D / 16;
     constexpr int ROWS = D + 2;                 // V^T rows, then a row of ones, then a row of zeros
@@ -397,7 +443,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     bf16x8 qh[NB][KS], ql[NB][KS];
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
-        load_q_operand<D, true>(q + ((size_t)h * M + lat0 + 32 * b + l32) * D, hh, c2, false, qh[b], ql[b]);
+        load_q_operand<DR, true>(q + ((size_t)h * M + lat0 + 32 * b + l32) * DR, hh, c2, false, qh[b], ql[b]);
     }
     u32x4 wzero;
     wzero[0] = 0u; wzero[1] = 0u; wzero[2] = 0u; wzero[3] = 0u;
@@ -436,13 +482,13 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         const int nk = min(tile_tok0(j) + l32, N - 1);
 #pragma unroll
         for (int s = 0; s < KS; ++s)
-            kk[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(kb + tok_off(ts, nk) + (D / 2) * hh + 8 * s));
+            kk[s] = as_bf16x8(row8_bf16<DR>(kb + tok_off(ts, nk), (D / 2) * hh + 8 * s));
     };
     auto load_v = [&](int j, u32x4 (&vv)[LOADS]) {
         const int nv = min(tile_tok0(j) + vtok, N - 1);
 #pragma unroll
         for (int i = 0; i < LOADS; ++i)
-            vv[i] = *reinterpret_cast<const u32x4 *>(vb + tok_off(ts, nv) + 8 * ((lane & 1) * LOADS + i));
+            vv[i] = row8_bf16<DR>(vb + tok_off(ts, nv), 8 * ((lane & 1) * LOADS + i));
     };
     auto write_vt = [&](const u32x4 (&vv)[LOADS], uint16_t *buf) {   // transposed: row = column of V
 #pragma unroll
@@ -505,7 +551,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         const int nv = min(tile_tok0(j) + vtok, N - 1);
 #pragma unroll
         for (int i = 0; i < LOADS; ++i)
-            yy[i] = *reinterpret_cast<const u32x4 *>(yb + tok_off(ts, nv) + 8 * ((lane & 1) * LOADS + i));
+            yy[i] = row8_bf16<DR>(yb + tok_off(ts, nv), 8 * ((lane & 1) * LOADS + i));
     };
     auto put_delta = [&](int j, const u32x4 (&gv)[LOADS], const u32x4 (&yy)[LOADS]) {
         float part = 0.f;
@@ -650,8 +696,8 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         for (int hv = 0; hv < HV; ++hv) {
             float4 lo4 = make_float4(o[b][hv][0], o[b][hv][1], o[b][hv][2], o[b][hv][3]);
             float4 hi4 = make_float4(o[b][hv][4], o[b][hv][5], o[b][hv][6], o[b][hv][7]);
-            *reinterpret_cast<float4 *>(o_part + slot * D + 16 * hv + 4 * hh) = lo4;
-            *reinterpret_cast<float4 *>(o_part + slot * D + 16 * hv + 8 + 4 * hh) = hi4;
+            if (quartet_inside<DR>(hv, hh, 0)) *reinterpret_cast<float4 *>(o_part + slot * DR + 16 * hv + 4 * hh) = lo4;
+            if (quartet_inside<DR>(hv, hh, 1)) *reinterpret_cast<float4 *>(o_part + slot * DR + 16 * hv + 8 + 4 * hh) = hi4;
         }
     }
 }
@@ -678,7 +724,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
 // fp32 range wherever R matters, which bwd_plan_kernel guarantees per (b,h) (plan[bh] = 1);
 // otherwise the ONE = false variant runs.  Each variant returns at once when the plan names the other.
 // ============================================================================================
-template <int D, int NB, int MINB, bool ONE>
+template <int DR, int NB, int MINB, bool ONE>
 __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const bf16_t *__restrict__ dy, const float *__restrict__ z, const float *__restrict__ lse_enc,
@@ -686,6 +732,7 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
     const float *__restrict__ delta, float ld_mul, const int *__restrict__ plan, float *__restrict__ dq_part,
     TokStride ts, int H, int N, int M, int chunk_len, int parts, int G, int TG, float c2)
 {
+    constexpr int D = padded_dim(DR);
     constexpr int KS = D / 16;
     constexpr int HV = D / 16;
     constexpr int ROWS = D + 1;                 // K^T rows, then a row of zeros
@@ -721,7 +768,7 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         const int m = lat0 + 32 * b + l32;
-        load_q_operand<D, true>(q + ((size_t)h * M + m) * D, hh, c2, false, qh[b], ql[b]);
+        load_q_operand<DR, true>(q + ((size_t)h * M + m) * DR, hh, c2, false, qh[b], ql[b]);
         const float le2 = lse_enc[(size_t)bh * M + m] * kLog2e;
         const float um = ONE ? fast_exp2(le2 - kap) : 1.f;   // folded into Z
         if constexpr (ONE) {
@@ -739,8 +786,9 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
         q_aug[b] = as_bf16x8(wq);
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            const float *zr = z + ((size_t)bh * M + m) * D + (D / 2) * hh + 8 * s;
-            const float *dr = dz + ((size_t)bh * M + m) * D + (D / 2) * hh + 8 * s;
+            float zr[8], dr[8];
+            row8_f32<DR>(z + ((size_t)bh * M + m) * DR, (D / 2) * hh + 8 * s, zr);
+            row8_f32<DR>(dz + ((size_t)bh * M + m) * DR, (D / 2) * hh + 8 * s, dr);
             u32x4 wz, wd, wzl, wdl;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -794,7 +842,7 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
         const int n = min(tile_tok0(j) + l32, N - 1);
 #pragma unroll
         for (int s = 0; s < KS; ++s)
-            t[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(base + tok_off(ts, n) + (D / 2) * hh + 8 * s));
+            t[s] = as_bf16x8(row8_bf16<DR>(base + tok_off(ts, n), (D / 2) * hh + 8 * s));
     };
     auto write_kt = [&](const bf16x8 (&t)[KS], uint16_t *buf) {   // transposed: row = d-index, column = token
 #pragma unroll
@@ -939,8 +987,8 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
         for (int hv = 0; hv < HV; ++hv) {
             float4 lo4 = make_float4(acc[b][hv][0], acc[b][hv][1], acc[b][hv][2], acc[b][hv][3]);
             float4 hi4 = make_float4(acc[b][hv][4], acc[b][hv][5], acc[b][hv][6], acc[b][hv][7]);
-            *reinterpret_cast<float4 *>(dq_part + slot * D + 16 * hv + 4 * hh) = lo4;
-            *reinterpret_cast<float4 *>(dq_part + slot * D + 16 * hv + 8 + 4 * hh) = hi4;
+            if (quartet_inside<DR>(hv, hh, 0)) *reinterpret_cast<float4 *>(dq_part + slot * DR + 16 * hv + 4 * hh) = lo4;
+            if (quartet_inside<DR>(hv, hh, 1)) *reinterpret_cast<float4 *>(dq_part + slot * DR + 16 * hv + 8 + 4 * hh) = hi4;
         }
     }
 }
@@ -963,7 +1011,7 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
 // (and into slots 4-6 of the correction image, against -delta in the token operand), w[n] is a
 // per-lane scalar here, and dS' = P (a + w c).  Runs only where plan[bh] = 1.
 // ============================================================================================
-template <int D, int MT, bool LO2, bool ONE>
+template <int DR, int MT, bool LO2, bool ONE>
 __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const bf16_t *__restrict__ dy, const float *__restrict__ z, const float *__restrict__ lse_enc,
@@ -971,6 +1019,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     const float *__restrict__ delta, float ld_mul, const int *__restrict__ plan, bf16_t *__restrict__ dk,
     bf16_t *__restrict__ dv, TokStride ts, int H, int N, float c2, float scale)
 {
+    constexpr int D = padded_dim(DR);
     constexpr int KS = D / 16;
     constexpr int HV = D / 16;
     constexpr int M = 32 * MT;
@@ -996,9 +1045,9 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
 
     // ---- build the operand images ----
     {
-        const bf16_t *qh_ = q + (size_t)h * M * D;
-        const float *zb = z + (size_t)bh * M * D;
-        const float *dzb = dz + (size_t)bh * M * D;
+        const bf16_t *qh_ = q + (size_t)h * M * DR;
+        const float *zb = z + (size_t)bh * M * DR;
+        const float *dzb = dz + (size_t)bh * M * DR;
         const float *eb = eps + (size_t)bh * M;
         const float *leb = lse_enc + (size_t)bh * M;
         for (int idx = tid; idx < MT * PER_TILE * 64; idx += 512) {
@@ -1022,15 +1071,15 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                 const int d0 = (D / 2) * hf + 8 * ks;
                 float x[8];
                 if (kind <= 1) {
-                    const u32x4 raw = *reinterpret_cast<const u32x4 *>(qh_ + (size_t)m * D + d0);
+                    const u32x4 raw = row8_bf16<DR>(qh_ + (size_t)m * DR, d0);
 #pragma unroll
                     for (int i = 0; i < 4; ++i) { x[2 * i] = bf16_lo(raw[i]) * c2; x[2 * i + 1] = bf16_hi(raw[i]) * c2; }
                 } else {
                     const bool is_z = (kind == 3 || kind == 5);
-                    const float *src = (is_z ? zb : dzb) + (size_t)m * D + d0;
+                    row8_f32<DR>((is_z ? zb : dzb) + (size_t)m * DR, d0, x);
                     const float um = (ONE && is_z) ? fast_exp2(leb[m] * kLog2e - kap) : 1.f;
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) x[i] = src[i] * um;
+                    for (int i = 0; i < 8; ++i) x[i] *= um;
                 }
                 const bool want_lo = (kind == 1 || kind >= 4);
 #pragma unroll
@@ -1050,11 +1099,12 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                 for (int i = 0; i < 8; i += 2) {
                     float a, b;
                     const int m0 = 32 * t + perm_index(s2, hf, i), m1 = 32 * t + perm_index(s2, hf, i + 1);
-                    const float q0 = __uint_as_float((uint32_t)qh_[(size_t)m0 * D + dd] << 16);
-                    const float q1 = __uint_as_float((uint32_t)qh_[(size_t)m1 * D + dd] << 16);
+                    const bool in = dd < DR;   // beyond the real head dimension every row image is zero
+                    const float q0 = in ? __uint_as_float((uint32_t)qh_[(size_t)m0 * DR + dd] << 16) : 0.f;
+                    const float q1 = in ? __uint_as_float((uint32_t)qh_[(size_t)m1 * DR + dd] << 16) : 0.f;
                     if (which == 0) {
-                        a = (r32 < 16) ? dzb[(size_t)m0 * D + dd] : -eb[m0] * q0;
-                        b = (r32 < 16) ? dzb[(size_t)m1 * D + dd] : -eb[m1] * q1;
+                        a = (r32 < 16) ? (in ? dzb[(size_t)m0 * DR + dd] : 0.f) : -eb[m0] * q0;
+                        b = (r32 < 16) ? (in ? dzb[(size_t)m1 * DR + dd] : 0.f) : -eb[m1] * q1;
                     } else {
                         a = (r32 < 16) ? q0 : 0.f;
                         b = (r32 < 16) ? q1 : 0.f;
@@ -1083,7 +1133,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
         const int n = min(tile * 32 + l32, N - 1);
 #pragma unroll
         for (int s = 0; s < KS; ++s)
-            t[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(base + tok_off(ts, n) + (D / 2) * hh + 8 * s));
+            t[s] = as_bf16x8(row8_bf16<DR>(base + tok_off(ts, n), (D / 2) * hh + 8 * s));
     };
     auto image = [&](int t, int sid) { return as_bf16x8(img[(t * PER_TILE + sid) * 64 + lane]); };
 
@@ -1201,14 +1251,14 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                 w0[1] = cvt_pk_bf16(acc1[hv][2], acc1[hv][3]);
                 w1[0] = cvt_pk_bf16(acc1[hv][4], acc1[hv][5]);
                 w1[1] = cvt_pk_bf16(acc1[hv][6], acc1[hv][7]);
-                *reinterpret_cast<u32x2 *>(dvr + 16 * hv + 4 * hh) = w0;
-                *reinterpret_cast<u32x2 *>(dvr + 16 * hv + 8 + 4 * hh) = w1;
+                if (quartet_inside<DR>(hv, hh, 0)) *reinterpret_cast<u32x2 *>(dvr + 16 * hv + 4 * hh) = w0;
+                if (quartet_inside<DR>(hv, hh, 1)) *reinterpret_cast<u32x2 *>(dvr + 16 * hv + 8 + 4 * hh) = w1;
                 w0[0] = cvt_pk_bf16(scale * (acc2[hv][0] + acc1[hv][8]), scale * (acc2[hv][1] + acc1[hv][9]));
                 w0[1] = cvt_pk_bf16(scale * (acc2[hv][2] + acc1[hv][10]), scale * (acc2[hv][3] + acc1[hv][11]));
                 w1[0] = cvt_pk_bf16(scale * (acc2[hv][4] + acc1[hv][12]), scale * (acc2[hv][5] + acc1[hv][13]));
                 w1[1] = cvt_pk_bf16(scale * (acc2[hv][6] + acc1[hv][14]), scale * (acc2[hv][7] + acc1[hv][15]));
-                *reinterpret_cast<u32x2 *>(dkr + 16 * hv + 4 * hh) = w0;
-                *reinterpret_cast<u32x2 *>(dkr + 16 * hv + 8 + 4 * hh) = w1;
+                if (quartet_inside<DR>(hv, hh, 0)) *reinterpret_cast<u32x2 *>(dkr + 16 * hv + 4 * hh) = w0;
+                if (quartet_inside<DR>(hv, hh, 1)) *reinterpret_cast<u32x2 *>(dkr + 16 * hv + 8 + 4 * hh) = w1;
             }
         }
 #pragma unroll
@@ -1242,7 +1292,7 @@ constexpr int kDecodeTargetBlocks = 512;
 bool mfma_supported(const flare_shape &s)
 {
     if (s.dtype != FLARE_BF16) return false;
-    if (s.d != 16 && s.d != 32) return false;
+    if (s.d != 4 && s.d != 8 && s.d != 16 && s.d != 32) return false;   // d < 16 runs padded to 16
     if (s.M == 32) return true;
     return s.M % 64 == 0 && s.M <= 256;
 }
@@ -1250,7 +1300,7 @@ bool mfma_supported(const flare_shape &s)
 MfmaPlan mfma_plan(const flare_shape &s)
 {
     MfmaPlan p;
-    const EncGeom e = enc_geom(s.M, s.d);
+    const EncGeom e = enc_geom(s.M, padded_dim(s.d));
     const int BH = s.B * s.H;
     // each chunk gives every token group at least 8 tiles of 32 tokens
     p.enc = plan_split(s.N, BH, 256 * e.TG, kEncodeTargetBlocks);
@@ -1271,7 +1321,7 @@ int mfma_encode(const flare_shape &s, const void *q, const void *k, const void *
                 float scale, void *ws, hipStream_t stream)
 {
     const MfmaPlan p = mfma_plan(s);
-    const EncGeom e = enc_geom(s.M, s.d);
+    const EncGeom e = enc_geom(s.M, padded_dim(s.d));
     Split sp;
     sp.chunks = p.parts;
     sp.chunk_len = 0;
@@ -1287,11 +1337,21 @@ int mfma_encode(const flare_shape &s, const void *q, const void *k, const void *
     encode_mfma_kernel<DD, NBB, 2, 0><<<grid, e.threads, 0, stream>>>(qq, kk, vv, nullptr, 1.f, nullptr, nullptr, nullptr, m_part, l_part, o_part, \
                                                                       tok_stride(s), s.H, s.N, s.M, p.enc.chunk_len, p.parts, e.G, \
                                                                       e.TG, c2)
-        if (s.d == 16 && e.NB == 1) FLARE_ENC(16, 1);
-        else if (s.d == 16 && e.NB == 2) FLARE_ENC(16, 2);
-        else if (s.d == 16) FLARE_ENC(16, 4);
-        else if (e.NB == 1) FLARE_ENC(32, 1);
-        else FLARE_ENC(32, 2);
+#define FLARE_ENC_NB(DD)                   \
+    do {                                   \
+        if (e.NB == 1) FLARE_ENC(DD, 1);   \
+        else if (e.NB == 2) FLARE_ENC(DD, 2); \
+        else FLARE_ENC(DD, 4);             \
+    } while (0)
+        switch (s.d) {
+            case 4: FLARE_ENC_NB(4); break;
+            case 8: FLARE_ENC_NB(8); break;
+            case 16: FLARE_ENC_NB(16); break;
+            default:
+                if (e.NB == 1) FLARE_ENC(32, 1);
+                else FLARE_ENC(32, 2);
+        }
+#undef FLARE_ENC_NB
 #undef FLARE_ENC
     }
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
@@ -1304,7 +1364,7 @@ int mfma_dz_partial(const flare_shape &s, const void *q, const void *k, const vo
                     hipStream_t stream)
 {
     const MfmaPlan p = mfma_plan(s);
-    const EncGeom e = enc_geom(s.M, s.d);
+    const EncGeom e = enc_geom(s.M, padded_dim(s.d));
     const int BH = s.B * s.H;
     const float c2 = scale * kLog2e;
     const dim3 grid(p.enc.chunks, BH);
@@ -1314,11 +1374,21 @@ int mfma_dz_partial(const flare_shape &s, const void *q, const void *k, const vo
     encode_mfma_kernel<DD, NBB, 2, 1><<<grid, e.threads, 0, stream>>>(qq, kk, gg, lse_dec2, ld_mul, (const bf16_t *)y, delta_out, ld_range, nullptr, nullptr, dz_part, \
                                                                       tok_stride(s), s.H, s.N, s.M, p.enc.chunk_len, p.parts, e.G,  \
                                                                       e.TG, c2)
-    if (s.d == 16 && e.NB == 1) FLARE_DZ(16, 1);
-    else if (s.d == 16 && e.NB == 2) FLARE_DZ(16, 2);
-    else if (s.d == 16) FLARE_DZ(16, 4);
-    else if (e.NB == 1) FLARE_DZ(32, 1);
-    else FLARE_DZ(32, 2);
+#define FLARE_DZ_NB(DD)                   \
+    do {                                  \
+        if (e.NB == 1) FLARE_DZ(DD, 1);   \
+        else if (e.NB == 2) FLARE_DZ(DD, 2); \
+        else FLARE_DZ(DD, 4);             \
+    } while (0)
+    switch (s.d) {
+        case 4: FLARE_DZ_NB(4); break;
+        case 8: FLARE_DZ_NB(8); break;
+        case 16: FLARE_DZ_NB(16); break;
+        default:
+            if (e.NB == 1) FLARE_DZ(32, 1);
+            else FLARE_DZ(32, 2);
+    }
+#undef FLARE_DZ_NB
 #undef FLARE_DZ
     return check_launch();
 }
@@ -1330,7 +1400,7 @@ int mfma_dq_partial(const flare_shape &s, const void *q, const void *k, const vo
                     float *dq_part, float scale, hipStream_t stream)
 {
     const MfmaPlan p = mfma_plan(s);
-    EncGeom e = enc_geom(s.M, s.d);
+    EncGeom e = enc_geom(s.M, padded_dim(s.d));
     if (e.NB == 4) {   // this kernel keeps more operands per latent tile: two tiles per wave at most
         e.NB = 2;
         e.G = s.M / 64;
@@ -1354,10 +1424,20 @@ int mfma_dq_partial(const flare_shape &s, const void *q, const void *k, const vo
                 qq, kk, vv, gg, z, lse_enc, dz, eps, lse_dec2, delta, ld_mul, plan, dq_part, tok_stride(s), s.H, \
                 s.N, s.M, p.enc.chunk_len, parts, e.G, e.TG, c2);                                                \
     } while (0)
-    if (s.d == 16 && e.NB == 1) FLARE_DQ(16, 1, 2);
-    else if (s.d == 16) FLARE_DQ(16, 2, 2);
-    else if (e.NB == 1) FLARE_DQ(32, 1, 2);
-    else FLARE_DQ(32, 2, 1);
+#define FLARE_DQ_NB(DD)                      \
+    do {                                     \
+        if (e.NB == 1) FLARE_DQ(DD, 1, 2);   \
+        else FLARE_DQ(DD, 2, 2);             \
+    } while (0)
+    switch (s.d) {
+        case 4: FLARE_DQ_NB(4); break;
+        case 8: FLARE_DQ_NB(8); break;
+        case 16: FLARE_DQ_NB(16); break;
+        default:
+            if (e.NB == 1) FLARE_DQ(32, 1, 2);
+            else FLARE_DQ(32, 2, 1);
+    }
+#undef FLARE_DQ_NB
 #undef FLARE_DQ
     return check_launch();
 }
@@ -1382,8 +1462,9 @@ int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v,
     const dim3 grid(blocks, BH);
     const float c2 = scale * kLog2e;
     const int MT = s.M / 32;
-    const bool lo2 = (s.d == 16);
-    const int KS = s.d / 16, HV = s.d / 16;
+    const int pd = padded_dim(s.d);
+    const bool lo2 = (pd == 16);
+    const int KS = pd / 16, HV = pd / 16;
     const size_t lds = (size_t)MT * ((lo2 ? 6 : 4) * KS + 1 + 4 * HV) * 1024;
     const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *vv = (const bf16_t *)v, *gg = (const bf16_t *)dy;
     LaunchTimer t(one_exp ? KID_BWD_DKDV : KID_BWD_DKDV_2EXP, stream);
@@ -1396,14 +1477,20 @@ int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v,
         kern<<<grid, 512, lds, stream>>>(qq, kk, vv, gg, z, lse_enc, dz, eps, lse_dec2, delta, ld_mul, plan,     \
                                          (bf16_t *)dk, (bf16_t *)dv, tok_stride(s), s.H, s.N, c2, scale);        \
     } while (0)
-    if (s.d == 16) {
-        switch (MT) {
-            case 1: FLARE_DKDV(16, 1, true); break;
-            case 2: FLARE_DKDV(16, 2, true); break;
-            case 4: FLARE_DKDV(16, 4, true); break;
-            case 8: FLARE_DKDV(16, 8, true); break;
-            default: return FLARE_EUNSUPPORTED;
-        }
+#define FLARE_DKDV_MT(DD)                              \
+    switch (MT) {                                      \
+        case 1: FLARE_DKDV(DD, 1, true); break;        \
+        case 2: FLARE_DKDV(DD, 2, true); break;        \
+        case 4: FLARE_DKDV(DD, 4, true); break;        \
+        case 8: FLARE_DKDV(DD, 8, true); break;        \
+        default: return FLARE_EUNSUPPORTED;            \
+    }
+    if (s.d == 4) {
+        FLARE_DKDV_MT(4)
+    } else if (s.d == 8) {
+        FLARE_DKDV_MT(8)
+    } else if (s.d == 16) {
+        FLARE_DKDV_MT(16)
     } else {
         switch (MT) {
             case 1: FLARE_DKDV(32, 1, false); break;
@@ -1478,7 +1565,7 @@ int mfma_bwd_plan(const flare_shape &s, const float *ld_range, const float *lse_
 int mfma_dq_parts(const flare_shape &s)
 {
     const MfmaPlan p = mfma_plan(s);
-    EncGeom e = enc_geom(s.M, s.d);
+    EncGeom e = enc_geom(s.M, padded_dim(s.d));
     if (e.NB == 4) {
         e.G = s.M / 64;
         e.TG = (e.G == 3) ? 1 : 4 / e.G;
@@ -1503,7 +1590,20 @@ static int launch_decode_family(const flare_shape &s, const void *q, const void 
     decode_mfma_kernel<DD, MTT, PREE, MINB, MODE><<<grid, 256, 0, stream>>>(qq, kk, z, yy, gg, lse_dec2, delta,      \
                                                                             tok_stride(s), s.H, s.N, c2)
     const int MT = s.M / 32;
-    if (s.d == 16) {
+#define FLARE_DEC_MT(DD)                               \
+    switch (MT) {                                      \
+        case 1: FLARE_DEC(DD, 1, true, 2); break;      \
+        case 2: FLARE_DEC(DD, 2, true, 2); break;      \
+        case 4: FLARE_DEC(DD, 4, true, 2); break;      \
+        case 6: FLARE_DEC(DD, 6, true, 2); break;      \
+        case 8: FLARE_DEC(DD, 8, true, 2); break;      \
+        default: return FLARE_EUNSUPPORTED;            \
+    }
+    if (s.d == 4) {
+        FLARE_DEC_MT(4)
+    } else if (s.d == 8) {
+        FLARE_DEC_MT(8)
+    } else if (s.d == 16) {
         switch (MT) {
             case 1: FLARE_DEC(16, 1, true, 2); break;
             case 2: FLARE_DEC(16, 2, true, 2); break;

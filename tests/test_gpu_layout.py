@@ -33,6 +33,8 @@ CASES = [
     (4, dict(N=5003)),              # d=16, M=256
     (5, dict(N=2001)),              # d=32, M=256
     (4, dict(N=33, H=3)),           # odd head count, two tiles
+    (2, dict(B=1, N=1200, d=8)),    # matrix-core path with the head dimension padded to 16
+    (4, dict(N=700, d=4, H=4)),
 ]
 
 

@@ -163,6 +163,31 @@ def test_edge_shapes_forward_backward(oracle, shape, dtype):
         assert slice_relerr(to_host(y), inp["v"]) <= (1e-6 if dtype == "f32" else 4e-3)
 
 
+# Head dimensions below 16 on the matrix-core path (contraction padded to 16): the regime of the paper's
+# PDE models (C = 64, H = 8, so D = 8; Section 5 and Appendix G settings) and of its D = 4 ablation.
+SMALL_D_SHAPES = [
+    # B, H, N, M, d
+    (1, 2, 1000, 64, 8),
+    (2, 1, 777, 256, 8),
+    (1, 3, 515, 128, 8),
+    (1, 2, 2049, 32, 8),
+    (1, 1, 999, 192, 8),      # three latent groups; dK/dV on the vector path
+    (1, 2, 1000, 64, 4),
+    (1, 2, 333, 256, 4),
+    (2, 2, 65, 128, 4),
+]
+
+
+@pytest.mark.parametrize("shape", SMALL_D_SHAPES)
+def test_small_head_dims_matrix_core_path(oracle, shape):
+    B, H, N, M, d = shape
+    _say("small d %s bf16" % (shape,))
+    inp = synth.make_inputs(2, B=B, H=H, N=N, M=M, d=d, dtype="bf16", with_dy=True, seed=4321 + N + M + d)
+    _forward_case(oracle, inp)
+    _backward_case(oracle, inp, saved=False)
+    _backward_case(oracle, inp, saved=True)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_sharp_softmax_stress(oracle, dtype):
     """Scores eight times larger: nearly one-hot softmaxes, the running max moves a lot."""
