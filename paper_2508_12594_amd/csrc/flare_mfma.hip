@@ -77,16 +77,22 @@ __device__ __forceinline__ void exp_pack(const f32x16 &dlt, bf16x8 &p0, bf16x8 &
 {
     u32x4 w0, w1;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        w0[i] = cvt_pk_bf16(fast_exp2(dlt[2 * i]), fast_exp2(dlt[2 * i + 1]));
-        w1[i] = cvt_pk_bf16(fast_exp2(dlt[8 + 2 * i]), fast_exp2(dlt[8 + 2 * i + 1]));
-    }
+    for (int i = 0; i < 4; ++i) w0[i] = cvt_pk_bf16(fast_exp2(dlt[2 * i]), fast_exp2(dlt[2 * i + 1]));
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w1[i] = cvt_pk_bf16(fast_exp2(dlt[8 + 2 * i]), fast_exp2(dlt[8 + 2 * i + 1]));
     p0 = as_bf16x8(w0);
     p1 = as_bf16x8(w1);
 }
 // Nothing may be scheduled across this point: keeps the matrix-core work of the next tile issued
 // ahead of the vector work of the current one.
 __device__ __forceinline__ void sched_fence() { __builtin_amdgcn_sched_barrier(0); }
+// Ask the scheduler for the next group of `n` instructions of one class, in the order the requests are
+// written (classes: matrix, transcendental, other vector ALU).  Used to spread the matrix
+// instructions of a tile between its vector instructions, so that the matrix pipe (32 clocks per
+// instruction) never blocks the wave's issue.
+#define FLARE_GROUP_MFMA(n) __builtin_amdgcn_sched_group_barrier(0x008, n, 0)
+#define FLARE_GROUP_TRANS(n) __builtin_amdgcn_sched_group_barrier(0x400, n, 0)
+#define FLARE_GROUP_VALU(n) __builtin_amdgcn_sched_group_barrier(0x002, n, 0)
 
 // Contraction slot (8*hh + i) of k-step s2 (0 or 1) of a 32-wide tile maps to this index within
 // the tile: the row that accumulator register 8*s2 + i holds.
@@ -314,10 +320,11 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
 #pragma unroll
         for (int hv = 0; hv < HV; ++hv) acc[hv] = splat16(0.f);
         s_cur = qk_full(0);
+        sched_fence();
 #pragma unroll
         for (int t = 0; t < MT; ++t) {
             if (t + 1 < MT) s_next = qk_full(t + 1);
-            sched_fence();
+            if constexpr (!(PRE && D == 16)) sched_fence();
             if constexpr (!PRE) {
 #pragma unroll
                 for (int i = 0; i < 16; ++i) s_cur[i] = fmaf(s_cur[i], ac2, -b2);
@@ -328,6 +335,29 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
             for (int hv = 0; hv < HV; ++hv) {
                 acc[hv] = mfma(zt[hv][2 * t], p0, acc[hv]);
                 acc[hv] = mfma(zt[hv][2 * t + 1], p1, acc[hv]);
+            }
+            if constexpr (PRE && D == 16) {
+                // order within the tile: the two score products of tile t+1 and the two value products of
+                // tile t, each followed by a share of the 16 exponentials and 8 packs of tile t
+                if (t + 1 < MT) {
+                    FLARE_GROUP_TRANS(4);
+                    FLARE_GROUP_MFMA(1);
+                    FLARE_GROUP_TRANS(4);
+                    FLARE_GROUP_MFMA(1);
+                    FLARE_GROUP_VALU(4);
+                    FLARE_GROUP_TRANS(4);
+                    FLARE_GROUP_MFMA(1);
+                    FLARE_GROUP_TRANS(4);
+                    FLARE_GROUP_VALU(4);
+                    FLARE_GROUP_MFMA(1);
+                } else {
+                    FLARE_GROUP_TRANS(8);
+                    FLARE_GROUP_VALU(4);
+                    FLARE_GROUP_MFMA(1);
+                    FLARE_GROUP_TRANS(8);
+                    FLARE_GROUP_VALU(4);
+                    FLARE_GROUP_MFMA(1);
+                }
             }
             sched_fence();
             s_cur = s_next;
