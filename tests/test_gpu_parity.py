@@ -261,6 +261,24 @@ def test_backward_wide_score_range_picks_variant_per_head(oracle):
             assert e["dk"] <= (TOL["bf16"] if h == 0 else 1e-1)
 
 
+@pytest.mark.parametrize("M,d", [(64, 16), (256, 16), (128, 32), (256, 32), (64, 8)])
+def test_keys_huge_where_every_latent_is_zero(oracle, M, d):
+    """Every other token has a key that is huge in the dimensions where all latent queries are zero: the
+    norms |q_m| |k_n| are hundreds of log2 units above the scores themselves, so any stabiliser derived
+    from norms rather than from the scores would underflow every weight of those tokens."""
+    _say("huge orthogonal keys M=%d d=%d" % (M, d))
+    inp = synth.make_inputs(1, B=1, H=2, N=1111, M=M, d=d, dtype="bf16", with_dy=True, seed=77 + M + d)
+    q, k = inp["q"].copy(), inp["k"].copy()
+    q[..., d // 2:] = 0.0
+    q[..., :d // 2] *= 6.0
+    k[:, :, ::2, d // 2:] = 300.0
+    k[:, :, 5::64, d // 2:] = -250.0          # and a few lone tokens elsewhere in a tile
+    inp["q"], inp["k"] = synth.bf16_round(q), synth.bf16_round(k)
+    _forward_case(oracle, inp)
+    _backward_case(oracle, inp, saved=False)
+    _backward_case(oracle, inp, saved=True)
+
+
 def test_constant_v_gives_constant_y():
     import torch
     inp = synth.make_inputs(2, B=1, N=2000, with_dy=False)
