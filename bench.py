@@ -171,6 +171,9 @@ def main():
         mean_s = ms / cnt * 1e-3
         ab = algorithmic_bytes(name, B, H, N, M, d, elem)
         ex = exponentials(name, B, H, N, M)
+        twin = name[:-5] if name.endswith("_2exp") else name + "_2exp"
+        if twin in prof and ms / cnt < 0.05 * prof[twin][0] / prof[twin][1]:
+            ab, ex = None, 0     # launched, but every (b,h) slice went to the other variant: it left at once
         kernels[name] = {"mean_us": round(mean_s * 1e6, 2), "launches_per_step": cnt // args.steps,
                          "algorithmic_GBps": (round(ab / mean_s / 1e9, 1) if ab else None),
                          "hbm_frac": (round(ab / mean_s / 1e9 / HBM_PEAK_GBS, 4) if ab else None),
