@@ -29,8 +29,9 @@
  *     elements (d, or H*d for FLARE_BNHD) below 2^32; d in {4, 8, 16, 32}; dtype f32 or bf16;
  *     either flare_layout for the token tensors (every "[B][H][N][d]" below reads [B][N][H][d]
  *     when shape->layout is FLARE_BNHD; the per-token statistic lse_dec is [B][H][N] always).
- *     Shapes with dtype bf16, d in {16,32} and M = 32 or a multiple of 64 up to 256 run on the
- *     matrix-core kernels; everything else runs on the fp32 vector kernels.
+ *     Shapes with dtype bf16 and M = 32, a multiple of 64 up to 256, or a multiple of 256 up to
+ *     2048 run on the matrix-core kernels (d < 16 with the contraction padded to 16; M > 256 in
+ *     chunks of 256 latents); everything else runs on the fp32 vector kernels.
  *   - Results are bit-identical from run to run for the same inputs and shape (no float atomics;
  *     every cross-block reduction is done in a fixed order).
  *   - Non-finite inputs give undefined results.
@@ -81,8 +82,9 @@ int flare_version(void);
 /* Static, NUL-terminated description of a flare_status value. */
 const char *flare_strerror(int status);
 
-/* Scratch bytes that flare_forward / flare_encode (fwd_bytes) and flare_backward (bwd_bytes)
- * need for this shape.  Either output pointer may be NULL.  Host-only; touches no device. */
+/* Scratch bytes that flare_forward / flare_encode / flare_decode (fwd_bytes) and flare_backward
+ * (bwd_bytes) need for this shape.  Either output pointer may be NULL.  Host-only; touches no
+ * device. */
 int flare_workspace_bytes(const flare_shape *shape, size_t *fwd_bytes, size_t *bwd_bytes);
 
 /*
@@ -98,13 +100,15 @@ int flare_encode(const flare_shape *shape, const void *q_lat, const void *k, con
 
 /*
  * Decode (Eq. flare_decode; Appendix E, per-token form of y_n): per-token softmax over the M
- * latents applied to Z.  Needs no workspace.
+ * latents applied to Z.  Only matrix-core shapes with M > 256 use the workspace (per-chunk partial
+ * results, merged in chunk order); for all others it may be NULL.
  *   q_lat [H][M][d] dtype, k [B][H][N][d] dtype, z [B][H][M][d] fp32        (in)
  *   y [B][H][N][d] dtype                                                    (out)
  *   lse_dec [B][H][N] fp32: log sum_m exp(S[m][n]), natural log; may be NULL (out, optional)
  */
 int flare_decode(const flare_shape *shape, const void *q_lat, const void *k, const float *z,
-                 void *y, float *lse_dec, float scale, void *stream);
+                 void *y, float *lse_dec, float scale,
+                 void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Forward of the mixer = flare_encode then flare_decode on the same stream (listing in

@@ -50,7 +50,7 @@ def load():
     lib.flare_strerror.argtypes = [ctypes.c_int]
     lib.flare_workspace_bytes.argtypes = [sp, ctypes.POINTER(ctypes.c_size_t), ctypes.POINTER(ctypes.c_size_t)]
     lib.flare_encode.argtypes = [sp, vp, vp, vp, fp, fp, ctypes.c_float, vp, ctypes.c_size_t, vp]
-    lib.flare_decode.argtypes = [sp, vp, vp, fp, vp, fp, ctypes.c_float, vp]
+    lib.flare_decode.argtypes = [sp, vp, vp, fp, vp, fp, ctypes.c_float, vp, ctypes.c_size_t, vp]
     lib.flare_forward.argtypes = [sp, vp, vp, vp, vp, fp, fp, fp, ctypes.c_float, vp, ctypes.c_size_t, vp]
     lib.flare_backward.argtypes = [sp, vp, vp, vp, vp, fp, vp, fp, fp, fp, vp, vp, ctypes.c_float, vp,
                                    ctypes.c_size_t, vp]
@@ -167,16 +167,17 @@ def _opt_lse_dec(lse_dec, shp):
     return _dev(lse_dec, "lse_dec", torch.float32, (shp.B, shp.H, shp.N))
 
 
-def decode(q_lat, k, z, scale, y=None, lse_dec=None, stream=None, layout="bhnd"):
+def decode(q_lat, k, z, scale, y=None, lse_dec=None, workspace=None, stream=None, layout="bhnd"):
     """flare_decode: returns y (k's shape and dtype); fills lse_dec[B,H,N] (fp32) when given."""
     torch = _torch()
     shp = _shape_of(q_lat, k, layout)
     if y is None:
         y = torch.empty_like(k)
+    ws, ws_p, ws_n = _workspace(shp, "fwd", workspace, k.device)
     _check(load().flare_decode(ctypes.byref(shp), _dev(q_lat, "q_lat"), _dev(k, "k"),
                                _dev(z, "z", torch.float32, (shp.B, shp.H, shp.M, shp.d)),
                                _dev(y, "y", k.dtype, k.shape), _opt_lse_dec(lse_dec, shp),
-                               ctypes.c_float(scale), _stream(stream)),
+                               ctypes.c_float(scale), ws_p, ws_n, _stream(stream)),
            "flare_decode")
     return y
 

@@ -38,7 +38,7 @@ ProfileState g_prof;
 const char *const kKernelNames[KID_COUNT] = {
     "encode_partial", "encode_merge", "decode", "bwd_token_stats", "bwd_prep", "bwd_dz_partial",
     "bwd_dz_merge", "bwd_dq_partial", "bwd_dq_reduce", "bwd_dkdv", "bwd_plan", "bwd_dq_partial_2exp",
-    "bwd_dkdv_2exp"};
+    "bwd_dkdv_2exp", "decode_merge", "bwd_dkdv_finish"};
 }  // namespace
 
 LaunchTimer::LaunchTimer(int kid, hipStream_t s) : slot(-1), stream(s)
@@ -98,7 +98,13 @@ int flare_workspace_bytes(const flare_shape *shape, size_t *fwd_bytes, size_t *b
     const int rc = check_shape(shape);
     if (rc != FLARE_OK) return rc;
     const ValuPlan p = valu_plan(*shape);
-    if (fwd_bytes) *fwd_bytes = mfma_supported(*shape) ? mfma_fwd_bytes(*shape) : p.fwd_bytes;
+    if (fwd_bytes) {
+        *fwd_bytes = p.fwd_bytes;
+        if (mfma_supported(*shape)) {   // the encode's partials are dead when the decode starts: one region
+            *fwd_bytes = mfma_fwd_bytes(*shape);
+            if (mfma_tok_part_bytes(*shape) > *fwd_bytes) *fwd_bytes = mfma_tok_part_bytes(*shape);
+        }
+    }
     if (bwd_bytes) *bwd_bytes = p.bwd_bytes;
     return FLARE_OK;
 }
@@ -121,15 +127,19 @@ int flare_encode(const flare_shape *shape, const void *q_lat, const void *k, con
 }
 
 int flare_decode(const flare_shape *shape, const void *q_lat, const void *k, const float *z, void *y,
-                 float *lse_dec, float scale, void *stream)
+                 float *lse_dec, float scale, void *workspace, size_t workspace_bytes, void *stream)
 {
     int rc = check_shape(shape);
     if (rc != FLARE_OK) return rc;
     if (!q_lat || !k || !z || !y) return FLARE_EINVAL;
-    if (!aligned16(q_lat) || !aligned16(k) || !aligned16(z) || !aligned16(y) || !aligned16(lse_dec))
+    if (!aligned16(q_lat) || !aligned16(k) || !aligned16(z) || !aligned16(y) || !aligned16(lse_dec) ||
+        !aligned16(workspace))
         return FLARE_EALIGN;
-    if (mfma_supported(*shape))
-        return mfma_decode(*shape, q_lat, k, z, y, lse_dec, scale, static_cast<hipStream_t>(stream));
+    if (mfma_supported(*shape)) {
+        const size_t need = mfma_tok_part_bytes(*shape);
+        if (need != 0 && (!workspace || workspace_bytes < need)) return FLARE_EWORKSPACE;
+        return mfma_decode(*shape, q_lat, k, z, y, lse_dec, scale, workspace, static_cast<hipStream_t>(stream));
+    }
     return valu_decode(*shape, q_lat, k, z, y, lse_dec, scale, static_cast<hipStream_t>(stream));
 }
 
@@ -141,7 +151,7 @@ int flare_forward(const flare_shape *shape, const void *q_lat, const void *k, co
     if (!aligned16(y) || !aligned16(lse_dec)) return FLARE_EALIGN;
     int rc = flare_encode(shape, q_lat, k, v, z, lse_enc, scale, workspace, workspace_bytes, stream);
     if (rc != FLARE_OK) return rc;
-    return flare_decode(shape, q_lat, k, z, y, lse_dec, scale, stream);
+    return flare_decode(shape, q_lat, k, z, y, lse_dec, scale, workspace, workspace_bytes, stream);
 }
 
 int flare_backward(const flare_shape *shape, const void *q_lat, const void *k, const void *v,

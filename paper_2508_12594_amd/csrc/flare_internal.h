@@ -23,6 +23,8 @@ enum KernelId {
     KID_BWD_PLAN,
     KID_BWD_DQ_PARTIAL_2EXP,
     KID_BWD_DKDV_2EXP,
+    KID_DECODE_MERGE,
+    KID_BWD_DKDV_FINISH,
     KID_COUNT
 };
 
@@ -103,17 +105,24 @@ MfmaPlan mfma_plan(const flare_shape &s);
 size_t mfma_fwd_bytes(const flare_shape &s);
 int mfma_encode(const flare_shape &s, const void *q, const void *k, const void *v, float *z,
                 float *lse_enc, float scale, void *ws, hipStream_t stream);
+// Shapes with M > 256 run the token-major kernels once per chunk of 256 latents.  The decode and the
+// token statistics then need mfma_tok_part_bytes(s) of scratch (`ws`; unused and may be NULL
+// otherwise), the dK/dV step mfma_dkdv_acc_bytes(s) for its fp32 sums.
+size_t mfma_tok_part_bytes(const flare_shape &s);
+size_t mfma_dkdv_acc_bytes(const flare_shape &s);
 int mfma_decode(const flare_shape &s, const void *q, const void *k, const float *z, void *y,
-                float *lse_dec, float scale, hipStream_t stream);
+                float *lse_dec, float scale, void *ws, hipStream_t stream);
 int mfma_token_stats(const flare_shape &s, const void *q, const void *k, const float *z, const void *dy,
-                     float *lse_dec2, float *delta, float scale, hipStream_t stream);
+                     float *lse_dec2, float *delta, float scale, void *ws, hipStream_t stream);
 bool mfma_dkdv_supported(const flare_shape &s);
 // In the backward launchers below the per-token decode statistic is read as
 // ld_mul * lse_dec2[n]: pass the workspace array with ld_mul = 1, or the forward's natural-log
 // lse_dec with ld_mul = log2(e).
 int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy, const float *z,
               const float *lse_enc, const float *dz, const float *eps, const float *lse_dec2, const float *delta,
-              float ld_mul, const int *plan, bool one_exp, void *dk, void *dv, float scale, hipStream_t stream);
+              float ld_mul, const int *plan, bool one_exp, void *dk, void *dv, float *acc32, int m0, float scale,
+              hipStream_t stream);
+int mfma_dkdv_finish(const flare_shape &s, const float *acc32, void *dk, void *dv, hipStream_t stream);
 int mfma_dq_parts(const flare_shape &s);
 int mfma_dq_partial(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy,
                     const float *z, const float *lse_enc, const float *dz, const float *eps,

@@ -212,8 +212,11 @@ template <int DR, int MT, bool PRE, int MINB, int MODE>
 __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const float *__restrict__ z,
     bf16_t *__restrict__ y, const bf16_t *__restrict__ dy, float *__restrict__ lse_dec2,
-    float *__restrict__ delta, TokStride ts, int H, int N, float c2)
+    float *__restrict__ delta, TokStride ts, TokStride ts_y, int H, int N, int Mtot, int m0, float c2)
 {
+    // The kernel works on the latents m0 .. m0 + M of the head's Mtot (M = 32*MT of them); with
+    // Mtot > M its outputs are one chunk's partial result (y normalised within the chunk, lse_dec of
+    // the chunk) that decode_merge_kernel combines.  ts_y: where the rows of y go.
     constexpr int D = padded_dim(DR);
     constexpr int KS = D / 16;   // k-steps of the score product
     constexpr int HV = D / 16;   // 16-wide column groups of Z, each with its own ones row
@@ -227,12 +230,12 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
     bf16x8 qh[MT][KS], ql[MT][KS];
 #pragma unroll
     for (int t = 0; t < MT; ++t)
-        load_q_operand<DR, PRE>(q + ((size_t)h * M + 32 * t + l32) * DR, hh, c2, flip, qh[t], ql[t]);
+        load_q_operand<DR, PRE>(q + ((size_t)h * Mtot + m0 + 32 * t + l32) * DR, hh, c2, flip, qh[t], ql[t]);
 
     // Zaug^T operand: row l32 (< 16: column 16*hv + l32 of Z; 16: ones; else zero)
     bf16x8 zt[HV][2 * MT];
     {
-        const float *zb = z + (size_t)bh * M * DR;
+        const float *zb = z + ((size_t)bh * Mtot + m0) * DR;
 #pragma unroll
         for (int hv = 0; hv < HV; ++hv)
 #pragma unroll
@@ -254,7 +257,7 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
     }
 
     const bf16_t *kb = k + tok_base(ts, bh, H);
-    bf16_t *yb = y + tok_base(ts, bh, H);
+    bf16_t *yb = y + tok_base(ts_y, bh, H);
     const int tiles = (N + 31) / 32;
     const int stride = gridDim.x * 4;
     int tile = blockIdx.x * 4 + wave;
@@ -403,9 +406,9 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
                 w0[1] = cvt_pk_bf16(acc[hv][2] * inv, acc[hv][3] * inv);
                 w1[0] = cvt_pk_bf16(acc[hv][4] * inv, acc[hv][5] * inv);
                 w1[1] = cvt_pk_bf16(acc[hv][6] * inv, acc[hv][7] * inv);
-                if (quartet_inside<DR>(hv, hh, 0)) *reinterpret_cast<u32x2 *>(yb + tok_off(ts, n) + 16 * hv + 4 * hh) = w0;
+                if (quartet_inside<DR>(hv, hh, 0)) *reinterpret_cast<u32x2 *>(yb + tok_off(ts_y, n) + 16 * hv + 4 * hh) = w0;
                 if (quartet_inside<DR>(hv, hh, 1))
-                    *reinterpret_cast<u32x2 *>(yb + tok_off(ts, n) + 16 * hv + 8 + 4 * hh) = w1;
+                    *reinterpret_cast<u32x2 *>(yb + tok_off(ts_y, n) + 16 * hv + 8 + 4 * hh) = w1;
             }
         }
 #pragma unroll
@@ -427,6 +430,13 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
 // of the next token tile) are issued before the vector work on the current one.
 // Output per wave: (c, row sums, unnormalised O) for its latents = one partial slot.
 // ============================================================================================
+// More than 256 latents per head are taken 256 at a time: the latent-major kernels get one more grid
+// dimension (each workgroup owns one such chunk and streams the tokens again), the token-major ones
+// run once per chunk and a merge kernel combines the chunks.
+constexpr int kLatChunk = 256;
+inline int lat_eff(int M) { return M > kLatChunk ? kLatChunk : M; }
+inline int lat_chunks(int M) { return (M + kLatChunk - 1) / kLatChunk; }
+
 constexpr float kLazy = 16.f;   // the stabiliser moves when a score exceeds it by this much (log2 units)
 constexpr int kVtStride = 36;   // uint16 per LDS row: 32 tokens + 4 pad (72 B, conflict-free b64 reads)
 
@@ -469,7 +479,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         vt[BUF + (D + 1) * kVtStride + lane] = 0;
     }
 
-    const int lat0 = 32 * NB * g;
+    const int lat0 = kLatChunk * blockIdx.z + 32 * NB * g;
     bf16x8 qh[NB][KS], ql[NB][KS];
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
@@ -575,7 +585,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         else return 0.f;
     };
     // delta of the wave's j-th tile (j < cnt) from its dY and Y rows: two lanes per token
-    const bool do_delta = (MODE == 1) && y_tok != nullptr;
+    const bool do_delta = (MODE == 1) && y_tok != nullptr && blockIdx.z == 0;
     const bf16_t *yb = (MODE == 1 && y_tok != nullptr) ? y_tok + tok_base(ts, bh, H) : vb;
     auto load_y = [&](int j, u32x4 (&yy)[LOADS]) {
         const int nv = min(tile_tok0(j) + vtok, N - 1);
@@ -704,7 +714,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     // partial slot of this wave: (bh, chunk*TG + tg), latents lat0 .. lat0 + 32*NB
     if (tg >= TG) return;
     const size_t part = (size_t)bh * parts + (size_t)chunk * TG + tg;
-    if (MODE == 1 && ld_range != nullptr && g == 0) {
+    if (MODE == 1 && ld_range != nullptr && g == 0 && blockIdx.z == 0) {
 #pragma unroll
         for (int off = 1; off < 32; off <<= 1) {   // both lane halves hold the same tokens
             nl_min = fminf(nl_min, __shfl_xor(nl_min, off));
@@ -791,7 +801,7 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
     }
 
     // ---- per-latent operands ----
-    const int lat0 = 32 * NB * g;
+    const int lat0 = kLatChunk * blockIdx.z + 32 * NB * g;
     constexpr bool LO2 = (D == 16);             // carry lo terms of dZ and Z as well
     bf16x8 qh[NB][KS], ql[NB][KS], q_aug[NB], dzb[NB][KS], zb[NB][KS], dzl[NB][KS], zl[NB][KS], dz_aug[NB];
     bf16x8 u_aug[ONE ? NB : 1];
@@ -1047,8 +1057,12 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     const bf16_t *__restrict__ dy, const float *__restrict__ z, const float *__restrict__ lse_enc,
     const float *__restrict__ dz, const float *__restrict__ eps, const float *__restrict__ lse_dec2,
     const float *__restrict__ delta, float ld_mul, const int *__restrict__ plan, bf16_t *__restrict__ dk,
-    bf16_t *__restrict__ dv, TokStride ts, int H, int N, float c2, float scale)
+    bf16_t *__restrict__ dv, float *__restrict__ acc32, TokStride ts, int H, int N, int Mtot, int m0, float c2,
+    float scale)
 {
+    // The kernel works on the latents m0 .. m0 + M of the head's Mtot.  With acc32 given (more than one
+    // latent chunk) it adds its dV and dK rows in fp32 to acc32[0][b*h][n][DR] and acc32[1][...] (the
+    // chunk with m0 = 0 stores instead) and dkdv_finish_kernel rounds the sums to dk and dv.
     constexpr int D = padded_dim(DR);
     constexpr int KS = D / 16;
     constexpr int HV = D / 16;
@@ -1068,18 +1082,18 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     float kap = 0.f;
     if constexpr (ONE) {
         kap = -INFINITY;
-        for (int m = lane; m < M; m += 64) kap = fmaxf(kap, lse_enc[(size_t)bh * M + m] * kLog2e);
+        for (int m = lane; m < Mtot; m += 64) kap = fmaxf(kap, lse_enc[(size_t)bh * Mtot + m] * kLog2e);
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) kap = fmaxf(kap, __shfl_xor(kap, off));
     }
 
     // ---- build the operand images ----
     {
-        const bf16_t *qh_ = q + (size_t)h * M * DR;
-        const float *zb = z + (size_t)bh * M * DR;
-        const float *dzb = dz + (size_t)bh * M * DR;
-        const float *eb = eps + (size_t)bh * M;
-        const float *leb = lse_enc + (size_t)bh * M;
+        const bf16_t *qh_ = q + ((size_t)h * Mtot + m0) * DR;
+        const float *zb = z + ((size_t)bh * Mtot + m0) * DR;
+        const float *dzb = dz + ((size_t)bh * Mtot + m0) * DR;
+        const float *eb = eps + (size_t)bh * Mtot + m0;
+        const float *leb = lse_enc + (size_t)bh * Mtot + m0;
         for (int idx = tid; idx < MT * PER_TILE * 64; idx += 512) {
             const int ln = idx & 63, sid = (idx >> 6) % PER_TILE, t = (idx >> 6) / PER_TILE;
             const int r32 = ln & 31, hf = ln >> 5;
@@ -1271,7 +1285,32 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                 }
             }
         }
-        if (n < N) {
+        if (n < N && acc32 != nullptr) {
+            float *dvr = acc32 + ((size_t)bh * N + n) * DR;
+            float *dkr = dvr + (size_t)gridDim.y * N * DR;
+            const bool first = m0 == 0;
+#pragma unroll
+            for (int hv = 0; hv < HV; ++hv)
+#pragma unroll
+                for (int up = 0; up < 2; ++up) {
+                    if (!quartet_inside<DR>(hv, hh, up)) continue;
+                    const int o = 16 * hv + 8 * up + 4 * hh;
+                    float4 a = make_float4(acc1[hv][4 * up], acc1[hv][4 * up + 1], acc1[hv][4 * up + 2],
+                                           acc1[hv][4 * up + 3]);
+                    float4 b = make_float4(scale * (acc2[hv][4 * up] + acc1[hv][8 + 4 * up]),
+                                           scale * (acc2[hv][4 * up + 1] + acc1[hv][9 + 4 * up]),
+                                           scale * (acc2[hv][4 * up + 2] + acc1[hv][10 + 4 * up]),
+                                           scale * (acc2[hv][4 * up + 3] + acc1[hv][11 + 4 * up]));
+                    if (!first) {
+                        const float4 pa = *reinterpret_cast<const float4 *>(dvr + o);
+                        const float4 pb = *reinterpret_cast<const float4 *>(dkr + o);
+                        a.x += pa.x; a.y += pa.y; a.z += pa.z; a.w += pa.w;
+                        b.x += pb.x; b.y += pb.y; b.z += pb.z; b.w += pb.w;
+                    }
+                    *reinterpret_cast<float4 *>(dvr + o) = a;
+                    *reinterpret_cast<float4 *>(dkr + o) = b;
+                }
+        } else if (n < N) {
             bf16_t *dkr = dk + tok_base(ts, bh, H) + tok_off(ts, n);
             bf16_t *dvr = dv + tok_base(ts, bh, H) + tok_off(ts, n);
 #pragma unroll
@@ -1324,13 +1363,14 @@ bool mfma_supported(const flare_shape &s)
     if (s.dtype != FLARE_BF16) return false;
     if (s.d != 4 && s.d != 8 && s.d != 16 && s.d != 32) return false;   // d < 16 runs padded to 16
     if (s.M == 32) return true;
-    return s.M % 64 == 0 && s.M <= 256;
+    if (s.M > kLatChunk) return s.M % kLatChunk == 0 && s.M <= 2048;   // whole chunks of 256 latents
+    return s.M % 64 == 0;
 }
 
 MfmaPlan mfma_plan(const flare_shape &s)
 {
     MfmaPlan p;
-    const EncGeom e = enc_geom(s.M, padded_dim(s.d));
+    const EncGeom e = enc_geom(lat_eff(s.M), padded_dim(s.d));
     const int BH = s.B * s.H;
     // each chunk gives every token group at least 8 tiles of 32 tokens
     p.enc = plan_split(s.N, BH, 256 * e.TG, kEncodeTargetBlocks);
@@ -1351,7 +1391,7 @@ int mfma_encode(const flare_shape &s, const void *q, const void *k, const void *
                 float scale, void *ws, hipStream_t stream)
 {
     const MfmaPlan p = mfma_plan(s);
-    const EncGeom e = enc_geom(s.M, padded_dim(s.d));
+    const EncGeom e = enc_geom(lat_eff(s.M), padded_dim(s.d));
     Split sp;
     sp.chunks = p.parts;
     sp.chunk_len = 0;
@@ -1359,7 +1399,7 @@ int mfma_encode(const flare_shape &s, const void *q, const void *k, const void *
     valu_fwd_layout(s, sp, ws, &m_part, &l_part, &o_part);
     const int BH = s.B * s.H;
     const float c2 = scale * kLog2e;
-    const dim3 grid(p.enc.chunks, BH);
+    const dim3 grid(p.enc.chunks, BH, lat_chunks(s.M));
     const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *vv = (const bf16_t *)v;
     {
         LaunchTimer t(KID_ENCODE_PARTIAL, stream);
@@ -1394,10 +1434,10 @@ int mfma_dz_partial(const flare_shape &s, const void *q, const void *k, const vo
                     hipStream_t stream)
 {
     const MfmaPlan p = mfma_plan(s);
-    const EncGeom e = enc_geom(s.M, padded_dim(s.d));
+    const EncGeom e = enc_geom(lat_eff(s.M), padded_dim(s.d));
     const int BH = s.B * s.H;
     const float c2 = scale * kLog2e;
-    const dim3 grid(p.enc.chunks, BH);
+    const dim3 grid(p.enc.chunks, BH, lat_chunks(s.M));
     const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *gg = (const bf16_t *)dy;
     LaunchTimer t(KID_BWD_DZ_PARTIAL, stream);
 #define FLARE_DZ(DD, NBB)                                                                                      \
@@ -1430,17 +1470,17 @@ int mfma_dq_partial(const flare_shape &s, const void *q, const void *k, const vo
                     float *dq_part, float scale, hipStream_t stream)
 {
     const MfmaPlan p = mfma_plan(s);
-    EncGeom e = enc_geom(s.M, padded_dim(s.d));
+    EncGeom e = enc_geom(lat_eff(s.M), padded_dim(s.d));
     if (e.NB == 4) {   // this kernel keeps more operands per latent tile: two tiles per wave at most
         e.NB = 2;
-        e.G = s.M / 64;
+        e.G = lat_eff(s.M) / 64;
         e.TG = (e.G == 3) ? 1 : 4 / e.G;
         e.threads = 64 * e.G * e.TG;
     }
     const int BH = s.B * s.H;
     const float c2 = scale * kLog2e;
     const int parts = p.enc.chunks * e.TG;
-    const dim3 grid(p.enc.chunks, BH);
+    const dim3 grid(p.enc.chunks, BH, lat_chunks(s.M));
     const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *vv = (const bf16_t *)v, *gg = (const bf16_t *)dy;
     LaunchTimer t(one_exp ? KID_BWD_DQ_PARTIAL : KID_BWD_DQ_PARTIAL_2EXP, stream);
 #define FLARE_DQ(DD, NBB, MINB)                                                                                  \
@@ -1477,13 +1517,14 @@ int mfma_dq_partial(const flare_shape &s, const void *q, const void *k, const vo
 bool mfma_dkdv_supported(const flare_shape &s)
 {
     if (!mfma_supported(s)) return false;
-    const int MT = s.M / 32;
+    const int MT = lat_eff(s.M) / 32;
     return MT == 1 || MT == 2 || MT == 4 || MT == 8;
 }
 
 int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy, const float *z,
               const float *lse_enc, const float *dz, const float *eps, const float *lse_dec2, const float *delta,
-              float ld_mul, const int *plan, bool one_exp, void *dk, void *dv, float scale, hipStream_t stream)
+              float ld_mul, const int *plan, bool one_exp, void *dk, void *dv, float *acc32, int m0, float scale,
+              hipStream_t stream)
 {
     const int BH = s.B * s.H;
     const int tiles = (s.N + 31) / 32;
@@ -1491,7 +1532,7 @@ int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v,
     if (blocks > (tiles + 7) / 8) blocks = (tiles + 7) / 8;
     const dim3 grid(blocks, BH);
     const float c2 = scale * kLog2e;
-    const int MT = s.M / 32;
+    const int MT = lat_eff(s.M) / 32;
     const int pd = padded_dim(s.d);
     const bool lo2 = (pd == 16);
     const int KS = pd / 16, HV = pd / 16;
@@ -1505,7 +1546,8 @@ int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v,
                                 (int)lds) != hipSuccess)                                                         \
             return FLARE_ELAUNCH;                                                                                \
         kern<<<grid, 512, lds, stream>>>(qq, kk, vv, gg, z, lse_enc, dz, eps, lse_dec2, delta, ld_mul, plan,     \
-                                         (bf16_t *)dk, (bf16_t *)dv, tok_stride(s), s.H, s.N, c2, scale);        \
+                                         (bf16_t *)dk, (bf16_t *)dv, acc32, tok_stride(s), s.H, s.N, s.M, m0,    \
+                                         c2, scale);                                                             \
     } while (0)
 #define FLARE_DKDV_MT(DD)                              \
     switch (MT) {                                      \
@@ -1531,6 +1573,50 @@ int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v,
         }
     }
 #undef FLARE_DKDV
+    return check_launch();
+}
+
+// fp32 sums of the per-chunk dV and dK rows (M > 256) -> dk, dv in the caller's layout
+namespace {
+template <int DR>
+__global__ __launch_bounds__(256) void dkdv_finish_kernel(const float *__restrict__ acc32, bf16_t *__restrict__ dk,
+                                                          bf16_t *__restrict__ dv, TokStride ts, int H, int N)
+{
+    const int n = blockIdx.x * 256 + threadIdx.x;
+    if (n >= N) return;
+    const int bh = blockIdx.y;
+    const float *sv = acc32 + ((size_t)bh * N + n) * DR;
+    const float *sk = sv + (size_t)gridDim.y * N * DR;
+    const size_t trow = tok_base(ts, bh, H) + tok_off(ts, n);
+#pragma unroll
+    for (int j = 0; j < DR; j += 4) {
+        const float4 a = *reinterpret_cast<const float4 *>(sv + j);
+        const float4 b = *reinterpret_cast<const float4 *>(sk + j);
+        u32x2 wa, wb;
+        wa[0] = cvt_pk_bf16(a.x, a.y); wa[1] = cvt_pk_bf16(a.z, a.w);
+        wb[0] = cvt_pk_bf16(b.x, b.y); wb[1] = cvt_pk_bf16(b.z, b.w);
+        *reinterpret_cast<u32x2 *>(dv + trow + j) = wa;
+        *reinterpret_cast<u32x2 *>(dk + trow + j) = wb;
+    }
+}
+}  // namespace
+
+size_t mfma_dkdv_acc_bytes(const flare_shape &s)
+{
+    if (s.M <= kLatChunk) return 0;
+    return ((size_t)s.B * s.H * s.N * s.d * 4 * 2 + 255) & ~(size_t)255;
+}
+
+int mfma_dkdv_finish(const flare_shape &s, const float *acc32, void *dk, void *dv, hipStream_t stream)
+{
+    const dim3 grid((s.N + 255) / 256, s.B * s.H);
+    LaunchTimer t(KID_BWD_DKDV_FINISH, stream);
+    switch (s.d) {
+        case 4: dkdv_finish_kernel<4><<<grid, 256, 0, stream>>>(acc32, (bf16_t *)dk, (bf16_t *)dv, tok_stride(s), s.H, s.N); break;
+        case 8: dkdv_finish_kernel<8><<<grid, 256, 0, stream>>>(acc32, (bf16_t *)dk, (bf16_t *)dv, tok_stride(s), s.H, s.N); break;
+        case 16: dkdv_finish_kernel<16><<<grid, 256, 0, stream>>>(acc32, (bf16_t *)dk, (bf16_t *)dv, tok_stride(s), s.H, s.N); break;
+        default: dkdv_finish_kernel<32><<<grid, 256, 0, stream>>>(acc32, (bf16_t *)dk, (bf16_t *)dv, tok_stride(s), s.H, s.N); break;
+    }
     return check_launch();
 }
 
@@ -1595,9 +1681,9 @@ int mfma_bwd_plan(const flare_shape &s, const float *ld_range, const float *lse_
 int mfma_dq_parts(const flare_shape &s)
 {
     const MfmaPlan p = mfma_plan(s);
-    EncGeom e = enc_geom(s.M, padded_dim(s.d));
+    EncGeom e = enc_geom(lat_eff(s.M), padded_dim(s.d));
     if (e.NB == 4) {
-        e.G = s.M / 64;
+        e.G = lat_eff(s.M) / 64;
         e.TG = (e.G == 3) ? 1 : 4 / e.G;
     }
     return p.enc.chunks * e.TG;
@@ -1605,7 +1691,8 @@ int mfma_dq_parts(const flare_shape &s)
 
 template <int MODE>
 static int launch_decode_family(const flare_shape &s, const void *q, const void *k, const float *z, void *y,
-                                const void *dy, float *lse_dec2, float *delta, float scale, hipStream_t stream)
+                                TokStride ts_y, const void *dy, float *lse_dec2, float *delta, int m0, int Mc,
+                                float scale, hipStream_t stream)
 {
     const int BH = s.B * s.H;
     const int tiles = (s.N + 31) / 32;
@@ -1618,8 +1705,8 @@ static int launch_decode_family(const flare_shape &s, const void *q, const void 
     LaunchTimer t(MODE == 0 ? KID_DECODE : KID_BWD_TOKEN_STATS, stream);
 #define FLARE_DEC(DD, MTT, PREE, MINB)                                                                          \
     decode_mfma_kernel<DD, MTT, PREE, MINB, MODE><<<grid, 256, 0, stream>>>(qq, kk, z, yy, gg, lse_dec2, delta,      \
-                                                                            tok_stride(s), s.H, s.N, c2)
-    const int MT = s.M / 32;
+                                                                            tok_stride(s), ts_y, s.H, s.N, s.M, m0, c2)
+    const int MT = Mc / 32;
 #define FLARE_DEC_MT(DD)                               \
     switch (MT) {                                      \
         case 1: FLARE_DEC(DD, 1, true, 2); break;      \
@@ -1634,14 +1721,7 @@ static int launch_decode_family(const flare_shape &s, const void *q, const void 
     } else if (s.d == 8) {
         FLARE_DEC_MT(8)
     } else if (s.d == 16) {
-        switch (MT) {
-            case 1: FLARE_DEC(16, 1, true, 2); break;
-            case 2: FLARE_DEC(16, 2, true, 2); break;
-            case 4: FLARE_DEC(16, 4, true, 2); break;
-            case 6: FLARE_DEC(16, 6, true, 2); break;
-            case 8: FLARE_DEC(16, 8, true, 2); break;
-            default: return FLARE_EUNSUPPORTED;
-        }
+        FLARE_DEC_MT(16)
     } else {
         switch (MT) {
             case 1: FLARE_DEC(32, 1, true, 2); break;
@@ -1652,20 +1732,124 @@ static int launch_decode_family(const flare_shape &s, const void *q, const void 
             default: return FLARE_EUNSUPPORTED;
         }
     }
+#undef FLARE_DEC_MT
 #undef FLARE_DEC
     return check_launch();
 }
 
-int mfma_decode(const flare_shape &s, const void *q, const void *k, const float *z, void *y, float *lse_dec,
-                float scale, hipStream_t stream)
+namespace {
+// Combine the per-chunk results of the decode (M > 256): for token n of (b,h),
+//   lse = log sum_c exp(lse_c),   y = sum_c exp(lse_c - lse) y_c        (softmax over all M latents).
+// MODE 0 writes y in the caller's layout and, when asked, lse_dec (natural log);
+// MODE 1 writes lse_dec2 = lse * log2(e) and delta = <dY_n, y> with y kept in fp32.
+// thread = token; the partial rows are [chunk][b*h][n][DR] bf16, the partial lse [chunk][b*h][n].
+template <int DR, int MODE>
+__global__ __launch_bounds__(256) void decode_merge_kernel(
+    const bf16_t *__restrict__ y_part, const float *__restrict__ lse_part, int chunks, bf16_t *__restrict__ y,
+    const bf16_t *__restrict__ dy, float *__restrict__ lse_out, float *__restrict__ delta, TokStride ts, int H,
+    int N, size_t rows_all)
 {
-    return launch_decode_family<0>(s, q, k, z, y, nullptr, lse_dec, nullptr, scale, stream);
+    const int n = blockIdx.x * 256 + threadIdx.x;
+    if (n >= N) return;
+    const int bh = blockIdx.y;
+    const size_t row = (size_t)bh * N + n;
+    float mx = -INFINITY;
+    for (int c = 0; c < chunks; ++c) mx = fmaxf(mx, lse_part[(size_t)c * rows_all + row]);
+    float acc[DR], tot = 0.f;
+#pragma unroll
+    for (int j = 0; j < DR; ++j) acc[j] = 0.f;
+    for (int c = 0; c < chunks; ++c) {
+        const float w = __expf(lse_part[(size_t)c * rows_all + row] - mx);
+        tot += w;
+        const bf16_t *src = y_part + ((size_t)c * rows_all + row) * DR;
+#pragma unroll
+        for (int j = 0; j < DR; j += 4) {
+            const u32x2 t = *reinterpret_cast<const u32x2 *>(src + j);
+            acc[j] = fmaf(w, bf16_lo(t[0]), acc[j]);
+            acc[j + 1] = fmaf(w, bf16_hi(t[0]), acc[j + 1]);
+            acc[j + 2] = fmaf(w, bf16_lo(t[1]), acc[j + 2]);
+            acc[j + 3] = fmaf(w, bf16_hi(t[1]), acc[j + 3]);
+        }
+    }
+    const float inv = 1.f / tot;
+    const float lse = mx + __logf(tot);
+    const size_t trow = tok_base(ts, bh, H) + tok_off(ts, n);
+    if constexpr (MODE == 0) {
+#pragma unroll
+        for (int j = 0; j < DR; j += 4) {
+            u32x2 w;
+            w[0] = cvt_pk_bf16(acc[j] * inv, acc[j + 1] * inv);
+            w[1] = cvt_pk_bf16(acc[j + 2] * inv, acc[j + 3] * inv);
+            *reinterpret_cast<u32x2 *>(y + trow + j) = w;
+        }
+        if (lse_out) lse_out[row] = lse;
+    } else {
+        float dl = 0.f;
+#pragma unroll
+        for (int j = 0; j < DR; j += 4) {
+            const u32x2 g = *reinterpret_cast<const u32x2 *>(dy + trow + j);
+            dl = fmaf(acc[j] * inv, bf16_lo(g[0]), dl);
+            dl = fmaf(acc[j + 1] * inv, bf16_hi(g[0]), dl);
+            dl = fmaf(acc[j + 2] * inv, bf16_lo(g[1]), dl);
+            dl = fmaf(acc[j + 3] * inv, bf16_hi(g[1]), dl);
+        }
+        lse_out[row] = lse * kLog2e;
+        delta[row] = dl;
+    }
+}
+}  // namespace
+
+// bytes of the per-chunk partial results of the token-major forward kernels (0 when M <= 256)
+size_t mfma_tok_part_bytes(const flare_shape &s)
+{
+    if (s.M <= kLatChunk) return 0;
+    const size_t rows = (size_t)s.B * s.H * s.N * lat_chunks(s.M);
+    return ((rows * s.d * 2 + 255) & ~(size_t)255) + ((rows * 4 + 255) & ~(size_t)255);
+}
+
+// decode (MODE 0) or token statistics (MODE 1) over all latents, in chunks of 256 when there are more
+template <int MODE>
+static int decode_all(const flare_shape &s, const void *q, const void *k, const float *z, void *y, const void *dy,
+                      float *lse_out, float *delta, float scale, void *ws, hipStream_t stream)
+{
+    if (s.M <= kLatChunk)
+        return launch_decode_family<MODE>(s, q, k, z, y, tok_stride(s), dy, lse_out, delta, 0, s.M, scale, stream);
+    const int C = lat_chunks(s.M);
+    const size_t rows = (size_t)s.B * s.H * s.N;
+    bf16_t *y_part = static_cast<bf16_t *>(ws);
+    float *lse_part = reinterpret_cast<float *>(static_cast<char *>(ws) + ((rows * C * s.d * 2 + 255) & ~(size_t)255));
+    const TokStride tp{(long long)s.H * s.N * s.d, (long long)s.N * s.d, s.d};   // partial rows: [b][h][n][d]
+    for (int c = 0; c < C; ++c) {
+        const int rc = launch_decode_family<0>(s, q, k, z, y_part + (size_t)c * rows * s.d, tp, nullptr,
+                                               lse_part + (size_t)c * rows, nullptr, c * kLatChunk, kLatChunk, scale,
+                                               stream);
+        if (rc != FLARE_OK) return rc;
+    }
+    const dim3 grid((s.N + 255) / 256, s.B * s.H);
+    LaunchTimer t(KID_DECODE_MERGE, stream);
+#define FLARE_DM(DD)                                                                                           \
+    decode_merge_kernel<DD, MODE><<<grid, 256, 0, stream>>>(y_part, lse_part, C, (bf16_t *)y, (const bf16_t *)dy, \
+                                                            lse_out, delta, tok_stride(s), s.H, s.N, rows)
+    switch (s.d) {
+        case 4: FLARE_DM(4); break;
+        case 8: FLARE_DM(8); break;
+        case 16: FLARE_DM(16); break;
+        default: FLARE_DM(32); break;
+    }
+#undef FLARE_DM
+    return check_launch();
+}
+
+int mfma_decode(const flare_shape &s, const void *q, const void *k, const float *z, void *y, float *lse_dec,
+                float scale, void *ws, hipStream_t stream)
+{
+    return decode_all<0>(s, q, k, z, y, nullptr, lse_dec, nullptr, scale, ws, stream);
 }
 
 int mfma_token_stats(const flare_shape &s, const void *q, const void *k, const float *z, const void *dy,
-                     float *lse_dec2, float *delta, float scale, hipStream_t stream)
+                     float *lse_dec2, float *delta, float scale, void *ws, hipStream_t stream)
 {
-    return launch_decode_family<1>(s, q, k, z, nullptr, dy, lse_dec2, delta, scale, stream);
+    return decode_all<1>(s, q, k, z, nullptr, dy, lse_dec2, delta, scale, ws, stream);
 }
 
 }  // namespace flare

@@ -525,7 +525,7 @@ __global__ __launch_bounds__(kTokenBlock) void dkdv_kernel(
 // ---- workspace carving --------------------------------------------------------------------
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-struct BwdWs { float *lse_dec2, *delta, *part, *dz, *eps, *ld_range; int *plan; };
+struct BwdWs { float *lse_dec2, *delta, *part, *dz, *eps, *ld_range; int *plan; void *tok_part; float *acc32; };
 
 // `slots` = partial slots per (b,h) the shared partial buffer must hold
 size_t bwd_layout(const flare_shape &s, int slots, void *ws, BwdWs *out)
@@ -547,6 +547,15 @@ size_t bwd_layout(const flare_shape &s, int slots, void *ws, BwdWs *out)
     off += align256(BH * slots * 2 * 4);
     if (out) out->plan = reinterpret_cast<int *>(base + off);
     off += align256(BH * 4);
+    if (mfma_supported(s)) {   // only shapes with more than 256 latents on the matrix-core path use these
+        if (out) out->tok_part = base + off;
+        off += mfma_tok_part_bytes(s);
+        if (out) out->acc32 = reinterpret_cast<float *>(base + off);
+        off += mfma_dkdv_acc_bytes(s);
+    } else if (out) {
+        out->tok_part = nullptr;
+        out->acc32 = nullptr;
+    }
     return off;
 }
 
@@ -630,7 +639,7 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
         bwd_prep_kernel<T, D><<<(unsigned)((rows + 255) / 256), 256, 0, stream>>>(
             y, dy, lse_dec, w.lse_dec2, w.delta, s.layout == FLARE_BNHD, s.H, s.N, rows);
     } else if (mf) {
-        const int rc = mfma_token_stats(s, q, k, z, dy, w.lse_dec2, w.delta, scale, stream);
+        const int rc = mfma_token_stats(s, q, k, z, dy, w.lse_dec2, w.delta, scale, w.tok_part, stream);
         if (rc != FLARE_OK) return rc;
     } else {
         LaunchTimer t(KID_BWD_TOKEN_STATS, stream);
@@ -679,12 +688,14 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     }
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     if (mf && mfma_dkdv_supported(s)) {
-        for (int one = 1; one >= 0; --one) {
-            const int rc = mfma_dkdv(s, q, k, v, dy, z, lse_enc, w.dz, w.eps, ld, w.delta, ld_mul, w.plan, one != 0,
-                                     dk, dv, scale, stream);
-            if (rc != FLARE_OK) return rc;
-        }
-        return FLARE_OK;
+        const bool chunked = mfma_dkdv_acc_bytes(s) != 0;   // more than 256 latents: one pass per chunk
+        for (int m0 = 0; m0 < s.M; m0 += 256)
+            for (int one = 1; one >= 0; --one) {
+                const int rc = mfma_dkdv(s, q, k, v, dy, z, lse_enc, w.dz, w.eps, ld, w.delta, ld_mul, w.plan,
+                                         one != 0, dk, dv, chunked ? w.acc32 : nullptr, m0, scale, stream);
+                if (rc != FLARE_OK) return rc;
+            }
+        return chunked ? mfma_dkdv_finish(s, w.acc32, dk, dv, stream) : FLARE_OK;
     }
     {
         LaunchTimer t(KID_BWD_DKDV, stream);

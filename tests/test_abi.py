@@ -58,7 +58,7 @@ def test_null_and_misaligned_pointers_are_rejected(lib):
     assert lib.flare_forward(ctypes.byref(shp), p, p, p, p, p, p, odd, one, p, 1 << 20, None) == -3
     assert lib.flare_forward(ctypes.byref(shp), p, p, p, p, p, p, None, one, p, 16, None) == -4
     assert lib.flare_forward(ctypes.byref(shp), p, p, p, p, p, p, None, one, None, 0, None) == -4
-    assert lib.flare_decode(ctypes.byref(shp), p, p, None, p, None, one, None) == -1
+    assert lib.flare_decode(ctypes.byref(shp), p, p, None, p, None, one, None, 0, None) == -1
     assert lib.flare_backward(ctypes.byref(shp), p, p, p, None, None, None, p, p, p, p, p, one, p,
                               1 << 20, None) == -1
     assert lib.flare_backward(ctypes.byref(shp), p, p, p, None, None, p, p, p, p, p, p, one, p,

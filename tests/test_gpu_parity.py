@@ -188,6 +188,29 @@ def test_small_head_dims_matrix_core_path(oracle, shape):
     _backward_case(oracle, inp, saved=True)
 
 
+# More than 256 latents per head on the matrix-core path (chunks of 256 latents): the paper's
+# million-point model uses up to M = 2048 (Section 5, "Scalability"; Appendix G).
+LARGE_M_SHAPES = [
+    # B, H, N, M, d
+    (1, 2, 1500, 512, 16),
+    (2, 1, 700, 768, 16),
+    (1, 1, 1031, 1024, 8),
+    (1, 1, 300, 2048, 8),
+    (1, 2, 900, 512, 32),
+    (1, 1, 333, 1024, 4),
+]
+
+
+@pytest.mark.parametrize("shape", LARGE_M_SHAPES)
+def test_many_latents_matrix_core_path(oracle, shape):
+    B, H, N, M, d = shape
+    _say("large M %s bf16" % (shape,))
+    inp = synth.make_inputs(2, B=B, H=H, N=N, M=M, d=d, dtype="bf16", with_dy=True, seed=999 + N + M + d)
+    _forward_case(oracle, inp)
+    _backward_case(oracle, inp, saved=False)
+    _backward_case(oracle, inp, saved=True)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_sharp_softmax_stress(oracle, dtype):
     """Scores eight times larger: nearly one-hot softmaxes, the running max moves a lot."""
