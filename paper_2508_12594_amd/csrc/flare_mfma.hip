@@ -479,7 +479,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         vt[BUF + (D + 1) * kVtStride + lane] = 0;
     }
 
-    const int lat0 = kLatChunk * blockIdx.z + 32 * NB * g;
+    const int lat0 = 32 * NB * (G * (int)blockIdx.z + g);   // a workgroup owns NB*G tiles of latents
     bf16x8 qh[NB][KS], ql[NB][KS];
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
@@ -801,7 +801,7 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
     }
 
     // ---- per-latent operands ----
-    const int lat0 = kLatChunk * blockIdx.z + 32 * NB * g;
+    const int lat0 = 32 * NB * (G * (int)blockIdx.z + g);   // a workgroup owns NB*G tiles of latents
     constexpr bool LO2 = (D == 16);             // carry lo terms of dZ and Z as well
     bf16x8 qh[NB][KS], ql[NB][KS], q_aug[NB], dzb[NB][KS], zb[NB][KS], dzl[NB][KS], zl[NB][KS], dz_aug[NB];
     bf16x8 u_aug[ONE ? NB : 1];
@@ -1353,6 +1353,28 @@ EncGeom enc_geom(int M, int d)
     return e;
 }
 
+// Geometry of the dQ kernel, which keeps more operands per latent tile than the encode: at most two
+// tiles per wave, and at d = 32 one (two waves per SIMD then fit; a workgroup covers 128 latents and
+// the third grid dimension the rest).  *zdim = workgroups along the latents.
+EncGeom dq_geom(const flare_shape &s, int *zdim)
+{
+    const int Me = lat_eff(s.M);
+    EncGeom e = enc_geom(Me, padded_dim(s.d));
+    if (e.NB == 4) {
+        e.NB = 2;
+        e.G = Me / 64;
+        e.TG = (e.G == 3) ? 1 : 4 / e.G;
+    }
+    if (s.d == 32 && Me % 128 == 0) {
+        e.NB = 1;
+        e.G = 4;
+        e.TG = 1;
+    }
+    e.threads = 64 * e.G * e.TG;
+    *zdim = s.M / (32 * e.NB * e.G);
+    return e;
+}
+
 constexpr int kEncodeTargetBlocks = 512;   // two 4-wave workgroups per CU
 constexpr int kDecodeTargetBlocks = 512;
 
@@ -1470,17 +1492,12 @@ int mfma_dq_partial(const flare_shape &s, const void *q, const void *k, const vo
                     float *dq_part, float scale, hipStream_t stream)
 {
     const MfmaPlan p = mfma_plan(s);
-    EncGeom e = enc_geom(lat_eff(s.M), padded_dim(s.d));
-    if (e.NB == 4) {   // this kernel keeps more operands per latent tile: two tiles per wave at most
-        e.NB = 2;
-        e.G = lat_eff(s.M) / 64;
-        e.TG = (e.G == 3) ? 1 : 4 / e.G;
-        e.threads = 64 * e.G * e.TG;
-    }
+    int zdim;
+    const EncGeom e = dq_geom(s, &zdim);
     const int BH = s.B * s.H;
     const float c2 = scale * kLog2e;
     const int parts = p.enc.chunks * e.TG;
-    const dim3 grid(p.enc.chunks, BH, lat_chunks(s.M));
+    const dim3 grid(p.enc.chunks, BH, zdim);
     const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *vv = (const bf16_t *)v, *gg = (const bf16_t *)dy;
     LaunchTimer t(one_exp ? KID_BWD_DQ_PARTIAL : KID_BWD_DQ_PARTIAL_2EXP, stream);
 #define FLARE_DQ(DD, NBB, MINB)                                                                                  \
@@ -1681,12 +1698,8 @@ int mfma_bwd_plan(const flare_shape &s, const float *ld_range, const float *lse_
 int mfma_dq_parts(const flare_shape &s)
 {
     const MfmaPlan p = mfma_plan(s);
-    EncGeom e = enc_geom(lat_eff(s.M), padded_dim(s.d));
-    if (e.NB == 4) {
-        e.G = lat_eff(s.M) / 64;
-        e.TG = (e.G == 3) ? 1 : 4 / e.G;
-    }
-    return p.enc.chunks * e.TG;
+    int zdim;
+    return p.enc.chunks * dq_geom(s, &zdim).TG;
 }
 
 template <int MODE>
