@@ -131,3 +131,34 @@ def explicit_w(q_h, k_h, scale):
     if rc != 0:
         raise RuntimeError("flare_oracle_explicit_w failed: %d" % rc)
     return we, wd, w
+
+
+def spectral(q_h, k_h, scale):
+    """Eigenpairs of one head's mixing matrix W = W_dec W_enc from its M x M companion
+    (Appendix C.1, Algorithm 1), in the algorithm's own steps and notation, fp64 numpy:
+
+        A = exp(scale * Q K^T)                       (step 1; the stabiliser below cancels in J)
+        L_N = 1 / column sums of A,  L_M = 1 / row sums of A          (steps 2, 3)
+        J = L_M^(1/2) A L_N^(1/2)                                      (step 4)
+        U Sigma^2 U^T = J J^T                                          (step 5, numpy.linalg.eigh)
+        eigenvalues = Sigma^2, eigenvectors = L_N^(1/2) J^T U Sigma^(-1)  (steps 6, 7)
+
+    q_h[M,d], k_h[N,d] -> (eigenvalues[M] in descending order, gram = J J^T [M,M],
+    eigenvectors[N,M] with column j belonging to eigenvalue j).  Columns whose eigenvalue is below
+    1e-300 are returned as zeros (Sigma^(-1) does not exist there)."""
+    q_h, k_h = _f64(q_h), _f64(k_h)
+    s = float(scale) * (q_h @ k_h.T)
+    smax = s.max()
+    a = np.exp(s - smax)                    # A / exp(smax): the common factor cancels in J ...
+    l_n = 1.0 / a.sum(axis=0)
+    l_m = 1.0 / a.sum(axis=1)
+    j = np.sqrt(l_m)[:, None] * a * np.sqrt(l_n)[None, :]
+    l_n = l_n * np.exp(-smax)               # ... and is put back into L_N, which step 7 uses on its own
+    gram = j @ j.T
+    lam, u = np.linalg.eigh(gram)
+    order = np.argsort(lam)[::-1]
+    lam, u = lam[order], u[:, order]
+    ok = lam > 1e-300
+    inv_sigma = np.where(ok, 1.0 / np.sqrt(np.where(ok, lam, 1.0)), 0.0)
+    vec = np.sqrt(l_n)[:, None] * (j.T @ u) * inv_sigma[None, :]
+    return lam, gram, vec

@@ -100,6 +100,30 @@ def test_spectral_identity(oracle):
     assert _relerr(w @ vec, vec * lam[None, :]) < 1e-10
 
 
+def test_spectral_function_against_brute_force(oracle):
+    """oracle.spectral (Algorithm 1) against the dense N x N eigenproblem it avoids, with a scale that
+    is not 1, and against what a row-stochastic W fixes: eigenvalue 1 with a constant eigenvector."""
+    N, M, d = 41, 6, 4
+    q, k, _ = _rand(11, 1, 1, N, M, d)
+    scale = 0.7
+    lam, gram, vec = oracle.spectral(q[0], k[0, 0], scale)
+    _, _, w = oracle.explicit_w(q[0], k[0, 0], scale)
+    ev = np.linalg.eigvals(w)
+    assert np.abs(ev.imag).max() < 1e-10
+    ev = np.sort(ev.real)[::-1]
+    np.testing.assert_allclose(lam, ev[:M], rtol=1e-9, atol=1e-13)
+    assert np.all(np.diff(lam) <= 1e-15) and abs(lam[0] - 1.0) < 1e-12
+    assert np.allclose(gram, gram.T, atol=1e-15) and abs(np.trace(gram) - lam.sum()) < 1e-12
+    # W x = lambda x for every returned column, and the first column is constant
+    assert _relerr(w @ vec, vec * lam[None, :]) < 1e-9
+    assert np.ptp(vec[:, 0]) < 1e-10 * abs(vec[0, 0])
+    # the columns are the right singular vectors of J scaled by L_N^(1/2): V^T V = I
+    a = np.exp(scale * q[0] @ k[0, 0].T)
+    l_n = 1.0 / a.sum(axis=0)
+    v = vec / np.sqrt(l_n)[:, None]
+    assert np.abs(v.T @ v - np.eye(M)).max() < 1e-9
+
+
 def test_permutation_equivariance(oracle):
     q, k, v = _rand(4, 2, 2, 33, 8, 4)
     perm = np.random.default_rng(0).permutation(33)
