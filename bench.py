@@ -90,6 +90,8 @@ def main():
     ap.add_argument("--head-dim", type=int, default=None, help="override d (for quick checks only)")
     ap.add_argument("--layout", choices=["bhnd", "bnhd"], default="bhnd",
                     help="memory order of k, v, y, dy, dk, dv: [B,H,N,d] (default) or [B,N,H,d]")
+    ap.add_argument("--spectral", action="store_true",
+                    help="also time flare_spectral (Algorithm 1 of the paper) on the workload; reported apart")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run three plain device copies of k (known size) first, for scaling profiler counters")
@@ -221,6 +223,23 @@ def main():
         "ms_per_step_with_events": round(t_step_prof * 1e3, 4),
         "roofline": roofline, "kernels": kernels,
     }
+
+    if args.spectral:     # not part of the step: the eigen-analysis of the same heads, from what the forward saved
+        fwd()
+        binding.spectral(dev["q"], dev["k"], lse, lse_dec, scale, layout=lay)      # warm-up
+        binding.profile_enable(True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        binding.spectral(dev["q"], dev["k"], lse, lse_dec, scale, layout=lay)
+        torch.cuda.synchronize()
+        t_sp = time.perf_counter() - t0
+        prof_sp = binding.profile_read()
+        binding.profile_enable(False)
+        out["spectral"] = {"ms": round(t_sp * 1e3, 3),
+                           "kernels_us": {n: round(ms / cnt * 1e3, 1) for n, (ms, cnt) in prof_sp.items()
+                                          if n.startswith("spectral")},
+                           "gram_exp_frac": round(B * H * N * M / (prof_sp["spectral_gram"][0] * 1e-3)
+                                                  / 1e9 / EXP_PEAK_GOPS, 4)}
 
     if not args.no_cpu_baseline:
         from oracle import flare_oracle

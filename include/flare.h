@@ -142,6 +142,27 @@ int flare_backward(const flare_shape *shape, const void *q_lat, const void *k, c
                    void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Eigenpairs of the mixing matrix W = W_decode W_encode (N x N, rank <= M) of every (b,h) without
+ * forming it (Appendix C.1 "Eigenanalysis procedure", Algorithm 1): with A = exp(S),
+ * L_M = 1 / row sums, L_N = 1 / column sums and J = L_M^(1/2) A L_N^(1/2), the nonzero eigenvalues
+ * of W are those of the M x M matrix J J^T = U Sigma^2 U^T and its eigenvectors are
+ * L_N^(1/2) J^T U Sigma^(-1) = W_decode (L_M^(1/2) U Sigma^(-1)).  The library forms J J^T in one
+ * pass over the tokens, diagonalises it on the device (cyclic Jacobi in fp64) and returns
+ *   eigenvalues [B][H][M] fp32, in descending order                                   (out)
+ *   z_vec [B][H][M][d] fp32 = L_M^(1/2) U Sigma^(-1) restricted to the eigenvectors number
+ *         first .. first + d - 1 (zero beyond M or where the eigenvalue is not positive): passed
+ *         as `z` to flare_decode it yields those d eigenvectors of W, one per column of y   (out)
+ *   gram [B][H][M][M] fp32 = J J^T; may be NULL                                       (out, optional)
+ *   q_lat, k as in the forward; lse_enc, lse_dec: what flare_forward wrote             (in)
+ * Supported for M <= 512.  flare_spectral_workspace_bytes gives the scratch size.  Eigenvectors
+ * are defined up to sign (and up to rotation within a repeated eigenvalue).
+ */
+int flare_spectral_workspace_bytes(const flare_shape *shape, size_t *bytes);
+int flare_spectral(const flare_shape *shape, const void *q_lat, const void *k, const float *lse_enc,
+                   const float *lse_dec, float scale, int first, float *eigenvalues, float *z_vec,
+                   float *gram, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Per-kernel timing for measurement (not part of the operator).  While enabled, every kernel
  * the library launches is bracketed by a pair of HIP events recorded on the launch stream.
  * flare_profile_enable(1) creates the event pool (the only allocation this library makes) and

@@ -19,7 +19,7 @@ LAYOUTS = {"bhnd": FLARE_BHND, "bnhd": FLARE_BNHD}
 EXPORTS = [
     "flare_version", "flare_strerror", "flare_workspace_bytes", "flare_encode", "flare_decode",
     "flare_forward", "flare_backward", "flare_profile_enable", "flare_profile_kernels",
-    "flare_profile_name", "flare_profile_read",
+    "flare_profile_name", "flare_profile_read", "flare_spectral_workspace_bytes", "flare_spectral",
 ]
 
 
@@ -54,11 +54,13 @@ def load():
     lib.flare_forward.argtypes = [sp, vp, vp, vp, vp, fp, fp, fp, ctypes.c_float, vp, ctypes.c_size_t, vp]
     lib.flare_backward.argtypes = [sp, vp, vp, vp, vp, fp, vp, fp, fp, fp, vp, vp, ctypes.c_float, vp,
                                    ctypes.c_size_t, vp]
+    lib.flare_spectral_workspace_bytes.argtypes = [sp, ctypes.POINTER(ctypes.c_size_t)]
+    lib.flare_spectral.argtypes = [sp, vp, vp, fp, fp, ctypes.c_float, ctypes.c_int, fp, fp, fp, vp, ctypes.c_size_t, vp]
     lib.flare_profile_enable.argtypes = [ctypes.c_int]
     lib.flare_profile_name.restype = ctypes.c_char_p
     lib.flare_profile_name.argtypes = [ctypes.c_int]
     lib.flare_profile_read.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
-    for name in ("flare_workspace_bytes", "flare_encode", "flare_decode", "flare_forward", "flare_backward",
+    for name in ("flare_spectral_workspace_bytes", "flare_spectral", "flare_workspace_bytes", "flare_encode", "flare_decode", "flare_forward", "flare_backward",
                  "flare_profile_enable", "flare_profile_kernels", "flare_profile_read"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -229,6 +231,28 @@ def backward(q_lat, k, v, dy, z, lse_enc, scale, y=None, lse_dec=None, dq_lat=No
                                  _dev(dk, "dk", k.dtype, k.shape), _dev(dv, "dv", k.dtype, k.shape),
                                  ctypes.c_float(scale), ws_p, ws_n, _stream(stream)), "flare_backward")
     return dq_lat, dk, dv
+
+
+def spectral(q_lat, k, lse_enc, lse_dec, scale, first=0, want_gram=False, stream=None, layout="bhnd"):
+    """flare_spectral: returns (eigenvalues[B,H,M] descending, z_vec[B,H,M,d], gram[B,H,M,M] or None).
+
+    decode(q_lat, k, z_vec, scale) then gives the eigenvectors number first .. first+d-1 of W."""
+    torch = _torch()
+    shp = _shape_of(q_lat, k, layout)
+    need = ctypes.c_size_t(0)
+    _check(load().flare_spectral_workspace_bytes(ctypes.byref(shp), ctypes.byref(need)), "flare_spectral_workspace_bytes")
+    ws = torch.empty(max(int(need.value), 256), dtype=torch.uint8, device=k.device)
+    ev = torch.empty((shp.B, shp.H, shp.M), dtype=torch.float32, device=k.device)
+    zv = torch.empty((shp.B, shp.H, shp.M, shp.d), dtype=torch.float32, device=k.device)
+    gram = torch.empty((shp.B, shp.H, shp.M, shp.M), dtype=torch.float32, device=k.device) if want_gram else None
+    _check(load().flare_spectral(ctypes.byref(shp), _dev(q_lat, "q_lat"), _dev(k, "k"),
+                                 _dev(lse_enc, "lse_enc", torch.float32, (shp.B, shp.H, shp.M)),
+                                 _dev(lse_dec, "lse_dec", torch.float32, (shp.B, shp.H, shp.N)),
+                                 ctypes.c_float(scale), ctypes.c_int(first), _dev(ev, "eigenvalues"),
+                                 _dev(zv, "z_vec"), None if gram is None else _dev(gram, "gram"),
+                                 ctypes.c_void_p(ws.data_ptr()), ctypes.c_size_t(ws.numel()), _stream(stream)),
+           "flare_spectral")
+    return ev, zv, gram
 
 
 def profile_enable(on):

@@ -16,7 +16,8 @@ LIB = os.path.join(HERE, "libflare.so")
 # source -> extra flags.  The matrix-core file never produces NaNs (masked scores are -inf and
 # are only ever compared, exponentiated or shifted by finite values), so it is compiled with
 # -fno-honor-nans: fmaxf chains then become v_max3_f32 without canonicalising moves.
-SOURCES = {"flare_api.hip": [], "flare_valu.hip": [], "flare_mfma.hip": ["-fno-honor-nans"]}
+SOURCES = {"flare_api.hip": [], "flare_valu.hip": [], "flare_mfma.hip": ["-fno-honor-nans"],
+           "flare_spectral.hip": []}
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

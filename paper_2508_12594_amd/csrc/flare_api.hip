@@ -38,7 +38,8 @@ ProfileState g_prof;
 const char *const kKernelNames[KID_COUNT] = {
     "encode_partial", "encode_merge", "decode", "bwd_token_stats", "bwd_prep", "bwd_dz_partial",
     "bwd_dz_merge", "bwd_dq_partial", "bwd_dq_reduce", "bwd_dkdv", "bwd_plan", "bwd_dq_partial_2exp",
-    "bwd_dkdv_2exp", "decode_merge", "bwd_dkdv_finish"};
+    "bwd_dkdv_2exp", "decode_merge", "bwd_dkdv_finish", "spectral_gram", "spectral_reduce", "spectral_eigen",
+    "spectral_post"};
 }  // namespace
 
 LaunchTimer::LaunchTimer(int kid, hipStream_t s) : slot(-1), stream(s)
@@ -171,6 +172,31 @@ int flare_backward(const flare_shape *shape, const void *q_lat, const void *k, c
     if (!workspace || workspace_bytes < need) return FLARE_EWORKSPACE;
     return valu_backward(*shape, q_lat, k, v, y, lse_dec, dy, z, lse_enc, dq_lat, dk, dv, scale, workspace,
                          static_cast<hipStream_t>(stream));
+}
+
+int flare_spectral_workspace_bytes(const flare_shape *shape, size_t *bytes)
+{
+    const int rc = check_shape(shape);
+    if (rc != FLARE_OK) return rc;
+    if (shape->M > 512) return FLARE_EUNSUPPORTED;
+    if (bytes) *bytes = spectral_bytes(*shape);
+    return FLARE_OK;
+}
+
+int flare_spectral(const flare_shape *shape, const void *q_lat, const void *k, const float *lse_enc,
+                   const float *lse_dec, float scale, int first, float *eigenvalues, float *z_vec, float *gram,
+                   void *workspace, size_t workspace_bytes, void *stream)
+{
+    const int rc = check_shape(shape);
+    if (rc != FLARE_OK) return rc;
+    if (shape->M > 512) return FLARE_EUNSUPPORTED;
+    if (!q_lat || !k || !lse_enc || !lse_dec || !eigenvalues || !z_vec || first < 0) return FLARE_EINVAL;
+    if (!aligned16(q_lat) || !aligned16(k) || !aligned16(lse_enc) || !aligned16(lse_dec) || !aligned16(eigenvalues) ||
+        !aligned16(z_vec) || !aligned16(gram) || !aligned16(workspace))
+        return FLARE_EALIGN;
+    if (!workspace || workspace_bytes < spectral_bytes(*shape)) return FLARE_EWORKSPACE;
+    return spectral_run(*shape, q_lat, k, lse_enc, lse_dec, scale, first, eigenvalues, z_vec, gram, workspace,
+                        static_cast<hipStream_t>(stream));
 }
 
 int flare_profile_enable(int on)

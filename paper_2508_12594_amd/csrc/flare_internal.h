@@ -25,6 +25,10 @@ enum KernelId {
     KID_BWD_DKDV_2EXP,
     KID_DECODE_MERGE,
     KID_BWD_DKDV_FINISH,
+    KID_SPECTRAL_GRAM,
+    KID_SPECTRAL_REDUCE,
+    KID_SPECTRAL_EIGEN,
+    KID_SPECTRAL_POST,
     KID_COUNT
 };
 
@@ -137,5 +141,13 @@ int mfma_dz_partial(const flare_shape &s, const void *q, const void *k, const vo
 // other.  ld_range[b*h][part] = (min, max) of lse_dec2 as mfma_dz_partial recorded it.
 int mfma_bwd_plan(const flare_shape &s, const float *ld_range, const float *lse_enc, int *plan, bool force_two,
                   hipStream_t stream);
+
+// ---- spectral analysis (Appendix C.1, Algorithm 1) ---------------------------------------------
+bool mfma_gram_supported(const flare_shape &s);
+int mfma_gram_partial(const flare_shape &s, const Split &sp, const void *q, const void *k, const float *lse_enc,
+                      const float *lse_dec, float *g_part, float scale, hipStream_t stream);
+size_t spectral_bytes(const flare_shape &s);
+int spectral_run(const flare_shape &s, const void *q, const void *k, const float *lse_enc, const float *lse_dec,
+                 float scale, int first, float *evals, float *zvec, float *gram, void *ws, hipStream_t stream);
 
 }  // namespace flare

@@ -220,7 +220,6 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
     constexpr int D = padded_dim(DR);
     constexpr int KS = D / 16;   // k-steps of the score product
     constexpr int HV = D / 16;   // 16-wide column groups of Z, each with its own ones row
-    constexpr int M = 32 * MT;
     const int lane = threadIdx.x & 63, l32 = lane & 31, hh = lane >> 5;
     const int wave = threadIdx.x >> 6;
     const int bh = blockIdx.y, h = bh % H;
@@ -1066,7 +1065,6 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     constexpr int D = padded_dim(DR);
     constexpr int KS = D / 16;
     constexpr int HV = D / 16;
-    constexpr int M = 32 * MT;
     constexpr int NA = (LO2 ? 6 : 4) * KS + 1;  // A-type images per latent tile (the last one: corrections)
     constexpr int NR = 4 * HV;                  // row images per latent tile (RW1, RW2) x 2 k-steps
     constexpr int PER_TILE = NA + NR;
@@ -1333,6 +1331,93 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
 #pragma unroll
         for (int s = 0; s < KS; ++s) { kt[s] = ktn[s]; vt[s] = vtn[s]; gt[s] = gtn[s]; }
     }
+}
+
+// ============================================================================================
+// Companion matrix of the spectral analysis (Appendix C.1, Algorithm 1, steps 1-4 and the product of
+// step 5):   G = J J^T,   J[m][n] = exp(S[m][n] - (lse_enc[m] + lse_dec[n]) / 2) = (P[m][n] R[n][m])^(1/2).
+// A workgroup has one wave per 32-latent tile and walks over the 32-token tiles of its chunk.  Per
+// token tile every wave forms its own J^T tile (rows = tokens, columns = its latents; both
+// half-normalisers ride in one correction k-step), rounds it to bf16 and publishes it in LDS; after
+// one barrier it multiplies its tile with every wave's tile: the packed accumulator layout is at
+// once a valid A operand (row = latent) and B operand (column = latent) over the same permuted
+// token order.  LDS is double-buffered, so one barrier per token tile suffices.
+// Output: the chunk's partial G, [b*h][chunk][M][M] fp32, summed in chunk order afterwards.
+// ============================================================================================
+template <int DR, int MT>
+__global__ __launch_bounds__(64 * MT) void gram_mfma_kernel(
+    const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const float *__restrict__ lse_enc,
+    const float *__restrict__ lse_dec, float *__restrict__ g_part, TokStride ts, int H, int N, int chunk_len,
+    int chunks, float c2)
+{
+    constexpr int D = padded_dim(DR);
+    constexpr int KS = D / 16;
+    constexpr int M = 32 * MT;
+    __shared__ __attribute__((aligned(16))) u32x4 jt[2][MT][2][64];
+    const int lane = threadIdx.x & 63, l32 = lane & 31, hh = lane >> 5;
+    const int wave = threadIdx.x >> 6;
+    const int bh = blockIdx.y, h = bh % H, chunk = blockIdx.x;
+    const bool lower = hh == 0;
+
+    bf16x8 qh[KS], ql[KS];
+    load_q_operand<DR, true>(q + ((size_t)h * M + 32 * wave + l32) * DR, hh, c2, false, qh, ql);
+    u32x4 wq;
+    wq[0] = lower ? split_bf16_pair(-0.5f * kLog2e * lse_enc[(size_t)bh * M + 32 * wave + l32]) : 0u;
+    wq[1] = lower ? 0x3f803f80u : 0u;      // slots 2,3 := 1 (pick the token's half-normaliser)
+    wq[2] = 0u; wq[3] = 0u;
+    const bf16x8 q_aug = as_bf16x8(wq);
+
+    const bf16_t *kb = k + tok_base(ts, bh, H);
+    const float *lb = lse_dec + (size_t)bh * N;
+    const int n0 = chunk * chunk_len;
+    const int n1 = min(N, n0 + chunk_len);
+    const int tiles = (n1 - n0 + 31) / 32;
+    f32x16 acc[MT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t) acc[t] = splat16(0.f);
+
+    for (int j = 0; j < tiles; ++j) {
+        const int tok0 = n0 + 32 * j;
+        const int n = min(tok0 + l32, N - 1);
+        bf16x8 kt[KS];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) kt[s] = as_bf16x8(row8_bf16<DR>(kb + tok_off(ts, n), (D / 2) * hh + 8 * s));
+        u32x4 wk;
+        wk[0] = lower ? 0x3f803f80u : 0u;                                      // slots 0,1 := 1
+        wk[1] = lower ? split_bf16_pair(-0.5f * kLog2e * lb[n]) : 0u;          // slots 2,3 := -lse_dec2[n] / 2
+        wk[2] = 0u; wk[3] = 0u;
+        f32x16 x = splat16(0.f);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) x = mfma(kt[ks], qh[ks], x);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) x = mfma(kt[ks], ql[ks], x);
+        x = mfma(as_bf16x8(wk), q_aug, x);
+        if (tok0 + 32 > n1) {   // rows past the chunk's end contribute nothing
+            const int rem = n1 - tok0 - 4 * hh;
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                if (8 * (r / 4) + (r % 4) >= rem) x[r] = -INFINITY;
+        }
+        bf16x8 p0, p1;
+        exp_pack(x, p0, p1);
+        u32x4 (*buf)[2][64] = jt[j & 1];
+        buf[wave][0][lane] = __builtin_bit_cast(u32x4, p0);
+        buf[wave][1][lane] = __builtin_bit_cast(u32x4, p1);
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            acc[t] = mfma(p0, as_bf16x8(buf[t][0][lane]), acc[t]);
+            acc[t] = mfma(p1, as_bf16x8(buf[t][1][lane]), acc[t]);
+        }
+    }
+    float *out = g_part + ((size_t)bh * chunks + chunk) * M * M;
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = 32 * wave + 8 * (r / 4) + 4 * hh + (r % 4);
+            out[(size_t)row * M + 32 * t + l32] = acc[t][r];
+        }
 }
 
 inline int check_launch() { return hipGetLastError() == hipSuccess ? FLARE_OK : FLARE_ELAUNCH; }
@@ -1850,6 +1935,40 @@ static int decode_all(const flare_shape &s, const void *q, const void *k, const 
         default: FLARE_DM(32); break;
     }
 #undef FLARE_DM
+    return check_launch();
+}
+
+// partial companion matrices [b*h][chunk][M][M]; the split of the token axis is returned in *sp
+bool mfma_gram_supported(const flare_shape &s)
+{
+    return mfma_supported(s) && (s.M == 32 || s.M == 64 || s.M == 128 || s.M == 256);
+}
+
+int mfma_gram_partial(const flare_shape &s, const Split &sp, const void *q, const void *k, const float *lse_enc,
+                      const float *lse_dec, float *g_part, float scale, hipStream_t stream)
+{
+    const dim3 grid(sp.chunks, s.B * s.H);
+    const float c2 = scale * kLog2e;
+    const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k;
+    LaunchTimer t(KID_SPECTRAL_GRAM, stream);
+#define FLARE_GRAM(DD, MTT)                                                                                  \
+    gram_mfma_kernel<DD, MTT><<<grid, 64 * MTT, 0, stream>>>(qq, kk, lse_enc, lse_dec, g_part, tok_stride(s), s.H, \
+                                                             s.N, sp.chunk_len, sp.chunks, c2)
+#define FLARE_GRAM_MT(DD)                       \
+    switch (s.M / 32) {                         \
+        case 1: FLARE_GRAM(DD, 1); break;       \
+        case 2: FLARE_GRAM(DD, 2); break;       \
+        case 4: FLARE_GRAM(DD, 4); break;       \
+        default: FLARE_GRAM(DD, 8); break;      \
+    }
+    switch (s.d) {
+        case 4: FLARE_GRAM_MT(4) break;
+        case 8: FLARE_GRAM_MT(8) break;
+        case 16: FLARE_GRAM_MT(16) break;
+        default: FLARE_GRAM_MT(32) break;
+    }
+#undef FLARE_GRAM_MT
+#undef FLARE_GRAM
     return check_launch();
 }
 
