@@ -26,7 +26,7 @@
  *   - Return value: FLARE_OK (0) or a negative flare_status.  Nothing is launched when an
  *     argument check fails.  A launch failure reported by the HIP runtime gives FLARE_ELAUNCH.
  *   - Supported shapes: B,H,N,M >= 1 with B*H <= 65535, N < 2^24 and N times the token stride in
- *     elements (d, or H*d for FLARE_BNHD) below 2^32; d in {4, 8, 16, 32}; dtype f32 or bf16;
+ *     elements (d, or H*d for FLARE_BNHD) below 2^32; d in {4, 8, 16, 32}; dtype f32, bf16 or f16;
  *     either flare_layout for the token tensors (every "[B][H][N][d]" below reads [B][N][H][d]
  *     when shape->layout is FLARE_BNHD; the per-token statistic lse_dec is [B][H][N] always).
  *     Shapes with dtype bf16 and M = 32, a multiple of 64 up to 256, or a multiple of 256 up to
@@ -47,7 +47,8 @@ extern "C" {
 
 typedef enum {
     FLARE_F32 = 0,   /* q_lat, k, v, y, dy, dk, dv are IEEE fp32 */
-    FLARE_BF16 = 1   /* ... are bfloat16; all accumulation and the saved statistics stay fp32 */
+    FLARE_BF16 = 1,  /* ... are bfloat16; all accumulation and the saved statistics stay fp32 */
+    FLARE_F16 = 2    /* ... are IEEE fp16 (the paper's autocast type); runs on the fp32 vector kernels */
 } flare_dtype;
 
 typedef enum {

@@ -12,6 +12,7 @@ LIB_PATH = os.path.join(_HERE, "libflare.so")
 
 FLARE_F32 = 0
 FLARE_BF16 = 1
+FLARE_F16 = 2
 FLARE_BHND = 0   # token tensors [B,H,N,d]
 FLARE_BNHD = 1   # token tensors [B,N,H,d] (= [B,N,C], C = H*d)
 LAYOUTS = {"bhnd": FLARE_BHND, "bnhd": FLARE_BNHD}
@@ -91,7 +92,9 @@ def _dtype_code(t):
         return FLARE_F32
     if t.dtype == torch.bfloat16:
         return FLARE_BF16
-    raise FlareError("dtype must be float32 or bfloat16, got %s" % t.dtype)
+    if t.dtype == torch.float16:
+        return FLARE_F16
+    raise FlareError("dtype must be float32, bfloat16 or float16, got %s" % t.dtype)
 
 
 def _shape_of(q, k, layout="bhnd"):

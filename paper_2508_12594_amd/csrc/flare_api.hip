@@ -62,7 +62,7 @@ int check_shape(const flare_shape *s)
 {
     if (!s) return FLARE_EINVAL;
     if (s->B < 1 || s->H < 1 || s->N < 1 || s->M < 1 || s->d < 1) return FLARE_EINVAL;
-    if (s->dtype != FLARE_F32 && s->dtype != FLARE_BF16) return FLARE_EUNSUPPORTED;
+    if (s->dtype != FLARE_F32 && s->dtype != FLARE_BF16 && s->dtype != FLARE_F16) return FLARE_EUNSUPPORTED;
     if (s->layout != FLARE_BHND && s->layout != FLARE_BNHD) return FLARE_EUNSUPPORTED;
     if (s->d != 4 && s->d != 8 && s->d != 16 && s->d != 32) return FLARE_EUNSUPPORTED;
     if ((long long)s->B * s->H > 65535) return FLARE_EUNSUPPORTED;

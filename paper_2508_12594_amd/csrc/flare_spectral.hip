@@ -18,6 +18,8 @@ namespace flare {
 namespace {
 
 typedef uint16_t bf16_t;
+struct f16_t { uint16_t bits; };
+__device__ __forceinline__ float elem(const f16_t *p, size_t i) { return (float)reinterpret_cast<const _Float16 *>(p)[i]; }
 __device__ __forceinline__ float elem(const float *p, size_t i) { return p[i]; }
 __device__ __forceinline__ float elem(const bf16_t *p, size_t i) { return __uint_as_float((uint32_t)p[i] << 16); }
 
@@ -221,6 +223,10 @@ int spectral_run(const flare_shape &s, const void *q, const void *k, const float
             gram_valu_kernel<float><<<grid, 256, s.M * 4, stream>>>((const float *)q, (const float *)k, lse_enc, lse_dec,
                                                                    g_part, ts, s.H, s.N, s.M, s.d, sp.chunk_len,
                                                                    sp.chunks, scale);
+        else if (s.dtype == FLARE_F16)
+            gram_valu_kernel<f16_t><<<grid, 256, s.M * 4, stream>>>((const f16_t *)q, (const f16_t *)k, lse_enc,
+                                                                   lse_dec, g_part, ts, s.H, s.N, s.M, s.d,
+                                                                   sp.chunk_len, sp.chunks, scale);
         else
             gram_valu_kernel<bf16_t><<<grid, 256, s.M * 4, stream>>>((const bf16_t *)q, (const bf16_t *)k, lse_enc,
                                                                     lse_dec, g_part, ts, s.H, s.N, s.M, s.d,

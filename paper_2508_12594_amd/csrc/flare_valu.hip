@@ -21,6 +21,7 @@ namespace flare {
 namespace {
 
 typedef uint16_t bf16_t;  // raw bfloat16 bits
+struct f16_t { uint16_t bits; };   // raw IEEE fp16 bits (a type of its own so that the row helpers can overload)
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
@@ -59,6 +60,29 @@ __device__ __forceinline__ void load_row(const bf16_t *__restrict__ p, float (&o
             out[8 * i + 4] = bf16_lo(t.z); out[8 * i + 5] = bf16_hi(t.z);
             out[8 * i + 6] = bf16_lo(t.w); out[8 * i + 7] = bf16_hi(t.w);
         }
+    }
+}
+template <int D>
+__device__ __forceinline__ void load_row(const f16_t *__restrict__ p, float (&out)[D])
+{
+    const _Float16 *h = reinterpret_cast<const _Float16 *>(p);
+    typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+    for (int i = 0; i < D / 4; ++i) {
+        const half4 t = *reinterpret_cast<const half4 *>(h + 4 * i);
+        out[4 * i] = (float)t[0]; out[4 * i + 1] = (float)t[1]; out[4 * i + 2] = (float)t[2]; out[4 * i + 3] = (float)t[3];
+    }
+}
+template <int D>
+__device__ __forceinline__ void store_row(f16_t *__restrict__ p, const float (&in)[D])
+{
+    _Float16 *h = reinterpret_cast<_Float16 *>(p);
+    typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+    for (int i = 0; i < D / 4; ++i) {
+        half4 t;
+        t[0] = (_Float16)in[4 * i]; t[1] = (_Float16)in[4 * i + 1]; t[2] = (_Float16)in[4 * i + 2]; t[3] = (_Float16)in[4 * i + 3];
+        *reinterpret_cast<half4 *>(h + 4 * i) = t;
     }
 }
 template <int D>
@@ -628,7 +652,7 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     // kernel reads lse_dec itself, scaled to log2 units.
     // With bf16 storage and d < 16, delta = <dY_n, Y_n> from the rounded y is too coarse (few terms, and
     // c - delta cancels): such shapes recompute the statistics even when y and lse_dec are given.
-    const bool saved = y && lse_dec && (s.dtype == FLARE_F32 || s.d >= 16);
+    const bool saved = y && lse_dec && (s.dtype != FLARE_BF16 || s.d >= 16);
     const bool fused = saved && mf && mfma_dkdv_supported(s);   // every later kernel is a matrix-core one
     const float *ld = fused ? lse_dec : w.lse_dec2;
     const float ld_mul = fused ? kLog2e : 1.f;
@@ -710,6 +734,14 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     do {                                                                          \
         if ((s).dtype == FLARE_F32) {                                             \
             typedef float T;                                                      \
+            switch ((s).d) {                                                      \
+                case 4: { constexpr int D = 4; return CALL; }                     \
+                case 8: { constexpr int D = 8; return CALL; }                     \
+                case 16: { constexpr int D = 16; return CALL; }                   \
+                case 32: { constexpr int D = 32; return CALL; }                   \
+            }                                                                     \
+        } else if ((s).dtype == FLARE_F16) {                                      \
+            typedef f16_t T;                                                      \
             switch ((s).d) {                                                      \
                 case 4: { constexpr int D = 4; return CALL; }                     \
                 case 8: { constexpr int D = 8; return CALL; }                     \

@@ -105,8 +105,12 @@ def make_inputs(cfg, *, B=None, H=None, N=None, M=None, d=None, dtype=None, with
         q, k, v = bf16_round(q), bf16_round(k), bf16_round(v)
         if dy is not None:
             dy = bf16_round(dy)
+    elif dtype == "f16":
+        q, k, v = (x.astype(np.float16).astype(np.float32) for x in (q, k, v))
+        if dy is not None:
+            dy = dy.astype(np.float16).astype(np.float32)
     elif dtype != "f32":
-        raise ValueError("dtype must be 'f32' or 'bf16'")
+        raise ValueError("dtype must be 'f32', 'bf16' or 'f16'")
     out.update(q=q, k=k, v=v)
     if dy is not None:
         out["dy"] = dy

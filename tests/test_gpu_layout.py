@@ -35,6 +35,8 @@ CASES = [
     (4, dict(N=33, H=3)),           # odd head count, two tiles
     (2, dict(B=1, N=1200, d=8)),    # matrix-core path with the head dimension padded to 16
     (4, dict(N=700, d=4, H=4)),
+    (2, dict(B=1, N=900, M=512)),                # latent chunks on the matrix-core path
+    (1, dict(N=400, dtype="f16")),               # fp16 storage
 ]
 
 

@@ -211,6 +211,18 @@ def test_many_latents_matrix_core_path(oracle, shape):
     _backward_case(oracle, inp, saved=True)
 
 
+@pytest.mark.parametrize("shape", [(1, 2, 1000, 64, 16), (2, 1, 515, 40, 8), (1, 1, 300, 256, 32), (1, 2, 129, 70, 4)])
+def test_fp16_storage(oracle, shape):
+    """IEEE fp16 inputs and outputs (the paper's autocast type, Appendix F): fp32 arithmetic on the vector
+    kernels, so only the rounding of the outputs to fp16 separates the result from the fp32 path's."""
+    B, H, N, M, d = shape
+    _say("fp16 storage %s" % (shape,))
+    inp = synth.make_inputs(1, B=B, H=H, N=N, M=M, d=d, dtype="f16", with_dy=True, seed=606 + N + M)
+    _forward_case(oracle, inp)
+    _backward_case(oracle, inp, saved=False)
+    _backward_case(oracle, inp, saved=True)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_sharp_softmax_stress(oracle, dtype):
     """Scores eight times larger: nearly one-hot softmaxes, the running max moves a lot."""
