@@ -231,14 +231,19 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
     for (int t = 0; t < MT; ++t)
         load_q_operand<DR, PRE>(q + ((size_t)h * Mtot + m0 + 32 * t + l32) * DR, hh, c2, flip, qh[t], ql[t]);
 
-    // Zaug^T operand: row l32 (< 16: column 16*hv + l32 of Z; 16: ones; else zero)
-    bf16x8 zt[HV][2 * MT];
+    // Zaug^T operand: row l32 (< 16: column 16*hv + l32 of Z; 16: ones; else zero).  In registers, or --
+    // for the shapes whose registers would not allow two waves per SIMD otherwise (ZLDS = !PRE) --
+    // built once per workgroup in LDS (the four waves share one (b,h)) and read per latent tile.
+    constexpr bool ZLDS = !PRE;
+    __shared__ __attribute__((aligned(16))) u32x4 zlds[ZLDS ? HV * 2 * MT * 64 : 1];
+    bf16x8 zt[ZLDS ? 1 : HV][ZLDS ? 1 : 2 * MT];
     {
         const float *zb = z + ((size_t)bh * Mtot + m0) * DR;
 #pragma unroll
         for (int hv = 0; hv < HV; ++hv)
 #pragma unroll
             for (int s = 0; s < 2 * MT; ++s) {
+                if (ZLDS && (s & 3) != wave) continue;   // each wave builds a quarter of the images
                 u32x4 w;
 #pragma unroll
                 for (int i = 0; i < 8; i += 2) {
@@ -251,9 +256,15 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
                     }
                     w[i / 2] = rne_bf16(a) | (rne_bf16(b) << 16);
                 }
-                zt[hv][s] = as_bf16x8(w);
+                if constexpr (ZLDS) zlds[(hv * 2 * MT + s) * 64 + lane] = w;
+                else zt[hv][s] = as_bf16x8(w);
             }
     }
+    if constexpr (ZLDS) __syncthreads();
+    auto z_op = [&](int hv, int s) {
+        if constexpr (ZLDS) return as_bf16x8(zlds[(hv * 2 * MT + s) * 64 + lane]);
+        else return zt[hv][s];
+    };
 
     const bf16_t *kb = k + tok_base(ts, bh, H);
     bf16_t *yb = y + tok_base(ts_y, bh, H);
@@ -335,8 +346,8 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
             exp_pack(s_cur, p0, p1);
 #pragma unroll
             for (int hv = 0; hv < HV; ++hv) {
-                acc[hv] = mfma(zt[hv][2 * t], p0, acc[hv]);
-                acc[hv] = mfma(zt[hv][2 * t + 1], p1, acc[hv]);
+                acc[hv] = mfma(z_op(hv, 2 * t), p0, acc[hv]);
+                acc[hv] = mfma(z_op(hv, 2 * t + 1), p1, acc[hv]);
             }
             if constexpr (PRE && D == 16) {
                 // order within the tile: the two score products of tile t+1 and the two value products of
@@ -1825,8 +1836,8 @@ static int launch_decode_family(const flare_shape &s, const void *q, const void 
             case 1: FLARE_DEC(32, 1, true, 2); break;
             case 2: FLARE_DEC(32, 2, true, 2); break;
             case 4: FLARE_DEC(32, 4, true, 2); break;
-            case 6: FLARE_DEC(32, 6, false, 1); break;
-            case 8: FLARE_DEC(32, 8, false, 1); break;
+            case 6: FLARE_DEC(32, 6, false, 2); break;
+            case 8: FLARE_DEC(32, 8, false, 2); break;
             default: return FLARE_EUNSUPPORTED;
         }
     }
