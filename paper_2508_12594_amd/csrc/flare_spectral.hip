@@ -88,54 +88,88 @@ __global__ __launch_bounds__(256) void gram_reduce_kernel(const float *__restric
 // diagonal, i.e. B ends as Lambda Q: row i is lambda_i times the i-th eigenvector, its length is
 // lambda_i.  Only whole rows are read and written (coalesced), nothing else is accumulated, and the
 // pairs of a round of the round-robin tournament (M' - 1 rounds per sweep, M' = M rounded up to
-// even) are disjoint: one wave per pair, one barrier per round.  Stops when no pair of rows of a
-// sweep had |cos| above 1e-13, or after 40 sweeps.
+// even) are disjoint: a wave per few pairs, one barrier per round.  At most 40 sweeps.
 constexpr int kJacobiThreads = 1024;
-constexpr int kRowRegs = 8;      // row elements per lane: M <= 64 * kRowRegs
+// RR = row elements per lane (M <= 64 * RR); a wave works on PB = 16 / RR pairs at a time so that
+// the loads of all of them are in flight together.
+template <int RR>
 __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(double *__restrict__ b_all, int M)
 {
+    constexpr int PB = 16 / RR;
     __shared__ unsigned long long worst;       // bits of the largest |cos| of the sweep (non-negative doubles order as integers)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     double *bm = b_all + (size_t)blockIdx.x * M * M;
     const int Mp = M + (M & 1), pairs = Mp / 2;
+    // Orthogonality is judged in absolute terms, inner product against the matrix's squared Frobenius
+    // norm F2: below 1e-22 F2 a pair is left alone, and the solver stops after a sweep in which no inner
+    // product exceeded 1e-18 F2.  (The eigenvalues are wanted to absolute accuracy; rows of tiny
+    // eigenvalues carry rounding noise of the large ones, which no rotation can make orthogonal in
+    // relative terms.)
+    __shared__ double fro[kJacobiThreads / 64];
+    {
+        double f = 0.0;
+        for (int i = tid; i < M * M; i += kJacobiThreads) f = fma(bm[i], bm[i], f);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) f += __shfl_xor(f, o);
+        if (lane == 0) fro[wave] = f;
+        __syncthreads();
+    }
+    double tiny = 0.0;
+    for (int w = 0; w < kJacobiThreads / 64; ++w) tiny += fro[w];
+    const double f2 = tiny;
+    tiny *= 1e-22;
     for (int sweep = 0; sweep < 40; ++sweep) {
         if (tid == 0) worst = 0ull;
         __syncthreads();
         for (int round = 0; round < Mp - 1; ++round) {
-            for (int i = wave; i < pairs; i += kJacobiThreads / 64) {
-                int p = (i == 0) ? Mp - 1 : (round + i) % (Mp - 1);
-                int q = (i == 0) ? round : (round - i + Mp - 1) % (Mp - 1);
-                if (p > q) { const int t = p; p = q; q = t; }
-                if (q >= M) continue;            // the padding index of an odd M
-                double x[kRowRegs], y[kRowRegs];
-                double al = 0.0, be = 0.0, ga = 0.0;
+            for (int i0 = wave * PB; i0 < pairs; i0 += (kJacobiThreads / 64) * PB) {
+                double x[PB][RR], y[PB][RR];
+                int pp[PB], qq[PB];
 #pragma unroll
-                for (int t = 0; t < kRowRegs; ++t) {
-                    const int j = lane + 64 * t;
-                    x[t] = (j < M) ? bm[(size_t)p * M + j] : 0.0;
-                    y[t] = (j < M) ? bm[(size_t)q * M + j] : 0.0;
-                    al = fma(x[t], x[t], al);
-                    be = fma(y[t], y[t], be);
-                    ga = fma(x[t], y[t], ga);
+                for (int b = 0; b < PB; ++b) {
+                    const int i = i0 + b;
+                    int p = (i == 0) ? Mp - 1 : (round + i) % (Mp - 1);
+                    int q = (i == 0) ? round : (round - i + Mp - 1) % (Mp - 1);
+                    if (p > q) { const int t = p; p = q; q = t; }
+                    const bool live = i < pairs && q < M;      // q == M: the padding index of an odd M
+                    pp[b] = live ? p : -1;
+                    qq[b] = q;
+#pragma unroll
+                    for (int t = 0; t < RR; ++t) {
+                        const int j = lane + 64 * t;
+                        x[b][t] = (live && j < M) ? bm[(size_t)p * M + j] : 0.0;
+                        y[b][t] = (live && j < M) ? bm[(size_t)q * M + j] : 0.0;
+                    }
                 }
 #pragma unroll
-                for (int o = 32; o > 0; o >>= 1) {
-                    al += __shfl_xor(al, o);
-                    be += __shfl_xor(be, o);
-                    ga += __shfl_xor(ga, o);
-                }
-                const double den = sqrt(al * be);
-                if (!(den > 1e-290) || !(fabs(ga) > 1e-15 * den)) continue;   // already orthogonal (or a null row)
-                if (lane == 0) atomicMax(&worst, (unsigned long long)__double_as_longlong(fabs(ga) / den));
-                const double zeta = (be - al) / (2.0 * ga);
-                const double t = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
-                const double c = 1.0 / sqrt(1.0 + t * t), sn = c * t;
+                for (int b = 0; b < PB; ++b) {
+                    if (pp[b] < 0) continue;
+                    double al = 0.0, be = 0.0, ga = 0.0;
 #pragma unroll
-                for (int r = 0; r < kRowRegs; ++r) {
-                    const int j = lane + 64 * r;
-                    if (j < M) {
-                        bm[(size_t)p * M + j] = c * x[r] - sn * y[r];
-                        bm[(size_t)q * M + j] = sn * x[r] + c * y[r];
+                    for (int t = 0; t < RR; ++t) {
+                        al = fma(x[b][t], x[b][t], al);
+                        be = fma(y[b][t], y[b][t], be);
+                        ga = fma(x[b][t], y[b][t], ga);
+                    }
+#pragma unroll
+                    for (int o = 32; o > 0; o >>= 1) {
+                        al += __shfl_xor(al, o);
+                        be += __shfl_xor(be, o);
+                        ga += __shfl_xor(ga, o);
+                    }
+                    const double den = sqrt(al * be);
+                    if (!(fabs(ga) > tiny) || !(fabs(ga) > 1e-15 * den)) continue;   // orthogonal already
+                    if (lane == 0) atomicMax(&worst, (unsigned long long)__double_as_longlong(fabs(ga)));
+                    const double zeta = (be - al) / (2.0 * ga);
+                    const double t = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
+                    const double c = 1.0 / sqrt(1.0 + t * t), sn = c * t;
+#pragma unroll
+                    for (int r = 0; r < RR; ++r) {
+                        const int j = lane + 64 * r;
+                        if (j < M) {
+                            bm[(size_t)pp[b] * M + j] = c * x[b][r] - sn * y[b][r];
+                            bm[(size_t)qq[b] * M + j] = sn * x[b][r] + c * y[b][r];
+                        }
                     }
                 }
             }
@@ -143,7 +177,7 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(double *__restri
         }
         const double w = __longlong_as_double((long long)worst);
         __syncthreads();
-        if (!(w > 1e-13)) break;
+        if (!(w > 1e-18 * f2)) break;
     }
 }
 
@@ -241,7 +275,10 @@ int spectral_run(const flare_shape &s, const void *q, const void *k, const float
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     {
         LaunchTimer t(KID_SPECTRAL_EIGEN, stream);
-        jacobi_kernel<<<(unsigned)BH, kJacobiThreads, 0, stream>>>(a, s.M);
+        if (s.M <= 64) jacobi_kernel<1><<<(unsigned)BH, kJacobiThreads, 0, stream>>>(a, s.M);
+        else if (s.M <= 128) jacobi_kernel<2><<<(unsigned)BH, kJacobiThreads, 0, stream>>>(a, s.M);
+        else if (s.M <= 256) jacobi_kernel<4><<<(unsigned)BH, kJacobiThreads, 0, stream>>>(a, s.M);
+        else jacobi_kernel<8><<<(unsigned)BH, kJacobiThreads, 0, stream>>>(a, s.M);
     }
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     {
