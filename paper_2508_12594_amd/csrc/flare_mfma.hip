@@ -930,15 +930,21 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
     };
 
     if (cnt > 0) {
-        bf16x8 kt[KS], ktn[KS], ktnn[KS], vt[KS], vtn[KS], gt[KS], gtn[KS], kT[HV][2];
-        float nld, nldn, dl, dln;
+        // keys are requested two tiles ahead; so are the other operands where registers allow (d <= 16)
+        constexpr bool DEEP = (D == 16);
+        bf16x8 kt[KS], ktn[KS], ktnn[KS], vt[KS], vtn[KS], vtnn[KS], gt[KS], gtn[KS], gtnn[KS], kT[HV][2];
+        float nld, nldn, nldnn, dl, dln, dlnn;
         float wrow[ONE ? 16 : 1];
         load_rows(kb, 0, kt);
         load_rows(kb, 1, ktn);
         load_rows(vb, 0, vt);
+        load_rows(vb, 1, vtn);
         load_rows(gb, 0, gt);
+        load_rows(gb, 1, gtn);
         nld = -lb[min(tile_tok0(0) + l32, N - 1)] * ld_mul;
         dl = db[min(tile_tok0(0) + l32, N - 1)];
+        nldn = -lb[min(tile_tok0(1) + l32, N - 1)] * ld_mul;
+        dln = db[min(tile_tok0(1) + l32, N - 1)];
         compiler_fence();
         write_kt(kt, lds);
         if constexpr (ONE) wl[0][l32] = fast_exp2(kap + nld);
@@ -950,13 +956,13 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
             const int tok0 = tile_tok0(j);
             uint16_t *buf_next = lds + ((j + 1) & 1) * BUF;
             load_rows(kb, j + 2, ktnn);
-            load_rows(vb, j + 1, vtn);
-            load_rows(gb, j + 1, gtn);
-            nldn = -lb[min(tile_tok0(j + 1) + l32, N - 1)] * ld_mul;
-            dln = db[min(tile_tok0(j + 1) + l32, N - 1)];
+            load_rows(vb, j + (DEEP ? 2 : 1), vtnn);
+            load_rows(gb, j + (DEEP ? 2 : 1), gtnn);
+            nldnn = -lb[min(tile_tok0(j + (DEEP ? 2 : 1)) + l32, N - 1)] * ld_mul;
+            dlnn = db[min(tile_tok0(j + (DEEP ? 2 : 1)) + l32, N - 1)];
             compiler_fence();
             write_kt(ktn, buf_next);
-            if constexpr (ONE) wl[(j + 1) & 1][l32] = fast_exp2(kap + nldn);
+            if constexpr (ONE) wl[(j + 1) & 1][l32] = fast_exp2(kap + (DEEP ? nldn : nldnn));
             compiler_fence();
 
             // token-side operands of the correction k-steps (zero outside the named slots)
@@ -1023,9 +1029,13 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
             read_kT(buf_next, kT);
             if constexpr (ONE) read_w(wl[(j + 1) & 1], wrow);
 #pragma unroll
-            for (int s = 0; s < KS; ++s) { kt[s] = ktn[s]; ktn[s] = ktnn[s]; vt[s] = vtn[s]; gt[s] = gtn[s]; }
-            nld = nldn;
-            dl = dln;
+            for (int s = 0; s < KS; ++s) {
+                kt[s] = ktn[s]; ktn[s] = ktnn[s];
+                vt[s] = DEEP ? vtn[s] : vtnn[s]; vtn[s] = vtnn[s];
+                gt[s] = DEEP ? gtn[s] : gtnn[s]; gtn[s] = gtnn[s];
+            }
+            nld = DEEP ? nldn : nldnn; nldn = nldnn;
+            dl = DEEP ? dln : dlnn; dln = dlnn;
         }
     }
 
