@@ -88,6 +88,8 @@ def main():
     ap.add_argument("--tokens", type=int, default=None, help="override N (for quick checks only)")
     ap.add_argument("--latents", type=int, default=None, help="override M (for quick checks only)")
     ap.add_argument("--head-dim", type=int, default=None, help="override d (for quick checks only)")
+    ap.add_argument("--dtype", choices=["f32", "bf16", "f16"], default=None,
+                    help="override the workload's storage type (for quick checks only)")
     ap.add_argument("--layout", choices=["bhnd", "bnhd"], default="bhnd",
                     help="memory order of k, v, y, dy, dk, dv: [B,H,N,d] (default) or [B,N,H,d]")
     ap.add_argument("--spectral", action="store_true",
@@ -115,9 +117,11 @@ def main():
         over["M"] = args.latents
     if args.head_dim is not None:
         over["d"] = args.head_dim
+    if args.dtype is not None:
+        over["dtype"] = args.dtype
     inp = synth.make_inputs(args.cfg, with_dy=True, **over)
     B, H, N, M, d = (inp[x] for x in "BHNMd")
-    dt = torch.float32 if inp["dtype"] == "f32" else torch.bfloat16
+    dt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[inp["dtype"]]
     elem = 4 if inp["dtype"] == "f32" else 2
     dev = {n: torch.from_numpy(inp[n]).to("cuda", dt).contiguous() for n in ("q", "k", "v", "dy")}
     if args.layout == "bnhd":
@@ -125,7 +129,7 @@ def main():
             dev[n] = dev[n].permute(0, 2, 1, 3).contiguous()
     lay = args.layout
     scale = inp["scale"]
-    code = binding.FLARE_F32 if inp["dtype"] == "f32" else binding.FLARE_BF16
+    code = {"f32": binding.FLARE_F32, "bf16": binding.FLARE_BF16, "f16": binding.FLARE_F16}[inp["dtype"]]
     fwd_b, bwd_b = binding.workspace_bytes(B, H, N, M, d, code)
     ws = torch.empty(max(fwd_b, bwd_b, 256), dtype=torch.uint8, device="cuda")
     y = torch.empty_like(dev["k"])
@@ -186,7 +190,8 @@ def main():
     dom_bytes = algorithmic_bytes(dom, B, H, N, M, d, elem)
     dom_exps = exponentials(dom, B, H, N, M)
     dom_s = kernels[dom]["mean_us"] * 1e-6
-    default_workload = args.cfg == 4 and args.tokens is None and args.latents is None and args.head_dim is None
+    default_workload = (args.cfg == 4 and args.tokens is None and args.latents is None and args.head_dim is None
+                        and args.dtype is None)
     traffic = sum(MEASURED_TRAFFIC_CFG4[dom]) if default_workload and dom in MEASURED_TRAFFIC_CFG4 else None
     # the roofline that binds this kernel: whichever lower bound on its duration is larger
     if dom_exps / (EXP_PEAK_GOPS * 1e9) > dom_bytes / (HBM_PEAK_GBS * 1e9):
@@ -213,7 +218,8 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": inp["dtype"], "data": "synthetic",
         "config": {"workload": synth.describe(args.cfg) + ("" if args.tokens is None else " [N overridden to %d]" % N)
                    + ("" if args.latents is None else " [M overridden to %d]" % M)
-                   + ("" if args.head_dim is None else " [d overridden to %d]" % d),
+                   + ("" if args.head_dim is None else " [d overridden to %d]" % d)
+                   + ("" if args.dtype is None else " [storage type overridden to %s]" % args.dtype),
                    "step": "flare_forward + flare_backward", "B": B, "H": H, "N": N, "M": M, "d": d,
                    "layout": "[B,H,N,d]" if lay == "bhnd" else "[B,N,H,d]"},
         "fwd": {"tokens_per_s": round(tokens / t_fwd, 1), "ms": round(t_fwd * 1e3, 4),

@@ -29,9 +29,13 @@
  *     elements (d, or H*d for FLARE_BNHD) below 2^32; d in {4, 8, 16, 32}; dtype f32, bf16 or f16;
  *     either flare_layout for the token tensors (every "[B][H][N][d]" below reads [B][N][H][d]
  *     when shape->layout is FLARE_BNHD; the per-token statistic lse_dec is [B][H][N] always).
- *     Shapes with dtype bf16 and M = 32, a multiple of 64 up to 256, or a multiple of 256 up to
- *     2048 run on the matrix-core kernels (d < 16 with the contraction padded to 16; M > 256 in
- *     chunks of 256 latents); everything else runs on the fp32 vector kernels.
+ *     Shapes with dtype bf16 or f16 and M = 32, a multiple of 64 up to 256, or a multiple of 256
+ *     up to 2048 run on the matrix-core kernels (d < 16 with the contraction padded to 16; M > 256
+ *     in chunks of 256 latents); everything else runs on the fp32 vector kernels.  On the matrix
+ *     cores the scores come from exact products of the stored 16-bit values, the softmax weights
+ *     and dS are rounded to bf16 whatever the storage type (with f16 storage v and dy are rounded
+ *     to bf16 as they are read), sums are fp32, and outputs are rounded once from fp32.  With f16
+ *     storage scale*log2(e)*q_lat and the scaled scores must stay below 65504 in magnitude.
  *   - Results are bit-identical from run to run for the same inputs and shape (no float atomics;
  *     every cross-block reduction is done in a fixed order).
  *   - Non-finite inputs give undefined results.
@@ -48,7 +52,7 @@ extern "C" {
 typedef enum {
     FLARE_F32 = 0,   /* q_lat, k, v, y, dy, dk, dv are IEEE fp32 */
     FLARE_BF16 = 1,  /* ... are bfloat16; all accumulation and the saved statistics stay fp32 */
-    FLARE_F16 = 2    /* ... are IEEE fp16 (the paper's autocast type); runs on the fp32 vector kernels */
+    FLARE_F16 = 2    /* ... are IEEE fp16 (the paper's autocast type, Appendix F); likewise */
 } flare_dtype;
 
 typedef enum {
@@ -132,9 +136,10 @@ int flare_forward(const flare_shape *shape, const void *q_lat, const void *k, co
  *   z, lse_enc: what flare_forward wrote for the same inputs                (in)
  *   y, lse_dec: what flare_forward wrote, or NULL.  When both are given, delta_n is taken from
  *     the stored y and the decode normaliser from lse_dec; when either is NULL both are
- *     recomputed from z (one more pass over the scores, Y in fp32).  With bf16 storage and
- *     d < 16 they are recomputed in either case: delta from a bf16-rounded y of so few
- *     elements would not meet the accuracy of the rest                      (in, optional)
+ *     recomputed from z (one more pass over the scores, Y in fp32).  With bf16 storage (or f16
+ *     storage on the matrix-core kernels) and d < 16 they are recomputed in either case: delta
+ *     from a y of bf16 accuracy and so few elements would not meet the accuracy of the rest
+ *                                                                           (in, optional)
  *   dq_lat [H][M][d] fp32 (summed over the batch), dk, dv [B][H][N][d] dtype (out)
  */
 int flare_backward(const flare_shape *shape, const void *q_lat, const void *k, const void *v,

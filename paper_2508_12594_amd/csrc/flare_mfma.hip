@@ -1,4 +1,4 @@
-// Matrix-core (MFMA) kernels of the FLARE mixer for bf16 storage on gfx950.
+// Matrix-core (MFMA) kernels of the FLARE mixer for bf16 and fp16 storage on gfx950.
 //
 // Both kernels are built from v_mfma_f32_32x32x16_bf16 and keep the M x N weights in
 // registers only.  The softmax work per score is one v_exp_f32, half a v_cvt_pk_bf16_f32 and
@@ -21,6 +21,13 @@
 //   B operand: column l32, contraction slots 8*hh .. 8*hh+7
 //   C/D:       column l32, register r (0..15) holds row 8*(r/4) + 4*hh + r%4
 //
+// fp16 storage (template flag F): the score products and everything that rides in their
+// contraction (q' hi + lo, stabilisers, log-sum-exp pairs) use v_mfma_f32_32x32x16_f16 on the raw
+// fp16 keys, so the scores are as exact as with bf16 storage.  The softmax weights, dS and the
+// operands they are multiplied with stay bf16 (their range is needed: normalised weights of a
+// million tokens are far below the smallest fp16 number), so the V, dY (and, where K is a value,
+// K) rows are rounded to bf16 after the load; outputs are rounded to fp16 from fp32.
+//
 // Equations: Section 3.1, Eq. flare_encode / Eq. flare_decode; Appendix E.
 #include "flare_internal.h"
 
@@ -30,12 +37,12 @@ namespace {
 typedef uint16_t bf16_t;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 w) { return __builtin_bit_cast(bf16x8, w); }
-__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 __device__ __forceinline__ uint32_t rne_bf16(float f)
 {
     uint32_t u = __float_as_uint(f);
@@ -58,6 +65,75 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 __device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c)
 {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+// Score-chain product: operands hold 8 elements of the storage type (bf16, or fp16 when F); they
+// are carried as bf16x8 registers either way.
+template <bool F>
+__device__ __forceinline__ f32x16 mfma_s(bf16x8 a, bf16x8 b, f32x16 c)
+{
+    if constexpr (F)
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c,
+                                                      0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+// ---- 16-bit elements of the storage type ----
+// value of the low / high half of a word
+template <bool F>
+__device__ __forceinline__ float elem_lo(uint32_t w)
+{
+    if constexpr (F) return (float)__builtin_bit_cast(f16x2, w)[0];
+    else return __uint_as_float(w << 16);
+}
+template <bool F>
+__device__ __forceinline__ float elem_hi(uint32_t w)
+{
+    if constexpr (F) return (float)__builtin_bit_cast(f16x2, w)[1];
+    else return __uint_as_float(w & 0xffff0000u);
+}
+// fp32 -> 16 bits, round to nearest even, and back
+template <bool F>
+__device__ __forceinline__ uint32_t rne_elem(float f)
+{
+    if constexpr (F) return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)f);
+    else return rne_bf16(f);
+}
+template <bool F>
+__device__ __forceinline__ float elem_value(uint32_t bits)
+{
+    if constexpr (F) return (float)__builtin_bit_cast(_Float16, (uint16_t)bits);
+    else return __uint_as_float(bits << 16);
+}
+template <bool F>
+__device__ __forceinline__ float elem_round(float x) { return elem_value<F>(rne_elem<F>(x)); }
+// two fp32 -> one packed word of the storage type (one v_cvt_pk_{bf16,f16}_f32)
+template <bool F>
+__device__ __forceinline__ uint32_t pack_elems(float a, float b)
+{
+    if constexpr (F) {
+        f32x2 v;
+        v[0] = a;
+        v[1] = b;
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+    } else {
+        return cvt_pk_bf16(a, b);
+    }
+}
+// 1.0 in the storage type, and twice in one word
+template <bool F> constexpr uint32_t kOne = F ? 0x3c00u : 0x3f80u;
+template <bool F> constexpr uint32_t kOnePair = F ? 0x3c003c00u : 0x3f803f80u;
+// 8 stored elements -> 8 bf16 (operands of the weight-side products); nothing to do for bf16 storage
+template <bool F>
+__device__ __forceinline__ u32x4 to_bf16_row(u32x4 w)
+{
+    if constexpr (F) {
+        u32x4 r;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r[i] = cvt_pk_bf16(elem_lo<true>(w[i]), elem_hi<true>(w[i]));
+        return r;
+    } else {
+        return w;
+    }
 }
 __device__ __forceinline__ f32x16 splat16(float x)
 {
@@ -142,7 +218,7 @@ __device__ __forceinline__ bool quartet_inside(int hv, int hh, int upper)
 // Lane half hh covers d-indices (D/2)*hh + 8*s + i for k-step s.  The same mapping is used for
 // the key operand.  PRE: multiply by c2 and split into hi + lo bf16 terms; else raw bits (sign
 // flipped when c2 < 0 so that the kernel can work with |c2|).
-template <int DR, bool PRE>
+template <int DR, bool PRE, bool F>
 __device__ __forceinline__ void load_q_operand(const bf16_t *__restrict__ q_row, int hh, float c2, bool flip,
                                                bf16x8 (&hi)[padded_dim(DR) / 16], bf16x8 (&lo)[padded_dim(DR) / 16])
 {
@@ -154,11 +230,11 @@ __device__ __forceinline__ void load_q_operand(const bf16_t *__restrict__ q_row,
             u32x4 wh, wl;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const float a = bf16_lo(w[i]) * c2, b = bf16_hi(w[i]) * c2;
-                const uint32_t ah = rne_bf16(a), bh = rne_bf16(b);
-                const float ar = a - __uint_as_float(ah << 16), br = b - __uint_as_float(bh << 16);
+                const float a = elem_lo<F>(w[i]) * c2, b = elem_hi<F>(w[i]) * c2;
+                const uint32_t ah = rne_elem<F>(a), bh = rne_elem<F>(b);
+                const float ar = a - elem_value<F>(ah), br = b - elem_value<F>(bh);
                 wh[i] = ah | (bh << 16);
-                wl[i] = rne_bf16(ar) | (rne_bf16(br) << 16);
+                wl[i] = rne_elem<F>(ar) | (rne_elem<F>(br) << 16);
             }
             hi[s] = as_bf16x8(wh);
             lo[s] = as_bf16x8(wl);
@@ -174,6 +250,13 @@ __device__ __forceinline__ void load_q_operand(const bf16_t *__restrict__ q_row,
     }
 }
 
+// x as a hi + lo pair of storage-type values packed in one word (hi in the low half)
+template <bool F>
+__device__ __forceinline__ uint32_t split_pair(float x)
+{
+    const uint32_t hi = rne_elem<F>(x);
+    return hi | (rne_elem<F>(x - elem_value<F>(hi)) << 16);
+}
 // x as a hi + lo pair of bf16 values packed in one word (hi in the low half)
 __device__ __forceinline__ uint32_t split_bf16_pair(float x)
 {
@@ -190,7 +273,6 @@ __device__ __forceinline__ bf16x8 with_slot0(bf16x8 x, uint32_t keep, uint32_t b
     w[0] = (w[0] & keep) | bits;
     return as_bf16x8(w);
 }
-__device__ __forceinline__ float bf16_round(float x) { return __uint_as_float(rne_bf16(x) << 16); }
 __device__ __forceinline__ void compiler_fence() { asm volatile("" ::: "memory"); }
 
 // ============================================================================================
@@ -208,7 +290,7 @@ __device__ __forceinline__ void compiler_fence() { asm volatile("" ::: "memory")
 // MODE 0 writes y and, when lse_dec2 is not NULL, log sum_m exp(S[m][n]) (natural log) there.
 // MODE 1 (first step of the backward when nothing was saved) writes per token
 //   lse_dec2[n] = log2 sum_m 2^S2[m][n]   and   delta[n] = <dY_n, Y_n>   (Y_n kept in fp32).
-template <int DR, int MT, bool PRE, int MINB, int MODE>
+template <int DR, int MT, bool PRE, int MINB, int MODE, bool F>
 __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const float *__restrict__ z,
     bf16_t *__restrict__ y, const bf16_t *__restrict__ dy, float *__restrict__ lse_dec2,
@@ -229,7 +311,7 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
     bf16x8 qh[MT][KS], ql[MT][KS];
 #pragma unroll
     for (int t = 0; t < MT; ++t)
-        load_q_operand<DR, PRE>(q + ((size_t)h * Mtot + m0 + 32 * t + l32) * DR, hh, c2, flip, qh[t], ql[t]);
+        load_q_operand<DR, PRE, F>(q + ((size_t)h * Mtot + m0 + 32 * t + l32) * DR, hh, c2, flip, qh[t], ql[t]);
 
     // Zaug^T operand: row l32 (< 16: column 16*hv + l32 of Z; 16: ones; else zero).  In registers, or --
     // for the shapes whose registers would not allow two waves per SIMD otherwise (ZLDS = !PRE) --
@@ -290,7 +372,7 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
         auto qk_hi = [&](int t) {
             f32x16 r = splat16(0.f);
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) r = mfma(qh[t][ks], kt[ks], r);
+            for (int ks = 0; ks < KS; ++ks) r = mfma_s<F>(qh[t][ks], kt[ks], r);
             return r;
         };
 
@@ -320,10 +402,10 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
         auto qk_full = [&](int t) {
             f32x16 r = cinit;
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) r = mfma(qh[t][ks], kt2[ks], r);
+            for (int ks = 0; ks < KS; ++ks) r = mfma_s<F>(qh[t][ks], kt2[ks], r);
             if constexpr (PRE) {
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) r = mfma(ql[t][ks], kt[ks], r);
+                for (int ks = 0; ks < KS; ++ks) r = mfma_s<F>(ql[t][ks], kt[ks], r);
             }
             return r;
         };
@@ -388,14 +470,14 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
                 g0[0] = 0u; g0[1] = 0u; g1[0] = 0u; g1[1] = 0u;
                 if (quartet_inside<DR>(hv, hh, 0)) g0 = *reinterpret_cast<const u32x2 *>(gr + 16 * hv + 4 * hh);
                 if (quartet_inside<DR>(hv, hh, 1)) g1 = *reinterpret_cast<const u32x2 *>(gr + 16 * hv + 8 + 4 * hh);
-                part = fmaf(acc[hv][0] * inv, bf16_lo(g0[0]), part);
-                part = fmaf(acc[hv][1] * inv, bf16_hi(g0[0]), part);
-                part = fmaf(acc[hv][2] * inv, bf16_lo(g0[1]), part);
-                part = fmaf(acc[hv][3] * inv, bf16_hi(g0[1]), part);
-                part = fmaf(acc[hv][4] * inv, bf16_lo(g1[0]), part);
-                part = fmaf(acc[hv][5] * inv, bf16_hi(g1[0]), part);
-                part = fmaf(acc[hv][6] * inv, bf16_lo(g1[1]), part);
-                part = fmaf(acc[hv][7] * inv, bf16_hi(g1[1]), part);
+                part = fmaf(acc[hv][0] * inv, elem_lo<F>(g0[0]), part);
+                part = fmaf(acc[hv][1] * inv, elem_hi<F>(g0[0]), part);
+                part = fmaf(acc[hv][2] * inv, elem_lo<F>(g0[1]), part);
+                part = fmaf(acc[hv][3] * inv, elem_hi<F>(g0[1]), part);
+                part = fmaf(acc[hv][4] * inv, elem_lo<F>(g1[0]), part);
+                part = fmaf(acc[hv][5] * inv, elem_hi<F>(g1[0]), part);
+                part = fmaf(acc[hv][6] * inv, elem_lo<F>(g1[1]), part);
+                part = fmaf(acc[hv][7] * inv, elem_hi<F>(g1[1]), part);
             }
             part += __shfl_xor(part, 32);
             // the stabiliser that was actually subtracted
@@ -412,10 +494,10 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
 #pragma unroll
             for (int hv = 0; hv < HV; ++hv) {
                 u32x2 w0, w1;
-                w0[0] = cvt_pk_bf16(acc[hv][0] * inv, acc[hv][1] * inv);
-                w0[1] = cvt_pk_bf16(acc[hv][2] * inv, acc[hv][3] * inv);
-                w1[0] = cvt_pk_bf16(acc[hv][4] * inv, acc[hv][5] * inv);
-                w1[1] = cvt_pk_bf16(acc[hv][6] * inv, acc[hv][7] * inv);
+                w0[0] = pack_elems<F>(acc[hv][0] * inv, acc[hv][1] * inv);
+                w0[1] = pack_elems<F>(acc[hv][2] * inv, acc[hv][3] * inv);
+                w1[0] = pack_elems<F>(acc[hv][4] * inv, acc[hv][5] * inv);
+                w1[1] = pack_elems<F>(acc[hv][6] * inv, acc[hv][7] * inv);
                 if (quartet_inside<DR>(hv, hh, 0)) *reinterpret_cast<u32x2 *>(yb + tok_off(ts_y, n) + 16 * hv + 4 * hh) = w0;
                 if (quartet_inside<DR>(hv, hh, 1))
                     *reinterpret_cast<u32x2 *>(yb + tok_off(ts_y, n) + 16 * hv + 8 + 4 * hh) = w1;
@@ -459,7 +541,7 @@ constexpr int kVtStride = 36;   // uint16 per LDS row: 32 tokens + 4 pad (72 B, 
 // loop), and the waves of latent group 0 store it to delta_out for the two kernels that follow.
 // Those waves also record the smallest and largest lse_dec2 they met, ld_range[part] = (min, max),
 // from which bwd_plan_kernel decides which variant of the next two kernels may run.
-template <int DR, int NB, int MINB, int MODE>
+template <int DR, int NB, int MINB, int MODE, bool F>
 __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const float *__restrict__ lse_dec2, float ld_mul, const bf16_t *__restrict__ y_tok,
@@ -493,7 +575,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     bf16x8 qh[NB][KS], ql[NB][KS];
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
-        load_q_operand<DR, true>(q + ((size_t)h * M + lat0 + 32 * b + l32) * DR, hh, c2, false, qh[b], ql[b]);
+        load_q_operand<DR, true, F>(q + ((size_t)h * M + lat0 + 32 * b + l32) * DR, hh, c2, false, qh[b], ql[b]);
     }
     u32x4 wzero;
     wzero[0] = 0u; wzero[1] = 0u; wzero[2] = 0u; wzero[3] = 0u;
@@ -544,10 +626,11 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
 #pragma unroll
         for (int i = 0; i < LOADS; ++i) {
             const int d0 = 8 * ((lane & 1) * LOADS + i);
+            const u32x4 wv = to_bf16_row<F>(vv[i]);   // the value side of the second product is bf16
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                buf[(d0 + 2 * e) * kVtStride + vtok] = (uint16_t)(vv[i][e] & 0xffffu);
-                buf[(d0 + 2 * e + 1) * kVtStride + vtok] = (uint16_t)(vv[i][e] >> 16);
+                buf[(d0 + 2 * e) * kVtStride + vtok] = (uint16_t)(wv[e] & 0xffffu);
+                buf[(d0 + 2 * e + 1) * kVtStride + vtok] = (uint16_t)(wv[e] >> 16);
             }
         }
     };
@@ -565,19 +648,19 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
             }
     };
     u32x4 w23;
-    w23[0] = 0u; w23[1] = hh == 0 ? 0x3f803f80u : 0u; w23[2] = 0u; w23[3] = 0u;
+    w23[0] = 0u; w23[1] = hh == 0 ? kOnePair<F> : 0u; w23[2] = 0u; w23[3] = 0u;
     const bf16x8 ones23 = as_bf16x8(w23);      // query side of the correction k-step: slots 2,3 = 1
     // scores minus the stabiliser of latent tile b against the token tile (kk; kk0a = key side of the correction k-step)
     auto qk = [&](int b, const bf16x8 (&kk)[KS], bf16x8 kk0a) {
         f32x16 r = splat16(0.f);
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) r = mfma(kk[ks], qh[b][ks], r);
+        for (int ks = 0; ks < KS; ++ks) r = mfma_s<F>(kk[ks], qh[b][ks], r);
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) r = mfma(kk[ks], ql[b][ks], r);
-        r = mfma(kk0a, MODE == 0 ? caug[MODE == 0 ? b : 0] : ones23, r);
+        for (int ks = 0; ks < KS; ++ks) r = mfma_s<F>(kk[ks], ql[b][ks], r);
+        r = mfma_s<F>(kk0a, MODE == 0 ? caug[MODE == 0 ? b : 0] : ones23, r);
         return r;
     };
-    const uint32_t one0 = hh == 0 ? 0x3f80u : 0u;
+    const uint32_t one0 = hh == 0 ? kOne<F> : 0u;
     const float *lb = (MODE == 1) ? lse_dec2 + (size_t)bh * N : nullptr;
     // Key operand of the correction k-step.  MODE 0: slot 0 := 1, else zero.  MODE 1: zero except
     // slots 2,3 := -lse_dec2 of this lane's token (hi + lo pair).
@@ -586,7 +669,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         else {
             u32x4 w;
             w[0] = 0u; w[2] = 0u; w[3] = 0u;
-            w[1] = hh == 0 ? split_bf16_pair(neg_lse) : 0u;
+            w[1] = hh == 0 ? split_pair<F>(neg_lse) : 0u;
             return as_bf16x8(w);
         }
     };
@@ -609,8 +692,8 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         for (int i = 0; i < LOADS; ++i)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                part = fmaf(bf16_lo(gv[i][e]), bf16_lo(yy[i][e]), part);
-                part = fmaf(bf16_hi(gv[i][e]), bf16_hi(yy[i][e]), part);
+                part = fmaf(elem_lo<F>(gv[i][e]), elem_lo<F>(yy[i][e]), part);
+                part = fmaf(elem_hi<F>(gv[i][e]), elem_hi<F>(yy[i][e]), part);
             }
         // the other half of the row is in the neighbouring lane: quad_perm [1,0,3,2]
         part += __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(part), 0xB1, 0xf, 0xf, true));
@@ -677,7 +760,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
                 float mx = (MODE == 0) ? max16(sc, -INFINITY) : 0.f;
                 if (MODE == 0 && (first || __any(mx > kLazy))) {
                     mx = fmaxf(mx, __shfl_xor(mx, 32));   // both lane halves hold tokens of the same latent
-                    const float cn = bf16_round(c[b] + (first ? mx : fmaxf(mx, 0.f)));
+                    const float cn = elem_round<F>(c[b] + (first ? mx : fmaxf(mx, 0.f)));
                     const float shift = cn - c[b];
                     if (!first) {
                         const float f = fast_exp2(-shift);
@@ -687,7 +770,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
                             for (int i = 0; i < 16; ++i) o[b][hv][i] *= f;
                     }
                     c[b] = cn;
-                    caug[b] = with_slot0(caug[b], keep0, hh == 0 ? rne_bf16(-cn) : 0u);
+                    caug[b] = with_slot0(caug[b], keep0, hh == 0 ? rne_elem<F>(-cn) : 0u);
 #pragma unroll
                     for (int i = 0; i < 16; ++i) sc[i] -= shift;
                     if constexpr (NB == 1) {   // the product already in flight is for this same latent tile
@@ -774,7 +857,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
 // fp32 range wherever R matters, which bwd_plan_kernel guarantees per (b,h) (plan[bh] = 1);
 // otherwise the ONE = false variant runs.  Each variant returns at once when the plan names the other.
 // ============================================================================================
-template <int DR, int NB, int MINB, bool ONE>
+template <int DR, int NB, int MINB, bool ONE, bool F>
 __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const bf16_t *__restrict__ dy, const float *__restrict__ z, const float *__restrict__ lse_enc,
@@ -818,7 +901,7 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         const int m = lat0 + 32 * b + l32;
-        load_q_operand<DR, true>(q + ((size_t)h * M + m) * DR, hh, c2, false, qh[b], ql[b]);
+        load_q_operand<DR, true, F>(q + ((size_t)h * M + m) * DR, hh, c2, false, qh[b], ql[b]);
         const float le2 = lse_enc[(size_t)bh * M + m] * kLog2e;
         const float um = ONE ? fast_exp2(le2 - kap) : 1.f;   // folded into Z
         if constexpr (ONE) {
@@ -830,8 +913,8 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
             u_aug[b] = as_bf16x8(wu);
         }
         u32x4 wq;
-        wq[0] = lower ? split_bf16_pair(-le2) : 0u;     // slots 0,1 := -lse_enc2 (hi + lo)
-        wq[1] = lower ? 0x3f803f80u : 0u;               // slots 2,3 := 1
+        wq[0] = lower ? split_pair<F>(-le2) : 0u;       // slots 0,1 := -lse_enc2 (hi + lo)
+        wq[1] = lower ? kOnePair<F> : 0u;               // slots 2,3 := 1
         wq[2] = 0u; wq[3] = 0u;
         q_aug[b] = as_bf16x8(wq);
 #pragma unroll
@@ -866,6 +949,9 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
     w11[0] = lower ? 0x3f803f80u : 0u;
     w11[1] = 0u; w11[2] = 0u; w11[3] = 0u;
     const bf16x8 ones_aug = as_bf16x8(w11);      // slots 0,1 = 1 in the lower lane half, else 0
+    w11[0] = lower ? kOnePair<F> : 0u;
+    const bf16x8 ones_s = as_bf16x8(w11);        // the same in the type of the score products
+    auto to_bf16 = [](bf16x8 x) { return as_bf16x8(to_bf16_row<F>(__builtin_bit_cast(u32x4, x))); };
 
     const bf16_t *kb = k + tok_base(ts, bh, H);
     const bf16_t *vb = v + tok_base(ts, bh, H);
@@ -897,7 +983,7 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
     auto write_kt = [&](const bf16x8 (&t)[KS], uint16_t *buf) {   // transposed: row = d-index, column = token
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            const u32x4 w = __builtin_bit_cast(u32x4, t[s]);
+            const u32x4 w = to_bf16_row<F>(__builtin_bit_cast(u32x4, t[s]));   // K as a value: bf16
             const int d0 = (D / 2) * hh + 8 * s;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -941,6 +1027,10 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
         load_rows(vb, 1, vtn);
         load_rows(gb, 0, gt);
         load_rows(gb, 1, gtn);
+        if constexpr (F) {   // V and dY meet bf16 operands: converted once, when they become current
+#pragma unroll
+            for (int s = 0; s < KS; ++s) { vt[s] = to_bf16(vt[s]); gt[s] = to_bf16(gt[s]); }
+        }
         nld = -lb[min(tile_tok0(0) + l32, N - 1)] * ld_mul;
         dl = db[min(tile_tok0(0) + l32, N - 1)];
         nldn = -lb[min(tile_tok0(1) + l32, N - 1)] * ld_mul;
@@ -968,8 +1058,8 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
             // token-side operands of the correction k-steps (zero outside the named slots)
             u32x4 wb;
             wb[0] = 0u; wb[2] = 0u; wb[3] = 0u;
-            wb[1] = lower ? split_bf16_pair(nld) : 0u;           // slots 2,3 := -lse_dec2[n]
-            const bf16x8 kt_a = ones_aug, kt_b = as_bf16x8(wb);  // slots 0,1 := 1 picks -lse_enc2
+            wb[1] = lower ? split_pair<F>(nld) : 0u;             // slots 2,3 := -lse_dec2[n]
+            const bf16x8 kt_a = ones_s, kt_b = as_bf16x8(wb);    // slots 0,1 := 1 picks -lse_enc2
             u32x4 wg;
             const uint32_t ds_ = split_bf16_pair(-dl);
             wg[0] = lower ? ds_ : 0u;
@@ -983,12 +1073,12 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
             for (int b = 0; b < NB; ++b) {
                 f32x16 x = splat16(0.f);
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) x = mfma(kt[ks], qh[b][ks], x);
+                for (int ks = 0; ks < KS; ++ks) x = mfma_s<F>(kt[ks], qh[b][ks], x);
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) x = mfma(kt[ks], ql[b][ks], x);
-                f32x16 s1 = mfma(kt_a, q_aug[b], x);
+                for (int ks = 0; ks < KS; ++ks) x = mfma_s<F>(kt[ks], ql[b][ks], x);
+                f32x16 s1 = mfma_s<F>(kt_a, q_aug[b], x);
                 f32x16 s2 = s1;
-                if constexpr (!ONE) s2 = mfma(kt_b, q_aug[b], x);
+                if constexpr (!ONE) s2 = mfma_s<F>(kt_b, q_aug[b], x);
                 f32x16 av = mfma(ones_aug, dz_aug[b], splat16(0.f));
                 f32x16 cv = mfma(g_aug, ONE ? u_aug[ONE ? b : 0] : ones_aug, splat16(0.f));
 #pragma unroll
@@ -1031,8 +1121,8 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
                 kt[s] = ktn[s]; ktn[s] = ktnn[s];
-                vt[s] = DEEP ? vtn[s] : vtnn[s]; vtn[s] = vtnn[s];
-                gt[s] = DEEP ? gtn[s] : gtnn[s]; gtn[s] = gtnn[s];
+                vt[s] = to_bf16(DEEP ? vtn[s] : vtnn[s]); vtn[s] = vtnn[s];
+                gt[s] = to_bf16(DEEP ? gtn[s] : gtnn[s]); gtn[s] = gtnn[s];
             }
             nld = DEEP ? nldn : nldnn; nldn = nldnn;
             dl = DEEP ? dln : dlnn; dln = dlnn;
@@ -1071,7 +1161,7 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
 // (and into slots 4-6 of the correction image, against -delta in the token operand), w[n] is a
 // per-lane scalar here, and dS' = P (a + w c).  Runs only where plan[bh] = 1.
 // ============================================================================================
-template <int DR, int MT, bool LO2, bool ONE>
+template <int DR, int MT, bool LO2, bool ONE, bool F>
 __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const bf16_t *__restrict__ dy, const float *__restrict__ z, const float *__restrict__ lse_enc,
@@ -1120,9 +1210,13 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
             if (sid == NA - 1) {
                 // correction operand: slots 0,1 = -lse_enc2 (hi + lo pair), slots 2,3 = 1, else zero
                 const float le2 = leb[32 * t + r32] * kLog2e;
-                w[0] = hf == 0 ? split_bf16_pair(-le2) : 0u;
-                w[1] = hf == 0 ? 0x3f803f80u : 0u;
+                w[0] = hf == 0 ? split_pair<F>(-le2) : 0u;
+                w[1] = hf == 0 ? kOnePair<F> : 0u;
                 w[2] = 0u; w[3] = 0u;
+                // Slots 4-6 belong to the c product, whose operands are bf16 whatever the storage type; the
+                // score products meet them with zeros in the token operand (and the c product meets slots
+                // 0-3 with zeros).  u <= 1 and finite 16-bit patterns of either type read as finite values
+                // of the other, so the foreign slots contribute exact zeros.
                 if constexpr (ONE) {   // slots 4,5,6 := u hi, u hi, u lo
                     const uint32_t us = split_bf16_pair(fast_exp2(le2 - kap));
                     w[2] = hf == 0 ? ((us & 0xffffu) | (us << 16)) : 0u;
@@ -1136,7 +1230,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                 if (kind <= 1) {
                     const u32x4 raw = row8_bf16<DR>(qh_ + (size_t)m * DR, d0);
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) { x[2 * i] = bf16_lo(raw[i]) * c2; x[2 * i + 1] = bf16_hi(raw[i]) * c2; }
+                    for (int i = 0; i < 4; ++i) { x[2 * i] = elem_lo<F>(raw[i]) * c2; x[2 * i + 1] = elem_hi<F>(raw[i]) * c2; }
                 } else {
                     const bool is_z = (kind == 3 || kind == 5);
                     row8_f32<DR>((is_z ? zb : dzb) + (size_t)m * DR, d0, x);
@@ -1147,10 +1241,19 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                 const bool want_lo = (kind == 1 || kind >= 4);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    uint32_t a = rne_bf16(x[2 * i]), b = rne_bf16(x[2 * i + 1]);
-                    if (want_lo) {
-                        a = rne_bf16(x[2 * i] - __uint_as_float(a << 16));
-                        b = rne_bf16(x[2 * i + 1] - __uint_as_float(b << 16));
+                    uint32_t a, b;
+                    if (kind <= 1) {   // q' feeds the score products: storage type
+                        a = rne_elem<F>(x[2 * i]); b = rne_elem<F>(x[2 * i + 1]);
+                        if (want_lo) {
+                            a = rne_elem<F>(x[2 * i] - elem_value<F>(a));
+                            b = rne_elem<F>(x[2 * i + 1] - elem_value<F>(b));
+                        }
+                    } else {
+                        a = rne_bf16(x[2 * i]); b = rne_bf16(x[2 * i + 1]);
+                        if (want_lo) {
+                            a = rne_bf16(x[2 * i] - __uint_as_float(a << 16));
+                            b = rne_bf16(x[2 * i + 1] - __uint_as_float(b << 16));
+                        }
                     }
                     w[i] = a | (b << 16);
                 }
@@ -1163,8 +1266,8 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                     float a, b;
                     const int m0 = 32 * t + perm_index(s2, hf, i), m1 = 32 * t + perm_index(s2, hf, i + 1);
                     const bool in = dd < DR;   // beyond the real head dimension every row image is zero
-                    const float q0 = in ? __uint_as_float((uint32_t)qh_[(size_t)m0 * DR + dd] << 16) : 0.f;
-                    const float q1 = in ? __uint_as_float((uint32_t)qh_[(size_t)m1 * DR + dd] << 16) : 0.f;
+                    const float q0 = in ? elem_value<F>(qh_[(size_t)m0 * DR + dd]) : 0.f;
+                    const float q1 = in ? elem_value<F>(qh_[(size_t)m1 * DR + dd]) : 0.f;
                     if (which == 0) {
                         a = (r32 < 16) ? (in ? dzb[(size_t)m0 * DR + dd] : 0.f) : -eb[m0] * q0;
                         b = (r32 < 16) ? (in ? dzb[(size_t)m1 * DR + dd] : 0.f) : -eb[m1] * q1;
@@ -1184,6 +1287,9 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     w11[0] = lower ? 0x3f803f80u : 0u;
     w11[1] = 0u; w11[2] = 0u; w11[3] = 0u;
     const bf16x8 ones_aug = as_bf16x8(w11);
+    w11[0] = lower ? kOnePair<F> : 0u;
+    const bf16x8 ones_s = as_bf16x8(w11);        // the same in the type of the score products
+    auto to_bf16 = [](bf16x8 x) { return as_bf16x8(to_bf16_row<F>(__builtin_bit_cast(u32x4, x))); };
 
     const bf16_t *kb = k + tok_base(ts, bh, H);
     const bf16_t *vb = v + tok_base(ts, bh, H);
@@ -1206,6 +1312,8 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
         load_cols(kb, tile, kt);
         load_cols(vb, tile, vt);
         load_cols(gb, tile, gt);
+#pragma unroll
+        for (int s = 0; s < KS; ++s) { vt[s] = to_bf16(vt[s]); gt[s] = to_bf16(gt[s]); }
     }
     for (; tile < tiles; tile += stride) {
         const int n = tile * 32 + l32;
@@ -1219,8 +1327,8 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
 
         u32x4 wb;
         wb[0] = 0u; wb[2] = 0u; wb[3] = 0u;
-        wb[1] = lower ? split_bf16_pair(nld) : 0u;           // slots 2,3 := -lse_dec2[n]
-        const bf16x8 kt_a = ones_aug, kt_b = as_bf16x8(wb);  // slots 0,1 := 1 picks -lse_enc2
+        wb[1] = lower ? split_pair<F>(nld) : 0u;             // slots 2,3 := -lse_dec2[n]
+        const bf16x8 kt_a = ones_s, kt_b = as_bf16x8(wb);    // slots 0,1 := 1 picks -lse_enc2
         u32x4 wg;
         const uint32_t ds_ = split_bf16_pair(-dl);
         wg[0] = (!ONE && lower) ? ds_ : 0u;                  // two exponentials: slots 0,1 := -delta (hi, lo)
@@ -1237,12 +1345,12 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
         auto scores = [&](int t, f32x16 &s1, f32x16 &s2) {
             f32x16 x = splat16(0.f);
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) x = mfma(image(t, 0 * KS + ks), kt[ks], x);
+            for (int ks = 0; ks < KS; ++ks) x = mfma_s<F>(image(t, 0 * KS + ks), kt[ks], x);
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) x = mfma(image(t, 1 * KS + ks), kt[ks], x);
+            for (int ks = 0; ks < KS; ++ks) x = mfma_s<F>(image(t, 1 * KS + ks), kt[ks], x);
             const bf16x8 qa = image(t, NA - 1);
-            s1 = mfma(qa, kt_a, x);
-            if constexpr (!ONE) s2 = mfma(qa, kt_b, x);
+            s1 = mfma_s<F>(qa, kt_a, x);
+            if constexpr (!ONE) s2 = mfma_s<F>(qa, kt_b, x);
         };
         // One latent tile, software-pipelined: the a and c products of tile t and the score products
         // of tile t+1 are issued first and run on the matrix cores while the vector ALUs
@@ -1335,22 +1443,22 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
 #pragma unroll
             for (int hv = 0; hv < HV; ++hv) {
                 u32x2 w0, w1;
-                w0[0] = cvt_pk_bf16(acc1[hv][0], acc1[hv][1]);
-                w0[1] = cvt_pk_bf16(acc1[hv][2], acc1[hv][3]);
-                w1[0] = cvt_pk_bf16(acc1[hv][4], acc1[hv][5]);
-                w1[1] = cvt_pk_bf16(acc1[hv][6], acc1[hv][7]);
+                w0[0] = pack_elems<F>(acc1[hv][0], acc1[hv][1]);
+                w0[1] = pack_elems<F>(acc1[hv][2], acc1[hv][3]);
+                w1[0] = pack_elems<F>(acc1[hv][4], acc1[hv][5]);
+                w1[1] = pack_elems<F>(acc1[hv][6], acc1[hv][7]);
                 if (quartet_inside<DR>(hv, hh, 0)) *reinterpret_cast<u32x2 *>(dvr + 16 * hv + 4 * hh) = w0;
                 if (quartet_inside<DR>(hv, hh, 1)) *reinterpret_cast<u32x2 *>(dvr + 16 * hv + 8 + 4 * hh) = w1;
-                w0[0] = cvt_pk_bf16(scale * (acc2[hv][0] + acc1[hv][8]), scale * (acc2[hv][1] + acc1[hv][9]));
-                w0[1] = cvt_pk_bf16(scale * (acc2[hv][2] + acc1[hv][10]), scale * (acc2[hv][3] + acc1[hv][11]));
-                w1[0] = cvt_pk_bf16(scale * (acc2[hv][4] + acc1[hv][12]), scale * (acc2[hv][5] + acc1[hv][13]));
-                w1[1] = cvt_pk_bf16(scale * (acc2[hv][6] + acc1[hv][14]), scale * (acc2[hv][7] + acc1[hv][15]));
+                w0[0] = pack_elems<F>(scale * (acc2[hv][0] + acc1[hv][8]), scale * (acc2[hv][1] + acc1[hv][9]));
+                w0[1] = pack_elems<F>(scale * (acc2[hv][2] + acc1[hv][10]), scale * (acc2[hv][3] + acc1[hv][11]));
+                w1[0] = pack_elems<F>(scale * (acc2[hv][4] + acc1[hv][12]), scale * (acc2[hv][5] + acc1[hv][13]));
+                w1[1] = pack_elems<F>(scale * (acc2[hv][6] + acc1[hv][14]), scale * (acc2[hv][7] + acc1[hv][15]));
                 if (quartet_inside<DR>(hv, hh, 0)) *reinterpret_cast<u32x2 *>(dkr + 16 * hv + 4 * hh) = w0;
                 if (quartet_inside<DR>(hv, hh, 1)) *reinterpret_cast<u32x2 *>(dkr + 16 * hv + 8 + 4 * hh) = w1;
             }
         }
 #pragma unroll
-        for (int s = 0; s < KS; ++s) { kt[s] = ktn[s]; vt[s] = vtn[s]; gt[s] = gtn[s]; }
+        for (int s = 0; s < KS; ++s) { kt[s] = ktn[s]; vt[s] = to_bf16(vtn[s]); gt[s] = to_bf16(gtn[s]); }
     }
 }
 
@@ -1381,7 +1489,7 @@ __global__ __launch_bounds__(64 * MT) void gram_mfma_kernel(
     const bool lower = hh == 0;
 
     bf16x8 qh[KS], ql[KS];
-    load_q_operand<DR, true>(q + ((size_t)h * M + 32 * wave + l32) * DR, hh, c2, false, qh, ql);
+    load_q_operand<DR, true, false>(q + ((size_t)h * M + 32 * wave + l32) * DR, hh, c2, false, qh, ql);
     u32x4 wq;
     wq[0] = lower ? split_bf16_pair(-0.5f * kLog2e * lse_enc[(size_t)bh * M + 32 * wave + l32]) : 0u;
     wq[1] = lower ? 0x3f803f80u : 0u;      // slots 2,3 := 1 (pick the token's half-normaliser)
@@ -1488,7 +1596,7 @@ constexpr int kDecodeTargetBlocks = 512;
 
 bool mfma_supported(const flare_shape &s)
 {
-    if (s.dtype != FLARE_BF16) return false;
+    if (s.dtype != FLARE_BF16 && s.dtype != FLARE_F16) return false;
     if (s.d != 4 && s.d != 8 && s.d != 16 && s.d != 32) return false;   // d < 16 runs padded to 16
     if (s.M == 32) return true;
     if (s.M > kLatChunk) return s.M % kLatChunk == 0 && s.M <= 2048;   // whole chunks of 256 latents
@@ -1531,10 +1639,18 @@ int mfma_encode(const flare_shape &s, const void *q, const void *k, const void *
     const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *vv = (const bf16_t *)v;
     {
         LaunchTimer t(KID_ENCODE_PARTIAL, stream);
-#define FLARE_ENC(DD, NBB)                                                                                   \
-    encode_mfma_kernel<DD, NBB, 2, 0><<<grid, e.threads, 0, stream>>>(qq, kk, vv, nullptr, 1.f, nullptr, nullptr, nullptr, m_part, l_part, o_part, \
-                                                                      tok_stride(s), s.H, s.N, s.M, p.enc.chunk_len, p.parts, e.G, \
-                                                                      e.TG, c2)
+        const bool f16 = s.dtype == FLARE_F16;
+#define FLARE_ENC(DD, NBB)                                                                                        \
+    do {                                                                                                          \
+        if (f16)                                                                                                  \
+            encode_mfma_kernel<DD, NBB, 2, 0, true><<<grid, e.threads, 0, stream>>>(                              \
+                qq, kk, vv, nullptr, 1.f, nullptr, nullptr, nullptr, m_part, l_part, o_part, tok_stride(s), s.H,  \
+                s.N, s.M, p.enc.chunk_len, p.parts, e.G, e.TG, c2);                                               \
+        else                                                                                                      \
+            encode_mfma_kernel<DD, NBB, 2, 0, false><<<grid, e.threads, 0, stream>>>(                             \
+                qq, kk, vv, nullptr, 1.f, nullptr, nullptr, nullptr, m_part, l_part, o_part, tok_stride(s), s.H,  \
+                s.N, s.M, p.enc.chunk_len, p.parts, e.G, e.TG, c2);                                               \
+    } while (0)
 #define FLARE_ENC_NB(DD)                   \
     do {                                   \
         if (e.NB == 1) FLARE_ENC(DD, 1);   \
@@ -1568,10 +1684,18 @@ int mfma_dz_partial(const flare_shape &s, const void *q, const void *k, const vo
     const dim3 grid(p.enc.chunks, BH, lat_chunks(s.M));
     const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *gg = (const bf16_t *)dy;
     LaunchTimer t(KID_BWD_DZ_PARTIAL, stream);
-#define FLARE_DZ(DD, NBB)                                                                                      \
-    encode_mfma_kernel<DD, NBB, 2, 1><<<grid, e.threads, 0, stream>>>(qq, kk, gg, lse_dec2, ld_mul, (const bf16_t *)y, delta_out, ld_range, nullptr, nullptr, dz_part, \
-                                                                      tok_stride(s), s.H, s.N, s.M, p.enc.chunk_len, p.parts, e.G,  \
-                                                                      e.TG, c2)
+    const bool f16 = s.dtype == FLARE_F16;
+#define FLARE_DZ(DD, NBB)                                                                                         \
+    do {                                                                                                          \
+        if (f16)                                                                                                  \
+            encode_mfma_kernel<DD, NBB, 2, 1, true><<<grid, e.threads, 0, stream>>>(                              \
+                qq, kk, gg, lse_dec2, ld_mul, (const bf16_t *)y, delta_out, ld_range, nullptr, nullptr, dz_part,  \
+                tok_stride(s), s.H, s.N, s.M, p.enc.chunk_len, p.parts, e.G, e.TG, c2);                           \
+        else                                                                                                      \
+            encode_mfma_kernel<DD, NBB, 2, 1, false><<<grid, e.threads, 0, stream>>>(                             \
+                qq, kk, gg, lse_dec2, ld_mul, (const bf16_t *)y, delta_out, ld_range, nullptr, nullptr, dz_part,  \
+                tok_stride(s), s.H, s.N, s.M, p.enc.chunk_len, p.parts, e.G, e.TG, c2);                           \
+    } while (0)
 #define FLARE_DZ_NB(DD)                   \
     do {                                  \
         if (e.NB == 1) FLARE_DZ(DD, 1);   \
@@ -1606,16 +1730,20 @@ int mfma_dq_partial(const flare_shape &s, const void *q, const void *k, const vo
     const dim3 grid(p.enc.chunks, BH, zdim);
     const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *vv = (const bf16_t *)v, *gg = (const bf16_t *)dy;
     LaunchTimer t(one_exp ? KID_BWD_DQ_PARTIAL : KID_BWD_DQ_PARTIAL_2EXP, stream);
+    const bool f16 = s.dtype == FLARE_F16;
+#define FLARE_DQ_ARGS                                                                                            \
+    qq, kk, vv, gg, z, lse_enc, dz, eps, lse_dec2, delta, ld_mul, plan, dq_part, tok_stride(s), s.H, s.N, s.M,   \
+        p.enc.chunk_len, parts, e.G, e.TG, c2
 #define FLARE_DQ(DD, NBB, MINB)                                                                                  \
     do {                                                                                                         \
-        if (one_exp)                                                                                             \
-            bwd_dq_mfma_kernel<DD, NBB, MINB, true><<<grid, e.threads, 0, stream>>>(                             \
-                qq, kk, vv, gg, z, lse_enc, dz, eps, lse_dec2, delta, ld_mul, plan, dq_part, tok_stride(s), s.H, \
-                s.N, s.M, p.enc.chunk_len, parts, e.G, e.TG, c2);                                                \
+        if (one_exp && f16)                                                                                      \
+            bwd_dq_mfma_kernel<DD, NBB, MINB, true, true><<<grid, e.threads, 0, stream>>>(FLARE_DQ_ARGS);        \
+        else if (one_exp)                                                                                        \
+            bwd_dq_mfma_kernel<DD, NBB, MINB, true, false><<<grid, e.threads, 0, stream>>>(FLARE_DQ_ARGS);       \
+        else if (f16)                                                                                            \
+            bwd_dq_mfma_kernel<DD, NBB, MINB, false, true><<<grid, e.threads, 0, stream>>>(FLARE_DQ_ARGS);       \
         else                                                                                                     \
-            bwd_dq_mfma_kernel<DD, NBB, MINB, false><<<grid, e.threads, 0, stream>>>(                            \
-                qq, kk, vv, gg, z, lse_enc, dz, eps, lse_dec2, delta, ld_mul, plan, dq_part, tok_stride(s), s.H, \
-                s.N, s.M, p.enc.chunk_len, parts, e.G, e.TG, c2);                                                \
+            bwd_dq_mfma_kernel<DD, NBB, MINB, false, false><<<grid, e.threads, 0, stream>>>(FLARE_DQ_ARGS);      \
     } while (0)
 #define FLARE_DQ_NB(DD)                      \
     do {                                     \
@@ -1632,6 +1760,7 @@ int mfma_dq_partial(const flare_shape &s, const void *q, const void *k, const vo
     }
 #undef FLARE_DQ_NB
 #undef FLARE_DQ
+#undef FLARE_DQ_ARGS
     return check_launch();
 }
 
@@ -1661,10 +1790,14 @@ int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v,
     const int KS = pd / 16, HV = pd / 16;
     const size_t lds = (size_t)MT * ((lo2 ? 6 : 4) * KS + 1 + 4 * HV) * 1024;
     const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *vv = (const bf16_t *)v, *gg = (const bf16_t *)dy;
+    const bool f16 = s.dtype == FLARE_F16;
     LaunchTimer t(one_exp ? KID_BWD_DKDV : KID_BWD_DKDV_2EXP, stream);
 #define FLARE_DKDV(DD, MTT, LO)                                                                                  \
     do {                                                                                                         \
-        auto kern = one_exp ? bwd_dkdv_mfma_kernel<DD, MTT, LO, true> : bwd_dkdv_mfma_kernel<DD, MTT, LO, false>; \
+        auto kern = f16 ? (one_exp ? bwd_dkdv_mfma_kernel<DD, MTT, LO, true, true>                               \
+                                   : bwd_dkdv_mfma_kernel<DD, MTT, LO, false, true>)                             \
+                        : (one_exp ? bwd_dkdv_mfma_kernel<DD, MTT, LO, true, false>                              \
+                                   : bwd_dkdv_mfma_kernel<DD, MTT, LO, false, false>);                           \
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
                                 (int)lds) != hipSuccess)                                                         \
             return FLARE_ELAUNCH;                                                                                \
@@ -1701,7 +1834,7 @@ int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v,
 
 // fp32 sums of the per-chunk dV and dK rows (M > 256) -> dk, dv in the caller's layout
 namespace {
-template <int DR>
+template <int DR, bool F>
 __global__ __launch_bounds__(256) void dkdv_finish_kernel(const float *__restrict__ acc32, bf16_t *__restrict__ dk,
                                                           bf16_t *__restrict__ dv, TokStride ts, int H, int N)
 {
@@ -1716,8 +1849,8 @@ __global__ __launch_bounds__(256) void dkdv_finish_kernel(const float *__restric
         const float4 a = *reinterpret_cast<const float4 *>(sv + j);
         const float4 b = *reinterpret_cast<const float4 *>(sk + j);
         u32x2 wa, wb;
-        wa[0] = cvt_pk_bf16(a.x, a.y); wa[1] = cvt_pk_bf16(a.z, a.w);
-        wb[0] = cvt_pk_bf16(b.x, b.y); wb[1] = cvt_pk_bf16(b.z, b.w);
+        wa[0] = pack_elems<F>(a.x, a.y); wa[1] = pack_elems<F>(a.z, a.w);
+        wb[0] = pack_elems<F>(b.x, b.y); wb[1] = pack_elems<F>(b.z, b.w);
         *reinterpret_cast<u32x2 *>(dv + trow + j) = wa;
         *reinterpret_cast<u32x2 *>(dk + trow + j) = wb;
     }
@@ -1734,12 +1867,23 @@ int mfma_dkdv_finish(const flare_shape &s, const float *acc32, void *dk, void *d
 {
     const dim3 grid((s.N + 255) / 256, s.B * s.H);
     LaunchTimer t(KID_BWD_DKDV_FINISH, stream);
+    const bool f16 = s.dtype == FLARE_F16;
+#define FLARE_FIN(DD)                                                                                          \
+    do {                                                                                                       \
+        if (f16)                                                                                               \
+            dkdv_finish_kernel<DD, true><<<grid, 256, 0, stream>>>(acc32, (bf16_t *)dk, (bf16_t *)dv,          \
+                                                                   tok_stride(s), s.H, s.N);                   \
+        else                                                                                                   \
+            dkdv_finish_kernel<DD, false><<<grid, 256, 0, stream>>>(acc32, (bf16_t *)dk, (bf16_t *)dv,         \
+                                                                    tok_stride(s), s.H, s.N);                  \
+    } while (0)
     switch (s.d) {
-        case 4: dkdv_finish_kernel<4><<<grid, 256, 0, stream>>>(acc32, (bf16_t *)dk, (bf16_t *)dv, tok_stride(s), s.H, s.N); break;
-        case 8: dkdv_finish_kernel<8><<<grid, 256, 0, stream>>>(acc32, (bf16_t *)dk, (bf16_t *)dv, tok_stride(s), s.H, s.N); break;
-        case 16: dkdv_finish_kernel<16><<<grid, 256, 0, stream>>>(acc32, (bf16_t *)dk, (bf16_t *)dv, tok_stride(s), s.H, s.N); break;
-        default: dkdv_finish_kernel<32><<<grid, 256, 0, stream>>>(acc32, (bf16_t *)dk, (bf16_t *)dv, tok_stride(s), s.H, s.N); break;
+        case 4: FLARE_FIN(4); break;
+        case 8: FLARE_FIN(8); break;
+        case 16: FLARE_FIN(16); break;
+        default: FLARE_FIN(32); break;
     }
+#undef FLARE_FIN
     return check_launch();
 }
 
@@ -1822,9 +1966,16 @@ static int launch_decode_family(const flare_shape &s, const void *q, const void 
     const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *gg = (const bf16_t *)dy;
     bf16_t *yy = (bf16_t *)y;
     LaunchTimer t(MODE == 0 ? KID_DECODE : KID_BWD_TOKEN_STATS, stream);
+    const bool f16 = s.dtype == FLARE_F16;
 #define FLARE_DEC(DD, MTT, PREE, MINB)                                                                          \
-    decode_mfma_kernel<DD, MTT, PREE, MINB, MODE><<<grid, 256, 0, stream>>>(qq, kk, z, yy, gg, lse_dec2, delta,      \
-                                                                            tok_stride(s), ts_y, s.H, s.N, s.M, m0, c2)
+    do {                                                                                                        \
+        if (f16)                                                                                                \
+            decode_mfma_kernel<DD, MTT, PREE, MINB, MODE, true><<<grid, 256, 0, stream>>>(                      \
+                qq, kk, z, yy, gg, lse_dec2, delta, tok_stride(s), ts_y, s.H, s.N, s.M, m0, c2);                \
+        else                                                                                                    \
+            decode_mfma_kernel<DD, MTT, PREE, MINB, MODE, false><<<grid, 256, 0, stream>>>(                     \
+                qq, kk, z, yy, gg, lse_dec2, delta, tok_stride(s), ts_y, s.H, s.N, s.M, m0, c2);                \
+    } while (0)
     const int MT = Mc / 32;
 #define FLARE_DEC_MT(DD)                               \
     switch (MT) {                                      \
@@ -1862,7 +2013,7 @@ namespace {
 // MODE 0 writes y in the caller's layout and, when asked, lse_dec (natural log);
 // MODE 1 writes lse_dec2 = lse * log2(e) and delta = <dY_n, y> with y kept in fp32.
 // thread = token; the partial rows are [chunk][b*h][n][DR] bf16, the partial lse [chunk][b*h][n].
-template <int DR, int MODE>
+template <int DR, int MODE, bool F>
 __global__ __launch_bounds__(256) void decode_merge_kernel(
     const bf16_t *__restrict__ y_part, const float *__restrict__ lse_part, int chunks, bf16_t *__restrict__ y,
     const bf16_t *__restrict__ dy, float *__restrict__ lse_out, float *__restrict__ delta, TokStride ts, int H,
@@ -1884,10 +2035,10 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(
 #pragma unroll
         for (int j = 0; j < DR; j += 4) {
             const u32x2 t = *reinterpret_cast<const u32x2 *>(src + j);
-            acc[j] = fmaf(w, bf16_lo(t[0]), acc[j]);
-            acc[j + 1] = fmaf(w, bf16_hi(t[0]), acc[j + 1]);
-            acc[j + 2] = fmaf(w, bf16_lo(t[1]), acc[j + 2]);
-            acc[j + 3] = fmaf(w, bf16_hi(t[1]), acc[j + 3]);
+            acc[j] = fmaf(w, elem_lo<F>(t[0]), acc[j]);
+            acc[j + 1] = fmaf(w, elem_hi<F>(t[0]), acc[j + 1]);
+            acc[j + 2] = fmaf(w, elem_lo<F>(t[1]), acc[j + 2]);
+            acc[j + 3] = fmaf(w, elem_hi<F>(t[1]), acc[j + 3]);
         }
     }
     const float inv = 1.f / tot;
@@ -1897,8 +2048,8 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(
 #pragma unroll
         for (int j = 0; j < DR; j += 4) {
             u32x2 w;
-            w[0] = cvt_pk_bf16(acc[j] * inv, acc[j + 1] * inv);
-            w[1] = cvt_pk_bf16(acc[j + 2] * inv, acc[j + 3] * inv);
+            w[0] = pack_elems<F>(acc[j] * inv, acc[j + 1] * inv);
+            w[1] = pack_elems<F>(acc[j + 2] * inv, acc[j + 3] * inv);
             *reinterpret_cast<u32x2 *>(y + trow + j) = w;
         }
         if (lse_out) lse_out[row] = lse;
@@ -1907,10 +2058,10 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(
 #pragma unroll
         for (int j = 0; j < DR; j += 4) {
             const u32x2 g = *reinterpret_cast<const u32x2 *>(dy + trow + j);
-            dl = fmaf(acc[j] * inv, bf16_lo(g[0]), dl);
-            dl = fmaf(acc[j + 1] * inv, bf16_hi(g[0]), dl);
-            dl = fmaf(acc[j + 2] * inv, bf16_lo(g[1]), dl);
-            dl = fmaf(acc[j + 3] * inv, bf16_hi(g[1]), dl);
+            dl = fmaf(acc[j] * inv, elem_lo<F>(g[0]), dl);
+            dl = fmaf(acc[j + 1] * inv, elem_hi<F>(g[0]), dl);
+            dl = fmaf(acc[j + 2] * inv, elem_lo<F>(g[1]), dl);
+            dl = fmaf(acc[j + 3] * inv, elem_hi<F>(g[1]), dl);
         }
         lse_out[row] = lse * kLog2e;
         delta[row] = dl;
@@ -1946,9 +2097,16 @@ static int decode_all(const flare_shape &s, const void *q, const void *k, const 
     }
     const dim3 grid((s.N + 255) / 256, s.B * s.H);
     LaunchTimer t(KID_DECODE_MERGE, stream);
-#define FLARE_DM(DD)                                                                                           \
-    decode_merge_kernel<DD, MODE><<<grid, 256, 0, stream>>>(y_part, lse_part, C, (bf16_t *)y, (const bf16_t *)dy, \
-                                                            lse_out, delta, tok_stride(s), s.H, s.N, rows)
+    const bool f16 = s.dtype == FLARE_F16;
+#define FLARE_DM(DD)                                                                                               \
+    do {                                                                                                           \
+        if (f16)                                                                                                   \
+            decode_merge_kernel<DD, MODE, true><<<grid, 256, 0, stream>>>(                                         \
+                y_part, lse_part, C, (bf16_t *)y, (const bf16_t *)dy, lse_out, delta, tok_stride(s), s.H, s.N, rows); \
+        else                                                                                                       \
+            decode_merge_kernel<DD, MODE, false><<<grid, 256, 0, stream>>>(                                        \
+                y_part, lse_part, C, (bf16_t *)y, (const bf16_t *)dy, lse_out, delta, tok_stride(s), s.H, s.N, rows); \
+    } while (0)
     switch (s.d) {
         case 4: FLARE_DM(4); break;
         case 8: FLARE_DM(8); break;
@@ -1962,7 +2120,7 @@ static int decode_all(const flare_shape &s, const void *q, const void *k, const 
 // partial companion matrices [b*h][chunk][M][M]; the split of the token axis is returned in *sp
 bool mfma_gram_supported(const flare_shape &s)
 {
-    return mfma_supported(s) && (s.M == 32 || s.M == 64 || s.M == 128 || s.M == 256);
+    return mfma_supported(s) && s.dtype == FLARE_BF16 && (s.M == 32 || s.M == 64 || s.M == 128 || s.M == 256);
 }
 
 int mfma_gram_partial(const flare_shape &s, const Split &sp, const void *q, const void *k, const float *lse_enc,

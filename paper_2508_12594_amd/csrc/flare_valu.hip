@@ -650,9 +650,11 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     // token statistics: from what the forward saved, or recomputed.  On the matrix-core path the
     // saved ones need no pass of their own: the dZ kernel forms delta while it streams dY, and every
     // kernel reads lse_dec itself, scaled to log2 units.
-    // With bf16 storage and d < 16, delta = <dY_n, Y_n> from the rounded y is too coarse (few terms, and
-    // c - delta cancels): such shapes recompute the statistics even when y and lse_dec are given.
-    const bool saved = y && lse_dec && (s.dtype != FLARE_BF16 || s.d >= 16);
+    // With bf16 storage (or bf16 softmax weights behind fp16 storage: the matrix-core path) and d < 16,
+    // delta = <dY_n, Y_n> from the forward's y is too coarse (few terms, and c - delta cancels): such
+    // shapes recompute the statistics even when y and lse_dec are given.
+    const bool coarse_y = (s.dtype == FLARE_BF16 || (s.dtype == FLARE_F16 && mf)) && s.d < 16;
+    const bool saved = y && lse_dec && !coarse_y;
     const bool fused = saved && mf && mfma_dkdv_supported(s);   // every later kernel is a matrix-core one
     const float *ld = fused ? lse_dec : w.lse_dec2;
     const float ld_mul = fused ? kLog2e : 1.f;

@@ -11,7 +11,7 @@ import numpy as np
 import pytest
 
 from paper_2508_12594_amd import binding, synth
-from tests._util import TOL, slice_relerr, to_device, to_host
+from tests._util import slice_relerr, to_device, to_host, tol_for
 
 pytestmark = pytest.mark.gpu
 
@@ -36,7 +36,9 @@ CASES = [
     (2, dict(B=1, N=1200, d=8)),    # matrix-core path with the head dimension padded to 16
     (4, dict(N=700, d=4, H=4)),
     (2, dict(B=1, N=900, M=512)),                # latent chunks on the matrix-core path
-    (1, dict(N=400, dtype="f16")),               # fp16 storage
+    (1, dict(N=400, M=72, dtype="f16")),         # fp16 storage, vector kernels
+    (4, dict(N=1100, dtype="f16")),              # fp16 storage, matrix-core path
+    (5, dict(N=700, dtype="f16")),
 ]
 
 
@@ -46,7 +48,7 @@ def test_token_major_layout(oracle, cfg, over, saved):
     import torch
     _say("layout bnhd cfg%d %s saved=%s" % (cfg, over, saved))
     inp = synth.make_inputs(cfg, with_dy=True, **over)
-    scale, tol = inp["scale"], TOL[inp["dtype"]]
+    scale, tol = inp["scale"], tol_for(inp)
     dev = to_device(inp)
     B, H, N, _ = dev["k"].shape
 

@@ -31,6 +31,7 @@ CASES = [
     ("bf16", 1, 2, 515, 128, 32, 3e-3, 1e-2),
     ("bf16", 1, 1, 333, 32, 8, 3e-3, 1e-2),
     ("bf16", 1, 1, 400, 96, 16, 3e-3, 1e-2),    # bf16 storage on the vector-ALU Gram kernel
+    ("f16", 1, 2, 500, 64, 16, 3e-3, 1e-2),     # fp16 storage: matrix-core forward, vector-ALU Gram kernel
 ]
 
 
