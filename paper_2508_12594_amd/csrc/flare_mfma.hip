@@ -837,8 +837,8 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
 
 // ============================================================================================
 // Backward, dQ partials (latent-major, same wave geometry as the encode).  For its NB latent tiles
-// a wave keeps, as B operands (column = latent, contraction over d): q' hi and lo, dZ and Z in
-// bf16 (hi and, at d = 16, lo).  Per 32-token tile it streams K, V and dY as A operands
+// a wave keeps, as B operands (column = latent, contraction over d): q' hi and lo, dZ (bf16-exact: it is
+// rounded where it is merged, before eps is formed) and Z in bf16 (hi and, at d = 16, lo).  Per 32-token tile it streams K, V and dY as A operands
 // (row = token) and forms, all on the matrix cores,
 //     S2 - lse_enc2[m]   (one more k-step: -lse_enc2 as a hi+lo pair in slots 0,1, against 1,1)
 //     S2 - lse_dec2[n]   (likewise -lse_dec2 in slots 2,3 of the token-side operand)
@@ -895,8 +895,8 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
 
     // ---- per-latent operands ----
     const int lat0 = 32 * NB * (G * (int)blockIdx.z + g);   // a workgroup owns NB*G tiles of latents
-    constexpr bool LO2 = (D == 16);             // carry lo terms of dZ and Z as well
-    bf16x8 qh[NB][KS], ql[NB][KS], q_aug[NB], dzb[NB][KS], zb[NB][KS], dzl[NB][KS], zl[NB][KS], dz_aug[NB];
+    constexpr bool LO2 = (D == 16);             // carry the lo term of Z as well (dZ arrives bf16-exact)
+    bf16x8 qh[NB][KS], ql[NB][KS], q_aug[NB], dzb[NB][KS], zb[NB][KS], zl[NB][KS], dz_aug[NB];
     bf16x8 u_aug[ONE ? NB : 1];
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
@@ -922,7 +922,7 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
             float zr[8], dr[8];
             row8_f32<DR>(z + ((size_t)bh * M + m) * DR, (D / 2) * hh + 8 * s, zr);
             row8_f32<DR>(dz + ((size_t)bh * M + m) * DR, (D / 2) * hh + 8 * s, dr);
-            u32x4 wz, wd, wzl, wdl;
+            u32x4 wz, wd, wzl;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const float za = zr[2 * i] * um, zc = zr[2 * i + 1] * um;
@@ -932,13 +932,10 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
                 wd[i] = d0 | (d1 << 16);
                 wzl[i] = rne_bf16(za - __uint_as_float(z0 << 16)) |
                          (rne_bf16(zc - __uint_as_float(z1 << 16)) << 16);
-                wdl[i] = rne_bf16(dr[2 * i] - __uint_as_float(d0 << 16)) |
-                         (rne_bf16(dr[2 * i + 1] - __uint_as_float(d1 << 16)) << 16);
             }
             zb[b][s] = as_bf16x8(wz);
             dzb[b][s] = as_bf16x8(wd);
             zl[b][s] = as_bf16x8(wzl);
-            dzl[b][s] = as_bf16x8(wdl);
         }
         u32x4 we;
         we[0] = lower ? split_bf16_pair(-eps[(size_t)bh * M + m]) : 0u;
@@ -1085,10 +1082,7 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
                 for (int ks = 0; ks < KS; ++ks) {
                     av = mfma(vt[ks], dzb[b][ks], av);
                     cv = mfma(gt[ks], zb[b][ks], cv);
-                    if constexpr (LO2) {
-                        av = mfma(vt[ks], dzl[b][ks], av);
-                        cv = mfma(gt[ks], zl[b][ks], cv);
-                    }
+                    if constexpr (LO2) cv = mfma(gt[ks], zl[b][ks], cv);
                 }
                 if (partial) {
 #pragma unroll
@@ -1156,7 +1150,10 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
 //   acc1 += RW1 . P   (rows 0-15: dV^T, rows 16-31: -(sum_m P eps_m q_m)^T)
 //   acc2 += RW2 . dS' (rows 0-15: (sum_m dS' q_m)^T)
 // and at the end  dV = acc1[0:16],  dK = scale * (acc2[0:16] + acc1[16:32]).
-// LO2: also carry lo terms of dZ and Z (more accurate a and c; needs more LDS).
+// LO2: also carry lo terms of dZ and Z (more accurate a and c; two more products per tile and more
+// LDS).  Not used: the rounding of dZ_m and Z_m is one error per latent, and dK_n and dV_n sum over
+// the latents, so it averages out (measured: dK error up by 5-10 %, time down by 9 %) -- unlike in the
+// dQ kernel, whose sums run over the tokens of one latent and add that error up coherently.
 // ONE: one exponential per score, as in the dQ kernel: R = P u[m] w[n]; u is folded into the Z images
 // (and into slots 4-6 of the correction image, against -delta in the token operand), w[n] is a
 // per-lane scalar here, and dS' = P (a + w c).  Runs only where plan[bh] = 1.
@@ -1786,7 +1783,7 @@ int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v,
     const float c2 = scale * kLog2e;
     const int MT = lat_eff(s.M) / 32;
     const int pd = padded_dim(s.d);
-    const bool lo2 = (pd == 16);
+    const bool lo2 = false;   // see the kernel's comment on LO2
     const int KS = pd / 16, HV = pd / 16;
     const size_t lds = (size_t)MT * ((lo2 ? 6 : 4) * KS + 1 + 4 * HV) * 1024;
     const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *vv = (const bf16_t *)v, *gg = (const bf16_t *)dy;
@@ -1807,10 +1804,10 @@ int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v,
     } while (0)
 #define FLARE_DKDV_MT(DD)                              \
     switch (MT) {                                      \
-        case 1: FLARE_DKDV(DD, 1, true); break;        \
-        case 2: FLARE_DKDV(DD, 2, true); break;        \
-        case 4: FLARE_DKDV(DD, 4, true); break;        \
-        case 8: FLARE_DKDV(DD, 8, true); break;        \
+        case 1: FLARE_DKDV(DD, 1, false); break;       \
+        case 2: FLARE_DKDV(DD, 2, false); break;       \
+        case 4: FLARE_DKDV(DD, 4, false); break;       \
+        case 8: FLARE_DKDV(DD, 8, false); break;       \
         default: return FLARE_EUNSUPPORTED;            \
     }
     if (s.d == 4) {

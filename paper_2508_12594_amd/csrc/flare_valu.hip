@@ -419,7 +419,7 @@ __device__ __forceinline__ void sum_slots(const float *__restrict__ part, int ou
 template <int D>
 __global__ __launch_bounds__(256) void dz_merge_kernel(
     const float *__restrict__ dz_part, const float *__restrict__ z,
-    float *__restrict__ dz, float *__restrict__ eps, int BH, int M, int parts)
+    float *__restrict__ dz, float *__restrict__ eps, int BH, int M, int parts, int round_bf16)
 {
     const int j = threadIdx.x & 15;
     const int m = blockIdx.x * 16 + (threadIdx.x >> 4);
@@ -429,6 +429,17 @@ __global__ __launch_bounds__(256) void dz_merge_kernel(
     sum_slots<D>(dz_part, bh, BH, 1, parts, M, live ? m : M - 1, j, acc);
     if (!live || j != 0) return;
     const size_t idx = (size_t)bh * M + m;
+    if (round_bf16) {
+        // The matrix-core kernels take dZ as a bf16 operand.  Rounding it here, before eps is formed,
+        // keeps a[m][n] = <dZ_m, V_n - Z_m> an exact expression in the rounded dZ (eps and the products
+        // see the same values), instead of leaving <V_n, rounding error> uncancelled in every score.
+#pragma unroll
+        for (int i = 0; i < D; ++i) {
+            uint32_t u = __float_as_uint(acc[i]);
+            u += 0x7fffu + ((u >> 16) & 1u);
+            acc[i] = __uint_as_float(u & 0xffff0000u);
+        }
+    }
     load_row<D>(z + idx * D, zr);
     store_row<D>(dz + idx * D, acc);
     eps[idx] = dot<D>(acc, zr);
@@ -690,7 +701,8 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     }
     {
         LaunchTimer t(KID_BWD_DZ_MERGE, stream);
-        dz_merge_kernel<D><<<dim3((s.M + 15) / 16, BH), 256, 0, stream>>>(w.part, z, w.dz, w.eps, BH, s.M, dz_parts);
+        dz_merge_kernel<D><<<dim3((s.M + 15) / 16, BH), 256, 0, stream>>>(w.part, z, w.dz, w.eps, BH, s.M, dz_parts,
+                                                                          mf ? 1 : 0);
     }
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     int dq_parts = plan.bwd.chunks;
