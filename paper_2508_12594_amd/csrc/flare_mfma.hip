@@ -1142,14 +1142,18 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
 // over all latent tiles).  Everything that depends on the latents only is prepared once per
 // workgroup as MFMA-ready operand images in LDS (one (b,h) per workgroup, 8 waves share it):
 //   A-type images (row = latent, contraction over d): q' hi, q' lo, dZ hi (and lo), Z hi (and
-//     lo), and a correction operand (slots 0,1 = -lse_enc2 as a hi+lo pair, slots 2,3 = 1,1);
+//     lo), and a correction operand (slots 0,1 = -lse_enc2 as a hi+lo pair, slots 2,3 = 1,1; slots
+//     8,9 = -eps as a hi+lo pair);
 //   row images (row = output column, contraction over the 32 latents in accumulator order):
-//     RW1 = [dZ^T ; -(eps q)^T]   and   RW2 = [q^T ; 0].
+//     RW1 = [dZ^T ; 0]   and   RW2 = [q^T ; 0].
 // Per token tile and latent tile:  P = 2^(S2 - lse_enc2[m]), R = 2^(S2 - lse_dec2[n]),
-//   a = <dZ_m, V_n>,  c = <Z_m, dY_n> - delta[n],  dS' = P a + R c  (fp32), then
-//   acc1 += RW1 . P   (rows 0-15: dV^T, rows 16-31: -(sum_m P eps_m q_m)^T)
-//   acc2 += RW2 . dS' (rows 0-15: (sum_m dS' q_m)^T)
-// and at the end  dV = acc1[0:16],  dK = scale * (acc2[0:16] + acc1[16:32]).
+//   a = <dZ_m, V_n> - eps[m],  c = <Z_m, dY_n> - delta[n],  dS = P a + R c  (fp32), then
+//   acc1 += RW1 . P   (rows 0-15: dV^T)
+//   acc2 += RW2 . dS  (rows 0-15: (sum_m dS q_m)^T)
+// and at the end  dV = acc1[0:16],  dK = scale * acc2[0:16].
+// (eps is subtracted inside the a chain, by one more product, so that a - eps = <dZ_m, V_n - Z_m>
+// cancels before dS is rounded: where a latent attends sharply to tokens of similar values the two
+// terms agree to several digits, and carrying -eps q separately through bf16 roundings lost them.)
 // LO2: also carry lo terms of dZ and Z (more accurate a and c; two more products per tile and more
 // LDS).  Not used: the rounding of dZ_m and Z_m is one error per latent, and dK_n and dV_n sum over
 // the latents, so it averages out (measured: dK error up by 5-10 %, time down by 9 %) -- unlike in the
@@ -1210,15 +1214,16 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                 w[0] = hf == 0 ? split_pair<F>(-le2) : 0u;
                 w[1] = hf == 0 ? kOnePair<F> : 0u;
                 w[2] = 0u; w[3] = 0u;
-                // Slots 4-6 belong to the c product, whose operands are bf16 whatever the storage type; the
-                // score products meet them with zeros in the token operand (and the c product meets slots
-                // 0-3 with zeros).  u <= 1 and finite 16-bit patterns of either type read as finite values
+                // Slots 4-6 belong to the c product and slots 8,9 to the a product, whose operands are bf16
+                // whatever the storage type; the score products meet them with zeros in the token operand
+                // (and the a and c products meet slots 0-3 with zeros).  u <= 1 and finite 16-bit patterns of either type read as finite values
                 // of the other, so the foreign slots contribute exact zeros.
                 if constexpr (ONE) {   // slots 4,5,6 := u hi, u hi, u lo
                     const uint32_t us = split_bf16_pair(fast_exp2(le2 - kap));
                     w[2] = hf == 0 ? ((us & 0xffffu) | (us << 16)) : 0u;
                     w[3] = hf == 0 ? (us >> 16) : 0u;
                 }
+                if (hf == 1) w[0] = split_bf16_pair(-eb[32 * t + r32]);   // slots 8,9 := -eps (bf16: the a chain)
             } else if (sid < NA) {
                 const int kind = sid / KS, ks = sid % KS;          // 0 qh, 1 ql, 2 dzh, 3 zh, 4 dzl, 5 zl
                 const int m = 32 * t + r32;
@@ -1266,8 +1271,8 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                     const float q0 = in ? elem_value<F>(qh_[(size_t)m0 * DR + dd]) : 0.f;
                     const float q1 = in ? elem_value<F>(qh_[(size_t)m1 * DR + dd]) : 0.f;
                     if (which == 0) {
-                        a = (r32 < 16) ? (in ? dzb[(size_t)m0 * DR + dd] : 0.f) : -eb[m0] * q0;
-                        b = (r32 < 16) ? (in ? dzb[(size_t)m1 * DR + dd] : 0.f) : -eb[m1] * q1;
+                        a = (r32 < 16 && in) ? dzb[(size_t)m0 * DR + dd] : 0.f;
+                        b = (r32 < 16 && in) ? dzb[(size_t)m1 * DR + dd] : 0.f;
                     } else {
                         a = (r32 < 16) ? q0 : 0.f;
                         b = (r32 < 16) ? q1 : 0.f;
@@ -1286,6 +1291,8 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     const bf16x8 ones_aug = as_bf16x8(w11);
     w11[0] = lower ? kOnePair<F> : 0u;
     const bf16x8 ones_s = as_bf16x8(w11);        // the same in the type of the score products
+    w11[0] = lower ? 0u : 0x3f803f80u;
+    const bf16x8 ones_eps = as_bf16x8(w11);      // slots 8,9 = 1 (bf16): picks -eps out of the correction image
     auto to_bf16 = [](bf16x8 x) { return as_bf16x8(to_bf16_row<F>(__builtin_bit_cast(u32x4, x))); };
 
     const bf16_t *kb = k + tok_base(ts, bh, H);
@@ -1354,7 +1361,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
         // exponentiate the scores of tile t (s1, s2, computed one step earlier).
         auto tile_step = [&](int t, f32x16 &s1, f32x16 &s2, f32x16 &s1n, f32x16 &s2n) {
             if constexpr (!PIPE) scores(t, s1, s2);   // not enough registers at d = 32: no look-ahead
-            f32x16 av = splat16(0.f);
+            f32x16 av = mfma(image(t, NA - 1), ones_eps, splat16(0.f));
             f32x16 cv = mfma(ONE ? image(t, NA - 1) : ones_aug, g_aug, splat16(0.f));
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
@@ -1421,10 +1428,8 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                     const int o = 16 * hv + 8 * up + 4 * hh;
                     float4 a = make_float4(acc1[hv][4 * up], acc1[hv][4 * up + 1], acc1[hv][4 * up + 2],
                                            acc1[hv][4 * up + 3]);
-                    float4 b = make_float4(scale * (acc2[hv][4 * up] + acc1[hv][8 + 4 * up]),
-                                           scale * (acc2[hv][4 * up + 1] + acc1[hv][9 + 4 * up]),
-                                           scale * (acc2[hv][4 * up + 2] + acc1[hv][10 + 4 * up]),
-                                           scale * (acc2[hv][4 * up + 3] + acc1[hv][11 + 4 * up]));
+                    float4 b = make_float4(scale * acc2[hv][4 * up], scale * acc2[hv][4 * up + 1],
+                                           scale * acc2[hv][4 * up + 2], scale * acc2[hv][4 * up + 3]);
                     if (!first) {
                         const float4 pa = *reinterpret_cast<const float4 *>(dvr + o);
                         const float4 pb = *reinterpret_cast<const float4 *>(dkr + o);
@@ -1446,10 +1451,10 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                 w1[1] = pack_elems<F>(acc1[hv][6], acc1[hv][7]);
                 if (quartet_inside<DR>(hv, hh, 0)) *reinterpret_cast<u32x2 *>(dvr + 16 * hv + 4 * hh) = w0;
                 if (quartet_inside<DR>(hv, hh, 1)) *reinterpret_cast<u32x2 *>(dvr + 16 * hv + 8 + 4 * hh) = w1;
-                w0[0] = pack_elems<F>(scale * (acc2[hv][0] + acc1[hv][8]), scale * (acc2[hv][1] + acc1[hv][9]));
-                w0[1] = pack_elems<F>(scale * (acc2[hv][2] + acc1[hv][10]), scale * (acc2[hv][3] + acc1[hv][11]));
-                w1[0] = pack_elems<F>(scale * (acc2[hv][4] + acc1[hv][12]), scale * (acc2[hv][5] + acc1[hv][13]));
-                w1[1] = pack_elems<F>(scale * (acc2[hv][6] + acc1[hv][14]), scale * (acc2[hv][7] + acc1[hv][15]));
+                w0[0] = pack_elems<F>(scale * acc2[hv][0], scale * acc2[hv][1]);
+                w0[1] = pack_elems<F>(scale * acc2[hv][2], scale * acc2[hv][3]);
+                w1[0] = pack_elems<F>(scale * acc2[hv][4], scale * acc2[hv][5]);
+                w1[1] = pack_elems<F>(scale * acc2[hv][6], scale * acc2[hv][7]);
                 if (quartet_inside<DR>(hv, hh, 0)) *reinterpret_cast<u32x2 *>(dkr + 16 * hv + 4 * hh) = w0;
                 if (quartet_inside<DR>(hv, hh, 1)) *reinterpret_cast<u32x2 *>(dkr + 16 * hv + 8 + 4 * hh) = w1;
             }
