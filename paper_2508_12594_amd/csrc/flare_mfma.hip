@@ -218,14 +218,19 @@ __device__ __forceinline__ bool quartet_inside(int hv, int hh, int upper)
 // Lane half hh covers d-indices (D/2)*hh + 8*s + i for k-step s.  The same mapping is used for
 // the key operand.  PRE: multiply by c2 and split into hi + lo bf16 terms; else raw bits (sign
 // flipped when c2 < 0 so that the kernel can work with |c2|).
-template <int DR, bool PRE, bool F>
+// PACKED (d <= 8 only, where the upper half of the padded contraction is free): the lower lane half
+// gets the hi terms and the upper one the lo terms of the same d-indices, so that ONE product with a
+// token operand that repeats its row in both halves gives the full-precision score; lo is unused.
+constexpr bool pack_dim(int dr) { return dr <= 8; }
+template <int DR, bool PRE, bool F, bool PACKED = false>
 __device__ __forceinline__ void load_q_operand(const bf16_t *__restrict__ q_row, int hh, float c2, bool flip,
                                                bf16x8 (&hi)[padded_dim(DR) / 16], bf16x8 (&lo)[padded_dim(DR) / 16])
 {
     constexpr int D = padded_dim(DR);
+    static_assert(!PACKED || (PRE && pack_dim(DR)), "packed operands need d <= 8 and the pre-scaled form");
 #pragma unroll
     for (int s = 0; s < D / 16; ++s) {
-        const u32x4 w = row8_bf16<DR>(q_row, (D / 2) * hh + 8 * s);
+        const u32x4 w = row8_bf16<DR>(q_row, PACKED ? 0 : (D / 2) * hh + 8 * s);
         if constexpr (PRE) {
             u32x4 wh, wl;
 #pragma unroll
@@ -236,7 +241,7 @@ __device__ __forceinline__ void load_q_operand(const bf16_t *__restrict__ q_row,
                 wh[i] = ah | (bh << 16);
                 wl[i] = rne_elem<F>(ar) | (rne_elem<F>(br) << 16);
             }
-            hi[s] = as_bf16x8(wh);
+            hi[s] = as_bf16x8((PACKED && hh) ? wl : wh);
             lo[s] = as_bf16x8(wl);
         } else {
             u32x4 wf = w;
@@ -302,6 +307,7 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
     constexpr int D = padded_dim(DR);
     constexpr int KS = D / 16;   // k-steps of the score product
     constexpr int HV = D / 16;   // 16-wide column groups of Z, each with its own ones row
+    constexpr bool PACK = PRE && pack_dim(DR);   // q' hi | lo in one operand, keys repeated in both lane halves
     const int lane = threadIdx.x & 63, l32 = lane & 31, hh = lane >> 5;
     const int wave = threadIdx.x >> 6;
     const int bh = blockIdx.y, h = bh % H;
@@ -311,7 +317,7 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
     bf16x8 qh[MT][KS], ql[MT][KS];
 #pragma unroll
     for (int t = 0; t < MT; ++t)
-        load_q_operand<DR, PRE, F>(q + ((size_t)h * Mtot + m0 + 32 * t + l32) * DR, hh, c2, flip, qh[t], ql[t]);
+        load_q_operand<DR, PRE, F, PACK>(q + ((size_t)h * Mtot + m0 + 32 * t + l32) * DR, hh, c2, flip, qh[t], ql[t]);
 
     // Zaug^T operand: row l32 (< 16: column 16*hv + l32 of Z; 16: ones; else zero).  In registers, or --
     // for the shapes whose registers would not allow two waves per SIMD otherwise (ZLDS = !PRE) --
@@ -358,7 +364,7 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
         const int nld = min(tile * 32 + l32, N - 1);
 #pragma unroll
         for (int s = 0; s < KS; ++s)
-            kt[s] = as_bf16x8(row8_bf16<DR>(kb + tok_off(ts, nld), (D / 2) * hh + 8 * s));
+            kt[s] = as_bf16x8(row8_bf16<DR>(kb + tok_off(ts, nld), PACK ? 0 : (D / 2) * hh + 8 * s));
     }
     for (; tile < tiles; tile += stride) {
         const int n = tile * 32 + l32;
@@ -367,7 +373,7 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
             const int nld = min(tn * 32 + l32, N - 1);
 #pragma unroll
             for (int s = 0; s < KS; ++s)
-                ktn[s] = as_bf16x8(row8_bf16<DR>(kb + tok_off(ts, nld), (D / 2) * hh + 8 * s));
+                ktn[s] = as_bf16x8(row8_bf16<DR>(kb + tok_off(ts, nld), PACK ? 0 : (D / 2) * hh + 8 * s));
         }
         auto qk_hi = [&](int t) {
             f32x16 r = splat16(0.f);
@@ -403,7 +409,7 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
             f32x16 r = cinit;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) r = mfma_s<F>(qh[t][ks], kt2[ks], r);
-            if constexpr (PRE) {
+            if constexpr (PRE && !PACK) {
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) r = mfma_s<F>(ql[t][ks], kt[ks], r);
             }
@@ -432,9 +438,19 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
                 acc[hv] = mfma(z_op(hv, 2 * t + 1), p1, acc[hv]);
             }
             if constexpr (PRE && D == 16) {
-                // order within the tile: the two score products of tile t+1 and the two value products of
-                // tile t, each followed by a share of the 16 exponentials and 8 packs of tile t
-                if (t + 1 < MT) {
+                // order within the tile: the two score products of tile t+1 (one when q' is packed) and the
+                // two value products of tile t, each followed by a share of the 16 exponentials and 8 packs
+                // of tile t
+                if (PACK && t + 1 < MT) {
+                    FLARE_GROUP_TRANS(4);
+                    FLARE_GROUP_MFMA(1);
+                    FLARE_GROUP_TRANS(4);
+                    FLARE_GROUP_VALU(4);
+                    FLARE_GROUP_MFMA(1);
+                    FLARE_GROUP_TRANS(8);
+                    FLARE_GROUP_VALU(4);
+                    FLARE_GROUP_MFMA(1);
+                } else if (t + 1 < MT) {
                     FLARE_GROUP_TRANS(4);
                     FLARE_GROUP_MFMA(1);
                     FLARE_GROUP_TRANS(4);
@@ -553,6 +569,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     constexpr int KS = D / 16;
     constexpr int HV = D / 16;
     constexpr int ROWS = D + 2;                 // V^T rows, then a row of ones, then a row of zeros
+    constexpr bool PACK = pack_dim(DR);         // q' hi | lo in one operand, keys repeated in both lane halves
     constexpr int BUF = ROWS * kVtStride;       // uint16 per buffer
     __shared__ __attribute__((aligned(16))) uint16_t vt_all[4][2 * BUF];
 
@@ -575,7 +592,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     bf16x8 qh[NB][KS], ql[NB][KS];
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
-        load_q_operand<DR, true, F>(q + ((size_t)h * M + lat0 + 32 * b + l32) * DR, hh, c2, false, qh[b], ql[b]);
+        load_q_operand<DR, true, F, PACK>(q + ((size_t)h * M + lat0 + 32 * b + l32) * DR, hh, c2, false, qh[b], ql[b]);
     }
     u32x4 wzero;
     wzero[0] = 0u; wzero[1] = 0u; wzero[2] = 0u; wzero[3] = 0u;
@@ -614,7 +631,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         const int nk = min(tile_tok0(j) + l32, N - 1);
 #pragma unroll
         for (int s = 0; s < KS; ++s)
-            kk[s] = as_bf16x8(row8_bf16<DR>(kb + tok_off(ts, nk), (D / 2) * hh + 8 * s));
+            kk[s] = as_bf16x8(row8_bf16<DR>(kb + tok_off(ts, nk), PACK ? 0 : (D / 2) * hh + 8 * s));
     };
     auto load_v = [&](int j, u32x4 (&vv)[LOADS]) {
         const int nv = min(tile_tok0(j) + vtok, N - 1);
@@ -655,8 +672,10 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         f32x16 r = splat16(0.f);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) r = mfma_s<F>(kk[ks], qh[b][ks], r);
+        if constexpr (!PACK) {
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) r = mfma_s<F>(kk[ks], ql[b][ks], r);
+            for (int ks = 0; ks < KS; ++ks) r = mfma_s<F>(kk[ks], ql[b][ks], r);
+        }
         r = mfma_s<F>(kk0a, MODE == 0 ? caug[MODE == 0 ? b : 0] : ones23, r);
         return r;
     };
@@ -869,6 +888,9 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
     constexpr int KS = D / 16;
     constexpr int HV = D / 16;
     constexpr int ROWS = D + 1;                 // K^T rows, then a row of zeros
+    // d <= 8: the upper half of the padded contraction carries what otherwise needs products of its own:
+    // q' lo and Z lo (K and dY rows repeated in both lane halves) and -eps (against ones in the V operand).
+    constexpr bool PACK = pack_dim(DR);
     constexpr int BUF = ROWS * kVtStride;
     __shared__ __attribute__((aligned(16))) uint16_t kt_all[4][2 * BUF];
     __shared__ __attribute__((aligned(16))) float wl_all[ONE ? 4 : 1][2][32];   // w[n] of a token tile
@@ -891,6 +913,13 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
     if (lane < kVtStride) {
         lds[D * kVtStride + lane] = 0;
         lds[BUF + D * kVtStride + lane] = 0;
+        if constexpr (PACK) {   // K^T rows 8-15 are never written: zero, so that the unused output rows stay finite
+#pragma unroll
+            for (int r = 8; r < 16; ++r) {
+                lds[r * kVtStride + lane] = 0;
+                lds[BUF + r * kVtStride + lane] = 0;
+            }
+        }
     }
 
     // ---- per-latent operands ----
@@ -901,7 +930,7 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         const int m = lat0 + 32 * b + l32;
-        load_q_operand<DR, true, F>(q + ((size_t)h * M + m) * DR, hh, c2, false, qh[b], ql[b]);
+        load_q_operand<DR, true, F, PACK>(q + ((size_t)h * M + m) * DR, hh, c2, false, qh[b], ql[b]);
         const float le2 = lse_enc[(size_t)bh * M + m] * kLog2e;
         const float um = ONE ? fast_exp2(le2 - kap) : 1.f;   // folded into Z
         if constexpr (ONE) {
@@ -920,7 +949,7 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             float zr[8], dr[8];
-            row8_f32<DR>(z + ((size_t)bh * M + m) * DR, (D / 2) * hh + 8 * s, zr);
+            row8_f32<DR>(z + ((size_t)bh * M + m) * DR, PACK ? 0 : (D / 2) * hh + 8 * s, zr);
             row8_f32<DR>(dz + ((size_t)bh * M + m) * DR, (D / 2) * hh + 8 * s, dr);
             u32x4 wz, wd, wzl;
 #pragma unroll
@@ -933,14 +962,19 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
                 wzl[i] = rne_bf16(za - __uint_as_float(z0 << 16)) |
                          (rne_bf16(zc - __uint_as_float(z1 << 16)) << 16);
             }
-            zb[b][s] = as_bf16x8(wz);
+            zb[b][s] = as_bf16x8((PACK && !lower) ? wzl : wz);
             dzb[b][s] = as_bf16x8(wd);
             zl[b][s] = as_bf16x8(wzl);
         }
         u32x4 we;
-        we[0] = lower ? split_bf16_pair(-eps[(size_t)bh * M + m]) : 0u;
+        we[0] = (lower != PACK) ? split_bf16_pair(-eps[(size_t)bh * M + m]) : 0u;
         we[1] = 0u; we[2] = 0u; we[3] = 0u;
         dz_aug[b] = as_bf16x8(we);
+        if constexpr (PACK) {   // slots 8,9 of the dZ operand := -eps (the rest of its upper half is zero)
+            u32x4 wd = __builtin_bit_cast(u32x4, dzb[b][0]);
+            if (!lower) wd[0] = we[0];
+            dzb[b][0] = as_bf16x8(wd);
+        }
     }
     u32x4 w11;
     w11[0] = lower ? 0x3f803f80u : 0u;
@@ -949,6 +983,12 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
     w11[0] = lower ? kOnePair<F> : 0u;
     const bf16x8 ones_s = as_bf16x8(w11);        // the same in the type of the score products
     auto to_bf16 = [](bf16x8 x) { return as_bf16x8(to_bf16_row<F>(__builtin_bit_cast(u32x4, x))); };
+    // V rows as the operand of the a product; PACK: slots 8,9 := 1 (the upper lane half loaded zeros)
+    auto v_operand = [&](bf16x8 x) {
+        u32x4 w = to_bf16_row<F>(__builtin_bit_cast(u32x4, x));
+        if (PACK && !lower) w[0] = 0x3f803f80u;
+        return as_bf16x8(w);
+    };
 
     const bf16_t *kb = k + tok_base(ts, bh, H);
     const bf16_t *vb = v + tok_base(ts, bh, H);
@@ -971,13 +1011,15 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
     for (int hv = 0; hv < HV; ++hv) krow[hv] = (l32 < 16) ? 16 * hv + l32 : D;
 
     auto tile_tok0 = [&](int j) { return n0 + 32 * (tg + min(j, cnt - 1) * TG); };
-    auto load_rows = [&](const bf16_t *base, int j, bf16x8 (&t)[KS]) {   // A operand: row = token
+    // A operand: row = token.  rep (PACK only): both lane halves get elements 0-7 of the row.
+    auto load_rows = [&](const bf16_t *base, int j, bf16x8 (&t)[KS], bool rep) {
         const int n = min(tile_tok0(j) + l32, N - 1);
 #pragma unroll
         for (int s = 0; s < KS; ++s)
-            t[s] = as_bf16x8(row8_bf16<DR>(base + tok_off(ts, n), (D / 2) * hh + 8 * s));
+            t[s] = as_bf16x8(row8_bf16<DR>(base + tok_off(ts, n), (PACK && rep) ? 0 : (D / 2) * hh + 8 * s));
     };
     auto write_kt = [&](const bf16x8 (&t)[KS], uint16_t *buf) {   // transposed: row = d-index, column = token
+        if (PACK && !lower) return;   // the upper lane half holds a copy of the same elements
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             const u32x4 w = to_bf16_row<F>(__builtin_bit_cast(u32x4, t[s]));   // K as a value: bf16
@@ -1018,15 +1060,15 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
         bf16x8 kt[KS], ktn[KS], ktnn[KS], vt[KS], vtn[KS], vtnn[KS], gt[KS], gtn[KS], gtnn[KS], kT[HV][2];
         float nld, nldn, nldnn, dl, dln, dlnn;
         float wrow[ONE ? 16 : 1];
-        load_rows(kb, 0, kt);
-        load_rows(kb, 1, ktn);
-        load_rows(vb, 0, vt);
-        load_rows(vb, 1, vtn);
-        load_rows(gb, 0, gt);
-        load_rows(gb, 1, gtn);
-        if constexpr (F) {   // V and dY meet bf16 operands: converted once, when they become current
+        load_rows(kb, 0, kt, true);
+        load_rows(kb, 1, ktn, true);
+        load_rows(vb, 0, vt, false);
+        load_rows(vb, 1, vtn, false);
+        load_rows(gb, 0, gt, true);
+        load_rows(gb, 1, gtn, true);
+        if constexpr (F || PACK) {   // V and dY meet bf16 operands: converted once, when they become current
 #pragma unroll
-            for (int s = 0; s < KS; ++s) { vt[s] = to_bf16(vt[s]); gt[s] = to_bf16(gt[s]); }
+            for (int s = 0; s < KS; ++s) { vt[s] = v_operand(vt[s]); gt[s] = to_bf16(gt[s]); }
         }
         nld = -lb[min(tile_tok0(0) + l32, N - 1)] * ld_mul;
         dl = db[min(tile_tok0(0) + l32, N - 1)];
@@ -1042,9 +1084,9 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
         for (int j = 0; j < cnt; ++j) {
             const int tok0 = tile_tok0(j);
             uint16_t *buf_next = lds + ((j + 1) & 1) * BUF;
-            load_rows(kb, j + 2, ktnn);
-            load_rows(vb, j + (DEEP ? 2 : 1), vtnn);
-            load_rows(gb, j + (DEEP ? 2 : 1), gtnn);
+            load_rows(kb, j + 2, ktnn, true);
+            load_rows(vb, j + (DEEP ? 2 : 1), vtnn, false);
+            load_rows(gb, j + (DEEP ? 2 : 1), gtnn, true);
             nldnn = -lb[min(tile_tok0(j + (DEEP ? 2 : 1)) + l32, N - 1)] * ld_mul;
             dlnn = db[min(tile_tok0(j + (DEEP ? 2 : 1)) + l32, N - 1)];
             compiler_fence();
@@ -1071,18 +1113,21 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
                 f32x16 x = splat16(0.f);
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) x = mfma_s<F>(kt[ks], qh[b][ks], x);
+                if constexpr (!PACK) {
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) x = mfma_s<F>(kt[ks], ql[b][ks], x);
+                    for (int ks = 0; ks < KS; ++ks) x = mfma_s<F>(kt[ks], ql[b][ks], x);
+                }
                 f32x16 s1 = mfma_s<F>(kt_a, q_aug[b], x);
                 f32x16 s2 = s1;
                 if constexpr (!ONE) s2 = mfma_s<F>(kt_b, q_aug[b], x);
-                f32x16 av = mfma(ones_aug, dz_aug[b], splat16(0.f));
+                f32x16 av = splat16(0.f);
+                if constexpr (!PACK) av = mfma(ones_aug, dz_aug[b], av);
                 f32x16 cv = mfma(g_aug, ONE ? u_aug[ONE ? b : 0] : ones_aug, splat16(0.f));
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
                     av = mfma(vt[ks], dzb[b][ks], av);
                     cv = mfma(gt[ks], zb[b][ks], cv);
-                    if constexpr (LO2) cv = mfma(gt[ks], zl[b][ks], cv);
+                    if constexpr (LO2 && !PACK) cv = mfma(gt[ks], zl[b][ks], cv);
                 }
                 if (partial) {
 #pragma unroll
@@ -1115,7 +1160,7 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
                 kt[s] = ktn[s]; ktn[s] = ktnn[s];
-                vt[s] = to_bf16(DEEP ? vtn[s] : vtnn[s]); vtn[s] = vtnn[s];
+                vt[s] = v_operand(DEEP ? vtn[s] : vtnn[s]); vtn[s] = vtnn[s];
                 gt[s] = to_bf16(DEEP ? gtn[s] : gtnn[s]); gtn[s] = gtnn[s];
             }
             nld = DEEP ? nldn : nldnn; nldn = nldnn;
@@ -1181,6 +1226,11 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     constexpr int NR = 4 * HV;                  // row images per latent tile (RW1, RW2) x 2 k-steps
     constexpr int PER_TILE = NA + NR;
     constexpr bool PIPE = (D == 16);            // look one latent tile ahead where registers allow
+    // d <= 8: the upper half of the padded contraction carries what otherwise needs products of its own.
+    // Images: q' hi | lo in one (keys repeated in both lane halves), slots 8,9 of the dZ image = -eps
+    // (against ones in the V operand), slots 8-10 of the Z image = u, u, u lo or 1, 1 (against -delta in
+    // the dY operand).  The q' lo image and the a / c parts of the correction image are then unused.
+    constexpr bool PACK = pack_dim(DR) && !LO2;
     extern __shared__ __attribute__((aligned(16))) u32x4 img[];   // [MT][PER_TILE][64 lanes]
 
     const int tid = threadIdx.x;
@@ -1230,7 +1280,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                 const int d0 = (D / 2) * hf + 8 * ks;
                 float x[8];
                 if (kind <= 1) {
-                    const u32x4 raw = row8_bf16<DR>(qh_ + (size_t)m * DR, d0);
+                    const u32x4 raw = row8_bf16<DR>(qh_ + (size_t)m * DR, PACK ? 0 : d0);
 #pragma unroll
                     for (int i = 0; i < 4; ++i) { x[2 * i] = elem_lo<F>(raw[i]) * c2; x[2 * i + 1] = elem_hi<F>(raw[i]) * c2; }
                 } else {
@@ -1240,7 +1290,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
 #pragma unroll
                     for (int i = 0; i < 8; ++i) x[i] *= um;
                 }
-                const bool want_lo = (kind == 1 || kind >= 4);
+                const bool want_lo = (kind == 1 || kind >= 4 || (PACK && kind == 0 && hf == 1));
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     uint32_t a, b;
@@ -1258,6 +1308,16 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                         }
                     }
                     w[i] = a | (b << 16);
+                }
+                if (PACK && hf == 1 && kind == 2) w[0] = split_bf16_pair(-eb[m]);   // slots 8,9 := -eps
+                if (PACK && hf == 1 && kind == 3) {                                  // slots 8,9,10 := u, u, u lo / 1, 1
+                    if constexpr (ONE) {
+                        const uint32_t us = split_bf16_pair(fast_exp2(leb[m] * kLog2e - kap));
+                        w[0] = (us & 0xffffu) | (us << 16);
+                        w[1] = us >> 16;
+                    } else {
+                        w[0] = 0x3f803f80u;
+                    }
                 }
             } else {
                 const int rsid = sid - NA;                          // (which, hv, s2)
@@ -1302,29 +1362,36 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     const float *db = delta + (size_t)bh * N;
     const int tiles = (N + 31) / 32;
     const int stride = gridDim.x * 8;
-    auto load_cols = [&](const bf16_t *base, int tile, bf16x8 (&t)[KS]) {   // B operand: column = token
+    // B operand: column = token.  rep (PACK only): both lane halves get elements 0-7 of the row.
+    auto load_cols = [&](const bf16_t *base, int tile, bf16x8 (&t)[KS], bool rep) {
         const int n = min(tile * 32 + l32, N - 1);
 #pragma unroll
         for (int s = 0; s < KS; ++s)
-            t[s] = as_bf16x8(row8_bf16<DR>(base + tok_off(ts, n), (D / 2) * hh + 8 * s));
+            t[s] = as_bf16x8(row8_bf16<DR>(base + tok_off(ts, n), (PACK && rep) ? 0 : (D / 2) * hh + 8 * s));
+    };
+    // V rows as the operand of the a product; PACK: slots 8,9 := 1 (the upper lane half loaded zeros)
+    auto v_operand = [&](bf16x8 x) {
+        u32x4 w = to_bf16_row<F>(__builtin_bit_cast(u32x4, x));
+        if (PACK && !lower) w[0] = 0x3f803f80u;
+        return as_bf16x8(w);
     };
     auto image = [&](int t, int sid) { return as_bf16x8(img[(t * PER_TILE + sid) * 64 + lane]); };
 
     int tile = blockIdx.x * 8 + wave;
     bf16x8 kt[KS], vt[KS], gt[KS], ktn[KS], vtn[KS], gtn[KS];
     if (tile < tiles) {
-        load_cols(kb, tile, kt);
-        load_cols(vb, tile, vt);
-        load_cols(gb, tile, gt);
+        load_cols(kb, tile, kt, true);
+        load_cols(vb, tile, vt, false);
+        load_cols(gb, tile, gt, false);
 #pragma unroll
-        for (int s = 0; s < KS; ++s) { vt[s] = to_bf16(vt[s]); gt[s] = to_bf16(gt[s]); }
+        for (int s = 0; s < KS; ++s) { vt[s] = v_operand(vt[s]); gt[s] = to_bf16(gt[s]); }
     }
     for (; tile < tiles; tile += stride) {
         const int n = tile * 32 + l32;
         const int tn = (tile + stride < tiles) ? tile + stride : tile;
-        load_cols(kb, tn, ktn);
-        load_cols(vb, tn, vtn);
-        load_cols(gb, tn, gtn);
+        load_cols(kb, tn, ktn, true);
+        load_cols(vb, tn, vtn, false);
+        load_cols(gb, tn, gtn, false);
         const size_t row = (size_t)min(n, N - 1);
         const float nld = -lb[row] * ld_mul, dl = db[row];
         const float wn = ONE ? fast_exp2(kap + nld) : 0.f;
@@ -1340,6 +1407,14 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
         wg[2] = (ONE && lower) ? ds_ : 0u;                   // one: slots 4,5,6 := -delta hi, lo, hi
         wg[3] = (ONE && lower) ? (ds_ & 0xffffu) : 0u;
         const bf16x8 g_aug = as_bf16x8(wg);
+        bf16x8 gc[KS];   // dY operand of the c product; PACK: slots 8,9,10 := -delta hi, lo, hi
+#pragma unroll
+        for (int s = 0; s < KS; ++s) gc[s] = gt[s];
+        if constexpr (PACK) {
+            u32x4 w = __builtin_bit_cast(u32x4, gt[0]);
+            if (!lower) { w[0] = ds_; w[1] = ONE ? (ds_ & 0xffffu) : 0u; }
+            gc[0] = as_bf16x8(w);
+        }
 
         f32x16 acc1[HV], acc2[HV];
 #pragma unroll
@@ -1350,8 +1425,10 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
             f32x16 x = splat16(0.f);
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) x = mfma_s<F>(image(t, 0 * KS + ks), kt[ks], x);
+            if constexpr (!PACK) {
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) x = mfma_s<F>(image(t, 1 * KS + ks), kt[ks], x);
+                for (int ks = 0; ks < KS; ++ks) x = mfma_s<F>(image(t, 1 * KS + ks), kt[ks], x);
+            }
             const bf16x8 qa = image(t, NA - 1);
             s1 = mfma_s<F>(qa, kt_a, x);
             if constexpr (!ONE) s2 = mfma_s<F>(qa, kt_b, x);
@@ -1361,12 +1438,15 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
         // exponentiate the scores of tile t (s1, s2, computed one step earlier).
         auto tile_step = [&](int t, f32x16 &s1, f32x16 &s2, f32x16 &s1n, f32x16 &s2n) {
             if constexpr (!PIPE) scores(t, s1, s2);   // not enough registers at d = 32: no look-ahead
-            f32x16 av = mfma(image(t, NA - 1), ones_eps, splat16(0.f));
-            f32x16 cv = mfma(ONE ? image(t, NA - 1) : ones_aug, g_aug, splat16(0.f));
+            f32x16 av = splat16(0.f), cv = splat16(0.f);
+            if constexpr (!PACK) {
+                av = mfma(image(t, NA - 1), ones_eps, av);
+                cv = mfma(ONE ? image(t, NA - 1) : ones_aug, g_aug, cv);
+            }
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 av = mfma(image(t, 2 * KS + ks), vt[ks], av);
-                cv = mfma(image(t, 3 * KS + ks), gt[ks], cv);
+                cv = mfma(image(t, 3 * KS + ks), gc[ks], cv);
                 if constexpr (LO2) {
                     av = mfma(image(t, 4 * KS + ks), vt[ks], av);
                     cv = mfma(image(t, 5 * KS + ks), gt[ks], cv);
@@ -1460,7 +1540,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
             }
         }
 #pragma unroll
-        for (int s = 0; s < KS; ++s) { kt[s] = ktn[s]; vt[s] = to_bf16(vtn[s]); gt[s] = to_bf16(gtn[s]); }
+        for (int s = 0; s < KS; ++s) { kt[s] = ktn[s]; vt[s] = v_operand(vtn[s]); gt[s] = to_bf16(gtn[s]); }
     }
 }
 
