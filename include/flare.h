@@ -52,7 +52,7 @@ extern "C" {
 typedef enum {
     FLARE_F32 = 0,   /* q_lat, k, v, y, dy, dk, dv are IEEE fp32 */
     FLARE_BF16 = 1,  /* ... are bfloat16; all accumulation and the saved statistics stay fp32 */
-    FLARE_F16 = 2    /* ... are IEEE fp16 (the paper's autocast type, Appendix F); likewise */
+    FLARE_F16 = 2    /* ... are IEEE fp16 (the paper's autocast type, Appendix G); likewise */
 } flare_dtype;
 
 typedef enum {
@@ -79,6 +79,10 @@ typedef struct {
     flare_dtype dtype;  /* element type of q_lat, k, v, y, dy, dk, dv */
     flare_layout layout; /* memory order of the token tensors k, v, y, dy, dk, dv (0 = [B][H][N][d]);
                             q_lat, z, lse_enc, lse_dec and dq_lat do not depend on it */
+    int shared_latents;  /* 0: every head has its own M latent queries, q_lat and dq_lat are [H][M][d]
+                            (Section 3.1).  1: all heads use one latent sequence (the shared-latent
+                            variant of the ablation in Appendix G): q_lat and dq_lat are [M][d], and
+                            dq_lat is summed over the heads as well as over the batch */
 } flare_shape;
 
 /* Library version: major*10000 + minor*100 + patch. */
@@ -93,7 +97,7 @@ const char *flare_strerror(int status);
 int flare_workspace_bytes(const flare_shape *shape, size_t *fwd_bytes, size_t *bwd_bytes);
 
 /*
- * Encode (Eq. flare_encode; Appendix E, per-latent form of z_m): split-N partial softmax
+ * Encode (Eq. flare_encode; Appendix F, per-latent form of z_m): split-N partial softmax
  * reductions followed by a fixed-order merge.
  *   q_lat [H][M][d] dtype, k, v [B][H][N][d] dtype                         (in)
  *   z       [B][H][M][d] fp32: the latent sequence Z                        (out)
@@ -104,7 +108,7 @@ int flare_encode(const flare_shape *shape, const void *q_lat, const void *k, con
                  void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * Decode (Eq. flare_decode; Appendix E, per-token form of y_n): per-token softmax over the M
+ * Decode (Eq. flare_decode; Appendix F, per-token form of y_n): per-token softmax over the M
  * latents applied to Z.  Only matrix-core shapes with M > 256 use the workspace (per-chunk partial
  * results, merged in chunk order); for all others it may be NULL.
  *   q_lat [H][M][d] dtype, k [B][H][N][d] dtype, z [B][H][M][d] fp32        (in)
@@ -126,7 +130,7 @@ int flare_forward(const flare_shape *shape, const void *q_lat, const void *k, co
 
 /*
  * Backward of the mixer.  The paper differentiates its two attention calls automatically
- * (Appendix F, "Time and memory complexity": one forward and backward pass is what it
+ * (Appendix G, "Time and memory complexity": one forward and backward pass is what it
  * times); the gradients follow from the softmax Jacobian.  With P = softmax_n(S) (M x N),
  * R = softmax_m(S^T) (N x M), Z = P V, Y = R Z:
  *     dZ = R^T dY,  delta_n = <dY_n, Y_n>,  eps_m = <dZ_m, Z_m>,  dV = P^T dZ,

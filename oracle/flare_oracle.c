@@ -7,7 +7,7 @@
  * tests, the smoke check and the benchmark's cpu_baseline leg load it.
  *
  * What it computes (paper: Section 3.1 "FLARE", Eq. flare_encode / Eq. flare_decode;
- * per-latent and per-token forms in Appendix E; explicit weights in the paragraph
+ * per-latent and per-token forms in Appendix F; explicit weights in the paragraph
  * "Low-rank communication", Eq. attn_W, and the unfused listing of Appendix C):
  *
  *   per batch item b and head h, with  S[m][n] = scale * sum_j q[h][m][j] * k[b][h][n][j]
@@ -60,7 +60,7 @@ static double score(const double *q_m, const double *k_n, int d, double scale)
 }
 
 /* Encode for one (b,h): Z[M][d], and the row statistics rmax[m] = max_n S[m][n],
- * rsum[m] = sum_n exp(S[m][n] - rmax[m]).   Appendix E, per-latent form of z_m. */
+ * rsum[m] = sum_n exp(S[m][n] - rmax[m]).   Appendix F, per-latent form of z_m. */
 static void encode_head(int N, int M, int d, const double *q, const double *k, const double *v,
                         double scale, double *z, double *rmax, double *rsum)
 {
@@ -102,7 +102,7 @@ static void token_stats(int M, int d, const double *q, const double *k_n, double
     *csum = sum;
 }
 
-/* Decode of one token: y_n[:] = sum_m R[n][m] Z[m][:].   Appendix E, per-token form of y_n. */
+/* Decode of one token: y_n[:] = sum_m R[n][m] Z[m][:].   Appendix F, per-token form of y_n. */
 static void decode_token(int M, int d, const double *q, const double *k_n, const double *z,
                          double scale, double *y_n)
 {

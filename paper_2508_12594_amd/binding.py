@@ -26,7 +26,8 @@ EXPORTS = [
 
 class FlareShape(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int), ("H", ctypes.c_int), ("N", ctypes.c_int), ("M", ctypes.c_int),
-                ("d", ctypes.c_int), ("dtype", ctypes.c_int), ("layout", ctypes.c_int)]
+                ("d", ctypes.c_int), ("dtype", ctypes.c_int), ("layout", ctypes.c_int),
+                ("shared_latents", ctypes.c_int)]
 
 
 class FlareError(RuntimeError):
@@ -100,16 +101,18 @@ def _dtype_code(t):
 def _shape_of(q, k, layout="bhnd"):
     if layout not in LAYOUTS:
         raise FlareError("layout must be 'bhnd' or 'bnhd'")
-    if q.dim() != 3 or k.dim() != 4:
-        raise FlareError("expected q_lat[H,M,d] and k[B,H,N,d] (layout 'bhnd') or k[B,N,H,d] (layout 'bnhd')")
-    H, M, d = q.shape
+    if q.dim() not in (2, 3) or k.dim() != 4:
+        raise FlareError("expected q_lat[H,M,d] (or [M,d]: one latent sequence shared by all heads) and "
+                         "k[B,H,N,d] (layout 'bhnd') or k[B,N,H,d] (layout 'bnhd')")
     if layout == "bhnd":
         B, Hk, N, dk = k.shape
     else:
         B, N, Hk, dk = k.shape
+    shared = q.dim() == 2
+    H, M, d = (Hk,) + tuple(q.shape) if shared else tuple(q.shape)
     if Hk != H or dk != d or q.dtype != k.dtype:
         raise FlareError("q_lat and k disagree on H, d or dtype")
-    return FlareShape(B, H, N, M, d, _dtype_code(k), LAYOUTS[layout])
+    return FlareShape(B, H, N, M, d, _dtype_code(k), LAYOUTS[layout], 1 if shared else 0)
 
 
 def _dev(t, name, dtype=None, shape=None):
@@ -218,7 +221,7 @@ def backward(q_lat, k, v, dy, z, lse_enc, scale, y=None, lse_dec=None, dq_lat=No
     torch = _torch()
     shp = _shape_of(q_lat, k, layout)
     if dq_lat is None:
-        dq_lat = torch.empty((shp.H, shp.M, shp.d), dtype=torch.float32, device=k.device)
+        dq_lat = torch.empty(tuple(q_lat.shape), dtype=torch.float32, device=k.device)
     if dk is None:
         dk = torch.empty_like(k)
     if dv is None:
@@ -230,7 +233,7 @@ def backward(q_lat, k, v, dy, z, lse_enc, scale, y=None, lse_dec=None, dq_lat=No
                                  _opt_lse_dec(lse_dec, shp), _dev(dy, "dy", k.dtype, k.shape),
                                  _dev(z, "z", torch.float32, (shp.B, shp.H, shp.M, shp.d)),
                                  _dev(lse_enc, "lse_enc", torch.float32, (shp.B, shp.H, shp.M)),
-                                 _dev(dq_lat, "dq_lat", torch.float32, (shp.H, shp.M, shp.d)),
+                                 _dev(dq_lat, "dq_lat", torch.float32, tuple(q_lat.shape)),
                                  _dev(dk, "dk", k.dtype, k.shape), _dev(dv, "dv", k.dtype, k.shape),
                                  ctypes.c_float(scale), ws_p, ws_n, _stream(stream)), "flare_backward")
     return dq_lat, dk, dv

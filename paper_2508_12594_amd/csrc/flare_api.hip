@@ -64,6 +64,7 @@ int check_shape(const flare_shape *s)
     if (s->B < 1 || s->H < 1 || s->N < 1 || s->M < 1 || s->d < 1) return FLARE_EINVAL;
     if (s->dtype != FLARE_F32 && s->dtype != FLARE_BF16 && s->dtype != FLARE_F16) return FLARE_EUNSUPPORTED;
     if (s->layout != FLARE_BHND && s->layout != FLARE_BNHD) return FLARE_EUNSUPPORTED;
+    if (s->shared_latents != 0 && s->shared_latents != 1) return FLARE_EINVAL;
     if (s->d != 4 && s->d != 8 && s->d != 16 && s->d != 32) return FLARE_EUNSUPPORTED;
     if ((long long)s->B * s->H > 65535) return FLARE_EUNSUPPORTED;
     // token rows are addressed with a 24-bit multiply (tok_off)
@@ -79,7 +80,7 @@ using namespace flare;
 
 extern "C" {
 
-int flare_version(void) { return 100; }
+int flare_version(void) { return 200; }
 
 const char *flare_strerror(int status)
 {

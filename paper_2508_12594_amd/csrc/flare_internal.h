@@ -49,14 +49,17 @@ Split plan_split(int N, int BH, int min_len, int target_blocks);
 
 // ---- where a row of a token tensor (k, v, y, dy, dk, dv) lives --------------------------------
 // Element (b, h, n, j) is at b*sb + h*sh + n*sn + j (in elements), for either layout of flare.h.
+// sq: elements between the latent queries of consecutive heads (M*d, or 0 when all heads share one
+// latent sequence): head h's queries start at q_lat + h*sq.
 struct TokStride {
-    long long sb, sh, sn;
+    long long sb, sh, sn, sq;
 };
 inline TokStride tok_stride(const flare_shape &s)
 {
     const long long H = s.H, N = s.N, d = s.d;
-    if (s.layout == FLARE_BNHD) return TokStride{N * H * d, d, H * d};
-    return TokStride{H * N * d, N * d, d};
+    const long long sq = s.shared_latents ? 0 : (long long)s.M * d;
+    if (s.layout == FLARE_BNHD) return TokStride{N * H * d, d, H * d, sq};
+    return TokStride{H * N * d, N * d, d, sq};
 }
 __device__ __forceinline__ size_t tok_base(const TokStride &t, int bh, int H)
 {

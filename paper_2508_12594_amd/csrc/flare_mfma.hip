@@ -28,7 +28,7 @@
 // million tokens are far below the smallest fp16 number), so the V, dY (and, where K is a value,
 // K) rows are rounded to bf16 after the load; outputs are rounded to fp16 from fp32.
 //
-// Equations: Section 3.1, Eq. flare_encode / Eq. flare_decode; Appendix E.
+// Equations: Section 3.1, Eq. flare_encode / Eq. flare_decode; Appendix F.
 #include "flare_internal.h"
 
 namespace flare {
@@ -317,7 +317,7 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
     bf16x8 qh[MT][KS], ql[MT][KS];
 #pragma unroll
     for (int t = 0; t < MT; ++t)
-        load_q_operand<DR, PRE, F, PACK>(q + ((size_t)h * Mtot + m0 + 32 * t + l32) * DR, hh, c2, flip, qh[t], ql[t]);
+        load_q_operand<DR, PRE, F, PACK>(q + (size_t)h * ts.sq + (size_t)(m0 + 32 * t + l32) * DR, hh, c2, flip, qh[t], ql[t]);
 
     // Zaug^T operand: row l32 (< 16: column 16*hv + l32 of Z; 16: ones; else zero).  In registers, or --
     // for the shapes whose registers would not allow two waves per SIMD otherwise (ZLDS = !PRE) --
@@ -592,7 +592,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     bf16x8 qh[NB][KS], ql[NB][KS];
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
-        load_q_operand<DR, true, F, PACK>(q + ((size_t)h * M + lat0 + 32 * b + l32) * DR, hh, c2, false, qh[b], ql[b]);
+        load_q_operand<DR, true, F, PACK>(q + (size_t)h * ts.sq + (size_t)(lat0 + 32 * b + l32) * DR, hh, c2, false, qh[b], ql[b]);
     }
     u32x4 wzero;
     wzero[0] = 0u; wzero[1] = 0u; wzero[2] = 0u; wzero[3] = 0u;
@@ -930,7 +930,7 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         const int m = lat0 + 32 * b + l32;
-        load_q_operand<DR, true, F, PACK>(q + ((size_t)h * M + m) * DR, hh, c2, false, qh[b], ql[b]);
+        load_q_operand<DR, true, F, PACK>(q + (size_t)h * ts.sq + (size_t)m * DR, hh, c2, false, qh[b], ql[b]);
         const float le2 = lse_enc[(size_t)bh * M + m] * kLog2e;
         const float um = ONE ? fast_exp2(le2 - kap) : 1.f;   // folded into Z
         if constexpr (ONE) {
@@ -1249,7 +1249,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
 
     // ---- build the operand images ----
     {
-        const bf16_t *qh_ = q + ((size_t)h * Mtot + m0) * DR;
+        const bf16_t *qh_ = q + (size_t)h * ts.sq + (size_t)m0 * DR;
         const float *zb = z + ((size_t)bh * Mtot + m0) * DR;
         const float *dzb = dz + ((size_t)bh * Mtot + m0) * DR;
         const float *eb = eps + (size_t)bh * Mtot + m0;
@@ -1571,7 +1571,7 @@ __global__ __launch_bounds__(64 * MT) void gram_mfma_kernel(
     const bool lower = hh == 0;
 
     bf16x8 qh[KS], ql[KS];
-    load_q_operand<DR, true, false>(q + ((size_t)h * M + 32 * wave + l32) * DR, hh, c2, false, qh, ql);
+    load_q_operand<DR, true, false>(q + (size_t)h * ts.sq + (size_t)(32 * wave + l32) * DR, hh, c2, false, qh, ql);
     u32x4 wq;
     wq[0] = lower ? split_bf16_pair(-0.5f * kLog2e * lse_enc[(size_t)bh * M + 32 * wave + l32]) : 0u;
     wq[1] = lower ? 0x3f803f80u : 0u;      // slots 2,3 := 1 (pick the token's half-normaliser)
@@ -2170,7 +2170,7 @@ static int decode_all(const flare_shape &s, const void *q, const void *k, const 
     const size_t rows = (size_t)s.B * s.H * s.N;
     bf16_t *y_part = static_cast<bf16_t *>(ws);
     float *lse_part = reinterpret_cast<float *>(static_cast<char *>(ws) + ((rows * C * s.d * 2 + 255) & ~(size_t)255));
-    const TokStride tp{(long long)s.H * s.N * s.d, (long long)s.N * s.d, s.d};   // partial rows: [b][h][n][d]
+    const TokStride tp{(long long)s.H * s.N * s.d, (long long)s.N * s.d, s.d, 0};   // partial rows: [b][h][n][d]
     for (int c = 0; c < C; ++c) {
         const int rc = launch_decode_family<0>(s, q, k, z, y_part + (size_t)c * rows * s.d, tp, nullptr,
                                                lse_part + (size_t)c * rows, nullptr, c * kLatChunk, kLatChunk, scale,

@@ -49,7 +49,7 @@ __global__ __launch_bounds__(256) void gram_valu_kernel(
         const T *kr = kb + (size_t)n * (size_t)ts.sn;
         const float hd = 0.5f * lse_dec[(size_t)bh * N + n];
         for (int m = tid; m < M; m += 256) {
-            const T *qr = q + ((size_t)h * M + m) * d;
+            const T *qr = q + (size_t)h * ts.sq + (size_t)m * d;
             float s = 0.f;
             for (int j = 0; j < d; ++j) s = fmaf(elem(qr, j), elem(kr, j), s);
             jcol[m] = __expf(scale * s - 0.5f * lse_enc[(size_t)bh * M + m] - hd);

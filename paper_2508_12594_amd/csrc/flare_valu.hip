@@ -11,7 +11,7 @@
 // one v_exp_f32 per score.  Every cross-block reduction goes through per-chunk partials
 // that are merged in a fixed order: results are bit-reproducible.
 //
-// Equations: Section 3.1, Eq. flare_encode / Eq. flare_decode; Appendix E per-latent and
+// Equations: Section 3.1, Eq. flare_encode / Eq. flare_decode; Appendix F per-latent and
 // per-token forms.  The backward follows the formulas in include/flare.h.
 #include <stdlib.h>
 
@@ -133,7 +133,7 @@ __global__ __launch_bounds__(kLatentBlock) void encode_partial_kernel(
     if (m >= M) return;
     const int bh = blockIdx.y, h = bh % H, chunk = blockIdx.x;
     float qm[D];
-    load_row<D>(q + ((size_t)h * M + m) * D, qm);
+    load_row<D>(q + (size_t)h * ts.sq + (size_t)m * D, qm);
 #pragma unroll
     for (int j = 0; j < D; ++j) qm[j] *= c2;
     const T *kb = k + tok_base(ts, bh, H);
@@ -266,7 +266,7 @@ __global__ __launch_bounds__(kTokenBlock) void token_pass_kernel(
     load_row<D>(k + trow, kn);
 #pragma unroll
     for (int j = 0; j < D; ++j) kn[j] *= c2;
-    const T *qh = q + (size_t)h * M * D;
+    const T *qh = q + (size_t)h * ts.sq;
     const float *zb = z + (size_t)bh * M * D;
 
     float mr = -INFINITY, l = 0.f, acc[D];
@@ -362,7 +362,7 @@ __global__ __launch_bounds__(kLatentBlock) void dz_partial_kernel(
     if (m >= M) return;
     const int bh = blockIdx.y, h = bh % H, chunk = blockIdx.x;
     float qm[D];
-    load_row<D>(q + ((size_t)h * M + m) * D, qm);
+    load_row<D>(q + (size_t)h * ts.sq + (size_t)m * D, qm);
 #pragma unroll
     for (int j = 0; j < D; ++j) qm[j] *= c2;
     const T *kb = k + tok_base(ts, bh, H);
@@ -460,7 +460,7 @@ __global__ __launch_bounds__(kLatentBlock) void dq_partial_kernel(
     if (m >= M) return;
     const int bh = blockIdx.y, h = bh % H, chunk = blockIdx.x;
     float qm[D], zm[D], dzm[D], acc[D];
-    load_row<D>(q + ((size_t)h * M + m) * D, qm);
+    load_row<D>(q + (size_t)h * ts.sq + (size_t)m * D, qm);
     load_row<D>(z + ((size_t)bh * M + m) * D, zm);
     load_row<D>(dz + ((size_t)bh * M + m) * D, dzm);
 #pragma unroll
@@ -530,7 +530,7 @@ __global__ __launch_bounds__(kTokenBlock) void dkdv_kernel(
     for (int j = 0; j < D; ++j) { kn[j] *= c2; ak[j] = 0.f; av[j] = 0.f; }
     const float ld2 = lse_dec2[row];
     const float dl = delta[row];
-    const T *qh = q + (size_t)h * M * D;
+    const T *qh = q + (size_t)h * ts.sq;
     const float *zb = z + (size_t)bh * M * D;
     const float *dzb = dz + (size_t)bh * M * D;
     const float *leb = lse_enc + (size_t)bh * M;
@@ -722,7 +722,12 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     {
         LaunchTimer t(KID_BWD_DQ_REDUCE, stream);
-        dq_reduce_kernel<D><<<dim3((s.M + 15) / 16, s.H), 256, 0, stream>>>(w.part, dq, s.B, s.H, s.M, dq_parts, scale);
+        // shared latents: one gradient for all heads, summed over (b, h) in that fixed order
+        if (s.shared_latents)
+            dq_reduce_kernel<D><<<dim3((s.M + 15) / 16, 1), 256, 0, stream>>>(w.part, dq, BH, 1, s.M, dq_parts, scale);
+        else
+            dq_reduce_kernel<D><<<dim3((s.M + 15) / 16, s.H), 256, 0, stream>>>(w.part, dq, s.B, s.H, s.M, dq_parts,
+                                                                                scale);
     }
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     if (mf && mfma_dkdv_supported(s)) {

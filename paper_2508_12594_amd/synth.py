@@ -5,8 +5,8 @@ arithmetic (no scores, no softmax).  It is the one piece shared by the HIP path'
 callers and by the CPU oracle's callers, so that both consume identical values.
 
 The five workloads mirror the shapes the paper times or trains on (Fig. 2 and
-Appendix F "Time and memory complexity": C=128, H=8, up to one million tokens;
-Section 5.4 / Appendix D.5: million-point meshes; Table 2: 4k-token sequences).
+Appendix G "Time and memory complexity": C=128, H=8, up to one million tokens;
+Section 5.2 / Appendix E: million-point meshes; Table 2: 4k-token sequences).
 The paper's datasets are not available, so smooth mesh-like fields stand in for them:
 points drawn uniformly in the unit square / cube, three smooth sine fields of the
 coordinates, lifted to C channels and projected to keys and values.

@@ -29,7 +29,7 @@ def test_header_symbols_are_exported(lib):
 
 
 def test_version_and_strerror(lib):
-    assert binding.version() >= 100
+    assert binding.version() >= 200
     assert binding.strerror(0) == "success"
     for code in (-1, -2, -3, -4, -5, -99):
         assert len(binding.strerror(code)) > 0
@@ -45,6 +45,8 @@ def test_workspace_bytes_and_shape_checks(lib):
         shp = binding.FlareShape(B, H, N, M, d, dt)
         assert lib.flare_workspace_bytes(ctypes.byref(shp), None, None) == want
     assert lib.flare_workspace_bytes(None, None, None) == -1
+    shp = binding.FlareShape(1, 1, 8, 32, 16, binding.FLARE_F32, 0, 2)      # shared_latents must be 0 or 1
+    assert lib.flare_workspace_bytes(ctypes.byref(shp), None, None) == -1
 
 
 def test_null_and_misaligned_pointers_are_rejected(lib):

@@ -165,7 +165,7 @@ def test_edge_shapes_forward_backward(oracle, shape, dtype):
 
 
 # Head dimensions below 16 on the matrix-core path (contraction padded to 16): the regime of the paper's
-# PDE models (C = 64, H = 8, so D = 8; Section 5 and Appendix G settings) and of its D = 4 ablation.
+# PDE models (C = 64, H = 8, so D = 8; Section 5 and Appendix D settings) and of its D = 4 ablation.
 SMALL_D_SHAPES = [
     # B, H, N, M, d
     (1, 2, 1000, 64, 8),
@@ -190,7 +190,7 @@ def test_small_head_dims_matrix_core_path(oracle, shape):
 
 
 # More than 256 latents per head on the matrix-core path (chunks of 256 latents): the paper's
-# million-point model uses up to M = 2048 (Section 5, "Scalability"; Appendix G).
+# million-point model uses up to M = 2048 (Section 5.2; Appendix E).
 LARGE_M_SHAPES = [
     # B, H, N, M, d
     (1, 2, 1500, 512, 16),
@@ -214,7 +214,7 @@ def test_many_latents_matrix_core_path(oracle, shape):
 
 @pytest.mark.parametrize("shape", [(1, 2, 1000, 72, 16), (2, 1, 515, 40, 8), (1, 1, 300, 200, 32), (1, 2, 129, 70, 4)])
 def test_fp16_storage(oracle, shape):
-    """IEEE fp16 inputs and outputs (the paper's autocast type, Appendix F) on shapes the vector kernels
+    """IEEE fp16 inputs and outputs (the paper's autocast type, Appendix G) on shapes the vector kernels
     take: fp32 arithmetic, so only the rounding of the outputs to fp16 separates the result from the
     fp32 path's."""
     B, H, N, M, d = shape

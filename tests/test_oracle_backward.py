@@ -1,7 +1,7 @@
 """Pins for the oracle's backward (CPU only).
 
 The paper derives no gradient (it relies on automatic differentiation through its two
-attention calls, Appendix F "Time and memory complexity"), so the oracle's formulas are
+attention calls, Appendix G "Time and memory complexity"), so the oracle's formulas are
 pinned by central finite differences of the oracle-independent explicit form W.V, by
 identities that follow from W being row-stochastic, and by torch autograd through the
 paper's listing in fp64.

@@ -4,7 +4,7 @@ Each test checks the oracle against something the paper or the mathematics fixes
 against itself: explicit W.V (Section 3.1, Eq. attn_W; Appendix C listing), the structure of
 W (rank <= M, row-stochastic), the spectral identity of Appendix C.1 / Algorithm 1,
 permutation equivariance (Section 5.3), closed forms that follow from the per-latent and
-per-token equations of Appendix E, and a library second opinion (the paper's own listing
+per-token equations of Appendix F, and a library second opinion (the paper's own listing
 run with torch's fp64 scaled_dot_product_attention).
 """
 import os
