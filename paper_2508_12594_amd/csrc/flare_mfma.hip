@@ -119,6 +119,21 @@ __device__ __forceinline__ uint32_t pack_elems(float a, float b)
         return cvt_pk_bf16(a, b);
     }
 }
+// Value of a stored dY element as the c product sees it: with fp16 storage the rows are rounded to
+// bf16 before they meet Z, and delta[n] = <dY_n, Y_n> must be formed from the same rounded values, or
+// c - delta = <dY_n, Z_m - Y_n> would not cancel where the latents agree (one latent: exactly zero).
+template <bool F>
+__device__ __forceinline__ float dy_lo(uint32_t w)
+{
+    if constexpr (F) return __uint_as_float(rne_bf16(elem_lo<true>(w)) << 16);
+    else return elem_lo<false>(w);
+}
+template <bool F>
+__device__ __forceinline__ float dy_hi(uint32_t w)
+{
+    if constexpr (F) return __uint_as_float(rne_bf16(elem_hi<true>(w)) << 16);
+    else return elem_hi<false>(w);
+}
 // 1.0 in the storage type, and twice in one word
 template <bool F> constexpr uint32_t kOne = F ? 0x3c00u : 0x3f80u;
 template <bool F> constexpr uint32_t kOnePair = F ? 0x3c003c00u : 0x3f803f80u;
@@ -255,6 +270,16 @@ __device__ __forceinline__ void load_q_operand(const bf16_t *__restrict__ q_row,
     }
 }
 
+// Any number of latents runs on tiles of 32: a latent index at or beyond the head's real count is a
+// padding latent.  Its operands are zeros (loads are clamped to the last real row, never past the
+// tensor), its results are not stored, and where it could enter a sum over the latents (the decode's
+// softmax, dK and dV) it is masked or multiplies zeros.
+__device__ __forceinline__ bf16x8 zero_operand()
+{
+    u32x4 w;
+    w[0] = 0u; w[1] = 0u; w[2] = 0u; w[3] = 0u;
+    return __builtin_bit_cast(bf16x8, w);
+}
 // x as a hi + lo pair of storage-type values packed in one word (hi in the low half)
 template <bool F>
 __device__ __forceinline__ uint32_t split_pair(float x)
@@ -295,15 +320,18 @@ __device__ __forceinline__ void compiler_fence() { asm volatile("" ::: "memory")
 // MODE 0 writes y and, when lse_dec2 is not NULL, log sum_m exp(S[m][n]) (natural log) there.
 // MODE 1 (first step of the backward when nothing was saved) writes per token
 //   lse_dec2[n] = log2 sum_m 2^S2[m][n]   and   delta[n] = <dY_n, Y_n>   (Y_n kept in fp32).
-template <int DR, int MT, bool PRE, int MINB, int MODE, bool F>
+// MASKED: some of the 32*MT latents are padding (instantiated apart so that the common case carries no
+// mask code between its matrix and vector instructions).
+template <int DR, int MT, bool PRE, int MINB, int MODE, bool F, bool MASKED>
 __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const float *__restrict__ z,
     bf16_t *__restrict__ y, const bf16_t *__restrict__ dy, float *__restrict__ lse_dec2,
     float *__restrict__ delta, TokStride ts, TokStride ts_y, int H, int N, int Mtot, int m0, float c2)
 {
-    // The kernel works on the latents m0 .. m0 + M of the head's Mtot (M = 32*MT of them); with
-    // Mtot > M its outputs are one chunk's partial result (y normalised within the chunk, lse_dec of
-    // the chunk) that decode_merge_kernel combines.  ts_y: where the rows of y go.
+    // The kernel works on the latents m0 .. m0 + M of the head's Mtot (M = 32*MT of them; those at or
+    // beyond Mtot are padding and get weight zero); with more than one chunk its outputs are one chunk's
+    // partial result (y normalised within the chunk, lse_dec of the chunk) that decode_merge_kernel
+    // combines.  ts_y: where the rows of y go.
     constexpr int D = padded_dim(DR);
     constexpr int KS = D / 16;   // k-steps of the score product
     constexpr int HV = D / 16;   // 16-wide column groups of Z, each with its own ones row
@@ -316,8 +344,16 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
 
     bf16x8 qh[MT][KS], ql[MT][KS];
 #pragma unroll
-    for (int t = 0; t < MT; ++t)
-        load_q_operand<DR, PRE, F, PACK>(q + (size_t)h * ts.sq + (size_t)(m0 + 32 * t + l32) * DR, hh, c2, flip, qh[t], ql[t]);
+    for (int t = 0; t < MT; ++t) {
+        const int m = m0 + 32 * t + l32;
+        load_q_operand<DR, PRE, F, PACK>(q + (size_t)h * ts.sq + (size_t)min(m, Mtot - 1) * DR, hh, c2, flip, qh[t],
+                                         ql[t]);
+        if (m >= Mtot) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) { qh[t][ks] = zero_operand(); ql[t][ks] = zero_operand(); }
+        }
+    }
+    const int mleft = Mtot - m0;   // real latents from m0 on (may exceed the 32*MT this kernel covers)
 
     // Zaug^T operand: row l32 (< 16: column 16*hv + l32 of Z; 16: ones; else zero).  In registers, or --
     // for the shapes whose registers would not allow two waves per SIMD otherwise (ZLDS = !PRE) --
@@ -337,8 +373,10 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
                 for (int i = 0; i < 8; i += 2) {
                     float a, b;
                     if (l32 < 16 && 16 * hv + l32 < DR) {
-                        a = zb[(size_t)(32 * (s / 2) + perm_index(s % 2, hh, i)) * DR + 16 * hv + l32];
-                        b = zb[(size_t)(32 * (s / 2) + perm_index(s % 2, hh, i + 1)) * DR + 16 * hv + l32];
+                        const int la = 32 * (s / 2) + perm_index(s % 2, hh, i);
+                        const int lb = 32 * (s / 2) + perm_index(s % 2, hh, i + 1);
+                        a = la < mleft ? zb[(size_t)la * DR + 16 * hv + l32] : 0.f;
+                        b = lb < mleft ? zb[(size_t)lb * DR + 16 * hv + l32] : 0.f;
                     } else {
                         a = b = (l32 == 16) ? 1.f : 0.f;
                     }
@@ -375,6 +413,15 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
             for (int s = 0; s < KS; ++s)
                 ktn[s] = as_bf16x8(row8_bf16<DR>(kb + tok_off(ts, nld), PACK ? 0 : (D / 2) * hh + 8 * s));
         }
+        // scores of padding latents (tile t, register r holds latent 32t + 8(r/4) + 4hh + r%4) := -inf
+        auto mask_padding = [&](f32x16 &sc, int t) {
+            if constexpr (!MASKED) return;
+            if (32 * (t + 1) > mleft) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (32 * t + 8 * (r / 4) + 4 * hh + (r % 4) >= mleft) sc[r] = -INFINITY;
+            }
+        };
         auto qk_hi = [&](int t) {
             f32x16 r = splat16(0.f);
 #pragma unroll
@@ -389,6 +436,7 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
         for (int t = 0; t < MT; ++t) {
             if (t + 1 < MT) s_next = qk_hi(t + 1);
             sched_fence();
+            mask_padding(s_cur, t);
             mx = max16(s_cur, mx);
             s_cur = s_next;
         }
@@ -430,6 +478,7 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
 #pragma unroll
                 for (int i = 0; i < 16; ++i) s_cur[i] = fmaf(s_cur[i], ac2, -b2);
             }
+            mask_padding(s_cur, t);
             bf16x8 p0, p1;
             exp_pack(s_cur, p0, p1);
 #pragma unroll
@@ -486,14 +535,14 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
                 g0[0] = 0u; g0[1] = 0u; g1[0] = 0u; g1[1] = 0u;
                 if (quartet_inside<DR>(hv, hh, 0)) g0 = *reinterpret_cast<const u32x2 *>(gr + 16 * hv + 4 * hh);
                 if (quartet_inside<DR>(hv, hh, 1)) g1 = *reinterpret_cast<const u32x2 *>(gr + 16 * hv + 8 + 4 * hh);
-                part = fmaf(acc[hv][0] * inv, elem_lo<F>(g0[0]), part);
-                part = fmaf(acc[hv][1] * inv, elem_hi<F>(g0[0]), part);
-                part = fmaf(acc[hv][2] * inv, elem_lo<F>(g0[1]), part);
-                part = fmaf(acc[hv][3] * inv, elem_hi<F>(g0[1]), part);
-                part = fmaf(acc[hv][4] * inv, elem_lo<F>(g1[0]), part);
-                part = fmaf(acc[hv][5] * inv, elem_hi<F>(g1[0]), part);
-                part = fmaf(acc[hv][6] * inv, elem_lo<F>(g1[1]), part);
-                part = fmaf(acc[hv][7] * inv, elem_hi<F>(g1[1]), part);
+                part = fmaf(acc[hv][0] * inv, dy_lo<F>(g0[0]), part);
+                part = fmaf(acc[hv][1] * inv, dy_hi<F>(g0[0]), part);
+                part = fmaf(acc[hv][2] * inv, dy_lo<F>(g0[1]), part);
+                part = fmaf(acc[hv][3] * inv, dy_hi<F>(g0[1]), part);
+                part = fmaf(acc[hv][4] * inv, dy_lo<F>(g1[0]), part);
+                part = fmaf(acc[hv][5] * inv, dy_hi<F>(g1[0]), part);
+                part = fmaf(acc[hv][6] * inv, dy_lo<F>(g1[1]), part);
+                part = fmaf(acc[hv][7] * inv, dy_hi<F>(g1[1]), part);
             }
             part += __shfl_xor(part, 32);
             // the stabiliser that was actually subtracted
@@ -542,7 +591,17 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
 // dimension (each workgroup owns one such chunk and streams the tokens again), the token-major ones
 // run once per chunk and a merge kernel combines the chunks.
 constexpr int kLatChunk = 256;
-inline int lat_eff(int M) { return M > kLatChunk ? kLatChunk : M; }
+// Any M runs on the tile geometry of the next size the kernels are instantiated for: 32, 64, 128, 192
+// (only when M is exactly 192), 256, or whole chunks of 256; the latents beyond M are padding.
+inline int pad_latents(int M)
+{
+    if (M <= 32) return 32;
+    if (M <= 64) return 64;
+    if (M <= 128) return 128;
+    if (M == 192) return 192;
+    return (M + kLatChunk - 1) / kLatChunk * kLatChunk;
+}
+inline int lat_eff(int M) { return M > kLatChunk ? kLatChunk : pad_latents(M); }   // latents per chunk (padded)
 inline int lat_chunks(int M) { return (M + kLatChunk - 1) / kLatChunk; }
 
 constexpr float kLazy = 16.f;   // the stabiliser moves when a score exceeds it by this much (log2 units)
@@ -591,8 +650,14 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     const int lat0 = 32 * NB * (G * (int)blockIdx.z + g);   // a workgroup owns NB*G tiles of latents
     bf16x8 qh[NB][KS], ql[NB][KS];
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
-        load_q_operand<DR, true, F, PACK>(q + (size_t)h * ts.sq + (size_t)(lat0 + 32 * b + l32) * DR, hh, c2, false, qh[b], ql[b]);
+    for (int b = 0; b < NB; ++b) {   // padding latents (at or beyond M): zero queries, nothing stored
+        const int m = lat0 + 32 * b + l32;
+        load_q_operand<DR, true, F, PACK>(q + (size_t)h * ts.sq + (size_t)min(m, M - 1) * DR, hh, c2, false, qh[b],
+                                          ql[b]);
+        if (m >= M) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) { qh[b][ks] = zero_operand(); ql[b][ks] = zero_operand(); }
+        }
     }
     u32x4 wzero;
     wzero[0] = 0u; wzero[1] = 0u; wzero[2] = 0u; wzero[3] = 0u;
@@ -711,8 +776,8 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         for (int i = 0; i < LOADS; ++i)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                part = fmaf(elem_lo<F>(gv[i][e]), elem_lo<F>(yy[i][e]), part);
-                part = fmaf(elem_hi<F>(gv[i][e]), elem_hi<F>(yy[i][e]), part);
+                part = fmaf(dy_lo<F>(gv[i][e]), elem_lo<F>(yy[i][e]), part);
+                part = fmaf(dy_hi<F>(gv[i][e]), elem_hi<F>(yy[i][e]), part);
             }
         // the other half of the row is in the neighbouring lane: quad_perm [1,0,3,2]
         part += __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(part), 0xB1, 0xf, 0xf, true));
@@ -839,6 +904,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     }
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
+        if (lat0 + 32 * b + l32 >= M) continue;
         const size_t slot = part * M + lat0 + 32 * b + l32;
         if (MODE == 0 && hh == 0) {
             m_part[slot] = (cnt > 0) ? c[b] : -INFINITY;
@@ -929,9 +995,15 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
     bf16x8 u_aug[ONE ? NB : 1];
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
-        const int m = lat0 + 32 * b + l32;
+        // padding latents (at or beyond M): every operand zero, loads clamped to the last real latent
+        const bool real = lat0 + 32 * b + l32 < M;
+        const int m = min(lat0 + 32 * b + l32, M - 1);
         load_q_operand<DR, true, F, PACK>(q + (size_t)h * ts.sq + (size_t)m * DR, hh, c2, false, qh[b], ql[b]);
-        const float le2 = lse_enc[(size_t)bh * M + m] * kLog2e;
+        if (!real) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) { qh[b][ks] = zero_operand(); ql[b][ks] = zero_operand(); }
+        }
+        const float le2 = real ? lse_enc[(size_t)bh * M + m] * kLog2e : 0.f;
         const float um = ONE ? fast_exp2(le2 - kap) : 1.f;   // folded into Z
         if constexpr (ONE) {
             const uint32_t us = split_bf16_pair(um);          // slots 0,1,2 := u hi, u hi, u lo
@@ -951,6 +1023,10 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
             float zr[8], dr[8];
             row8_f32<DR>(z + ((size_t)bh * M + m) * DR, PACK ? 0 : (D / 2) * hh + 8 * s, zr);
             row8_f32<DR>(dz + ((size_t)bh * M + m) * DR, (D / 2) * hh + 8 * s, dr);
+            if (!real) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) { zr[i] = 0.f; dr[i] = 0.f; }
+            }
             u32x4 wz, wd, wzl;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -967,7 +1043,7 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
             zl[b][s] = as_bf16x8(wzl);
         }
         u32x4 we;
-        we[0] = (lower != PACK) ? split_bf16_pair(-eps[(size_t)bh * M + m]) : 0u;
+        we[0] = (lower != PACK) ? split_bf16_pair(real ? -eps[(size_t)bh * M + m] : 0.f) : 0u;
         we[1] = 0u; we[2] = 0u; we[3] = 0u;
         dz_aug[b] = as_bf16x8(we);
         if constexpr (PACK) {   // slots 8,9 of the dZ operand := -eps (the rest of its upper half is zero)
@@ -1171,6 +1247,7 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
     const size_t part = (size_t)bh * parts + (size_t)chunk * TG + tg;
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
+        if (lat0 + 32 * b + l32 >= M) continue;
         const size_t slot = part * M + lat0 + 32 * b + l32;
 #pragma unroll
         for (int hv = 0; hv < HV; ++hv) {
@@ -1188,7 +1265,8 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
 // workgroup as MFMA-ready operand images in LDS (one (b,h) per workgroup, 8 waves share it):
 //   A-type images (row = latent, contraction over d): q' hi, q' lo, dZ hi (and lo), Z hi (and
 //     lo), and a correction operand (slots 0,1 = -lse_enc2 as a hi+lo pair, slots 2,3 = 1,1; slots
-//     8,9 = -eps as a hi+lo pair);
+//     8,9 = -eps as a hi+lo pair; slots 10,11 = 1,1 or, with one exponential, slots 4-6 = u: they
+//     pick -delta[n] out of the token-side operand of the c chain's correction k-step);
 //   row images (row = output column, contraction over the 32 latents in accumulator order):
 //     RW1 = [dZ^T ; 0]   and   RW2 = [q^T ; 0].
 // Per token tile and latent tile:  P = 2^(S2 - lse_enc2[m]), R = 2^(S2 - lse_dec2[n]),
@@ -1254,13 +1332,19 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
         const float *dzb = dz + ((size_t)bh * Mtot + m0) * DR;
         const float *eb = eps + (size_t)bh * Mtot + m0;
         const float *leb = lse_enc + (size_t)bh * Mtot + m0;
+        // Padding latents (at or beyond Mtot; mleft = real ones from m0 on): loads are clamped to the last
+        // real latent and every value that could reach dK or dV is zero -- q, Z, dZ, eps, u and the ones
+        // that pick -delta -- so that a = c = 0 and dS = 0 whatever P and R come out as.
+        const int mleft = Mtot - m0;
         for (int idx = tid; idx < MT * PER_TILE * 64; idx += 512) {
             const int ln = idx & 63, sid = (idx >> 6) % PER_TILE, t = (idx >> 6) / PER_TILE;
             const int r32 = ln & 31, hf = ln >> 5;
             u32x4 w;
             if (sid == NA - 1) {
                 // correction operand: slots 0,1 = -lse_enc2 (hi + lo pair), slots 2,3 = 1, else zero
-                const float le2 = leb[32 * t + r32] * kLog2e;
+                const bool real = 32 * t + r32 < mleft;
+                const int mc = min(32 * t + r32, mleft - 1);
+                const float le2 = real ? leb[mc] * kLog2e : 0.f;
                 w[0] = hf == 0 ? split_pair<F>(-le2) : 0u;
                 w[1] = hf == 0 ? kOnePair<F> : 0u;
                 w[2] = 0u; w[3] = 0u;
@@ -1269,14 +1353,18 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                 // (and the a and c products meet slots 0-3 with zeros).  u <= 1 and finite 16-bit patterns of either type read as finite values
                 // of the other, so the foreign slots contribute exact zeros.
                 if constexpr (ONE) {   // slots 4,5,6 := u hi, u hi, u lo
-                    const uint32_t us = split_bf16_pair(fast_exp2(le2 - kap));
+                    const uint32_t us = split_bf16_pair(real ? fast_exp2(le2 - kap) : 0.f);
                     w[2] = hf == 0 ? ((us & 0xffffu) | (us << 16)) : 0u;
                     w[3] = hf == 0 ? (us >> 16) : 0u;
                 }
-                if (hf == 1) w[0] = split_bf16_pair(-eb[32 * t + r32]);   // slots 8,9 := -eps (bf16: the a chain)
+                if (hf == 1) {
+                    w[0] = split_bf16_pair(real ? -eb[mc] : 0.f);          // slots 8,9 := -eps (bf16: the a chain)
+                    if (!ONE && real) w[1] = 0x3f803f80u;                  // slots 10,11 := 1 (picks -delta, two exponentials)
+                }
             } else if (sid < NA) {
                 const int kind = sid / KS, ks = sid % KS;          // 0 qh, 1 ql, 2 dzh, 3 zh, 4 dzl, 5 zl
-                const int m = 32 * t + r32;
+                const bool real = 32 * t + r32 < mleft;
+                const int m = min(32 * t + r32, mleft - 1);
                 const int d0 = (D / 2) * hf + 8 * ks;
                 float x[8];
                 if (kind <= 1) {
@@ -1289,6 +1377,10 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                     const float um = (ONE && is_z) ? fast_exp2(leb[m] * kLog2e - kap) : 1.f;
 #pragma unroll
                     for (int i = 0; i < 8; ++i) x[i] *= um;
+                }
+                if (!real) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) x[i] = 0.f;
                 }
                 const bool want_lo = (kind == 1 || kind >= 4 || (PACK && kind == 0 && hf == 1));
 #pragma unroll
@@ -1309,8 +1401,8 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                     }
                     w[i] = a | (b << 16);
                 }
-                if (PACK && hf == 1 && kind == 2) w[0] = split_bf16_pair(-eb[m]);   // slots 8,9 := -eps
-                if (PACK && hf == 1 && kind == 3) {                                  // slots 8,9,10 := u, u, u lo / 1, 1
+                if (PACK && hf == 1 && kind == 2 && real) w[0] = split_bf16_pair(-eb[m]);   // slots 8,9 := -eps
+                if (PACK && hf == 1 && kind == 3 && real) {                          // slots 8,9,10 := u, u, u lo / 1, 1
                     if constexpr (ONE) {
                         const uint32_t us = split_bf16_pair(fast_exp2(leb[m] * kLog2e - kap));
                         w[0] = (us & 0xffffu) | (us << 16);
@@ -1326,13 +1418,14 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
 #pragma unroll
                 for (int i = 0; i < 8; i += 2) {
                     float a, b;
-                    const int m0 = 32 * t + perm_index(s2, hf, i), m1 = 32 * t + perm_index(s2, hf, i + 1);
+                    const int ma = 32 * t + perm_index(s2, hf, i), mb = 32 * t + perm_index(s2, hf, i + 1);
                     const bool in = dd < DR;   // beyond the real head dimension every row image is zero
-                    const float q0 = in ? elem_value<F>(qh_[(size_t)m0 * DR + dd]) : 0.f;
-                    const float q1 = in ? elem_value<F>(qh_[(size_t)m1 * DR + dd]) : 0.f;
+                    const bool ina = in && ma < mleft, inb = in && mb < mleft;
+                    const float q0 = ina ? elem_value<F>(qh_[(size_t)ma * DR + dd]) : 0.f;
+                    const float q1 = inb ? elem_value<F>(qh_[(size_t)mb * DR + dd]) : 0.f;
                     if (which == 0) {
-                        a = (r32 < 16 && in) ? dzb[(size_t)m0 * DR + dd] : 0.f;
-                        b = (r32 < 16 && in) ? dzb[(size_t)m1 * DR + dd] : 0.f;
+                        a = (r32 < 16 && ina) ? dzb[(size_t)ma * DR + dd] : 0.f;
+                        b = (r32 < 16 && inb) ? dzb[(size_t)mb * DR + dd] : 0.f;
                     } else {
                         a = (r32 < 16) ? q0 : 0.f;
                         b = (r32 < 16) ? q1 : 0.f;
@@ -1346,9 +1439,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     __syncthreads();
 
     u32x4 w11;
-    w11[0] = lower ? 0x3f803f80u : 0u;
     w11[1] = 0u; w11[2] = 0u; w11[3] = 0u;
-    const bf16x8 ones_aug = as_bf16x8(w11);
     w11[0] = lower ? kOnePair<F> : 0u;
     const bf16x8 ones_s = as_bf16x8(w11);        // the same in the type of the score products
     w11[0] = lower ? 0u : 0x3f803f80u;
@@ -1402,8 +1493,8 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
         const bf16x8 kt_a = ones_s, kt_b = as_bf16x8(wb);    // slots 0,1 := 1 picks -lse_enc2
         u32x4 wg;
         const uint32_t ds_ = split_bf16_pair(-dl);
-        wg[0] = (!ONE && lower) ? ds_ : 0u;                  // two exponentials: slots 0,1 := -delta (hi, lo)
-        wg[1] = 0u;
+        wg[0] = 0u;
+        wg[1] = (!ONE && !lower) ? ds_ : 0u;                 // two exponentials: slots 10,11 := -delta (hi, lo)
         wg[2] = (ONE && lower) ? ds_ : 0u;                   // one: slots 4,5,6 := -delta hi, lo, hi
         wg[3] = (ONE && lower) ? (ds_ & 0xffffu) : 0u;
         const bf16x8 g_aug = as_bf16x8(wg);
@@ -1441,7 +1532,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
             f32x16 av = splat16(0.f), cv = splat16(0.f);
             if constexpr (!PACK) {
                 av = mfma(image(t, NA - 1), ones_eps, av);
-                cv = mfma(ONE ? image(t, NA - 1) : ones_aug, g_aug, cv);
+                cv = mfma(image(t, NA - 1), g_aug, cv);
             }
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
@@ -1667,7 +1758,7 @@ EncGeom dq_geom(const flare_shape &s, int *zdim)
         e.TG = 1;
     }
     e.threads = 64 * e.G * e.TG;
-    *zdim = s.M / (32 * e.NB * e.G);
+    *zdim = pad_latents(s.M) / (32 * e.NB * e.G);
     return e;
 }
 
@@ -1680,9 +1771,7 @@ bool mfma_supported(const flare_shape &s)
 {
     if (s.dtype != FLARE_BF16 && s.dtype != FLARE_F16) return false;
     if (s.d != 4 && s.d != 8 && s.d != 16 && s.d != 32) return false;   // d < 16 runs padded to 16
-    if (s.M == 32) return true;
-    if (s.M > kLatChunk) return s.M % kLatChunk == 0 && s.M <= 2048;   // whole chunks of 256 latents
-    return s.M % 64 == 0;
+    return s.M <= 2048;   // any number of latents: tiles of 32, the last ones padded
 }
 
 MfmaPlan mfma_plan(const flare_shape &s)
@@ -1850,9 +1939,7 @@ int mfma_dq_partial(const flare_shape &s, const void *q, const void *k, const vo
 // the operand images need (4 or 6)*KS + 1 + 4*HV KiB of LDS per latent tile.
 bool mfma_dkdv_supported(const flare_shape &s)
 {
-    if (!mfma_supported(s)) return false;
-    const int MT = lat_eff(s.M) / 32;
-    return MT == 1 || MT == 2 || MT == 4 || MT == 8;
+    return mfma_supported(s);
 }
 
 int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy, const float *z,
@@ -1866,7 +1953,7 @@ int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v,
     if (blocks > (tiles + 7) / 8) blocks = (tiles + 7) / 8;
     const dim3 grid(blocks, BH);
     const float c2 = scale * kLog2e;
-    const int MT = lat_eff(s.M) / 32;
+    const int MT = lat_eff(s.M) == 192 ? 8 : lat_eff(s.M) / 32;   // instantiated for 1, 2, 4, 8 tiles
     const int pd = padded_dim(s.d);
     const bool lo2 = false;   // see the kernel's comment on LO2
     const int KS = pd / 16, HV = pd / 16;
@@ -2049,14 +2136,18 @@ static int launch_decode_family(const flare_shape &s, const void *q, const void 
     bf16_t *yy = (bf16_t *)y;
     LaunchTimer t(MODE == 0 ? KID_DECODE : KID_BWD_TOKEN_STATS, stream);
     const bool f16 = s.dtype == FLARE_F16;
+    const bool masked = s.M - m0 < Mc;   // padding latents in this launch
+#define FLARE_DEC_ARGS qq, kk, z, yy, gg, lse_dec2, delta, tok_stride(s), ts_y, s.H, s.N, s.M, m0, c2
 #define FLARE_DEC(DD, MTT, PREE, MINB)                                                                          \
     do {                                                                                                        \
-        if (f16)                                                                                                \
-            decode_mfma_kernel<DD, MTT, PREE, MINB, MODE, true><<<grid, 256, 0, stream>>>(                      \
-                qq, kk, z, yy, gg, lse_dec2, delta, tok_stride(s), ts_y, s.H, s.N, s.M, m0, c2);                \
+        if (f16 && masked)                                                                                      \
+            decode_mfma_kernel<DD, MTT, PREE, MINB, MODE, true, true><<<grid, 256, 0, stream>>>(FLARE_DEC_ARGS); \
+        else if (f16)                                                                                           \
+            decode_mfma_kernel<DD, MTT, PREE, MINB, MODE, true, false><<<grid, 256, 0, stream>>>(FLARE_DEC_ARGS); \
+        else if (masked)                                                                                        \
+            decode_mfma_kernel<DD, MTT, PREE, MINB, MODE, false, true><<<grid, 256, 0, stream>>>(FLARE_DEC_ARGS); \
         else                                                                                                    \
-            decode_mfma_kernel<DD, MTT, PREE, MINB, MODE, false><<<grid, 256, 0, stream>>>(                     \
-                qq, kk, z, yy, gg, lse_dec2, delta, tok_stride(s), ts_y, s.H, s.N, s.M, m0, c2);                \
+            decode_mfma_kernel<DD, MTT, PREE, MINB, MODE, false, false><<<grid, 256, 0, stream>>>(FLARE_DEC_ARGS); \
     } while (0)
     const int MT = Mc / 32;
 #define FLARE_DEC_MT(DD)                               \
@@ -2086,6 +2177,7 @@ static int launch_decode_family(const flare_shape &s, const void *q, const void 
     }
 #undef FLARE_DEC_MT
 #undef FLARE_DEC
+#undef FLARE_DEC_ARGS
     return check_launch();
 }
 
@@ -2140,10 +2232,10 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(
 #pragma unroll
         for (int j = 0; j < DR; j += 4) {
             const u32x2 g = *reinterpret_cast<const u32x2 *>(dy + trow + j);
-            dl = fmaf(acc[j] * inv, elem_lo<F>(g[0]), dl);
-            dl = fmaf(acc[j + 1] * inv, elem_hi<F>(g[0]), dl);
-            dl = fmaf(acc[j + 2] * inv, elem_lo<F>(g[1]), dl);
-            dl = fmaf(acc[j + 3] * inv, elem_hi<F>(g[1]), dl);
+            dl = fmaf(acc[j] * inv, dy_lo<F>(g[0]), dl);
+            dl = fmaf(acc[j + 1] * inv, dy_hi<F>(g[0]), dl);
+            dl = fmaf(acc[j + 2] * inv, dy_lo<F>(g[1]), dl);
+            dl = fmaf(acc[j + 3] * inv, dy_hi<F>(g[1]), dl);
         }
         lse_out[row] = lse * kLog2e;
         delta[row] = dl;
@@ -2165,7 +2257,8 @@ static int decode_all(const flare_shape &s, const void *q, const void *k, const 
                       float *lse_out, float *delta, float scale, void *ws, hipStream_t stream)
 {
     if (s.M <= kLatChunk)
-        return launch_decode_family<MODE>(s, q, k, z, y, tok_stride(s), dy, lse_out, delta, 0, s.M, scale, stream);
+        return launch_decode_family<MODE>(s, q, k, z, y, tok_stride(s), dy, lse_out, delta, 0, lat_eff(s.M), scale,
+                                          stream);
     const int C = lat_chunks(s.M);
     const size_t rows = (size_t)s.B * s.H * s.N;
     bf16_t *y_part = static_cast<bf16_t *>(ws);

@@ -9,11 +9,9 @@ TOL = {"f32": 1e-5, "bf16": 2e-2, "f16": 1e-3}
 
 
 def on_matrix_cores(dtype, M):
-    """The library's documented rule: 16-bit storage with M = 32, a multiple of 64 up to 256, or a
-    multiple of 256 up to 2048 runs on the matrix-core kernels."""
-    if dtype == "f32":
-        return False
-    return M == 32 or (M <= 256 and M % 64 == 0) or (M > 256 and M % 256 == 0 and M <= 2048)
+    """The library's documented rule: 16-bit storage with at most 2048 latents per head runs on the
+    matrix-core kernels (tiles of 32 latents, the last ones padded)."""
+    return dtype != "f32" and M <= 2048
 
 
 def tol_for(inp):

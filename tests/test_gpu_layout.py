@@ -36,7 +36,7 @@ CASES = [
     (2, dict(B=1, N=1200, d=8)),    # matrix-core path with the head dimension padded to 16
     (4, dict(N=700, d=4, H=4)),
     (2, dict(B=1, N=900, M=512)),                # latent chunks on the matrix-core path
-    (1, dict(N=400, M=72, dtype="f16")),         # fp16 storage, vector kernels
+    (1, dict(N=400, M=72, dtype="f16")),         # fp16 storage, 8 padding latents
     (4, dict(N=1100, dtype="f16")),              # fp16 storage, matrix-core path
     (5, dict(N=700, dtype="f16")),
 ]

@@ -172,7 +172,7 @@ SMALL_D_SHAPES = [
     (2, 1, 777, 256, 8),
     (1, 3, 515, 128, 8),
     (1, 2, 2049, 32, 8),
-    (1, 1, 999, 192, 8),      # three latent groups; dK/dV on the vector path
+    (1, 1, 999, 192, 8),      # three latent groups; dK/dV with two padding tiles
     (1, 2, 1000, 64, 4),
     (1, 2, 333, 256, 4),
     (2, 2, 65, 128, 4),
@@ -212,18 +212,68 @@ def test_many_latents_matrix_core_path(oracle, shape):
     _backward_case(oracle, inp, saved=True)
 
 
-@pytest.mark.parametrize("shape", [(1, 2, 1000, 72, 16), (2, 1, 515, 40, 8), (1, 1, 300, 200, 32), (1, 2, 129, 70, 4)])
-def test_fp16_storage(oracle, shape):
-    """IEEE fp16 inputs and outputs (the paper's autocast type, Appendix G) on shapes the vector kernels
-    take: fp32 arithmetic, so only the rounding of the outputs to fp16 separates the result from the
-    fp32 path's."""
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("shape", [(1, 1, 200, 2100, 8), (1, 2, 70, 2049, 16)])
+def test_sixteen_bit_storage_on_vector_kernels(oracle, shape, dtype):
+    """More than 2048 latents per head: the fp32 vector kernels with 16-bit storage (fp32 arithmetic, so
+    only the rounding of the outputs separates the result from the fp32 path's)."""
     B, H, N, M, d = shape
-    assert not on_matrix_cores("f16", M)
-    _say("fp16 storage %s" % (shape,))
-    inp = synth.make_inputs(1, B=B, H=H, N=N, M=M, d=d, dtype="f16", with_dy=True, seed=606 + N + M)
-    _forward_case(oracle, inp)
-    _backward_case(oracle, inp, saved=False)
-    _backward_case(oracle, inp, saved=True)
+    assert not on_matrix_cores(dtype, M)
+    _say("16-bit storage on the vector kernels %s %s" % (dtype, shape))
+    inp = synth.make_inputs(1, B=B, H=H, N=N, M=M, d=d, dtype=dtype, with_dy=True, seed=606 + N + M)
+    tol = TOL["f16"] if dtype == "f16" else 8e-3       # outputs rounded to 2^-11 / 2^-8 relative
+    _forward_case(oracle, inp, tol=tol)
+    _backward_case(oracle, inp, tol=tol, saved=False)
+    _backward_case(oracle, inp, tol=tol, saved=True)
+
+
+# Numbers of latents that are not a multiple of the tile sizes: padding latents inside the last tile, whole
+# padding tiles (M = 40 runs on the 64-latent geometry, M = 300 on two chunks of 256), M = 1.
+ODD_M_SHAPES = [
+    # B, H, N, M, d
+    (1, 2, 1000, 1, 16),
+    (2, 1, 700, 16, 16),
+    (1, 2, 900, 40, 32),
+    (1, 3, 600, 96, 8),
+    (1, 1, 1500, 100, 16),
+    (1, 2, 800, 160, 32),
+    (1, 1, 999, 200, 4),
+    (1, 2, 500, 255, 16),
+    (1, 1, 600, 300, 16),
+    (1, 1, 400, 513, 8),
+    (1, 1, 300, 1000, 32),
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("shape", ODD_M_SHAPES)
+def test_any_number_of_latents_matrix_core_path(oracle, shape, dtype):
+    B, H, N, M, d = shape
+    _say("odd M %s %s" % (shape, dtype))
+    inp = synth.make_inputs(2, B=B, H=H, N=N, M=M, d=d, dtype=dtype, with_dy=True, seed=515 + N + M + d)
+    tol = TOL["bf16"]
+    _forward_case(oracle, inp, tol=tol)
+    _backward_case(oracle, inp, tol=tol, saved=False)
+    _backward_case(oracle, inp, tol=tol, saved=True)
+
+
+def test_padding_latents_do_not_depend_on_what_lies_beyond_q(oracle):
+    """The last tile's loads are clamped to the last real latent: the result must not change when the
+    memory after q_lat changes (q_lat placed at the end of one buffer, then followed by other data)."""
+    import torch
+    inp = synth.make_inputs(2, B=1, H=2, N=700, M=40, d=16, dtype="bf16", with_dy=True, seed=99)
+    dev = to_device(inp)
+    outs = []
+    for fill in (0.0, 1e30):
+        buf = torch.full((dev["q"].numel() + 4096,), fill, dtype=torch.bfloat16, device="cuda")
+        q = buf[:dev["q"].numel()].view_as(dev["q"])
+        q.copy_(dev["q"])
+        y, z, lse = binding.forward(q, dev["k"], dev["v"], inp["scale"])
+        dq, dk, dv = binding.backward(q, dev["k"], dev["v"], dev["dy"], z, lse, inp["scale"])
+        torch.cuda.synchronize()
+        outs.append((y, z, lse, dq, dk, dv))
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
 
 
 # fp16 storage on the matrix-core path: scores from fp16 products (exact as with bf16 storage), softmax
@@ -235,7 +285,7 @@ F16_MATRIX_CASES = [
     (4, dict(N=5003)),                            # d=16, M=256
     (5, dict(N=3001)),                            # d=32, M=256 (decode with Z in LDS)
     (2, dict(B=1, N=1000, M=32)),
-    (2, dict(B=1, N=1200, M=192)),                # dK/dV on the vector kernels
+    (2, dict(B=1, N=1200, M=192)),                # dK/dV with two padding tiles
     (2, dict(B=1, H=2, N=1000, M=64, d=8)),
     (2, dict(B=1, H=2, N=333, M=256, d=4)),
     (2, dict(B=1, H=2, N=900, M=512)),            # two latent chunks
