@@ -106,25 +106,41 @@ def test_forward_backward_262k(oracle):
         assert max(errs.values()) <= tol
 
 
-@pytest.mark.parametrize("saved", [True, False])
-def test_forward_backward_million_tokens(oracle, saved):
+MILLION_VARIANTS = [
+    # overrides of config 4, saved statistics, bnhd layout
+    (dict(), True, False),
+    (dict(), False, False),
+    (dict(dtype="f16"), True, False),             # the paper's autocast type on the matrix cores
+    (dict(M=200), True, False),                   # 56 padding latents in the last tiles
+    (dict(d=8), False, True),                     # the paper's head dimension for PDE meshes, token-major layout
+    (dict(M=512, H=2, d=8), True, False),         # two latent chunks
+]
+
+
+@pytest.mark.parametrize("over,saved,bnhd", MILLION_VARIANTS)
+def test_forward_backward_million_tokens(oracle, over, saved, bnhd):
     """The step bench.py times: config 4 (N = 1,000,000, M = 256, d = 16) forward + backward, with the
-    forward's y and lse_dec handed to the backward (saved) or recomputed."""
+    forward's y and lse_dec handed to the backward (saved) or recomputed; and variants of it (storage
+    type, number of latents, head dimension, layout) at the same million tokens."""
     import torch
-    _say("full forward+backward cfg4 saved=%s" % saved)
-    inp = synth.make_inputs(4, with_dy=True)
+    _say("full forward+backward cfg4 %s saved=%s bnhd=%s" % (over, saved, bnhd))
+    inp = synth.make_inputs(4, with_dy=True, **over)
     N, scale, tol = inp["N"], inp["scale"], TOL["bf16"]
     dev = to_device(inp)
+    layout = "bnhd" if bnhd else "bhnd"
+    conv = (lambda t: t.permute(0, 2, 1, 3).contiguous()) if bnhd else (lambda t: t)
+    back = (lambda t: t.permute(0, 2, 1, 3)) if bnhd else (lambda t: t)
+    k, v, dy = conv(dev["k"]), conv(dev["v"]), conv(dev["dy"])
     lse_dec = torch.empty(dev["k"].shape[:3], dtype=torch.float32, device="cuda") if saved else None
-    y, z, lse = binding.forward(dev["q"], dev["k"], dev["v"], scale, lse_dec=lse_dec)
-    dq, dk, dv = binding.backward(dev["q"], dev["k"], dev["v"], dev["dy"], z, lse, scale,
-                                  y=y if saved else None, lse_dec=lse_dec)
+    y, z, lse = binding.forward(dev["q"], k, v, scale, lse_dec=lse_dec, layout=layout)
+    dq, dk, dv = binding.backward(dev["q"], k, v, dy, z, lse, scale, y=y if saved else None, lse_dec=lse_dec,
+                                  layout=layout)
     torch.cuda.synchronize()
-    dq_h, dk_h, dv_h = (to_host(t) for t in (dq, dk, dv))
+    dq_h, dk_h, dv_h = to_host(dq), to_host(back(dk)), to_host(back(dv))
     for t in (dq_h, dk_h, dv_h):
         assert np.isfinite(t).all()
     tok = _sample_tokens(N, 2048, 6)
-    h = 3
+    h = inp["H"] - 1 if over else 3
     sl = (slice(None), slice(h, h + 1))
     dq_ref, dk_ref, dv_ref = oracle.backward(inp["q"][h:h + 1], inp["k"][sl], inp["v"][sl], inp["dy"][sl], scale,
                                              tok=tok)
