@@ -127,8 +127,10 @@ bool mfma_dkdv_supported(const flare_shape &s);
 // lse_dec with ld_mul = log2(e).
 int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy, const float *z,
               const float *lse_enc, const float *dz, const float *eps, const float *lse_dec2, const float *delta,
-              float ld_mul, const int *plan, bool one_exp, void *dk, void *dv, float *acc32, int m0, float scale,
-              hipStream_t stream);
+              float ld_mul, const int *plan, bool one_exp, void *dk, void *dv, float *acc32, float *dq_part, int m0,
+              float scale, hipStream_t stream);
+int mfma_dkdv_blocks(const flare_shape &s);
+bool mfma_dq_fused(const flare_shape &s);
 int mfma_dkdv_finish(const flare_shape &s, const float *acc32, void *dk, void *dv, hipStream_t stream);
 int mfma_dq_parts(const flare_shape &s);
 int mfma_dq_partial(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy,

@@ -1277,30 +1277,45 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
 // (eps is subtracted inside the a chain, by one more product, so that a - eps = <dZ_m, V_n - Z_m>
 // cancels before dS is rounded: where a latent attends sharply to tokens of similar values the two
 // terms agree to several digits, and carrying -eps q separately through bf16 roundings lost them.)
-// LO2: also carry lo terms of dZ and Z (more accurate a and c; two more products per tile and more
-// LDS).  Not used: the rounding of dZ_m and Z_m is one error per latent, and dK_n and dV_n sum over
-// the latents, so it averages out (measured: dK error up by 5-10 %, time down by 9 %) -- unlike in the
-// dQ kernel, whose sums run over the tokens of one latent and add that error up coherently.
+// No lo terms of dZ and Z for dK and dV: dZ arrives bf16-exact, and the rounding of Z_m is one error per
+// latent, which the sums of dK_n and dV_n over the latents average out (measured: dK error up by
+// 5-10 %, time down by 9 %) -- unlike in dQ, whose sums run over the tokens of one latent and add that
+// error up coherently (the DQ variant below therefore carries the lo term of Z).
 // ONE: one exponential per score, as in the dQ kernel: R = P u[m] w[n]; u is folded into the Z images
 // (and into slots 4-6 of the correction image, against -delta in the token operand), w[n] is a
 // per-lane scalar here, and dS' = P (a + w c).  Runs only where plan[bh] = 1.
 // ============================================================================================
-template <int DR, int MT, bool LO2, bool ONE, bool F>
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+constexpr int kDsStride = 40;   // uint16 per row of the transposed dS tile (80 B: 16-byte aligned, conflict-free b128 reads)
+constexpr int kFusedWaveLds = 32 * kDsStride + 16 * kVtStride;   // uint16 per wave: dS^T tile, then K^T tile
+
+template <int DR, int MT, bool DQ, bool ONE, bool F>
 __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const bf16_t *__restrict__ dy, const float *__restrict__ z, const float *__restrict__ lse_enc,
     const float *__restrict__ dz, const float *__restrict__ eps, const float *__restrict__ lse_dec2,
     const float *__restrict__ delta, float ld_mul, const int *__restrict__ plan, bf16_t *__restrict__ dk,
-    bf16_t *__restrict__ dv, float *__restrict__ acc32, TokStride ts, int H, int N, int Mtot, int m0, float c2,
-    float scale)
+    bf16_t *__restrict__ dv, float *__restrict__ acc32, float *__restrict__ dq_part, TokStride ts, int H, int N,
+    int Mtot, int m0, float c2, float scale)
 {
+    // DQ (d = 16 only): the kernel also forms the dQ partials, so that the scores, a, c and dS of a tile
+    // pair are computed once for all three gradients.  dS of a tile reaches the dQ product transposed
+    // (contraction over the tokens) through a wave-private LDS tile, and that product is
+    //     dQ^T[dd][m] += K^T[dd][n] dS^T[n][m]     with v_mfma_f32_16x16x32_bf16
+    // (16 output rows = d: no wasted rows, four accumulator registers per 16 latents), so a wave keeps
+    // dQ of all 32*MT latents in 8*MT registers.  At the end the eight waves add their partials in a
+    // fixed order through LDS and the workgroup writes slot blockIdx.x of dq_part
+    // ([(b*h) * gridDim.x + blockIdx.x][Mtot][d], summed and scaled by dq_reduce_kernel).  The c chain
+    // then carries the lo term of Z (dQ sums dS over the tokens of one latent and would add up its
+    // rounding coherently, see the dQ kernel).
     // The kernel works on the latents m0 .. m0 + M of the head's Mtot.  With acc32 given (more than one
     // latent chunk) it adds its dV and dK rows in fp32 to acc32[0][b*h][n][DR] and acc32[1][...] (the
     // chunk with m0 = 0 stores instead) and dkdv_finish_kernel rounds the sums to dk and dv.
     constexpr int D = padded_dim(DR);
     constexpr int KS = D / 16;
     constexpr int HV = D / 16;
-    constexpr int NA = (LO2 ? 6 : 4) * KS + 1;  // A-type images per latent tile (the last one: corrections)
+    static_assert(!DQ || DR == 16, "the fused dQ product is written for d = 16");
+    constexpr int NA = 4 * KS + 1;              // A-type images per latent tile (the last one: corrections)
     constexpr int NR = 4 * HV;                  // row images per latent tile (RW1, RW2) x 2 k-steps
     constexpr int PER_TILE = NA + NR;
     constexpr bool PIPE = (D == 16);            // look one latent tile ahead where registers allow
@@ -1308,7 +1323,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     // Images: q' hi | lo in one (keys repeated in both lane halves), slots 8,9 of the dZ image = -eps
     // (against ones in the V operand), slots 8-10 of the Z image = u, u, u lo or 1, 1 (against -delta in
     // the dY operand).  The q' lo image and the a / c parts of the correction image are then unused.
-    constexpr bool PACK = pack_dim(DR) && !LO2;
+    constexpr bool PACK = pack_dim(DR);
     extern __shared__ __attribute__((aligned(16))) u32x4 img[];   // [MT][PER_TILE][64 lanes]
 
     const int tid = threadIdx.x;
@@ -1362,7 +1377,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                     if (!ONE && real) w[1] = 0x3f803f80u;                  // slots 10,11 := 1 (picks -delta, two exponentials)
                 }
             } else if (sid < NA) {
-                const int kind = sid / KS, ks = sid % KS;          // 0 qh, 1 ql, 2 dzh, 3 zh, 4 dzl, 5 zl
+                const int kind = sid / KS, ks = sid % KS;          // 0 q' hi, 1 q' lo, 2 dZ, 3 Z hi, 4 Z lo (DQ only)
                 const bool real = 32 * t + r32 < mleft;
                 const int m = min(32 * t + r32, mleft - 1);
                 const int d0 = (D / 2) * hf + 8 * ks;
@@ -1372,7 +1387,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
 #pragma unroll
                     for (int i = 0; i < 4; ++i) { x[2 * i] = elem_lo<F>(raw[i]) * c2; x[2 * i + 1] = elem_hi<F>(raw[i]) * c2; }
                 } else {
-                    const bool is_z = (kind == 3 || kind == 5);
+                    const bool is_z = kind >= 3;
                     row8_f32<DR>((is_z ? zb : dzb) + (size_t)m * DR, d0, x);
                     const float um = (ONE && is_z) ? fast_exp2(leb[m] * kLog2e - kap) : 1.f;
 #pragma unroll
@@ -1468,6 +1483,16 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     };
     auto image = [&](int t, int sid) { return as_bf16x8(img[(t * PER_TILE + sid) * 64 + lane]); };
 
+    // fused dQ: wave-private LDS tiles and the accumulators dQ^T[dd = 4 (lane / 16) + r][m = 32 t + 16 jb + lane % 16]
+    uint16_t *ds_t = reinterpret_cast<uint16_t *>(img + MT * PER_TILE * 64) + (DQ ? wave * kFusedWaveLds : 0);
+    uint16_t *k_t = ds_t + 32 * kDsStride;
+    f32x4 dqa[DQ ? MT : 1][2];
+#pragma unroll
+    for (int t = 0; t < (DQ ? MT : 1); ++t)
+#pragma unroll
+        for (int jb = 0; jb < 2; ++jb) dqa[t][jb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int c16 = lane & 15, g16 = lane >> 4;
+
     int tile = blockIdx.x * 8 + wave;
     bf16x8 kt[KS], vt[KS], gt[KS], ktn[KS], vtn[KS], gtn[KS];
     if (tile < tiles) {
@@ -1511,6 +1536,25 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
 #pragma unroll
         for (int hv = 0; hv < HV; ++hv) { acc1[hv] = splat16(0.f); acc2[hv] = splat16(0.f); }
 
+        // fused dQ: K^T of this token tile as the A operand of the 16x16x32 product (row = dd = lane % 16,
+        // tokens 8 (lane / 16) .. + 7), through the wave's LDS tile; rows of tokens past N are zero
+        bf16x8 k_op = zero_operand();
+        if constexpr (DQ) {
+            const u32x4 w = (n < N) ? to_bf16_row<F>(__builtin_bit_cast(u32x4, kt[0])) : __builtin_bit_cast(u32x4, zero_operand());
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                k_t[(8 * hh + 2 * e) * kVtStride + l32] = (uint16_t)(w[e] & 0xffffu);
+                k_t[(8 * hh + 2 * e + 1) * kVtStride + l32] = (uint16_t)(w[e] >> 16);
+            }
+            compiler_fence();
+            const uint16_t *rowp = k_t + c16 * kVtStride + 8 * g16;
+            const u32x2 lo2 = *reinterpret_cast<const u32x2 *>(rowp);
+            const u32x2 hi2 = *reinterpret_cast<const u32x2 *>(rowp + 4);
+            u32x4 ka;
+            ka[0] = lo2[0]; ka[1] = lo2[1]; ka[2] = hi2[0]; ka[3] = hi2[1];
+            k_op = as_bf16x8(ka);
+        }
+
         // Score products of latent tile t (minus lse_enc2 / minus lse_dec2): 2*KS + 2 MFMAs.
         auto scores = [&](int t, f32x16 &s1, f32x16 &s2) {
             f32x16 x = splat16(0.f);
@@ -1538,10 +1582,6 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
             for (int ks = 0; ks < KS; ++ks) {
                 av = mfma(image(t, 2 * KS + ks), vt[ks], av);
                 cv = mfma(image(t, 3 * KS + ks), gc[ks], cv);
-                if constexpr (LO2) {
-                    av = mfma(image(t, 4 * KS + ks), vt[ks], av);
-                    cv = mfma(image(t, 5 * KS + ks), gt[ks], cv);
-                }
             }
             if constexpr (PIPE) {
                 if (t + 1 < MT) scores(t + 1, s1n, s2n);
@@ -1572,6 +1612,24 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                 acc2[hv] = mfma(rw[(1 * HV + hv) * 2 + 0], as_bf16x8(d0), acc2[hv]);
                 acc2[hv] = mfma(rw[(1 * HV + hv) * 2 + 1], as_bf16x8(d1), acc2[hv]);
             }
+            if constexpr (DQ) {
+                // dS (this lane: token l32, latents 8 (r/4) + 4 hh + r%4 for r = 0..15) -> LDS [latent][token]
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int ma = 8 * (i / 2) + 4 * hh + 2 * (i % 2);          // latent of the low half of d0[i]
+                    ds_t[ma * kDsStride + l32] = (uint16_t)(d0[i] & 0xffffu);
+                    ds_t[(ma + 1) * kDsStride + l32] = (uint16_t)(d0[i] >> 16);
+                    ds_t[(16 + ma) * kDsStride + l32] = (uint16_t)(d1[i] & 0xffffu);
+                    ds_t[(16 + ma + 1) * kDsStride + l32] = (uint16_t)(d1[i] >> 16);
+                }
+                compiler_fence();
+#pragma unroll
+                for (int jb = 0; jb < 2; ++jb) {
+                    const u32x4 bop = *reinterpret_cast<const u32x4 *>(ds_t + (16 * jb + c16) * kDsStride + 8 * g16);
+                    dqa[t][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k_op, as_bf16x8(bop), dqa[t][jb], 0, 0, 0);
+                }
+                compiler_fence();
+            }
             sched_fence();
         };
         {
@@ -1579,6 +1637,12 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
             if constexpr (PIPE) scores(0, sa1, sa2);
             if constexpr (MT == 1) {
                 tile_step(0, sa1, sa2, sb1, sb2);
+            } else if constexpr (DQ) {   // unrolled: the dQ accumulators are indexed by the latent tile
+#pragma unroll
+                for (int t = 0; t < MT; t += 2) {
+                    tile_step(t, sa1, sa2, sb1, sb2);
+                    tile_step(t + 1, sb1, sb2, sa1, sa2);
+                }
             } else {
 #pragma unroll 1
                 for (int t = 0; t < MT; t += 2) {
@@ -1632,6 +1696,35 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
         }
 #pragma unroll
         for (int s = 0; s < KS; ++s) { kt[s] = ktn[s]; vt[s] = v_operand(vtn[s]); gt[s] = to_bf16(gtn[s]); }
+    }
+
+    if constexpr (DQ) {
+        // The eight waves add their dQ partials in wave order (fixed, so the bits are reproducible) in a
+        // [32*MT][16] fp32 buffer that reuses the image memory, then the workgroup stores its slot.
+        float *red = reinterpret_cast<float *>(img);
+        for (int w = 0; w < 8; ++w) {
+            __syncthreads();   // first pass: every wave is done with the images
+            if (wave == w) {
+#pragma unroll
+                for (int t = 0; t < MT; ++t)
+#pragma unroll
+                    for (int jb = 0; jb < 2; ++jb) {
+                        float4 *cell = reinterpret_cast<float4 *>(red + (32 * t + 16 * jb + c16) * 16 + 4 * g16);
+                        float4 x = make_float4(dqa[t][jb][0], dqa[t][jb][1], dqa[t][jb][2], dqa[t][jb][3]);
+                        if (w > 0) {
+                            const float4 o = *cell;
+                            x.x += o.x; x.y += o.y; x.z += o.z; x.w += o.w;
+                        }
+                        *cell = x;
+                    }
+            }
+        }
+        __syncthreads();
+        const int mleft = Mtot - m0;
+        float *out = dq_part + (((size_t)bh * gridDim.x + blockIdx.x) * Mtot + m0) * 16;
+        for (int i = tid; i < 32 * MT * 4; i += 512) {      // float4 pieces: latent i / 4, columns 4 (i % 4) ..
+            if (i / 4 < mleft) *reinterpret_cast<float4 *>(out + (size_t)i * 4) = *reinterpret_cast<const float4 *>(red + (size_t)i * 4);
+        }
     }
 }
 
@@ -1942,22 +2035,42 @@ bool mfma_dkdv_supported(const flare_shape &s)
     return mfma_supported(s);
 }
 
-int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy, const float *z,
-              const float *lse_enc, const float *dz, const float *eps, const float *lse_dec2, const float *delta,
-              float ld_mul, const int *plan, bool one_exp, void *dk, void *dv, float *acc32, int m0, float scale,
-              hipStream_t stream)
+// workgroups per (b,h) of the dK/dV kernel (= dQ partial slots per (b,h) when it also forms dQ)
+int mfma_dkdv_blocks(const flare_shape &s)
 {
     const int BH = s.B * s.H;
     const int tiles = (s.N + 31) / 32;
     int blocks = (256 + BH - 1) / BH;                 // one 8-wave workgroup per CU
     if (blocks > (tiles + 7) / 8) blocks = (tiles + 7) / 8;
-    const dim3 grid(blocks, BH);
+    return blocks;
+}
+
+// The dK/dV kernel can form the dQ partials as well (one pass over the scores for all three gradients);
+// written for d = 16.  FLARE_BWD_SEPARATE_DQ=1 in the environment keeps the separate dQ kernel (a switch
+// for measurements; read at every call).
+bool mfma_dq_fused(const flare_shape &s)
+{
+    if (!mfma_supported(s) || s.d != 16) return false;
+    const char *e = getenv("FLARE_BWD_SEPARATE_DQ");
+    return !(e != nullptr && e[0] != '\0' && e[0] != '0');
+}
+
+int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy, const float *z,
+              const float *lse_enc, const float *dz, const float *eps, const float *lse_dec2, const float *delta,
+              float ld_mul, const int *plan, bool one_exp, void *dk, void *dv, float *acc32, float *dq_part, int m0,
+              float scale, hipStream_t stream)
+{
+    // dq_part != NULL: also write the dQ partials (mfma_dq_fused(s) must hold), slot layout
+    // [(b*h) * mfma_dkdv_blocks(s) + block][M][d]
+    const int BH = s.B * s.H;
+    const dim3 grid(mfma_dkdv_blocks(s), BH);
+    const bool fuse = dq_part != nullptr;
+    if (fuse && !mfma_dq_fused(s)) return FLARE_EUNSUPPORTED;
     const float c2 = scale * kLog2e;
     const int MT = lat_eff(s.M) == 192 ? 8 : lat_eff(s.M) / 32;   // instantiated for 1, 2, 4, 8 tiles
     const int pd = padded_dim(s.d);
-    const bool lo2 = false;   // see the kernel's comment on LO2
     const int KS = pd / 16, HV = pd / 16;
-    const size_t lds = (size_t)MT * ((lo2 ? 6 : 4) * KS + 1 + 4 * HV) * 1024;
+    const size_t lds = (size_t)MT * (4 * KS + 1 + 4 * HV) * 1024 + (fuse ? 8 * kFusedWaveLds * 2 : 0);
     const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *vv = (const bf16_t *)v, *gg = (const bf16_t *)dy;
     const bool f16 = s.dtype == FLARE_F16;
     LaunchTimer t(one_exp ? KID_BWD_DKDV : KID_BWD_DKDV_2EXP, stream);
@@ -1971,8 +2084,8 @@ int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v,
                                 (int)lds) != hipSuccess)                                                         \
             return FLARE_ELAUNCH;                                                                                \
         kern<<<grid, 512, lds, stream>>>(qq, kk, vv, gg, z, lse_enc, dz, eps, lse_dec2, delta, ld_mul, plan,     \
-                                         (bf16_t *)dk, (bf16_t *)dv, acc32, tok_stride(s), s.H, s.N, s.M, m0,    \
-                                         c2, scale);                                                             \
+                                         (bf16_t *)dk, (bf16_t *)dv, acc32, dq_part, tok_stride(s), s.H, s.N,    \
+                                         s.M, m0, c2, scale);                                                    \
     } while (0)
 #define FLARE_DKDV_MT(DD)                              \
     switch (MT) {                                      \
@@ -1986,6 +2099,14 @@ int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v,
         FLARE_DKDV_MT(4)
     } else if (s.d == 8) {
         FLARE_DKDV_MT(8)
+    } else if (s.d == 16 && fuse) {
+        switch (MT) {
+            case 1: FLARE_DKDV(16, 1, true); break;
+            case 2: FLARE_DKDV(16, 2, true); break;
+            case 4: FLARE_DKDV(16, 4, true); break;
+            case 8: FLARE_DKDV(16, 8, true); break;
+            default: return FLARE_EUNSUPPORTED;
+        }
     } else if (s.d == 16) {
         FLARE_DKDV_MT(16)
     } else {

@@ -610,6 +610,7 @@ inline int bwd_slots(const flare_shape &s, const ValuPlan &plan)
     if (mfma_supported(s)) {
         mf = mfma_plan(s).parts;
         if (mfma_dq_parts(s) > mf) mf = mfma_dq_parts(s);
+        if (mfma_dkdv_blocks(s) > mf) mf = mfma_dkdv_blocks(s);
     }
     return plan.bwd.chunks > mf ? plan.bwd.chunks : mf;
 }
@@ -706,7 +707,10 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     }
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     int dq_parts = plan.bwd.chunks;
-    if (mf) {
+    const bool dq_fused = mf && mfma_dkdv_supported(s) && mfma_dq_fused(s);   // dQ comes out of the dK/dV kernel
+    if (dq_fused) {
+        dq_parts = mfma_dkdv_blocks(s);
+    } else if (mf) {
         dq_parts = mfma_dq_parts(s);
         for (int one = 1; one >= 0; --one) {   // each (b,h) slice is computed by exactly one of the two
             const int rc = mfma_dq_partial(s, q, k, v, dy, z, lse_enc, w.dz, w.eps, ld, w.delta, ld_mul, w.plan,
@@ -720,7 +724,7 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
                                                                        plan.bwd.chunk_len, plan.bwd.chunks, c2);
     }
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
-    {
+    auto reduce_dq = [&]() -> int {
         LaunchTimer t(KID_BWD_DQ_REDUCE, stream);
         // shared latents: one gradient for all heads, summed over (b, h) in that fixed order
         if (s.shared_latents)
@@ -728,17 +732,26 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
         else
             dq_reduce_kernel<D><<<dim3((s.M + 15) / 16, s.H), 256, 0, stream>>>(w.part, dq, s.B, s.H, s.M, dq_parts,
                                                                                 scale);
+        return check_launch();
+    };
+    if (!dq_fused) {
+        const int rc = reduce_dq();
+        if (rc != FLARE_OK) return rc;
     }
-    if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     if (mf && mfma_dkdv_supported(s)) {
         const bool chunked = mfma_dkdv_acc_bytes(s) != 0;   // more than 256 latents: one pass per chunk
         for (int m0 = 0; m0 < s.M; m0 += 256)
             for (int one = 1; one >= 0; --one) {
                 const int rc = mfma_dkdv(s, q, k, v, dy, z, lse_enc, w.dz, w.eps, ld, w.delta, ld_mul, w.plan,
-                                         one != 0, dk, dv, chunked ? w.acc32 : nullptr, m0, scale, stream);
+                                         one != 0, dk, dv, chunked ? w.acc32 : nullptr, dq_fused ? w.part : nullptr,
+                                         m0, scale, stream);
                 if (rc != FLARE_OK) return rc;
             }
-        return chunked ? mfma_dkdv_finish(s, w.acc32, dk, dv, stream) : FLARE_OK;
+        if (chunked) {
+            const int rc = mfma_dkdv_finish(s, w.acc32, dk, dv, stream);
+            if (rc != FLARE_OK) return rc;
+        }
+        return dq_fused ? reduce_dq() : FLARE_OK;
     }
     {
         LaunchTimer t(KID_BWD_DKDV, stream);
