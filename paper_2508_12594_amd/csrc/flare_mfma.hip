@@ -1298,7 +1298,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     bf16_t *__restrict__ dv, float *__restrict__ acc32, float *__restrict__ dq_part, TokStride ts, int H, int N,
     int Mtot, int m0, float c2, float scale)
 {
-    // DQ (d = 16 only): the kernel also forms the dQ partials, so that the scores, a, c and dS of a tile
+    // DQ (d <= 16): the kernel also forms the dQ partials, so that the scores, a, c and dS of a tile
     // pair are computed once for all three gradients.  dS of a tile reaches the dQ product transposed
     // (contraction over the tokens) through a wave-private LDS tile, and that product is
     //     dQ^T[dd][m] += K^T[dd][n] dS^T[n][m]     with v_mfma_f32_16x16x32_bf16
@@ -1314,7 +1314,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     constexpr int D = padded_dim(DR);
     constexpr int KS = D / 16;
     constexpr int HV = D / 16;
-    static_assert(!DQ || DR == 16, "the fused dQ product is written for d = 16");
+    static_assert(!DQ || DR <= 16, "the fused dQ product is written for d <= 16 (16 output rows)");
     constexpr int NA = 4 * KS + 1;              // A-type images per latent tile (the last one: corrections)
     constexpr int NR = 4 * HV;                  // row images per latent tile (RW1, RW2) x 2 k-steps
     constexpr int PER_TILE = NA + NR;
@@ -1324,6 +1324,13 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     // (against ones in the V operand), slots 8-10 of the Z image = u, u, u lo or 1, 1 (against -delta in
     // the dY operand).  The q' lo image and the a / c parts of the correction image are then unused.
     constexpr bool PACK = pack_dim(DR);
+    // PACK with DQ: the upper half of the Z image carries the lo term of Z instead (dY rows repeated in both
+    // lane halves), as the separate dQ kernel has it at d <= 8, and -delta comes in through the correction
+    // image as at d = 16: dQ sums dS over the tokens of one latent, and with so few terms per dot product
+    // the rounding of Z_m showed (9.7e-3 against 2.6e-3 on a 1500-token case).  The host uses this
+    // instantiation only with at least 32 latents: with very few, c - delta must cancel against a delta
+    // that the decode formed from the rounded Z alone.
+    constexpr bool ZPACK = PACK && DQ;
     extern __shared__ __attribute__((aligned(16))) u32x4 img[];   // [MT][PER_TILE][64 lanes]
 
     const int tid = threadIdx.x;
@@ -1388,7 +1395,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                     for (int i = 0; i < 4; ++i) { x[2 * i] = elem_lo<F>(raw[i]) * c2; x[2 * i + 1] = elem_hi<F>(raw[i]) * c2; }
                 } else {
                     const bool is_z = kind >= 3;
-                    row8_f32<DR>((is_z ? zb : dzb) + (size_t)m * DR, d0, x);
+                    row8_f32<DR>((is_z ? zb : dzb) + (size_t)m * DR, (ZPACK && is_z) ? 0 : d0, x);
                     const float um = (ONE && is_z) ? fast_exp2(leb[m] * kLog2e - kap) : 1.f;
 #pragma unroll
                     for (int i = 0; i < 8; ++i) x[i] *= um;
@@ -1397,7 +1404,8 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
 #pragma unroll
                     for (int i = 0; i < 8; ++i) x[i] = 0.f;
                 }
-                const bool want_lo = (kind == 1 || kind >= 4 || (PACK && kind == 0 && hf == 1));
+                const bool want_lo = (kind == 1 || kind >= 4 || (PACK && kind == 0 && hf == 1) ||
+                                      (ZPACK && kind == 3 && hf == 1));
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     uint32_t a, b;
@@ -1417,7 +1425,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                     w[i] = a | (b << 16);
                 }
                 if (PACK && hf == 1 && kind == 2 && real) w[0] = split_bf16_pair(-eb[m]);   // slots 8,9 := -eps
-                if (PACK && hf == 1 && kind == 3 && real) {                          // slots 8,9,10 := u, u, u lo / 1, 1
+                if (PACK && !ZPACK && hf == 1 && kind == 3 && real) {                // slots 8,9,10 := u, u, u lo / 1, 1
                     if constexpr (ONE) {
                         const uint32_t us = split_bf16_pair(fast_exp2(leb[m] * kLog2e - kap));
                         w[0] = (us & 0xffffu) | (us << 16);
@@ -1486,6 +1494,12 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     // fused dQ: wave-private LDS tiles and the accumulators dQ^T[dd = 4 (lane / 16) + r][m = 32 t + 16 jb + lane % 16]
     uint16_t *ds_t = reinterpret_cast<uint16_t *>(img + MT * PER_TILE * 64) + (DQ ? wave * kFusedWaveLds : 0);
     uint16_t *k_t = ds_t + 32 * kDsStride;
+    if constexpr (DQ && PACK) {   // K^T rows 8-15 are never written at d <= 8: zero (the output rows 8-15 are dropped)
+        if (lane < kVtStride) {
+#pragma unroll
+            for (int r = 8; r < 16; ++r) k_t[r * kVtStride + lane] = 0;
+        }
+    }
     f32x4 dqa[DQ ? MT : 1][2];
 #pragma unroll
     for (int t = 0; t < (DQ ? MT : 1); ++t)
@@ -1498,7 +1512,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     if (tile < tiles) {
         load_cols(kb, tile, kt, true);
         load_cols(vb, tile, vt, false);
-        load_cols(gb, tile, gt, false);
+        load_cols(gb, tile, gt, ZPACK);
 #pragma unroll
         for (int s = 0; s < KS; ++s) { vt[s] = v_operand(vt[s]); gt[s] = to_bf16(gt[s]); }
     }
@@ -1507,7 +1521,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
         const int tn = (tile + stride < tiles) ? tile + stride : tile;
         load_cols(kb, tn, ktn, true);
         load_cols(vb, tn, vtn, false);
-        load_cols(gb, tn, gtn, false);
+        load_cols(gb, tn, gtn, ZPACK);
         const size_t row = (size_t)min(n, N - 1);
         const float nld = -lb[row] * ld_mul, dl = db[row];
         const float wn = ONE ? fast_exp2(kap + nld) : 0.f;
@@ -1526,7 +1540,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
         bf16x8 gc[KS];   // dY operand of the c product; PACK: slots 8,9,10 := -delta hi, lo, hi
 #pragma unroll
         for (int s = 0; s < KS; ++s) gc[s] = gt[s];
-        if constexpr (PACK) {
+        if constexpr (PACK && !ZPACK) {
             u32x4 w = __builtin_bit_cast(u32x4, gt[0]);
             if (!lower) { w[0] = ds_; w[1] = ONE ? (ds_ & 0xffffu) : 0u; }
             gc[0] = as_bf16x8(w);
@@ -1541,10 +1555,12 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
         bf16x8 k_op = zero_operand();
         if constexpr (DQ) {
             const u32x4 w = (n < N) ? to_bf16_row<F>(__builtin_bit_cast(u32x4, kt[0])) : __builtin_bit_cast(u32x4, zero_operand());
+            if (!(PACK && hh)) {   // d <= 8: the upper lane half holds a copy of the same elements
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                k_t[(8 * hh + 2 * e) * kVtStride + l32] = (uint16_t)(w[e] & 0xffffu);
-                k_t[(8 * hh + 2 * e + 1) * kVtStride + l32] = (uint16_t)(w[e] >> 16);
+                for (int e = 0; e < 4; ++e) {
+                    k_t[(8 * hh + 2 * e) * kVtStride + l32] = (uint16_t)(w[e] & 0xffffu);
+                    k_t[(8 * hh + 2 * e + 1) * kVtStride + l32] = (uint16_t)(w[e] >> 16);
+                }
             }
             compiler_fence();
             const uint16_t *rowp = k_t + c16 * kVtStride + 8 * g16;
@@ -1574,10 +1590,8 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
         auto tile_step = [&](int t, f32x16 &s1, f32x16 &s2, f32x16 &s1n, f32x16 &s2n) {
             if constexpr (!PIPE) scores(t, s1, s2);   // not enough registers at d = 32: no look-ahead
             f32x16 av = splat16(0.f), cv = splat16(0.f);
-            if constexpr (!PACK) {
-                av = mfma(image(t, NA - 1), ones_eps, av);
-                cv = mfma(image(t, NA - 1), g_aug, cv);
-            }
+            if constexpr (!PACK) av = mfma(image(t, NA - 1), ones_eps, av);
+            if constexpr (!PACK || ZPACK) cv = mfma(image(t, NA - 1), g_aug, cv);
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 av = mfma(image(t, 2 * KS + ks), vt[ks], av);
@@ -1721,9 +1735,13 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
         }
         __syncthreads();
         const int mleft = Mtot - m0;
-        float *out = dq_part + (((size_t)bh * gridDim.x + blockIdx.x) * Mtot + m0) * 16;
-        for (int i = tid; i < 32 * MT * 4; i += 512) {      // float4 pieces: latent i / 4, columns 4 (i % 4) ..
-            if (i / 4 < mleft) *reinterpret_cast<float4 *>(out + (size_t)i * 4) = *reinterpret_cast<const float4 *>(red + (size_t)i * 4);
+        float *out = dq_part + (((size_t)bh * gridDim.x + blockIdx.x) * Mtot + m0) * DR;
+        constexpr int PCS = DR / 4;                             // float4 pieces of a DR-element row
+        for (int i = tid; i < 32 * MT * PCS; i += 512) {        // latent i / PCS, columns 4 (i % PCS) ..
+            const int lat = i / PCS, pc = i % PCS;
+            if (lat < mleft)
+                *reinterpret_cast<float4 *>(out + (size_t)lat * DR + 4 * pc) =
+                    *reinterpret_cast<const float4 *>(red + (size_t)lat * 16 + 4 * pc);
         }
     }
 }
@@ -2046,11 +2064,15 @@ int mfma_dkdv_blocks(const flare_shape &s)
 }
 
 // The dK/dV kernel can form the dQ partials as well (one pass over the scores for all three gradients);
-// written for d = 16.  FLARE_BWD_SEPARATE_DQ=1 in the environment keeps the separate dQ kernel (a switch
+// written for d <= 16 and used at d = 8 and 16.  At d = 4 the separate dQ kernel stays: it carries the lo
+// term of Z in its c chain, for which the fused kernel has no free slots next to the corrections at d = 4,
+// and with four-term dot products that term is worth a factor 4 in dQ's error (measured 3.3e-2 against
+// 8.6e-3 on a 333-token mesh case).  FLARE_BWD_SEPARATE_DQ=1 in the environment keeps the separate dQ kernel (a switch
 // for measurements; read at every call).
 bool mfma_dq_fused(const flare_shape &s)
 {
-    if (!mfma_supported(s) || s.d != 16) return false;
+    if (!mfma_supported(s) || (s.d != 8 && s.d != 16)) return false;
+    if (s.d == 8 && s.M < 32) return false;   // see ZPACK in the kernel
     const char *e = getenv("FLARE_BWD_SEPARATE_DQ");
     return !(e != nullptr && e[0] != '\0' && e[0] != '0');
 }
@@ -2095,18 +2117,22 @@ int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v,
         case 8: FLARE_DKDV(DD, 8, false); break;       \
         default: return FLARE_EUNSUPPORTED;            \
     }
-    if (s.d == 4) {
+#define FLARE_DKDV_MT_DQ(DD)                           \
+    switch (MT) {                                      \
+        case 1: FLARE_DKDV(DD, 1, true); break;        \
+        case 2: FLARE_DKDV(DD, 2, true); break;        \
+        case 4: FLARE_DKDV(DD, 4, true); break;        \
+        case 8: FLARE_DKDV(DD, 8, true); break;        \
+        default: return FLARE_EUNSUPPORTED;            \
+    }
+    if (s.d == 8 && fuse) {
+        FLARE_DKDV_MT_DQ(8)
+    } else if (s.d == 16 && fuse) {
+        FLARE_DKDV_MT_DQ(16)
+    } else if (s.d == 4) {
         FLARE_DKDV_MT(4)
     } else if (s.d == 8) {
         FLARE_DKDV_MT(8)
-    } else if (s.d == 16 && fuse) {
-        switch (MT) {
-            case 1: FLARE_DKDV(16, 1, true); break;
-            case 2: FLARE_DKDV(16, 2, true); break;
-            case 4: FLARE_DKDV(16, 4, true); break;
-            case 8: FLARE_DKDV(16, 8, true); break;
-            default: return FLARE_EUNSUPPORTED;
-        }
     } else if (s.d == 16) {
         FLARE_DKDV_MT(16)
     } else {
@@ -2118,6 +2144,8 @@ int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v,
             default: return FLARE_EUNSUPPORTED;
         }
     }
+#undef FLARE_DKDV_MT_DQ
+#undef FLARE_DKDV_MT
 #undef FLARE_DKDV
     return check_launch();
 }
