@@ -320,18 +320,19 @@ __device__ __forceinline__ void compiler_fence() { asm volatile("" ::: "memory")
 // MODE 0 writes y and, when lse_dec2 is not NULL, log sum_m exp(S[m][n]) (natural log) there.
 // MODE 1 (first step of the backward when nothing was saved) writes per token
 //   lse_dec2[n] = log2 sum_m 2^S2[m][n]   and   delta[n] = <dY_n, Y_n>   (Y_n kept in fp32).
-// MASKED: some of the 32*MT latents are padding (instantiated apart so that the common case carries no
-// mask code between its matrix and vector instructions).
-template <int DR, int MT, bool PRE, int MINB, int MODE, bool F, bool MASKED>
+template <int DR, int MT, bool PRE, int MINB, int MODE, bool F>
 __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const float *__restrict__ z,
     bf16_t *__restrict__ y, const bf16_t *__restrict__ dy, float *__restrict__ lse_dec2,
     float *__restrict__ delta, TokStride ts, TokStride ts_y, int H, int N, int Mtot, int m0, float c2)
 {
-    // The kernel works on the latents m0 .. m0 + M of the head's Mtot (M = 32*MT of them; those at or
-    // beyond Mtot are padding and get weight zero); with more than one chunk its outputs are one chunk's
-    // partial result (y normalised within the chunk, lse_dec of the chunk) that decode_merge_kernel
-    // combines.  ts_y: where the rows of y go.
+    // The kernel works on the latents m0 .. m0 + M of the head's Mtot (M = 32*MT of them); with more than
+    // one chunk its outputs are one chunk's partial result (y normalised within the chunk, lse_dec of the
+    // chunk) that decode_merge_kernel combines.  ts_y: where the rows of y go.
+    // Latents at or beyond Mtot are padding and cost no mask code in the loops: a padding latent gets the
+    // queries of the last real one (the clamped load), so its score never exceeds the real maximum and
+    // its weight is at most 1, and its row of Zaug -- the Z values and the 1 that feeds the denominator --
+    // is zero, so that weight multiplies zeros only.
     constexpr int D = padded_dim(DR);
     constexpr int KS = D / 16;   // k-steps of the score product
     constexpr int HV = D / 16;   // 16-wide column groups of Z, each with its own ones row
@@ -348,10 +349,6 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
         const int m = m0 + 32 * t + l32;
         load_q_operand<DR, PRE, F, PACK>(q + (size_t)h * ts.sq + (size_t)min(m, Mtot - 1) * DR, hh, c2, flip, qh[t],
                                          ql[t]);
-        if (m >= Mtot) {
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) { qh[t][ks] = zero_operand(); ql[t][ks] = zero_operand(); }
-        }
     }
     const int mleft = Mtot - m0;   // real latents from m0 on (may exceed the 32*MT this kernel covers)
 
@@ -377,8 +374,9 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
                         const int lb = 32 * (s / 2) + perm_index(s % 2, hh, i + 1);
                         a = la < mleft ? zb[(size_t)la * DR + 16 * hv + l32] : 0.f;
                         b = lb < mleft ? zb[(size_t)lb * DR + 16 * hv + l32] : 0.f;
-                    } else {
-                        a = b = (l32 == 16) ? 1.f : 0.f;
+                    } else {   // row 16: ones (for the real latents), the rest: zero
+                        a = (l32 == 16 && 32 * (s / 2) + perm_index(s % 2, hh, i) < mleft) ? 1.f : 0.f;
+                        b = (l32 == 16 && 32 * (s / 2) + perm_index(s % 2, hh, i + 1) < mleft) ? 1.f : 0.f;
                     }
                     w[i / 2] = rne_bf16(a) | (rne_bf16(b) << 16);
                 }
@@ -413,15 +411,6 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
             for (int s = 0; s < KS; ++s)
                 ktn[s] = as_bf16x8(row8_bf16<DR>(kb + tok_off(ts, nld), PACK ? 0 : (D / 2) * hh + 8 * s));
         }
-        // scores of padding latents (tile t, register r holds latent 32t + 8(r/4) + 4hh + r%4) := -inf
-        auto mask_padding = [&](f32x16 &sc, int t) {
-            if constexpr (!MASKED) return;
-            if (32 * (t + 1) > mleft) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    if (32 * t + 8 * (r / 4) + 4 * hh + (r % 4) >= mleft) sc[r] = -INFINITY;
-            }
-        };
         auto qk_hi = [&](int t) {
             f32x16 r = splat16(0.f);
 #pragma unroll
@@ -436,7 +425,6 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
         for (int t = 0; t < MT; ++t) {
             if (t + 1 < MT) s_next = qk_hi(t + 1);
             sched_fence();
-            mask_padding(s_cur, t);
             mx = max16(s_cur, mx);
             s_cur = s_next;
         }
@@ -478,7 +466,6 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
 #pragma unroll
                 for (int i = 0; i < 16; ++i) s_cur[i] = fmaf(s_cur[i], ac2, -b2);
             }
-            mask_padding(s_cur, t);
             bf16x8 p0, p1;
             exp_pack(s_cur, p0, p1);
 #pragma unroll
@@ -2285,18 +2272,13 @@ static int launch_decode_family(const flare_shape &s, const void *q, const void 
     bf16_t *yy = (bf16_t *)y;
     LaunchTimer t(MODE == 0 ? KID_DECODE : KID_BWD_TOKEN_STATS, stream);
     const bool f16 = s.dtype == FLARE_F16;
-    const bool masked = s.M - m0 < Mc;   // padding latents in this launch
 #define FLARE_DEC_ARGS qq, kk, z, yy, gg, lse_dec2, delta, tok_stride(s), ts_y, s.H, s.N, s.M, m0, c2
 #define FLARE_DEC(DD, MTT, PREE, MINB)                                                                          \
     do {                                                                                                        \
-        if (f16 && masked)                                                                                      \
-            decode_mfma_kernel<DD, MTT, PREE, MINB, MODE, true, true><<<grid, 256, 0, stream>>>(FLARE_DEC_ARGS); \
-        else if (f16)                                                                                           \
-            decode_mfma_kernel<DD, MTT, PREE, MINB, MODE, true, false><<<grid, 256, 0, stream>>>(FLARE_DEC_ARGS); \
-        else if (masked)                                                                                        \
-            decode_mfma_kernel<DD, MTT, PREE, MINB, MODE, false, true><<<grid, 256, 0, stream>>>(FLARE_DEC_ARGS); \
+        if (f16)                                                                                                \
+            decode_mfma_kernel<DD, MTT, PREE, MINB, MODE, true><<<grid, 256, 0, stream>>>(FLARE_DEC_ARGS);      \
         else                                                                                                    \
-            decode_mfma_kernel<DD, MTT, PREE, MINB, MODE, false, false><<<grid, 256, 0, stream>>>(FLARE_DEC_ARGS); \
+            decode_mfma_kernel<DD, MTT, PREE, MINB, MODE, false><<<grid, 256, 0, stream>>>(FLARE_DEC_ARGS);     \
     } while (0)
     const int MT = Mc / 32;
 #define FLARE_DEC_MT(DD)                               \
