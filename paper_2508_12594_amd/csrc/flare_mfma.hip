@@ -1,14 +1,14 @@
 // Matrix-core (MFMA) kernels of the FLARE mixer for bf16 and fp16 storage on gfx950.
 //
-// Both kernels are built from v_mfma_f32_32x32x16_bf16 and keep the M x N weights in
+// The kernels are built from v_mfma_f32_32x32x16_bf16 and keep the M x N weights in
 // registers only.  The softmax work per score is one v_exp_f32, half a v_cvt_pk_bf16_f32 and
 // half a v_max3_f32: the score MFMAs already deliver  S2 - stabiliser  because
 //   * q is pre-multiplied by scale*log2(e) and split into two bf16 terms (hi + lo), so the
 //     product is exact to ~2^-17 and the exponential is a bare 2^x;
-//   * the stabiliser rides in the contraction: slot 0 of the lo product carries
-//     (1) x (-stabiliser) instead of q_lo[0] x k[0], a term of relative size 2^-9 of one of the
-//     d products.  The stabiliser is therefore kept bf16-representable; any value near the
-//     maximum is a valid stabiliser.
+//   * the stabiliser rides in the matrix instruction: as the C operand the score products start
+//     from (decode: one splat of -max per token tile), or in a k-step of its own whose operands
+//     hold it as a hi + lo pair against ones (encode, and the log-sum-exp normalisers, -eps and
+//     -delta of the backward).
 // The probabilities are rounded to bf16 once and feed the second MFMA straight from the
 // accumulator layout: the contraction index of the second product (tokens in the encode,
 // latents in the decode) is order-free, so the value operand is simply loaded in the
