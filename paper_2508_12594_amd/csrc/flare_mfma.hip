@@ -1517,11 +1517,16 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
         wb[0] = 0u; wb[2] = 0u; wb[3] = 0u;
         wb[1] = lower ? split_pair<F>(nld) : 0u;             // slots 2,3 := -lse_dec2[n]
         const bf16x8 kt_a = ones_s, kt_b = as_bf16x8(wb);    // slots 0,1 := 1 picks -lse_enc2
+        // Token side of the correction k-step(s).  Two exponentials: g_aug picks -delta for the c chain
+        // (slots 10,11 against the image's ones) and ones_eps picks -eps for the a chain.  One exponential:
+        // dS = P (a + w c), and w[n] is this lane's scalar, so ONE product serves both chains: slots 8,9 = 1
+        // pick -eps and slots 4,5,6 = -w delta (hi, lo, hi) meet u (hi, hi, lo); the a chain starts from
+        // it and the c chain from zero.
         u32x4 wg;
-        const uint32_t ds_ = split_bf16_pair(-dl);
-        wg[0] = 0u;
+        const uint32_t ds_ = split_bf16_pair(ONE ? -dl * wn : -dl);
+        wg[0] = (ONE && !lower && !PACK) ? 0x3f803f80u : 0u;
         wg[1] = (!ONE && !lower) ? ds_ : 0u;                 // two exponentials: slots 10,11 := -delta (hi, lo)
-        wg[2] = (ONE && lower) ? ds_ : 0u;                   // one: slots 4,5,6 := -delta hi, lo, hi
+        wg[2] = (ONE && lower) ? ds_ : 0u;                   // one: slots 4,5,6 := -w delta hi, lo, hi
         wg[3] = (ONE && lower) ? (ds_ & 0xffffu) : 0u;
         const bf16x8 g_aug = as_bf16x8(wg);
         bf16x8 gc[KS];   // dY operand of the c product; PACK: slots 8,9,10 := -delta hi, lo, hi
@@ -1529,7 +1534,8 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
         for (int s = 0; s < KS; ++s) gc[s] = gt[s];
         if constexpr (PACK && !ZPACK) {
             u32x4 w = __builtin_bit_cast(u32x4, gt[0]);
-            if (!lower) { w[0] = ds_; w[1] = ONE ? (ds_ & 0xffffu) : 0u; }
+            const uint32_t dp_ = split_bf16_pair(-dl);   // here c keeps its own correction: -delta unscaled
+            if (!lower) { w[0] = dp_; w[1] = ONE ? (dp_ & 0xffffu) : 0u; }
             gc[0] = as_bf16x8(w);
         }
 
@@ -1577,8 +1583,12 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
         auto tile_step = [&](int t, f32x16 &s1, f32x16 &s2, f32x16 &s1n, f32x16 &s2n) {
             if constexpr (!PIPE) scores(t, s1, s2);   // not enough registers at d = 32: no look-ahead
             f32x16 av = splat16(0.f), cv = splat16(0.f);
-            if constexpr (!PACK) av = mfma(image(t, NA - 1), ones_eps, av);
-            if constexpr (!PACK || ZPACK) cv = mfma(image(t, NA - 1), g_aug, cv);
+            if constexpr (ONE) {
+                if constexpr (!PACK || ZPACK) av = mfma(image(t, NA - 1), g_aug, av);
+            } else {
+                if constexpr (!PACK) av = mfma(image(t, NA - 1), ones_eps, av);
+                if constexpr (!PACK || ZPACK) cv = mfma(image(t, NA - 1), g_aug, cv);
+            }
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 av = mfma(image(t, 2 * KS + ks), vt[ks], av);
