@@ -13,11 +13,11 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libflare.so")
-# source -> extra flags.  The matrix-core file never produces NaNs (masked scores are -inf and
-# are only ever compared, exponentiated or shifted by finite values), so it is compiled with
+# source -> extra flags.  The matrix-core files never produce NaNs (masked scores are -inf and
+# are only ever compared, exponentiated or shifted by finite values), so they are compiled with
 # -fno-honor-nans: fmaxf chains then become v_max3_f32 without canonicalising moves.
-SOURCES = {"flare_api.hip": [], "flare_valu.hip": [], "flare_mfma.hip": ["-fno-honor-nans"],
-           "flare_spectral.hip": []}
+SOURCES = {"flare_api.hip": [], "flare_valu.hip": [], "flare_mfma_fwd.hip": ["-fno-honor-nans"],
+           "flare_mfma_bwd.hip": ["-fno-honor-nans"], "flare_spectral.hip": []}
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -1,0 +1,1120 @@
+// Matrix-core kernels of the second backward pass: dQ, dK, dV (one kernel at d = 8 and 16, two otherwise),
+// the per-(b,h) choice between the one- and two-exponential variants, and the fp32 sums of latent chunks.
+// Operand layouts, helpers and the tile geometry are in flare_mfma_common.h.
+#include "flare_mfma_common.h"
+
+namespace flare {
+namespace {
+
+// ============================================================================================
+// Backward, dQ partials (latent-major, same wave geometry as the encode).  For its NB latent tiles
+// a wave keeps, as B operands (column = latent, contraction over d): q' hi and lo, dZ (bf16-exact: it is
+// rounded where it is merged, before eps is formed) and Z in bf16 (hi and, at d = 16, lo).  Per 32-token tile it streams K, V and dY as A operands
+// (row = token) and forms, all on the matrix cores,
+//     S2 - lse_enc2[m]   (one more k-step: -lse_enc2 as a hi+lo pair in slots 0,1, against 1,1)
+//     S2 - lse_dec2[n]   (likewise -lse_dec2 in slots 2,3 of the token-side operand)
+//     a[n][m] = <V_n, dZ_m> - eps[m]      (-eps rides in one more, otherwise empty, k-step)
+//     c[n][m] = <dY_n, Z_m> - delta[n]    (-delta likewise)
+// then dS^T = 2^(..) a + 2^(..) c in fp32, rounds it to bf16 and accumulates
+//     dQ^T[dd][m] += K^T[dd][n] dS^T[n][m]
+// with K^T read back from a wave-private, double-buffered LDS tile.  Masked tokens have both
+// exponents at -inf, so their dS is exactly zero.
+//
+// ONE = true is the variant with one exponential per score.  With kappa = max_m lse_enc2[m],
+//     R[n][m] = P[m][n] * u[m] * w[n],   u[m] = 2^(lse_enc2[m] - kappa),  w[n] = 2^(kappa - lse_dec2[n]),
+// so dS^T = P * (a + w[n] * u[m] c): u is folded into the Z operand (and multiplies delta in the
+// correction k-step), w[n] is a per-row factor that goes from the token's lane to the rows of
+// the accumulator layout through 128 bytes of LDS.  It is exact as long as u, w and P stay in
+// fp32 range wherever R matters, which bwd_plan_kernel guarantees per (b,h) (plan[bh] = 1);
+// otherwise the ONE = false variant runs.  Each variant returns at once when the plan names the other.
+// ============================================================================================
+template <int DR, int NB, int MINB, bool ONE, bool F>
+__global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
+    const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
+    const bf16_t *__restrict__ dy, const float *__restrict__ z, const float *__restrict__ lse_enc,
+    const float *__restrict__ dz, const float *__restrict__ eps, const float *__restrict__ lse_dec2,
+    const float *__restrict__ delta, float ld_mul, const int *__restrict__ plan, float *__restrict__ dq_part,
+    TokStride ts, int H, int N, int M, int chunk_len, int parts, int G, int TG, float c2)
+{
+    constexpr int D = padded_dim(DR);
+    constexpr int KS = D / 16;
+    constexpr int HV = D / 16;
+    constexpr int ROWS = D + 1;                 // K^T rows, then a row of zeros
+    // d <= 8: the upper half of the padded contraction carries what otherwise needs products of its own:
+    // q' lo and Z lo (K and dY rows repeated in both lane halves) and -eps (against ones in the V operand).
+    constexpr bool PACK = pack_dim(DR);
+    constexpr int BUF = ROWS * kVtStride;
+    __shared__ __attribute__((aligned(16))) uint16_t kt_all[4][2 * BUF];
+    __shared__ __attribute__((aligned(16))) float wl_all[ONE ? 4 : 1][2][32];   // w[n] of a token tile
+
+    const int lane = threadIdx.x & 63, l32 = lane & 31, hh = lane >> 5;
+    const int wave = threadIdx.x >> 6;
+    const int g = wave % G, tg = wave / G;
+    const int bh = blockIdx.y, h = bh % H, chunk = blockIdx.x;
+    if ((plan[bh] != 0) != ONE) return;         // the other variant owns this (b,h)
+    const bool lower = hh == 0;
+    uint16_t *lds = kt_all[wave];
+    float (*wl)[32] = wl_all[ONE ? wave : 0];
+    float kap = 0.f;
+    if constexpr (ONE) {
+        kap = -INFINITY;
+        for (int m = lane; m < M; m += 64) kap = fmaxf(kap, lse_enc[(size_t)bh * M + m] * kLog2e);
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) kap = fmaxf(kap, __shfl_xor(kap, off));
+    }
+    if (lane < kVtStride) {
+        lds[D * kVtStride + lane] = 0;
+        lds[BUF + D * kVtStride + lane] = 0;
+        if constexpr (PACK) {   // K^T rows 8-15 are never written: zero, so that the unused output rows stay finite
+#pragma unroll
+            for (int r = 8; r < 16; ++r) {
+                lds[r * kVtStride + lane] = 0;
+                lds[BUF + r * kVtStride + lane] = 0;
+            }
+        }
+    }
+
+    // ---- per-latent operands ----
+    const int lat0 = 32 * NB * (G * (int)blockIdx.z + g);   // a workgroup owns NB*G tiles of latents
+    constexpr bool LO2 = (D == 16);             // carry the lo term of Z as well (dZ arrives bf16-exact)
+    bf16x8 qh[NB][KS], ql[NB][KS], q_aug[NB], dzb[NB][KS], zb[NB][KS], zl[NB][KS], dz_aug[NB];
+    bf16x8 u_aug[ONE ? NB : 1];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        // padding latents (at or beyond M): every operand zero, loads clamped to the last real latent
+        const bool real = lat0 + 32 * b + l32 < M;
+        const int m = min(lat0 + 32 * b + l32, M - 1);
+        load_q_operand<DR, true, F, PACK>(q + (size_t)h * ts.sq + (size_t)m * DR, hh, c2, false, qh[b], ql[b]);
+        if (!real) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) { qh[b][ks] = zero_operand(); ql[b][ks] = zero_operand(); }
+        }
+        const float le2 = real ? lse_enc[(size_t)bh * M + m] * kLog2e : 0.f;
+        const float um = ONE ? fast_exp2(le2 - kap) : 1.f;   // folded into Z
+        if constexpr (ONE) {
+            const uint32_t us = split_bf16_pair(um);          // slots 0,1,2 := u hi, u hi, u lo
+            u32x4 wu;
+            wu[0] = lower ? ((us & 0xffffu) | (us << 16)) : 0u;
+            wu[1] = lower ? (us >> 16) : 0u;
+            wu[2] = 0u; wu[3] = 0u;
+            u_aug[b] = as_bf16x8(wu);
+        }
+        u32x4 wq;
+        wq[0] = lower ? split_pair<F>(-le2) : 0u;       // slots 0,1 := -lse_enc2 (hi + lo)
+        wq[1] = lower ? kOnePair<F> : 0u;               // slots 2,3 := 1
+        wq[2] = 0u; wq[3] = 0u;
+        q_aug[b] = as_bf16x8(wq);
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            float zr[8], dr[8];
+            row8_f32<DR>(z + ((size_t)bh * M + m) * DR, PACK ? 0 : (D / 2) * hh + 8 * s, zr);
+            row8_f32<DR>(dz + ((size_t)bh * M + m) * DR, (D / 2) * hh + 8 * s, dr);
+            if (!real) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) { zr[i] = 0.f; dr[i] = 0.f; }
+            }
+            u32x4 wz, wd, wzl;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float za = zr[2 * i] * um, zc = zr[2 * i + 1] * um;
+                const uint32_t z0 = rne_bf16(za), z1 = rne_bf16(zc);
+                const uint32_t d0 = rne_bf16(dr[2 * i]), d1 = rne_bf16(dr[2 * i + 1]);
+                wz[i] = z0 | (z1 << 16);
+                wd[i] = d0 | (d1 << 16);
+                wzl[i] = rne_bf16(za - __uint_as_float(z0 << 16)) |
+                         (rne_bf16(zc - __uint_as_float(z1 << 16)) << 16);
+            }
+            zb[b][s] = as_bf16x8((PACK && !lower) ? wzl : wz);
+            dzb[b][s] = as_bf16x8(wd);
+            zl[b][s] = as_bf16x8(wzl);
+        }
+        u32x4 we;
+        we[0] = (lower != PACK) ? split_bf16_pair(real ? -eps[(size_t)bh * M + m] : 0.f) : 0u;
+        we[1] = 0u; we[2] = 0u; we[3] = 0u;
+        dz_aug[b] = as_bf16x8(we);
+        if constexpr (PACK) {   // slots 8,9 of the dZ operand := -eps (the rest of its upper half is zero)
+            u32x4 wd = __builtin_bit_cast(u32x4, dzb[b][0]);
+            if (!lower) wd[0] = we[0];
+            dzb[b][0] = as_bf16x8(wd);
+        }
+    }
+    u32x4 w11;
+    w11[0] = lower ? 0x3f803f80u : 0u;
+    w11[1] = 0u; w11[2] = 0u; w11[3] = 0u;
+    const bf16x8 ones_aug = as_bf16x8(w11);      // slots 0,1 = 1 in the lower lane half, else 0
+    w11[0] = lower ? kOnePair<F> : 0u;
+    const bf16x8 ones_s = as_bf16x8(w11);        // the same in the type of the score products
+    auto to_bf16 = [](bf16x8 x) { return as_bf16x8(to_bf16_row<F>(__builtin_bit_cast(u32x4, x))); };
+    // V rows as the operand of the a product; PACK: slots 8,9 := 1 (the upper lane half loaded zeros)
+    auto v_operand = [&](bf16x8 x) {
+        u32x4 w = to_bf16_row<F>(__builtin_bit_cast(u32x4, x));
+        if (PACK && !lower) w[0] = 0x3f803f80u;
+        return as_bf16x8(w);
+    };
+
+    const bf16_t *kb = k + tok_base(ts, bh, H);
+    const bf16_t *vb = v + tok_base(ts, bh, H);
+    const bf16_t *gb = dy + tok_base(ts, bh, H);
+    const float *lb = lse_dec2 + (size_t)bh * N;
+    const float *db = delta + (size_t)bh * N;
+    const int n0 = chunk * chunk_len;
+    const int n1 = min(N, n0 + chunk_len);
+    const int tiles = (n1 - n0 + 31) / 32;
+    const int cnt = (tiles > tg) ? (tiles - tg + TG - 1) / TG : 0;
+
+    f32x16 acc[NB][HV];
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int hv = 0; hv < HV; ++hv) acc[b][hv] = splat16(0.f);
+
+    int krow[HV];
+#pragma unroll
+    for (int hv = 0; hv < HV; ++hv) krow[hv] = (l32 < 16) ? 16 * hv + l32 : D;
+
+    auto tile_tok0 = [&](int j) { return n0 + 32 * (tg + min(j, cnt - 1) * TG); };
+    // A operand: row = token.  rep (PACK only): both lane halves get elements 0-7 of the row.
+    auto load_rows = [&](const bf16_t *base, int j, bf16x8 (&t)[KS], bool rep) {
+        const int n = min(tile_tok0(j) + l32, N - 1);
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+            t[s] = as_bf16x8(row8_bf16<DR>(base + tok_off(ts, n), (PACK && rep) ? 0 : (D / 2) * hh + 8 * s));
+    };
+    auto write_kt = [&](const bf16x8 (&t)[KS], uint16_t *buf) {   // transposed: row = d-index, column = token
+        if (PACK && !lower) return;   // the upper lane half holds a copy of the same elements
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const u32x4 w = to_bf16_row<F>(__builtin_bit_cast(u32x4, t[s]));   // K as a value: bf16
+            const int d0 = (D / 2) * hh + 8 * s;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                buf[(d0 + 2 * e) * kVtStride + l32] = (uint16_t)(w[e] & 0xffffu);
+                buf[(d0 + 2 * e + 1) * kVtStride + l32] = (uint16_t)(w[e] >> 16);
+            }
+        }
+    };
+    auto read_kT = [&](const uint16_t *buf, bf16x8 (&kT)[HV][2]) {
+#pragma unroll
+        for (int hv = 0; hv < HV; ++hv)
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+                const uint16_t *row = buf + krow[hv] * kVtStride + 16 * s2 + 4 * hh;
+                const u32x2 a = *reinterpret_cast<const u32x2 *>(row);
+                const u32x2 b = *reinterpret_cast<const u32x2 *>(row + 8);
+                u32x4 w;
+                w[0] = a[0]; w[1] = a[1]; w[2] = b[0]; w[3] = b[1];
+                kT[hv][s2] = as_bf16x8(w);
+            }
+    };
+
+    // w[n] of a tile: written by the token's lane, read back as the 16 rows of this lane's registers
+    auto read_w = [&](const float *buf, float (&wr)[16]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float4 t = *reinterpret_cast<const float4 *>(buf + 8 * i + 4 * hh);
+            wr[4 * i] = t.x; wr[4 * i + 1] = t.y; wr[4 * i + 2] = t.z; wr[4 * i + 3] = t.w;
+        }
+    };
+
+    if (cnt > 0) {
+        // keys are requested two tiles ahead; so are the other operands where registers allow (d <= 16)
+        constexpr bool DEEP = (D == 16);
+        bf16x8 kt[KS], ktn[KS], ktnn[KS], vt[KS], vtn[KS], vtnn[KS], gt[KS], gtn[KS], gtnn[KS], kT[HV][2];
+        float nld, nldn, nldnn, dl, dln, dlnn;
+        float wrow[ONE ? 16 : 1];
+        load_rows(kb, 0, kt, true);
+        load_rows(kb, 1, ktn, true);
+        load_rows(vb, 0, vt, false);
+        load_rows(vb, 1, vtn, false);
+        load_rows(gb, 0, gt, true);
+        load_rows(gb, 1, gtn, true);
+        if constexpr (F || PACK) {   // V and dY meet bf16 operands: converted once, when they become current
+#pragma unroll
+            for (int s = 0; s < KS; ++s) { vt[s] = v_operand(vt[s]); gt[s] = to_bf16(gt[s]); }
+        }
+        nld = -lb[min(tile_tok0(0) + l32, N - 1)] * ld_mul;
+        dl = db[min(tile_tok0(0) + l32, N - 1)];
+        nldn = -lb[min(tile_tok0(1) + l32, N - 1)] * ld_mul;
+        dln = db[min(tile_tok0(1) + l32, N - 1)];
+        compiler_fence();
+        write_kt(kt, lds);
+        if constexpr (ONE) wl[0][l32] = fast_exp2(kap + nld);
+        compiler_fence();
+        read_kT(lds, kT);
+        if constexpr (ONE) read_w(wl[0], wrow);
+
+        for (int j = 0; j < cnt; ++j) {
+            const int tok0 = tile_tok0(j);
+            uint16_t *buf_next = lds + ((j + 1) & 1) * BUF;
+            load_rows(kb, j + 2, ktnn, true);
+            load_rows(vb, j + (DEEP ? 2 : 1), vtnn, false);
+            load_rows(gb, j + (DEEP ? 2 : 1), gtnn, true);
+            nldnn = -lb[min(tile_tok0(j + (DEEP ? 2 : 1)) + l32, N - 1)] * ld_mul;
+            dlnn = db[min(tile_tok0(j + (DEEP ? 2 : 1)) + l32, N - 1)];
+            compiler_fence();
+            write_kt(ktn, buf_next);
+            if constexpr (ONE) wl[(j + 1) & 1][l32] = fast_exp2(kap + (DEEP ? nldn : nldnn));
+            compiler_fence();
+
+            // token-side operands of the correction k-steps (zero outside the named slots)
+            u32x4 wb;
+            wb[0] = 0u; wb[2] = 0u; wb[3] = 0u;
+            wb[1] = lower ? split_pair<F>(nld) : 0u;             // slots 2,3 := -lse_dec2[n]
+            const bf16x8 kt_a = ones_s, kt_b = as_bf16x8(wb);    // slots 0,1 := 1 picks -lse_enc2
+            u32x4 wg;
+            const uint32_t ds_ = split_bf16_pair(-dl);
+            wg[0] = lower ? ds_ : 0u;
+            wg[1] = (ONE && lower) ? (ds_ & 0xffffu) : 0u;       // ONE: slots 0,1,2 := -delta hi, lo, hi
+            wg[2] = 0u; wg[3] = 0u;
+            const bf16x8 g_aug = as_bf16x8(wg);
+
+            const int rem = n1 - tok0 - 4 * hh;
+            const bool partial = tok0 + 32 > n1;
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                f32x16 x = splat16(0.f);
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) x = mfma_s<F>(kt[ks], qh[b][ks], x);
+                if constexpr (!PACK) {
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) x = mfma_s<F>(kt[ks], ql[b][ks], x);
+                }
+                f32x16 s1 = mfma_s<F>(kt_a, q_aug[b], x);
+                f32x16 s2 = s1;
+                if constexpr (!ONE) s2 = mfma_s<F>(kt_b, q_aug[b], x);
+                f32x16 av = splat16(0.f);
+                if constexpr (!PACK) av = mfma(ones_aug, dz_aug[b], av);
+                f32x16 cv = mfma(g_aug, ONE ? u_aug[ONE ? b : 0] : ones_aug, splat16(0.f));
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    av = mfma(vt[ks], dzb[b][ks], av);
+                    cv = mfma(gt[ks], zb[b][ks], cv);
+                    if constexpr (LO2 && !PACK) cv = mfma(gt[ks], zl[b][ks], cv);
+                }
+                if (partial) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (8 * (r / 4) + (r % 4) >= rem) { s1[r] = -INFINITY; s2[r] = -INFINITY; }
+                }
+                f32x16 ds;
+                if constexpr (ONE) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) ds[i] = fast_exp2(s1[i]) * fmaf(cv[i], wrow[i], av[i]);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) ds[i] = fmaf(fast_exp2(s2[i]), cv[i], fast_exp2(s1[i]) * av[i]);
+                }
+                u32x4 w0, w1;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    w0[i] = cvt_pk_bf16(ds[2 * i], ds[2 * i + 1]);
+                    w1[i] = cvt_pk_bf16(ds[8 + 2 * i], ds[8 + 2 * i + 1]);
+                }
+#pragma unroll
+                for (int hv = 0; hv < HV; ++hv) {
+                    acc[b][hv] = mfma(kT[hv][0], as_bf16x8(w0), acc[b][hv]);
+                    acc[b][hv] = mfma(kT[hv][1], as_bf16x8(w1), acc[b][hv]);
+                }
+            }
+            compiler_fence();
+            read_kT(buf_next, kT);
+            if constexpr (ONE) read_w(wl[(j + 1) & 1], wrow);
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                kt[s] = ktn[s]; ktn[s] = ktnn[s];
+                vt[s] = v_operand(DEEP ? vtn[s] : vtnn[s]); vtn[s] = vtnn[s];
+                gt[s] = to_bf16(DEEP ? gtn[s] : gtnn[s]); gtn[s] = gtnn[s];
+            }
+            nld = DEEP ? nldn : nldnn; nldn = nldnn;
+            dl = DEEP ? dln : dlnn; dln = dlnn;
+        }
+    }
+
+    const size_t part = (size_t)bh * parts + (size_t)chunk * TG + tg;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        if (lat0 + 32 * b + l32 >= M) continue;
+        const size_t slot = part * M + lat0 + 32 * b + l32;
+#pragma unroll
+        for (int hv = 0; hv < HV; ++hv) {
+            float4 lo4 = make_float4(acc[b][hv][0], acc[b][hv][1], acc[b][hv][2], acc[b][hv][3]);
+            float4 hi4 = make_float4(acc[b][hv][4], acc[b][hv][5], acc[b][hv][6], acc[b][hv][7]);
+            if (quartet_inside<DR>(hv, hh, 0)) *reinterpret_cast<float4 *>(dq_part + slot * DR + 16 * hv + 4 * hh) = lo4;
+            if (quartet_inside<DR>(hv, hh, 1)) *reinterpret_cast<float4 *>(dq_part + slot * DR + 16 * hv + 8 + 4 * hh) = hi4;
+        }
+    }
+}
+
+// ============================================================================================
+// Backward, dK and dV (token-major, like the decode: one wave owns 32 tokens at a time and walks
+// over all latent tiles).  Everything that depends on the latents only is prepared once per
+// workgroup as MFMA-ready operand images in LDS (one (b,h) per workgroup, 8 waves share it):
+//   A-type images (row = latent, contraction over d): q' hi, q' lo, dZ hi (and lo), Z hi (and
+//     lo), and a correction operand (slots 0,1 = -lse_enc2 as a hi+lo pair, slots 2,3 = 1,1; slots
+//     8,9 = -eps as a hi+lo pair; slots 10,11 = 1,1 or, with one exponential, slots 4-6 = u: they
+//     pick -delta[n] out of the token-side operand of the c chain's correction k-step);
+//   row images (row = output column, contraction over the 32 latents in accumulator order):
+//     RW1 = [dZ^T ; 0]   and   RW2 = [q^T ; 0].
+// Per token tile and latent tile:  P = 2^(S2 - lse_enc2[m]), R = 2^(S2 - lse_dec2[n]),
+//   a = <dZ_m, V_n> - eps[m],  c = <Z_m, dY_n> - delta[n],  dS = P a + R c  (fp32), then
+//   acc1 += RW1 . P   (rows 0-15: dV^T)
+//   acc2 += RW2 . dS  (rows 0-15: (sum_m dS q_m)^T)
+// and at the end  dV = acc1[0:16],  dK = scale * acc2[0:16].
+// (eps is subtracted inside the a chain, by one more product, so that a - eps = <dZ_m, V_n - Z_m>
+// cancels before dS is rounded: where a latent attends sharply to tokens of similar values the two
+// terms agree to several digits, and carrying -eps q separately through bf16 roundings lost them.)
+// No lo terms of dZ and Z for dK and dV: dZ arrives bf16-exact, and the rounding of Z_m is one error per
+// latent, which the sums of dK_n and dV_n over the latents average out (measured: dK error up by
+// 5-10 %, time down by 9 %) -- unlike in dQ, whose sums run over the tokens of one latent and add that
+// error up coherently (the DQ variant below therefore carries the lo term of Z).
+// ONE: one exponential per score, as in the dQ kernel: R = P u[m] w[n]; u is folded into the Z images
+// (and into slots 4-6 of the correction image, against -delta in the token operand), w[n] is a
+// per-lane scalar here, and dS' = P (a + w c).  Runs only where plan[bh] = 1.
+// ============================================================================================
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+constexpr int kDsStride = 40;   // uint16 per row of the transposed dS tile (80 B: 16-byte aligned, conflict-free b128 reads)
+constexpr int kFusedWaveLds = 32 * kDsStride + 16 * kVtStride;   // uint16 per wave: dS^T tile, then K^T tile
+
+template <int DR, int MT, bool DQ, bool ONE, bool F>
+__global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
+    const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
+    const bf16_t *__restrict__ dy, const float *__restrict__ z, const float *__restrict__ lse_enc,
+    const float *__restrict__ dz, const float *__restrict__ eps, const float *__restrict__ lse_dec2,
+    const float *__restrict__ delta, float ld_mul, const int *__restrict__ plan, bf16_t *__restrict__ dk,
+    bf16_t *__restrict__ dv, float *__restrict__ acc32, float *__restrict__ dq_part, TokStride ts, int H, int N,
+    int Mtot, int m0, float c2, float scale)
+{
+    // DQ (d <= 16): the kernel also forms the dQ partials, so that the scores, a, c and dS of a tile
+    // pair are computed once for all three gradients.  dS of a tile reaches the dQ product transposed
+    // (contraction over the tokens) through a wave-private LDS tile, and that product is
+    //     dQ^T[dd][m] += K^T[dd][n] dS^T[n][m]     with v_mfma_f32_16x16x32_bf16
+    // (16 output rows = d: no wasted rows, four accumulator registers per 16 latents), so a wave keeps
+    // dQ of all 32*MT latents in 8*MT registers.  At the end the eight waves add their partials in a
+    // fixed order through LDS and the workgroup writes slot blockIdx.x of dq_part
+    // ([(b*h) * gridDim.x + blockIdx.x][Mtot][d], summed and scaled by dq_reduce_kernel).  The c chain
+    // then carries the lo term of Z (dQ sums dS over the tokens of one latent and would add up its
+    // rounding coherently, see the dQ kernel).
+    // The kernel works on the latents m0 .. m0 + M of the head's Mtot.  With acc32 given (more than one
+    // latent chunk) it adds its dV and dK rows in fp32 to acc32[0][b*h][n][DR] and acc32[1][...] (the
+    // chunk with m0 = 0 stores instead) and dkdv_finish_kernel rounds the sums to dk and dv.
+    constexpr int D = padded_dim(DR);
+    constexpr int KS = D / 16;
+    constexpr int HV = D / 16;
+    static_assert(!DQ || DR <= 16, "the fused dQ product is written for d <= 16 (16 output rows)");
+    constexpr int NA = 4 * KS + 1;              // A-type images per latent tile (the last one: corrections)
+    constexpr int NR = 4 * HV;                  // row images per latent tile (RW1, RW2) x 2 k-steps
+    constexpr int PER_TILE = NA + NR;
+    constexpr bool PIPE = (D == 16);            // look one latent tile ahead where registers allow
+    // d <= 8: the upper half of the padded contraction carries what otherwise needs products of its own.
+    // Images: q' hi | lo in one (keys repeated in both lane halves), slots 8,9 of the dZ image = -eps
+    // (against ones in the V operand), slots 8-10 of the Z image = u, u, u lo or 1, 1 (against -delta in
+    // the dY operand).  The q' lo image and the a / c parts of the correction image are then unused.
+    constexpr bool PACK = pack_dim(DR);
+    // PACK with DQ: the upper half of the Z image carries the lo term of Z instead (dY rows repeated in both
+    // lane halves), as the separate dQ kernel has it at d <= 8, and -delta comes in through the correction
+    // image as at d = 16: dQ sums dS over the tokens of one latent, and with so few terms per dot product
+    // the rounding of Z_m showed (9.7e-3 against 2.6e-3 on a 1500-token case).  The host uses this
+    // instantiation only with at least 32 latents: with very few, c - delta must cancel against a delta
+    // that the decode formed from the rounded Z alone.
+    constexpr bool ZPACK = PACK && DQ;
+    extern __shared__ __attribute__((aligned(16))) u32x4 img[];   // [MT][PER_TILE][64 lanes]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
+    const int wave = tid >> 6;
+    const int bh = blockIdx.y, h = bh % H;
+    const bool lower = hh == 0;
+    if ((plan[bh] != 0) != ONE) return;         // the other variant owns this (b,h); uniform over the workgroup
+    float kap = 0.f;
+    if constexpr (ONE) {
+        kap = -INFINITY;
+        for (int m = lane; m < Mtot; m += 64) kap = fmaxf(kap, lse_enc[(size_t)bh * Mtot + m] * kLog2e);
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) kap = fmaxf(kap, __shfl_xor(kap, off));
+    }
+
+    // ---- build the operand images ----
+    {
+        const bf16_t *qh_ = q + (size_t)h * ts.sq + (size_t)m0 * DR;
+        const float *zb = z + ((size_t)bh * Mtot + m0) * DR;
+        const float *dzb = dz + ((size_t)bh * Mtot + m0) * DR;
+        const float *eb = eps + (size_t)bh * Mtot + m0;
+        const float *leb = lse_enc + (size_t)bh * Mtot + m0;
+        // Padding latents (at or beyond Mtot; mleft = real ones from m0 on): loads are clamped to the last
+        // real latent and every value that could reach dK or dV is zero -- q, Z, dZ, eps, u and the ones
+        // that pick -delta -- so that a = c = 0 and dS = 0 whatever P and R come out as.
+        const int mleft = Mtot - m0;
+        for (int idx = tid; idx < MT * PER_TILE * 64; idx += 512) {
+            const int ln = idx & 63, sid = (idx >> 6) % PER_TILE, t = (idx >> 6) / PER_TILE;
+            const int r32 = ln & 31, hf = ln >> 5;
+            u32x4 w;
+            if (sid == NA - 1) {
+                // correction operand: slots 0,1 = -lse_enc2 (hi + lo pair), slots 2,3 = 1, else zero
+                const bool real = 32 * t + r32 < mleft;
+                const int mc = min(32 * t + r32, mleft - 1);
+                const float le2 = real ? leb[mc] * kLog2e : 0.f;
+                w[0] = hf == 0 ? split_pair<F>(-le2) : 0u;
+                w[1] = hf == 0 ? kOnePair<F> : 0u;
+                w[2] = 0u; w[3] = 0u;
+                // Slots 4-6 belong to the c product and slots 8,9 to the a product, whose operands are bf16
+                // whatever the storage type; the score products meet them with zeros in the token operand
+                // (and the a and c products meet slots 0-3 with zeros).  u <= 1 and finite 16-bit patterns of either type read as finite values
+                // of the other, so the foreign slots contribute exact zeros.
+                if constexpr (ONE) {   // slots 4,5,6 := u hi, u hi, u lo
+                    const uint32_t us = split_bf16_pair(real ? fast_exp2(le2 - kap) : 0.f);
+                    w[2] = hf == 0 ? ((us & 0xffffu) | (us << 16)) : 0u;
+                    w[3] = hf == 0 ? (us >> 16) : 0u;
+                }
+                if (hf == 1) {
+                    w[0] = split_bf16_pair(real ? -eb[mc] : 0.f);          // slots 8,9 := -eps (bf16: the a chain)
+                    if (!ONE && real) w[1] = 0x3f803f80u;                  // slots 10,11 := 1 (picks -delta, two exponentials)
+                }
+            } else if (sid < NA) {
+                const int kind = sid / KS, ks = sid % KS;          // 0 q' hi, 1 q' lo, 2 dZ, 3 Z hi, 4 Z lo (DQ only)
+                const bool real = 32 * t + r32 < mleft;
+                const int m = min(32 * t + r32, mleft - 1);
+                const int d0 = (D / 2) * hf + 8 * ks;
+                float x[8];
+                if (kind <= 1) {
+                    const u32x4 raw = row8_bf16<DR>(qh_ + (size_t)m * DR, PACK ? 0 : d0);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) { x[2 * i] = elem_lo<F>(raw[i]) * c2; x[2 * i + 1] = elem_hi<F>(raw[i]) * c2; }
+                } else {
+                    const bool is_z = kind >= 3;
+                    row8_f32<DR>((is_z ? zb : dzb) + (size_t)m * DR, (ZPACK && is_z) ? 0 : d0, x);
+                    const float um = (ONE && is_z) ? fast_exp2(leb[m] * kLog2e - kap) : 1.f;
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) x[i] *= um;
+                }
+                if (!real) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) x[i] = 0.f;
+                }
+                const bool want_lo = (kind == 1 || kind >= 4 || (PACK && kind == 0 && hf == 1) ||
+                                      (ZPACK && kind == 3 && hf == 1));
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    uint32_t a, b;
+                    if (kind <= 1) {   // q' feeds the score products: storage type
+                        a = rne_elem<F>(x[2 * i]); b = rne_elem<F>(x[2 * i + 1]);
+                        if (want_lo) {
+                            a = rne_elem<F>(x[2 * i] - elem_value<F>(a));
+                            b = rne_elem<F>(x[2 * i + 1] - elem_value<F>(b));
+                        }
+                    } else {
+                        a = rne_bf16(x[2 * i]); b = rne_bf16(x[2 * i + 1]);
+                        if (want_lo) {
+                            a = rne_bf16(x[2 * i] - __uint_as_float(a << 16));
+                            b = rne_bf16(x[2 * i + 1] - __uint_as_float(b << 16));
+                        }
+                    }
+                    w[i] = a | (b << 16);
+                }
+                if (PACK && hf == 1 && kind == 2 && real) w[0] = split_bf16_pair(-eb[m]);   // slots 8,9 := -eps
+                if (PACK && !ZPACK && hf == 1 && kind == 3 && real) {                // slots 8,9,10 := u, u, u lo / 1, 1
+                    if constexpr (ONE) {
+                        const uint32_t us = split_bf16_pair(fast_exp2(leb[m] * kLog2e - kap));
+                        w[0] = (us & 0xffffu) | (us << 16);
+                        w[1] = us >> 16;
+                    } else {
+                        w[0] = 0x3f803f80u;
+                    }
+                }
+            } else {
+                const int rsid = sid - NA;                          // (which, hv, s2)
+                const int which = rsid / (2 * HV), hv = (rsid / 2) % HV, s2 = rsid % 2;
+                const int dd = 16 * hv + (r32 & 15);
+#pragma unroll
+                for (int i = 0; i < 8; i += 2) {
+                    float a, b;
+                    const int ma = 32 * t + perm_index(s2, hf, i), mb = 32 * t + perm_index(s2, hf, i + 1);
+                    const bool in = dd < DR;   // beyond the real head dimension every row image is zero
+                    const bool ina = in && ma < mleft, inb = in && mb < mleft;
+                    const float q0 = ina ? elem_value<F>(qh_[(size_t)ma * DR + dd]) : 0.f;
+                    const float q1 = inb ? elem_value<F>(qh_[(size_t)mb * DR + dd]) : 0.f;
+                    if (which == 0) {
+                        a = (r32 < 16 && ina) ? dzb[(size_t)ma * DR + dd] : 0.f;
+                        b = (r32 < 16 && inb) ? dzb[(size_t)mb * DR + dd] : 0.f;
+                    } else {
+                        a = (r32 < 16) ? q0 : 0.f;
+                        b = (r32 < 16) ? q1 : 0.f;
+                    }
+                    w[i / 2] = rne_bf16(a) | (rne_bf16(b) << 16);
+                }
+            }
+            img[idx] = w;
+        }
+    }
+    __syncthreads();
+
+    u32x4 w11;
+    w11[1] = 0u; w11[2] = 0u; w11[3] = 0u;
+    w11[0] = lower ? kOnePair<F> : 0u;
+    const bf16x8 ones_s = as_bf16x8(w11);        // the same in the type of the score products
+    w11[0] = lower ? 0u : 0x3f803f80u;
+    const bf16x8 ones_eps = as_bf16x8(w11);      // slots 8,9 = 1 (bf16): picks -eps out of the correction image
+    auto to_bf16 = [](bf16x8 x) { return as_bf16x8(to_bf16_row<F>(__builtin_bit_cast(u32x4, x))); };
+
+    const bf16_t *kb = k + tok_base(ts, bh, H);
+    const bf16_t *vb = v + tok_base(ts, bh, H);
+    const bf16_t *gb = dy + tok_base(ts, bh, H);
+    const float *lb = lse_dec2 + (size_t)bh * N;
+    const float *db = delta + (size_t)bh * N;
+    const int tiles = (N + 31) / 32;
+    const int stride = gridDim.x * 8;
+    // B operand: column = token.  rep (PACK only): both lane halves get elements 0-7 of the row.
+    auto load_cols = [&](const bf16_t *base, int tile, bf16x8 (&t)[KS], bool rep) {
+        const int n = min(tile * 32 + l32, N - 1);
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+            t[s] = as_bf16x8(row8_bf16<DR>(base + tok_off(ts, n), (PACK && rep) ? 0 : (D / 2) * hh + 8 * s));
+    };
+    // V rows as the operand of the a product; PACK: slots 8,9 := 1 (the upper lane half loaded zeros)
+    auto v_operand = [&](bf16x8 x) {
+        u32x4 w = to_bf16_row<F>(__builtin_bit_cast(u32x4, x));
+        if (PACK && !lower) w[0] = 0x3f803f80u;
+        return as_bf16x8(w);
+    };
+    auto image = [&](int t, int sid) { return as_bf16x8(img[(t * PER_TILE + sid) * 64 + lane]); };
+
+    // fused dQ: wave-private LDS tiles and the accumulators dQ^T[dd = 4 (lane / 16) + r][m = 32 t + 16 jb + lane % 16]
+    uint16_t *ds_t = reinterpret_cast<uint16_t *>(img + MT * PER_TILE * 64) + (DQ ? wave * kFusedWaveLds : 0);
+    uint16_t *k_t = ds_t + 32 * kDsStride;
+    if constexpr (DQ && PACK) {   // K^T rows 8-15 are never written at d <= 8: zero (the output rows 8-15 are dropped)
+        if (lane < kVtStride) {
+#pragma unroll
+            for (int r = 8; r < 16; ++r) k_t[r * kVtStride + lane] = 0;
+        }
+    }
+    f32x4 dqa[DQ ? MT : 1][2];
+#pragma unroll
+    for (int t = 0; t < (DQ ? MT : 1); ++t)
+#pragma unroll
+        for (int jb = 0; jb < 2; ++jb) dqa[t][jb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int c16 = lane & 15, g16 = lane >> 4;
+
+    int tile = blockIdx.x * 8 + wave;
+    bf16x8 kt[KS], vt[KS], gt[KS], ktn[KS], vtn[KS], gtn[KS];
+    if (tile < tiles) {
+        load_cols(kb, tile, kt, true);
+        load_cols(vb, tile, vt, false);
+        load_cols(gb, tile, gt, ZPACK);
+#pragma unroll
+        for (int s = 0; s < KS; ++s) { vt[s] = v_operand(vt[s]); gt[s] = to_bf16(gt[s]); }
+    }
+    for (; tile < tiles; tile += stride) {
+        const int n = tile * 32 + l32;
+        const int tn = (tile + stride < tiles) ? tile + stride : tile;
+        load_cols(kb, tn, ktn, true);
+        load_cols(vb, tn, vtn, false);
+        load_cols(gb, tn, gtn, ZPACK);
+        const size_t row = (size_t)min(n, N - 1);
+        const float nld = -lb[row] * ld_mul, dl = db[row];
+        const float wn = ONE ? fast_exp2(kap + nld) : 0.f;
+
+        u32x4 wb;
+        wb[0] = 0u; wb[2] = 0u; wb[3] = 0u;
+        wb[1] = lower ? split_pair<F>(nld) : 0u;             // slots 2,3 := -lse_dec2[n]
+        const bf16x8 kt_a = ones_s, kt_b = as_bf16x8(wb);    // slots 0,1 := 1 picks -lse_enc2
+        // Token side of the correction k-step(s).  Two exponentials: g_aug picks -delta for the c chain
+        // (slots 10,11 against the image's ones) and ones_eps picks -eps for the a chain.  One exponential:
+        // dS = P (a + w c), and w[n] is this lane's scalar, so ONE product serves both chains: slots 8,9 = 1
+        // pick -eps and slots 4,5,6 = -w delta (hi, lo, hi) meet u (hi, hi, lo); the a chain starts from
+        // it and the c chain from zero.
+        u32x4 wg;
+        const uint32_t ds_ = split_bf16_pair(ONE ? -dl * wn : -dl);
+        wg[0] = (ONE && !lower && !PACK) ? 0x3f803f80u : 0u;
+        wg[1] = (!ONE && !lower) ? ds_ : 0u;                 // two exponentials: slots 10,11 := -delta (hi, lo)
+        wg[2] = (ONE && lower) ? ds_ : 0u;                   // one: slots 4,5,6 := -w delta hi, lo, hi
+        wg[3] = (ONE && lower) ? (ds_ & 0xffffu) : 0u;
+        const bf16x8 g_aug = as_bf16x8(wg);
+        bf16x8 gc[KS];   // dY operand of the c product; PACK: slots 8,9,10 := -delta hi, lo, hi
+#pragma unroll
+        for (int s = 0; s < KS; ++s) gc[s] = gt[s];
+        if constexpr (PACK && !ZPACK) {
+            u32x4 w = __builtin_bit_cast(u32x4, gt[0]);
+            const uint32_t dp_ = split_bf16_pair(-dl);   // here c keeps its own correction: -delta unscaled
+            if (!lower) { w[0] = dp_; w[1] = ONE ? (dp_ & 0xffffu) : 0u; }
+            gc[0] = as_bf16x8(w);
+        }
+
+        f32x16 acc1[HV], acc2[HV];
+#pragma unroll
+        for (int hv = 0; hv < HV; ++hv) { acc1[hv] = splat16(0.f); acc2[hv] = splat16(0.f); }
+
+        // fused dQ: K^T of this token tile as the A operand of the 16x16x32 product (row = dd = lane % 16,
+        // tokens 8 (lane / 16) .. + 7), through the wave's LDS tile; rows of tokens past N are zero
+        bf16x8 k_op = zero_operand();
+        if constexpr (DQ) {
+            const u32x4 w = (n < N) ? to_bf16_row<F>(__builtin_bit_cast(u32x4, kt[0])) : __builtin_bit_cast(u32x4, zero_operand());
+            if (!(PACK && hh)) {   // d <= 8: the upper lane half holds a copy of the same elements
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    k_t[(8 * hh + 2 * e) * kVtStride + l32] = (uint16_t)(w[e] & 0xffffu);
+                    k_t[(8 * hh + 2 * e + 1) * kVtStride + l32] = (uint16_t)(w[e] >> 16);
+                }
+            }
+            compiler_fence();
+            const uint16_t *rowp = k_t + c16 * kVtStride + 8 * g16;
+            const u32x2 lo2 = *reinterpret_cast<const u32x2 *>(rowp);
+            const u32x2 hi2 = *reinterpret_cast<const u32x2 *>(rowp + 4);
+            u32x4 ka;
+            ka[0] = lo2[0]; ka[1] = lo2[1]; ka[2] = hi2[0]; ka[3] = hi2[1];
+            k_op = as_bf16x8(ka);
+        }
+
+        // Score products of latent tile t (minus lse_enc2 / minus lse_dec2): 2*KS + 2 MFMAs.
+        auto scores = [&](int t, f32x16 &s1, f32x16 &s2) {
+            f32x16 x = splat16(0.f);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) x = mfma_s<F>(image(t, 0 * KS + ks), kt[ks], x);
+            if constexpr (!PACK) {
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) x = mfma_s<F>(image(t, 1 * KS + ks), kt[ks], x);
+            }
+            const bf16x8 qa = image(t, NA - 1);
+            s1 = mfma_s<F>(qa, kt_a, x);
+            if constexpr (!ONE) s2 = mfma_s<F>(qa, kt_b, x);
+        };
+        // One latent tile, software-pipelined: the a and c products of tile t and the score products
+        // of tile t+1 are issued first and run on the matrix cores while the vector ALUs
+        // exponentiate the scores of tile t (s1, s2, computed one step earlier).
+        auto tile_step = [&](int t, f32x16 &s1, f32x16 &s2, f32x16 &s1n, f32x16 &s2n) {
+            if constexpr (!PIPE) scores(t, s1, s2);   // not enough registers at d = 32: no look-ahead
+            f32x16 av = splat16(0.f), cv = splat16(0.f);
+            if constexpr (ONE) {
+                if constexpr (!PACK || ZPACK) av = mfma(image(t, NA - 1), g_aug, av);
+            } else {
+                if constexpr (!PACK) av = mfma(image(t, NA - 1), ones_eps, av);
+                if constexpr (!PACK || ZPACK) cv = mfma(image(t, NA - 1), g_aug, cv);
+            }
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                av = mfma(image(t, 2 * KS + ks), vt[ks], av);
+                cv = mfma(image(t, 3 * KS + ks), gc[ks], cv);
+            }
+            if constexpr (PIPE) {
+                if (t + 1 < MT) scores(t + 1, s1n, s2n);
+            }
+            bf16x8 rw[NR];
+#pragma unroll
+            for (int r = 0; r < NR; ++r) rw[r] = image(t, NA + r);
+            sched_fence();
+            f32x16 pv, rv;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                pv[i] = fast_exp2(s1[i]);
+                if constexpr (ONE) rv[i] = pv[i] * fmaf(cv[i], wn, av[i]);     // dS' = P (a + w[n] u[m] c)
+                else rv[i] = fmaf(fast_exp2(s2[i]), cv[i], pv[i] * av[i]);     // dS' = P a + R c
+            }
+            u32x4 p0, p1, d0, d1;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                p0[i] = cvt_pk_bf16(pv[2 * i], pv[2 * i + 1]);
+                p1[i] = cvt_pk_bf16(pv[8 + 2 * i], pv[8 + 2 * i + 1]);
+                d0[i] = cvt_pk_bf16(rv[2 * i], rv[2 * i + 1]);
+                d1[i] = cvt_pk_bf16(rv[8 + 2 * i], rv[8 + 2 * i + 1]);
+            }
+#pragma unroll
+            for (int hv = 0; hv < HV; ++hv) {
+                acc1[hv] = mfma(rw[(0 * HV + hv) * 2 + 0], as_bf16x8(p0), acc1[hv]);
+                acc1[hv] = mfma(rw[(0 * HV + hv) * 2 + 1], as_bf16x8(p1), acc1[hv]);
+                acc2[hv] = mfma(rw[(1 * HV + hv) * 2 + 0], as_bf16x8(d0), acc2[hv]);
+                acc2[hv] = mfma(rw[(1 * HV + hv) * 2 + 1], as_bf16x8(d1), acc2[hv]);
+            }
+            if constexpr (DQ) {
+                // dS (this lane: token l32, latents 8 (r/4) + 4 hh + r%4 for r = 0..15) -> LDS [latent][token]
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int ma = 8 * (i / 2) + 4 * hh + 2 * (i % 2);          // latent of the low half of d0[i]
+                    ds_t[ma * kDsStride + l32] = (uint16_t)(d0[i] & 0xffffu);
+                    ds_t[(ma + 1) * kDsStride + l32] = (uint16_t)(d0[i] >> 16);
+                    ds_t[(16 + ma) * kDsStride + l32] = (uint16_t)(d1[i] & 0xffffu);
+                    ds_t[(16 + ma + 1) * kDsStride + l32] = (uint16_t)(d1[i] >> 16);
+                }
+                compiler_fence();
+#pragma unroll
+                for (int jb = 0; jb < 2; ++jb) {
+                    const u32x4 bop = *reinterpret_cast<const u32x4 *>(ds_t + (16 * jb + c16) * kDsStride + 8 * g16);
+                    dqa[t][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k_op, as_bf16x8(bop), dqa[t][jb], 0, 0, 0);
+                }
+                compiler_fence();
+            }
+            sched_fence();
+        };
+        {
+            f32x16 sa1 = splat16(0.f), sa2 = splat16(0.f), sb1 = splat16(0.f), sb2 = splat16(0.f);
+            if constexpr (PIPE) scores(0, sa1, sa2);
+            if constexpr (MT == 1) {
+                tile_step(0, sa1, sa2, sb1, sb2);
+            } else if constexpr (DQ) {   // unrolled: the dQ accumulators are indexed by the latent tile
+#pragma unroll
+                for (int t = 0; t < MT; t += 2) {
+                    tile_step(t, sa1, sa2, sb1, sb2);
+                    tile_step(t + 1, sb1, sb2, sa1, sa2);
+                }
+            } else {
+#pragma unroll 1
+                for (int t = 0; t < MT; t += 2) {
+                    tile_step(t, sa1, sa2, sb1, sb2);
+                    tile_step(t + 1, sb1, sb2, sa1, sa2);
+                }
+            }
+        }
+        if (n < N && acc32 != nullptr) {
+            float *dvr = acc32 + ((size_t)bh * N + n) * DR;
+            float *dkr = dvr + (size_t)gridDim.y * N * DR;
+            const bool first = m0 == 0;
+#pragma unroll
+            for (int hv = 0; hv < HV; ++hv)
+#pragma unroll
+                for (int up = 0; up < 2; ++up) {
+                    if (!quartet_inside<DR>(hv, hh, up)) continue;
+                    const int o = 16 * hv + 8 * up + 4 * hh;
+                    float4 a = make_float4(acc1[hv][4 * up], acc1[hv][4 * up + 1], acc1[hv][4 * up + 2],
+                                           acc1[hv][4 * up + 3]);
+                    float4 b = make_float4(scale * acc2[hv][4 * up], scale * acc2[hv][4 * up + 1],
+                                           scale * acc2[hv][4 * up + 2], scale * acc2[hv][4 * up + 3]);
+                    if (!first) {
+                        const float4 pa = *reinterpret_cast<const float4 *>(dvr + o);
+                        const float4 pb = *reinterpret_cast<const float4 *>(dkr + o);
+                        a.x += pa.x; a.y += pa.y; a.z += pa.z; a.w += pa.w;
+                        b.x += pb.x; b.y += pb.y; b.z += pb.z; b.w += pb.w;
+                    }
+                    *reinterpret_cast<float4 *>(dvr + o) = a;
+                    *reinterpret_cast<float4 *>(dkr + o) = b;
+                }
+        } else if (n < N) {
+            bf16_t *dkr = dk + tok_base(ts, bh, H) + tok_off(ts, n);
+            bf16_t *dvr = dv + tok_base(ts, bh, H) + tok_off(ts, n);
+#pragma unroll
+            for (int hv = 0; hv < HV; ++hv) {
+                u32x2 w0, w1;
+                w0[0] = pack_elems<F>(acc1[hv][0], acc1[hv][1]);
+                w0[1] = pack_elems<F>(acc1[hv][2], acc1[hv][3]);
+                w1[0] = pack_elems<F>(acc1[hv][4], acc1[hv][5]);
+                w1[1] = pack_elems<F>(acc1[hv][6], acc1[hv][7]);
+                if (quartet_inside<DR>(hv, hh, 0)) *reinterpret_cast<u32x2 *>(dvr + 16 * hv + 4 * hh) = w0;
+                if (quartet_inside<DR>(hv, hh, 1)) *reinterpret_cast<u32x2 *>(dvr + 16 * hv + 8 + 4 * hh) = w1;
+                w0[0] = pack_elems<F>(scale * acc2[hv][0], scale * acc2[hv][1]);
+                w0[1] = pack_elems<F>(scale * acc2[hv][2], scale * acc2[hv][3]);
+                w1[0] = pack_elems<F>(scale * acc2[hv][4], scale * acc2[hv][5]);
+                w1[1] = pack_elems<F>(scale * acc2[hv][6], scale * acc2[hv][7]);
+                if (quartet_inside<DR>(hv, hh, 0)) *reinterpret_cast<u32x2 *>(dkr + 16 * hv + 4 * hh) = w0;
+                if (quartet_inside<DR>(hv, hh, 1)) *reinterpret_cast<u32x2 *>(dkr + 16 * hv + 8 + 4 * hh) = w1;
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < KS; ++s) { kt[s] = ktn[s]; vt[s] = v_operand(vtn[s]); gt[s] = to_bf16(gtn[s]); }
+    }
+
+    if constexpr (DQ) {
+        // The eight waves add their dQ partials in wave order (fixed, so the bits are reproducible) in a
+        // [32*MT][16] fp32 buffer that reuses the image memory, then the workgroup stores its slot.
+        float *red = reinterpret_cast<float *>(img);
+        for (int w = 0; w < 8; ++w) {
+            __syncthreads();   // first pass: every wave is done with the images
+            if (wave == w) {
+#pragma unroll
+                for (int t = 0; t < MT; ++t)
+#pragma unroll
+                    for (int jb = 0; jb < 2; ++jb) {
+                        float4 *cell = reinterpret_cast<float4 *>(red + (32 * t + 16 * jb + c16) * 16 + 4 * g16);
+                        float4 x = make_float4(dqa[t][jb][0], dqa[t][jb][1], dqa[t][jb][2], dqa[t][jb][3]);
+                        if (w > 0) {
+                            const float4 o = *cell;
+                            x.x += o.x; x.y += o.y; x.z += o.z; x.w += o.w;
+                        }
+                        *cell = x;
+                    }
+            }
+        }
+        __syncthreads();
+        const int mleft = Mtot - m0;
+        float *out = dq_part + (((size_t)bh * gridDim.x + blockIdx.x) * Mtot + m0) * DR;
+        constexpr int PCS = DR / 4;                             // float4 pieces of a DR-element row
+        for (int i = tid; i < 32 * MT * PCS; i += 512) {        // latent i / PCS, columns 4 (i % PCS) ..
+            const int lat = i / PCS, pc = i % PCS;
+            if (lat < mleft)
+                *reinterpret_cast<float4 *>(out + (size_t)lat * DR + 4 * pc) =
+                    *reinterpret_cast<const float4 *>(red + (size_t)lat * 16 + 4 * pc);
+        }
+    }
+}
+
+}  // namespace
+
+// dQ partials of the backward; slot layout as the encode partials: [(b*h) * parts + part][M][d]
+int mfma_dq_partial(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy,
+                    const float *z, const float *lse_enc, const float *dz, const float *eps,
+                    const float *lse_dec2, const float *delta, float ld_mul, const int *plan, bool one_exp,
+                    float *dq_part, float scale, hipStream_t stream)
+{
+    const MfmaPlan p = mfma_plan(s);
+    int zdim;
+    const EncGeom e = dq_geom(s, &zdim);
+    const int BH = s.B * s.H;
+    const float c2 = scale * kLog2e;
+    const int parts = p.enc.chunks * e.TG;
+    const dim3 grid(p.enc.chunks, BH, zdim);
+    const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *vv = (const bf16_t *)v, *gg = (const bf16_t *)dy;
+    LaunchTimer t(one_exp ? KID_BWD_DQ_PARTIAL : KID_BWD_DQ_PARTIAL_2EXP, stream);
+    const bool f16 = s.dtype == FLARE_F16;
+#define FLARE_DQ_ARGS                                                                                            \
+    qq, kk, vv, gg, z, lse_enc, dz, eps, lse_dec2, delta, ld_mul, plan, dq_part, tok_stride(s), s.H, s.N, s.M,   \
+        p.enc.chunk_len, parts, e.G, e.TG, c2
+#define FLARE_DQ(DD, NBB, MINB)                                                                                  \
+    do {                                                                                                         \
+        if (one_exp && f16)                                                                                      \
+            bwd_dq_mfma_kernel<DD, NBB, MINB, true, true><<<grid, e.threads, 0, stream>>>(FLARE_DQ_ARGS);        \
+        else if (one_exp)                                                                                        \
+            bwd_dq_mfma_kernel<DD, NBB, MINB, true, false><<<grid, e.threads, 0, stream>>>(FLARE_DQ_ARGS);       \
+        else if (f16)                                                                                            \
+            bwd_dq_mfma_kernel<DD, NBB, MINB, false, true><<<grid, e.threads, 0, stream>>>(FLARE_DQ_ARGS);       \
+        else                                                                                                     \
+            bwd_dq_mfma_kernel<DD, NBB, MINB, false, false><<<grid, e.threads, 0, stream>>>(FLARE_DQ_ARGS);      \
+    } while (0)
+#define FLARE_DQ_NB(DD)                      \
+    do {                                     \
+        if (e.NB == 1) FLARE_DQ(DD, 1, 2);   \
+        else FLARE_DQ(DD, 2, 2);             \
+    } while (0)
+    switch (s.d) {
+        case 4: FLARE_DQ_NB(4); break;
+        case 8: FLARE_DQ_NB(8); break;
+        case 16: FLARE_DQ_NB(16); break;
+        default:
+            if (e.NB == 1) FLARE_DQ(32, 1, 2);
+            else FLARE_DQ(32, 2, 1);
+    }
+#undef FLARE_DQ_NB
+#undef FLARE_DQ
+#undef FLARE_DQ_ARGS
+    return check_launch();
+}
+
+// dK and dV of the backward.  One workgroup of 8 waves per (b,h) slice and block of token tiles;
+// the operand images need (4 or 6)*KS + 1 + 4*HV KiB of LDS per latent tile.
+bool mfma_dkdv_supported(const flare_shape &s)
+{
+    return mfma_supported(s);
+}
+
+// workgroups per (b,h) of the dK/dV kernel (= dQ partial slots per (b,h) when it also forms dQ)
+int mfma_dkdv_blocks(const flare_shape &s)
+{
+    const int BH = s.B * s.H;
+    const int tiles = (s.N + 31) / 32;
+    int blocks = (256 + BH - 1) / BH;                 // one 8-wave workgroup per CU
+    if (blocks > (tiles + 7) / 8) blocks = (tiles + 7) / 8;
+    return blocks;
+}
+
+// The dK/dV kernel can form the dQ partials as well (one pass over the scores for all three gradients);
+// written for d <= 16 and used at d = 8 and 16.  At d = 4 the separate dQ kernel stays: it carries the lo
+// term of Z in its c chain, for which the fused kernel has no free slots next to the corrections at d = 4,
+// and with four-term dot products that term is worth a factor 4 in dQ's error (measured 3.3e-2 against
+// 8.6e-3 on a 333-token mesh case).  FLARE_BWD_SEPARATE_DQ=1 in the environment keeps the separate dQ kernel (a switch
+// for measurements; read at every call).
+bool mfma_dq_fused(const flare_shape &s)
+{
+    if (!mfma_supported(s) || (s.d != 8 && s.d != 16)) return false;
+    if (s.d == 8 && s.M < 32) return false;   // see ZPACK in the kernel
+    const char *e = getenv("FLARE_BWD_SEPARATE_DQ");
+    return !(e != nullptr && e[0] != '\0' && e[0] != '0');
+}
+
+int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy, const float *z,
+              const float *lse_enc, const float *dz, const float *eps, const float *lse_dec2, const float *delta,
+              float ld_mul, const int *plan, bool one_exp, void *dk, void *dv, float *acc32, float *dq_part, int m0,
+              float scale, hipStream_t stream)
+{
+    // dq_part != NULL: also write the dQ partials (mfma_dq_fused(s) must hold), slot layout
+    // [(b*h) * mfma_dkdv_blocks(s) + block][M][d]
+    const int BH = s.B * s.H;
+    const dim3 grid(mfma_dkdv_blocks(s), BH);
+    const bool fuse = dq_part != nullptr;
+    if (fuse && !mfma_dq_fused(s)) return FLARE_EUNSUPPORTED;
+    const float c2 = scale * kLog2e;
+    const int MT = lat_eff(s.M) == 192 ? 8 : lat_eff(s.M) / 32;   // instantiated for 1, 2, 4, 8 tiles
+    const int pd = padded_dim(s.d);
+    const int KS = pd / 16, HV = pd / 16;
+    const size_t lds = (size_t)MT * (4 * KS + 1 + 4 * HV) * 1024 + (fuse ? 8 * kFusedWaveLds * 2 : 0);
+    const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *vv = (const bf16_t *)v, *gg = (const bf16_t *)dy;
+    const bool f16 = s.dtype == FLARE_F16;
+    LaunchTimer t(one_exp ? KID_BWD_DKDV : KID_BWD_DKDV_2EXP, stream);
+#define FLARE_DKDV(DD, MTT, LO)                                                                                  \
+    do {                                                                                                         \
+        auto kern = f16 ? (one_exp ? bwd_dkdv_mfma_kernel<DD, MTT, LO, true, true>                               \
+                                   : bwd_dkdv_mfma_kernel<DD, MTT, LO, false, true>)                             \
+                        : (one_exp ? bwd_dkdv_mfma_kernel<DD, MTT, LO, true, false>                              \
+                                   : bwd_dkdv_mfma_kernel<DD, MTT, LO, false, false>);                           \
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                (int)lds) != hipSuccess)                                                         \
+            return FLARE_ELAUNCH;                                                                                \
+        kern<<<grid, 512, lds, stream>>>(qq, kk, vv, gg, z, lse_enc, dz, eps, lse_dec2, delta, ld_mul, plan,     \
+                                         (bf16_t *)dk, (bf16_t *)dv, acc32, dq_part, tok_stride(s), s.H, s.N,    \
+                                         s.M, m0, c2, scale);                                                    \
+    } while (0)
+#define FLARE_DKDV_MT(DD)                              \
+    switch (MT) {                                      \
+        case 1: FLARE_DKDV(DD, 1, false); break;       \
+        case 2: FLARE_DKDV(DD, 2, false); break;       \
+        case 4: FLARE_DKDV(DD, 4, false); break;       \
+        case 8: FLARE_DKDV(DD, 8, false); break;       \
+        default: return FLARE_EUNSUPPORTED;            \
+    }
+#define FLARE_DKDV_MT_DQ(DD)                           \
+    switch (MT) {                                      \
+        case 1: FLARE_DKDV(DD, 1, true); break;        \
+        case 2: FLARE_DKDV(DD, 2, true); break;        \
+        case 4: FLARE_DKDV(DD, 4, true); break;        \
+        case 8: FLARE_DKDV(DD, 8, true); break;        \
+        default: return FLARE_EUNSUPPORTED;            \
+    }
+    if (s.d == 8 && fuse) {
+        FLARE_DKDV_MT_DQ(8)
+    } else if (s.d == 16 && fuse) {
+        FLARE_DKDV_MT_DQ(16)
+    } else if (s.d == 4) {
+        FLARE_DKDV_MT(4)
+    } else if (s.d == 8) {
+        FLARE_DKDV_MT(8)
+    } else if (s.d == 16) {
+        FLARE_DKDV_MT(16)
+    } else {
+        switch (MT) {
+            case 1: FLARE_DKDV(32, 1, false); break;
+            case 2: FLARE_DKDV(32, 2, false); break;
+            case 4: FLARE_DKDV(32, 4, false); break;
+            case 8: FLARE_DKDV(32, 8, false); break;
+            default: return FLARE_EUNSUPPORTED;
+        }
+    }
+#undef FLARE_DKDV_MT_DQ
+#undef FLARE_DKDV_MT
+#undef FLARE_DKDV
+    return check_launch();
+}
+
+// fp32 sums of the per-chunk dV and dK rows (M > 256) -> dk, dv in the caller's layout
+namespace {
+template <int DR, bool F>
+__global__ __launch_bounds__(256) void dkdv_finish_kernel(const float *__restrict__ acc32, bf16_t *__restrict__ dk,
+                                                          bf16_t *__restrict__ dv, TokStride ts, int H, int N)
+{
+    const int n = blockIdx.x * 256 + threadIdx.x;
+    if (n >= N) return;
+    const int bh = blockIdx.y;
+    const float *sv = acc32 + ((size_t)bh * N + n) * DR;
+    const float *sk = sv + (size_t)gridDim.y * N * DR;
+    const size_t trow = tok_base(ts, bh, H) + tok_off(ts, n);
+#pragma unroll
+    for (int j = 0; j < DR; j += 4) {
+        const float4 a = *reinterpret_cast<const float4 *>(sv + j);
+        const float4 b = *reinterpret_cast<const float4 *>(sk + j);
+        u32x2 wa, wb;
+        wa[0] = pack_elems<F>(a.x, a.y); wa[1] = pack_elems<F>(a.z, a.w);
+        wb[0] = pack_elems<F>(b.x, b.y); wb[1] = pack_elems<F>(b.z, b.w);
+        *reinterpret_cast<u32x2 *>(dv + trow + j) = wa;
+        *reinterpret_cast<u32x2 *>(dk + trow + j) = wb;
+    }
+}
+}  // namespace
+
+size_t mfma_dkdv_acc_bytes(const flare_shape &s)
+{
+    if (s.M <= kLatChunk) return 0;
+    return ((size_t)s.B * s.H * s.N * s.d * 4 * 2 + 255) & ~(size_t)255;
+}
+
+int mfma_dkdv_finish(const flare_shape &s, const float *acc32, void *dk, void *dv, hipStream_t stream)
+{
+    const dim3 grid((s.N + 255) / 256, s.B * s.H);
+    LaunchTimer t(KID_BWD_DKDV_FINISH, stream);
+    const bool f16 = s.dtype == FLARE_F16;
+#define FLARE_FIN(DD)                                                                                          \
+    do {                                                                                                       \
+        if (f16)                                                                                               \
+            dkdv_finish_kernel<DD, true><<<grid, 256, 0, stream>>>(acc32, (bf16_t *)dk, (bf16_t *)dv,          \
+                                                                   tok_stride(s), s.H, s.N);                   \
+        else                                                                                                   \
+            dkdv_finish_kernel<DD, false><<<grid, 256, 0, stream>>>(acc32, (bf16_t *)dk, (bf16_t *)dv,         \
+                                                                    tok_stride(s), s.H, s.N);                  \
+    } while (0)
+    switch (s.d) {
+        case 4: FLARE_FIN(4); break;
+        case 8: FLARE_FIN(8); break;
+        case 16: FLARE_FIN(16); break;
+        default: FLARE_FIN(32); break;
+    }
+#undef FLARE_FIN
+    return check_launch();
+}
+
+// Which variant of the dQ and dK/dV kernels may run for a (b,h): plan[bh] = 1 (one exponential per
+// score) iff, with kappa = max_m lse_enc2[m], every u[m] = 2^(lse_enc2[m] - kappa) >= 2^-kPlanSpan and
+// every w[n] = 2^(kappa - lse_dec2[n]) lies in [2^-kPlanSpan, 2^kPlanSpan].  Then wherever
+// R = P u w is above 2^-(126 - 2 kPlanSpan), P is a normal fp32 number and nothing is lost; anything
+// else (wide score ranges, non-finite statistics) takes the two-exponential kernels.
+constexpr float kPlanSpan = 50.f;
+namespace {
+__global__ __launch_bounds__(256) void bwd_plan_kernel(const float *__restrict__ ld_range,
+                                                       const float *__restrict__ lse_enc, int *__restrict__ plan,
+                                                       int parts, int M, int force_two)
+{
+    __shared__ float red[4][4];
+    const int bh = blockIdx.x, tid = threadIdx.x;
+    float le_min = INFINITY, le_max = -INFINITY, ld_min = INFINITY, ld_max = -INFINITY;
+    for (int m = tid; m < M; m += 256) {
+        const float v = lse_enc[(size_t)bh * M + m] * kLog2e;
+        le_min = fminf(le_min, v);
+        le_max = fmaxf(le_max, v);
+    }
+    for (int p = tid; p < parts; p += 256) {
+        ld_min = fminf(ld_min, ld_range[2 * ((size_t)bh * parts + p)]);
+        ld_max = fmaxf(ld_max, ld_range[2 * ((size_t)bh * parts + p) + 1]);
+    }
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        le_min = fminf(le_min, __shfl_xor(le_min, off));
+        le_max = fmaxf(le_max, __shfl_xor(le_max, off));
+        ld_min = fminf(ld_min, __shfl_xor(ld_min, off));
+        ld_max = fmaxf(ld_max, __shfl_xor(ld_max, off));
+    }
+    if ((tid & 63) == 0) {
+        red[tid >> 6][0] = le_min; red[tid >> 6][1] = le_max;
+        red[tid >> 6][2] = ld_min; red[tid >> 6][3] = ld_max;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < 4; ++w) {
+            le_min = fminf(le_min, red[w][0]); le_max = fmaxf(le_max, red[w][1]);
+            ld_min = fminf(ld_min, red[w][2]); ld_max = fmaxf(ld_max, red[w][3]);
+        }
+        // written so that a NaN anywhere makes the test fail
+        const bool ok = (le_max - le_min <= kPlanSpan) && (le_max - ld_min <= kPlanSpan) &&
+                        (ld_max - le_max <= kPlanSpan) && fabsf(le_max) < 1e30f;
+        plan[bh] = (ok && !force_two) ? 1 : 0;
+    }
+}
+}  // namespace
+
+int mfma_bwd_plan(const flare_shape &s, const float *ld_range, const float *lse_enc, int *plan, bool force_two,
+                  hipStream_t stream)
+{
+    LaunchTimer t(KID_BWD_PLAN, stream);
+    bwd_plan_kernel<<<s.B * s.H, 256, 0, stream>>>(ld_range, lse_enc, plan, mfma_plan(s).parts, s.M,
+                                                   force_two ? 1 : 0);
+    return check_launch();
+}
+
+// partial slots per (b,h) that mfma_dq_partial writes
+int mfma_dq_parts(const flare_shape &s)
+{
+    const MfmaPlan p = mfma_plan(s);
+    int zdim;
+    return p.enc.chunks * dq_geom(s, &zdim).TG;
+}
+
+}  // namespace flare

@@ -1,0 +1,1011 @@
+// Matrix-core kernels of the forward (encode, decode), of the first backward pass (dZ partials, token
+// statistics: the same two kernels in their MODE 1) and of the spectral analysis (companion matrix).
+// Operand layouts, helpers and the tile geometry are in flare_mfma_common.h.
+#include "flare_mfma_common.h"
+
+namespace flare {
+namespace {
+
+// ============================================================================================
+// Decode.  One wave owns 32 tokens at a time and all M latents:
+//   pass 1: scores from the hi terms only -> per-token maximum = stabiliser b;
+//   pass 2: full scores minus b (-b is the C operand the score products of all latent tiles
+//           start from: one 16-register splat per token tile), 2^x, pack, and
+//           Y^T += Zaug^T . E with Zaug = [Z | 1].
+// Q (as A operand) and Z^T (as A operand, latents in the permuted order) live in registers
+// for the whole kernel; K streams from HBM straight into the B-operand layout; no LDS.
+// Each pass issues the MFMAs of latent tile t+1 before the vector work on tile t.
+// PRE = false (shapes whose operands would not fit otherwise): raw q, no lo term, and
+// 2^(|c2| s - b) formed with one v_fma_f32 per score.
+// ============================================================================================
+// MODE 0 writes y and, when lse_dec2 is not NULL, log sum_m exp(S[m][n]) (natural log) there.
+// MODE 1 (first step of the backward when nothing was saved) writes per token
+//   lse_dec2[n] = log2 sum_m 2^S2[m][n]   and   delta[n] = <dY_n, Y_n>   (Y_n kept in fp32).
+template <int DR, int MT, bool PRE, int MINB, int MODE, bool F>
+__global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
+    const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const float *__restrict__ z,
+    bf16_t *__restrict__ y, const bf16_t *__restrict__ dy, float *__restrict__ lse_dec2,
+    float *__restrict__ delta, TokStride ts, TokStride ts_y, int H, int N, int Mtot, int m0, float c2)
+{
+    // The kernel works on the latents m0 .. m0 + M of the head's Mtot (M = 32*MT of them); with more than
+    // one chunk its outputs are one chunk's partial result (y normalised within the chunk, lse_dec of the
+    // chunk) that decode_merge_kernel combines.  ts_y: where the rows of y go.
+    // Latents at or beyond Mtot are padding and cost no mask code in the loops: a padding latent gets the
+    // queries of the last real one (the clamped load), so its score never exceeds the real maximum and
+    // its weight is at most 1, and its row of Zaug -- the Z values and the 1 that feeds the denominator --
+    // is zero, so that weight multiplies zeros only.
+    constexpr int D = padded_dim(DR);
+    constexpr int KS = D / 16;   // k-steps of the score product
+    constexpr int HV = D / 16;   // 16-wide column groups of Z, each with its own ones row
+    constexpr bool PACK = PRE && pack_dim(DR);   // q' hi | lo in one operand, keys repeated in both lane halves
+    const int lane = threadIdx.x & 63, l32 = lane & 31, hh = lane >> 5;
+    const int wave = threadIdx.x >> 6;
+    const int bh = blockIdx.y, h = bh % H;
+    const bool flip = c2 < 0.f;
+    const float ac2 = PRE ? c2 : fabsf(c2);
+
+    bf16x8 qh[MT][KS], ql[MT][KS];
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+        const int m = m0 + 32 * t + l32;
+        load_q_operand<DR, PRE, F, PACK>(q + (size_t)h * ts.sq + (size_t)min(m, Mtot - 1) * DR, hh, c2, flip, qh[t],
+                                         ql[t]);
+    }
+    const int mleft = Mtot - m0;   // real latents from m0 on (may exceed the 32*MT this kernel covers)
+
+    // Zaug^T operand: row l32 (< 16: column 16*hv + l32 of Z; 16: ones; else zero).  In registers, or --
+    // for the shapes whose registers would not allow two waves per SIMD otherwise (ZLDS = !PRE) --
+    // built once per workgroup in LDS (the four waves share one (b,h)) and read per latent tile.
+    constexpr bool ZLDS = !PRE;
+    __shared__ __attribute__((aligned(16))) u32x4 zlds[ZLDS ? HV * 2 * MT * 64 : 1];
+    bf16x8 zt[ZLDS ? 1 : HV][ZLDS ? 1 : 2 * MT];
+    {
+        const float *zb = z + ((size_t)bh * Mtot + m0) * DR;
+#pragma unroll
+        for (int hv = 0; hv < HV; ++hv)
+#pragma unroll
+            for (int s = 0; s < 2 * MT; ++s) {
+                if (ZLDS && (s & 3) != wave) continue;   // each wave builds a quarter of the images
+                u32x4 w;
+#pragma unroll
+                for (int i = 0; i < 8; i += 2) {
+                    float a, b;
+                    if (l32 < 16 && 16 * hv + l32 < DR) {
+                        const int la = 32 * (s / 2) + perm_index(s % 2, hh, i);
+                        const int lb = 32 * (s / 2) + perm_index(s % 2, hh, i + 1);
+                        a = la < mleft ? zb[(size_t)la * DR + 16 * hv + l32] : 0.f;
+                        b = lb < mleft ? zb[(size_t)lb * DR + 16 * hv + l32] : 0.f;
+                    } else {   // row 16: ones (for the real latents), the rest: zero
+                        a = (l32 == 16 && 32 * (s / 2) + perm_index(s % 2, hh, i) < mleft) ? 1.f : 0.f;
+                        b = (l32 == 16 && 32 * (s / 2) + perm_index(s % 2, hh, i + 1) < mleft) ? 1.f : 0.f;
+                    }
+                    w[i / 2] = rne_bf16(a) | (rne_bf16(b) << 16);
+                }
+                if constexpr (ZLDS) zlds[(hv * 2 * MT + s) * 64 + lane] = w;
+                else zt[hv][s] = as_bf16x8(w);
+            }
+    }
+    if constexpr (ZLDS) __syncthreads();
+    auto z_op = [&](int hv, int s) {
+        if constexpr (ZLDS) return as_bf16x8(zlds[(hv * 2 * MT + s) * 64 + lane]);
+        else return zt[hv][s];
+    };
+
+    const bf16_t *kb = k + tok_base(ts, bh, H);
+    bf16_t *yb = y + tok_base(ts_y, bh, H);
+    const int tiles = (N + 31) / 32;
+    const int stride = gridDim.x * 4;
+    int tile = blockIdx.x * 4 + wave;
+    bf16x8 kt[KS], ktn[KS];
+    if (tile < tiles) {
+        const int nld = min(tile * 32 + l32, N - 1);
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+            kt[s] = as_bf16x8(row8_bf16<DR>(kb + tok_off(ts, nld), PACK ? 0 : (D / 2) * hh + 8 * s));
+    }
+    for (; tile < tiles; tile += stride) {
+        const int n = tile * 32 + l32;
+        {   // prefetch the keys of this wave's next tile (the last tile is simply loaded again)
+            const int tn = (tile + stride < tiles) ? tile + stride : tile;
+            const int nld = min(tn * 32 + l32, N - 1);
+#pragma unroll
+            for (int s = 0; s < KS; ++s)
+                ktn[s] = as_bf16x8(row8_bf16<DR>(kb + tok_off(ts, nld), PACK ? 0 : (D / 2) * hh + 8 * s));
+        }
+        auto qk_hi = [&](int t) {
+            f32x16 r = splat16(0.f);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) r = mfma_s<F>(qh[t][ks], kt[ks], r);
+            return r;
+        };
+
+        // pass 1: per-token maximum over the latents
+        float mx = -INFINITY;
+        f32x16 s_cur = qk_hi(0), s_next;
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            if (t + 1 < MT) s_next = qk_hi(t + 1);
+            sched_fence();
+            mx = max16(s_cur, mx);
+            s_cur = s_next;
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        // stabiliser: -max as the starting value of the score accumulators (PRE), or folded into the fma
+        const f32x16 cinit = splat16(PRE ? -mx : 0.f);
+        const float b2 = mx * ac2;
+        // The hi products are recomputed in pass 2 rather than kept (8 tiles x 16 registers would
+        // not fit); an opaque copy of the keys stops the compiler from merging the two passes.
+        bf16x8 kt2[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            u32x4 w = __builtin_bit_cast(u32x4, kt[ks]);
+            asm volatile("" : "+v"(w));
+            kt2[ks] = as_bf16x8(w);
+        }
+        auto qk_full = [&](int t) {
+            f32x16 r = cinit;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) r = mfma_s<F>(qh[t][ks], kt2[ks], r);
+            if constexpr (PRE && !PACK) {
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) r = mfma_s<F>(ql[t][ks], kt[ks], r);
+            }
+            return r;
+        };
+
+        // pass 2: per latent tile 2^x, pack, and the value product
+        f32x16 acc[HV];
+#pragma unroll
+        for (int hv = 0; hv < HV; ++hv) acc[hv] = splat16(0.f);
+        s_cur = qk_full(0);
+        sched_fence();
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            if (t + 1 < MT) s_next = qk_full(t + 1);
+            if constexpr (!(PRE && D == 16)) sched_fence();
+            if constexpr (!PRE) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) s_cur[i] = fmaf(s_cur[i], ac2, -b2);
+            }
+            bf16x8 p0, p1;
+            exp_pack(s_cur, p0, p1);
+#pragma unroll
+            for (int hv = 0; hv < HV; ++hv) {
+                acc[hv] = mfma(z_op(hv, 2 * t), p0, acc[hv]);
+                acc[hv] = mfma(z_op(hv, 2 * t + 1), p1, acc[hv]);
+            }
+            if constexpr (PRE && D == 16) {
+                // order within the tile: the two score products of tile t+1 (one when q' is packed) and the
+                // two value products of tile t, each followed by a share of the 16 exponentials and 8 packs
+                // of tile t
+                if (PACK && t + 1 < MT) {
+                    FLARE_GROUP_TRANS(4);
+                    FLARE_GROUP_MFMA(1);
+                    FLARE_GROUP_TRANS(4);
+                    FLARE_GROUP_VALU(4);
+                    FLARE_GROUP_MFMA(1);
+                    FLARE_GROUP_TRANS(8);
+                    FLARE_GROUP_VALU(4);
+                    FLARE_GROUP_MFMA(1);
+                } else if (t + 1 < MT) {
+                    FLARE_GROUP_TRANS(4);
+                    FLARE_GROUP_MFMA(1);
+                    FLARE_GROUP_TRANS(4);
+                    FLARE_GROUP_MFMA(1);
+                    FLARE_GROUP_VALU(4);
+                    FLARE_GROUP_TRANS(4);
+                    FLARE_GROUP_MFMA(1);
+                    FLARE_GROUP_TRANS(4);
+                    FLARE_GROUP_VALU(4);
+                    FLARE_GROUP_MFMA(1);
+                } else {
+                    FLARE_GROUP_TRANS(8);
+                    FLARE_GROUP_VALU(4);
+                    FLARE_GROUP_MFMA(1);
+                    FLARE_GROUP_TRANS(8);
+                    FLARE_GROUP_VALU(4);
+                    FLARE_GROUP_MFMA(1);
+                }
+            }
+            sched_fence();
+            s_cur = s_next;
+        }
+        // row 16 (register 8 of the lower lane half) is the softmax denominator
+        const float den = __shfl(acc[0][8], l32);
+        const float inv = 1.f / den;
+        if constexpr (MODE == 1) {
+            const size_t row = (size_t)bh * N + min(n, N - 1);
+            const bf16_t *gr = dy + tok_base(ts, bh, H) + tok_off(ts, min(n, N - 1));
+            float part = 0.f;
+#pragma unroll
+            for (int hv = 0; hv < HV; ++hv) {
+                u32x2 g0, g1;
+                g0[0] = 0u; g0[1] = 0u; g1[0] = 0u; g1[1] = 0u;
+                if (quartet_inside<DR>(hv, hh, 0)) g0 = *reinterpret_cast<const u32x2 *>(gr + 16 * hv + 4 * hh);
+                if (quartet_inside<DR>(hv, hh, 1)) g1 = *reinterpret_cast<const u32x2 *>(gr + 16 * hv + 8 + 4 * hh);
+                part = fmaf(acc[hv][0] * inv, dy_lo<F>(g0[0]), part);
+                part = fmaf(acc[hv][1] * inv, dy_hi<F>(g0[0]), part);
+                part = fmaf(acc[hv][2] * inv, dy_lo<F>(g0[1]), part);
+                part = fmaf(acc[hv][3] * inv, dy_hi<F>(g0[1]), part);
+                part = fmaf(acc[hv][4] * inv, dy_lo<F>(g1[0]), part);
+                part = fmaf(acc[hv][5] * inv, dy_hi<F>(g1[0]), part);
+                part = fmaf(acc[hv][6] * inv, dy_lo<F>(g1[1]), part);
+                part = fmaf(acc[hv][7] * inv, dy_hi<F>(g1[1]), part);
+            }
+            part += __shfl_xor(part, 32);
+            // the stabiliser that was actually subtracted
+            const float used = PRE ? mx : b2;
+            if (n < N && hh == 0) {
+                lse_dec2[row] = used + log2f(den);
+                delta[row] = part;
+            }
+        } else if (n < N) {
+            if (lse_dec2 && hh == 0) {   // optional saved statistic of the forward, natural log
+                const float used = PRE ? mx : b2;
+                lse_dec2[(size_t)bh * N + n] = (used + log2f(den)) * kLn2;
+            }
+#pragma unroll
+            for (int hv = 0; hv < HV; ++hv) {
+                u32x2 w0, w1;
+                w0[0] = pack_elems<F>(acc[hv][0] * inv, acc[hv][1] * inv);
+                w0[1] = pack_elems<F>(acc[hv][2] * inv, acc[hv][3] * inv);
+                w1[0] = pack_elems<F>(acc[hv][4] * inv, acc[hv][5] * inv);
+                w1[1] = pack_elems<F>(acc[hv][6] * inv, acc[hv][7] * inv);
+                if (quartet_inside<DR>(hv, hh, 0)) *reinterpret_cast<u32x2 *>(yb + tok_off(ts_y, n) + 16 * hv + 4 * hh) = w0;
+                if (quartet_inside<DR>(hv, hh, 1))
+                    *reinterpret_cast<u32x2 *>(yb + tok_off(ts_y, n) + 16 * hv + 8 + 4 * hh) = w1;
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < KS; ++s) kt[s] = ktn[s];
+    }
+}
+
+// ============================================================================================
+// Encode partials.  A workgroup has up to 4 waves; wave w works on latent group w % G (NB tiles
+// of 32 latents) and on every TG-th 32-token tile of the chunk, starting at tile w / G.  Per tile
+// and latent tile:
+//   S2^T - c = K . Q'^T  (rows = tokens, columns = latents; -c rides in a k-step of its own:
+//   key side 1 in slot 0, query side -c in slot 0, so that every lo term of q' stays in),
+//   lazy online softmax: c moves only when a score exceeds it by more than kLazy (or on the
+//   first tile), then O is rescaled; 2^x, pack; O^T += Vaug^T . P^T, Vaug = [V | 1].
+// V^T is formed through a wave-private, double-buffered LDS tile (no workgroup barrier
+// anywhere): the values of tile j+1 are written while tile j is computed and read back at its
+// end.  Keys are prefetched one tile ahead, values two.  The MFMAs of the next latent tile (or
+// of the next token tile) are issued before the vector work on the current one.
+// Output per wave: (c, row sums, unnormalised O) for its latents = one partial slot.
+// ============================================================================================
+// MODE 1 (second step of the backward) reuses the same machinery for dZ = R^T dY: the values are
+// dY, the weights are R^T[n][m] = 2^(S2 - lse_dec2[n]) with the per-token -lse_dec2 carried as a
+// hi + lo bf16 pair in one more k-step (token side: slots 2,3; query side: 1,1), and there is no
+// softmax state: only the unnormalised sums are written.  lse_dec2 is read as ld_mul * lse_dec2[n]
+// (ld_mul = log2 e when the array holds the forward's natural-log statistic).  When y_tok is given,
+// every wave also forms delta[n] = <dY_n, Y_n> from the rows it streams anyway (no branch in the
+// loop), and the waves of latent group 0 store it to delta_out for the two kernels that follow.
+// Those waves also record the smallest and largest lse_dec2 they met, ld_range[part] = (min, max),
+// from which bwd_plan_kernel decides which variant of the next two kernels may run.
+template <int DR, int NB, int MINB, int MODE, bool F>
+__global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
+    const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
+    const float *__restrict__ lse_dec2, float ld_mul, const bf16_t *__restrict__ y_tok,
+    float *__restrict__ delta_out, float *__restrict__ ld_range,
+    float *__restrict__ m_part, float *__restrict__ l_part, float *__restrict__ o_part,
+    TokStride ts, int H, int N, int M, int chunk_len, int parts, int G, int TG, float c2)
+{
+    constexpr int D = padded_dim(DR);
+    constexpr int KS = D / 16;
+    constexpr int HV = D / 16;
+    constexpr int ROWS = D + 2;                 // V^T rows, then a row of ones, then a row of zeros
+    constexpr bool PACK = pack_dim(DR);         // q' hi | lo in one operand, keys repeated in both lane halves
+    constexpr int BUF = ROWS * kVtStride;       // uint16 per buffer
+    __shared__ __attribute__((aligned(16))) uint16_t vt_all[4][2 * BUF];
+
+    const int lane = threadIdx.x & 63, l32 = lane & 31, hh = lane >> 5;
+    const int wave = threadIdx.x >> 6;
+    const int g = wave % G, tg = wave / G;
+    const int bh = blockIdx.y, h = bh % H, chunk = blockIdx.x;
+    const uint32_t keep0 = hh == 0 ? 0xffff0000u : 0xffffffffu;
+    uint16_t *vt = vt_all[wave];
+
+    // constant rows of the value operand, in both buffers
+    if (lane < kVtStride) {
+        vt[D * kVtStride + lane] = 0x3f80;
+        vt[(D + 1) * kVtStride + lane] = 0;
+        vt[BUF + D * kVtStride + lane] = 0x3f80;
+        vt[BUF + (D + 1) * kVtStride + lane] = 0;
+    }
+
+    const int lat0 = 32 * NB * (G * (int)blockIdx.z + g);   // a workgroup owns NB*G tiles of latents
+    bf16x8 qh[NB][KS], ql[NB][KS];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {   // padding latents (at or beyond M): zero queries, nothing stored
+        const int m = lat0 + 32 * b + l32;
+        load_q_operand<DR, true, F, PACK>(q + (size_t)h * ts.sq + (size_t)min(m, M - 1) * DR, hh, c2, false, qh[b],
+                                          ql[b]);
+        if (m >= M) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) { qh[b][ks] = zero_operand(); ql[b][ks] = zero_operand(); }
+        }
+    }
+    u32x4 wzero;
+    wzero[0] = 0u; wzero[1] = 0u; wzero[2] = 0u; wzero[3] = 0u;
+    bf16x8 caug[MODE == 0 ? NB : 1];             // query side of the stabiliser k-step: slot 0 := -c
+#pragma unroll
+    for (int b = 0; b < (MODE == 0 ? NB : 1); ++b) caug[b] = as_bf16x8(wzero);
+
+    const bf16_t *kb = k + tok_base(ts, bh, H);
+    const bf16_t *vb = v + tok_base(ts, bh, H);
+    const int n0 = chunk * chunk_len;
+    const int n1 = min(N, n0 + chunk_len);
+    const int tiles = (n1 - n0 + 31) / 32;
+    const int cnt = (tiles > tg) ? (tiles - tg + TG - 1) / TG : 0;   // tiles of this wave
+
+    float c[NB];
+    float nl_min = INFINITY, nl_max = -INFINITY;   // range of -lse_dec2 over this wave's tokens (MODE 1)
+    f32x16 o[NB][HV];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        c[b] = 0.f;
+#pragma unroll
+        for (int hv = 0; hv < HV; ++hv) o[b][hv] = splat16(0.f);
+    }
+
+    // row of the value operand this lane supplies for column group hv
+    int vrow[HV];
+#pragma unroll
+    for (int hv = 0; hv < HV; ++hv) vrow[hv] = (l32 < 16) ? 16 * hv + l32 : (l32 == 16 ? D : D + 1);
+
+    // keys: A operand, row = token.  values: 32 tokens x D in 16-byte pieces, two lanes per token.
+    constexpr int PIECES = D / 8;          // 16-byte pieces per token row
+    constexpr int LOADS = PIECES / 2;      // pieces per lane (64 lanes cover 32 tokens x 2 pieces)
+    const int vtok = lane >> 1;
+    auto tile_tok0 = [&](int j) { return n0 + 32 * (tg + min(j, cnt - 1) * TG); };   // j-th tile of this wave
+    auto load_k = [&](int j, bf16x8 (&kk)[KS]) {
+        const int nk = min(tile_tok0(j) + l32, N - 1);
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+            kk[s] = as_bf16x8(row8_bf16<DR>(kb + tok_off(ts, nk), PACK ? 0 : (D / 2) * hh + 8 * s));
+    };
+    auto load_v = [&](int j, u32x4 (&vv)[LOADS]) {
+        const int nv = min(tile_tok0(j) + vtok, N - 1);
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i)
+            vv[i] = row8_bf16<DR>(vb + tok_off(ts, nv), 8 * ((lane & 1) * LOADS + i));
+    };
+    auto write_vt = [&](const u32x4 (&vv)[LOADS], uint16_t *buf) {   // transposed: row = column of V
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) {
+            const int d0 = 8 * ((lane & 1) * LOADS + i);
+            const u32x4 wv = to_bf16_row<F>(vv[i]);   // the value side of the second product is bf16
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                buf[(d0 + 2 * e) * kVtStride + vtok] = (uint16_t)(wv[e] & 0xffffu);
+                buf[(d0 + 2 * e + 1) * kVtStride + vtok] = (uint16_t)(wv[e] >> 16);
+            }
+        }
+    };
+    auto read_va = [&](const uint16_t *buf, bf16x8 (&va)[HV][2]) {
+#pragma unroll
+        for (int hv = 0; hv < HV; ++hv)
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+                const uint16_t *row = buf + vrow[hv] * kVtStride + 16 * s2 + 4 * hh;
+                const u32x2 a = *reinterpret_cast<const u32x2 *>(row);
+                const u32x2 b = *reinterpret_cast<const u32x2 *>(row + 8);
+                u32x4 w;
+                w[0] = a[0]; w[1] = a[1]; w[2] = b[0]; w[3] = b[1];
+                va[hv][s2] = as_bf16x8(w);
+            }
+    };
+    u32x4 w23;
+    w23[0] = 0u; w23[1] = hh == 0 ? kOnePair<F> : 0u; w23[2] = 0u; w23[3] = 0u;
+    const bf16x8 ones23 = as_bf16x8(w23);      // query side of the correction k-step: slots 2,3 = 1
+    // scores minus the stabiliser of latent tile b against the token tile (kk; kk0a = key side of the correction k-step)
+    auto qk = [&](int b, const bf16x8 (&kk)[KS], bf16x8 kk0a) {
+        f32x16 r = splat16(0.f);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) r = mfma_s<F>(kk[ks], qh[b][ks], r);
+        if constexpr (!PACK) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) r = mfma_s<F>(kk[ks], ql[b][ks], r);
+        }
+        r = mfma_s<F>(kk0a, MODE == 0 ? caug[MODE == 0 ? b : 0] : ones23, r);
+        return r;
+    };
+    const uint32_t one0 = hh == 0 ? kOne<F> : 0u;
+    const float *lb = (MODE == 1) ? lse_dec2 + (size_t)bh * N : nullptr;
+    // Key operand of the correction k-step.  MODE 0: slot 0 := 1, else zero.  MODE 1: zero except
+    // slots 2,3 := -lse_dec2 of this lane's token (hi + lo pair).
+    auto k_aug = [&](bf16x8 k0, float neg_lse) {
+        if constexpr (MODE == 0) return with_slot0(as_bf16x8(wzero), keep0, one0);
+        else {
+            u32x4 w;
+            w[0] = 0u; w[2] = 0u; w[3] = 0u;
+            w[1] = hh == 0 ? split_pair<F>(neg_lse) : 0u;
+            return as_bf16x8(w);
+        }
+    };
+    auto load_lse = [&](int j) {
+        if constexpr (MODE == 1) return -lb[min(tile_tok0(j) + l32, N - 1)] * ld_mul;
+        else return 0.f;
+    };
+    // delta of the wave's j-th tile (j < cnt) from its dY and Y rows: two lanes per token
+    const bool do_delta = (MODE == 1) && y_tok != nullptr && blockIdx.z == 0;
+    const bf16_t *yb = (MODE == 1 && y_tok != nullptr) ? y_tok + tok_base(ts, bh, H) : vb;
+    auto load_y = [&](int j, u32x4 (&yy)[LOADS]) {
+        const int nv = min(tile_tok0(j) + vtok, N - 1);
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i)
+            yy[i] = row8_bf16<DR>(yb + tok_off(ts, nv), 8 * ((lane & 1) * LOADS + i));
+    };
+    auto put_delta = [&](int j, const u32x4 (&gv)[LOADS], const u32x4 (&yy)[LOADS]) {
+        float part = 0.f;
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                part = fmaf(dy_lo<F>(gv[i][e]), elem_lo<F>(yy[i][e]), part);
+                part = fmaf(dy_hi<F>(gv[i][e]), elem_hi<F>(yy[i][e]), part);
+            }
+        // the other half of the row is in the neighbouring lane: quad_perm [1,0,3,2]
+        part += __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(part), 0xB1, 0xf, 0xf, true));
+        const int n = n0 + 32 * (tg + j * TG) + vtok;
+        if (do_delta && j < cnt && g == 0 && (lane & 1) == 0 && n < n1) delta_out[(size_t)bh * N + n] = part;
+    };
+
+    if (cnt > 0) {
+        bf16x8 kt[KS], ktn[KS], va[HV][2];
+        u32x4 vr1[LOADS], vr2[LOADS], yr1[LOADS], yr2[LOADS];
+        f32x16 S[NB];
+        bool first = true;
+
+        // prologue: tile 0 fully staged, tile 1's values in flight
+        float nl = load_lse(0), nln = 0.f;
+        load_k(0, kt);
+        load_v(0, vr1);
+        if (do_delta) {
+            load_y(0, yr1);
+            put_delta(0, vr1, yr1);
+            load_y(1, yr1);
+        }
+        compiler_fence();
+        write_vt(vr1, vt);
+        compiler_fence();
+        read_va(vt, va);
+        load_v(1, vr1);
+#pragma unroll
+        for (int b = 0; b < NB; ++b) S[b] = splat16(0.f);
+        S[0] = qk(0, kt, k_aug(kt[0], nl));
+
+        for (int j = 0; j < cnt; ++j) {
+            const int tok0 = tile_tok0(j);
+            uint16_t *buf_next = vt + ((j + 1) & 1) * BUF;
+            nln = load_lse(j + 1);
+            load_k(j + 1, ktn);
+            load_v(j + 2, vr2);
+            if constexpr (MODE == 1) {
+                // (when y_tok is NULL, yb aliases the dY rows: the loads stay in bounds, nothing is stored)
+                load_y(j + 2, yr2);
+                put_delta(j + 1, vr1, yr1);   // vr1, yr1: rows of tile j+1 (nothing stored past the last tile)
+            }
+            compiler_fence();
+            write_vt(vr1, buf_next);          // values of tile j+1
+            compiler_fence();
+            const bf16x8 kt0a = k_aug(kt[0], nl);
+
+            // register r of this lane holds token tok0 + 8*(r/4) + 4*hh + r%4: valid iff 8*(r/4) + r%4 < rem
+            const int rem = n1 - tok0 - 4 * hh;
+            const bool partial = tok0 + 32 > n1;
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                // issue the next score product first: the next latent tile, or tile 0 of the next tokens
+                f32x16 nxt;
+                if (b + 1 < NB) nxt = qk(b + 1, kt, kt0a);
+                else nxt = qk(0, ktn, k_aug(ktn[0], nln));
+                sched_fence();
+                f32x16 sc = S[b];
+                if (partial) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (8 * (r / 4) + (r % 4) >= rem) sc[r] = -INFINITY;
+                }
+                float mx = (MODE == 0) ? max16(sc, -INFINITY) : 0.f;
+                if (MODE == 0 && (first || __any(mx > kLazy))) {
+                    mx = fmaxf(mx, __shfl_xor(mx, 32));   // both lane halves hold tokens of the same latent
+                    const float cn = elem_round<F>(c[b] + (first ? mx : fmaxf(mx, 0.f)));
+                    const float shift = cn - c[b];
+                    if (!first) {
+                        const float f = fast_exp2(-shift);
+#pragma unroll
+                        for (int hv = 0; hv < HV; ++hv)
+#pragma unroll
+                            for (int i = 0; i < 16; ++i) o[b][hv][i] *= f;
+                    }
+                    c[b] = cn;
+                    caug[b] = with_slot0(caug[b], keep0, hh == 0 ? rne_elem<F>(-cn) : 0u);
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) sc[i] -= shift;
+                    if constexpr (NB == 1) {   // the product already in flight is for this same latent tile
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) nxt[i] -= shift;
+                    }
+                }
+                bf16x8 p0, p1;
+                exp_pack(sc, p0, p1);
+#pragma unroll
+                for (int hv = 0; hv < HV; ++hv) {
+                    o[b][hv] = mfma(va[hv][0], p0, o[b][hv]);
+                    o[b][hv] = mfma(va[hv][1], p1, o[b][hv]);
+                }
+                sched_fence();
+                S[(b + 1) % NB] = nxt;
+            }
+            first = false;
+            if constexpr (MODE == 1) { nl_min = fminf(nl_min, nl); nl_max = fmaxf(nl_max, nl); }
+            nl = nln;
+            compiler_fence();
+            read_va(buf_next, va);            // value operand of tile j+1 (written at the top of this iteration)
+#pragma unroll
+            for (int s = 0; s < KS; ++s) kt[s] = ktn[s];
+#pragma unroll
+            for (int i = 0; i < LOADS; ++i) vr1[i] = vr2[i];
+            if (do_delta) {
+#pragma unroll
+                for (int i = 0; i < LOADS; ++i) yr1[i] = yr2[i];
+            }
+        }
+    }
+
+    // partial slot of this wave: (bh, chunk*TG + tg), latents lat0 .. lat0 + 32*NB
+    if (tg >= TG) return;
+    const size_t part = (size_t)bh * parts + (size_t)chunk * TG + tg;
+    if (MODE == 1 && ld_range != nullptr && g == 0 && blockIdx.z == 0) {
+#pragma unroll
+        for (int off = 1; off < 32; off <<= 1) {   // both lane halves hold the same tokens
+            nl_min = fminf(nl_min, __shfl_xor(nl_min, off));
+            nl_max = fmaxf(nl_max, __shfl_xor(nl_max, off));
+        }
+        if (lane == 0) {   // a wave without tiles leaves (+inf, -inf): neutral
+            ld_range[2 * part] = -nl_max;
+            ld_range[2 * part + 1] = -nl_min;
+        }
+    }
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        if (lat0 + 32 * b + l32 >= M) continue;
+        const size_t slot = part * M + lat0 + 32 * b + l32;
+        if (MODE == 0 && hh == 0) {
+            m_part[slot] = (cnt > 0) ? c[b] : -INFINITY;
+            l_part[slot] = o[b][0][8];
+        }
+#pragma unroll
+        for (int hv = 0; hv < HV; ++hv) {
+            float4 lo4 = make_float4(o[b][hv][0], o[b][hv][1], o[b][hv][2], o[b][hv][3]);
+            float4 hi4 = make_float4(o[b][hv][4], o[b][hv][5], o[b][hv][6], o[b][hv][7]);
+            if (quartet_inside<DR>(hv, hh, 0)) *reinterpret_cast<float4 *>(o_part + slot * DR + 16 * hv + 4 * hh) = lo4;
+            if (quartet_inside<DR>(hv, hh, 1)) *reinterpret_cast<float4 *>(o_part + slot * DR + 16 * hv + 8 + 4 * hh) = hi4;
+        }
+    }
+}
+
+// ============================================================================================
+// Companion matrix of the spectral analysis (Appendix C.1, Algorithm 1, steps 1-4 and the product of
+// step 5):   G = J J^T,   J[m][n] = exp(S[m][n] - (lse_enc[m] + lse_dec[n]) / 2) = (P[m][n] R[n][m])^(1/2).
+// A workgroup has one wave per 32-latent tile and walks over the 32-token tiles of its chunk.  Per
+// token tile every wave forms its own J^T tile (rows = tokens, columns = its latents; both
+// half-normalisers ride in one correction k-step), rounds it to bf16 and publishes it in LDS; after
+// one barrier it multiplies its tile with every wave's tile: the packed accumulator layout is at
+// once a valid A operand (row = latent) and B operand (column = latent) over the same permuted
+// token order.  LDS is double-buffered, so one barrier per token tile suffices.
+// Output: the chunk's partial G, [b*h][chunk][M][M] fp32, summed in chunk order afterwards.
+// ============================================================================================
+template <int DR, int MT>
+__global__ __launch_bounds__(64 * MT) void gram_mfma_kernel(
+    const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const float *__restrict__ lse_enc,
+    const float *__restrict__ lse_dec, float *__restrict__ g_part, TokStride ts, int H, int N, int chunk_len,
+    int chunks, float c2)
+{
+    constexpr int D = padded_dim(DR);
+    constexpr int KS = D / 16;
+    constexpr int M = 32 * MT;
+    __shared__ __attribute__((aligned(16))) u32x4 jt[2][MT][2][64];
+    const int lane = threadIdx.x & 63, l32 = lane & 31, hh = lane >> 5;
+    const int wave = threadIdx.x >> 6;
+    const int bh = blockIdx.y, h = bh % H, chunk = blockIdx.x;
+    const bool lower = hh == 0;
+
+    bf16x8 qh[KS], ql[KS];
+    load_q_operand<DR, true, false>(q + (size_t)h * ts.sq + (size_t)(32 * wave + l32) * DR, hh, c2, false, qh, ql);
+    u32x4 wq;
+    wq[0] = lower ? split_bf16_pair(-0.5f * kLog2e * lse_enc[(size_t)bh * M + 32 * wave + l32]) : 0u;
+    wq[1] = lower ? 0x3f803f80u : 0u;      // slots 2,3 := 1 (pick the token's half-normaliser)
+    wq[2] = 0u; wq[3] = 0u;
+    const bf16x8 q_aug = as_bf16x8(wq);
+
+    const bf16_t *kb = k + tok_base(ts, bh, H);
+    const float *lb = lse_dec + (size_t)bh * N;
+    const int n0 = chunk * chunk_len;
+    const int n1 = min(N, n0 + chunk_len);
+    const int tiles = (n1 - n0 + 31) / 32;
+    f32x16 acc[MT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t) acc[t] = splat16(0.f);
+
+    for (int j = 0; j < tiles; ++j) {
+        const int tok0 = n0 + 32 * j;
+        const int n = min(tok0 + l32, N - 1);
+        bf16x8 kt[KS];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) kt[s] = as_bf16x8(row8_bf16<DR>(kb + tok_off(ts, n), (D / 2) * hh + 8 * s));
+        u32x4 wk;
+        wk[0] = lower ? 0x3f803f80u : 0u;                                      // slots 0,1 := 1
+        wk[1] = lower ? split_bf16_pair(-0.5f * kLog2e * lb[n]) : 0u;          // slots 2,3 := -lse_dec2[n] / 2
+        wk[2] = 0u; wk[3] = 0u;
+        f32x16 x = splat16(0.f);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) x = mfma(kt[ks], qh[ks], x);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) x = mfma(kt[ks], ql[ks], x);
+        x = mfma(as_bf16x8(wk), q_aug, x);
+        if (tok0 + 32 > n1) {   // rows past the chunk's end contribute nothing
+            const int rem = n1 - tok0 - 4 * hh;
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                if (8 * (r / 4) + (r % 4) >= rem) x[r] = -INFINITY;
+        }
+        bf16x8 p0, p1;
+        exp_pack(x, p0, p1);
+        u32x4 (*buf)[2][64] = jt[j & 1];
+        buf[wave][0][lane] = __builtin_bit_cast(u32x4, p0);
+        buf[wave][1][lane] = __builtin_bit_cast(u32x4, p1);
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            acc[t] = mfma(p0, as_bf16x8(buf[t][0][lane]), acc[t]);
+            acc[t] = mfma(p1, as_bf16x8(buf[t][1][lane]), acc[t]);
+        }
+    }
+    float *out = g_part + ((size_t)bh * chunks + chunk) * M * M;
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = 32 * wave + 8 * (r / 4) + 4 * hh + (r % 4);
+            out[(size_t)row * M + 32 * t + l32] = acc[t][r];
+        }
+}
+
+}  // namespace
+
+bool mfma_supported(const flare_shape &s)
+{
+    if (s.dtype != FLARE_BF16 && s.dtype != FLARE_F16) return false;
+    if (s.d != 4 && s.d != 8 && s.d != 16 && s.d != 32) return false;   // d < 16 runs padded to 16
+    return s.M <= 2048;   // any number of latents: tiles of 32, the last ones padded
+}
+
+MfmaPlan mfma_plan(const flare_shape &s)
+{
+    MfmaPlan p;
+    const EncGeom e = enc_geom(lat_eff(s.M), padded_dim(s.d));
+    const int BH = s.B * s.H;
+    // each chunk gives every token group at least 8 tiles of 32 tokens
+    p.enc = plan_split(s.N, BH, 256 * e.TG, kEncodeTargetBlocks);
+    p.parts = p.enc.chunks * e.TG;
+    return p;
+}
+
+size_t mfma_fwd_bytes(const flare_shape &s)
+{
+    const MfmaPlan p = mfma_plan(s);
+    Split sp;
+    sp.chunks = p.parts;
+    sp.chunk_len = 0;
+    return valu_fwd_layout(s, sp, nullptr, nullptr, nullptr, nullptr);
+}
+
+int mfma_encode(const flare_shape &s, const void *q, const void *k, const void *v, float *z, float *lse_enc,
+                float scale, void *ws, hipStream_t stream)
+{
+    const MfmaPlan p = mfma_plan(s);
+    const EncGeom e = enc_geom(lat_eff(s.M), padded_dim(s.d));
+    Split sp;
+    sp.chunks = p.parts;
+    sp.chunk_len = 0;
+    float *m_part, *l_part, *o_part;
+    valu_fwd_layout(s, sp, ws, &m_part, &l_part, &o_part);
+    const int BH = s.B * s.H;
+    const float c2 = scale * kLog2e;
+    const dim3 grid(p.enc.chunks, BH, lat_chunks(s.M));
+    const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *vv = (const bf16_t *)v;
+    {
+        LaunchTimer t(KID_ENCODE_PARTIAL, stream);
+        const bool f16 = s.dtype == FLARE_F16;
+#define FLARE_ENC(DD, NBB)                                                                                        \
+    do {                                                                                                          \
+        if (f16)                                                                                                  \
+            encode_mfma_kernel<DD, NBB, 2, 0, true><<<grid, e.threads, 0, stream>>>(                              \
+                qq, kk, vv, nullptr, 1.f, nullptr, nullptr, nullptr, m_part, l_part, o_part, tok_stride(s), s.H,  \
+                s.N, s.M, p.enc.chunk_len, p.parts, e.G, e.TG, c2);                                               \
+        else                                                                                                      \
+            encode_mfma_kernel<DD, NBB, 2, 0, false><<<grid, e.threads, 0, stream>>>(                             \
+                qq, kk, vv, nullptr, 1.f, nullptr, nullptr, nullptr, m_part, l_part, o_part, tok_stride(s), s.H,  \
+                s.N, s.M, p.enc.chunk_len, p.parts, e.G, e.TG, c2);                                               \
+    } while (0)
+#define FLARE_ENC_NB(DD)                   \
+    do {                                   \
+        if (e.NB == 1) FLARE_ENC(DD, 1);   \
+        else if (e.NB == 2) FLARE_ENC(DD, 2); \
+        else FLARE_ENC(DD, 4);             \
+    } while (0)
+        switch (s.d) {
+            case 4: FLARE_ENC_NB(4); break;
+            case 8: FLARE_ENC_NB(8); break;
+            case 16: FLARE_ENC_NB(16); break;
+            default:
+                if (e.NB == 1) FLARE_ENC(32, 1);
+                else FLARE_ENC(32, 2);
+        }
+#undef FLARE_ENC_NB
+#undef FLARE_ENC
+    }
+    if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
+    return launch_encode_merge(s, m_part, l_part, o_part, z, lse_enc, p.parts, stream);
+}
+
+// dZ partials of the backward (the encode machinery with values dY and weights R^T)
+int mfma_dz_partial(const flare_shape &s, const void *q, const void *k, const void *dy, const float *lse_dec2,
+                    float ld_mul, const void *y, float *delta_out, float *ld_range, float *dz_part, float scale,
+                    hipStream_t stream)
+{
+    const MfmaPlan p = mfma_plan(s);
+    const EncGeom e = enc_geom(lat_eff(s.M), padded_dim(s.d));
+    const int BH = s.B * s.H;
+    const float c2 = scale * kLog2e;
+    const dim3 grid(p.enc.chunks, BH, lat_chunks(s.M));
+    const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *gg = (const bf16_t *)dy;
+    LaunchTimer t(KID_BWD_DZ_PARTIAL, stream);
+    const bool f16 = s.dtype == FLARE_F16;
+#define FLARE_DZ(DD, NBB)                                                                                         \
+    do {                                                                                                          \
+        if (f16)                                                                                                  \
+            encode_mfma_kernel<DD, NBB, 2, 1, true><<<grid, e.threads, 0, stream>>>(                              \
+                qq, kk, gg, lse_dec2, ld_mul, (const bf16_t *)y, delta_out, ld_range, nullptr, nullptr, dz_part,  \
+                tok_stride(s), s.H, s.N, s.M, p.enc.chunk_len, p.parts, e.G, e.TG, c2);                           \
+        else                                                                                                      \
+            encode_mfma_kernel<DD, NBB, 2, 1, false><<<grid, e.threads, 0, stream>>>(                             \
+                qq, kk, gg, lse_dec2, ld_mul, (const bf16_t *)y, delta_out, ld_range, nullptr, nullptr, dz_part,  \
+                tok_stride(s), s.H, s.N, s.M, p.enc.chunk_len, p.parts, e.G, e.TG, c2);                           \
+    } while (0)
+#define FLARE_DZ_NB(DD)                   \
+    do {                                  \
+        if (e.NB == 1) FLARE_DZ(DD, 1);   \
+        else if (e.NB == 2) FLARE_DZ(DD, 2); \
+        else FLARE_DZ(DD, 4);             \
+    } while (0)
+    switch (s.d) {
+        case 4: FLARE_DZ_NB(4); break;
+        case 8: FLARE_DZ_NB(8); break;
+        case 16: FLARE_DZ_NB(16); break;
+        default:
+            if (e.NB == 1) FLARE_DZ(32, 1);
+            else FLARE_DZ(32, 2);
+    }
+#undef FLARE_DZ_NB
+#undef FLARE_DZ
+    return check_launch();
+}
+
+template <int MODE>
+static int launch_decode_family(const flare_shape &s, const void *q, const void *k, const float *z, void *y,
+                                TokStride ts_y, const void *dy, float *lse_dec2, float *delta, int m0, int Mc,
+                                float scale, hipStream_t stream)
+{
+    const int BH = s.B * s.H;
+    const int tiles = (s.N + 31) / 32;
+    int blocks = (kDecodeTargetBlocks + BH - 1) / BH;
+    if (blocks > (tiles + 3) / 4) blocks = (tiles + 3) / 4;
+    const dim3 grid(blocks, BH);
+    const float c2 = scale * kLog2e;
+    const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *gg = (const bf16_t *)dy;
+    bf16_t *yy = (bf16_t *)y;
+    LaunchTimer t(MODE == 0 ? KID_DECODE : KID_BWD_TOKEN_STATS, stream);
+    const bool f16 = s.dtype == FLARE_F16;
+#define FLARE_DEC_ARGS qq, kk, z, yy, gg, lse_dec2, delta, tok_stride(s), ts_y, s.H, s.N, s.M, m0, c2
+#define FLARE_DEC(DD, MTT, PREE, MINB)                                                                          \
+    do {                                                                                                        \
+        if (f16)                                                                                                \
+            decode_mfma_kernel<DD, MTT, PREE, MINB, MODE, true><<<grid, 256, 0, stream>>>(FLARE_DEC_ARGS);      \
+        else                                                                                                    \
+            decode_mfma_kernel<DD, MTT, PREE, MINB, MODE, false><<<grid, 256, 0, stream>>>(FLARE_DEC_ARGS);     \
+    } while (0)
+    const int MT = Mc / 32;
+#define FLARE_DEC_MT(DD)                               \
+    switch (MT) {                                      \
+        case 1: FLARE_DEC(DD, 1, true, 2); break;      \
+        case 2: FLARE_DEC(DD, 2, true, 2); break;      \
+        case 4: FLARE_DEC(DD, 4, true, 2); break;      \
+        case 6: FLARE_DEC(DD, 6, true, 2); break;      \
+        case 8: FLARE_DEC(DD, 8, true, 2); break;      \
+        default: return FLARE_EUNSUPPORTED;            \
+    }
+    if (s.d == 4) {
+        FLARE_DEC_MT(4)
+    } else if (s.d == 8) {
+        FLARE_DEC_MT(8)
+    } else if (s.d == 16) {
+        FLARE_DEC_MT(16)
+    } else {
+        switch (MT) {
+            case 1: FLARE_DEC(32, 1, true, 2); break;
+            case 2: FLARE_DEC(32, 2, true, 2); break;
+            case 4: FLARE_DEC(32, 4, true, 2); break;
+            case 6: FLARE_DEC(32, 6, false, 2); break;
+            case 8: FLARE_DEC(32, 8, false, 2); break;
+            default: return FLARE_EUNSUPPORTED;
+        }
+    }
+#undef FLARE_DEC_MT
+#undef FLARE_DEC
+#undef FLARE_DEC_ARGS
+    return check_launch();
+}
+
+namespace {
+// Combine the per-chunk results of the decode (M > 256): for token n of (b,h),
+//   lse = log sum_c exp(lse_c),   y = sum_c exp(lse_c - lse) y_c        (softmax over all M latents).
+// MODE 0 writes y in the caller's layout and, when asked, lse_dec (natural log);
+// MODE 1 writes lse_dec2 = lse * log2(e) and delta = <dY_n, y> with y kept in fp32.
+// thread = token; the partial rows are [chunk][b*h][n][DR] bf16, the partial lse [chunk][b*h][n].
+template <int DR, int MODE, bool F>
+__global__ __launch_bounds__(256) void decode_merge_kernel(
+    const bf16_t *__restrict__ y_part, const float *__restrict__ lse_part, int chunks, bf16_t *__restrict__ y,
+    const bf16_t *__restrict__ dy, float *__restrict__ lse_out, float *__restrict__ delta, TokStride ts, int H,
+    int N, size_t rows_all)
+{
+    const int n = blockIdx.x * 256 + threadIdx.x;
+    if (n >= N) return;
+    const int bh = blockIdx.y;
+    const size_t row = (size_t)bh * N + n;
+    float mx = -INFINITY;
+    for (int c = 0; c < chunks; ++c) mx = fmaxf(mx, lse_part[(size_t)c * rows_all + row]);
+    float acc[DR], tot = 0.f;
+#pragma unroll
+    for (int j = 0; j < DR; ++j) acc[j] = 0.f;
+    for (int c = 0; c < chunks; ++c) {
+        const float w = __expf(lse_part[(size_t)c * rows_all + row] - mx);
+        tot += w;
+        const bf16_t *src = y_part + ((size_t)c * rows_all + row) * DR;
+#pragma unroll
+        for (int j = 0; j < DR; j += 4) {
+            const u32x2 t = *reinterpret_cast<const u32x2 *>(src + j);
+            acc[j] = fmaf(w, elem_lo<F>(t[0]), acc[j]);
+            acc[j + 1] = fmaf(w, elem_hi<F>(t[0]), acc[j + 1]);
+            acc[j + 2] = fmaf(w, elem_lo<F>(t[1]), acc[j + 2]);
+            acc[j + 3] = fmaf(w, elem_hi<F>(t[1]), acc[j + 3]);
+        }
+    }
+    const float inv = 1.f / tot;
+    const float lse = mx + __logf(tot);
+    const size_t trow = tok_base(ts, bh, H) + tok_off(ts, n);
+    if constexpr (MODE == 0) {
+#pragma unroll
+        for (int j = 0; j < DR; j += 4) {
+            u32x2 w;
+            w[0] = pack_elems<F>(acc[j] * inv, acc[j + 1] * inv);
+            w[1] = pack_elems<F>(acc[j + 2] * inv, acc[j + 3] * inv);
+            *reinterpret_cast<u32x2 *>(y + trow + j) = w;
+        }
+        if (lse_out) lse_out[row] = lse;
+    } else {
+        float dl = 0.f;
+#pragma unroll
+        for (int j = 0; j < DR; j += 4) {
+            const u32x2 g = *reinterpret_cast<const u32x2 *>(dy + trow + j);
+            dl = fmaf(acc[j] * inv, dy_lo<F>(g[0]), dl);
+            dl = fmaf(acc[j + 1] * inv, dy_hi<F>(g[0]), dl);
+            dl = fmaf(acc[j + 2] * inv, dy_lo<F>(g[1]), dl);
+            dl = fmaf(acc[j + 3] * inv, dy_hi<F>(g[1]), dl);
+        }
+        lse_out[row] = lse * kLog2e;
+        delta[row] = dl;
+    }
+}
+}  // namespace
+
+// bytes of the per-chunk partial results of the token-major forward kernels (0 when M <= 256)
+size_t mfma_tok_part_bytes(const flare_shape &s)
+{
+    if (s.M <= kLatChunk) return 0;
+    const size_t rows = (size_t)s.B * s.H * s.N * lat_chunks(s.M);
+    return ((rows * s.d * 2 + 255) & ~(size_t)255) + ((rows * 4 + 255) & ~(size_t)255);
+}
+
+// decode (MODE 0) or token statistics (MODE 1) over all latents, in chunks of 256 when there are more
+template <int MODE>
+static int decode_all(const flare_shape &s, const void *q, const void *k, const float *z, void *y, const void *dy,
+                      float *lse_out, float *delta, float scale, void *ws, hipStream_t stream)
+{
+    if (s.M <= kLatChunk)
+        return launch_decode_family<MODE>(s, q, k, z, y, tok_stride(s), dy, lse_out, delta, 0, lat_eff(s.M), scale,
+                                          stream);
+    const int C = lat_chunks(s.M);
+    const size_t rows = (size_t)s.B * s.H * s.N;
+    bf16_t *y_part = static_cast<bf16_t *>(ws);
+    float *lse_part = reinterpret_cast<float *>(static_cast<char *>(ws) + ((rows * C * s.d * 2 + 255) & ~(size_t)255));
+    const TokStride tp{(long long)s.H * s.N * s.d, (long long)s.N * s.d, s.d, 0};   // partial rows: [b][h][n][d]
+    for (int c = 0; c < C; ++c) {
+        const int rc = launch_decode_family<0>(s, q, k, z, y_part + (size_t)c * rows * s.d, tp, nullptr,
+                                               lse_part + (size_t)c * rows, nullptr, c * kLatChunk, kLatChunk, scale,
+                                               stream);
+        if (rc != FLARE_OK) return rc;
+    }
+    const dim3 grid((s.N + 255) / 256, s.B * s.H);
+    LaunchTimer t(KID_DECODE_MERGE, stream);
+    const bool f16 = s.dtype == FLARE_F16;
+#define FLARE_DM(DD)                                                                                               \
+    do {                                                                                                           \
+        if (f16)                                                                                                   \
+            decode_merge_kernel<DD, MODE, true><<<grid, 256, 0, stream>>>(                                         \
+                y_part, lse_part, C, (bf16_t *)y, (const bf16_t *)dy, lse_out, delta, tok_stride(s), s.H, s.N, rows); \
+        else                                                                                                       \
+            decode_merge_kernel<DD, MODE, false><<<grid, 256, 0, stream>>>(                                        \
+                y_part, lse_part, C, (bf16_t *)y, (const bf16_t *)dy, lse_out, delta, tok_stride(s), s.H, s.N, rows); \
+    } while (0)
+    switch (s.d) {
+        case 4: FLARE_DM(4); break;
+        case 8: FLARE_DM(8); break;
+        case 16: FLARE_DM(16); break;
+        default: FLARE_DM(32); break;
+    }
+#undef FLARE_DM
+    return check_launch();
+}
+
+// partial companion matrices [b*h][chunk][M][M]; the split of the token axis is returned in *sp
+bool mfma_gram_supported(const flare_shape &s)
+{
+    return mfma_supported(s) && s.dtype == FLARE_BF16 && (s.M == 32 || s.M == 64 || s.M == 128 || s.M == 256);
+}
+
+int mfma_gram_partial(const flare_shape &s, const Split &sp, const void *q, const void *k, const float *lse_enc,
+                      const float *lse_dec, float *g_part, float scale, hipStream_t stream)
+{
+    const dim3 grid(sp.chunks, s.B * s.H);
+    const float c2 = scale * kLog2e;
+    const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k;
+    LaunchTimer t(KID_SPECTRAL_GRAM, stream);
+#define FLARE_GRAM(DD, MTT)                                                                                  \
+    gram_mfma_kernel<DD, MTT><<<grid, 64 * MTT, 0, stream>>>(qq, kk, lse_enc, lse_dec, g_part, tok_stride(s), s.H, \
+                                                             s.N, sp.chunk_len, sp.chunks, c2)
+#define FLARE_GRAM_MT(DD)                       \
+    switch (s.M / 32) {                         \
+        case 1: FLARE_GRAM(DD, 1); break;       \
+        case 2: FLARE_GRAM(DD, 2); break;       \
+        case 4: FLARE_GRAM(DD, 4); break;       \
+        default: FLARE_GRAM(DD, 8); break;      \
+    }
+    switch (s.d) {
+        case 4: FLARE_GRAM_MT(4) break;
+        case 8: FLARE_GRAM_MT(8) break;
+        case 16: FLARE_GRAM_MT(16) break;
+        default: FLARE_GRAM_MT(32) break;
+    }
+#undef FLARE_GRAM_MT
+#undef FLARE_GRAM
+    return check_launch();
+}
+
+int mfma_decode(const flare_shape &s, const void *q, const void *k, const float *z, void *y, float *lse_dec,
+                float scale, void *ws, hipStream_t stream)
+{
+    return decode_all<0>(s, q, k, z, y, nullptr, lse_dec, nullptr, scale, ws, stream);
+}
+
+int mfma_token_stats(const flare_shape &s, const void *q, const void *k, const float *z, const void *dy,
+                     float *lse_dec2, float *delta, float scale, void *ws, hipStream_t stream)
+{
+    return decode_all<1>(s, q, k, z, nullptr, dy, lse_dec2, delta, scale, ws, stream);
+}
+
+}  // namespace flare

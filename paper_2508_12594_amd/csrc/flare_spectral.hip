@@ -5,7 +5,7 @@
 // applied to an M x M "latent sequence".  With lse_enc = log row sums of A and lse_dec = log column
 // sums (what the forward leaves behind),  J[m][n] = exp(S[m][n] - (lse_enc[m] + lse_dec[n]) / 2).
 //
-// Steps here:  G as a streaming reduction over the tokens (matrix-core kernel in flare_mfma.hip,
+// Steps here:  G as a streaming reduction over the tokens (matrix-core kernel in flare_mfma_fwd.hip,
 // or the fp32 kernel below), a fixed-order sum of the per-chunk partials, a one-sided cyclic Jacobi
 // eigensolver in fp64 (one workgroup per (b,h); the rotations of a round act on disjoint pairs of
 // rows), and a last kernel that orders the eigenvalues and forms the decode-ready block
