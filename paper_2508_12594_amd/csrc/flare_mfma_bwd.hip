@@ -50,7 +50,8 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
     const int lane = threadIdx.x & 63, l32 = lane & 31, hh = lane >> 5;
     const int wave = threadIdx.x >> 6;
     const int g = wave % G, tg = wave / G;
-    const int bh = blockIdx.y, h = bh % H, chunk = blockIdx.x;
+    const GridPos gp = grid_pos(ts, H, DR * 2);
+    const int bh = gp.y, h = bh % H, chunk = gp.x;
     if ((plan[bh] != 0) != ONE) return;         // the other variant owns this (b,h)
     const bool lower = hh == 0;
     uint16_t *lds = kt_all[wave];
@@ -390,8 +391,8 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     //     dQ^T[dd][m] += K^T[dd][n] dS^T[n][m]     with v_mfma_f32_16x16x32_bf16
     // (16 output rows = d: no wasted rows, four accumulator registers per 16 latents), so a wave keeps
     // dQ of all 32*MT latents in 8*MT registers.  At the end the eight waves add their partials in a
-    // fixed order through LDS and the workgroup writes slot blockIdx.x of dq_part
-    // ([(b*h) * gridDim.x + blockIdx.x][Mtot][d], summed and scaled by dq_reduce_kernel).  The c chain
+    // fixed order through LDS and the workgroup writes slot x (its grid position) of dq_part
+    // ([(b*h) * gridDim.x + x][Mtot][d], summed and scaled by dq_reduce_kernel).  The c chain
     // then carries the lo term of Z (dQ sums dS over the tokens of one latent and would add up its
     // rounding coherently, see the dQ kernel).
     // The kernel works on the latents m0 .. m0 + M of the head's Mtot.  With acc32 given (more than one
@@ -422,7 +423,8 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     const int tid = threadIdx.x;
     const int lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
     const int wave = tid >> 6;
-    const int bh = blockIdx.y, h = bh % H;
+    const GridPos gp = grid_pos(ts, H, DR * 2);
+    const int bh = gp.y, h = bh % H;
     const bool lower = hh == 0;
     if ((plan[bh] != 0) != ONE) return;         // the other variant owns this (b,h); uniform over the workgroup
     float kap = 0.f;
@@ -593,7 +595,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
         for (int jb = 0; jb < 2; ++jb) dqa[t][jb] = f32x4{0.f, 0.f, 0.f, 0.f};
     const int c16 = lane & 15, g16 = lane >> 4;
 
-    int tile = blockIdx.x * 8 + wave;
+    int tile = gp.x * 8 + wave;
     bf16x8 kt[KS], vt[KS], gt[KS], ktn[KS], vtn[KS], gtn[KS];
     if (tile < tiles) {
         load_cols(kb, tile, kt, true);
@@ -831,7 +833,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
         }
         __syncthreads();
         const int mleft = Mtot - m0;
-        float *out = dq_part + (((size_t)bh * gridDim.x + blockIdx.x) * Mtot + m0) * DR;
+        float *out = dq_part + (((size_t)bh * gridDim.x + gp.x) * Mtot + m0) * DR;
         constexpr int PCS = DR / 4;                             // float4 pieces of a DR-element row
         for (int i = tid; i < 32 * MT * PCS; i += 512) {        // latent i / PCS, columns 4 (i % PCS) ..
             const int lat = i / PCS, pc = i % PCS;

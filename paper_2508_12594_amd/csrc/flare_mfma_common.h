@@ -328,6 +328,44 @@ inline int lat_chunks(int M) { return (M + kLatChunk - 1) / kLatChunk; }
 constexpr float kLazy = 16.f;   // the stabiliser moves when a score exceeds it by this much (log2 units)
 constexpr int kVtStride = 36;   // uint16 per LDS row: 32 tokens + 4 pad (72 B, conflict-free b64 reads)
 
+// The grid position (x = token chunk, y = b*H + h) that this workgroup works on.
+// With the [B,H,N,d] layout it is the workgroup's own.  With [B,N,H,d] the rows of neighbouring heads
+// lie side by side within a token: 128 / (2 d) heads share each 128-byte cache line.  Workgroups go to the
+// eight XCDs, each with an L2 of its own, round-robin by their linear index, so the workgroups that walk
+// over the same tokens for the heads of one line would land on different XCDs, and each of those L2s
+// would fetch the whole line for its own part of it (measured at d = 32: twice to three times the bytes
+// of the other layout).  So the linear index is re-read as (XCD, slot within the XCD), and the heads
+// of one line take consecutive slots of one XCD: they are dispatched together there and share the
+// fetched lines.  A remainder that does not fill a round of the eight XCDs keeps the plain order.
+// The mapping is a bijection of the grid's (x, y) plane; planes (gridDim.z) are mapped alike.
+struct GridPos { int x, y; };
+__device__ __forceinline__ GridPos grid_pos(const TokStride &ts, int H, int row_bytes)
+{
+    GridPos p{(int)blockIdx.x, (int)blockIdx.y};
+    if (ts.sh >= ts.sn) return p;                 // heads are not interleaved within a token
+    int hg = 128 / row_bytes;                     // heads per cache line
+    while (hg > 1 && H % hg != 0) hg >>= 1;
+    if (hg <= 1) return p;
+    const int gx = gridDim.x, hgroups = H / hg;
+    const int L = p.x + gx * p.y;
+    const int groups = gx * ((int)gridDim.y / hg);          // (chunk, b, group of heads)
+    const int full = (groups / 8) * 8 * hg;                 // workgroups in whole rounds of the eight XCDs
+    int g, hs;
+    if (L < full) {
+        const int slot = L >> 3;
+        hs = slot % hg;
+        g = (slot / hg) * 8 + (L & 7);
+    } else {
+        const int r = L - full;
+        g = (groups / 8) * 8 + r / hg;
+        hs = r % hg;
+    }
+    const int yg = g / gx;                                  // b * hgroups + group of heads
+    p.x = g % gx;
+    p.y = (yg / hgroups) * H + (yg % hgroups) * hg + hs;
+    return p;
+}
+
 inline int check_launch() { return hipGetLastError() == hipSuccess ? FLARE_OK : FLARE_ELAUNCH; }
 
 // latent-group geometry of the encode for a given M

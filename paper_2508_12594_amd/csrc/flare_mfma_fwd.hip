@@ -40,7 +40,8 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
     constexpr bool PACK = PRE && pack_dim(DR);   // q' hi | lo in one operand, keys repeated in both lane halves
     const int lane = threadIdx.x & 63, l32 = lane & 31, hh = lane >> 5;
     const int wave = threadIdx.x >> 6;
-    const int bh = blockIdx.y, h = bh % H;
+    const GridPos gp = grid_pos(ts, H, DR * 2);
+    const int bh = gp.y, h = bh % H;
     const bool flip = c2 < 0.f;
     const float ac2 = PRE ? c2 : fabsf(c2);
 
@@ -95,7 +96,7 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
     bf16_t *yb = y + tok_base(ts_y, bh, H);
     const int tiles = (N + 31) / 32;
     const int stride = gridDim.x * 4;
-    int tile = blockIdx.x * 4 + wave;
+    int tile = gp.x * 4 + wave;
     bf16x8 kt[KS], ktn[KS];
     if (tile < tiles) {
         const int nld = min(tile * 32 + l32, N - 1);
@@ -303,7 +304,8 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     const int lane = threadIdx.x & 63, l32 = lane & 31, hh = lane >> 5;
     const int wave = threadIdx.x >> 6;
     const int g = wave % G, tg = wave / G;
-    const int bh = blockIdx.y, h = bh % H, chunk = blockIdx.x;
+    const GridPos gp = grid_pos(ts, H, DR * 2);
+    const int bh = gp.y, h = bh % H, chunk = gp.x;
     const uint32_t keep0 = hh == 0 ? 0xffff0000u : 0xffffffffu;
     uint16_t *vt = vt_all[wave];
 
@@ -611,7 +613,8 @@ __global__ __launch_bounds__(64 * MT) void gram_mfma_kernel(
     __shared__ __attribute__((aligned(16))) u32x4 jt[2][MT][2][64];
     const int lane = threadIdx.x & 63, l32 = lane & 31, hh = lane >> 5;
     const int wave = threadIdx.x >> 6;
-    const int bh = blockIdx.y, h = bh % H, chunk = blockIdx.x;
+    const GridPos gp = grid_pos(ts, H, DR * 2);
+    const int bh = gp.y, h = bh % H, chunk = gp.x;
     const bool lower = hh == 0;
 
     bf16x8 qh[KS], ql[KS];
