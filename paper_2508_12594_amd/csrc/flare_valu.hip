@@ -829,8 +829,9 @@ ValuPlan valu_plan(const flare_shape &s)
 {
     ValuPlan p;
     const int BH = s.B * s.H;
-    p.enc = plan_split(s.N, BH, 256, 2048);
-    p.bwd = plan_split(s.N, BH, 256, 2048);
+    // chunks of at least 64 tokens: short sequences with few heads still spread over the chip
+    p.enc = plan_split(s.N, BH, 64, 2048);
+    p.bwd = plan_split(s.N, BH, 64, 2048);
     p.fwd_bytes = valu_fwd_layout(s, p.enc, nullptr, nullptr, nullptr, nullptr);
     p.bwd_bytes = bwd_layout(s, bwd_slots(s, p), nullptr, nullptr);
     return p;
