@@ -829,9 +829,16 @@ ValuPlan valu_plan(const flare_shape &s)
 {
     ValuPlan p;
     const int BH = s.B * s.H;
-    // chunks of at least 64 tokens: short sequences with few heads still spread over the chip
+    // chunks of at least 64 tokens: short sequences with few heads still spread over the chip; and of at
+    // most 8192: a thread adds its chunk's terms one after the other in fp32, and the rounding of such a
+    // sum grows with the square root of its length (the partial results are then combined by a tree)
     p.enc = plan_split(s.N, BH, 64, 2048);
-    p.bwd = plan_split(s.N, BH, 64, 2048);
+    constexpr int kMaxChunk = 8192;
+    if (p.enc.chunk_len > kMaxChunk) {
+        p.enc.chunk_len = kMaxChunk;
+        p.enc.chunks = (s.N + kMaxChunk - 1) / kMaxChunk;
+    }
+    p.bwd = p.enc;
     p.fwd_bytes = valu_fwd_layout(s, p.enc, nullptr, nullptr, nullptr, nullptr);
     p.bwd_bytes = bwd_layout(s, bwd_slots(s, p), nullptr, nullptr);
     return p;

@@ -13,7 +13,7 @@ import numpy as np
 import pytest
 
 from paper_2508_12594_amd import binding, synth
-from tests._util import TOL, slice_relerr, to_device, to_host
+from tests._util import TOL, slice_relerr, to_device, to_host, tol_for
 
 pytestmark = pytest.mark.gpu
 
@@ -114,6 +114,7 @@ MILLION_VARIANTS = [
     (dict(M=200), True, False),                   # 56 padding latents in the last tiles
     (dict(d=8), False, True),                     # the paper's head dimension for PDE meshes, token-major layout
     (dict(M=512, H=2, d=8), True, False),         # two latent chunks
+    (dict(dtype="f32", M=64), True, False),       # the fp32 vector kernels: sums of 10^6 terms within 1e-5
 ]
 
 
@@ -125,7 +126,7 @@ def test_forward_backward_million_tokens(oracle, over, saved, bnhd):
     import torch
     _say("full forward+backward cfg4 %s saved=%s bnhd=%s" % (over, saved, bnhd))
     inp = synth.make_inputs(4, with_dy=True, **over)
-    N, scale, tol = inp["N"], inp["scale"], TOL["bf16"]
+    N, scale, tol = inp["N"], inp["scale"], tol_for(inp)
     dev = to_device(inp)
     layout = "bnhd" if bnhd else "bhnd"
     conv = (lambda t: t.permute(0, 2, 1, 3).contiguous()) if bnhd else (lambda t: t)
@@ -166,3 +167,43 @@ def test_backward_full_small_workloads(oracle):
                 slice_relerr(to_host(dv), dv_ref))
         _say("   err dq %.3e  dk %.3e  dv %.3e  (tol %.0e)" % (errs + (tol,)))
         assert max(errs) <= tol
+
+
+@pytest.mark.parametrize("dtype,layout", [("bf16", "bhnd"), ("bf16", "bnhd"), ("f32", "bhnd")])
+def test_token_tensors_beyond_two_to_the_31_elements(dtype, layout):
+    """Maximum sizes: 17 copies of the million-token item in one call, so that the element offsets
+    into k, v, y, dy, dk, dv pass 2^31 (and the byte offsets 2^32, fp32: 2^33).  The
+    batch items are independent and go through the same kernels in the same configuration, so every
+    item must equal item 0 bit for bit (y, z, lse_enc, dk, dv); item 0 must agree with a one-item call
+    (whose token axis is split differently, so only up to rounding), and dq_lat, the sum over the
+    batch, must be B times the one-item result."""
+    import torch
+    B = 17
+    over = dict(dtype=dtype) if dtype != "bf16" else dict()
+    if dtype == "f32":
+        over.update(M=64)       # the fp32 kernels run on the vector ALUs: fewer latents keep the case short
+    _say("offsets beyond 2^31 elements: %d copies of cfg4 %s %s" % (B, over, layout))
+    inp = synth.make_inputs(4, with_dy=True, **over)
+    scale = inp["scale"]
+    dev = to_device(inp)
+    conv = (lambda t: t.permute(0, 2, 1, 3).contiguous()) if layout == "bnhd" else (lambda t: t)
+    one = {n: conv(dev[n]) for n in ("k", "v", "dy")}
+    assert B * one["k"].numel() > 2 ** 31
+    y1, z1, lse1 = binding.forward(dev["q"], one["k"], one["v"], scale, layout=layout)
+    dq1, dk1, dv1 = binding.backward(dev["q"], one["k"], one["v"], one["dy"], z1, lse1, scale, layout=layout)
+    many = {n: t.expand(B, *t.shape[1:]).contiguous() for n, t in one.items()}
+    y, z, lse = binding.forward(dev["q"], many["k"], many["v"], scale, layout=layout)
+    dq, dk, dv = binding.backward(dev["q"], many["k"], many["v"], many["dy"], z, lse, scale, layout=layout)
+    torch.cuda.synchronize()
+    # two runs of the library with different splits of the 10^6 tokens: each carries its own rounding
+    # (fp32 sums of 10^6 terms; bf16 weights), so their distance is up to twice that of one run from the truth
+    loose = 1e-5 if dtype == "f32" else 4e-3
+    for name, got, want in (("y", y, y1), ("z", z, z1), ("lse_enc", lse, lse1), ("dk", dk, dk1), ("dv", dv, dv1)):
+        for b in range(1, B):
+            assert torch.equal(got[b], got[0]), "%s of batch item %d differs from item 0" % (name, b)
+        err = float((got[0].double() - want[0].double()).norm() / want[0].double().norm())
+        _say("   %s of item 0 against the one-item call: %.2e" % (name, err))
+        assert err <= loose
+    e_q = float((dq.double() - B * dq1.double()).norm() / (B * dq1.double()).norm())
+    _say("   dq against B x one item: %.2e" % e_q)
+    assert e_q <= loose
