@@ -435,6 +435,29 @@ def test_constant_v_gives_constant_y():
     assert float((z - 1.5).abs().max()) <= 1e-5
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+def test_zero_scale_gives_plain_means(dtype):
+    """scale = 0: every score is zero, both softmaxes are uniform, so each latent holds the mean of the
+    values, every token receives it back, and the scores do not depend on q or k: dq = dk = 0 and
+    dv_n = mean of dy for every token (closed forms, no oracle needed)."""
+    import torch
+    _say("zero scale %s" % dtype)
+    inp = synth.make_inputs(1, B=2, H=2, N=777, M=96, d=16, dtype=dtype, with_dy=True, seed=4242)
+    dev = to_device(inp)
+    y, z, lse = binding.forward(dev["q"], dev["k"], dev["v"], 0.0)
+    dq, dk, dv = binding.backward(dev["q"], dev["k"], dev["v"], dev["dy"], z, lse, 0.0)
+    torch.cuda.synchronize()
+    tol = 1e-5 if dtype == "f32" else 2e-2
+    v_mean = dev["v"].double().mean(dim=2, keepdim=True)                     # [B,H,1,d]
+    g_mean = dev["dy"].double().mean(dim=2, keepdim=True)
+    rel = lambda a, b: float((a.double() - b).norm() / b.norm())
+    assert rel(z, v_mean.expand(-1, -1, 96, -1)) <= (1e-5 if dtype == "f32" else 2e-3)
+    assert rel(y, v_mean.expand(-1, -1, 777, -1)) <= tol
+    assert rel(dv, g_mean.expand(-1, -1, 777, -1)) <= tol
+    assert float((lse - float(np.log(777))).abs().max()) <= 1e-5
+    assert float(dq.abs().max()) == 0.0 and float(dk.float().abs().max()) == 0.0
+
+
 @pytest.mark.parametrize("cfg,over", [(1, dict()), (2, dict(B=1, N=5000)), (5, dict(N=2048))])
 def test_bit_reproducible(cfg, over):
     """Same inputs, same shape: identical bits on every run (fixed-order reductions)."""
