@@ -857,14 +857,12 @@ static int launch_decode_family(const flare_shape &s, const void *q, const void 
 namespace {
 // Combine the per-chunk results of the decode (M > 256): for token n of (b,h),
 //   lse = log sum_c exp(lse_c),   y = sum_c exp(lse_c - lse) y_c        (softmax over all M latents).
-// MODE 0 writes y in the caller's layout and, when asked, lse_dec (natural log);
-// MODE 1 writes lse_dec2 = lse * log2(e) and delta = <dY_n, y> with y kept in fp32.
-// thread = token; the partial rows are [chunk][b*h][n][DR] bf16, the partial lse [chunk][b*h][n].
-template <int DR, int MODE, bool F>
+// Writes y in the caller's layout and, when asked, lse_dec (natural log).
+// thread = token; the partial rows are [chunk][b*h][n][DR] in the storage type, the partial lse [chunk][b*h][n].
+template <int DR, bool F>
 __global__ __launch_bounds__(256) void decode_merge_kernel(
     const bf16_t *__restrict__ y_part, const float *__restrict__ lse_part, int chunks, bf16_t *__restrict__ y,
-    const bf16_t *__restrict__ dy, float *__restrict__ lse_out, float *__restrict__ delta, TokStride ts, int H,
-    int N, size_t rows_all)
+    float *__restrict__ lse_out, TokStride ts, int H, int N, size_t rows_all)
 {
     const int n = blockIdx.x * 256 + threadIdx.x;
     if (n >= N) return;
@@ -889,30 +887,40 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(
         }
     }
     const float inv = 1.f / tot;
-    const float lse = mx + __logf(tot);
     const size_t trow = tok_base(ts, bh, H) + tok_off(ts, n);
-    if constexpr (MODE == 0) {
 #pragma unroll
-        for (int j = 0; j < DR; j += 4) {
-            u32x2 w;
-            w[0] = pack_elems<F>(acc[j] * inv, acc[j + 1] * inv);
-            w[1] = pack_elems<F>(acc[j + 2] * inv, acc[j + 3] * inv);
-            *reinterpret_cast<u32x2 *>(y + trow + j) = w;
-        }
-        if (lse_out) lse_out[row] = lse;
-    } else {
-        float dl = 0.f;
-#pragma unroll
-        for (int j = 0; j < DR; j += 4) {
-            const u32x2 g = *reinterpret_cast<const u32x2 *>(dy + trow + j);
-            dl = fmaf(acc[j] * inv, dy_lo<F>(g[0]), dl);
-            dl = fmaf(acc[j + 1] * inv, dy_hi<F>(g[0]), dl);
-            dl = fmaf(acc[j + 2] * inv, dy_lo<F>(g[1]), dl);
-            dl = fmaf(acc[j + 3] * inv, dy_hi<F>(g[1]), dl);
-        }
-        lse_out[row] = lse * kLog2e;
-        delta[row] = dl;
+    for (int j = 0; j < DR; j += 4) {
+        u32x2 w;
+        w[0] = pack_elems<F>(acc[j] * inv, acc[j + 1] * inv);
+        w[1] = pack_elems<F>(acc[j + 2] * inv, acc[j + 3] * inv);
+        *reinterpret_cast<u32x2 *>(y + trow + j) = w;
     }
+    if (lse_out) lse_out[row] = mx + __logf(tot);
+}
+
+// Combine the per-chunk token statistics of the backward (M > 256).  Chunk c gives, for token n,
+// lse2_c = log2 sum_{m in c} 2^S2[m][n] and delta_c = <dY_n, Y_n^c> with Y_n^c the decode over the chunk's
+// latents alone, formed in fp32 registers; then
+//   lse_dec2 = log2 sum_c 2^lse2_c,   delta = sum_c 2^(lse2_c - lse_dec2) delta_c.
+// (Going through 16-bit rows of Y^c instead would put their rounding into delta, and c - delta is a
+// difference that must cancel: measured 2.9e-2 against 7e-3 in dq_lat at d = 4.)  thread = token row.
+__global__ __launch_bounds__(256) void stats_merge_kernel(const float *__restrict__ lse_part,
+                                                          const float *__restrict__ delta_part, int chunks,
+                                                          float *__restrict__ lse_out, float *__restrict__ delta,
+                                                          size_t rows)
+{
+    const size_t row = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (row >= rows) return;
+    float mx = -INFINITY;
+    for (int c = 0; c < chunks; ++c) mx = fmaxf(mx, lse_part[(size_t)c * rows + row]);
+    float tot = 0.f, dl = 0.f;
+    for (int c = 0; c < chunks; ++c) {
+        const float w = fast_exp2(lse_part[(size_t)c * rows + row] - mx);
+        tot += w;
+        dl = fmaf(w, delta_part[(size_t)c * rows + row], dl);
+    }
+    lse_out[row] = mx + log2f(tot);
+    delta[row] = dl / tot;
 }
 }  // namespace
 
@@ -934,35 +942,50 @@ static int decode_all(const flare_shape &s, const void *q, const void *k, const 
                                           stream);
     const int C = lat_chunks(s.M);
     const size_t rows = (size_t)s.B * s.H * s.N;
-    bf16_t *y_part = static_cast<bf16_t *>(ws);
     float *lse_part = reinterpret_cast<float *>(static_cast<char *>(ws) + ((rows * C * s.d * 2 + 255) & ~(size_t)255));
-    const TokStride tp{(long long)s.H * s.N * s.d, (long long)s.N * s.d, s.d, 0};   // partial rows: [b][h][n][d]
-    for (int c = 0; c < C; ++c) {
-        const int rc = launch_decode_family<0>(s, q, k, z, y_part + (size_t)c * rows * s.d, tp, nullptr,
-                                               lse_part + (size_t)c * rows, nullptr, c * kLatChunk, kLatChunk, scale,
-                                               stream);
-        if (rc != FLARE_OK) return rc;
-    }
-    const dim3 grid((s.N + 255) / 256, s.B * s.H);
-    LaunchTimer t(KID_DECODE_MERGE, stream);
-    const bool f16 = s.dtype == FLARE_F16;
-#define FLARE_DM(DD)                                                                                               \
-    do {                                                                                                           \
-        if (f16)                                                                                                   \
-            decode_merge_kernel<DD, MODE, true><<<grid, 256, 0, stream>>>(                                         \
-                y_part, lse_part, C, (bf16_t *)y, (const bf16_t *)dy, lse_out, delta, tok_stride(s), s.H, s.N, rows); \
-        else                                                                                                       \
-            decode_merge_kernel<DD, MODE, false><<<grid, 256, 0, stream>>>(                                        \
-                y_part, lse_part, C, (bf16_t *)y, (const bf16_t *)dy, lse_out, delta, tok_stride(s), s.H, s.N, rows); \
+    if constexpr (MODE == 1) {
+        // per-chunk statistics in fp32 (delta_c in the space of the partial rows, which this mode does not need)
+        float *delta_part = static_cast<float *>(ws);
+        for (int c = 0; c < C; ++c) {
+            const int rc = launch_decode_family<1>(s, q, k, z, nullptr, tok_stride(s), dy, lse_part + (size_t)c * rows,
+                                                   delta_part + (size_t)c * rows, c * kLatChunk, kLatChunk, scale,
+                                                   stream);
+            if (rc != FLARE_OK) return rc;
+        }
+        LaunchTimer t(KID_DECODE_MERGE, stream);
+        stats_merge_kernel<<<(unsigned)((rows + 255) / 256), 256, 0, stream>>>(lse_part, delta_part, C, lse_out, delta,
+                                                                              rows);
+        return check_launch();
+    } else {
+        bf16_t *y_part = static_cast<bf16_t *>(ws);
+        const TokStride tp{(long long)s.H * s.N * s.d, (long long)s.N * s.d, s.d, 0};   // partial rows: [b][h][n][d]
+        for (int c = 0; c < C; ++c) {
+            const int rc = launch_decode_family<0>(s, q, k, z, y_part + (size_t)c * rows * s.d, tp, nullptr,
+                                                   lse_part + (size_t)c * rows, nullptr, c * kLatChunk, kLatChunk,
+                                                   scale, stream);
+            if (rc != FLARE_OK) return rc;
+        }
+        const dim3 grid((s.N + 255) / 256, s.B * s.H);
+        LaunchTimer t(KID_DECODE_MERGE, stream);
+        const bool f16 = s.dtype == FLARE_F16;
+#define FLARE_DM(DD)                                                                                              \
+    do {                                                                                                          \
+        if (f16)                                                                                                  \
+            decode_merge_kernel<DD, true><<<grid, 256, 0, stream>>>(y_part, lse_part, C, (bf16_t *)y, lse_out,    \
+                                                                    tok_stride(s), s.H, s.N, rows);               \
+        else                                                                                                      \
+            decode_merge_kernel<DD, false><<<grid, 256, 0, stream>>>(y_part, lse_part, C, (bf16_t *)y, lse_out,   \
+                                                                     tok_stride(s), s.H, s.N, rows);              \
     } while (0)
-    switch (s.d) {
-        case 4: FLARE_DM(4); break;
-        case 8: FLARE_DM(8); break;
-        case 16: FLARE_DM(16); break;
-        default: FLARE_DM(32); break;
-    }
+        switch (s.d) {
+            case 4: FLARE_DM(4); break;
+            case 8: FLARE_DM(8); break;
+            case 16: FLARE_DM(16); break;
+            default: FLARE_DM(32); break;
+        }
 #undef FLARE_DM
-    return check_launch();
+        return check_launch();
+    }
 }
 
 // partial companion matrices [b*h][chunk][M][M]; the split of the token axis is returned in *sp
