@@ -512,6 +512,16 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                     }
                     w[i] = a | (b << 16);
                 }
+                if constexpr (DR == 4 && !ZPACK) {   // slots 4-7 of the Z image := its lo part (dY repeated there)
+                    if (kind == 3 && hf == 0) {
+#pragma unroll
+                        for (int i = 0; i < 2; ++i) {
+                            const uint32_t a = rne_bf16(x[2 * i] - __uint_as_float(w[i] << 16));
+                            const uint32_t b = rne_bf16(x[2 * i + 1] - __uint_as_float(w[i] & 0xffff0000u));
+                            w[2 + i] = a | (b << 16);
+                        }
+                    }
+                }
                 if (PACK && hf == 1 && kind == 2 && real) w[0] = split_bf16_pair(-eb[m]);   // slots 8,9 := -eps
                 if (PACK && !ZPACK && hf == 1 && kind == 3 && real) {                // slots 8,9,10 := u, u, u lo / 1, 1
                     if constexpr (ONE) {
@@ -637,6 +647,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
             u32x4 w = __builtin_bit_cast(u32x4, gt[0]);
             const uint32_t dp_ = split_bf16_pair(-dl);   // here c keeps its own correction: -delta unscaled
             if (!lower) { w[0] = dp_; w[1] = ONE ? (dp_ & 0xffffu) : 0u; }
+            if (DR == 4 && lower) { w[2] = w[0]; w[3] = w[1]; }   // against the lo part of Z in slots 4-7
             gc[0] = as_bf16x8(w);
         }
 

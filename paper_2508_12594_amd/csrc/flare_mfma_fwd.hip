@@ -25,7 +25,7 @@ template <int DR, int MT, bool PRE, int MINB, int MODE, bool F>
 __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const float *__restrict__ z,
     bf16_t *__restrict__ y, const bf16_t *__restrict__ dy, float *__restrict__ lse_dec2,
-    float *__restrict__ delta, TokStride ts, TokStride ts_y, int H, int N, int Mtot, int m0, float c2)
+    float *__restrict__ delta, TokStride ts, TokStride ts_y, int H, int N, int Mtot, int m0, float c2, int z_lo)
 {
     // The kernel works on the latents m0 .. m0 + M of the head's Mtot (M = 32*MT of them); with more than
     // one chunk its outputs are one chunk's partial result (y normalised within the chunk, lse_dec of the
@@ -76,6 +76,15 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
                         const int lb = 32 * (s / 2) + perm_index(s % 2, hh, i + 1);
                         a = la < mleft ? zb[(size_t)la * DR + 16 * hv + l32] : 0.f;
                         b = lb < mleft ? zb[(size_t)lb * DR + 16 * hv + l32] : 0.f;
+                    } else if (MODE == 1 && DR <= 8 && z_lo && l32 >= 8 && l32 < 8 + DR) {
+                        // rows 8 .. 8 + d - 1 (free at d <= 8): what the rounding of Z to bf16 left over, so
+                        // that the rows of Y behind delta carry Z as a hi + lo pair like the c chain does
+                        const int la = 32 * (s / 2) + perm_index(s % 2, hh, i);
+                        const int lb = 32 * (s / 2) + perm_index(s % 2, hh, i + 1);
+                        a = la < mleft ? zb[(size_t)la * DR + l32 - 8] : 0.f;
+                        b = lb < mleft ? zb[(size_t)lb * DR + l32 - 8] : 0.f;
+                        a -= __uint_as_float(rne_bf16(a) << 16);
+                        b -= __uint_as_float(rne_bf16(b) << 16);
                     } else {   // row 16: ones (for the real latents), the rest: zero
                         a = (l32 == 16 && 32 * (s / 2) + perm_index(s % 2, hh, i) < mleft) ? 1.f : 0.f;
                         b = (l32 == 16 && 32 * (s / 2) + perm_index(s % 2, hh, i + 1) < mleft) ? 1.f : 0.f;
@@ -224,6 +233,10 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
                 g0[0] = 0u; g0[1] = 0u; g1[0] = 0u; g1[1] = 0u;
                 if (quartet_inside<DR>(hv, hh, 0)) g0 = *reinterpret_cast<const u32x2 *>(gr + 16 * hv + 4 * hh);
                 if (quartet_inside<DR>(hv, hh, 1)) g1 = *reinterpret_cast<const u32x2 *>(gr + 16 * hv + 8 + 4 * hh);
+                if constexpr (DR <= 8) {   // rows 8 + j: the lo part of column j (zero unless z_lo), same lane
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) acc[hv][i] += acc[hv][4 + i];
+                }
                 part = fmaf(acc[hv][0] * inv, dy_lo<F>(g0[0]), part);
                 part = fmaf(acc[hv][1] * inv, dy_hi<F>(g0[0]), part);
                 part = fmaf(acc[hv][2] * inv, dy_lo<F>(g0[1]), part);
@@ -802,7 +815,7 @@ int mfma_dz_partial(const flare_shape &s, const void *q, const void *k, const vo
 template <int MODE>
 static int launch_decode_family(const flare_shape &s, const void *q, const void *k, const float *z, void *y,
                                 TokStride ts_y, const void *dy, float *lse_dec2, float *delta, int m0, int Mc,
-                                float scale, hipStream_t stream)
+                                float scale, hipStream_t stream, bool z_lo = false)
 {
     const int BH = s.B * s.H;
     const int tiles = (s.N + 31) / 32;
@@ -814,7 +827,7 @@ static int launch_decode_family(const flare_shape &s, const void *q, const void 
     bf16_t *yy = (bf16_t *)y;
     LaunchTimer t(MODE == 0 ? KID_DECODE : KID_BWD_TOKEN_STATS, stream);
     const bool f16 = s.dtype == FLARE_F16;
-#define FLARE_DEC_ARGS qq, kk, z, yy, gg, lse_dec2, delta, tok_stride(s), ts_y, s.H, s.N, s.M, m0, c2
+#define FLARE_DEC_ARGS qq, kk, z, yy, gg, lse_dec2, delta, tok_stride(s), ts_y, s.H, s.N, s.M, m0, c2, z_lo ? 1 : 0
 #define FLARE_DEC(DD, MTT, PREE, MINB)                                                                          \
     do {                                                                                                        \
         if (f16)                                                                                                \
@@ -935,11 +948,11 @@ size_t mfma_tok_part_bytes(const flare_shape &s)
 // decode (MODE 0) or token statistics (MODE 1) over all latents, in chunks of 256 when there are more
 template <int MODE>
 static int decode_all(const flare_shape &s, const void *q, const void *k, const float *z, void *y, const void *dy,
-                      float *lse_out, float *delta, float scale, void *ws, hipStream_t stream)
+                      float *lse_out, float *delta, float scale, void *ws, hipStream_t stream, bool z_lo = false)
 {
     if (s.M <= kLatChunk)
         return launch_decode_family<MODE>(s, q, k, z, y, tok_stride(s), dy, lse_out, delta, 0, lat_eff(s.M), scale,
-                                          stream);
+                                          stream, z_lo);
     const int C = lat_chunks(s.M);
     const size_t rows = (size_t)s.B * s.H * s.N;
     float *lse_part = reinterpret_cast<float *>(static_cast<char *>(ws) + ((rows * C * s.d * 2 + 255) & ~(size_t)255));
@@ -949,7 +962,7 @@ static int decode_all(const flare_shape &s, const void *q, const void *k, const 
         for (int c = 0; c < C; ++c) {
             const int rc = launch_decode_family<1>(s, q, k, z, nullptr, tok_stride(s), dy, lse_part + (size_t)c * rows,
                                                    delta_part + (size_t)c * rows, c * kLatChunk, kLatChunk, scale,
-                                                   stream);
+                                                   stream, z_lo);
             if (rc != FLARE_OK) return rc;
         }
         LaunchTimer t(KID_DECODE_MERGE, stream);
@@ -1031,7 +1044,11 @@ int mfma_decode(const flare_shape &s, const void *q, const void *k, const float 
 int mfma_token_stats(const flare_shape &s, const void *q, const void *k, const float *z, const void *dy,
                      float *lse_dec2, float *delta, float scale, void *ws, hipStream_t stream)
 {
-    return decode_all<1>(s, q, k, z, nullptr, dy, lse_dec2, delta, scale, ws, stream);
+    // d <= 8: delta from rows of Y that carry Z as a hi + lo pair, where every kernel that subtracts it from
+    // c = <Z_m, dY_n> carries that pair too (c - delta must cancel where one latent dominates a token): the
+    // dQ kernel does, the dK/dV kernel at d = 4, and at d = 8 its instantiation that also forms dQ.
+    const bool z_lo = s.d == 4 || (s.d == 8 && mfma_dkdv_supported(s) && mfma_dq_fused(s));
+    return decode_all<1>(s, q, k, z, nullptr, dy, lse_dec2, delta, scale, ws, stream, z_lo);
 }
 
 }  // namespace flare
