@@ -1,4 +1,4 @@
-// Matrix-core kernels of the second backward pass: dQ, dK, dV (one kernel at d = 8 and 16, two otherwise),
+// Matrix-core kernels of the second backward pass: dQ, dK, dV (one kernel at d <= 16, two otherwise),
 // the per-(b,h) choice between the one- and two-exponential variants, and the fp32 sums of latent chunks.
 // Operand layouts, helpers and the tile geometry are in flare_mfma_common.h.
 #include "flare_mfma_common.h"
@@ -924,15 +924,14 @@ int mfma_dkdv_blocks(const flare_shape &s)
 }
 
 // The dK/dV kernel can form the dQ partials as well (one pass over the scores for all three gradients);
-// written for d <= 16 and used at d = 8 and 16.  At d = 4 the separate dQ kernel stays: it carries the lo
-// term of Z in its c chain, for which the fused kernel has no free slots next to the corrections at d = 4,
-// and with four-term dot products that term is worth a factor 4 in dQ's error (measured 3.3e-2 against
-// 8.6e-3 on a 333-token mesh case).  FLARE_BWD_SEPARATE_DQ=1 in the environment keeps the separate dQ kernel (a switch
+// written for and used at d <= 16 (at d = 32 the dQ accumulators alone would take 128 registers).  At d <= 8
+// it carries the lo term of Z in the upper half of its Z image (ZPACK in the kernel) and is taken with at
+// least 32 latents only.  FLARE_BWD_SEPARATE_DQ=1 in the environment keeps the separate dQ kernel (a switch
 // for measurements; read at every call).
 bool mfma_dq_fused(const flare_shape &s)
 {
-    if (!mfma_supported(s) || (s.d != 8 && s.d != 16)) return false;
-    if (s.d == 8 && s.M < 32) return false;   // see ZPACK in the kernel
+    if (!mfma_supported(s) || s.d == 32) return false;
+    if (s.d <= 8 && s.M < 32) return false;   // see ZPACK in the kernel
     const char *e = getenv("FLARE_BWD_SEPARATE_DQ");
     return !(e != nullptr && e[0] != '\0' && e[0] != '0');
 }
@@ -985,7 +984,9 @@ int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v,
         case 8: FLARE_DKDV(DD, 8, true); break;        \
         default: return FLARE_EUNSUPPORTED;            \
     }
-    if (s.d == 8 && fuse) {
+    if (s.d == 4 && fuse) {
+        FLARE_DKDV_MT_DQ(4)
+    } else if (s.d == 8 && fuse) {
         FLARE_DKDV_MT_DQ(8)
     } else if (s.d == 16 && fuse) {
         FLARE_DKDV_MT_DQ(16)

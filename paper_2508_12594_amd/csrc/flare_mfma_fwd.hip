@@ -1046,7 +1046,7 @@ int mfma_token_stats(const flare_shape &s, const void *q, const void *k, const f
 {
     // d <= 8: delta from rows of Y that carry Z as a hi + lo pair, where every kernel that subtracts it from
     // c = <Z_m, dY_n> carries that pair too (c - delta must cancel where one latent dominates a token): the
-    // dQ kernel does, the dK/dV kernel at d = 4, and at d = 8 its instantiation that also forms dQ.
+    // dQ kernel does, the dK/dV kernel that also forms dQ does, and the plain dK/dV kernel does at d = 4 only.
     const bool z_lo = s.d == 4 || (s.d == 8 && mfma_dkdv_supported(s) && mfma_dq_fused(s));
     return decode_all<1>(s, q, k, z, nullptr, dy, lse_dec2, delta, scale, ws, stream, z_lo);
 }
