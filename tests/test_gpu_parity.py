@@ -356,10 +356,11 @@ def test_backward_two_exponential_kernels(oracle, cfg, over, monkeypatch):
     assert slice_relerr(to_host(dk2), to_host(dk1)) <= TOL["bf16"]
 
 
-@pytest.mark.parametrize("cfg,over", [(4, dict(N=3001)), (2, dict(B=1, N=1500, d=8)), (4, dict(N=900, M=100, dtype="f16"))])
+@pytest.mark.parametrize("cfg,over", [(4, dict(N=3001)), (2, dict(B=1, N=1500, d=8)), (2, dict(B=1, N=1500, d=4)),
+                                      (4, dict(N=900, M=100, dtype="f16"))])
 def test_backward_separate_dq_kernel(oracle, cfg, over, monkeypatch):
-    """At d = 8 and 16 the dK/dV kernel also forms dQ; FLARE_BWD_SEPARATE_DQ=1 runs the separate dQ kernel
-    (the one d = 4 and d = 32 use) on the same shapes.  Both must meet the bar and agree closely."""
+    """At d <= 16 the dK/dV kernel also forms dQ; FLARE_BWD_SEPARATE_DQ=1 runs the separate dQ kernel
+    (the one d = 32 uses) on the same shapes.  Both must meet the bar and agree closely."""
     _say("backward with the separate dQ kernel, cfg%d %s" % (cfg, over))
     inp = synth.make_inputs(cfg, with_dy=True, **over)
     tol = TOL["bf16"]
