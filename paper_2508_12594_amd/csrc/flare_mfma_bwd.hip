@@ -414,9 +414,9 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     // PACK with DQ: the upper half of the Z image carries the lo term of Z instead (dY rows repeated in both
     // lane halves), as the separate dQ kernel has it at d <= 8, and -delta comes in through the correction
     // image as at d = 16: dQ sums dS over the tokens of one latent, and with so few terms per dot product
-    // the rounding of Z_m showed (9.7e-3 against 2.6e-3 on a 1500-token case).  The host uses this
-    // instantiation only with at least 32 latents: with very few, c - delta must cancel against a delta
-    // that the decode formed from the rounded Z alone.
+    // the rounding of Z_m showed (9.7e-3 against 2.6e-3 on a 1500-token case).  The delta it subtracts
+    // comes from rows of Y formed with the same hi + lo pair (the token-statistics kernel at d <= 8), so
+    // c - delta cancels where one latent dominates a token, down to a single latent.
     constexpr bool ZPACK = PACK && DQ;
     extern __shared__ __attribute__((aligned(16))) u32x4 img[];   // [MT][PER_TILE][64 lanes]
 
@@ -925,13 +925,12 @@ int mfma_dkdv_blocks(const flare_shape &s)
 
 // The dK/dV kernel can form the dQ partials as well (one pass over the scores for all three gradients);
 // written for and used at d <= 16 (at d = 32 the dQ accumulators alone would take 128 registers).  At d <= 8
-// it carries the lo term of Z in the upper half of its Z image (ZPACK in the kernel) and is taken with at
-// least 32 latents only.  FLARE_BWD_SEPARATE_DQ=1 in the environment keeps the separate dQ kernel (a switch
+// it carries the lo term of Z in the upper half of its Z image (ZPACK in the kernel), like the token-statistics
+// kernel that forms the delta it subtracts.  FLARE_BWD_SEPARATE_DQ=1 in the environment keeps the separate dQ kernel (a switch
 // for measurements; read at every call).
 bool mfma_dq_fused(const flare_shape &s)
 {
     if (!mfma_supported(s) || s.d == 32) return false;
-    if (s.d <= 8 && s.M < 32) return false;   // see ZPACK in the kernel
     const char *e = getenv("FLARE_BWD_SEPARATE_DQ");
     return !(e != nullptr && e[0] != '\0' && e[0] != '0');
 }
