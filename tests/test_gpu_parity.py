@@ -436,6 +436,23 @@ def test_constant_v_gives_constant_y():
     assert float((z - 1.5).abs().max()) <= 1e-5
 
 
+@pytest.mark.parametrize("M,d,dtype", [(282, 4, "bf16"), (512, 4, "bf16"), (282, 4, "f16"), (2, 8, "bf16"), (512, 16, "bf16")])
+def test_latent_that_dominates_many_tokens(oracle, M, d, dtype):
+    """Mesh-like inputs on which one latent of head 1 decodes 66 tokens almost alone (R ~ 1, Y_n ~ Z_m): there
+    c - delta = <dY_n, Z_m - Y_n> cancels, and it only does so if both sides see the same Z_m.  With delta
+    from a decode that rounded Z to bf16 and c from Z as a hi + lo pair that latent's row of dq_lat was wrong
+    by half (dq_lat 2.9e-2 at M = 282, 6.9e-2 at M = 512).  At d <= 8 half the bar now, and no row far off;
+    d = 16 (delta from the saved bf16 y, rounded independently per token) for comparison, at the bar."""
+    _say("dominant latent M=%d d=%d %s" % (M, d, dtype))
+    inp = synth.make_inputs(2, B=2, H=3, N=365, M=M, d=d, dtype=dtype, with_dy=True, seed=777 + 1375)
+    for saved in (False, True):
+        dq, _, _ = _backward_case(oracle, inp, scale=1.0 / np.sqrt(d), tol=1e-2 if d <= 8 else TOL["bf16"], saved=saved)
+        dq_ref = oracle.backward(inp["q"], inp["k"], inp["v"], inp["dy"], 1.0 / np.sqrt(d))[0]
+        rows = np.linalg.norm(to_host(dq) - dq_ref, axis=2) / np.linalg.norm(dq_ref, axis=2).mean(axis=1, keepdims=True)
+        _say("   worst row of dq: %.2f of the mean row norm" % rows.max())
+        assert rows.max() <= (0.25 if d <= 8 else 0.6)      # it was 1.5 (M = 512, d = 4); d = 16: the saved bf16 y
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_zero_scale_gives_plain_means(dtype):
     """scale = 0: every score is zero, both softmaxes are uniform, so each latent holds the mean of the
