@@ -693,6 +693,12 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
         // of tile t+1 are issued first and run on the matrix cores while the vector ALUs
         // exponentiate the scores of tile t (s1, s2, computed one step earlier).
         auto tile_step = [&](int t, f32x16 &s1, f32x16 &s2, f32x16 &s1n, f32x16 &s2n) {
+            // The wave takes issue priority over its SIMD's other wave while it feeds the matrix cores (the a and
+            // c products, the next tile's scores) and drops it for the vector block: the matrix pipe starts
+            // at once and the other wave's vector instructions fill the gaps (measured -4.5 % at d = 16, -2 to
+            // -6 % at the other shapes; holding the priority over the accumulation products as well was
+            // slower, and the same switch in the encode kernel changed nothing, in the dQ kernel it cost 5 %).
+            __builtin_amdgcn_s_setprio(1);
             if constexpr (!PIPE) scores(t, s1, s2);   // not enough registers at d = 32: no look-ahead
             f32x16 av = splat16(0.f), cv = splat16(0.f);
             if constexpr (ONE) {
@@ -713,6 +719,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
 #pragma unroll
             for (int r = 0; r < NR; ++r) rw[r] = image(t, NA + r);
             sched_fence();
+            __builtin_amdgcn_s_setprio(0);
             f32x16 pv, rv;
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
