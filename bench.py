@@ -71,10 +71,10 @@ def exponentials(kernel, B, H, N, M):
 # plain 256 MB device copy in the same run (FETCH_SIZE x 2.00, WRITE_SIZE x 1.00); see
 # profiles/forward_backward_cfg4_hbm_traffic.md.
 MEASURED_TRAFFIC_CFG4 = {
-    "encode_partial": (251216 * 2.0 * 1024, 18432 * 1024),
-    "decode": (125957 * 2.0 * 1024, 281250 * 1024),
-    "bwd_dz_partial": (397685 * 2.0 * 1024, 47782 * 1024),
-    "bwd_dkdv": (408251 * 2.0 * 1024, 505120 * 1024),
+    "encode_partial": (250642 * 2.0 * 1024, 18432 * 1024),
+    "decode": (125963 * 2.0 * 1024, 281250 * 1024),
+    "bwd_dz_partial": (441142 * 2.0 * 1024, 47911 * 1024),
+    "bwd_dkdv": (408256 * 2.0 * 1024, 505120 * 1024),
 }
 
 
