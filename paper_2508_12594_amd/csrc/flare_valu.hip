@@ -247,6 +247,42 @@ __global__ __launch_bounds__(256) void encode_merge_kernel(
     lse_enc[idx] = (gm + log2f(l)) * kLn2;
 }
 
+// The same merge for few partial slots (at most kFewSlots: many (b,h) pairs of short sequences).  With
+// 16 threads per latent striding over the slots most of them would idle and each would fetch whole rows
+// from scattered slots; here the D / 2 threads of a latent own two columns each and walk over the slots
+// in order, so a workgroup reads one contiguous piece per slot.  One maximum first (exact in any order),
+// then one pass of weighted sums in slot order: the bits depend on the slot count only.
+constexpr int kFewSlots = 8;   // (measured: with 16 and 32 slots in a row the slot-parallel kernels are the faster ones)
+template <int D>
+__global__ __launch_bounds__(256) void encode_merge_few_kernel(
+    const float *__restrict__ m_part, const float *__restrict__ l_part, const float *__restrict__ o_part,
+    float *__restrict__ z, float *__restrict__ lse_enc, int BH, int M, int parts)
+{
+    constexpr int L = D / 2, ROWS = 256 / L;
+    const int j = threadIdx.x % L;
+    const int m = blockIdx.x * ROWS + threadIdx.x / L;
+    const int bh = blockIdx.y;
+    if (m >= M) return;
+    const size_t s0 = (size_t)bh * parts * M + m;   // slot p of this latent: s0 + p * M
+    float gm = -INFINITY;
+    for (int p = 0; p < parts; ++p) gm = fmaxf(gm, m_part[s0 + (size_t)p * M]);
+    float l = 0.f, o0 = 0.f, o1 = 0.f;
+    for (int p = 0; p < parts; ++p) {
+        const size_t slot = s0 + (size_t)p * M;
+        const float mp = m_part[slot];
+        if (mp == -INFINITY) continue;              // an empty slot contributes nothing
+        const float w = fast_exp2(mp - gm);
+        const float2 oc = *reinterpret_cast<const float2 *>(o_part + slot * D + 2 * j);
+        l = fmaf(l_part[slot], w, l);
+        o0 = fmaf(oc.x, w, o0);
+        o1 = fmaf(oc.y, w, o1);
+    }
+    const float inv = 1.f / l;
+    const size_t idx = (size_t)bh * M + m;
+    *reinterpret_cast<float2 *>(z + idx * D + 2 * j) = make_float2(o0 * inv, o1 * inv);
+    if (j == 0) lse_enc[idx] = (gm + log2f(l)) * kLn2;
+}
+
 // ---------------------------------------------------------------------------------------
 // Per-token pass over the latents.  MODE 0: decode, writes y.  MODE 1: backward statistics,
 // writes lse_dec2[n] = log2 sum_m 2^S2[m][n] and delta[n] = <dY_n, Y_n>.
@@ -443,6 +479,68 @@ __global__ __launch_bounds__(256) void dz_merge_kernel(
     load_row<D>(z + idx * D, zr);
     store_row<D>(dz + idx * D, acc);
     eps[idx] = dot<D>(acc, zr);
+}
+
+// Few slots (at most kFewSlots in all): the D / 2 threads of a row own two columns each and add the slots in
+// order (see encode_merge_few_kernel); same slot addressing as sum_slots.
+template <int D>
+__device__ __forceinline__ float2 sum_slots_few(const float *__restrict__ part, int outer, int n_outer, int groups,
+                                                int inner, int M, int m, int j)
+{
+    float a0 = 0.f, a1 = 0.f;
+    for (int g = 0; g < groups; ++g)
+        for (int i = 0; i < inner; ++i) {
+            const size_t slot = ((size_t)g * n_outer + outer) * inner + i;
+            const float2 t = *reinterpret_cast<const float2 *>(part + (slot * M + m) * D + 2 * j);
+            a0 += t.x;
+            a1 += t.y;
+        }
+    return make_float2(a0, a1);
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void dz_merge_few_kernel(
+    const float *__restrict__ dz_part, const float *__restrict__ z,
+    float *__restrict__ dz, float *__restrict__ eps, int BH, int M, int parts, int round_bf16)
+{
+    constexpr int L = D / 2, ROWS = 256 / L;
+    const int j = threadIdx.x % L;
+    const int m = blockIdx.x * ROWS + threadIdx.x / L;
+    const int bh = blockIdx.y;
+    const bool live = m < M;                         // no early exit: the row's lanes meet in the shuffles below
+    float2 a = sum_slots_few<D>(dz_part, bh, BH, 1, parts, M, live ? m : M - 1, j);
+    if (round_bf16) {                                // as in dz_merge_kernel: round before eps is formed
+        uint32_t u = __float_as_uint(a.x);
+        u += 0x7fffu + ((u >> 16) & 1u);
+        a.x = __uint_as_float(u & 0xffff0000u);
+        u = __float_as_uint(a.y);
+        u += 0x7fffu + ((u >> 16) & 1u);
+        a.y = __uint_as_float(u & 0xffff0000u);
+    }
+    const size_t idx = (size_t)bh * M + (live ? m : M - 1);
+    const float2 zr = *reinterpret_cast<const float2 *>(z + idx * D + 2 * j);
+    float e = fmaf(a.y, zr.y, a.x * zr.x);
+#pragma unroll
+    for (int off = 1; off < L; off <<= 1) {          // fixed tree over the row's lanes (L is a power of two)
+        const float o = __shfl_xor(e, off);
+        e = ((j & off) == 0) ? (e + o) : (o + e);
+    }
+    if (!live) return;
+    *reinterpret_cast<float2 *>(dz + idx * D + 2 * j) = a;
+    if (j == 0) eps[idx] = e;
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void dq_reduce_few_kernel(
+    const float *__restrict__ dq_part, float *__restrict__ dq, int B, int H, int M, int parts, float scale)
+{
+    constexpr int L = D / 2, ROWS = 256 / L;
+    const int j = threadIdx.x % L;
+    const int m = blockIdx.x * ROWS + threadIdx.x / L;
+    const int h = blockIdx.y;
+    if (m >= M) return;
+    const float2 a = sum_slots_few<D>(dq_part, h, H, B, parts, M, m, j);
+    *reinterpret_cast<float2 *>(dq + ((size_t)h * M + m) * D + 2 * j) = make_float2(a.x * scale, a.y * scale);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -700,10 +798,15 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
         }
         if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     }
+    constexpr int kFewRows = 256 / (D / 2);   // rows per workgroup of the few-slot merge kernels
     {
         LaunchTimer t(KID_BWD_DZ_MERGE, stream);
-        dz_merge_kernel<D><<<dim3((s.M + 15) / 16, BH), 256, 0, stream>>>(w.part, z, w.dz, w.eps, BH, s.M, dz_parts,
-                                                                          mf ? 1 : 0);
+        if (dz_parts <= kFewSlots)
+            dz_merge_few_kernel<D><<<dim3((s.M + kFewRows - 1) / kFewRows, BH), 256, 0, stream>>>(
+                w.part, z, w.dz, w.eps, BH, s.M, dz_parts, mf ? 1 : 0);
+        else
+            dz_merge_kernel<D><<<dim3((s.M + 15) / 16, BH), 256, 0, stream>>>(w.part, z, w.dz, w.eps, BH, s.M,
+                                                                              dz_parts, mf ? 1 : 0);
     }
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     int dq_parts = plan.bwd.chunks;
@@ -727,11 +830,13 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     auto reduce_dq = [&]() -> int {
         LaunchTimer t(KID_BWD_DQ_REDUCE, stream);
         // shared latents: one gradient for all heads, summed over (b, h) in that fixed order
-        if (s.shared_latents)
-            dq_reduce_kernel<D><<<dim3((s.M + 15) / 16, 1), 256, 0, stream>>>(w.part, dq, BH, 1, s.M, dq_parts, scale);
+        const int groups = s.shared_latents ? BH : s.B, outers = s.shared_latents ? 1 : s.H;
+        if ((long long)groups * dq_parts <= kFewSlots)
+            dq_reduce_few_kernel<D><<<dim3((s.M + kFewRows - 1) / kFewRows, outers), 256, 0, stream>>>(
+                w.part, dq, groups, outers, s.M, dq_parts, scale);
         else
-            dq_reduce_kernel<D><<<dim3((s.M + 15) / 16, s.H), 256, 0, stream>>>(w.part, dq, s.B, s.H, s.M, dq_parts,
-                                                                                scale);
+            dq_reduce_kernel<D><<<dim3((s.M + 15) / 16, outers), 256, 0, stream>>>(w.part, dq, groups, outers, s.M,
+                                                                                 dq_parts, scale);
         return check_launch();
     };
     if (!dq_fused) {
@@ -815,6 +920,20 @@ int launch_encode_merge(const flare_shape &s, const float *m_part, const float *
     const int BH = s.B * s.H;
     const dim3 blocks((s.M + 15) / 16, BH);
     LaunchTimer t(KID_ENCODE_MERGE, stream);
+    if (parts <= kFewSlots) {
+#define FLARE_EMF(DD)                                                                                          \
+    encode_merge_few_kernel<DD><<<dim3((s.M + 256 / (DD / 2) - 1) / (256 / (DD / 2)), BH), 256, 0, stream>>>(   \
+        m_part, l_part, o_part, z, lse_enc, BH, s.M, parts)
+        switch (s.d) {
+            case 4: FLARE_EMF(4); break;
+            case 8: FLARE_EMF(8); break;
+            case 16: FLARE_EMF(16); break;
+            case 32: FLARE_EMF(32); break;
+            default: return FLARE_EUNSUPPORTED;
+        }
+#undef FLARE_EMF
+        return check_launch();
+    }
     switch (s.d) {
         case 4: encode_merge_kernel<4><<<blocks, 256, 0, stream>>>(m_part, l_part, o_part, z, lse_enc, BH, s.M, parts); break;
         case 8: encode_merge_kernel<8><<<blocks, 256, 0, stream>>>(m_part, l_part, o_part, z, lse_enc, BH, s.M, parts); break;
