@@ -142,8 +142,9 @@ int flare_forward(const flare_shape *shape, const void *q_lat, const void *k, co
  *   y, lse_dec: what flare_forward wrote, or NULL.  When both are given, delta_n is taken from
  *     the stored y and the decode normaliser from lse_dec; when either is NULL both are
  *     recomputed from z (one more pass over the scores, Y in fp32).  With bf16 storage (or f16
- *     storage on the matrix-core kernels) and d < 16 they are recomputed in either case: delta
- *     from a y of bf16 accuracy and so few elements would not meet the accuracy of the rest
+ *     storage on the matrix-core kernels) and d < 16, or at most 32 tokens, they are recomputed in
+ *     either case: delta from a y of bf16 accuracy and so few terms would not meet the accuracy of
+ *     the rest
  *                                                                           (in, optional)
  *   dq_lat [H][M][d] fp32 (summed over the batch), dk, dv [B][H][N][d] dtype (out)
  */

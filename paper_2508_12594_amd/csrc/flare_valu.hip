@@ -763,7 +763,10 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     // With bf16 storage (or bf16 softmax weights behind fp16 storage: the matrix-core path) and d < 16,
     // delta = <dY_n, Y_n> from the forward's y is too coarse (few terms, and c - delta cancels): such
     // shapes recompute the statistics even when y and lse_dec are given.
-    const bool coarse_y = (s.dtype == FLARE_BF16 || (s.dtype == FLARE_F16 && mf)) && s.d < 16;
+    // The same with at most one tile of tokens: every dot product and sum is short, nothing averages the
+    // rounding of y out (2 and 3 tokens: dq_lat, dK 2.1-2.4e-2 from the saved y, 8e-3 recomputed), and the
+    // recomputation costs nothing at that size.
+    const bool coarse_y = (s.dtype == FLARE_BF16 || (s.dtype == FLARE_F16 && mf)) && (s.d < 16 || s.N <= 32);
     const bool saved = y && lse_dec && !coarse_y;
     const bool fused = saved && mf && mfma_dkdv_supported(s);   // every later kernel is a matrix-core one
     const float *ld = fused ? lse_dec : w.lse_dec2;
