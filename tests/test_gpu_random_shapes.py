@@ -39,7 +39,7 @@ def _draw_case(i):
     return dict(i=i, dtype=dtype, B=B, H=H, N=N, M=M, d=d, layout=layout, saved=saved, gain=gain, kind=kind)
 
 
-CASES = [_draw_case(i) for i in range(48)]
+CASES = [_draw_case(i) for i in range(128)]
 SENTINEL = 12288.0   # exactly representable in fp32, bf16 and fp16
 
 
