@@ -97,7 +97,10 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
             u32x4 wu;
             wu[0] = lower ? ((us & 0xffffu) | (us << 16)) : 0u;
             wu[1] = lower ? (us >> 16) : 0u;
-            wu[2] = 0u; wu[3] = 0u;
+            // slots 4,5 := -eps (hi + lo): with one exponential the a chain's correction rides in the same
+            // product as the c chain's (against ones in the token operand), see the tile loop
+            wu[2] = (!PACK && lower) ? split_bf16_pair(real ? -eps[(size_t)bh * M + m] : 0.f) : 0u;
+            wu[3] = 0u;
             u_aug[b] = as_bf16x8(wu);
         }
         u32x4 wq;
@@ -262,11 +265,16 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
             wb[0] = 0u; wb[2] = 0u; wb[3] = 0u;
             wb[1] = lower ? split_pair<F>(nld) : 0u;             // slots 2,3 := -lse_dec2[n]
             const bf16x8 kt_a = ones_s, kt_b = as_bf16x8(wb);    // slots 0,1 := 1 picks -lse_enc2
+            // One exponential (d >= 16): dS = P (a + w c) and w[n] is this lane's token's, so ONE product serves
+            // both corrections: slots 0,1,2 = -w delta (hi, lo, hi) meet u (hi, hi, lo) and slots 4,5 = 1 pick
+            // -eps; the a chain starts from it and the c chain from zero.
+            constexpr bool MERGED = ONE && !PACK;
             u32x4 wg;
-            const uint32_t ds_ = split_bf16_pair(-dl);
+            const uint32_t ds_ = split_bf16_pair(MERGED ? -dl * fast_exp2(kap + nld) : -dl);
             wg[0] = lower ? ds_ : 0u;
             wg[1] = (ONE && lower) ? (ds_ & 0xffffu) : 0u;       // ONE: slots 0,1,2 := -delta hi, lo, hi
-            wg[2] = 0u; wg[3] = 0u;
+            wg[2] = (MERGED && lower) ? 0x3f803f80u : 0u;
+            wg[3] = 0u;
             const bf16x8 g_aug = as_bf16x8(wg);
 
             const int rem = n1 - tok0 - 4 * hh;
@@ -283,9 +291,13 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
                 f32x16 s1 = mfma_s<F>(kt_a, q_aug[b], x);
                 f32x16 s2 = s1;
                 if constexpr (!ONE) s2 = mfma_s<F>(kt_b, q_aug[b], x);
-                f32x16 av = splat16(0.f);
-                if constexpr (!PACK) av = mfma(ones_aug, dz_aug[b], av);
-                f32x16 cv = mfma(g_aug, ONE ? u_aug[ONE ? b : 0] : ones_aug, splat16(0.f));
+                f32x16 av = splat16(0.f), cv = splat16(0.f);
+                if constexpr (MERGED) {
+                    av = mfma(g_aug, u_aug[ONE ? b : 0], av);
+                } else {
+                    if constexpr (!PACK) av = mfma(ones_aug, dz_aug[b], av);
+                    cv = mfma(g_aug, ONE ? u_aug[ONE ? b : 0] : ones_aug, cv);
+                }
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
                     av = mfma(vt[ks], dzb[b][ks], av);
