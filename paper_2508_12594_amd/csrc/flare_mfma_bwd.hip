@@ -38,7 +38,11 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
 {
     constexpr int D = padded_dim(DR);
     constexpr int KS = D / 16;
-    constexpr int HV = D / 16;
+    // Row blocks of the dQ accumulation.  d <= 16: one 32x32 product per 16 columns (rows 16-31 of the K^T
+    // operand are zero).  d = 32: the 32 columns fill the 32 rows of ONE product (WIDE).
+    constexpr bool WIDE = (D == 32);
+    constexpr int HV = WIDE ? 1 : D / 16;
+    constexpr int QUARTS = WIDE ? 4 : 2;        // 4-column pieces per lane and accumulator: columns 8 q + 4 hh (+ 16 hv)
     constexpr int ROWS = D + 1;                 // K^T rows, then a row of zeros
     // d <= 8: the upper half of the padded contraction carries what otherwise needs products of its own:
     // q' lo and Z lo (K and dY rows repeated in both lane halves) and -eps (against ones in the V operand).
@@ -174,7 +178,7 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
 
     int krow[HV];
 #pragma unroll
-    for (int hv = 0; hv < HV; ++hv) krow[hv] = (l32 < 16) ? 16 * hv + l32 : D;
+    for (int hv = 0; hv < HV; ++hv) krow[hv] = WIDE ? l32 : ((l32 < 16) ? 16 * hv + l32 : D);
 
     auto tile_tok0 = [&](int j) { return n0 + 32 * (tg + min(j, cnt - 1) * TG); };
     // A operand: row = token.  rep (PACK only): both lane halves get elements 0-7 of the row.
@@ -349,12 +353,14 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
         if (lat0 + 32 * b + l32 >= M) continue;
         const size_t slot = part * M + lat0 + 32 * b + l32;
 #pragma unroll
-        for (int hv = 0; hv < HV; ++hv) {
-            float4 lo4 = make_float4(acc[b][hv][0], acc[b][hv][1], acc[b][hv][2], acc[b][hv][3]);
-            float4 hi4 = make_float4(acc[b][hv][4], acc[b][hv][5], acc[b][hv][6], acc[b][hv][7]);
-            if (quartet_inside<DR>(hv, hh, 0)) *reinterpret_cast<float4 *>(dq_part + slot * DR + 16 * hv + 4 * hh) = lo4;
-            if (quartet_inside<DR>(hv, hh, 1)) *reinterpret_cast<float4 *>(dq_part + slot * DR + 16 * hv + 8 + 4 * hh) = hi4;
-        }
+        for (int hv = 0; hv < HV; ++hv)
+#pragma unroll
+            for (int qd = 0; qd < QUARTS; ++qd) {
+                const int o = 16 * hv + 8 * qd + 4 * hh;
+                if (o >= DR) continue;
+                *reinterpret_cast<float4 *>(dq_part + slot * DR + o) = make_float4(
+                    acc[b][hv][4 * qd], acc[b][hv][4 * qd + 1], acc[b][hv][4 * qd + 2], acc[b][hv][4 * qd + 3]);
+            }
     }
 }
 
@@ -367,7 +373,7 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
 //     8,9 = -eps as a hi+lo pair; slots 10,11 = 1,1 or, with one exponential, slots 4-6 = u: they
 //     pick -delta[n] out of the token-side operand of the c chain's correction k-step);
 //   row images (row = output column, contraction over the 32 latents in accumulator order):
-//     RW1 = [dZ^T ; 0]   and   RW2 = [q^T ; 0].
+//     RW1 = [dZ^T ; 0]   and   RW2 = [q^T ; 0]   (d = 32: all 32 rows are columns of dZ and q).
 // Per token tile and latent tile:  P = 2^(S2 - lse_enc2[m]), R = 2^(S2 - lse_dec2[n]),
 //   a = <dZ_m, V_n> - eps[m],  c = <Z_m, dY_n> - delta[n],  dS = P a + R c  (fp32), then
 //   acc1 += RW1 . P   (rows 0-15: dV^T)
@@ -412,7 +418,12 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     // chunk with m0 = 0 stores instead) and dkdv_finish_kernel rounds the sums to dk and dv.
     constexpr int D = padded_dim(DR);
     constexpr int KS = D / 16;
-    constexpr int HV = D / 16;
+    // Row blocks of the two accumulations.  d <= 16: one 32x32 product per 16 columns (rows 16-31 of its
+    // operand image are zero).  d = 32: the 32 columns fill the 32 rows of ONE product (WIDE), half the
+    // matrix instructions of two half-empty ones.
+    constexpr bool WIDE = (D == 32);
+    constexpr int HV = WIDE ? 1 : D / 16;
+    constexpr int QUARTS = WIDE ? 4 : 2;        // 4-column pieces per lane and accumulator: columns 8 q + 4 hh (+ 16 hv)
     static_assert(!DQ || DR <= 16, "the fused dQ product is written for d <= 16 (16 output rows)");
     constexpr int NA = 4 * KS + 1;              // A-type images per latent tile (the last one: corrections)
     constexpr int NR = 4 * HV;                  // row images per latent tile (RW1, RW2) x 2 k-steps
@@ -547,7 +558,8 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
             } else {
                 const int rsid = sid - NA;                          // (which, hv, s2)
                 const int which = rsid / (2 * HV), hv = (rsid / 2) % HV, s2 = rsid % 2;
-                const int dd = 16 * hv + (r32 & 15);
+                const int dd = WIDE ? r32 : 16 * hv + (r32 & 15);
+                const bool row_live = WIDE || r32 < 16;
 #pragma unroll
                 for (int i = 0; i < 8; i += 2) {
                     float a, b;
@@ -557,11 +569,11 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                     const float q0 = ina ? elem_value<F>(qh_[(size_t)ma * DR + dd]) : 0.f;
                     const float q1 = inb ? elem_value<F>(qh_[(size_t)mb * DR + dd]) : 0.f;
                     if (which == 0) {
-                        a = (r32 < 16 && ina) ? dzb[(size_t)ma * DR + dd] : 0.f;
-                        b = (r32 < 16 && inb) ? dzb[(size_t)mb * DR + dd] : 0.f;
+                        a = (row_live && ina) ? dzb[(size_t)ma * DR + dd] : 0.f;
+                        b = (row_live && inb) ? dzb[(size_t)mb * DR + dd] : 0.f;
                     } else {
-                        a = (r32 < 16) ? q0 : 0.f;
-                        b = (r32 < 16) ? q1 : 0.f;
+                        a = row_live ? q0 : 0.f;
+                        b = row_live ? q1 : 0.f;
                     }
                     w[i / 2] = rne_bf16(a) | (rne_bf16(b) << 16);
                 }
@@ -793,48 +805,40 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                 }
             }
         }
-        if (n < N && acc32 != nullptr) {
-            float *dvr = acc32 + ((size_t)bh * N + n) * DR;
-            float *dkr = dvr + (size_t)gridDim.y * N * DR;
-            const bool first = m0 == 0;
+        // registers 4 q .. 4 q + 3 of an accumulator: columns (16 hv +) 8 q + 4 hh .. + 3 of this lane's token
+        if (n < N) {
 #pragma unroll
             for (int hv = 0; hv < HV; ++hv)
 #pragma unroll
-                for (int up = 0; up < 2; ++up) {
-                    if (!quartet_inside<DR>(hv, hh, up)) continue;
-                    const int o = 16 * hv + 8 * up + 4 * hh;
-                    float4 a = make_float4(acc1[hv][4 * up], acc1[hv][4 * up + 1], acc1[hv][4 * up + 2],
-                                           acc1[hv][4 * up + 3]);
-                    float4 b = make_float4(scale * acc2[hv][4 * up], scale * acc2[hv][4 * up + 1],
-                                           scale * acc2[hv][4 * up + 2], scale * acc2[hv][4 * up + 3]);
-                    if (!first) {
-                        const float4 pa = *reinterpret_cast<const float4 *>(dvr + o);
-                        const float4 pb = *reinterpret_cast<const float4 *>(dkr + o);
-                        a.x += pa.x; a.y += pa.y; a.z += pa.z; a.w += pa.w;
-                        b.x += pb.x; b.y += pb.y; b.z += pb.z; b.w += pb.w;
+                for (int qd = 0; qd < QUARTS; ++qd) {
+                    const int o = 16 * hv + 8 * qd + 4 * hh;
+                    if (o >= DR) continue;
+                    float4 a = make_float4(acc1[hv][4 * qd], acc1[hv][4 * qd + 1], acc1[hv][4 * qd + 2],
+                                           acc1[hv][4 * qd + 3]);
+                    float4 b = make_float4(scale * acc2[hv][4 * qd], scale * acc2[hv][4 * qd + 1],
+                                           scale * acc2[hv][4 * qd + 2], scale * acc2[hv][4 * qd + 3]);
+                    if (acc32 != nullptr) {
+                        float *dvr = acc32 + ((size_t)bh * N + n) * DR + o;
+                        float *dkr = dvr + (size_t)gridDim.y * N * DR;
+                        if (m0 != 0) {
+                            const float4 pa = *reinterpret_cast<const float4 *>(dvr);
+                            const float4 pb = *reinterpret_cast<const float4 *>(dkr);
+                            a.x += pa.x; a.y += pa.y; a.z += pa.z; a.w += pa.w;
+                            b.x += pb.x; b.y += pb.y; b.z += pb.z; b.w += pb.w;
+                        }
+                        *reinterpret_cast<float4 *>(dvr) = a;
+                        *reinterpret_cast<float4 *>(dkr) = b;
+                    } else {
+                        const size_t at = tok_base(ts, bh, H) + tok_off(ts, n) + o;
+                        u32x2 w;
+                        w[0] = pack_elems<F>(a.x, a.y);
+                        w[1] = pack_elems<F>(a.z, a.w);
+                        *reinterpret_cast<u32x2 *>(dv + at) = w;
+                        w[0] = pack_elems<F>(b.x, b.y);
+                        w[1] = pack_elems<F>(b.z, b.w);
+                        *reinterpret_cast<u32x2 *>(dk + at) = w;
                     }
-                    *reinterpret_cast<float4 *>(dvr + o) = a;
-                    *reinterpret_cast<float4 *>(dkr + o) = b;
                 }
-        } else if (n < N) {
-            bf16_t *dkr = dk + tok_base(ts, bh, H) + tok_off(ts, n);
-            bf16_t *dvr = dv + tok_base(ts, bh, H) + tok_off(ts, n);
-#pragma unroll
-            for (int hv = 0; hv < HV; ++hv) {
-                u32x2 w0, w1;
-                w0[0] = pack_elems<F>(acc1[hv][0], acc1[hv][1]);
-                w0[1] = pack_elems<F>(acc1[hv][2], acc1[hv][3]);
-                w1[0] = pack_elems<F>(acc1[hv][4], acc1[hv][5]);
-                w1[1] = pack_elems<F>(acc1[hv][6], acc1[hv][7]);
-                if (quartet_inside<DR>(hv, hh, 0)) *reinterpret_cast<u32x2 *>(dvr + 16 * hv + 4 * hh) = w0;
-                if (quartet_inside<DR>(hv, hh, 1)) *reinterpret_cast<u32x2 *>(dvr + 16 * hv + 8 + 4 * hh) = w1;
-                w0[0] = pack_elems<F>(scale * acc2[hv][0], scale * acc2[hv][1]);
-                w0[1] = pack_elems<F>(scale * acc2[hv][2], scale * acc2[hv][3]);
-                w1[0] = pack_elems<F>(scale * acc2[hv][4], scale * acc2[hv][5]);
-                w1[1] = pack_elems<F>(scale * acc2[hv][6], scale * acc2[hv][7]);
-                if (quartet_inside<DR>(hv, hh, 0)) *reinterpret_cast<u32x2 *>(dkr + 16 * hv + 4 * hh) = w0;
-                if (quartet_inside<DR>(hv, hh, 1)) *reinterpret_cast<u32x2 *>(dkr + 16 * hv + 8 + 4 * hh) = w1;
-            }
         }
 #pragma unroll
         for (int s = 0; s < KS; ++s) { kt[s] = ktn[s]; vt[s] = v_operand(vtn[s]); gt[s] = to_bf16(gtn[s]); }
@@ -968,7 +972,7 @@ int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v,
     const float c2 = scale * kLog2e;
     const int MT = lat_eff(s.M) == 192 ? 8 : lat_eff(s.M) / 32;   // instantiated for 1, 2, 4, 8 tiles
     const int pd = padded_dim(s.d);
-    const int KS = pd / 16, HV = pd / 16;
+    const int KS = pd / 16, HV = (pd == 32) ? 1 : pd / 16;   // d = 32: one 32-row block of row images
     const size_t lds = (size_t)MT * (4 * KS + 1 + 4 * HV) * 1024 + (fuse ? 8 * kFusedWaveLds * 2 : 0);
     const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *vv = (const bf16_t *)v, *gg = (const bf16_t *)dy;
     const bool f16 = s.dtype == FLARE_F16;
