@@ -95,6 +95,8 @@ def main():
                     help="memory order of k, v, y, dy, dk, dv: [B,H,N,d] (default) or [B,N,H,d]")
     ap.add_argument("--spectral", action="store_true",
                     help="also time flare_spectral (Algorithm 1 of the paper) on the workload; reported apart")
+    ap.add_argument("--y-f32", action="store_true",
+                    help="the forward writes y in fp32 and the backward takes delta from it (flare_shape.y_f32)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run three plain device copies of k (known size) first, for scaling profiler counters")
@@ -133,7 +135,7 @@ def main():
     code = {"f32": binding.FLARE_F32, "bf16": binding.FLARE_BF16, "f16": binding.FLARE_F16}[inp["dtype"]]
     fwd_b, bwd_b = binding.workspace_bytes(B, H, N, M, d, code)
     ws = torch.empty(max(fwd_b, bwd_b, 256), dtype=torch.uint8, device="cuda")
-    y = torch.empty_like(dev["k"])
+    y = torch.empty_like(dev["k"], dtype=torch.float32) if args.y_f32 else torch.empty_like(dev["k"])
     z = torch.empty((B, H, M, d), dtype=torch.float32, device="cuda")
     lse = torch.empty((B, H, M), dtype=torch.float32, device="cuda")
     lse_dec = torch.empty((B, H, N), dtype=torch.float32, device="cuda")
@@ -193,7 +195,7 @@ def main():
     dom_exps = exponentials(dom, B, H, N, M)
     dom_s = kernels[dom]["mean_us"] * 1e-6
     default_workload = (args.cfg == 4 and args.tokens is None and args.latents is None and args.head_dim is None
-                        and args.dtype is None)
+                        and args.dtype is None and not args.y_f32)
     traffic = sum(MEASURED_TRAFFIC_CFG4[dom]) if default_workload and dom in MEASURED_TRAFFIC_CFG4 else None
     # the roofline that binds this kernel: whichever lower bound on its duration is larger
     if dom_exps / (EXP_PEAK_GOPS * 1e9) > dom_bytes / (HBM_PEAK_GBS * 1e9):
@@ -221,7 +223,8 @@ def main():
         "config": {"workload": synth.describe(args.cfg) + ("" if args.tokens is None else " [N overridden to %d]" % N)
                    + ("" if args.latents is None else " [M overridden to %d]" % M)
                    + ("" if args.head_dim is None else " [d overridden to %d]" % d)
-                   + ("" if args.dtype is None else " [storage type overridden to %s]" % args.dtype),
+                   + ("" if args.dtype is None else " [storage type overridden to %s]" % args.dtype)
+                   + (" [y in fp32]" if args.y_f32 else ""),
                    "step": "flare_forward + flare_backward", "B": B, "H": H, "N": N, "M": M, "d": d,
                    "layout": "[B,H,N,d]" if lay == "bhnd" else "[B,N,H,d]"},
         "fwd": {"tokens_per_s": round(tokens / t_fwd, 1), "ms": round(t_fwd * 1e3, 4),

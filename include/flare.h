@@ -84,6 +84,12 @@ typedef struct {
                             (Section 3.1).  1: all heads use one latent sequence (the shared-latent
                             variant of the ablation in Appendix G): q_lat and dq_lat are [M][d], and
                             dq_lat is summed over the heads as well as over the batch */
+    int y_f32;           /* 0: y has the element type dtype.  1 (16-bit dtypes on the matrix-core kernels with
+                            M <= 256 only, else FLARE_EUNSUPPORTED): flare_decode / flare_forward write y as
+                            fp32 (same layout), and the y handed to flare_backward is that fp32 tensor.  The
+                            backward then takes delta_n = <dY_n, Y_n> from an unrounded Y, so that no shape
+                            needs the recomputation described at flare_backward (at d < 16 that pass is a
+                            sixth of the step), at the price of a y of twice the bytes */
 } flare_shape;
 
 /* Library version: major*10000 + minor*100 + patch. */
@@ -144,7 +150,7 @@ int flare_forward(const flare_shape *shape, const void *q_lat, const void *k, co
  *     recomputed from z (one more pass over the scores, Y in fp32).  With bf16 storage (or f16
  *     storage on the matrix-core kernels) and d < 16, or at most 32 tokens, they are recomputed in
  *     either case: delta from a y of bf16 accuracy and so few terms would not meet the accuracy of
- *     the rest
+ *     the rest -- unless shape->y_f32 is set and y is the forward's fp32 output
  *                                                                           (in, optional)
  *   dq_lat [H][M][d] fp32 (summed over the batch), dk, dv [B][H][N][d] dtype (out)
  */

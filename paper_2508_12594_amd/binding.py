@@ -27,7 +27,7 @@ EXPORTS = [
 class FlareShape(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int), ("H", ctypes.c_int), ("N", ctypes.c_int), ("M", ctypes.c_int),
                 ("d", ctypes.c_int), ("dtype", ctypes.c_int), ("layout", ctypes.c_int),
-                ("shared_latents", ctypes.c_int)]
+                ("shared_latents", ctypes.c_int), ("y_f32", ctypes.c_int)]
 
 
 class FlareError(RuntimeError):
@@ -98,7 +98,7 @@ def _dtype_code(t):
     raise FlareError("dtype must be float32, bfloat16 or float16, got %s" % t.dtype)
 
 
-def _shape_of(q, k, layout="bhnd"):
+def _shape_of(q, k, layout="bhnd", y_f32=False):
     if layout not in LAYOUTS:
         raise FlareError("layout must be 'bhnd' or 'bnhd'")
     if q.dim() not in (2, 3) or k.dim() != 4:
@@ -112,7 +112,13 @@ def _shape_of(q, k, layout="bhnd"):
     H, M, d = (Hk,) + tuple(q.shape) if shared else tuple(q.shape)
     if Hk != H or dk != d or q.dtype != k.dtype:
         raise FlareError("q_lat and k disagree on H, d or dtype")
-    return FlareShape(B, H, N, M, d, _dtype_code(k), LAYOUTS[layout], 1 if shared else 0)
+    return FlareShape(B, H, N, M, d, _dtype_code(k), LAYOUTS[layout], 1 if shared else 0, 1 if y_f32 else 0)
+
+
+def _wants_f32_y(y, k, y_f32):
+    """flare_shape.y_f32: asked for, or implied by an fp32 y next to 16-bit token tensors."""
+    torch = _torch()
+    return bool(y_f32) or (y is not None and y.dtype == torch.float32 and k.dtype != torch.float32)
 
 
 def _dev(t, name, dtype=None, shape=None):
@@ -175,37 +181,43 @@ def _opt_lse_dec(lse_dec, shp):
     return _dev(lse_dec, "lse_dec", torch.float32, (shp.B, shp.H, shp.N))
 
 
-def decode(q_lat, k, z, scale, y=None, lse_dec=None, workspace=None, stream=None, layout="bhnd"):
-    """flare_decode: returns y (k's shape and dtype); fills lse_dec[B,H,N] (fp32) when given."""
+def decode(q_lat, k, z, scale, y=None, lse_dec=None, workspace=None, stream=None, layout="bhnd", y_f32=False):
+    """flare_decode: returns y (k's shape; k's dtype, or fp32 with y_f32 / when an fp32 y is passed);
+    fills lse_dec[B,H,N] (fp32) when given."""
     torch = _torch()
-    shp = _shape_of(q_lat, k, layout)
+    f32y = _wants_f32_y(y, k, y_f32)
+    shp = _shape_of(q_lat, k, layout, f32y)
+    ydt = torch.float32 if f32y else k.dtype
     if y is None:
-        y = torch.empty_like(k)
+        y = torch.empty(k.shape, dtype=ydt, device=k.device)
     ws, ws_p, ws_n = _workspace(shp, "fwd", workspace, k.device)
     _check(load().flare_decode(ctypes.byref(shp), _dev(q_lat, "q_lat"), _dev(k, "k"),
                                _dev(z, "z", torch.float32, (shp.B, shp.H, shp.M, shp.d)),
-                               _dev(y, "y", k.dtype, k.shape), _opt_lse_dec(lse_dec, shp),
+                               _dev(y, "y", ydt, k.shape), _opt_lse_dec(lse_dec, shp),
                                ctypes.c_float(scale), ws_p, ws_n, _stream(stream)),
            "flare_decode")
     return y
 
 
 def forward(q_lat, k, v, scale, y=None, z=None, lse_enc=None, lse_dec=None, workspace=None, stream=None,
-            layout="bhnd"):
+            layout="bhnd", y_f32=False):
     """flare_forward: returns (y, z, lse_enc); fills lse_dec[B,H,N] (fp32) when given.
 
-    layout 'bhnd': k, v, y are [B,H,N,d]; 'bnhd': they are [B,N,H,d]."""
+    layout 'bhnd': k, v, y are [B,H,N,d]; 'bnhd': they are [B,N,H,d].  y_f32 (or an fp32 y next to 16-bit
+    inputs): y is written in fp32, for a backward that takes delta from it (flare_shape.y_f32)."""
     torch = _torch()
-    shp = _shape_of(q_lat, k, layout)
+    f32y = _wants_f32_y(y, k, y_f32)
+    shp = _shape_of(q_lat, k, layout, f32y)
+    ydt = torch.float32 if f32y else k.dtype
     if y is None:
-        y = torch.empty_like(k)
+        y = torch.empty(k.shape, dtype=ydt, device=k.device)
     if z is None:
         z = torch.empty((shp.B, shp.H, shp.M, shp.d), dtype=torch.float32, device=k.device)
     if lse_enc is None:
         lse_enc = torch.empty((shp.B, shp.H, shp.M), dtype=torch.float32, device=k.device)
     ws, ws_p, ws_n = _workspace(shp, "fwd", workspace, k.device)
     _check(load().flare_forward(ctypes.byref(shp), _dev(q_lat, "q_lat"), _dev(k, "k"),
-                                _dev(v, "v", k.dtype, k.shape), _dev(y, "y", k.dtype, k.shape),
+                                _dev(v, "v", k.dtype, k.shape), _dev(y, "y", ydt, k.shape),
                                 _dev(z, "z", torch.float32, (shp.B, shp.H, shp.M, shp.d)),
                                 _dev(lse_enc, "lse_enc", torch.float32, (shp.B, shp.H, shp.M)),
                                 _opt_lse_dec(lse_dec, shp),
@@ -217,9 +229,11 @@ def backward(q_lat, k, v, dy, z, lse_enc, scale, y=None, lse_dec=None, dq_lat=No
              workspace=None, stream=None, layout="bhnd"):
     """flare_backward: returns (dq_lat[H,M,d] fp32, dk, dv in k's dtype).
 
-    Pass the forward's y and lse_dec to reuse them; without both, they are recomputed from z."""
+    Pass the forward's y and lse_dec to reuse them; without both, they are recomputed from z.  An fp32 y next
+    to 16-bit inputs is the forward's y_f32 output."""
     torch = _torch()
-    shp = _shape_of(q_lat, k, layout)
+    f32y = _wants_f32_y(y, k, False)
+    shp = _shape_of(q_lat, k, layout, f32y)
     if dq_lat is None:
         dq_lat = torch.empty(tuple(q_lat.shape), dtype=torch.float32, device=k.device)
     if dk is None:
@@ -229,7 +243,7 @@ def backward(q_lat, k, v, dy, z, lse_enc, scale, y=None, lse_dec=None, dq_lat=No
     ws, ws_p, ws_n = _workspace(shp, "bwd", workspace, k.device)
     _check(load().flare_backward(ctypes.byref(shp), _dev(q_lat, "q_lat"), _dev(k, "k"),
                                  _dev(v, "v", k.dtype, k.shape),
-                                 None if y is None else _dev(y, "y", k.dtype, k.shape),
+                                 None if y is None else _dev(y, "y", torch.float32 if f32y else k.dtype, k.shape),
                                  _opt_lse_dec(lse_dec, shp), _dev(dy, "dy", k.dtype, k.shape),
                                  _dev(z, "z", torch.float32, (shp.B, shp.H, shp.M, shp.d)),
                                  _dev(lse_enc, "lse_enc", torch.float32, (shp.B, shp.H, shp.M)),

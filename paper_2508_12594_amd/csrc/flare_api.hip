@@ -65,6 +65,8 @@ int check_shape(const flare_shape *s)
     if (s->dtype != FLARE_F32 && s->dtype != FLARE_BF16 && s->dtype != FLARE_F16) return FLARE_EUNSUPPORTED;
     if (s->layout != FLARE_BHND && s->layout != FLARE_BNHD) return FLARE_EUNSUPPORTED;
     if (s->shared_latents != 0 && s->shared_latents != 1) return FLARE_EINVAL;
+    if (s->y_f32 != 0 && s->y_f32 != 1) return FLARE_EINVAL;
+    if (s->y_f32 && (s->dtype == FLARE_F32 || s->M > 256)) return FLARE_EUNSUPPORTED;
     if (s->d != 4 && s->d != 8 && s->d != 16 && s->d != 32) return FLARE_EUNSUPPORTED;
     if ((long long)s->B * s->H > 65535) return FLARE_EUNSUPPORTED;
     // token rows are addressed with a 24-bit multiply (tok_off)
@@ -80,7 +82,7 @@ using namespace flare;
 
 extern "C" {
 
-int flare_version(void) { return 200; }
+int flare_version(void) { return 300; }   // 0.3.0: flare_shape grew by y_f32
 
 const char *flare_strerror(int status)
 {

@@ -25,8 +25,11 @@ template <int DR, int MT, bool PRE, int MINB, int MODE, bool F>
 __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const float *__restrict__ z,
     bf16_t *__restrict__ y, const bf16_t *__restrict__ dy, float *__restrict__ lse_dec2,
-    float *__restrict__ delta, TokStride ts, TokStride ts_y, int H, int N, int Mtot, int m0, float c2, int z_lo)
+    float *__restrict__ delta, TokStride ts, TokStride ts_y, int H, int N, int Mtot, int m0, float c2, int flags)
 {
+    // flags: bit 0 (d <= 8): Z enters the value product as a hi + lo pair (see the Zaug operand below);
+    // bit 1 (MODE 0): y is an fp32 tensor of the same layout (flare_shape.y_f32)
+    const bool z_lo = (flags & 1) != 0, y32 = (flags & 2) != 0;
     // The kernel works on the latents m0 .. m0 + M of the head's Mtot (M = 32*MT of them); with more than
     // one chunk its outputs are one chunk's partial result (y normalised within the chunk, lse_dec of the
     // chunk) that decode_merge_kernel combines.  ts_y: where the rows of y go.
@@ -76,7 +79,7 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
                         const int lb = 32 * (s / 2) + perm_index(s % 2, hh, i + 1);
                         a = la < mleft ? zb[(size_t)la * DR + 16 * hv + l32] : 0.f;
                         b = lb < mleft ? zb[(size_t)lb * DR + 16 * hv + l32] : 0.f;
-                    } else if (MODE == 1 && DR <= 8 && z_lo && l32 >= 8 && l32 < 8 + DR) {
+                    } else if (DR <= 8 && z_lo && l32 >= 8 && l32 < 8 + DR) {
                         // rows 8 .. 8 + d - 1 (free at d <= 8): what the rounding of Z to bf16 left over, so
                         // that the rows of Y behind delta carry Z as a hi + lo pair like the c chain does
                         const int la = 32 * (s / 2) + perm_index(s % 2, hh, i);
@@ -258,6 +261,21 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
                 const float used = PRE ? mx : b2;
                 lse_dec2[(size_t)bh * N + n] = (used + log2f(den)) * kLn2;
             }
+            if constexpr (DR <= 8) {   // rows 8 + j: the lo part of column j (zero unless z_lo), same lane
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc[0][i] += acc[0][4 + i];
+            }
+            if (y32) {
+                float *yf = reinterpret_cast<float *>(y) + tok_base(ts_y, bh, H) + tok_off(ts_y, n);
+#pragma unroll
+                for (int hv = 0; hv < HV; ++hv)
+#pragma unroll
+                    for (int up = 0; up < 2; ++up)
+                        if (quartet_inside<DR>(hv, hh, up))
+                            *reinterpret_cast<float4 *>(yf + 16 * hv + 8 * up + 4 * hh) =
+                                make_float4(acc[hv][4 * up] * inv, acc[hv][4 * up + 1] * inv, acc[hv][4 * up + 2] * inv,
+                                            acc[hv][4 * up + 3] * inv);
+            } else
 #pragma unroll
             for (int hv = 0; hv < HV; ++hv) {
                 u32x2 w0, w1;
@@ -815,7 +833,7 @@ int mfma_dz_partial(const flare_shape &s, const void *q, const void *k, const vo
 template <int MODE>
 static int launch_decode_family(const flare_shape &s, const void *q, const void *k, const float *z, void *y,
                                 TokStride ts_y, const void *dy, float *lse_dec2, float *delta, int m0, int Mc,
-                                float scale, hipStream_t stream, bool z_lo = false)
+                                float scale, hipStream_t stream, int flags = 0)
 {
     const int BH = s.B * s.H;
     const int tiles = (s.N + 31) / 32;
@@ -827,7 +845,7 @@ static int launch_decode_family(const flare_shape &s, const void *q, const void 
     bf16_t *yy = (bf16_t *)y;
     LaunchTimer t(MODE == 0 ? KID_DECODE : KID_BWD_TOKEN_STATS, stream);
     const bool f16 = s.dtype == FLARE_F16;
-#define FLARE_DEC_ARGS qq, kk, z, yy, gg, lse_dec2, delta, tok_stride(s), ts_y, s.H, s.N, s.M, m0, c2, z_lo ? 1 : 0
+#define FLARE_DEC_ARGS qq, kk, z, yy, gg, lse_dec2, delta, tok_stride(s), ts_y, s.H, s.N, s.M, m0, c2, flags
 #define FLARE_DEC(DD, MTT, PREE, MINB)                                                                          \
     do {                                                                                                        \
         if (f16)                                                                                                \
@@ -948,11 +966,11 @@ size_t mfma_tok_part_bytes(const flare_shape &s)
 // decode (MODE 0) or token statistics (MODE 1) over all latents, in chunks of 256 when there are more
 template <int MODE>
 static int decode_all(const flare_shape &s, const void *q, const void *k, const float *z, void *y, const void *dy,
-                      float *lse_out, float *delta, float scale, void *ws, hipStream_t stream, bool z_lo = false)
+                      float *lse_out, float *delta, float scale, void *ws, hipStream_t stream, int flags = 0)
 {
     if (s.M <= kLatChunk)
         return launch_decode_family<MODE>(s, q, k, z, y, tok_stride(s), dy, lse_out, delta, 0, lat_eff(s.M), scale,
-                                          stream, z_lo);
+                                          stream, flags);
     const int C = lat_chunks(s.M);
     const size_t rows = (size_t)s.B * s.H * s.N;
     float *lse_part = reinterpret_cast<float *>(static_cast<char *>(ws) + ((rows * C * s.d * 2 + 255) & ~(size_t)255));
@@ -962,7 +980,7 @@ static int decode_all(const flare_shape &s, const void *q, const void *k, const 
         for (int c = 0; c < C; ++c) {
             const int rc = launch_decode_family<1>(s, q, k, z, nullptr, tok_stride(s), dy, lse_part + (size_t)c * rows,
                                                    delta_part + (size_t)c * rows, c * kLatChunk, kLatChunk, scale,
-                                                   stream, z_lo);
+                                                   stream, flags);
             if (rc != FLARE_OK) return rc;
         }
         LaunchTimer t(KID_DECODE_MERGE, stream);
@@ -1038,7 +1056,10 @@ int mfma_gram_partial(const flare_shape &s, const Split &sp, const void *q, cons
 int mfma_decode(const flare_shape &s, const void *q, const void *k, const float *z, void *y, float *lse_dec,
                 float scale, void *ws, hipStream_t stream)
 {
-    return decode_all<0>(s, q, k, z, y, nullptr, lse_dec, nullptr, scale, ws, stream);
+    // an fp32 y (M <= 256 only) is what the backward will form delta from: at d <= 8 its rows carry Z as the
+    // hi + lo pair that the backward's c chain carries (see mfma_token_stats)
+    const int flags = s.y_f32 ? (2 | (s.d <= 8 ? 1 : 0)) : 0;
+    return decode_all<0>(s, q, k, z, y, nullptr, lse_dec, nullptr, scale, ws, stream, flags);
 }
 
 int mfma_token_stats(const flare_shape &s, const void *q, const void *k, const float *z, const void *dy,
@@ -1048,7 +1069,7 @@ int mfma_token_stats(const flare_shape &s, const void *q, const void *k, const f
     // c = <Z_m, dY_n> carries that pair too (c - delta must cancel where one latent dominates a token): the
     // dQ kernel does, the dK/dV kernel that also forms dQ does, and the plain dK/dV kernel does at d = 4 only.
     const bool z_lo = s.d == 4 || (s.d == 8 && mfma_dkdv_supported(s) && mfma_dq_fused(s));
-    return decode_all<1>(s, q, k, z, nullptr, dy, lse_dec2, delta, scale, ws, stream, z_lo);
+    return decode_all<1>(s, q, k, z, nullptr, dy, lse_dec2, delta, scale, ws, stream, z_lo ? 1 : 0);
 }
 
 }  // namespace flare

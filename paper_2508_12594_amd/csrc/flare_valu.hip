@@ -385,6 +385,25 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(
     lse_dec2[row] = lse_dec[row] * kLog2e;
 }
 
+// The same from the forward's fp32 y (flare_shape.y_f32): delta[n] = <dY_n, Y_n> with an unrounded Y.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void bwd_prep_y32_kernel(
+    const float *__restrict__ y, const T *__restrict__ dy, float *__restrict__ delta, bool head_fastest, int H, int N,
+    size_t rows)
+{
+    const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= rows) return;
+    size_t row = t;
+    if (head_fastest) {
+        const size_t bn = t / H, h = t % H, b = bn / N, n = bn % N;
+        row = (b * H + h) * N + n;
+    }
+    float a[D], g[D];
+    load_row<D>(y + t * D, a);
+    load_row<D>(dy + t * D, g);
+    delta[row] = dot<D>(a, g);
+}
+
 // ---------------------------------------------------------------------------------------
 // dZ partials: thread = latent m; dZ[m] += R[n][m] dY[n] over the chunk's tokens.
 // ---------------------------------------------------------------------------------------
@@ -766,12 +785,19 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     // The same with at most one tile of tokens: every dot product and sum is short, nothing averages the
     // rounding of y out (2 and 3 tokens: dq_lat, dK 2.1-2.4e-2 from the saved y, 8e-3 recomputed), and the
     // recomputation costs nothing at that size.
-    const bool coarse_y = (s.dtype == FLARE_BF16 || (s.dtype == FLARE_F16 && mf)) && (s.d < 16 || s.N <= 32);
+    const bool coarse_y = (s.dtype == FLARE_BF16 || (s.dtype == FLARE_F16 && mf)) && (s.d < 16 || s.N <= 32) &&
+                          !s.y_f32;   // an fp32 y is not coarse
     const bool saved = y && lse_dec && !coarse_y;
     const bool fused = saved && mf && mfma_dkdv_supported(s);   // every later kernel is a matrix-core one
     const float *ld = fused ? lse_dec : w.lse_dec2;
     const float ld_mul = fused ? kLog2e : 1.f;
-    if (fused) {
+    const bool y32 = fused && s.y_f32;          // delta from the fp32 y, by a pass of its own over y and dY
+    if (y32) {
+        LaunchTimer t(KID_BWD_PREP, stream);
+        const size_t rows = (size_t)BH * s.N;
+        bwd_prep_y32_kernel<T, D><<<(unsigned)((rows + 255) / 256), 256, 0, stream>>>(
+            reinterpret_cast<const float *>(y), dy, w.delta, s.layout == FLARE_BNHD, s.H, s.N, rows);
+    } else if (fused) {
     } else if (saved) {
         LaunchTimer t(KID_BWD_PREP, stream);
         const size_t rows = (size_t)BH * s.N;
@@ -787,8 +813,8 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     }
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     if (mf) {
-        int rc = mfma_dz_partial(s, q, k, dy, ld, ld_mul, fused ? y : nullptr, fused ? w.delta : nullptr,
-                                 w.ld_range, w.part, scale, stream);
+        int rc = mfma_dz_partial(s, q, k, dy, ld, ld_mul, (fused && !y32) ? y : nullptr,
+                                 (fused && !y32) ? w.delta : nullptr, w.ld_range, w.part, scale, stream);
         if (rc != FLARE_OK) return rc;
         rc = mfma_bwd_plan(s, w.ld_range, lse_enc, w.plan, force_two_exp(), stream);
         if (rc != FLARE_OK) return rc;

@@ -10,9 +10,10 @@ from tests._util import slice_relerr, to_device, to_host, tol_for
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("cfg,over,layout", [(1, dict(N=600), "bhnd"), (2, dict(B=2, N=1500), "bhnd"),
-                                             (4, dict(N=1200, dtype="f16"), "bnhd")])
-def test_autograd_matches_oracle(oracle, cfg, over, layout):
+@pytest.mark.parametrize("cfg,over,layout,y_f32", [(1, dict(N=600), "bhnd", False), (2, dict(B=2, N=1500), "bhnd", False),
+                                                   (4, dict(N=1200, dtype="f16"), "bnhd", False),
+                                                   (2, dict(B=2, N=1500, d=8), "bnhd", True)])
+def test_autograd_matches_oracle(oracle, cfg, over, layout, y_f32):
     import torch
     print("[case] autograd cfg%d %s %s" % (cfg, over, layout), flush=True)
     inp = synth.make_inputs(cfg, with_dy=True, **over)
@@ -23,8 +24,9 @@ def test_autograd_matches_oracle(oracle, cfg, over, layout):
     q = dev["q"].clone().requires_grad_(True)
     k = conv(dev["k"]).clone().requires_grad_(True)
     v = conv(dev["v"]).clone().requires_grad_(True)
-    y = flare_mixer(q, k, v, scale, layout=layout)
-    y.backward(conv(dev["dy"]))
+    y = flare_mixer(q, k, v, scale, layout=layout, y_f32=y_f32)
+    assert y.dtype == (torch.float32 if y_f32 else k.dtype)
+    y.backward(conv(dev["dy"]).to(y.dtype))
     torch.cuda.synchronize()
     y_ref, _, _ = oracle.forward(inp["q"], inp["k"], inp["v"], scale)
     dq_ref, dk_ref, dv_ref = oracle.backward(inp["q"], inp["k"], inp["v"], inp["dy"], scale)
