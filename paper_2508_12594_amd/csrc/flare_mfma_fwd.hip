@@ -316,7 +316,7 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
 // loop), and the waves of latent group 0 store it to delta_out for the two kernels that follow.
 // Those waves also record the smallest and largest lse_dec2 they met, ld_range[part] = (min, max),
 // from which bwd_plan_kernel decides which variant of the next two kernels may run.
-template <int DR, int NB, int MINB, int MODE, bool F>
+template <int DR, int NB, int MINB, int MODE, bool F, bool Y32 = false>
 __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const float *__restrict__ lse_dec2, float ld_mul, const bf16_t *__restrict__ y_tok,
@@ -324,6 +324,8 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     float *__restrict__ m_part, float *__restrict__ l_part, float *__restrict__ o_part,
     TokStride ts, int H, int N, int M, int chunk_len, int parts, int G, int TG, float c2)
 {
+    // Y32 (MODE 1, d <= 8 only): y_tok points to fp32 rows (flare_shape.y_f32) instead of rows of the storage type
+    static_assert(!Y32 || (MODE == 1 && DR <= 8), "fp32 rows of y: written for the statistics of d <= 8");
     constexpr int D = padded_dim(DR);
     constexpr int KS = D / 16;
     constexpr int HV = D / 16;
@@ -465,14 +467,41 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     // delta of the wave's j-th tile (j < cnt) from its dY and Y rows: two lanes per token
     const bool do_delta = (MODE == 1) && y_tok != nullptr && blockIdx.z == 0;
     const bf16_t *yb = (MODE == 1 && y_tok != nullptr) ? y_tok + tok_base(ts, bh, H) : vb;
+    // fp32 rows of y (d <= 8: one 16-byte piece of dY per token, in the even lane of its pair): the even lane
+    // takes columns 0-3, the odd lane columns 4-7 (d = 8), four floats each -- the same registers as a
+    // 16-bit piece -- and the odd lane fetches its half of the dY piece from its neighbour
     auto load_y = [&](int j, u32x4 (&yy)[LOADS]) {
         const int nv = min(tile_tok0(j) + vtok, N - 1);
+        if constexpr (Y32) {
+            {
+                const float *yf = reinterpret_cast<const float *>(y_tok) + tok_base(ts, bh, H) + tok_off(ts, nv);
+                u32x4 w;
+                w[0] = 0u; w[1] = 0u; w[2] = 0u; w[3] = 0u;
+                if (DR == 8 || (lane & 1) == 0) w = *reinterpret_cast<const u32x4 *>(yf + 4 * (lane & 1));
+                yy[0] = w;
+                return;
+            }
+        }
 #pragma unroll
         for (int i = 0; i < LOADS; ++i)
             yy[i] = row8_bf16<DR>(yb + tok_off(ts, nv), 8 * ((lane & 1) * LOADS + i));
     };
     auto put_delta = [&](int j, const u32x4 (&gv)[LOADS], const u32x4 (&yy)[LOADS]) {
         float part = 0.f;
+        bool done = false;
+        if constexpr (Y32) {
+            {
+                const uint32_t n2 = (uint32_t)__builtin_amdgcn_mov_dpp((int)gv[0][2], 0xB1, 0xf, 0xf, true);
+                const uint32_t n3 = (uint32_t)__builtin_amdgcn_mov_dpp((int)gv[0][3], 0xB1, 0xf, 0xf, true);
+                const uint32_t g0 = (lane & 1) ? n2 : gv[0][0], g1 = (lane & 1) ? n3 : gv[0][1];
+                part = dy_lo<F>(g0) * __uint_as_float(yy[0][0]);
+                part = fmaf(dy_hi<F>(g0), __uint_as_float(yy[0][1]), part);
+                part = fmaf(dy_lo<F>(g1), __uint_as_float(yy[0][2]), part);
+                part = fmaf(dy_hi<F>(g1), __uint_as_float(yy[0][3]), part);
+                done = true;
+            }
+        }
+        if (!done) {
 #pragma unroll
         for (int i = 0; i < LOADS; ++i)
 #pragma unroll
@@ -480,6 +509,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
                 part = fmaf(dy_lo<F>(gv[i][e]), elem_lo<F>(yy[i][e]), part);
                 part = fmaf(dy_hi<F>(gv[i][e]), elem_hi<F>(yy[i][e]), part);
             }
+        }
         // the other half of the row is in the neighbouring lane: quad_perm [1,0,3,2]
         part += __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(part), 0xB1, 0xf, 0xf, true));
         const int n = n0 + 32 * (tg + j * TG) + vtok;
@@ -800,16 +830,26 @@ int mfma_dz_partial(const flare_shape &s, const void *q, const void *k, const vo
     const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *gg = (const bf16_t *)dy;
     LaunchTimer t(KID_BWD_DZ_PARTIAL, stream);
     const bool f16 = s.dtype == FLARE_F16;
+    if (y != nullptr && s.y_f32 && s.d > 8) return FLARE_EUNSUPPORTED;   // the caller forms delta itself there
+    const int y32 = (y != nullptr && s.y_f32) ? 1 : 0;
+#define FLARE_DZ_ARGS                                                                                            \
+    qq, kk, gg, lse_dec2, ld_mul, (const bf16_t *)y, delta_out, ld_range, nullptr, nullptr, dz_part, tok_stride(s), \
+        s.H, s.N, s.M, p.enc.chunk_len, p.parts, e.G, e.TG, c2
 #define FLARE_DZ(DD, NBB)                                                                                         \
     do {                                                                                                          \
+        if constexpr (DD <= 8) {                                                                                  \
+            if (y32 && f16) {                                                                                     \
+                encode_mfma_kernel<DD, NBB, 2, 1, true, true><<<grid, e.threads, 0, stream>>>(FLARE_DZ_ARGS);     \
+                break;                                                                                            \
+            } else if (y32) {                                                                                     \
+                encode_mfma_kernel<DD, NBB, 2, 1, false, true><<<grid, e.threads, 0, stream>>>(FLARE_DZ_ARGS);    \
+                break;                                                                                            \
+            }                                                                                                     \
+        }                                                                                                         \
         if (f16)                                                                                                  \
-            encode_mfma_kernel<DD, NBB, 2, 1, true><<<grid, e.threads, 0, stream>>>(                              \
-                qq, kk, gg, lse_dec2, ld_mul, (const bf16_t *)y, delta_out, ld_range, nullptr, nullptr, dz_part,  \
-                tok_stride(s), s.H, s.N, s.M, p.enc.chunk_len, p.parts, e.G, e.TG, c2);                           \
+            encode_mfma_kernel<DD, NBB, 2, 1, true><<<grid, e.threads, 0, stream>>>(FLARE_DZ_ARGS);               \
         else                                                                                                      \
-            encode_mfma_kernel<DD, NBB, 2, 1, false><<<grid, e.threads, 0, stream>>>(                             \
-                qq, kk, gg, lse_dec2, ld_mul, (const bf16_t *)y, delta_out, ld_range, nullptr, nullptr, dz_part,  \
-                tok_stride(s), s.H, s.N, s.M, p.enc.chunk_len, p.parts, e.G, e.TG, c2);                           \
+            encode_mfma_kernel<DD, NBB, 2, 1, false><<<grid, e.threads, 0, stream>>>(FLARE_DZ_ARGS);              \
     } while (0)
 #define FLARE_DZ_NB(DD)                   \
     do {                                  \
@@ -827,6 +867,7 @@ int mfma_dz_partial(const flare_shape &s, const void *q, const void *k, const vo
     }
 #undef FLARE_DZ_NB
 #undef FLARE_DZ
+#undef FLARE_DZ_ARGS
     return check_launch();
 }
 

@@ -791,7 +791,8 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     const bool fused = saved && mf && mfma_dkdv_supported(s);   // every later kernel is a matrix-core one
     const float *ld = fused ? lse_dec : w.lse_dec2;
     const float ld_mul = fused ? kLog2e : 1.f;
-    const bool y32 = fused && s.y_f32;          // delta from the fp32 y, by a pass of its own over y and dY
+    // delta from the fp32 y: at d <= 8 inside the dZ kernel like from a 16-bit y, else by a pass of its own
+    const bool y32 = fused && s.y_f32 && s.d > 8;
     if (y32) {
         LaunchTimer t(KID_BWD_PREP, stream);
         const size_t rows = (size_t)BH * s.N;
