@@ -133,7 +133,7 @@ def main():
     lay = args.layout
     scale = inp["scale"]
     code = {"f32": binding.FLARE_F32, "bf16": binding.FLARE_BF16, "f16": binding.FLARE_F16}[inp["dtype"]]
-    fwd_b, bwd_b = binding.workspace_bytes(B, H, N, M, d, code)
+    fwd_b, bwd_b = binding.workspace_bytes(B, H, N, M, d, code, args.y_f32)
     ws = torch.empty(max(fwd_b, bwd_b, 256), dtype=torch.uint8, device="cuda")
     y = torch.empty_like(dev["k"], dtype=torch.float32) if args.y_f32 else torch.empty_like(dev["k"])
     z = torch.empty((B, H, M, d), dtype=torch.float32, device="cuda")

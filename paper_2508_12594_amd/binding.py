@@ -137,9 +137,12 @@ def _stream(stream):
     return ctypes.c_void_p(s.cuda_stream)
 
 
-def workspace_bytes(B, H, N, M, d, dtype_code):
+def workspace_bytes(B, H, N, M, d, dtype_code, y_f32=False):
     """(forward bytes, backward bytes) of scratch for this shape (the same for both layouts)."""
-    shp = FlareShape(B, H, N, M, d, dtype_code, FLARE_BHND)
+    return _shape_workspace_bytes(FlareShape(B, H, N, M, d, dtype_code, FLARE_BHND, 0, 1 if y_f32 else 0))
+
+
+def _shape_workspace_bytes(shp):
     f, b = ctypes.c_size_t(0), ctypes.c_size_t(0)
     _check(load().flare_workspace_bytes(ctypes.byref(shp), ctypes.byref(f), ctypes.byref(b)),
            "flare_workspace_bytes")
@@ -148,7 +151,7 @@ def workspace_bytes(B, H, N, M, d, dtype_code):
 
 def _workspace(shp, which, workspace, device):
     torch = _torch()
-    f, b = workspace_bytes(shp.B, shp.H, shp.N, shp.M, shp.d, shp.dtype)
+    f, b = _shape_workspace_bytes(shp)
     need = f if which == "fwd" else b
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)

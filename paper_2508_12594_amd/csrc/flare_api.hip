@@ -66,7 +66,7 @@ int check_shape(const flare_shape *s)
     if (s->layout != FLARE_BHND && s->layout != FLARE_BNHD) return FLARE_EUNSUPPORTED;
     if (s->shared_latents != 0 && s->shared_latents != 1) return FLARE_EINVAL;
     if (s->y_f32 != 0 && s->y_f32 != 1) return FLARE_EINVAL;
-    if (s->y_f32 && (s->dtype == FLARE_F32 || s->M > 256)) return FLARE_EUNSUPPORTED;
+    if (s->y_f32 && (s->dtype == FLARE_F32 || s->M > 2048)) return FLARE_EUNSUPPORTED;   // matrix-core shapes only
     if (s->d != 4 && s->d != 8 && s->d != 16 && s->d != 32) return FLARE_EUNSUPPORTED;
     if ((long long)s->B * s->H > 65535) return FLARE_EUNSUPPORTED;
     // token rows are addressed with a 24-bit multiply (tok_off)

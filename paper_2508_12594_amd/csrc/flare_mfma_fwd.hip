@@ -970,6 +970,42 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(
     if (lse_out) lse_out[row] = mx + __logf(tot);
 }
 
+// The same for fp32 rows (flare_shape.y_f32): fp32 partial rows in, fp32 y out.
+template <int DR>
+__global__ __launch_bounds__(256) void decode_merge_f32_kernel(
+    const float *__restrict__ y_part, const float *__restrict__ lse_part, int chunks, float *__restrict__ y,
+    float *__restrict__ lse_out, TokStride ts, int H, int N, size_t rows_all)
+{
+    const int n = blockIdx.x * 256 + threadIdx.x;
+    if (n >= N) return;
+    const int bh = blockIdx.y;
+    const size_t row = (size_t)bh * N + n;
+    float mx = -INFINITY;
+    for (int c = 0; c < chunks; ++c) mx = fmaxf(mx, lse_part[(size_t)c * rows_all + row]);
+    float acc[DR], tot = 0.f;
+#pragma unroll
+    for (int j = 0; j < DR; ++j) acc[j] = 0.f;
+    for (int c = 0; c < chunks; ++c) {
+        const float w = __expf(lse_part[(size_t)c * rows_all + row] - mx);
+        tot += w;
+        const float *src = y_part + ((size_t)c * rows_all + row) * DR;
+#pragma unroll
+        for (int j = 0; j < DR; j += 4) {
+            const float4 t = *reinterpret_cast<const float4 *>(src + j);
+            acc[j] = fmaf(w, t.x, acc[j]);
+            acc[j + 1] = fmaf(w, t.y, acc[j + 1]);
+            acc[j + 2] = fmaf(w, t.z, acc[j + 2]);
+            acc[j + 3] = fmaf(w, t.w, acc[j + 3]);
+        }
+    }
+    const float inv = 1.f / tot;
+    float *dst = y + tok_base(ts, bh, H) + tok_off(ts, n);
+#pragma unroll
+    for (int j = 0; j < DR; j += 4)
+        *reinterpret_cast<float4 *>(dst + j) = make_float4(acc[j] * inv, acc[j + 1] * inv, acc[j + 2] * inv, acc[j + 3] * inv);
+    if (lse_out) lse_out[row] = mx + __logf(tot);
+}
+
 // Combine the per-chunk token statistics of the backward (M > 256).  Chunk c gives, for token n,
 // lse2_c = log2 sum_{m in c} 2^S2[m][n] and delta_c = <dY_n, Y_n^c> with Y_n^c the decode over the chunk's
 // latents alone, formed in fp32 registers; then
@@ -1001,7 +1037,7 @@ size_t mfma_tok_part_bytes(const flare_shape &s)
 {
     if (s.M <= kLatChunk) return 0;
     const size_t rows = (size_t)s.B * s.H * s.N * lat_chunks(s.M);
-    return ((rows * s.d * 2 + 255) & ~(size_t)255) + ((rows * 4 + 255) & ~(size_t)255);
+    return ((rows * s.d * (s.y_f32 ? 4 : 2) + 255) & ~(size_t)255) + ((rows * 4 + 255) & ~(size_t)255);
 }
 
 // decode (MODE 0) or token statistics (MODE 1) over all latents, in chunks of 256 when there are more
@@ -1014,7 +1050,8 @@ static int decode_all(const flare_shape &s, const void *q, const void *k, const 
                                           stream, flags);
     const int C = lat_chunks(s.M);
     const size_t rows = (size_t)s.B * s.H * s.N;
-    float *lse_part = reinterpret_cast<float *>(static_cast<char *>(ws) + ((rows * C * s.d * 2 + 255) & ~(size_t)255));
+    const size_t es = s.y_f32 ? 4 : 2;          // bytes per element of the partial rows
+    float *lse_part = reinterpret_cast<float *>(static_cast<char *>(ws) + ((rows * C * s.d * es + 255) & ~(size_t)255));
     if constexpr (MODE == 1) {
         // per-chunk statistics in fp32 (delta_c in the space of the partial rows, which this mode does not need)
         float *delta_part = static_cast<float *>(ws);
@@ -1032,13 +1069,23 @@ static int decode_all(const flare_shape &s, const void *q, const void *k, const 
         bf16_t *y_part = static_cast<bf16_t *>(ws);
         const TokStride tp{(long long)s.H * s.N * s.d, (long long)s.N * s.d, s.d, 0};   // partial rows: [b][h][n][d]
         for (int c = 0; c < C; ++c) {
-            const int rc = launch_decode_family<0>(s, q, k, z, y_part + (size_t)c * rows * s.d, tp, nullptr,
-                                                   lse_part + (size_t)c * rows, nullptr, c * kLatChunk, kLatChunk,
-                                                   scale, stream);
+            void *part_c = static_cast<char *>(ws) + (size_t)c * rows * s.d * es;
+            const int rc = launch_decode_family<0>(s, q, k, z, part_c, tp, nullptr, lse_part + (size_t)c * rows, nullptr,
+                                                   c * kLatChunk, kLatChunk, scale, stream, flags);
             if (rc != FLARE_OK) return rc;
         }
         const dim3 grid((s.N + 255) / 256, s.B * s.H);
         LaunchTimer t(KID_DECODE_MERGE, stream);
+        if (s.y_f32) {
+            const float *yp = static_cast<const float *>(ws);
+            switch (s.d) {
+                case 4: decode_merge_f32_kernel<4><<<grid, 256, 0, stream>>>(yp, lse_part, C, (float *)y, lse_out, tok_stride(s), s.H, s.N, rows); break;
+                case 8: decode_merge_f32_kernel<8><<<grid, 256, 0, stream>>>(yp, lse_part, C, (float *)y, lse_out, tok_stride(s), s.H, s.N, rows); break;
+                case 16: decode_merge_f32_kernel<16><<<grid, 256, 0, stream>>>(yp, lse_part, C, (float *)y, lse_out, tok_stride(s), s.H, s.N, rows); break;
+                default: decode_merge_f32_kernel<32><<<grid, 256, 0, stream>>>(yp, lse_part, C, (float *)y, lse_out, tok_stride(s), s.H, s.N, rows); break;
+            }
+            return check_launch();
+        }
         const bool f16 = s.dtype == FLARE_F16;
 #define FLARE_DM(DD)                                                                                              \
     do {                                                                                                          \
@@ -1097,7 +1144,7 @@ int mfma_gram_partial(const flare_shape &s, const Split &sp, const void *q, cons
 int mfma_decode(const flare_shape &s, const void *q, const void *k, const float *z, void *y, float *lse_dec,
                 float scale, void *ws, hipStream_t stream)
 {
-    // an fp32 y (M <= 256 only) is what the backward will form delta from: at d <= 8 its rows carry Z as the
+    // an fp32 y is what the backward will form delta from: at d <= 8 its rows carry Z as the
     // hi + lo pair that the backward's c chain carries (see mfma_token_stats)
     const int flags = s.y_f32 ? (2 | (s.d <= 8 ? 1 : 0)) : 0;
     return decode_all<0>(s, q, k, z, y, nullptr, lse_dec, nullptr, scale, ws, stream, flags);

@@ -21,6 +21,9 @@ CASES = [
     (3, dict(B=2, N=700, dtype="f16"), "bhnd"),
     (2, dict(B=1, N=20, M=7, d=8), "bhnd"),          # a single token tile, few latents
     (2, dict(B=2, H=3, N=365, M=200, d=4, seed=777 + 1375), "bhnd"),   # a latent that dominates many tokens
+    (2, dict(B=1, N=1500, M=512, d=8), "bhnd"),      # more than 256 latents: fp32 partial rows per chunk of latents
+    (4, dict(N=900, M=300, d=16), "bnhd"),
+    (2, dict(B=1, H=2, N=700, M=1000, d=4, dtype="f16"), "bhnd"),
 ]
 
 
@@ -59,10 +62,10 @@ def test_forward_backward_with_fp32_y(oracle, cfg, over, layout):
 
 def test_fp32_y_is_refused_where_it_is_not_built():
     import torch
-    inp = synth.make_inputs(2, B=1, N=300, M=512, with_dy=False)
+    inp = synth.make_inputs(2, B=1, H=1, N=100, M=2100, with_dy=False)
     dev = to_device(inp)
     with pytest.raises(binding.FlareError):
-        binding.forward(dev["q"], dev["k"], dev["v"], inp["scale"], y_f32=True)      # more than 256 latents
+        binding.forward(dev["q"], dev["k"], dev["v"], inp["scale"], y_f32=True)      # beyond the matrix-core kernels
     inp = synth.make_inputs(1, N=300, with_dy=False)
     dev = to_device(inp)
     shp = binding._shape_of(dev["q"], dev["k"], "bhnd", True)                        # fp32 storage: y is fp32 anyway
