@@ -72,3 +72,16 @@ def test_fp32_y_is_refused_where_it_is_not_built():
     import ctypes
     assert binding.load().flare_workspace_bytes(ctypes.byref(shp), None, None) == -2
     torch.cuda.synchronize()
+
+
+def test_decode_alone_writes_the_same_fp32_y():
+    import torch
+    inp = synth.make_inputs(2, B=2, N=1111, d=8, with_dy=False)
+    dev = to_device(inp)
+    y, z, _ = binding.forward(dev["q"], dev["k"], dev["v"], inp["scale"], y_f32=True)
+    y2 = binding.decode(dev["q"], dev["k"], z, inp["scale"], y_f32=True)
+    y16 = binding.decode(dev["q"], dev["k"], z, inp["scale"])
+    torch.cuda.synchronize()
+    assert y2.dtype == torch.float32 and torch.equal(y, y2)
+    # the 16-bit y of the ordinary path is this one rounded, up to the lo part of Z that only the fp32 rows carry
+    assert float((y16.float() - y).abs().max()) <= 2.0 ** -7 * float(y.abs().max())
