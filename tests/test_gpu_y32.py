@@ -85,3 +85,22 @@ def test_decode_alone_writes_the_same_fp32_y():
     assert y2.dtype == torch.float32 and torch.equal(y, y2)
     # the 16-bit y of the ordinary path is this one rounded, up to the lo part of Z that only the fp32 rows carry
     assert float((y16.float() - y).abs().max()) <= 2.0 ** -7 * float(y.abs().max())
+
+
+def test_million_tokens_fp32_y_agrees_with_recomputed_statistics():
+    """Full size (N = 1,000,000, M = 256, H = 8, d = 8, the launch configuration of bench.py --head-dim 8 --y-f32):
+    the gradients from the fp32 y against those from the recomputed statistics, which the full-size tests
+    check against the oracle."""
+    import torch
+    inp = synth.make_inputs(4, with_dy=True, d=8)
+    dev = to_device(inp)
+    scale = inp["scale"]
+    lse_dec = torch.empty(dev["k"].shape[:3], dtype=torch.float32, device="cuda")
+    y, z, lse = binding.forward(dev["q"], dev["k"], dev["v"], scale, lse_dec=lse_dec, y_f32=True)
+    dq, dk, dv = binding.backward(dev["q"], dev["k"], dev["v"], dev["dy"], z, lse, scale, y=y, lse_dec=lse_dec)
+    dq0, dk0, dv0 = binding.backward(dev["q"], dev["k"], dev["v"], dev["dy"], z, lse, scale)
+    torch.cuda.synchronize()
+    rel = lambda a, b: float((a.double() - b.double()).norm() / b.double().norm())
+    errs = (rel(dq, dq0), rel(dk, dk0), rel(dv, dv0))
+    print("[case]    fp32 y against recomputed statistics at N = 10^6: dq %.2e dk %.2e dv %.2e" % errs, flush=True)
+    assert max(errs) <= 5e-3
