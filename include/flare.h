@@ -150,7 +150,9 @@ int flare_forward(const flare_shape *shape, const void *q_lat, const void *k, co
  *     recomputed from z (one more pass over the scores, Y in fp32).  With bf16 storage (or f16
  *     storage on the matrix-core kernels) and d < 16, or at most 32 tokens, they are recomputed in
  *     either case: delta from a y of bf16 accuracy and so few terms would not meet the accuracy of
- *     the rest -- unless shape->y_f32 is set and y is the forward's fp32 output
+ *     the rest -- unless shape->y_f32 is set and y is the forward's fp32 output.  (16-bit shapes of
+ *     fewer than 8 tokens run on the fp32 kernels throughout, forward and backward: with so few tokens
+ *     the gradients' differences cancel too far for bf16 operands.)
  *                                                                           (in, optional)
  *   dq_lat [H][M][d] fp32 (summed over the batch), dk, dv [B][H][N][d] dtype (out)
  */

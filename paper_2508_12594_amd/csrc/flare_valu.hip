@@ -401,6 +401,16 @@ __global__ __launch_bounds__(256) void bwd_prep_y32_kernel(
     float a[D], g[D];
     load_row<D>(y + t * D, a);
     load_row<D>(dy + t * D, g);
+    if constexpr (sizeof(T) == 2) {
+        // The matrix-core kernels take dY as a bf16 operand (fp16 storage is rounded to bf16 when read), and
+        // c - delta = <dY_n, Z_m - Y_n> only cancels if delta is formed from the same rounded values.
+#pragma unroll
+        for (int i = 0; i < D; ++i) {
+            uint32_t u = __float_as_uint(g[i]);
+            u += 0x7fffu + ((u >> 16) & 1u);
+            g[i] = __uint_as_float(u & 0xffff0000u);
+        }
+    }
     delta[row] = dot<D>(a, g);
 }
 
@@ -783,9 +793,11 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     // delta = <dY_n, Y_n> from the forward's y is too coarse (few terms, and c - delta cancels): such
     // shapes recompute the statistics even when y and lse_dec are given.
     // The same with at most one tile of tokens: every dot product and sum is short, nothing averages the
-    // rounding of y out (2 and 3 tokens: dq_lat, dK 2.1-2.4e-2 from the saved y, 8e-3 recomputed), and the
-    // recomputation costs nothing at that size.
-    const bool coarse_y = (s.dtype == FLARE_BF16 || (s.dtype == FLARE_F16 && mf)) && (s.d < 16 || s.N <= 32) &&
+    // rounding of y out (dq_lat, dK 2.1-2.4e-2 from the saved y, 8e-3 recomputed), and the recomputation costs
+    // nothing at that size.
+    // (at most one tile of tokens: any 16-bit y, also fp16 on the fp32 kernels)
+    const bool bf16_weights = s.dtype == FLARE_BF16 || (s.dtype == FLARE_F16 && mf);
+    const bool coarse_y = s.dtype != FLARE_F32 && ((bf16_weights && s.d < 16) || s.N <= 32) &&
                           !s.y_f32;   // an fp32 y is not coarse
     const bool saved = y && lse_dec && !coarse_y;
     const bool fused = saved && mf && mfma_dkdv_supported(s);   // every later kernel is a matrix-core one

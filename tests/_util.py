@@ -8,14 +8,14 @@ import numpy as np
 TOL = {"f32": 1e-5, "bf16": 2e-2, "f16": 1e-3}
 
 
-def on_matrix_cores(dtype, M):
-    """The library's documented rule: 16-bit storage with at most 2048 latents per head runs on the
-    matrix-core kernels (tiles of 32 latents, the last ones padded)."""
-    return dtype != "f32" and M <= 2048
+def on_matrix_cores(dtype, M, N=None):
+    """The library's documented rule: 16-bit storage with at most 2048 latents per head and at least 8
+    tokens runs on the matrix-core kernels (tiles of 32 latents, the last ones padded)."""
+    return dtype != "f32" and M <= 2048 and (N is None or N >= 8)
 
 
 def tol_for(inp):
-    if inp["dtype"] == "f16" and on_matrix_cores("f16", inp["q"].shape[1]):
+    if inp["dtype"] == "f16" and on_matrix_cores("f16", inp["q"].shape[1], inp["k"].shape[2]):
         return TOL["bf16"]
     return TOL[inp["dtype"]]
 

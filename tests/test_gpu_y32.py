@@ -24,6 +24,9 @@ CASES = [
     (2, dict(B=1, N=1500, M=512, d=8), "bhnd"),      # more than 256 latents: fp32 partial rows per chunk of latents
     (4, dict(N=900, M=300, d=16), "bnhd"),
     (2, dict(B=1, H=2, N=700, M=1000, d=4, dtype="f16"), "bhnd"),
+    # fp16 storage at d = 16: delta comes from a pass of its own, which must round dY to bf16 as the kernels do
+    (2, dict(B=1, H=1, N=12, M=234, d=16, dtype="f16", seed=777 + 542), "bhnd"),
+    (3, dict(B=1, N=333, M=234, d=16, dtype="f16"), "bnhd"),
 ]
 
 
