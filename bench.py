@@ -185,7 +185,8 @@ def main():
         ab = algorithmic_bytes(name, B, H, N, M, d, elem)
         ex = exponentials(name, B, H, N, M)
         twin = name[:-5] if name.endswith("_2exp") else name + "_2exp"
-        if twin in prof and ms / cnt < 0.05 * prof[twin][0] / prof[twin][1]:
+        twin_ms = prof[twin][0] / prof[twin][1] if twin in prof else 0.0
+        if ms / cnt < 0.05 * twin_ms or (ms / cnt < 0.010 and ms / cnt < 0.3 * twin_ms):
             ab, ex = None, 0     # launched, but every (b,h) slice went to the other variant: it left at once
         kernels[name] = {"mean_us": round(mean_s * 1e6, 2), "launches_per_step": cnt // prof_steps,
                          "algorithmic_GBps": (round(ab / per_step_s / 1e9, 1) if ab else None),
