@@ -29,7 +29,7 @@
  *     elements (d, or H*d for FLARE_BNHD) below 2^32; d in {4, 8, 16, 32}; dtype f32, bf16 or f16;
  *     either flare_layout for the token tensors (every "[B][H][N][d]" below reads [B][N][H][d]
  *     when shape->layout is FLARE_BNHD; the per-token statistic lse_dec is [B][H][N] always).
- *     Shapes with dtype bf16 or f16 and M <= 2048 run on the matrix-core kernels (d < 16 with the
+ *     Shapes with dtype bf16 or f16, M <= 2048 and N >= 8 run on the matrix-core kernels (d < 16 with the
  *     contraction padded to 16; M in tiles of 32 on the geometry of the next of 32, 64, 128, 256
  *     or a multiple of 256, the latents beyond M being padding that is masked; M > 256 in chunks
  *     of 256 latents); everything else runs on the fp32 vector kernels.  On the matrix
