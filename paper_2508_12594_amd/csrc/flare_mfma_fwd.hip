@@ -748,8 +748,7 @@ bool mfma_supported(const flare_shape &s)
     // A handful of tokens: every Z_m lies in the span of those few value rows, so c - delta = <dY_n, Z_m - Y_n>
     // and a - eps cancel almost completely and the bf16 operands' rounding shows in dQ and dK (two tokens,
     // fp16 storage, d = 16: up to 1.6e-1 measured).  The fp32 kernels take such shapes; they cost nothing there.
-    // (An fp32 y exists only on this path, so that option keeps it.)
-    if (s.N < 8 && !s.y_f32) return false;
+    if (s.N < 8) return false;
     return s.M <= 2048;   // any number of latents: tiles of 32, the last ones padded
 }
 

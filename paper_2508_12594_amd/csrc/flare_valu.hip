@@ -291,8 +291,9 @@ template <typename T, int D, int MODE>
 __global__ __launch_bounds__(kTokenBlock) void token_pass_kernel(
     const T *__restrict__ q, const T *__restrict__ k, const float *__restrict__ z,
     T *__restrict__ y, const T *__restrict__ dy, float *__restrict__ lse_dec2, float *__restrict__ delta,
-    TokStride ts, int H, int N, int M, float c2)
+    TokStride ts, int H, int N, int M, float c2, int y_f32)
 {
+    // y_f32 (MODE 0, 16-bit T): y points to fp32 rows (flare_shape.y_f32)
     const int n = blockIdx.x * kTokenBlock + threadIdx.x;
     const int bh = blockIdx.y, h = bh % H;
     const bool valid = n < N;
@@ -352,7 +353,8 @@ __global__ __launch_bounds__(kTokenBlock) void token_pass_kernel(
     for (int j = 0; j < D; ++j) acc[j] *= inv;
     if (!valid) return;
     if constexpr (MODE == 0) {
-        store_row<D>(y + trow, acc);
+        if (sizeof(T) == 2 && y_f32) store_row<D>(reinterpret_cast<float *>(y) + trow, acc);
+        else store_row<D>(y + trow, acc);
         if (lse_dec2) lse_dec2[row] = (mr + log2f(l)) * kLn2;   // optional saved statistic, natural log
     } else {
         float g[D];
@@ -766,7 +768,7 @@ int decode_impl(const flare_shape &s, const T *q, const T *k, const float *z, T 
 {
     LaunchTimer t(KID_DECODE, stream);
     token_pass_kernel<T, D, 0><<<dim3((s.N + kTokenBlock - 1) / kTokenBlock, s.B * s.H), kTokenBlock, 0, stream>>>(
-        q, k, z, y, nullptr, lse_dec, nullptr, tok_stride(s), s.H, s.N, s.M, scale * kLog2e);
+        q, k, z, y, nullptr, lse_dec, nullptr, tok_stride(s), s.H, s.N, s.M, scale * kLog2e, s.y_f32);
     return check_launch();
 }
 
@@ -798,7 +800,8 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     // (at most one tile of tokens: any 16-bit y, also fp16 on the fp32 kernels)
     const bool bf16_weights = s.dtype == FLARE_BF16 || (s.dtype == FLARE_F16 && mf);
     const bool coarse_y = s.dtype != FLARE_F32 && ((bf16_weights && s.d < 16) || s.N <= 32) &&
-                          !s.y_f32;   // an fp32 y is not coarse
+                          !(s.y_f32 && mf);   // an fp32 y is not coarse (the fp32 kernels, which take the
+                                              // 16-bit shapes of fewer than 8 tokens, never read it: they recompute)
     const bool saved = y && lse_dec && !coarse_y;
     const bool fused = saved && mf && mfma_dkdv_supported(s);   // every later kernel is a matrix-core one
     const float *ld = fused ? lse_dec : w.lse_dec2;
@@ -822,7 +825,7 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     } else {
         LaunchTimer t(KID_BWD_TOKEN_STATS, stream);
         token_pass_kernel<T, D, 1><<<tok_grid, kTokenBlock, 0, stream>>>(q, k, z, nullptr, dy, w.lse_dec2, w.delta,
-                                                                         ts, s.H, s.N, s.M, c2);
+                                                                         ts, s.H, s.N, s.M, c2, 0);
     }
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     if (mf) {
