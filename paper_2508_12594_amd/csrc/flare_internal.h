@@ -20,7 +20,6 @@ enum KernelId {
     KID_BWD_DQ_PARTIAL,
     KID_BWD_DQ_REDUCE,
     KID_BWD_DKDV,
-    KID_BWD_PLAN,
     KID_BWD_DQ_PARTIAL_2EXP,
     KID_BWD_DKDV_2EXP,
     KID_DECODE_MERGE,
@@ -144,8 +143,40 @@ int mfma_dz_partial(const flare_shape &s, const void *q, const void *k, const vo
 // The dQ and dK/dV kernels exist in two variants, one and two exponentials per score.  Both are
 // launched; each leaves at once the (b,h) slices that plan[b*h] (1 = one exponential) gives to the
 // other.  ld_range[b*h][part] = (min, max) of lse_dec2 as mfma_dz_partial recorded it.
-int mfma_bwd_plan(const flare_shape &s, const float *ld_range, const float *lse_enc, int *plan, bool force_two,
-                  hipStream_t stream);
+// plan[bh] = 1 iff, with kappa = max_m lse_enc2[m], every u[m] = 2^(lse_enc2[m] - kappa) >= 2^-kPlanSpan and
+// every w[n] = 2^(kappa - lse_dec2[n]) lies in [2^-kPlanSpan, 2^kPlanSpan].  Then wherever
+// R = P u w is above 2^-(126 - 2 kPlanSpan), P is a normal fp32 number and nothing is lost; anything
+// else (wide score ranges, non-finite statistics) takes the two-exponential kernels.
+// Called by one whole wave (of the kernel that merges the dZ partials: everything it reads is complete by then).
+constexpr float kPlanSpan = 50.f;
+__device__ __forceinline__ void bwd_plan_wave(const float *__restrict__ ld_range, const float *__restrict__ lse_enc,
+                                              int *__restrict__ plan, int bh, int parts, int M, int force_two)
+{
+    const int lane = threadIdx.x & 63;
+    float le_min = INFINITY, le_max = -INFINITY, ld_min = INFINITY, ld_max = -INFINITY;
+    for (int m = lane; m < M; m += 64) {
+        const float v = lse_enc[(size_t)bh * M + m] * 1.4426950408889634f;
+        le_min = fminf(le_min, v);
+        le_max = fmaxf(le_max, v);
+    }
+    for (int p = lane; p < parts; p += 64) {
+        ld_min = fminf(ld_min, ld_range[2 * ((size_t)bh * parts + p)]);
+        ld_max = fmaxf(ld_max, ld_range[2 * ((size_t)bh * parts + p) + 1]);
+    }
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        le_min = fminf(le_min, __shfl_xor(le_min, off));
+        le_max = fmaxf(le_max, __shfl_xor(le_max, off));
+        ld_min = fminf(ld_min, __shfl_xor(ld_min, off));
+        ld_max = fmaxf(ld_max, __shfl_xor(ld_max, off));
+    }
+    if (lane == 0) {
+        // written so that a NaN anywhere makes the test fail
+        const bool ok = (le_max - le_min <= kPlanSpan) && (le_max - ld_min <= kPlanSpan) &&
+                        (ld_max - le_max <= kPlanSpan) && fabsf(le_max) < 1e30f;
+        plan[bh] = (ok && !force_two) ? 1 : 0;
+    }
+}
 
 // ---- spectral analysis (Appendix C.1, Algorithm 1) ---------------------------------------------
 bool mfma_gram_supported(const flare_shape &s);

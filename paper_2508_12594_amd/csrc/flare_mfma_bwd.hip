@@ -25,7 +25,7 @@ namespace {
 // so dS^T = P * (a + w[n] * u[m] c): u is folded into the Z operand (and multiplies delta in the
 // correction k-step), w[n] is a per-row factor that goes from the token's lane to the rows of
 // the accumulator layout through 128 bytes of LDS.  It is exact as long as u, w and P stay in
-// fp32 range wherever R matters, which bwd_plan_kernel guarantees per (b,h) (plan[bh] = 1);
+// fp32 range wherever R matters, which bwd_plan_wave guarantees per (b,h) (plan[bh] = 1);
 // otherwise the ONE = false variant runs.  Each variant returns at once when the plan names the other.
 // ============================================================================================
 template <int DR, int NB, int MINB, bool ONE, bool F>
@@ -1085,63 +1085,6 @@ int mfma_dkdv_finish(const flare_shape &s, const float *acc32, void *dk, void *d
         default: FLARE_FIN(32); break;
     }
 #undef FLARE_FIN
-    return check_launch();
-}
-
-// Which variant of the dQ and dK/dV kernels may run for a (b,h): plan[bh] = 1 (one exponential per
-// score) iff, with kappa = max_m lse_enc2[m], every u[m] = 2^(lse_enc2[m] - kappa) >= 2^-kPlanSpan and
-// every w[n] = 2^(kappa - lse_dec2[n]) lies in [2^-kPlanSpan, 2^kPlanSpan].  Then wherever
-// R = P u w is above 2^-(126 - 2 kPlanSpan), P is a normal fp32 number and nothing is lost; anything
-// else (wide score ranges, non-finite statistics) takes the two-exponential kernels.
-constexpr float kPlanSpan = 50.f;
-namespace {
-__global__ __launch_bounds__(256) void bwd_plan_kernel(const float *__restrict__ ld_range,
-                                                       const float *__restrict__ lse_enc, int *__restrict__ plan,
-                                                       int parts, int M, int force_two)
-{
-    __shared__ float red[4][4];
-    const int bh = blockIdx.x, tid = threadIdx.x;
-    float le_min = INFINITY, le_max = -INFINITY, ld_min = INFINITY, ld_max = -INFINITY;
-    for (int m = tid; m < M; m += 256) {
-        const float v = lse_enc[(size_t)bh * M + m] * kLog2e;
-        le_min = fminf(le_min, v);
-        le_max = fmaxf(le_max, v);
-    }
-    for (int p = tid; p < parts; p += 256) {
-        ld_min = fminf(ld_min, ld_range[2 * ((size_t)bh * parts + p)]);
-        ld_max = fmaxf(ld_max, ld_range[2 * ((size_t)bh * parts + p) + 1]);
-    }
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        le_min = fminf(le_min, __shfl_xor(le_min, off));
-        le_max = fmaxf(le_max, __shfl_xor(le_max, off));
-        ld_min = fminf(ld_min, __shfl_xor(ld_min, off));
-        ld_max = fmaxf(ld_max, __shfl_xor(ld_max, off));
-    }
-    if ((tid & 63) == 0) {
-        red[tid >> 6][0] = le_min; red[tid >> 6][1] = le_max;
-        red[tid >> 6][2] = ld_min; red[tid >> 6][3] = ld_max;
-    }
-    __syncthreads();
-    if (tid == 0) {
-        for (int w = 1; w < 4; ++w) {
-            le_min = fminf(le_min, red[w][0]); le_max = fmaxf(le_max, red[w][1]);
-            ld_min = fminf(ld_min, red[w][2]); ld_max = fmaxf(ld_max, red[w][3]);
-        }
-        // written so that a NaN anywhere makes the test fail
-        const bool ok = (le_max - le_min <= kPlanSpan) && (le_max - ld_min <= kPlanSpan) &&
-                        (ld_max - le_max <= kPlanSpan) && fabsf(le_max) < 1e30f;
-        plan[bh] = (ok && !force_two) ? 1 : 0;
-    }
-}
-}  // namespace
-
-int mfma_bwd_plan(const flare_shape &s, const float *ld_range, const float *lse_enc, int *plan, bool force_two,
-                  hipStream_t stream)
-{
-    LaunchTimer t(KID_BWD_PLAN, stream);
-    bwd_plan_kernel<<<s.B * s.H, 256, 0, stream>>>(ld_range, lse_enc, plan, mfma_plan(s).parts, s.M,
-                                                   force_two ? 1 : 0);
     return check_launch();
 }
 

@@ -486,11 +486,17 @@ __device__ __forceinline__ void sum_slots(const float *__restrict__ part, int ou
 template <int D>
 __global__ __launch_bounds__(256) void dz_merge_kernel(
     const float *__restrict__ dz_part, const float *__restrict__ z,
-    float *__restrict__ dz, float *__restrict__ eps, int BH, int M, int parts, int round_bf16)
+    float *__restrict__ dz, float *__restrict__ eps, int BH, int M, int parts, int round_bf16,
+    const float *__restrict__ ld_range, const float *__restrict__ lse_enc, int *__restrict__ plan, int force_two)
 {
     const int j = threadIdx.x & 15;
     const int m = blockIdx.x * 16 + (threadIdx.x >> 4);
     const int bh = blockIdx.y;
+    // matrix-core path: one more workgroup per (b,h) decides which variant of the next kernels runs
+    if (plan != nullptr && blockIdx.x == gridDim.x - 1) {
+        if (threadIdx.x < 64) bwd_plan_wave(ld_range, lse_enc, plan, bh, parts, M, force_two);
+        return;
+    }
     const bool live = m < M;
     float acc[D], zr[D];
     sum_slots<D>(dz_part, bh, BH, 1, parts, M, live ? m : M - 1, j, acc);
@@ -532,12 +538,17 @@ __device__ __forceinline__ float2 sum_slots_few(const float *__restrict__ part, 
 template <int D>
 __global__ __launch_bounds__(256) void dz_merge_few_kernel(
     const float *__restrict__ dz_part, const float *__restrict__ z,
-    float *__restrict__ dz, float *__restrict__ eps, int BH, int M, int parts, int round_bf16)
+    float *__restrict__ dz, float *__restrict__ eps, int BH, int M, int parts, int round_bf16,
+    const float *__restrict__ ld_range, const float *__restrict__ lse_enc, int *__restrict__ plan, int force_two)
 {
     constexpr int L = D / 2, ROWS = 256 / L;
     const int j = threadIdx.x % L;
     const int m = blockIdx.x * ROWS + threadIdx.x / L;
     const int bh = blockIdx.y;
+    if (plan != nullptr && blockIdx.x == gridDim.x - 1) {
+        if (threadIdx.x < 64) bwd_plan_wave(ld_range, lse_enc, plan, bh, parts, M, force_two);
+        return;
+    }
     const bool live = m < M;                         // no early exit: the row's lanes meet in the shuffles below
     float2 a = sum_slots_few<D>(dz_part, bh, BH, 1, parts, M, live ? m : M - 1, j);
     if (round_bf16) {                                // as in dz_merge_kernel: round before eps is formed
@@ -832,8 +843,6 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
         int rc = mfma_dz_partial(s, q, k, dy, ld, ld_mul, (fused && !y32) ? y : nullptr,
                                  (fused && !y32) ? w.delta : nullptr, w.ld_range, w.part, scale, stream);
         if (rc != FLARE_OK) return rc;
-        rc = mfma_bwd_plan(s, w.ld_range, lse_enc, w.plan, force_two_exp(), stream);
-        if (rc != FLARE_OK) return rc;
     } else {
         {
             LaunchTimer t(KID_BWD_DZ_PARTIAL, stream);
@@ -847,11 +856,13 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     {
         LaunchTimer t(KID_BWD_DZ_MERGE, stream);
         if (dz_parts <= kFewSlots)
-            dz_merge_few_kernel<D><<<dim3((s.M + kFewRows - 1) / kFewRows, BH), 256, 0, stream>>>(
-                w.part, z, w.dz, w.eps, BH, s.M, dz_parts, mf ? 1 : 0);
+            dz_merge_few_kernel<D><<<dim3((s.M + kFewRows - 1) / kFewRows + (mf ? 1 : 0), BH), 256, 0, stream>>>(
+                w.part, z, w.dz, w.eps, BH, s.M, dz_parts, mf ? 1 : 0, w.ld_range, lse_enc, mf ? w.plan : nullptr,
+                force_two_exp() ? 1 : 0);
         else
-            dz_merge_kernel<D><<<dim3((s.M + 15) / 16, BH), 256, 0, stream>>>(w.part, z, w.dz, w.eps, BH, s.M,
-                                                                              dz_parts, mf ? 1 : 0);
+            dz_merge_kernel<D><<<dim3((s.M + 15) / 16 + (mf ? 1 : 0), BH), 256, 0, stream>>>(
+                w.part, z, w.dz, w.eps, BH, s.M, dz_parts, mf ? 1 : 0, w.ld_range, lse_enc, mf ? w.plan : nullptr,
+                force_two_exp() ? 1 : 0);
     }
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     int dq_parts = plan.bwd.chunks;

@@ -16,7 +16,7 @@ import sys
 def _short(name):
     for key in ("encode_mfma_kernel", "decode_mfma_kernel", "bwd_dq_mfma_kernel", "bwd_dkdv_mfma_kernel",
                 "encode_merge_kernel", "dz_merge_kernel", "dq_reduce_kernel", "encode_partial_kernel",
-                "token_pass_kernel", "dz_partial_kernel", "dq_partial_kernel", "dkdv_kernel", "bwd_plan_kernel",
+                "token_pass_kernel", "dz_partial_kernel", "dq_partial_kernel", "dkdv_kernel",
                 "bwd_prep_kernel"):
         if key in name:
             args = name[name.index(key) + len(key):]
