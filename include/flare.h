@@ -84,10 +84,10 @@ typedef struct {
                             (Section 3.1).  1: all heads use one latent sequence (the shared-latent
                             variant of the ablation in Appendix G): q_lat and dq_lat are [M][d], and
                             dq_lat is summed over the heads as well as over the batch */
-    int y_f32;           /* 0: y has the element type dtype.  1 (16-bit dtypes on the matrix-core kernels, i.e.
-                            M <= 2048, else FLARE_EUNSUPPORTED): flare_decode / flare_forward write y as
-                            fp32 (same layout), and the y handed to flare_backward is that fp32 tensor.  The
-                            backward then takes delta_n = <dY_n, Y_n> from an unrounded Y, so that no shape
+    int y_f32;           /* 0: y has the element type dtype.  1 (16-bit dtypes with M <= 2048, else
+                            FLARE_EUNSUPPORTED): flare_decode / flare_forward write y as fp32 (same layout),
+                            and the y handed to flare_backward is that fp32 tensor.  The backward then takes
+                            delta_n = <dY_n, Y_n> from an unrounded Y, so that no shape of 8 tokens or more
                             needs the recomputation described at flare_backward (at d < 16 that pass is a
                             sixth of the step), at the price of a y of twice the bytes */
 } flare_shape;
