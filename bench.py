@@ -98,6 +98,9 @@ def main():
     ap.add_argument("--y-f32", action="store_true",
                     help="the forward writes y in fp32 and the backward takes delta from it (flare_shape.y_f32)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--machine-rates", action="store_true",
+                    help="run the machine-rate micro-benchmarks of libflare_rates.so instead of the workload and "
+                         "print their table (the rates the issue bound and the exponential ceiling are priced with)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run three plain device copies of k (known size) first, for scaling profiler counters")
     args = ap.parse_args()
@@ -113,6 +116,15 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
+    if args.machine_rates:
+        from paper_2508_12594_amd import rates
+        rows = rates.run_all()
+        for r in rows:
+            print("%-100s waves/SIMD %d param %2d: %9.4f ms  %7s clk/instr  %6.0f MHz %s" % (
+                r["experiment"], r["waves_per_simd"], r["param"], r["ms"], r.get("clk_per_instr", "-"),
+                r["shader_mhz"], ("%.0f GB/s" % r["GBps"]) if "GBps" in r else ""), file=sys.stderr, flush=True)
+        print(json.dumps({"machine_rates": rows}), flush=True)
+        return
     binding.load()
 
     over = {} if args.tokens is None else {"N": args.tokens}

@@ -6,15 +6,23 @@
 namespace flare {
 namespace {
 
+template <bool B>
+struct PlainTag { static constexpr bool value = B; };
+
 // ============================================================================================
-// Decode.  One wave owns 32 tokens at a time and all M latents:
-//   pass 1: scores from the hi terms only -> per-token maximum = stabiliser b;
-//   pass 2: full scores minus b (-b is the C operand the score products of all latent tiles
-//           start from: one 16-register splat per token tile), 2^x, pack, and
-//           Y^T += Zaug^T . E with Zaug = [Z | 1].
+// Decode.  One wave owns 32 tokens at a time and all M latents.  One pass over the latent tiles:
+//   the stabiliser b of a token is its largest score (hi terms only) among the FIRST 32 latents: a
+//   real score, so b <= max_m S2 and the largest weight is at least 1; the other weights may exceed
+//   1 by whatever the later latents' scores exceed b, which fp32 sums and bf16 weights (same
+//   exponent range) absorb up to 2^64;
+//   per latent tile: full scores minus b (-b is the C operand the score products of all latent
+//   tiles start from: one 16-register splat per token tile), 2^x, pack, and
+//   Y^T += Zaug^T . E with Zaug = [Z | 1].
+//   Only when a token's denominator comes out above 2^64 (or not finite) the tile is done again
+//   with the exact maximum over all latents (one more sweep of hi products first).
 // Q (as A operand) and Z^T (as A operand, latents in the permuted order) live in registers
 // for the whole kernel; K streams from HBM straight into the B-operand layout; no LDS.
-// Each pass issues the MFMAs of latent tile t+1 before the vector work on tile t.
+// The MFMAs of latent tile t+1 are issued before the vector work on tile t.
 // PRE = false (shapes whose operands would not fit otherwise): raw q, no lo term, and
 // 2^(|c2| s - b) formed with one v_fma_f32 per score.
 // ============================================================================================
@@ -132,22 +140,8 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
             return r;
         };
 
-        // pass 1: per-token maximum over the latents
-        float mx = -INFINITY;
-        f32x16 s_cur = qk_hi(0), s_next;
-#pragma unroll
-        for (int t = 0; t < MT; ++t) {
-            if (t + 1 < MT) s_next = qk_hi(t + 1);
-            sched_fence();
-            mx = max16(s_cur, mx);
-            s_cur = s_next;
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        // stabiliser: -max as the starting value of the score accumulators (PRE), or folded into the fma
-        const f32x16 cinit = splat16(PRE ? -mx : 0.f);
-        const float b2 = mx * ac2;
-        // The hi products are recomputed in pass 2 rather than kept (8 tiles x 16 registers would
-        // not fit); an opaque copy of the keys stops the compiler from merging the two passes.
+        // The hi products behind the stabiliser are recomputed in the main sweep rather than kept; an
+        // opaque copy of the keys stops the compiler from merging the two.
         bf16x8 kt2[KS];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
@@ -155,73 +149,98 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
             asm volatile("" : "+v"(w));
             kt2[ks] = as_bf16x8(w);
         }
-        auto qk_full = [&](int t) {
-            f32x16 r = cinit;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) r = mfma_s<F>(qh[t][ks], kt2[ks], r);
-            if constexpr (PRE && !PACK) {
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) r = mfma_s<F>(ql[t][ks], kt[ks], r);
-            }
-            return r;
-        };
-
-        // pass 2: per latent tile 2^x, pack, and the value product
         f32x16 acc[HV];
+        float mx, b2;
+        for (bool exact = false;; exact = true) {
+            // stabiliser: the maximum over the first latent tile, or (second attempt) over all of them
+            mx = -INFINITY;
+            f32x16 s_cur = qk_hi(0), s_next;
+            if (!exact) {
+                mx = max16(s_cur, mx);
+            } else {
 #pragma unroll
-        for (int hv = 0; hv < HV; ++hv) acc[hv] = splat16(0.f);
-        s_cur = qk_full(0);
-        sched_fence();
-#pragma unroll
-        for (int t = 0; t < MT; ++t) {
-            if (t + 1 < MT) s_next = qk_full(t + 1);
-            if constexpr (!(PRE && D == 16)) sched_fence();
-            if constexpr (!PRE) {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) s_cur[i] = fmaf(s_cur[i], ac2, -b2);
-            }
-            bf16x8 p0, p1;
-            exp_pack(s_cur, p0, p1);
-#pragma unroll
-            for (int hv = 0; hv < HV; ++hv) {
-                acc[hv] = mfma(z_op(hv, 2 * t), p0, acc[hv]);
-                acc[hv] = mfma(z_op(hv, 2 * t + 1), p1, acc[hv]);
-            }
-            if constexpr (PRE && D == 16) {
-                // order within the tile: the two score products of tile t+1 (one when q' is packed) and the
-                // two value products of tile t, each followed by a share of the 16 exponentials and 8 packs
-                // of tile t
-                if (PACK && t + 1 < MT) {
-                    FLARE_GROUP_TRANS(4);
-                    FLARE_GROUP_MFMA(1);
-                    FLARE_GROUP_TRANS(4);
-                    FLARE_GROUP_VALU(4);
-                    FLARE_GROUP_MFMA(1);
-                    FLARE_GROUP_TRANS(8);
-                    FLARE_GROUP_VALU(4);
-                    FLARE_GROUP_MFMA(1);
-                } else if (t + 1 < MT) {
-                    FLARE_GROUP_TRANS(4);
-                    FLARE_GROUP_MFMA(1);
-                    FLARE_GROUP_TRANS(4);
-                    FLARE_GROUP_MFMA(1);
-                    FLARE_GROUP_VALU(4);
-                    FLARE_GROUP_TRANS(4);
-                    FLARE_GROUP_MFMA(1);
-                    FLARE_GROUP_TRANS(4);
-                    FLARE_GROUP_VALU(4);
-                    FLARE_GROUP_MFMA(1);
-                } else {
-                    FLARE_GROUP_TRANS(8);
-                    FLARE_GROUP_VALU(4);
-                    FLARE_GROUP_MFMA(1);
-                    FLARE_GROUP_TRANS(8);
-                    FLARE_GROUP_VALU(4);
-                    FLARE_GROUP_MFMA(1);
+                for (int t = 0; t < MT; ++t) {
+                    if (t + 1 < MT) s_next = qk_hi(t + 1);
+                    sched_fence();
+                    mx = max16(s_cur, mx);
+                    s_cur = s_next;
                 }
             }
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            // -b as the starting value of the score accumulators (PRE), or folded into the fma
+            const f32x16 cinit = splat16(PRE ? -mx : 0.f);
+            b2 = mx * ac2;
+            auto qk_full = [&](int t) {
+                f32x16 r = cinit;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) r = mfma_s<F>(qh[t][ks], kt2[ks], r);
+                if constexpr (PRE && !PACK) {
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) r = mfma_s<F>(ql[t][ks], kt[ks], r);
+                }
+                return r;
+            };
+
+            // per latent tile 2^x, pack, and the value product
+#pragma unroll
+            for (int hv = 0; hv < HV; ++hv) acc[hv] = splat16(0.f);
+            s_cur = qk_full(0);
             sched_fence();
-            s_cur = s_next;
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+                if (t + 1 < MT) s_next = qk_full(t + 1);
+                if constexpr (!(PRE && D == 16)) sched_fence();
+                if constexpr (!PRE) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) s_cur[i] = fmaf(s_cur[i], ac2, -b2);
+                }
+                bf16x8 p0, p1;
+                exp_pack(s_cur, p0, p1);
+#pragma unroll
+                for (int hv = 0; hv < HV; ++hv) {
+                    acc[hv] = mfma(z_op(hv, 2 * t), p0, acc[hv]);
+                    acc[hv] = mfma(z_op(hv, 2 * t + 1), p1, acc[hv]);
+                }
+                if constexpr (PRE && D == 16) {
+                    // order within the tile: the two score products of tile t+1 (one when q' is packed) and the
+                    // two value products of tile t, each followed by a share of the 16 exponentials and 8 packs
+                    // of tile t
+                    if (PACK && t + 1 < MT) {
+                        FLARE_GROUP_TRANS(4);
+                        FLARE_GROUP_MFMA(1);
+                        FLARE_GROUP_TRANS(4);
+                        FLARE_GROUP_VALU(4);
+                        FLARE_GROUP_MFMA(1);
+                        FLARE_GROUP_TRANS(8);
+                        FLARE_GROUP_VALU(4);
+                        FLARE_GROUP_MFMA(1);
+                    } else if (t + 1 < MT) {
+                        FLARE_GROUP_TRANS(4);
+                        FLARE_GROUP_MFMA(1);
+                        FLARE_GROUP_TRANS(4);
+                        FLARE_GROUP_MFMA(1);
+                        FLARE_GROUP_VALU(4);
+                        FLARE_GROUP_TRANS(4);
+                        FLARE_GROUP_MFMA(1);
+                        FLARE_GROUP_TRANS(4);
+                        FLARE_GROUP_VALU(4);
+                        FLARE_GROUP_MFMA(1);
+                    } else {
+                        FLARE_GROUP_TRANS(8);
+                        FLARE_GROUP_VALU(4);
+                        FLARE_GROUP_MFMA(1);
+                        FLARE_GROUP_TRANS(8);
+                        FLARE_GROUP_VALU(4);
+                        FLARE_GROUP_MFMA(1);
+                    }
+                }
+                sched_fence();
+                s_cur = s_next;
+            }
+            // A later latent tile beat the first one by more than 2^64 for some token (its denominator, row 16,
+            // is huge or not finite): once more with the exact maximum.  Exponent field >= 127 + 64.
+            const bool over = (__float_as_uint(acc[0][8]) & 0x7f800000u) >= ((127u + 64u) << 23);
+            if (exact || !__any(over)) break;
         }
         // row 16 (register 8 of the lower lane half) is the softmax denominator
         const float den = __shfl(acc[0][8], l32);
@@ -365,8 +384,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     u32x4 wzero;
     wzero[0] = 0u; wzero[1] = 0u; wzero[2] = 0u; wzero[3] = 0u;
     bf16x8 caug[MODE == 0 ? NB : 1];             // query side of the stabiliser k-step: slot 0 := -c
-#pragma unroll
-    for (int b = 0; b < (MODE == 0 ? NB : 1); ++b) caug[b] = as_bf16x8(wzero);
+    caug[0] = as_bf16x8(wzero);
 
     const bf16_t *kb = k + tok_base(ts, bh, H);
     const bf16_t *vb = v + tok_base(ts, bh, H);
@@ -379,7 +397,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     float nl_min = INFINITY, nl_max = -INFINITY;   // range of -lse_dec2 over this wave's tokens (MODE 1)
     f32x16 o[NB][HV];
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
+    for (int b = 0; b < NB; ++b) {   // what a wave without tiles stores
         c[b] = 0.f;
 #pragma unroll
         for (int hv = 0; hv < HV; ++hv) o[b][hv] = splat16(0.f);
@@ -436,7 +454,8 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     w23[0] = 0u; w23[1] = hh == 0 ? kOnePair<F> : 0u; w23[2] = 0u; w23[3] = 0u;
     const bf16x8 ones23 = as_bf16x8(w23);      // query side of the correction k-step: slots 2,3 = 1
     // scores minus the stabiliser of latent tile b against the token tile (kk; kk0a = key side of the correction k-step)
-    auto qk = [&](int b, const bf16x8 (&kk)[KS], bf16x8 kk0a) {
+    // (plain: without the correction k-step -- the encode's sweep that needs no stabiliser)
+    auto qk = [&](int b, const bf16x8 (&kk)[KS], bf16x8 kk0a, bool plain) {
         f32x16 r = splat16(0.f);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) r = mfma_s<F>(kk[ks], qh[b][ks], r);
@@ -444,7 +463,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) r = mfma_s<F>(kk[ks], ql[b][ks], r);
         }
-        r = mfma_s<F>(kk0a, MODE == 0 ? caug[MODE == 0 ? b : 0] : ones23, r);
+        if (!plain) r = mfma_s<F>(kk0a, MODE == 0 ? caug[MODE == 0 ? b : 0] : ones23, r);
         return r;
     };
     const uint32_t one0 = hh == 0 ? kOne<F> : 0u;
@@ -516,7 +535,20 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         if (do_delta && j < cnt && g == 0 && (lane & 1) == 0 && n < n1) delta_out[(size_t)bh * N + n] = part;
     };
 
-    if (cnt > 0) {
+    // One sweep over this wave's token tiles.  PLAIN (encode only): the weights are 2^S2 as they come, with no
+    // stabiliser (c = 0: no running maximum, no correction k-step, no rescaling) -- right whenever the row sums
+    // end up in a range that shows that nothing overflowed and nothing that matters was flushed to zero, which
+    // the caller checks afterwards; otherwise the same tiles are swept again with the lazy online softmax.
+    auto sweep = [&](auto plain_tag) {
+        constexpr bool PLAIN = decltype(plain_tag)::value;
+        static_assert(!PLAIN || MODE == 0, "only the encode has a softmax state to leave out");
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            c[b] = 0.f;
+#pragma unroll
+            for (int hv = 0; hv < HV; ++hv) o[b][hv] = splat16(0.f);
+            if constexpr (MODE == 0) caug[b] = as_bf16x8(wzero);
+        }
         bf16x8 kt[KS], ktn[KS], va[HV][2];
         u32x4 vr1[LOADS], vr2[LOADS], yr1[LOADS], yr2[LOADS];
         f32x16 S[NB];
@@ -538,7 +570,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         load_v(1, vr1);
 #pragma unroll
         for (int b = 0; b < NB; ++b) S[b] = splat16(0.f);
-        S[0] = qk(0, kt, k_aug(kt[0], nl));
+        S[0] = qk(0, kt, k_aug(kt[0], nl), PLAIN);
 
         for (int j = 0; j < cnt; ++j) {
             const int tok0 = tile_tok0(j);
@@ -563,8 +595,8 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
             for (int b = 0; b < NB; ++b) {
                 // issue the next score product first: the next latent tile, or tile 0 of the next tokens
                 f32x16 nxt;
-                if (b + 1 < NB) nxt = qk(b + 1, kt, kt0a);
-                else nxt = qk(0, ktn, k_aug(ktn[0], nln));
+                if (b + 1 < NB) nxt = qk(b + 1, kt, kt0a, PLAIN);
+                else nxt = qk(0, ktn, k_aug(ktn[0], nln), PLAIN);
                 sched_fence();
                 f32x16 sc = S[b];
                 if (partial) {
@@ -572,8 +604,8 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
                     for (int r = 0; r < 16; ++r)
                         if (8 * (r / 4) + (r % 4) >= rem) sc[r] = -INFINITY;
                 }
-                float mx = (MODE == 0) ? max16(sc, -INFINITY) : 0.f;
-                if (MODE == 0 && (first || __any(mx > kLazy))) {
+                float mx = (MODE == 0 && !PLAIN) ? max16(sc, -INFINITY) : 0.f;
+                if (MODE == 0 && !PLAIN && (first || __any(mx > kLazy))) {
                     mx = fmaxf(mx, __shfl_xor(mx, 32));   // both lane halves hold tokens of the same latent
                     const float cn = elem_round<F>(c[b] + (first ? mx : fmaxf(mx, 0.f)));
                     const float shift = cn - c[b];
@@ -616,6 +648,23 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
 #pragma unroll
                 for (int i = 0; i < LOADS; ++i) yr1[i] = yr2[i];
             }
+        }
+    };
+    if (cnt > 0) {
+        if constexpr (MODE == 0) {
+            sweep(PlainTag<true>{});
+            // Row sums (register 8 of the lower lane half) between 2^-80 and 2^100: no weight overflowed, and the
+            // largest score of the latent in this slot is above -94, so whatever was flushed to zero is below
+            // 2^-32 of it.  Anything else (also NaN, inf): the slot is swept again with a stabiliser.
+            bool redo = false;
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const uint32_t e = (__float_as_uint(o[b][0][8]) >> 23) & 0xffu;
+                redo |= hh == 0 && lat0 + 32 * b + l32 < M && (e < 127u - 80u || e > 127u + 100u);
+            }
+            if (__any(redo)) sweep(PlainTag<false>{});
+        } else {
+            sweep(PlainTag<false>{});
         }
     }
 
