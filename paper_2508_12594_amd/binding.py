@@ -42,7 +42,7 @@ def load():
     global _lib
     if _lib is not None:
         return _lib
-    path = os.environ.get("FLARE_LIB_PATH") or LIB_PATH    # another build of the library, for A/B timing
+    path = LIB_PATH    # (to time another build, point LIB_PATH at it before the first call)
     if not os.path.exists(path):
         raise FlareError("libflare.so not found at %s: run `python -m paper_2508_12594_amd.build`" % path)
     lib = ctypes.CDLL(path)
@@ -149,12 +149,17 @@ def _shape_workspace_bytes(shp):
     return int(f.value), int(b.value)
 
 
-def _workspace(shp, which, workspace, device):
+def _workspace(shp, which, workspace, device, stream=None):
     torch = _torch()
     f, b = _shape_workspace_bytes(shp)
     need = f if which == "fwd" else b
     if workspace is None:
+        # A temporary block: the kernels are only enqueued when the call returns, so the caching allocator must
+        # learn on which stream they run, or it could hand the block to other work on the allocating stream
+        # while kernels on `stream` still use it.
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
+        if stream is not None and stream != torch.cuda.current_stream():
+            workspace.record_stream(stream)
     if workspace.dtype != torch.uint8:
         raise FlareError("workspace must be a uint8 tensor")
     return workspace, ctypes.c_void_p(workspace.data_ptr()), ctypes.c_size_t(workspace.numel())
@@ -168,7 +173,7 @@ def encode(q_lat, k, v, scale, z=None, lse_enc=None, workspace=None, stream=None
         z = torch.empty((shp.B, shp.H, shp.M, shp.d), dtype=torch.float32, device=k.device)
     if lse_enc is None:
         lse_enc = torch.empty((shp.B, shp.H, shp.M), dtype=torch.float32, device=k.device)
-    ws, ws_p, ws_n = _workspace(shp, "fwd", workspace, k.device)
+    ws, ws_p, ws_n = _workspace(shp, "fwd", workspace, k.device, stream)
     _check(load().flare_encode(ctypes.byref(shp), _dev(q_lat, "q_lat"), _dev(k, "k"),
                                _dev(v, "v", k.dtype, k.shape),
                                _dev(z, "z", torch.float32, (shp.B, shp.H, shp.M, shp.d)),
@@ -193,7 +198,7 @@ def decode(q_lat, k, z, scale, y=None, lse_dec=None, workspace=None, stream=None
     ydt = torch.float32 if f32y else k.dtype
     if y is None:
         y = torch.empty(k.shape, dtype=ydt, device=k.device)
-    ws, ws_p, ws_n = _workspace(shp, "fwd", workspace, k.device)
+    ws, ws_p, ws_n = _workspace(shp, "fwd", workspace, k.device, stream)
     _check(load().flare_decode(ctypes.byref(shp), _dev(q_lat, "q_lat"), _dev(k, "k"),
                                _dev(z, "z", torch.float32, (shp.B, shp.H, shp.M, shp.d)),
                                _dev(y, "y", ydt, k.shape), _opt_lse_dec(lse_dec, shp),
@@ -218,7 +223,7 @@ def forward(q_lat, k, v, scale, y=None, z=None, lse_enc=None, lse_dec=None, work
         z = torch.empty((shp.B, shp.H, shp.M, shp.d), dtype=torch.float32, device=k.device)
     if lse_enc is None:
         lse_enc = torch.empty((shp.B, shp.H, shp.M), dtype=torch.float32, device=k.device)
-    ws, ws_p, ws_n = _workspace(shp, "fwd", workspace, k.device)
+    ws, ws_p, ws_n = _workspace(shp, "fwd", workspace, k.device, stream)
     _check(load().flare_forward(ctypes.byref(shp), _dev(q_lat, "q_lat"), _dev(k, "k"),
                                 _dev(v, "v", k.dtype, k.shape), _dev(y, "y", ydt, k.shape),
                                 _dev(z, "z", torch.float32, (shp.B, shp.H, shp.M, shp.d)),
@@ -243,7 +248,7 @@ def backward(q_lat, k, v, dy, z, lse_enc, scale, y=None, lse_dec=None, dq_lat=No
         dk = torch.empty_like(k)
     if dv is None:
         dv = torch.empty_like(k)
-    ws, ws_p, ws_n = _workspace(shp, "bwd", workspace, k.device)
+    ws, ws_p, ws_n = _workspace(shp, "bwd", workspace, k.device, stream)
     _check(load().flare_backward(ctypes.byref(shp), _dev(q_lat, "q_lat"), _dev(k, "k"),
                                  _dev(v, "v", k.dtype, k.shape),
                                  None if y is None else _dev(y, "y", torch.float32 if f32y else k.dtype, k.shape),
