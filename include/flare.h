@@ -62,7 +62,8 @@ typedef enum {
     FLARE_EUNSUPPORTED = -2,  /* d, dtype, layout or B*H outside the supported set */
     FLARE_EALIGN = -3,        /* a data pointer is not 16-byte aligned */
     FLARE_EWORKSPACE = -4,    /* workspace is NULL or smaller than flare_workspace_bytes reports */
-    FLARE_ELAUNCH = -5        /* the HIP runtime rejected a launch or an event call */
+    FLARE_ELAUNCH = -5,       /* the HIP runtime rejected a launch or an event call */
+    FLARE_ESTATIC = -6        /* flare_forward_static: the shape needs more scratch than FLARE_STATIC_SCRATCH_BYTES */
 } flare_status;
 
 typedef enum {
@@ -134,6 +135,24 @@ int flare_decode(const flare_shape *shape, const void *q_lat, const void *k, con
 int flare_forward(const flare_shape *shape, const void *q_lat, const void *k, const void *v,
                   void *y, float *z, float *lse_enc, float *lse_dec, float scale,
                   void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * flare_forward for callers that cannot allocate and have no workspace to pass: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and kernels as
+ * flare_forward, but the scratch (the encode's per-wave partial sums; with M > 256 also the decode's
+ * per-chunk rows) lives in an array of FLARE_STATIC_SCRATCH_BYTES that the library's code object holds in
+ * device memory, once per GPU the library runs on, until the process ends.  The call allocates and frees
+ * nothing and calls no allocating routine; on its first call on a device it looks the array's address up
+ * (hipGetSymbolAddress) and keeps it, so make that first call outside a capture.  A shape whose
+ * flare_workspace_bytes forward size exceeds FLARE_STATIC_SCRATCH_BYTES is refused with FLARE_ESTATIC and
+ * nothing is launched (the five reference workloads need 0.5 ... 18 MiB).  Nothing in the array has to start
+ * at zero (every partial slot is written before it is read), so no clearing is enqueued.  All calls on one GPU
+ * share the one array: calls that overlap there (different streams, or different threads without ordering)
+ * race; order them on one stream.
+ */
+#define FLARE_STATIC_SCRATCH_BYTES (32u << 20)
+int flare_forward_static(const flare_shape *shape, const void *q_lat, const void *k, const void *v,
+                         void *y, float *z, float *lse_enc, float *lse_dec, float scale, void *stream);
 
 /*
  * Backward of the mixer.  The paper differentiates its two attention calls automatically

@@ -19,7 +19,7 @@ LAYOUTS = {"bhnd": FLARE_BHND, "bnhd": FLARE_BNHD}
 
 EXPORTS = [
     "flare_version", "flare_strerror", "flare_workspace_bytes", "flare_encode", "flare_decode",
-    "flare_forward", "flare_backward", "flare_profile_enable", "flare_profile_kernels",
+    "flare_forward", "flare_forward_static", "flare_backward", "flare_profile_enable", "flare_profile_kernels",
     "flare_profile_name", "flare_profile_read", "flare_spectral_workspace_bytes", "flare_spectral",
 ]
 
@@ -54,6 +54,8 @@ def load():
     lib.flare_encode.argtypes = [sp, vp, vp, vp, fp, fp, ctypes.c_float, vp, ctypes.c_size_t, vp]
     lib.flare_decode.argtypes = [sp, vp, vp, fp, vp, fp, ctypes.c_float, vp, ctypes.c_size_t, vp]
     lib.flare_forward.argtypes = [sp, vp, vp, vp, vp, fp, fp, fp, ctypes.c_float, vp, ctypes.c_size_t, vp]
+    lib.flare_forward_static.argtypes = [sp, vp, vp, vp, vp, fp, fp, fp, ctypes.c_float, vp]
+    lib.flare_forward_static.restype = ctypes.c_int
     lib.flare_backward.argtypes = [sp, vp, vp, vp, vp, fp, vp, fp, fp, fp, vp, vp, ctypes.c_float, vp,
                                    ctypes.c_size_t, vp]
     lib.flare_spectral_workspace_bytes.argtypes = [sp, ctypes.POINTER(ctypes.c_size_t)]
@@ -230,6 +232,24 @@ def forward(q_lat, k, v, scale, y=None, z=None, lse_enc=None, lse_dec=None, work
                                 _dev(lse_enc, "lse_enc", torch.float32, (shp.B, shp.H, shp.M)),
                                 _opt_lse_dec(lse_dec, shp),
                                 ctypes.c_float(scale), ws_p, ws_n, _stream(stream)), "flare_forward")
+    return y, z, lse_enc
+
+
+STATIC_SCRATCH_BYTES = 32 << 20   # FLARE_STATIC_SCRATCH_BYTES of include/flare.h
+
+
+def forward_static(q_lat, k, v, scale, y, z, lse_enc, lse_dec=None, stream=None, layout="bhnd"):
+    """flare_forward_static: the forward with the library's own static scratch; every output is the caller's."""
+    torch = _torch()
+    f32y = _wants_f32_y(y, k, False)
+    shp = _shape_of(q_lat, k, layout, f32y)
+    ydt = torch.float32 if f32y else k.dtype
+    _check(load().flare_forward_static(ctypes.byref(shp), _dev(q_lat, "q_lat"), _dev(k, "k"),
+                                       _dev(v, "v", k.dtype, k.shape), _dev(y, "y", ydt, k.shape),
+                                       _dev(z, "z", torch.float32, (shp.B, shp.H, shp.M, shp.d)),
+                                       _dev(lse_enc, "lse_enc", torch.float32, (shp.B, shp.H, shp.M)),
+                                       _opt_lse_dec(lse_dec, shp), ctypes.c_float(scale), _stream(stream)),
+           "flare_forward_static")
     return y, z, lse_enc
 
 

@@ -2,6 +2,8 @@
 // The operator itself lives in the kernel files; see include/flare.h for the contract.
 #include <stdio.h>
 
+#include <atomic>
+
 #include "flare_internal.h"
 
 namespace flare {
@@ -56,6 +58,24 @@ LaunchTimer::~LaunchTimer()
 
 namespace {
 
+// Scratch of flare_forward_static: one copy per GPU, inside the code object.  In host code the name below
+// is only a handle for hipGetSymbolAddress; the device address is looked up once per device and kept.
+static __device__ __align__(256) unsigned char scratch[FLARE_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device (NULL on a HIP error or a device index beyond the table).
+void *static_scratch()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p) return p;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+    g_scratch_ptr[dev].store(p, std::memory_order_release);   // two threads may both get here: same address
+    return p;
+}
+
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 int check_shape(const flare_shape *s)
@@ -93,6 +113,7 @@ const char *flare_strerror(int status)
         case FLARE_EALIGN: return "pointer is not 16-byte aligned";
         case FLARE_EWORKSPACE: return "workspace missing or too small";
         case FLARE_ELAUNCH: return "HIP runtime rejected a launch";
+        case FLARE_ESTATIC: return "shape needs more scratch than the static buffer of flare_forward_static holds";
         default: return "unknown flare status";
     }
 }
@@ -156,6 +177,19 @@ int flare_forward(const flare_shape *shape, const void *q_lat, const void *k, co
     int rc = flare_encode(shape, q_lat, k, v, z, lse_enc, scale, workspace, workspace_bytes, stream);
     if (rc != FLARE_OK) return rc;
     return flare_decode(shape, q_lat, k, z, y, lse_dec, scale, workspace, workspace_bytes, stream);
+}
+
+int flare_forward_static(const flare_shape *shape, const void *q_lat, const void *k, const void *v, void *y,
+                         float *z, float *lse_enc, float *lse_dec, float scale, void *stream)
+{
+    const int rc = check_shape(shape);
+    if (rc != FLARE_OK) return rc;
+    size_t need = 0;
+    flare_workspace_bytes(shape, &need, nullptr);
+    if (need > FLARE_STATIC_SCRATCH_BYTES) return FLARE_ESTATIC;
+    void *ws = static_scratch();
+    if (!ws) return FLARE_ELAUNCH;
+    return flare_forward(shape, q_lat, k, v, y, z, lse_enc, lse_dec, scale, ws, FLARE_STATIC_SCRATCH_BYTES, stream);
 }
 
 int flare_backward(const flare_shape *shape, const void *q_lat, const void *k, const void *v,

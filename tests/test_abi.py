@@ -31,7 +31,7 @@ def test_header_symbols_are_exported(lib):
 def test_version_and_strerror(lib):
     assert binding.version() >= 200
     assert binding.strerror(0) == "success"
-    for code in (-1, -2, -3, -4, -5, -99):
+    for code in (-1, -2, -3, -4, -5, -6, -99):
         assert len(binding.strerror(code)) > 0
 
 
@@ -61,6 +61,10 @@ def test_null_and_misaligned_pointers_are_rejected(lib):
     assert lib.flare_forward(ctypes.byref(shp), p, p, p, p, p, p, None, one, p, 16, None) == -4
     assert lib.flare_forward(ctypes.byref(shp), p, p, p, p, p, p, None, one, None, 0, None) == -4
     assert lib.flare_decode(ctypes.byref(shp), p, p, None, p, None, one, None, 0, None) == -1
+    # the entry point with the static scratch: shape and size checks come before anything touches a device
+    big = binding.FlareShape(1, 8, 1 << 20, 2048, 8, binding.FLARE_BF16)
+    assert lib.flare_forward_static(ctypes.byref(big), p, p, p, p, p, p, None, one, None) == -6
+    assert lib.flare_forward_static(None, p, p, p, p, p, p, None, one, None) == -1
     assert lib.flare_backward(ctypes.byref(shp), p, p, p, None, None, None, p, p, p, p, p, one, p,
                               1 << 20, None) == -1
     assert lib.flare_backward(ctypes.byref(shp), p, p, p, None, None, p, p, p, p, p, p, one, p,
