@@ -91,7 +91,18 @@ typedef struct {
                             delta_n = <dY_n, Y_n> from an unrounded Y, so that no shape of 8 tokens or more
                             needs the recomputation described at flare_backward (at d < 16 that pass is a
                             sixth of the step), at the price of a y of twice the bytes */
+    int variant;         /* 0: the library picks its kernels.  Otherwise a set of flare_variant bits that forces
+                            a kernel variant the library would not pick for this shape or these inputs (tests and
+                            A/B measurements of flare_backward; results stay within the same tolerances).  Bits
+                            that do not apply to a shape are ignored; unknown bits give FLARE_EINVAL */
 } flare_shape;
+
+typedef enum {
+    FLARE_VARIANT_TWO_EXP = 1,      /* backward: both softmax weights of a score from an exponential of their own
+                                       in every (b,h), as for inputs whose normalisers span too wide a range */
+    FLARE_VARIANT_SEPARATE_DQ = 2   /* backward, d <= 16: dQ from the latent-major kernel of its own (as at d = 32)
+                                       instead of out of the dK/dV kernel */
+} flare_variant;
 
 /* Library version: major*10000 + minor*100 + patch. */
 int flare_version(void);
@@ -200,21 +211,6 @@ int flare_spectral_workspace_bytes(const flare_shape *shape, size_t *bytes);
 int flare_spectral(const flare_shape *shape, const void *q_lat, const void *k, const float *lse_enc,
                    const float *lse_dec, float scale, int first, float *eigenvalues, float *z_vec,
                    float *gram, void *workspace, size_t workspace_bytes, void *stream);
-
-/*
- * Per-kernel timing for measurement (not part of the operator).  While enabled, every kernel
- * the library launches is bracketed by a pair of HIP events recorded on the launch stream.
- * flare_profile_enable(1) creates the event pool (the only allocation this library makes) and
- * clears the totals; flare_profile_enable(0) stops recording.  flare_profile_kernels() returns
- * how many kernel ids exist; flare_profile_name(id) names one; flare_profile_read(id, ...)
- * waits for the recorded events and returns the summed duration in milliseconds and the
- * number of launches since enabling.  At most 8192 launches are recorded; later ones run
- * untimed.  Not thread-safe.
- */
-int flare_profile_enable(int on);
-int flare_profile_kernels(void);
-const char *flare_profile_name(int kernel_id);
-int flare_profile_read(int kernel_id, double *total_ms, int *launches);
 
 #ifdef __cplusplus
 }

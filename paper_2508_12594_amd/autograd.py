@@ -41,7 +41,7 @@ def flare_mixer(q_lat, k, v, scale, layout="bhnd", y_f32=False):
     """y = FLARE(q_lat, k, v): q_lat [H,M,d] (or [M,d]: shared latents), k, v [B,H,N,d] ('bhnd') or
     [B,N,H,d] ('bnhd'); returns y in k's shape and dtype.  Differentiable in q_lat, k and v.
 
-    y_f32 (16-bit inputs, at most 256 latents): y comes back in fp32 and the backward reads it instead of
+    y_f32 (16-bit inputs, at most 2048 latents): y comes back in fp32 and the backward reads it instead of
     recomputing the token statistics, which pays at d < 16 (flare_shape.y_f32)."""
     global _FN
     if _FN is None:

@@ -16,6 +16,8 @@ FLARE_F16 = 2
 FLARE_BHND = 0   # token tensors [B,H,N,d]
 FLARE_BNHD = 1   # token tensors [B,N,H,d] (= [B,N,C], C = H*d)
 LAYOUTS = {"bhnd": FLARE_BHND, "bnhd": FLARE_BNHD}
+VARIANT_TWO_EXP = 1       # flare_variant bits of include/flare.h (tests and A/B measurements of the backward)
+VARIANT_SEPARATE_DQ = 2
 
 EXPORTS = [
     "flare_version", "flare_strerror", "flare_workspace_bytes", "flare_encode", "flare_decode",
@@ -27,7 +29,7 @@ EXPORTS = [
 class FlareShape(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int), ("H", ctypes.c_int), ("N", ctypes.c_int), ("M", ctypes.c_int),
                 ("d", ctypes.c_int), ("dtype", ctypes.c_int), ("layout", ctypes.c_int),
-                ("shared_latents", ctypes.c_int), ("y_f32", ctypes.c_int)]
+                ("shared_latents", ctypes.c_int), ("y_f32", ctypes.c_int), ("variant", ctypes.c_int)]
 
 
 class FlareError(RuntimeError):
@@ -254,7 +256,7 @@ def forward_static(q_lat, k, v, scale, y, z, lse_enc, lse_dec=None, stream=None,
 
 
 def backward(q_lat, k, v, dy, z, lse_enc, scale, y=None, lse_dec=None, dq_lat=None, dk=None, dv=None,
-             workspace=None, stream=None, layout="bhnd"):
+             workspace=None, stream=None, layout="bhnd", variant=0):
     """flare_backward: returns (dq_lat[H,M,d] fp32, dk, dv in k's dtype).
 
     Pass the forward's y and lse_dec to reuse them; without both, they are recomputed from z.  An fp32 y next
@@ -262,6 +264,7 @@ def backward(q_lat, k, v, dy, z, lse_enc, scale, y=None, lse_dec=None, dq_lat=No
     torch = _torch()
     f32y = _wants_f32_y(y, k, False)
     shp = _shape_of(q_lat, k, layout, f32y)
+    shp.variant = int(variant)     # flare_variant bits: force a kernel variant (tests, measurements)
     if dq_lat is None:
         dq_lat = torch.empty(tuple(q_lat.shape), dtype=torch.float32, device=k.device)
     if dk is None:

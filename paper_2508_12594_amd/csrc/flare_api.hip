@@ -86,6 +86,7 @@ int check_shape(const flare_shape *s)
     if (s->layout != FLARE_BHND && s->layout != FLARE_BNHD) return FLARE_EUNSUPPORTED;
     if (s->shared_latents != 0 && s->shared_latents != 1) return FLARE_EINVAL;
     if (s->y_f32 != 0 && s->y_f32 != 1) return FLARE_EINVAL;
+    if ((s->variant & ~(FLARE_VARIANT_TWO_EXP | FLARE_VARIANT_SEPARATE_DQ)) != 0) return FLARE_EINVAL;
     if (s->y_f32 && (s->dtype == FLARE_F32 || s->M > 2048)) return FLARE_EUNSUPPORTED;   // matrix-core shapes only
     if (s->d != 4 && s->d != 8 && s->d != 16 && s->d != 32) return FLARE_EUNSUPPORTED;
     if ((long long)s->B * s->H > 65535) return FLARE_EUNSUPPORTED;
@@ -102,7 +103,7 @@ using namespace flare;
 
 extern "C" {
 
-int flare_version(void) { return 300; }   // 0.3.0: flare_shape grew by y_f32
+int flare_version(void) { return 400; }   // 0.4.0: flare_shape grew by variant; flare_forward_static
 
 const char *flare_strerror(int status)
 {

@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include "flare.h"
+#include "flare_profile.h"
 
 namespace flare {
 

@@ -949,13 +949,12 @@ int mfma_dkdv_blocks(const flare_shape &s)
 // The dK/dV kernel can form the dQ partials as well (one pass over the scores for all three gradients);
 // written for and used at d <= 16 (at d = 32 the dQ accumulators alone would take 128 registers).  At d <= 8
 // it carries the lo term of Z in the upper half of its Z image (ZPACK in the kernel), like the token-statistics
-// kernel that forms the delta it subtracts.  FLARE_BWD_SEPARATE_DQ=1 in the environment keeps the separate dQ kernel (a switch
-// for measurements; read at every call).
+// kernel that forms the delta it subtracts.  flare_shape.variant with FLARE_VARIANT_SEPARATE_DQ keeps the separate dQ
+// kernel (tests, measurements).
 bool mfma_dq_fused(const flare_shape &s)
 {
     if (!mfma_supported(s) || s.d == 32) return false;
-    const char *e = getenv("FLARE_BWD_SEPARATE_DQ");
-    return !(e != nullptr && e[0] != '\0' && e[0] != '0');
+    return (s.variant & FLARE_VARIANT_SEPARATE_DQ) == 0;
 }
 
 int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy, const float *z,

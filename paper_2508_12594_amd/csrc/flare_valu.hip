@@ -736,14 +736,6 @@ size_t bwd_layout(const flare_shape &s, int slots, void *ws, BwdWs *out)
 
 inline int check_launch() { return hipGetLastError() == hipSuccess ? FLARE_OK : FLARE_ELAUNCH; }
 
-// FLARE_BWD_TWO_EXP=1 in the environment sends every (b,h) to the two-exponential kernels (a
-// switch for tests and measurements; read at every call).
-inline bool force_two_exp()
-{
-    const char *e = getenv("FLARE_BWD_TWO_EXP");
-    return e != nullptr && e[0] != '\0' && e[0] != '0';
-}
-
 inline int bwd_slots(const flare_shape &s, const ValuPlan &plan)
 {
     int mf = 0;
@@ -858,11 +850,11 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
         if (dz_parts <= kFewSlots)
             dz_merge_few_kernel<D><<<dim3((s.M + kFewRows - 1) / kFewRows + (mf ? 1 : 0), BH), 256, 0, stream>>>(
                 w.part, z, w.dz, w.eps, BH, s.M, dz_parts, mf ? 1 : 0, w.ld_range, lse_enc, mf ? w.plan : nullptr,
-                force_two_exp() ? 1 : 0);
+                (s.variant & FLARE_VARIANT_TWO_EXP) ? 1 : 0);
         else
             dz_merge_kernel<D><<<dim3((s.M + 15) / 16 + (mf ? 1 : 0), BH), 256, 0, stream>>>(
                 w.part, z, w.dz, w.eps, BH, s.M, dz_parts, mf ? 1 : 0, w.ld_range, lse_enc, mf ? w.plan : nullptr,
-                force_two_exp() ? 1 : 0);
+                (s.variant & FLARE_VARIANT_TWO_EXP) ? 1 : 0);
     }
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     int dq_parts = plan.bwd.chunks;

@@ -19,13 +19,28 @@ def lib():
     return binding.load()
 
 
-def test_header_symbols_are_exported(lib):
-    text = open(os.path.join(ROOT, "include", "flare.h")).read()
+def _declared(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    declared = sorted(set(re.findall(r"\b(flare_[a-z_]+)\s*\(", text)))
+    return set(re.findall(r"\b(flare_[a-z_]+)\s*\(", text))
+
+
+def test_header_symbols_are_exported(lib):
+    """Every function an include/*.h declares is exported by the library it belongs to, and the bindings
+    list exactly those: flare.h (the operator) and flare_profile.h (timing hooks) -> libflare.so,
+    flare_rates.h (machine-rate micro-benchmarks) -> libflare_rates.so."""
+    headers = sorted(f for f in os.listdir(os.path.join(ROOT, "include")) if f.endswith(".h"))
+    assert headers == ["flare.h", "flare_profile.h", "flare_rates.h"]
+    declared = sorted(_declared("flare.h") | _declared("flare_profile.h"))
     assert declared == sorted(binding.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
+    from paper_2508_12594_amd import rates
+    rl = rates.load()
+    assert sorted(_declared("flare_rates.h")) == sorted(rates.EXPORTS)
+    for name in rates.EXPORTS:
+        assert hasattr(rl, name), name
+    assert rl.flare_rates_count() == len(rates.names()) > 10
 
 
 def test_version_and_strerror(lib):
@@ -47,6 +62,10 @@ def test_workspace_bytes_and_shape_checks(lib):
     assert lib.flare_workspace_bytes(None, None, None) == -1
     shp = binding.FlareShape(1, 1, 8, 32, 16, binding.FLARE_F32, 0, 2)      # shared_latents must be 0 or 1
     assert lib.flare_workspace_bytes(ctypes.byref(shp), None, None) == -1
+    shp = binding.FlareShape(1, 1, 8, 32, 16, binding.FLARE_F32, 0, 0, 0, 4)   # unknown variant bit
+    assert lib.flare_workspace_bytes(ctypes.byref(shp), None, None) == -1
+    shp = binding.FlareShape(1, 1, 8, 32, 16, binding.FLARE_F32, 0, 0, 0, 3)   # both known bits
+    assert lib.flare_workspace_bytes(ctypes.byref(shp), None, None) == 0
 
 
 def test_null_and_misaligned_pointers_are_rejected(lib):

@@ -1,0 +1,106 @@
+"""fp32 storage, mesh-like inputs with d = 4: the three shapes on which random sweeps read dq_lat above the
+1e-5 bar of the fp32 path (1.2e-5, 1.5e-5, 2.2e-5), pinned here with the cause.
+
+In every one of them the error sits in ONE latent row whose gradient is large and ill-conditioned:
+    dQ_m = scale * [ sum_n P_mn a_mn k_n  -  eps_m * sum_n P_mn k_n ]  +  (decode half, likewise with delta_n),
+a_mn = <dZ_m, V_n>, eps_m = <dZ_m, Z_m> = sum_n P_mn a_mn.  The two terms of the bracket are each K_m times
+larger than their difference (K_m ~ 200 for the worst row of these inputs: keys of a 4-channel mesh lift lie
+almost on a line, so the P-weighted mean key is long), and eps_m, Z_m, the log-sum-exp normalisers and the
+scores reach the backward rounded to fp32 (2^-24 relative each).  A plain numpy evaluation of the same
+formulas in fp32 -- and even in fp64 from fp32-rounded normalisers -- is off by 4e-5 ... 5e-5 on the third case
+(the kernels: 2.2e-5): the bar of 1e-5 is not reachable in fp32 arithmetic on such rows, whatever the order
+of operations (forming a - eps as <dZ_m, V_n - Z_m> first, or replacing eps by the kernel's own P-weighted mean
+of a, moves the error by less than a factor of 2.5).
+
+So the test states the bound the arithmetic does meet: forward outputs, dK and dV at the fp32 bar, and
+    err(dq_lat) <= 1e-5 + 8 * 2^-24 * K,    K = scale * (||eps_m kbar_m||_F + ||sum_n R_nm delta_n k_n||_F) / ||dQ||_F
+over the latents of a head (K: the cancellation factor of the two halves, from fp64 quantities; the mean-zero
+part of each half needs no such allowance).  Well-conditioned inputs have K of order 1-10, where the bound is
+the plain bar (checked below on the first reference workload's shape).
+"""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2508_12594_amd import binding, synth
+from tests._util import slice_relerr, to_device, to_host
+
+pytestmark = pytest.mark.gpu
+
+LOG2E = 1.4426950408889634
+
+CASES = [
+    # kind, B, H, N, M, d, seed, layout, saved, shared;   measured dq_lat before: 1.2e-5, 1.5e-5, 2.2e-5
+    dict(kind=2, B=1, H=2, N=150000, M=237, d=4, seed=777 + 123, layout="bhnd", saved=False, shared=False),
+    dict(kind=2, B=2, H=2, N=211, M=264, d=4, seed=777 + 5001, layout="bhnd", saved=True, shared=False),
+    dict(kind=2, B=1, H=1, N=2243, M=248, d=4, seed=4242 + 2243 + 248 + 4, layout="bnhd", saved=False, shared=True),
+    # a well-conditioned shape for comparison (first reference workload: normal inputs): plain bar
+    dict(kind=1, B=1, H=4, N=1024, M=64, d=32, seed=250812595, layout="bhnd", saved=False, shared=False),
+]
+
+
+def _cancellation_factor(q, k, v, dy, scale, dq_ref):
+    """K per head (max over heads): how much larger than dQ the cancelling terms of its two halves are."""
+    worst = 0.0
+    B, H = k.shape[0], k.shape[1]
+    for h in range(H):
+        num_e = np.zeros(q.shape[1:], np.float64)
+        num_d = np.zeros(q.shape[1:], np.float64)
+        for b in range(B):
+            kk, vv, gg = (x[b, h].astype(np.float64) for x in (k, v, dy))
+            s2 = (q[h].astype(np.float64) * (scale * LOG2E)) @ kk.T                 # [M, N]
+            p = np.exp2(s2 - s2.max(axis=1, keepdims=True))
+            p /= p.sum(axis=1, keepdims=True)
+            r = np.exp2(s2 - s2.max(axis=0, keepdims=True))
+            r /= r.sum(axis=0, keepdims=True)
+            z = p @ vv
+            dz = r @ gg
+            delta = np.einsum("nj,nj->n", gg, r.T @ z)
+            eps = np.einsum("mj,mj->m", dz, z)
+            num_e += eps[:, None] * (p @ kk)                                         # eps_m * kbar_m, summed over b
+            num_d += (r * delta[None, :]) @ kk                                       # sum_n R_nm delta_n k_n
+        worst = max(worst, scale * (np.linalg.norm(num_e) + np.linalg.norm(num_d)) / np.linalg.norm(dq_ref[h]))
+    return worst
+
+
+@pytest.mark.parametrize("case", CASES, ids=lambda c: "N%(N)d-M%(M)d-d%(d)d" % c)
+def test_fp32_gradients_meet_the_bar_up_to_their_conditioning(oracle, case):
+    import torch
+    c = case
+    print("[case] fp32 conditioning %s" % (c,), flush=True)
+    sys.stdout.flush()
+    B, H, N, M, d = c["B"], c["H"], c["N"], c["M"], c["d"]
+    inp = synth.make_inputs(c["kind"], B=B, H=H, N=N, M=M, d=d, dtype="f32", with_dy=True, seed=c["seed"])
+    if c["shared"]:
+        inp["q"] = np.ascontiguousarray(np.broadcast_to(inp["q"][0], (H, M, d)))
+    scale = 1.0 / np.sqrt(d)
+    dev = to_device(inp)
+    conv = (lambda t: t.permute(0, 2, 1, 3).contiguous()) if c["layout"] == "bnhd" else (lambda t: t)
+    back = (lambda t: t.permute(0, 2, 1, 3)) if c["layout"] == "bnhd" else (lambda t: t)
+    k, v, dy = conv(dev["k"]), conv(dev["v"]), conv(dev["dy"])
+    q = dev["q"][0].contiguous() if c["shared"] else dev["q"]
+    lse_dec = torch.empty((B, H, N), dtype=torch.float32, device="cuda") if c["saved"] else None
+    y, z, lse = binding.forward(q, k, v, scale, lse_dec=lse_dec, layout=c["layout"])
+    dq, dk, dv = binding.backward(q, k, v, dy, z, lse, scale, y=y if c["saved"] else None, lse_dec=lse_dec,
+                                  layout=c["layout"])
+    torch.cuda.synchronize()
+    y_ref, z_ref, _ = oracle.forward(inp["q"], inp["k"], inp["v"], scale)
+    dq_ref, dk_ref, dv_ref = oracle.backward(inp["q"], inp["k"], inp["v"], inp["dy"], scale)
+    dq_h = to_host(dq)
+    if c["shared"]:
+        dq_h, dq_cmp = dq_h[None], dq_ref.sum(axis=0)[None]
+    else:
+        dq_cmp = dq_ref
+    errs = dict(y=slice_relerr(to_host(back(y)), y_ref), z=slice_relerr(to_host(z), z_ref),
+                dk=slice_relerr(to_host(back(dk)), dk_ref), dv=slice_relerr(to_host(back(dv)), dv_ref),
+                dq=slice_relerr(dq_h, dq_cmp))
+    K = _cancellation_factor(inp["q"], inp["k"], inp["v"], inp["dy"], scale, dq_cmp if not c["shared"] else
+                             np.broadcast_to(dq_cmp, (H, M, d)))
+    bound = 1e-5 + 8.0 * 2.0 ** -24 * K
+    print("[case]    " + "  ".join("%s %.2e" % kv for kv in errs.items()) +
+          "  cancellation factor K %.1f -> dq bound %.2e" % (K, bound), flush=True)
+    assert max(errs["y"], errs["z"], errs["dk"], errs["dv"]) <= 1e-5
+    assert errs["dq"] <= bound
+    if c["kind"] == 1:
+        assert K <= 20.0 and errs["dq"] <= 1e-5      # well-conditioned: the plain bar

@@ -12,7 +12,7 @@ import numpy as np
 import pytest
 
 from paper_2508_12594_amd import binding, synth
-from tests._util import TOL, on_matrix_cores, slice_relerr, to_device, to_host
+from tests._util import ROW_FACTOR, TOL, on_matrix_cores, row_relerr, slice_relerr, to_device, to_host
 
 pytestmark = pytest.mark.gpu
 
@@ -35,6 +35,10 @@ def _forward_case(oracle, inp, scale=None, tol=None):
     e_l = float(np.max(np.abs(to_host(lse) - lse_ref)))
     _say("   err y %.3e  z %.3e  lse(abs) %.3e  (tol %.0e)" % (e_y, e_z, e_l, tol))
     assert e_y <= tol and e_z <= tol
+    if y_ref.shape[2] >= 10000:     # many tokens: a few wrong rows would vanish in the norm; look at the worst one
+        r_y, r_z = row_relerr(to_host(y), y_ref), row_relerr(to_host(z), z_ref)
+        _say("   worst row y %.3e  z %.3e" % (r_y, r_z))
+        assert max(r_y, r_z) <= ROW_FACTOR * tol
     # absolute error of the log-sum-exp: rounding of the scores (relative to |S|) plus, on the bf16
     # path, the bf16 rounding of the weights that are summed
     coarse = inp["dtype"] == "bf16" or (inp["dtype"] == "f16" and tol >= TOL["bf16"])
@@ -42,8 +46,9 @@ def _forward_case(oracle, inp, scale=None, tol=None):
     return y, z, lse
 
 
-def _backward_case(oracle, inp, scale=None, tol=None, zero_dq_dk=False, saved=False):
-    """saved=True hands the forward's y and lse_dec to the backward (no recomputation)."""
+def _backward_case(oracle, inp, scale=None, tol=None, zero_dq_dk=False, saved=False, variant=0):
+    """saved=True hands the forward's y and lse_dec to the backward (no recomputation); variant: flare_variant
+    bits that force a kernel variant of the backward."""
     import torch
     scale = inp["scale"] if scale is None else scale
     tol = TOL[inp["dtype"]] if tol is None else tol
@@ -51,7 +56,7 @@ def _backward_case(oracle, inp, scale=None, tol=None, zero_dq_dk=False, saved=Fa
     lse_dec = torch.empty(dev["k"].shape[:3], dtype=torch.float32, device="cuda") if saved else None
     y, z, lse = binding.forward(dev["q"], dev["k"], dev["v"], scale, lse_dec=lse_dec)
     dq, dk, dv = binding.backward(dev["q"], dev["k"], dev["v"], dev["dy"], z, lse, scale,
-                                  y=y if saved else None, lse_dec=lse_dec)
+                                  y=y if saved else None, lse_dec=lse_dec, variant=variant)
     torch.cuda.synchronize()
     dq_ref, dk_ref, dv_ref = oracle.backward(inp["q"], inp["k"], inp["v"], inp["dy"], scale)
     e_v = slice_relerr(to_host(dv), dv_ref)
@@ -67,6 +72,10 @@ def _backward_case(oracle, inp, scale=None, tol=None, zero_dq_dk=False, saved=Fa
         e_k = slice_relerr(to_host(dk), dk_ref)
     _say("   err dq %.3e  dk %.3e  dv %.3e  (tol %.0e)" % (e_q, e_k, e_v, tol))
     assert e_q <= tol and e_k <= tol and e_v <= tol
+    if dk_ref.shape[2] >= 10000 and not zero_dq_dk:
+        rows = (row_relerr(to_host(dq), dq_ref), row_relerr(to_host(dk), dk_ref), row_relerr(to_host(dv), dv_ref))
+        _say("   worst row dq %.3e  dk %.3e  dv %.3e" % rows)
+        assert max(rows) <= ROW_FACTOR * tol
     return dq, dk, dv
 
 
@@ -335,12 +344,11 @@ def test_fp16_storage_matrix_core_path(oracle, cfg, over):
         assert slice_relerr(to_host(y), inp["v"]) <= 4e-3   # Y = v, through one rounding to bf16
 
 
-def test_fp16_matrix_core_two_exponential_kernels(oracle, monkeypatch):
+def test_fp16_matrix_core_two_exponential_kernels(oracle):
     _say("fp16 on matrix cores, two-exponential backward")
-    monkeypatch.setenv("FLARE_BWD_TWO_EXP", "1")
     for cfg, over in [(4, dict(N=2100)), (5, dict(N=1100))]:
         inp = synth.make_inputs(cfg, with_dy=True, dtype="f16", **over)
-        _backward_case(oracle, inp, tol=TOL["bf16"], saved=True)
+        _backward_case(oracle, inp, tol=TOL["bf16"], saved=True, variant=binding.VARIANT_TWO_EXP)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -368,15 +376,13 @@ def test_large_score_offsets(oracle, dtype):
 
 
 @pytest.mark.parametrize("cfg,over", [(2, dict(B=2, N=2050)), (4, dict(N=3001)), (5, dict(N=1999)), (3, dict(B=1, N=700))])
-def test_backward_two_exponential_kernels(oracle, cfg, over, monkeypatch):
+def test_backward_two_exponential_kernels(oracle, cfg, over):
     """The matrix-core backward has a one-exponential and a two-exponential variant of its last
     two kernels; the library picks per (b,h).  Force the second and check it to the same bar."""
     _say("backward, two-exponential kernels forced, cfg%d %s" % (cfg, over))
     inp = synth.make_inputs(cfg, with_dy=True, **over)
     dq1, dk1, dv1 = _backward_case(oracle, inp, saved=True)
-    monkeypatch.setenv("FLARE_BWD_TWO_EXP", "1")
-    dq2, dk2, dv2 = _backward_case(oracle, inp, saved=True)
-    monkeypatch.delenv("FLARE_BWD_TWO_EXP")
+    dq2, dk2, dv2 = _backward_case(oracle, inp, saved=True, variant=binding.VARIANT_TWO_EXP)
     # dV does not depend on the variant's arithmetic beyond P: identical; dq, dk agree closely
     assert slice_relerr(to_host(dq2), to_host(dq1)) <= TOL["bf16"]
     assert slice_relerr(to_host(dk2), to_host(dk1)) <= TOL["bf16"]
@@ -384,16 +390,14 @@ def test_backward_two_exponential_kernels(oracle, cfg, over, monkeypatch):
 
 @pytest.mark.parametrize("cfg,over", [(4, dict(N=3001)), (2, dict(B=1, N=1500, d=8)), (2, dict(B=1, N=1500, d=4)),
                                       (4, dict(N=900, M=100, dtype="f16"))])
-def test_backward_separate_dq_kernel(oracle, cfg, over, monkeypatch):
-    """At d <= 16 the dK/dV kernel also forms dQ; FLARE_BWD_SEPARATE_DQ=1 runs the separate dQ kernel
+def test_backward_separate_dq_kernel(oracle, cfg, over):
+    """At d <= 16 the dK/dV kernel also forms dQ; FLARE_VARIANT_SEPARATE_DQ runs the separate dQ kernel
     (the one d = 32 uses) on the same shapes.  Both must meet the bar and agree closely."""
     _say("backward with the separate dQ kernel, cfg%d %s" % (cfg, over))
     inp = synth.make_inputs(cfg, with_dy=True, **over)
     tol = TOL["bf16"]
     dq1, dk1, dv1 = _backward_case(oracle, inp, tol=tol, saved=True)
-    monkeypatch.setenv("FLARE_BWD_SEPARATE_DQ", "1")
-    dq2, dk2, dv2 = _backward_case(oracle, inp, tol=tol, saved=True)
-    monkeypatch.delenv("FLARE_BWD_SEPARATE_DQ")
+    dq2, dk2, dv2 = _backward_case(oracle, inp, tol=tol, saved=True, variant=binding.VARIANT_SEPARATE_DQ)
     import torch
     assert torch.equal(dv1, dv2)
     assert slice_relerr(to_host(dq2), to_host(dq1)) <= tol and slice_relerr(to_host(dk2), to_host(dk1)) <= tol
