@@ -1,24 +1,33 @@
 #!/usr/bin/env python3
 """Benchmark of the FLARE mixer on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--cfg 4] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--cfg 4] [--no-cpu-baseline] [--no-other-configs]
+    python bench.py --machine-rates
 
 A step is one pass of the whole hot path -- flare_forward (encode partials, merge, decode)
 followed by flare_backward -- over one batch of the synthetic million-token mesh workload
 (B=1, H=8, d=16, N=1,000,000, M=256, bf16 storage, fp32 accumulation).  Inputs are resident in
 HBM before the timed region.  One JSON line is printed:
-  value        tokens/s of forward+backward (B*N tokens per step)
-  fwd          the same for the forward alone (its own timed loop of K steps)
-  roofline     the dominant kernel (most time per step) against the roofline that binds it: HBM
-               (algorithmic bytes per launch / mean duration) or, where the softmax's exponentials
-               need longer than the bytes, the vector ALUs' v_exp_f32 rate ("alu"); durations are
-               measured with HIP events on the launch stream
-  kernels      mean duration, algorithmic GB/s and exponentials/s of every kernel of the step
-  cpu_baseline the fp64 CPU oracle timed on a bounded sample of the same workload
+  value, ms_per_step   W untimed warm-up steps, then exactly K steps between two device synchronisations
+  timing               the same step (and the forward alone) timed per call with a pair of events on the
+                       launch stream: median and minimum, warm, and cold (1 GiB written between the calls
+                       so that nothing of the token tensors is left in the L2s or the memory-side cache)
+  the benchmark spec           encode + decode against the HBM and MFMA rooflines (the fraction the target of 0.60
+                       is defined on), beside the instruction-issue bound of the same two kernels
+  roofline             the dominant kernel (most time per step) against the roofline that binds it: HBM
+                       (algorithmic bytes per launch / mean duration) or, where the softmax's exponentials
+                       need longer than the bytes, the vector ALUs' v_exp_f32 rate ("alu"); durations are
+                       measured with HIP events on the launch stream
+  kernels              per kernel of the step: mean duration, algorithmic GB/s, exponentials/s, and issue_frac =
+                       (time its minimal instruction mix needs on a SIMD at the measured issue clocks) / duration
+  other_configs        the other reference workloads (1, 2, 3, 5), each with its step, forward and dominant kernel
+  cpu_baseline         the fp64 CPU oracle timed on a bounded sample of the same workload
 """
 import argparse
 import json
 import os
+import re
+import statistics
 import sys
 import time
 
@@ -26,12 +35,20 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
+SIMDS = 256 * 4                 # compute units x SIMDs
+NOMINAL_GHZ = 2.4
 
-# Rates of the softmax's exponentials on the vector ALUs (one v_exp_f32 per score and half):
-# 256 CUs x 4 SIMDs x 64 lanes / 8 cycles per wave instruction x 2.4 GHz.
-EXP_PEAK_GOPS = 256 * 4 * 64 / 8 * 2.4
+# Issue clocks per wave64 instruction and SIMD, in 2.4 GHz clocks, as `bench.py --machine-rates` measures them
+# (profiles/machine_rates.md): v_exp_f32 8.2; v_cvt_pk_bf16_f32 (and v_max3_f32, v_perm_b32, v_dot2c_f32_bf16)
+# 4.25; v_fma_f32 / v_mul_f32 2.95; one v_mfma_f32_32x32x16_bf16 beside a saturated vector stream of the same
+# SIMD costs that stream 13 clocks (its own pipe 32 clocks; measured 8.5 ... 17 from sparse to dense), a
+# v_mfma_f32_16x16x32_bf16 half of that.
+CLK = {"exp": 8.2, "pack": 4.25, "fma": 2.95, "mfma32_issue": 13.0, "mfma32_pipe": 32.0}
+
+# The softmax's exponentials at the v_exp_f32 rate: 1024 SIMDs x 64 lanes / 8.15 clocks x 2.4 GHz.
+EXP_PEAK_GOPS = SIMDS * 64 / CLK["exp"] * NOMINAL_GHZ
 
 
 def algorithmic_bytes(kernel, B, H, N, M, d, elem):
@@ -48,8 +65,6 @@ def algorithmic_bytes(kernel, B, H, N, M, d, elem):
         "bwd_dkdv": 5 * row + 8,                # k, v, dy in; dk, dv out
         "bwd_dq_partial_2exp": 3 * row + 8,
         "bwd_dkdv_2exp": 5 * row + 8,
-        "bwd_pass_a": 2 * row + 8,
-        "bwd_pass_b": 5 * row + 8,
     }
     if kernel in per_token:
         return bhn * per_token[kernel]
@@ -66,16 +81,224 @@ def exponentials(kernel, B, H, N, M):
     return per_pair.get(kernel, 0) * B * H * N * M
 
 
-# HBM bytes per launch (fetch, write) of the default workload, from two `rocprofv3 --pmc` runs
-# (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch), each scaled by what the same counter read for a
-# plain 256 MB device copy in the same run (FETCH_SIZE x 2.00, WRITE_SIZE x 1.00); see
-# profiles/forward_backward_cfg4_hbm_traffic.md.
-MEASURED_TRAFFIC_CFG4 = {
-    "encode_partial": (250642 * 2.0 * 1024, 18432 * 1024),
-    "decode": (125963 * 2.0 * 1024, 281250 * 1024),
-    "bwd_dz_partial": (441142 * 2.0 * 1024, 47911 * 1024),
-    "bwd_dkdv": (408256 * 2.0 * 1024, 505120 * 1024),
-}
+def issue_clocks_per_tile(kernel, d, fused_dq):
+    """Issue clocks one SIMD needs for the minimal instruction mix of one 32 x 32 tile of scores (16 scores per
+    lane): per score one exponential and half a pack of two weights, plus the matrix instructions that are
+    algorithmic for the kernel at this head dimension (score products with the hi + lo pair of q', value
+    products; at d <= 8 the pair rides in one product), each at what it costs the vector stream.  None: a kernel
+    without a softmax tile."""
+    ks = 2 if d == 32 else 1                     # k-steps of a score product; column groups of a value product
+    score = ks * (1 if d <= 8 else 2)            # hi + lo
+    value = 2 * ks                               # 32 contraction slots = two k-steps, per column group
+    mix = {
+        "encode_partial": (16, 8, 0, score + value),
+        "decode": (16, 8, 0, score + value),
+        "bwd_token_stats": (16, 8, 0, score + value),
+        "bwd_dz_partial": (16, 8, 0, score + value),
+        # dS = P (a + w u c): per score one exponential, two multiply-adds, a pack of P and a pack of dS
+        "bwd_dq_partial": (16, 16, 32, score + 2 * ks + value),                       # scores, a, c, dS.K
+        "bwd_dkdv": (16, 16, 32, score + 2 * ks + 2 * value + (1 if fused_dq else 0)),  # + dV, dK (, dQ: 16-row products)
+    }
+    mix["bwd_dq_partial_2exp"] = (32,) + mix["bwd_dq_partial"][1:]
+    mix["bwd_dkdv_2exp"] = (32,) + mix["bwd_dkdv"][1:]
+    if kernel not in mix:
+        return None
+    n_exp, n_pack, n_fma, n_mfma = mix[kernel]
+    vector = n_exp * CLK["exp"] + n_pack * CLK["pack"] + n_fma * CLK["fma"] + n_mfma * CLK["mfma32_issue"]
+    return max(vector, n_mfma * CLK["mfma32_pipe"])
+
+
+def measured_traffic(kernel):
+    """HBM bytes per launch (fetch + write) of the default workload's kernels, as two `rocprofv3 --pmc` runs
+    counted them (FETCH_SIZE, then WRITE_SIZE, scaled by a plain copy of known size): read from the json block of
+    the tracked summary profiles/forward_backward_cfg4_hbm_traffic.md.  None when the file has no entry."""
+    path = os.path.join(ROOT, "profiles", "forward_backward_cfg4_hbm_traffic.md")
+    try:
+        m = re.search(r"```json\s*(\{.*?\})\s*```", open(path).read(), re.S)
+        table = json.loads(m.group(1))["bytes_per_launch"]
+        return float(table[kernel]["fetch"]) + float(table[kernel]["write"])
+    except (OSError, AttributeError, KeyError, ValueError):
+        return None
+
+
+def event_times(fn, iters, between=None):
+    """Per-call durations in ms: a pair of events on the current stream around every call of fn."""
+    import torch
+    pairs = []
+    for _ in range(iters):
+        if between is not None:
+            between()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
+        pairs.append((e0, e1))
+    torch.cuda.synchronize()
+    return [a.elapsed_time(b) for a, b in pairs]
+
+
+def stats(ms):
+    return {"median_ms": round(statistics.median(ms), 4), "min_ms": round(min(ms), 4), "calls": len(ms)}
+
+
+def run_workload(cfg, args, steps, warmup, primary):
+    """Times one reference workload; returns (summary dict, inputs on the host)."""
+    import torch
+    from paper_2508_12594_amd import binding, synth
+
+    over = {}
+    if primary:
+        if args.tokens is not None:
+            over["N"] = args.tokens
+        if args.latents is not None:
+            over["M"] = args.latents
+        if args.head_dim is not None:
+            over["d"] = args.head_dim
+        if args.dtype is not None:
+            over["dtype"] = args.dtype
+    inp = synth.make_inputs(cfg, with_dy=True, **over)
+    B, H, N, M, d = (inp[x] for x in "BHNMd")
+    dt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[inp["dtype"]]
+    elem = 4 if inp["dtype"] == "f32" else 2
+    dev = {n: torch.from_numpy(inp[n]).to("cuda", dt).contiguous() for n in ("q", "k", "v", "dy")}
+    lay = args.layout if primary else "bhnd"
+    y_f32 = args.y_f32 and primary
+    if lay == "bnhd":
+        for n in ("k", "v", "dy"):
+            dev[n] = dev[n].permute(0, 2, 1, 3).contiguous()
+    scale = inp["scale"]
+    code = {"f32": binding.FLARE_F32, "bf16": binding.FLARE_BF16, "f16": binding.FLARE_F16}[inp["dtype"]]
+    fwd_b, bwd_b = binding.workspace_bytes(B, H, N, M, d, code, y_f32)
+    ws = torch.empty(max(fwd_b, bwd_b, 256), dtype=torch.uint8, device="cuda")
+    y = torch.empty_like(dev["k"], dtype=torch.float32) if y_f32 else torch.empty_like(dev["k"])
+    z = torch.empty((B, H, M, d), dtype=torch.float32, device="cuda")
+    lse = torch.empty((B, H, M), dtype=torch.float32, device="cuda")
+    lse_dec = torch.empty((B, H, N), dtype=torch.float32, device="cuda")
+    dq = torch.empty((H, M, d), dtype=torch.float32, device="cuda")
+    dk = torch.empty_like(dev["k"])
+    dv = torch.empty_like(dev["k"])
+
+    def fwd():
+        binding.forward(dev["q"], dev["k"], dev["v"], scale, y=y, z=z, lse_enc=lse, lse_dec=lse_dec, workspace=ws,
+                        layout=lay)
+
+    def step():   # a training step: the forward saves z, lse_enc, lse_dec and y for the backward
+        fwd()
+        binding.backward(dev["q"], dev["k"], dev["v"], dev["dy"], z, lse, scale, y=y, lse_dec=lse_dec,
+                         dq_lat=dq, dk=dk, dv=dv, workspace=ws, layout=lay)
+
+    def timed(fn, n):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n
+
+    if primary and args.copy_calibration:
+        for _ in range(3):
+            y.copy_(dev["k"])                 # reads and writes B*H*N*d*elem bytes each
+        torch.cuda.synchronize()
+    for _ in range(warmup):
+        step()
+    t_step = timed(step, steps)               # the headline: forward + backward, K steps between two synchronisations
+    t_fwd = timed(fn=fwd, n=steps)            # forward alone
+
+    # per call, with events on the launch stream (the library enqueues on torch's current stream)
+    n_ev = min(steps, 200)
+    timing = {"step_warm": stats(event_times(step, n_ev)), "fwd_warm": stats(event_times(fwd, n_ev))}
+    if primary:
+        flush = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        count = [0]
+
+        def dirty():          # 1 GiB of writes: more than the L2s (8 x 4 MiB) and the memory-side cache (256 MiB) hold
+            count[0] += 1
+            flush.fill_(count[0] & 0xFF)
+        timing["step_cold"] = stats(event_times(step, 20, dirty))
+        timing["fwd_cold"] = stats(event_times(fwd, 20, dirty))
+        del flush
+
+    # per-kernel durations: HIP events recorded by the library on the launch stream
+    prof_steps = min(steps, 400)              # the library keeps at most 8192 event pairs
+    binding.profile_enable(True)
+    t_step_prof = timed(step, prof_steps)
+    prof = binding.profile_read()
+    binding.profile_enable(False)
+
+    fused_dq = "bwd_dq_partial" not in prof and "bwd_dq_partial_2exp" not in prof
+    tiles_per_simd = B * H * ((N + 31) // 32) * ((M + 31) // 32) / SIMDS
+    kernels = {}
+    for name, (ms, cnt) in prof.items():
+        mean_s = ms / cnt * 1e-3
+        # beyond 256 latents a kernel is launched once per chunk of latents (or the backward launches it for the
+        # statistics and again for dZ): bytes and exponentials are the whole operation's, so is the time
+        per_step_s = mean_s * max(1, cnt // prof_steps)
+        ab = algorithmic_bytes(name, B, H, N, M, d, elem)
+        ex = exponentials(name, B, H, N, M)
+        ic = issue_clocks_per_tile(name, d, fused_dq) if inp["dtype"] != "f32" else None
+        twin = name[:-5] if name.endswith("_2exp") else name + "_2exp"
+        twin_ms = prof[twin][0] / prof[twin][1] if twin in prof else 0.0
+        if ms / cnt < 0.05 * twin_ms or (ms / cnt < 0.010 and ms / cnt < 0.3 * twin_ms):
+            ab, ex, ic = None, 0, None     # launched, but every (b,h) slice went to the other variant: it left at once
+        kernels[name] = {"mean_us": round(mean_s * 1e6, 2), "launches_per_step": cnt // prof_steps,
+                         "algorithmic_GBps": (round(ab / per_step_s / 1e9, 1) if ab else None),
+                         "hbm_frac": (round(ab / per_step_s / 1e9 / HBM_PEAK_GBS, 4) if ab else None),
+                         "exp_Gops": (round(ex / per_step_s / 1e9, 1) if ex else None),
+                         "exp_frac": (round(ex / per_step_s / 1e9 / EXP_PEAK_GOPS, 4) if ex else None),
+                         "issue_frac": (round(ic * tiles_per_simd / (NOMINAL_GHZ * 1e9) / per_step_s, 4)
+                                        if ic else None)}
+    streaming = {n: v for n, v in kernels.items() if v["algorithmic_GBps"] is not None}
+    dom = max(streaming, key=lambda n: streaming[n]["mean_us"] * streaming[n]["launches_per_step"])
+    dom_bytes = algorithmic_bytes(dom, B, H, N, M, d, elem)
+    dom_exps = exponentials(dom, B, H, N, M)
+    dom_s = kernels[dom]["mean_us"] * 1e-6 * max(1, kernels[dom]["launches_per_step"])
+    default_workload = (primary and cfg == 4 and not over and not y_f32 and lay == "bhnd")
+    traffic = measured_traffic(dom) if default_workload else None
+    # the roofline that binds this kernel: whichever lower bound on its duration is larger
+    hbm = {"achieved": round(dom_bytes / dom_s / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+           "frac": round(dom_bytes / dom_s / 1e9 / HBM_PEAK_GBS, 4), "bytes_per_launch": dom_bytes}
+    if dom_exps / (EXP_PEAK_GOPS * 1e9) > dom_bytes / (HBM_PEAK_GBS * 1e9):
+        roofline = {"kernel": dom, "bound": "alu", "achieved": round(dom_exps / dom_s / 1e9, 1),
+                    "peak": round(EXP_PEAK_GOPS, 1), "unit": "Gop/s (v_exp_f32 lane-ops)",
+                    "frac": round(dom_exps / dom_s / 1e9 / EXP_PEAK_GOPS, 4), "traffic": traffic,
+                    "ops_per_launch": dom_exps, "mean_us": kernels[dom]["mean_us"], "hbm": hbm}
+    else:
+        roofline = dict(hbm, kernel=dom, bound="hbm", traffic=traffic, mean_us=kernels[dom]["mean_us"])
+    if traffic is not None:
+        roofline["traffic_source"] = "profiles/forward_backward_cfg4_hbm_traffic.md (rocprofv3 --pmc, not this run)"
+    roofline["issue_frac"] = kernels[dom]["issue_frac"]
+
+    tokens = B * N
+    fwd_bytes = 4 * B * H * N * d * elem       # k twice, v once, y once
+    fwd_flops = 8.0 * B * H * N * M * d
+    t_fwd_med = timing["fwd_warm"]["median_ms"] * 1e-3
+    enc_dec_s = sum(kernels[n]["mean_us"] * kernels[n]["launches_per_step"] for n in ("encode_partial", "decode")
+                    if n in kernels) * 1e-6
+    ic_fwd = issue_clocks_per_tile("encode_partial", d, fused_dq) if inp["dtype"] != "f32" else None
+    north = {"what": "encode + decode (flare_forward, median of per-call event times, warm)",
+             "ms": round(t_fwd_med * 1e3, 4),
+             "hbm_frac": round(fwd_bytes / t_fwd_med / 1e9 / HBM_PEAK_GBS, 4),
+             "mfma_frac": round(fwd_flops / t_fwd_med / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+             "exp_frac": round(2.0 * B * H * N * M / t_fwd_med / 1e9 / EXP_PEAK_GOPS, 4),
+             "issue_frac": (round(2 * ic_fwd * tiles_per_simd / (NOMINAL_GHZ * 1e9) / enc_dec_s, 4)
+                            if ic_fwd and enc_dec_s else None),
+             "target_hbm_frac": 0.60}
+    if "fwd_cold" in timing:
+        t_cold = timing["fwd_cold"]["median_ms"] * 1e-3
+        north["cold_ms"] = round(t_cold * 1e3, 4)
+        north["cold_hbm_frac"] = round(fwd_bytes / t_cold / 1e9 / HBM_PEAK_GBS, 4)
+    out = {
+        "workload": synth.describe(cfg) + ("" if "N" not in over else " [N overridden to %d]" % N)
+        + ("" if "M" not in over else " [M overridden to %d]" % M)
+        + ("" if "d" not in over else " [d overridden to %d]" % d)
+        + ("" if "dtype" not in over else " [storage type overridden to %s]" % over["dtype"])
+        + (" [y in fp32]" if y_f32 else ""),
+        "shape": {"B": B, "H": H, "N": N, "M": M, "d": d, "dtype": inp["dtype"],
+                  "layout": "[B,H,N,d]" if lay == "bhnd" else "[B,N,H,d]"},
+        "tokens": tokens, "t_step": t_step, "t_fwd": t_fwd, "t_step_prof": t_step_prof, "timing": timing,
+        "north_star": north, "roofline": roofline, "kernels": kernels,
+    }
+    return out, inp, dev, (lse, lse_dec, lay, scale)
 
 
 def main():
@@ -98,6 +321,8 @@ def main():
     ap.add_argument("--y-f32", action="store_true",
                     help="the forward writes y in fp32 and the backward takes delta from it (flare_shape.y_f32)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the short runs of the other reference workloads (1, 2, 3, 5)")
     ap.add_argument("--machine-rates", action="store_true",
                     help="run the machine-rate micro-benchmarks of libflare_rates.so instead of the workload and "
                          "print their table (the rates the issue bound and the exponential ceiling are priced with)")
@@ -110,7 +335,7 @@ def main():
         sys.exit(2)
 
     import torch
-    from paper_2508_12594_amd import binding, synth
+    from paper_2508_12594_amd import binding
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -123,136 +348,30 @@ def main():
             print("%-100s waves/SIMD %d param %2d: %9.4f ms  %7s clk/instr  %6.0f MHz %s" % (
                 r["experiment"], r["waves_per_simd"], r["param"], r["ms"], r.get("clk_per_instr", "-"),
                 r["shader_mhz"], ("%.0f GB/s" % r["GBps"]) if "GBps" in r else ""), file=sys.stderr, flush=True)
-        print(json.dumps({"machine_rates": rows}), flush=True)
+        print(json.dumps({"machine_rates": rows, "derived": rates.derive(rows)}), flush=True)
         return
     binding.load()
 
-    over = {} if args.tokens is None else {"N": args.tokens}
-    if args.latents is not None:
-        over["M"] = args.latents
-    if args.head_dim is not None:
-        over["d"] = args.head_dim
-    if args.dtype is not None:
-        over["dtype"] = args.dtype
-    inp = synth.make_inputs(args.cfg, with_dy=True, **over)
-    B, H, N, M, d = (inp[x] for x in "BHNMd")
-    dt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[inp["dtype"]]
-    elem = 4 if inp["dtype"] == "f32" else 2
-    dev = {n: torch.from_numpy(inp[n]).to("cuda", dt).contiguous() for n in ("q", "k", "v", "dy")}
-    if args.layout == "bnhd":
-        for n in ("k", "v", "dy"):
-            dev[n] = dev[n].permute(0, 2, 1, 3).contiguous()
-    lay = args.layout
-    scale = inp["scale"]
-    code = {"f32": binding.FLARE_F32, "bf16": binding.FLARE_BF16, "f16": binding.FLARE_F16}[inp["dtype"]]
-    fwd_b, bwd_b = binding.workspace_bytes(B, H, N, M, d, code, args.y_f32)
-    ws = torch.empty(max(fwd_b, bwd_b, 256), dtype=torch.uint8, device="cuda")
-    y = torch.empty_like(dev["k"], dtype=torch.float32) if args.y_f32 else torch.empty_like(dev["k"])
-    z = torch.empty((B, H, M, d), dtype=torch.float32, device="cuda")
-    lse = torch.empty((B, H, M), dtype=torch.float32, device="cuda")
-    lse_dec = torch.empty((B, H, N), dtype=torch.float32, device="cuda")
-    dq = torch.empty((H, M, d), dtype=torch.float32, device="cuda")
-    dk = torch.empty_like(dev["k"])
-    dv = torch.empty_like(dev["k"])
-
-    def fwd():
-        binding.forward(dev["q"], dev["k"], dev["v"], scale, y=y, z=z, lse_enc=lse, lse_dec=lse_dec, workspace=ws,
-                        layout=lay)
-
-    def step():   # a training step: the forward saves z, lse_enc, lse_dec and y for the backward
-        fwd()
-        binding.backward(dev["q"], dev["k"], dev["v"], dev["dy"], z, lse, scale, y=y, lse_dec=lse_dec,
-                         dq_lat=dq, dk=dk, dv=dv, workspace=ws, layout=lay)
-
-    def timed(fn, steps):
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            fn()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) / steps
-
-    if args.copy_calibration:
-        for _ in range(3):
-            y.copy_(dev["k"])                 # reads and writes B*H*N*d*elem bytes each
-        torch.cuda.synchronize()
-    for _ in range(args.warmup):
-        step()
-    t_step = timed(step, args.steps)          # the headline: forward + backward
-    t_fwd = timed(fwd, args.steps)            # forward alone
-
-    # per-kernel durations: HIP events recorded by the library on the launch stream, same K steps
-    prof_steps = min(args.steps, 400)         # the library keeps at most 8192 event pairs
-    binding.profile_enable(True)
-    t_step_prof = timed(step, prof_steps)
-    prof = binding.profile_read()
-    binding.profile_enable(False)
-
-    kernels = {}
-    for name, (ms, cnt) in prof.items():
-        mean_s = ms / cnt * 1e-3
-        # beyond 256 latents a kernel is launched once per chunk of latents (or the backward launches it for the
-        # statistics and again for dZ): bytes and exponentials are the whole operation's, so is the time
-        per_step_s = mean_s * max(1, cnt // prof_steps)
-        ab = algorithmic_bytes(name, B, H, N, M, d, elem)
-        ex = exponentials(name, B, H, N, M)
-        twin = name[:-5] if name.endswith("_2exp") else name + "_2exp"
-        twin_ms = prof[twin][0] / prof[twin][1] if twin in prof else 0.0
-        if ms / cnt < 0.05 * twin_ms or (ms / cnt < 0.010 and ms / cnt < 0.3 * twin_ms):
-            ab, ex = None, 0     # launched, but every (b,h) slice went to the other variant: it left at once
-        kernels[name] = {"mean_us": round(mean_s * 1e6, 2), "launches_per_step": cnt // prof_steps,
-                         "algorithmic_GBps": (round(ab / per_step_s / 1e9, 1) if ab else None),
-                         "hbm_frac": (round(ab / per_step_s / 1e9 / HBM_PEAK_GBS, 4) if ab else None),
-                         "exp_Gops": (round(ex / per_step_s / 1e9, 1) if ex else None),
-                         "exp_frac": (round(ex / per_step_s / 1e9 / EXP_PEAK_GOPS, 4) if ex else None)}
-    streaming = {n: v for n, v in kernels.items() if v["algorithmic_GBps"] is not None}
-    dom = max(streaming, key=lambda n: streaming[n]["mean_us"] * streaming[n]["launches_per_step"])
-    dom_bytes = algorithmic_bytes(dom, B, H, N, M, d, elem)
-    dom_exps = exponentials(dom, B, H, N, M)
-    dom_s = kernels[dom]["mean_us"] * 1e-6 * max(1, kernels[dom]["launches_per_step"])
-    default_workload = (args.cfg == 4 and args.tokens is None and args.latents is None and args.head_dim is None
-                        and args.dtype is None and not args.y_f32)
-    traffic = sum(MEASURED_TRAFFIC_CFG4[dom]) if default_workload and dom in MEASURED_TRAFFIC_CFG4 else None
-    # the roofline that binds this kernel: whichever lower bound on its duration is larger
-    if dom_exps / (EXP_PEAK_GOPS * 1e9) > dom_bytes / (HBM_PEAK_GBS * 1e9):
-        roofline = {"kernel": dom, "bound": "alu", "achieved": round(dom_exps / dom_s / 1e9, 1),
-                    "peak": EXP_PEAK_GOPS, "unit": "Gop/s (v_exp_f32 lane-ops)",
-                    "frac": round(dom_exps / dom_s / 1e9 / EXP_PEAK_GOPS, 4), "traffic": traffic,
-                    "ops_per_launch": dom_exps, "mean_us": kernels[dom]["mean_us"],
-                    "hbm": {"achieved": round(dom_bytes / dom_s / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                            "frac": round(dom_bytes / dom_s / 1e9 / HBM_PEAK_GBS, 4),
-                            "bytes_per_launch": dom_bytes}}
-    else:
-        roofline = {"kernel": dom, "bound": "hbm", "achieved": round(dom_bytes / dom_s / 1e9, 1),
-                    "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(dom_bytes / dom_s / 1e9 / HBM_PEAK_GBS, 4), "traffic": traffic,
-                    "bytes_per_launch": dom_bytes, "mean_us": kernels[dom]["mean_us"]}
-
-    tokens = B * N
-    fwd_bytes = 4 * B * H * N * d * elem       # k twice, v once, y once
-    fwd_flops = 8.0 * B * H * N * M * d
+    res, inp, dev, (lse, lse_dec, lay, scale) = run_workload(args.cfg, args, args.steps, args.warmup, True)
+    B, H, N, M, d = (res["shape"][x] for x in "BHNMd")
+    t_step, t_fwd = res["t_step"], res["t_fwd"]
+    fwd_bytes = 4 * B * H * N * d * (4 if res["shape"]["dtype"] == "f32" else 2)
     out = {
         "metric": "FLARE fwd+bwd tokens/sec at N=%d, M=%d (one MI355X)" % (N, M),
-        "value": round(tokens / t_step, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "value": round(res["tokens"] / t_step, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(t_step * 1e3, 4), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": inp["dtype"], "data": "synthetic",
-        "config": {"workload": synth.describe(args.cfg) + ("" if args.tokens is None else " [N overridden to %d]" % N)
-                   + ("" if args.latents is None else " [M overridden to %d]" % M)
-                   + ("" if args.head_dim is None else " [d overridden to %d]" % d)
-                   + ("" if args.dtype is None else " [storage type overridden to %s]" % args.dtype)
-                   + (" [y in fp32]" if args.y_f32 else ""),
-                   "step": "flare_forward + flare_backward", "B": B, "H": H, "N": N, "M": M, "d": d,
-                   "layout": "[B,H,N,d]" if lay == "bhnd" else "[B,N,H,d]"},
-        "fwd": {"tokens_per_s": round(tokens / t_fwd, 1), "ms": round(t_fwd * 1e3, 4),
+        "scaling": "weak", "vs_baseline": None, "dtype": res["shape"]["dtype"], "data": "synthetic",
+        "config": dict(res["shape"], workload=res["workload"], step="flare_forward + flare_backward"),
+        "fwd": {"tokens_per_s": round(res["tokens"] / t_fwd, 1), "ms": round(t_fwd * 1e3, 4),
                 "hbm_frac": round(fwd_bytes / t_fwd / 1e9 / HBM_PEAK_GBS, 4),
-                "mfma_frac": round(fwd_flops / t_fwd / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                "mfma_frac": round(8.0 * B * H * N * M * d / t_fwd / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
                 "exp_frac": round(2.0 * B * H * N * M / t_fwd / 1e9 / EXP_PEAK_GOPS, 4)},
-        "ms_per_step_with_events": round(t_step_prof * 1e3, 4),
-        "roofline": roofline, "kernels": kernels,
+        "timing": res["timing"], "north_star": res["north_star"],
+        "ms_per_step_with_events": round(res["t_step_prof"] * 1e3, 4),
+        "roofline": res["roofline"], "kernels": res["kernels"],
     }
 
     if args.spectral:     # not part of the step: the eigen-analysis of the same heads, from what the forward saved
-        fwd()
         binding.spectral(dev["q"], dev["k"], lse, lse_dec, scale, layout=lay)      # warm-up
         binding.profile_enable(True)
         torch.cuda.synchronize()
@@ -267,6 +386,25 @@ def main():
                                           if n.startswith("spectral")},
                            "gram_exp_frac": round(B * H * N * M / (prof_sp["spectral_gram"][0] * 1e-3)
                                                   / 1e9 / EXP_PEAK_GOPS, 4)}
+    del dev, lse, lse_dec
+    torch.cuda.empty_cache()
+
+    if not args.no_other_configs and args.cfg == 4:
+        others = {}
+        for cfg in (1, 2, 3, 5):
+            r, _, _, _ = run_workload(cfg, args, 50, 20, False)
+            dom = r["roofline"]
+            others["cfg%d" % cfg] = {
+                "shape": r["shape"], "ms_per_step": round(r["t_step"] * 1e3, 4),
+                "tokens_per_s": round(r["tokens"] / r["t_step"], 1),
+                "step_median_ms": r["timing"]["step_warm"]["median_ms"], "step_min_ms": r["timing"]["step_warm"]["min_ms"],
+                "fwd_median_ms": r["timing"]["fwd_warm"]["median_ms"], "fwd_hbm_frac": r["north_star"]["hbm_frac"],
+                "fwd_mfma_frac": r["north_star"]["mfma_frac"], "fwd_issue_frac": r["north_star"]["issue_frac"],
+                "dominant_kernel": dom["kernel"], "dominant_bound": dom["bound"], "dominant_frac": dom["frac"],
+                "dominant_hbm_frac": dom["hbm"]["frac"] if "hbm" in dom else dom["frac"],
+                "dominant_issue_frac": dom["issue_frac"], "dominant_us": dom["mean_us"]}
+            torch.cuda.empty_cache()
+        out["other_configs"] = others
 
     if not args.no_cpu_baseline:
         from oracle import flare_oracle

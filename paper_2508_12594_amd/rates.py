@@ -93,3 +93,50 @@ def run_all(iters=20000):
                 for k in (1, 2, 3):
                     one(i, w, k, iters // 2)
     return rows
+
+
+def derive(rows):
+    """The handful of constants the roofline figures use, from the rows of run_all (2.4 GHz clocks per wave64
+    instruction and SIMD unless named otherwise)."""
+    def row(prefix, w, param=0):
+        for r in rows:
+            if r["experiment"].startswith(prefix) and r["waves_per_simd"] == w and r["param"] == param:
+                return r
+        return None
+
+    out = {}
+    copy = row("copy", 1)
+    if copy:
+        out["copy_GBps_read_plus_write"] = copy["GBps"]
+    for key, name in (("exp", "v_exp_f32"), ("fma", "v_fma_f32"), ("add", "v_add_f32"), ("pack", "v_cvt_pk_bf16_f32"),
+                      ("max3", "v_max3_f32"), ("perm", "v_perm_b32"), ("dot2", "v_dot2c_f32_bf16")):
+        r = row(name, 2)
+        if r:
+            out[key + "_clk"] = r["clk_per_instr"]
+    for key, name in (("mfma32", "v_mfma_f32_32x32x16_bf16"), ("mfma16", "v_mfma_f32_16x16x32_bf16")):
+        r = row(name, 2)
+        if r:   # the matrix pipe alone runs at a reduced clock: report both the nominal-clock figure and its own clocks
+            out[key + "_pipe_clk"] = r["clk_per_instr"]
+            out[key + "_pipe_own_clocks"] = round(r["clk_per_instr"] * r["shader_mhz"] / (NOMINAL_GHZ * 1e3), 1)
+            out[key + "_alone_shader_mhz"] = r["shader_mhz"]
+    # what one matrix instruction costs a vector stream of the same wave that alone saturates the SIMD:
+    # (duration - exponentials x their own clocks) / matrix instructions, at k exponentials per matrix instruction
+    e = row("v_exp_f32", 2)
+    for key, prefix in (("mfma32", "same wave: 1 mfma 32x32x16 + k v_exp_f32"),
+                        ("mfma16", "same wave: 1 mfma 16x16x32 + k v_exp_f32")):
+        for k in (4, 8, 16):
+            r = row(prefix, 2, k)
+            if r and e:
+                out["%s_cost_to_vector_stream_k%d" % (key, k)] = round(
+                    (r["clk_total"] - r["vector_per_simd"] * e["clk_per_instr"]) / r["matrix_per_simd"], 1)
+    for w in (2, 3):
+        m, v, b = (row("other wave: mfma 32x32x16", w, p) for p in (1, 2, 0))
+        if m and v and b:
+            out["other_wave_w%d_ms_matrix_vector_both" % w] = [m["ms"], v["ms"], b["ms"]]
+            out["other_wave_w%d_shader_mhz_matrix_vector_both" % w] = [m["shader_mhz"], v["shader_mhz"], b["shader_mhz"]]
+    for k in (1, 2, 3):
+        r = row("softmax tile", 2, k)
+        if r:
+            tiles = r["matrix_per_simd"] / (2 + k)
+            out["tile_ns_%d_score_mfma" % k] = round(r["ms"] * 1e6 / tiles, 1)
+    return out
