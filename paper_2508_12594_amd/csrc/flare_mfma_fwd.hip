@@ -572,7 +572,14 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         for (int b = 0; b < NB; ++b) S[b] = splat16(0.f);
         S[0] = qk(0, kt, k_aug(kt[0], nl), PLAIN);
 
-        for (int j = 0; j < cnt; ++j) {
+        // One token tile.  TAIL: the wave's last tile, the only one that can reach past the chunk's end (its rows
+        // beyond n1 are masked); the tiles before it carry no mask code, so that their matrix and vector
+        // instructions form one scheduling region.
+        auto tile = [&](int j, auto tail_tag) {
+            constexpr bool TAIL = decltype(tail_tag)::value;
+            // SPREAD: the score products of the next latent tile and the value products of this one are issued
+            // between the exponentials and packs of this tile instead of in one burst before and after them
+            constexpr bool SPREAD = !TAIL && D == 16 && !PACK && (PLAIN || MODE == 1);
             const int tok0 = tile_tok0(j);
             uint16_t *buf_next = vt + ((j + 1) & 1) * BUF;
             nln = load_lse(j + 1);
@@ -590,14 +597,14 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
 
             // register r of this lane holds token tok0 + 8*(r/4) + 4*hh + r%4: valid iff 8*(r/4) + r%4 < rem
             const int rem = n1 - tok0 - 4 * hh;
-            const bool partial = tok0 + 32 > n1;
+            const bool partial = TAIL && tok0 + 32 > n1;
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
                 // issue the next score product first: the next latent tile, or tile 0 of the next tokens
                 f32x16 nxt;
                 if (b + 1 < NB) nxt = qk(b + 1, kt, kt0a, PLAIN);
                 else nxt = qk(0, ktn, k_aug(ktn[0], nln), PLAIN);
-                sched_fence();
+                if constexpr (!SPREAD) sched_fence();
                 f32x16 sc = S[b];
                 if (partial) {
 #pragma unroll
@@ -632,6 +639,19 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
                     o[b][hv] = mfma(va[hv][0], p0, o[b][hv]);
                     o[b][hv] = mfma(va[hv][1], p1, o[b][hv]);
                 }
+                if constexpr (SPREAD) {
+                    FLARE_GROUP_TRANS(4);
+                    FLARE_GROUP_MFMA(1);
+                    FLARE_GROUP_TRANS(4);
+                    FLARE_GROUP_MFMA(1);
+                    FLARE_GROUP_VALU(4);
+                    if constexpr (MODE == 1) FLARE_GROUP_MFMA(1);   // the correction k-step of the next scores
+                    FLARE_GROUP_TRANS(4);
+                    FLARE_GROUP_MFMA(1);
+                    FLARE_GROUP_TRANS(4);
+                    FLARE_GROUP_VALU(4);
+                    FLARE_GROUP_MFMA(1);
+                }
                 sched_fence();
                 S[(b + 1) % NB] = nxt;
             }
@@ -648,7 +668,9 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
 #pragma unroll
                 for (int i = 0; i < LOADS; ++i) yr1[i] = yr2[i];
             }
-        }
+        };
+        for (int j = 0; j + 1 < cnt; ++j) tile(j, PlainTag<false>{});
+        tile(cnt - 1, PlainTag<true>{});
     };
     if (cnt > 0) {
         if constexpr (MODE == 0) {
