@@ -162,3 +162,22 @@ def spectral(q_h, k_h, scale):
     inv_sigma = np.where(ok, 1.0 / np.sqrt(np.where(ok, lam, 1.0)), 0.0)
     vec = np.sqrt(l_n)[:, None] * (j.T @ u) * inv_sigma[None, :]
     return lam, gram, vec
+
+
+def output_projection(y, w_out, bias=None):
+    """The linear layer that follows the mixer (Section 3.1: the head outputs are concatenated along the
+    feature dimension and passed through a final linear projection; Appendix B.2 "FLARE": a single linear layer):
+
+        out[b][n][:] = concat_h(y[b][h][n][:]) @ w_out + bias,      w_out[C][C_out], C = H * d, bias[C_out] or None
+
+    y[B,H,N,d] -> out[B,N,C_out], fp64, written as the definition (head concatenation, then one matrix product)."""
+    y = _f64(y)
+    w_out = _f64(w_out)
+    B, H, N, d = y.shape
+    if w_out.ndim != 2 or w_out.shape[0] != H * d:
+        raise ValueError("w_out must be [H*d, C_out]")
+    cat = np.ascontiguousarray(np.transpose(y, (0, 2, 1, 3))).reshape(B, N, H * d)     # [B, N, C]: head h in columns h*d ...
+    out = cat @ w_out
+    if bias is not None:
+        out = out + _f64(bias)[None, None, :]
+    return out

@@ -241,3 +241,43 @@ def test_torch_sdpa_second_opinion(oracle):
         ty = F.scaled_dot_product_attention(tk, tq.expand(2, -1, -1, -1), tz, scale=scale)
         y, z, _ = oracle.forward(q, k, v, scale)
         assert _relerr(z, tz.numpy()) < 1e-12 and _relerr(y, ty.numpy()) < 1e-12
+
+
+# ---- the output projection behind the mixer (Section 3.1, Appendix B.2) ----------------------------------------
+def test_output_projection_against_loops_and_special_weights(oracle):
+    rng = np.random.default_rng(31)
+    B, H, N, d, Co = 2, 3, 5, 4, 7
+    y = rng.standard_normal((B, H, N, d))
+    w = rng.standard_normal((H * d, Co))
+    bias = rng.standard_normal(Co)
+    out = oracle.output_projection(y, w, bias)
+    assert out.shape == (B, N, Co)
+    # brute force: every output element from its definition, loops only
+    for b in range(B):
+        for n in range(N):
+            for c in range(Co):
+                s = bias[c]
+                for h in range(H):
+                    for j in range(d):
+                        s += y[b, h, n, j] * w[h * d + j, c]
+                assert abs(out[b, n, c] - s) <= 1e-12
+    # identity weights: the projection is the concatenation of the heads, head h in columns h*d .. h*d+d-1
+    cat = oracle.output_projection(y, np.eye(H * d))
+    for h in range(H):
+        assert np.array_equal(cat[:, :, h * d:(h + 1) * d], y[:, h])
+    # a one-hot column picks one channel of one head; a transposed weight matrix would pick another
+    e = np.zeros((H * d, 1))
+    e[1 * d + 2, 0] = 1.0
+    assert np.array_equal(oracle.output_projection(y, e)[..., 0], y[:, 1, :, 2])
+    # linear in y and in w_out, affine in the bias
+    y2 = rng.standard_normal(y.shape)
+    lhs = oracle.output_projection(2.0 * y - 3.0 * y2, w)
+    rhs = 2.0 * oracle.output_projection(y, w) - 3.0 * oracle.output_projection(y2, w)
+    assert np.abs(lhs - rhs).max() <= 1e-12
+    assert np.abs(oracle.output_projection(y, w, bias) - oracle.output_projection(y, w) - bias).max() <= 1e-13
+    # the heads do not mix before the projection: zeroing head 0's rows of w_out removes exactly head 0's part
+    w0 = w.copy()
+    w0[:d] = 0.0
+    y0 = y.copy()
+    y0[:, 0] = 0.0
+    assert np.abs(oracle.output_projection(y, w0) - oracle.output_projection(y0, w)).max() <= 1e-13
