@@ -320,6 +320,9 @@ def main():
                     help="also time flare_spectral (Algorithm 1 of the paper) on the workload; reported apart")
     ap.add_argument("--y-f32", action="store_true",
                     help="the forward writes y in fp32 and the backward takes delta from it (flare_shape.y_f32)")
+    ap.add_argument("--projection", action="store_true",
+                    help="also time the forward with the output projection fused into the decode "
+                         "(flare_forward_project, [B,N,H,d] layout) against flare_forward followed by a library GEMM")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-configs", action="store_true",
                     help="skip the short runs of the other reference workloads (1, 2, 3, 5)")
@@ -386,6 +389,36 @@ def main():
                                           if n.startswith("spectral")},
                            "gram_exp_frac": round(B * H * N * M / (prof_sp["spectral_gram"][0] * 1e-3)
                                                   / 1e9 / EXP_PEAK_GOPS, 4)}
+    if args.projection:   # the block's output linear layer behind the mixer: fused into the decode, or a GEMM of its own
+        C = H * d
+        tdt = dev["k"].dtype
+        kk, vv = (dev[n] if lay == "bnhd" else dev[n].permute(0, 2, 1, 3).contiguous() for n in ("k", "v"))
+        gen = torch.Generator(device="cuda").manual_seed(1)
+        w_out = (torch.randn((C, C), generator=gen, device="cuda") / C ** 0.5).to(tdt)
+        y_p = torch.empty_like(kk)
+        out_p = torch.empty((B, N, C), dtype=tdt, device="cuda")
+        z_p = torch.empty((B, H, M, d), dtype=torch.float32, device="cuda")
+        l_p = torch.empty((B, H, M), dtype=torch.float32, device="cuda")
+        fb, _ = binding.workspace_bytes(B, H, N, M, d, binding.FLARE_BF16 if tdt == torch.bfloat16 else binding.FLARE_F16)
+        ws_p = torch.empty(max(fb, 256), dtype=torch.uint8, device="cuda")
+
+        def separate():
+            binding.forward(dev["q"], kk, vv, scale, y=y_p, z=z_p, lse_enc=l_p, workspace=ws_p, layout="bnhd")
+            torch.matmul(y_p.view(B * N, C), w_out, out=out_p.view(B * N, C))
+
+        def fused():
+            binding.forward_project(dev["q"], kk, vv, w_out, scale, out=out_p, z=z_p, lse_enc=l_p, workspace=ws_p)
+
+        def fused_keep_y():
+            binding.forward_project(dev["q"], kk, vv, w_out, scale, out=out_p, y=y_p, z=z_p, lse_enc=l_p, workspace=ws_p)
+
+        proj = {}
+        for name, fn in (("forward_then_gemm", separate), ("fused", fused), ("fused_storing_y", fused_keep_y)):
+            for _ in range(20):
+                fn()
+            proj[name] = stats(event_times(fn, 100))
+        out["projection"] = proj
+        del kk, vv, y_p, out_p, ws_p
     del dev, lse, lse_dec
     torch.cuda.empty_cache()
 

@@ -148,6 +148,31 @@ int flare_forward(const flare_shape *shape, const void *q_lat, const void *k, co
                   void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Decode fused with the linear layer that follows the mixer in a FLARE block (Section 3.1: "the outputs from all
+ * heads are concatenated along the feature dimension and passed through a final linear projection"; Appendix B.2,
+ * "FLARE": a single linear layer):
+ *     out[b][n][:] = concat_h(Y_h[b][n][:]) . w_out + bias,        C = H * d,
+ * so that y need not be written and read back between the two (it is still written when y is not NULL, e.g. for
+ * flare_backward).  One workgroup per 32-token tile with one wave per head; the sum over the heads is the
+ * contraction of one matrix product, in a fixed order (bit-reproducible).
+ *   q_lat, k, z as for flare_decode, with shape->layout = FLARE_BNHD (k is [B][N][H][d] = [B][N][C])      (in)
+ *   w_out [C][C] of the storage dtype, row = input channel h*d + j, column = output channel               (in)
+ *   bias  [C] fp32, or NULL                                                                               (in, optional)
+ *   out   [B][N][C] of the storage dtype (rounded once from fp32)                                         (out)
+ *   y     [B][N][H][d] dtype, lse_dec [B][H][N] fp32: as flare_decode writes them, or NULL              (out, optional)
+ * Supported (else FLARE_EUNSUPPORTED, nothing launched): dtype bf16 or f16, layout FLARE_BNHD, d = 16,
+ * H in {2, 4, 8}, M <= 256, N >= 8, y_f32 = 0.  The rows of Y enter the projection rounded to the storage
+ * dtype, exactly the values a separate flare_decode would have stored.  Needs no workspace.
+ * flare_forward_project = flare_encode followed by flare_decode_project on the same stream.
+ */
+int flare_decode_project(const flare_shape *shape, const void *q_lat, const void *k, const float *z,
+                         const void *w_out, const float *bias, void *out, void *y, float *lse_dec, float scale,
+                         void *stream);
+int flare_forward_project(const flare_shape *shape, const void *q_lat, const void *k, const void *v,
+                          const void *w_out, const float *bias, void *out, void *y, float *z, float *lse_enc,
+                          float *lse_dec, float scale, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * flare_forward for callers that cannot allocate and have no workspace to pass: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and kernels as
  * flare_forward, but the scratch (the encode's per-wave partial sums; with M > 256 also the decode's

@@ -21,7 +21,7 @@ VARIANT_SEPARATE_DQ = 2
 
 EXPORTS = [
     "flare_version", "flare_strerror", "flare_workspace_bytes", "flare_encode", "flare_decode",
-    "flare_forward", "flare_forward_static", "flare_backward", "flare_profile_enable", "flare_profile_kernels",
+    "flare_forward", "flare_forward_static", "flare_decode_project", "flare_forward_project", "flare_backward", "flare_profile_enable", "flare_profile_kernels",
     "flare_profile_name", "flare_profile_read", "flare_spectral_workspace_bytes", "flare_spectral",
 ]
 
@@ -58,6 +58,11 @@ def load():
     lib.flare_forward.argtypes = [sp, vp, vp, vp, vp, fp, fp, fp, ctypes.c_float, vp, ctypes.c_size_t, vp]
     lib.flare_forward_static.argtypes = [sp, vp, vp, vp, vp, fp, fp, fp, ctypes.c_float, vp]
     lib.flare_forward_static.restype = ctypes.c_int
+    lib.flare_decode_project.argtypes = [sp, vp, vp, fp, vp, fp, vp, vp, fp, ctypes.c_float, vp]
+    lib.flare_decode_project.restype = ctypes.c_int
+    lib.flare_forward_project.argtypes = [sp, vp, vp, vp, vp, fp, vp, vp, fp, fp, fp, ctypes.c_float, vp,
+                                          ctypes.c_size_t, vp]
+    lib.flare_forward_project.restype = ctypes.c_int
     lib.flare_backward.argtypes = [sp, vp, vp, vp, vp, fp, vp, fp, fp, fp, vp, vp, ctypes.c_float, vp,
                                    ctypes.c_size_t, vp]
     lib.flare_spectral_workspace_bytes.argtypes = [sp, ctypes.POINTER(ctypes.c_size_t)]
@@ -235,6 +240,35 @@ def forward(q_lat, k, v, scale, y=None, z=None, lse_enc=None, lse_dec=None, work
                                 _opt_lse_dec(lse_dec, shp),
                                 ctypes.c_float(scale), ws_p, ws_n, _stream(stream)), "flare_forward")
     return y, z, lse_enc
+
+
+def forward_project(q_lat, k, v, w_out, scale, bias=None, out=None, y=None, z=None, lse_enc=None, lse_dec=None,
+                    workspace=None, stream=None, keep_y=False):
+    """flare_forward_project: the forward with the output projection fused into the decode.  Token tensors are
+    [B,N,H,d] (layout 'bnhd'), w_out [C,C] in their dtype, bias [C] fp32 or None.  Returns (out[B,N,C], z, lse_enc);
+    y (the mixer's own output, for a backward) is written only when given or when keep_y is set."""
+    torch = _torch()
+    shp = _shape_of(q_lat, k, "bnhd", False)
+    C = shp.H * shp.d
+    if out is None:
+        out = torch.empty((shp.B, shp.N, C), dtype=k.dtype, device=k.device)
+    if y is None and keep_y:
+        y = torch.empty_like(k)
+    if z is None:
+        z = torch.empty((shp.B, shp.H, shp.M, shp.d), dtype=torch.float32, device=k.device)
+    if lse_enc is None:
+        lse_enc = torch.empty((shp.B, shp.H, shp.M), dtype=torch.float32, device=k.device)
+    ws, ws_p, ws_n = _workspace(shp, "fwd", workspace, k.device, stream)
+    _check(load().flare_forward_project(ctypes.byref(shp), _dev(q_lat, "q_lat"), _dev(k, "k"),
+                                        _dev(v, "v", k.dtype, k.shape), _dev(w_out, "w_out", k.dtype, (C, C)),
+                                        None if bias is None else _dev(bias, "bias", torch.float32, (C,)),
+                                        _dev(out, "out", k.dtype, (shp.B, shp.N, C)),
+                                        None if y is None else _dev(y, "y", k.dtype, k.shape),
+                                        _dev(z, "z", torch.float32, (shp.B, shp.H, shp.M, shp.d)),
+                                        _dev(lse_enc, "lse_enc", torch.float32, (shp.B, shp.H, shp.M)),
+                                        _opt_lse_dec(lse_dec, shp), ctypes.c_float(scale), ws_p, ws_n,
+                                        _stream(stream)), "flare_forward_project")
+    return out, z, lse_enc
 
 
 STATIC_SCRATCH_BYTES = 32 << 20   # FLARE_STATIC_SCRATCH_BYTES of include/flare.h

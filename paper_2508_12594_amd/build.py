@@ -21,7 +21,8 @@ RATES_SOURCES = {"machine_rates.hip": []}
 # are only ever compared, exponentiated or shifted by finite values), so they are compiled with
 # -fno-honor-nans: fmaxf chains then become v_max3_f32 without canonicalising moves.
 SOURCES = {"flare_api.hip": [], "flare_valu.hip": [], "flare_mfma_fwd.hip": ["-fno-honor-nans"],
-           "flare_mfma_bwd.hip": ["-fno-honor-nans"], "flare_spectral.hip": []}
+           "flare_mfma_bwd.hip": ["-fno-honor-nans"], "flare_mfma_proj.hip": ["-fno-honor-nans"],
+           "flare_spectral.hip": []}
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -41,7 +41,7 @@ const char *const kKernelNames[KID_COUNT] = {
     "encode_partial", "encode_merge", "decode", "bwd_token_stats", "bwd_prep", "bwd_dz_partial",
     "bwd_dz_merge", "bwd_dq_partial", "bwd_dq_reduce", "bwd_dkdv", "bwd_dq_partial_2exp",
     "bwd_dkdv_2exp", "decode_merge", "bwd_dkdv_finish", "spectral_gram", "spectral_reduce", "spectral_eigen",
-    "spectral_post"};
+    "spectral_post", "decode_project"};
 }  // namespace
 
 LaunchTimer::LaunchTimer(int kid, hipStream_t s) : slot(-1), stream(s)
@@ -191,6 +191,36 @@ int flare_forward_static(const flare_shape *shape, const void *q_lat, const void
     void *ws = static_scratch();
     if (!ws) return FLARE_ELAUNCH;
     return flare_forward(shape, q_lat, k, v, y, z, lse_enc, lse_dec, scale, ws, FLARE_STATIC_SCRATCH_BYTES, stream);
+}
+
+int flare_decode_project(const flare_shape *shape, const void *q_lat, const void *k, const float *z,
+                         const void *w_out, const float *bias, void *out, void *y, float *lse_dec, float scale,
+                         void *stream)
+{
+    const int rc = check_shape(shape);
+    if (rc != FLARE_OK) return rc;
+    if (!q_lat || !k || !z || !w_out || !out) return FLARE_EINVAL;
+    if (!aligned16(q_lat) || !aligned16(k) || !aligned16(z) || !aligned16(w_out) || !aligned16(bias) ||
+        !aligned16(out) || !aligned16(y) || !aligned16(lse_dec))
+        return FLARE_EALIGN;
+    if (!mfma_project_supported(*shape)) return FLARE_EUNSUPPORTED;
+    return mfma_decode_project(*shape, q_lat, k, z, w_out, bias, out, y, lse_dec, scale,
+                               static_cast<hipStream_t>(stream));
+}
+
+int flare_forward_project(const flare_shape *shape, const void *q_lat, const void *k, const void *v,
+                          const void *w_out, const float *bias, void *out, void *y, float *z, float *lse_enc,
+                          float *lse_dec, float scale, void *workspace, size_t workspace_bytes, void *stream)
+{
+    const int rc0 = check_shape(shape);
+    if (rc0 != FLARE_OK) return rc0;
+    if (!w_out || !out) return FLARE_EINVAL;
+    if (!mfma_project_supported(*shape)) return FLARE_EUNSUPPORTED;     // before anything is launched
+    if (!aligned16(w_out) || !aligned16(bias) || !aligned16(out) || !aligned16(y) || !aligned16(lse_dec))
+        return FLARE_EALIGN;
+    const int rc = flare_encode(shape, q_lat, k, v, z, lse_enc, scale, workspace, workspace_bytes, stream);
+    if (rc != FLARE_OK) return rc;
+    return flare_decode_project(shape, q_lat, k, z, w_out, bias, out, y, lse_dec, scale, stream);
 }
 
 int flare_backward(const flare_shape *shape, const void *q_lat, const void *k, const void *v,

@@ -29,6 +29,7 @@ enum KernelId {
     KID_SPECTRAL_REDUCE,
     KID_SPECTRAL_EIGEN,
     KID_SPECTRAL_POST,
+    KID_DECODE_PROJECT,
     KID_COUNT
 };
 
@@ -119,6 +120,10 @@ size_t mfma_tok_part_bytes(const flare_shape &s);
 size_t mfma_dkdv_acc_bytes(const flare_shape &s);
 int mfma_decode(const flare_shape &s, const void *q, const void *k, const float *z, void *y,
                 float *lse_dec, float scale, void *ws, hipStream_t stream);
+// decode fused with the output projection (flare_mfma_proj.hip); y and lse_dec may be NULL
+bool mfma_project_supported(const flare_shape &s);
+int mfma_decode_project(const flare_shape &s, const void *q, const void *k, const float *z, const void *w_out,
+                        const float *bias, void *out, void *y, float *lse_dec, float scale, hipStream_t stream);
 int mfma_token_stats(const flare_shape &s, const void *q, const void *k, const float *z, const void *dy,
                      float *lse_dec2, float *delta, float scale, void *ws, hipStream_t stream);
 bool mfma_dkdv_supported(const flare_shape &s);

@@ -1,0 +1,86 @@
+"""GPU parity of the decode fused with the output projection (flare_decode_project / flare_forward_project):
+out = concat_h(Y_h) . w_out + bias for token tensors in the [B,N,H,d] order (Section 3.1: the head outputs are
+concatenated and passed through a final linear projection; Appendix B.2).
+
+Three checks per case: `out` against the fp64 oracle (mixer, then oracle.output_projection) at the bar of the
+storage type; the y and lse_dec the fused kernel writes on request against a separate flare_forward, bit for
+bit (same arithmetic in the same order); and `out` against the oracle's projection of the y that was actually
+stored, which isolates the projection (fp32 sums of exact 16-bit products, one rounding of the result).
+"""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2508_12594_amd import binding, synth
+from tests._util import TOL, row_relerr, slice_relerr, to_host
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    # dtype, B, H, N, M, bias
+    ("bf16", 2, 8, 3001, 256, True),      # the million-token workload's head geometry, ragged tail
+    ("bf16", 1, 8, 64, 256, False),       # two tiles
+    ("bf16", 3, 4, 777, 64, True),
+    ("f16", 1, 8, 1500, 96, True),        # padded latent tiles, fp16 products
+    ("bf16", 2, 2, 100, 32, False),
+    ("bf16", 1, 8, 9, 200, True),         # one ragged tile, 56 padding latents
+]
+
+
+@pytest.mark.parametrize("dtype,B,H,N,M,with_bias", CASES)
+def test_fused_projection(oracle, dtype, B, H, N, M, with_bias):
+    import torch
+    print("[case] fused projection %s B=%d H=%d N=%d M=%d bias=%s" % (dtype, B, H, N, M, with_bias), flush=True)
+    sys.stdout.flush()
+    d, C = 16, 16 * H
+    inp = synth.make_inputs(2, B=B, H=H, N=N, M=M, d=d, dtype=dtype, with_dy=False, seed=9100 + N + M + H)
+    rng = np.random.Generator(np.random.PCG64(77 + N))
+    rnd = synth.bf16_round if dtype == "bf16" else (lambda a: a.astype(np.float16).astype(np.float32))
+    w = rnd((rng.standard_normal((C, C)) / np.sqrt(C)).astype(np.float32))
+    bias = rng.standard_normal(C).astype(np.float32) if with_bias else None
+    tdt = {"bf16": torch.bfloat16, "f16": torch.float16}[dtype]
+    q = torch.from_numpy(inp["q"]).to("cuda", tdt)
+    k, v = (torch.from_numpy(inp[n]).to("cuda", tdt).permute(0, 2, 1, 3).contiguous() for n in ("k", "v"))
+    wd = torch.from_numpy(w).to("cuda", tdt)
+    bd = torch.from_numpy(bias).cuda() if with_bias else None
+    scale = inp["scale"]
+    lse_dec = torch.empty((B, H, N), dtype=torch.float32, device="cuda")
+    out, z, lse = binding.forward_project(q, k, v, wd, scale, bias=bd, lse_dec=lse_dec, keep_y=False)
+    y2 = torch.empty_like(k)
+    out2, _, _ = binding.forward_project(q, k, v, wd, scale, bias=bd, y=y2)
+    lse_dec1 = torch.empty_like(lse_dec)
+    y1, z1, lse1 = binding.forward(q, k, v, scale, lse_dec=lse_dec1, layout="bnhd")
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2), "out depends on whether y is stored"
+    assert torch.equal(y2, y1), "y of the fused kernel differs from flare_forward's"
+    assert torch.equal(lse_dec, lse_dec1) and torch.equal(z, z1) and torch.equal(lse, lse1)
+
+    y_ref, _, _ = oracle.forward(inp["q"], inp["k"], inp["v"], scale)
+    out_ref = oracle.output_projection(y_ref, w, bias)
+    tol = TOL["bf16"]          # bf16 softmax weights whatever the storage type
+    out_h = to_host(out)
+    err = slice_relerr(out_h[:, None], out_ref[:, None])
+    worst = row_relerr(out_h[:, None], out_ref[:, None])
+    # the projection alone: from the stored y, only the final rounding and the order of the fp32 sums remain
+    y_stored = to_host(y2).astype(np.float64).transpose(0, 2, 1, 3)
+    out_from_y = oracle.output_projection(y_stored, w, bias)
+    err_p = slice_relerr(out_h[:, None], out_from_y[:, None])
+    print("[case]    out %.3e (worst row %.3e)  projection alone %.3e  (tol %.0e)" % (err, worst, err_p, tol), flush=True)
+    assert err <= tol and worst <= 8 * tol
+    assert err_p <= (4e-3 if dtype == "bf16" else 6e-4)      # 2^-9 (2^-12) rounding of the output, relative to its rows
+
+
+def test_fused_projection_refuses_other_shapes():
+    import ctypes
+    import torch
+    lib = binding.load()
+    x = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+    p = ctypes.c_void_p(x.data_ptr())
+    one = ctypes.c_float(1.0)
+    for shp in (binding.FlareShape(1, 8, 64, 64, 16, binding.FLARE_BF16, binding.FLARE_BHND),     # layout
+                binding.FlareShape(1, 8, 64, 64, 32, binding.FLARE_BF16, binding.FLARE_BNHD),     # d
+                binding.FlareShape(1, 3, 64, 64, 16, binding.FLARE_BF16, binding.FLARE_BNHD),     # H
+                binding.FlareShape(1, 8, 64, 512, 16, binding.FLARE_BF16, binding.FLARE_BNHD),    # M
+                binding.FlareShape(1, 8, 64, 64, 16, binding.FLARE_F32, binding.FLARE_BNHD)):     # dtype
+        assert lib.flare_decode_project(ctypes.byref(shp), p, p, p, p, None, p, None, None, one, None) == -2
