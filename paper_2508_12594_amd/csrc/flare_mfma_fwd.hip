@@ -188,7 +188,15 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
             sched_fence();
 #pragma unroll
             for (int t = 0; t < MT; ++t) {
-                if (t + 1 < MT) s_next = qk_full(t + 1);
+                // SPLIT (d = 16, q' as a hi + lo pair): the two dependent score products of tile t+1 and the two
+                // dependent value products of tile t alternate (hi, value, lo, value), so that each finds its
+                // predecessor's result ready instead of waiting for the matrix pipe to drain
+                constexpr bool SPLIT = PRE && D == 16 && !PACK;
+                if constexpr (SPLIT) {
+                    if (t + 1 < MT) s_next = mfma_s<F>(qh[t + 1][0], kt2[0], cinit);
+                } else {
+                    if (t + 1 < MT) s_next = qk_full(t + 1);
+                }
                 if constexpr (!(PRE && D == 16)) sched_fence();
                 if constexpr (!PRE) {
 #pragma unroll
@@ -196,10 +204,16 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
                 }
                 bf16x8 p0, p1;
                 exp_pack(s_cur, p0, p1);
+                if constexpr (SPLIT) {
+                    acc[0] = mfma(z_op(0, 2 * t), p0, acc[0]);
+                    if (t + 1 < MT) s_next = mfma_s<F>(ql[t + 1][0], kt[0], s_next);
+                    acc[0] = mfma(z_op(0, 2 * t + 1), p1, acc[0]);
+                } else {
 #pragma unroll
-                for (int hv = 0; hv < HV; ++hv) {
-                    acc[hv] = mfma(z_op(hv, 2 * t), p0, acc[hv]);
-                    acc[hv] = mfma(z_op(hv, 2 * t + 1), p1, acc[hv]);
+                    for (int hv = 0; hv < HV; ++hv) {
+                        acc[hv] = mfma(z_op(hv, 2 * t), p0, acc[hv]);
+                        acc[hv] = mfma(z_op(hv, 2 * t + 1), p1, acc[hv]);
+                    }
                 }
                 if constexpr (PRE && D == 16) {
                     // order within the tile: the two score products of tile t+1 (one when q' is packed) and the
@@ -216,15 +230,15 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
                         FLARE_GROUP_MFMA(1);
                     } else if (t + 1 < MT) {
                         FLARE_GROUP_TRANS(4);
-                        FLARE_GROUP_MFMA(1);
-                        FLARE_GROUP_TRANS(4);
-                        FLARE_GROUP_MFMA(1);
-                        FLARE_GROUP_VALU(4);
-                        FLARE_GROUP_TRANS(4);
-                        FLARE_GROUP_MFMA(1);
+                        FLARE_GROUP_MFMA(1);      // hi product of the next scores
                         FLARE_GROUP_TRANS(4);
                         FLARE_GROUP_VALU(4);
-                        FLARE_GROUP_MFMA(1);
+                        FLARE_GROUP_MFMA(1);      // first value product
+                        FLARE_GROUP_TRANS(4);
+                        FLARE_GROUP_MFMA(1);      // lo product
+                        FLARE_GROUP_TRANS(4);
+                        FLARE_GROUP_VALU(4);
+                        FLARE_GROUP_MFMA(1);      // second value product
                     } else {
                         FLARE_GROUP_TRANS(8);
                         FLARE_GROUP_VALU(4);
@@ -466,6 +480,14 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         if (!plain) r = mfma_s<F>(kk0a, MODE == 0 ? caug[MODE == 0 ? b : 0] : ones23, r);
         return r;
     };
+    // The same in two parts (d = 16, q' as a hi + lo pair), for the tiles that spread their matrix instructions:
+    // the correction k-step and the hi product first, the lo product on top of them later.
+    auto qk_first = [&](int b, const bf16x8 (&kk)[KS], bf16x8 kk0a, bool plain) {
+        f32x16 r = splat16(0.f);
+        if (!plain) r = mfma_s<F>(kk0a, MODE == 0 ? caug[MODE == 0 ? b : 0] : ones23, r);
+        return mfma_s<F>(kk[0], qh[b][0], r);
+    };
+    auto qk_second = [&](int b, const bf16x8 (&kk)[KS], f32x16 r) { return mfma_s<F>(kk[0], ql[b][0], r); };
     const uint32_t one0 = hh == 0 ? kOne<F> : 0u;
     const float *lb = (MODE == 1) ? lse_dec2 + (size_t)bh * N : nullptr;
     // Key operand of the correction k-step.  MODE 0: slot 0 := 1, else zero.  MODE 1: zero except
@@ -602,9 +624,14 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
             for (int b = 0; b < NB; ++b) {
                 // issue the next score product first: the next latent tile, or tile 0 of the next tokens
                 f32x16 nxt;
-                if (b + 1 < NB) nxt = qk(b + 1, kt, kt0a, PLAIN);
-                else nxt = qk(0, ktn, k_aug(ktn[0], nln), PLAIN);
-                if constexpr (!SPREAD) sched_fence();
+                if constexpr (SPREAD) {
+                    if (b + 1 < NB) nxt = qk_first(b + 1, kt, kt0a, PLAIN);
+                    else nxt = qk_first(0, ktn, k_aug(ktn[0], nln), PLAIN);
+                } else {
+                    if (b + 1 < NB) nxt = qk(b + 1, kt, kt0a, PLAIN);
+                    else nxt = qk(0, ktn, k_aug(ktn[0], nln), PLAIN);
+                    sched_fence();
+                }
                 f32x16 sc = S[b];
                 if (partial) {
 #pragma unroll
@@ -634,23 +661,29 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
                 }
                 bf16x8 p0, p1;
                 exp_pack(sc, p0, p1);
-#pragma unroll
-                for (int hv = 0; hv < HV; ++hv) {
-                    o[b][hv] = mfma(va[hv][0], p0, o[b][hv]);
-                    o[b][hv] = mfma(va[hv][1], p1, o[b][hv]);
-                }
                 if constexpr (SPREAD) {
-                    FLARE_GROUP_TRANS(4);
-                    FLARE_GROUP_MFMA(1);
-                    FLARE_GROUP_TRANS(4);
-                    FLARE_GROUP_MFMA(1);
-                    FLARE_GROUP_VALU(4);
+                    // dependent pairs alternate (hi, value, lo, value): each finds its predecessor's result ready
+                    o[b][0] = mfma(va[0][0], p0, o[b][0]);
+                    if (b + 1 < NB) nxt = qk_second(b + 1, kt, nxt);
+                    else nxt = qk_second(0, ktn, nxt);
+                    o[b][0] = mfma(va[0][1], p1, o[b][0]);
                     if constexpr (MODE == 1) FLARE_GROUP_MFMA(1);   // the correction k-step of the next scores
                     FLARE_GROUP_TRANS(4);
-                    FLARE_GROUP_MFMA(1);
+                    FLARE_GROUP_MFMA(1);      // hi product of the next scores
                     FLARE_GROUP_TRANS(4);
                     FLARE_GROUP_VALU(4);
-                    FLARE_GROUP_MFMA(1);
+                    FLARE_GROUP_MFMA(1);      // first value product
+                    FLARE_GROUP_TRANS(4);
+                    FLARE_GROUP_MFMA(1);      // lo product
+                    FLARE_GROUP_TRANS(4);
+                    FLARE_GROUP_VALU(4);
+                    FLARE_GROUP_MFMA(1);      // second value product
+                } else {
+#pragma unroll
+                    for (int hv = 0; hv < HV; ++hv) {
+                        o[b][hv] = mfma(va[hv][0], p0, o[b][hv]);
+                        o[b][hv] = mfma(va[hv][1], p1, o[b][hv]);
+                    }
                 }
                 sched_fence();
                 S[(b + 1) % NB] = nxt;

@@ -139,17 +139,19 @@ __global__ __launch_bounds__(64 * HW, 8 / HW) void decode_project_kernel(
             sched_fence();
 #pragma unroll
             for (int t = 0; t < MT; ++t) {
-                if (t + 1 < MT) s_next = qk_full(t + 1);
+                // dependent pairs alternate (hi, value, lo, value), as in decode_mfma_kernel
+                if (t + 1 < MT) s_next = mfma_s<F>(qh[t + 1][0], kt2, cinit);
                 bf16x8 p0, p1;
                 exp_pack(s_cur, p0, p1);
                 acc = mfma(zt[2 * t], p0, acc);
+                if (t + 1 < MT) s_next = mfma_s<F>(ql[t + 1][0], kt, s_next);
                 acc = mfma(zt[2 * t + 1], p1, acc);
                 if (t + 1 < MT) {
                     FLARE_GROUP_TRANS(4);
                     FLARE_GROUP_MFMA(1);
                     FLARE_GROUP_TRANS(4);
-                    FLARE_GROUP_MFMA(1);
                     FLARE_GROUP_VALU(4);
+                    FLARE_GROUP_MFMA(1);
                     FLARE_GROUP_TRANS(4);
                     FLARE_GROUP_MFMA(1);
                     FLARE_GROUP_TRANS(4);
