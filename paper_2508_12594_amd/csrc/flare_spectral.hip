@@ -6,9 +6,9 @@
 // sums (what the forward leaves behind),  J[m][n] = exp(S[m][n] - (lse_enc[m] + lse_dec[n]) / 2).
 //
 // Steps here:  G as a streaming reduction over the tokens (matrix-core kernel in flare_mfma_fwd.hip,
-// or the fp32 kernel below), a fixed-order sum of the per-chunk partials, a one-sided cyclic Jacobi
-// eigensolver in fp64 (one workgroup per (b,h); the rotations of a round act on disjoint pairs of
-// rows), and a last kernel that orders the eigenvalues and forms the decode-ready block
+// or the fp32 kernel below), a fixed-order sum of the per-chunk partials, a symmetric eigensolver in fp64
+// (one workgroup per (b,h): Householder tridiagonalisation, then the implicit QL iteration with its
+// rotations applied to the rows of Q^T), and a last kernel that orders the eigenvalues and forms the decode-ready block
 // L_M^(1/2) U Sigma^(-1) of d consecutive eigenvectors.
 #include <stdlib.h>
 
@@ -82,111 +82,333 @@ __global__ __launch_bounds__(256) void gram_reduce_kernel(const float *__restric
     if (gram) gram[i] = (float)s;
 }
 
-// ---- one-sided cyclic Jacobi eigensolver, fp64, one workgroup of 1024 threads per matrix ------------------
-// G is symmetric positive semi-definite, G = Q^T Lambda Q.  Rotating ROWS of B = G against each other
-// until they are mutually orthogonal applies an orthogonal Q from the left with (QG)(QG)^T = Q G^2 Q^T
-// diagonal, i.e. B ends as Lambda Q: row i is lambda_i times the i-th eigenvector, its length is
-// lambda_i.  Only whole rows are read and written (coalesced), nothing else is accumulated, and the
-// pairs of a round of the round-robin tournament (M' - 1 rounds per sweep, M' = M rounded up to
-// even) are disjoint: a wave per few pairs, one barrier per round.  At most 40 sweeps.
-constexpr int kJacobiThreads = 1024;
-// RR = row elements per lane (M <= 64 * RR); a wave works on PB = 16 / RR pairs at a time so that
-// the loads of all of them are in flight together.
-template <int RR>
-__global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(double *__restrict__ b_all, int M)
+// ---- symmetric eigensolver, fp64, one workgroup per matrix ------------------------------------------------
+// G = Q T Q^T by Householder reflections (T tridiagonal), then the implicit-shift QL iteration on T with its
+// plane rotations applied to the rows of Q^T; at the end row j of the matrix buffer is the j-th eigenvector and
+// lam[j] its eigenvalue (unordered).  Thread j owns column j throughout, so every pass over a matrix reads and
+// writes whole rows side by side; all sums run in a fixed order (bit-reproducible).
+//   1. for k = 0 .. M-3:  x = G[k][k+1..] (= the column below the diagonal, G is kept symmetric in full),
+//      sigma = |x|, alpha = -sign(x_0) sigma, v = x - alpha e_0, beta = 1 / (sigma (sigma + |x_0|)), so that
+//      H = I - beta v v^T maps x to alpha e_0;  p = beta G22 v,  w = p - (beta p.v / 2) v,
+//      G22 -= v w^T + w v^T  (= H G22 H);  v stays in row k for step 2, d[k] = G[k][k], e[k] = alpha.
+//   2. Q = H_0 ... H_{M-3} accumulated from the last reflector to the first (each touches only the trailing
+//      block), then transposed into the first buffer.
+//   3. QL with Wilkinson shifts on (d, e): thread 0 runs the scalar recurrence of one iteration and leaves the
+//      rotations (c_i, s_i) in LDS (1 / r from the hardware reciprocal square root and two Newton steps: no
+//      division, no square root in the chain); meanwhile one thread per column applies the rotations of the
+//      previous iteration to its column of Q^T, rows m .. l, with the rows and rotations it will need requested
+//      eight steps ahead.  The two sides swap LDS buffers at one barrier per iteration.  An off-diagonal element counts as zero at
+//      2^-52 (|d_m| + |d_m+1|) + 1e-22 |T|: the eigenvalues are wanted to absolute accuracy (the largest is 1).
+// 60 iterations without convergence for one eigenvalue: the solver stops and reports it (status != 0; the caller
+// then returns NaN eigenvalues).  The previous solver here, a one-sided Jacobi method on the rows of G, needed
+// ~2500 rounds of row-pair rotations through global memory (102 ms for eight 256 x 256 matrices).
+constexpr int kEigThreads = 1024;
+
+__device__ __forceinline__ double block_sum(double x, double *red)
 {
-    constexpr int PB = 16 / RR;
-    __shared__ unsigned long long worst;       // bits of the largest |cos| of the sweep (non-negative doubles order as integers)
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    double *bm = b_all + (size_t)blockIdx.x * M * M;
-    const int Mp = M + (M & 1), pairs = Mp / 2;
-    // Orthogonality is judged in absolute terms, inner product against the matrix's squared Frobenius
-    // norm F2: below 1e-22 F2 a pair is left alone, and the solver stops after a sweep in which no inner
-    // product exceeded 1e-18 F2.  (The eigenvalues are wanted to absolute accuracy; rows of tiny
-    // eigenvalues carry rounding noise of the large ones, which no rotation can make orthogonal in
-    // relative terms.)
-    __shared__ double fro[kJacobiThreads / 64];
-    {
-        double f = 0.0;
-        for (int i = tid; i < M * M; i += kJacobiThreads) f = fma(bm[i], bm[i], f);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) f += __shfl_xor(f, o);
-        if (lane == 0) fro[wave] = f;
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
+    __syncthreads();                 // red may still be read from the previous call
+    if (lane == 0) red[wave] = x;
+    __syncthreads();
+    double s = 0.0;
+#pragma unroll
+    for (int w = 0; w < kEigThreads / 64; ++w) s += red[w];
+    return s;
+}
+
+// 1 / sqrt(h) to full fp64 accuracy from the hardware estimate y (relative error e0 <= 2^-20, far more than it
+// needs) and one third-order step: with e = 1 - h y^2,  1/sqrt(h) = y (1 - e)^(-1/2) = y (1 + e/2 + 3 e^2/8 + O(e^3)).
+// (h > 0, normal.)
+__device__ __forceinline__ double rsqrt_full(double h)
+{
+    const double y = __builtin_amdgcn_rsq(h);
+    const double e = fma(-h * y, y, 1.0);
+    return fma(y * e, fma(0.375, e, 0.5), y);
+}
+
+// sum over rows i = first, first + RG, ... < M of mat[i][j] * vec[i], eight rows requested at a time; one fixed order
+template <int RG>
+__device__ __forceinline__ double column_dot(const double *__restrict__ mat, const double *vec, int first, int M, int j)
+{
+    double acc = 0.0;
+    int i = first;
+    for (; i + 7 * RG < M; i += 8 * RG) {
+        double x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) x[u] = mat[(size_t)(i + u * RG) * M + j];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc = fma(x[u], vec[i + u * RG], acc);
+    }
+    for (; i < M; i += RG) acc = fma(mat[(size_t)i * M + j], vec[i], acc);
+    return acc;
+}
+
+// CP: columns the workgroup can hold (256 or 512); the 1024 threads are RG = 1024 / CP groups of CP threads,
+// thread (g, j) owns column j and, in the passes over a matrix, the rows i = g (mod RG).
+template <int CP>
+__global__ __launch_bounds__(kEigThreads) void eigen_kernel(double *__restrict__ a_all, double *__restrict__ q_all,
+                                                            double *__restrict__ lam_all, int *__restrict__ status_all,
+                                                            int M)
+{
+    constexpr int RG = kEigThreads / CP;
+    __shared__ double d[CP], e[CP], v[CP], w[CP], beta[CP], part[RG][CP], red[kEigThreads / 64];
+    __shared__ double cc[2][CP], ss[2][CP];
+    __shared__ int ctl[2][4];        // per buffer: top row, bottom row, kind (0 rotate, 2 finished), failed
+    __shared__ double x_first;
+    const int tid = threadIdx.x, j = tid % CP, g = tid / CP;
+    const bool col = j < M;
+    double *a = a_all + (size_t)blockIdx.x * M * M;
+    double *qm = q_all + (size_t)blockIdx.x * M * M;
+
+    // ---- 1. tridiagonalisation ----
+    for (int k = 0; k + 2 < M; ++k) {
+        const double xj = (g == 0 && col && j > k) ? a[(size_t)k * M + j] : 0.0;
+        if (g == 0 && j == k + 1) x_first = xj;     // read by all after the barriers of the sum (row k is overwritten below)
+        const double sig2 = block_sum(xj * xj, red);
+        const double x0 = x_first;
+        if (tid == 0) d[k] = a[(size_t)k * M + k];
+        if (!(sig2 > 0.0)) {         // nothing to eliminate in this row
+            if (tid == 0) { e[k] = 0.0; beta[k] = 0.0; }
+            continue;
+        }
+        const double sigma = sqrt(sig2);
+        const double alpha = x0 >= 0.0 ? -sigma : sigma;
+        const double bt = 1.0 / (sigma * (sigma + fabs(x0)));
+        if (g == 0) {
+            const double vj = (col && j > k) ? (j == k + 1 ? xj - alpha : xj) : 0.0;
+            v[j] = vj;
+            if (col && j > k) a[(size_t)k * M + j] = vj;
+        }
+        if (tid == 0) { e[k] = alpha; beta[k] = bt; }
+        __syncthreads();
+        {   // p = beta G22 v: each row group sums its rows, group 0 adds the groups in order
+            double pj = 0.0;
+            if (col && j > k) pj = column_dot<RG>(a, v, k + 1 + g, M, j);
+            part[g][j] = pj;
+        }
+        __syncthreads();
+        double pj = 0.0, vj = 0.0;
+        if (g == 0) {
+#pragma unroll
+            for (int r = 0; r < RG; ++r) pj += part[r][j];
+            pj *= bt;
+            vj = v[j];
+        }
+        const double kk = 0.5 * bt * block_sum(g == 0 ? pj * vj : 0.0, red);
+        if (g == 0) w[j] = pj - kk * vj;
+        __syncthreads();
+        if (col && j > k) {
+            const double wj = w[j], vv = v[j];
+            int i = k + 1 + g;
+            for (; i + 7 * RG < M; i += 8 * RG) {      // eight rows requested before the first is used
+                double x[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) x[u] = a[(size_t)(i + u * RG) * M + j];
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    a[(size_t)(i + u * RG) * M + j] = x[u] - v[i + u * RG] * wj - w[i + u * RG] * vv;
+            }
+            for (; i < M; i += RG) {
+                const size_t at = (size_t)i * M + j;
+                a[at] = a[at] - v[i] * wj - w[i] * vv;
+            }
+        }
         __syncthreads();
     }
-    double tiny = 0.0;
-    for (int w = 0; w < kJacobiThreads / 64; ++w) tiny += fro[w];
-    const double f2 = tiny;
-    tiny *= 1e-22;
-    for (int sweep = 0; sweep < 40; ++sweep) {
-        if (tid == 0) worst = 0ull;
+    if (tid == 0) {
+        if (M >= 2) {
+            d[M - 2] = a[(size_t)(M - 2) * M + M - 2];
+            e[M - 2] = a[(size_t)(M - 1) * M + M - 2];
+        }
+        d[M - 1] = a[(size_t)(M - 1) * M + M - 1];
+        e[M - 1] = 0.0;
+    }
+    // ---- 2. Q = H_0 ... H_{M-3}, then its transpose into the first buffer ----
+    if (col)
+        for (int i = g; i < M; i += RG) qm[(size_t)i * M + j] = (i == j) ? 1.0 : 0.0;
+    __syncthreads();
+    for (int k = M - 3; k >= 0; --k) {
+        const double bt = beta[k];
+        if (bt == 0.0) continue;     // uniform: beta is in LDS
+        if (g == 0) v[j] = (col && j > k) ? a[(size_t)k * M + j] : 0.0;
         __syncthreads();
-        for (int round = 0; round < Mp - 1; ++round) {
-            for (int i0 = wave * PB; i0 < pairs; i0 += (kJacobiThreads / 64) * PB) {
-                double x[PB][RR], y[PB][RR];
-                int pp[PB], qq[PB];
+        {
+            double t = 0.0;
+            if (col && j > k) t = column_dot<RG>(qm, v, k + 1 + g, M, j);
+            part[g][j] = t;
+        }
+        __syncthreads();
+        if (col && j > k) {
+            double t = 0.0;
 #pragma unroll
-                for (int b = 0; b < PB; ++b) {
-                    const int i = i0 + b;
-                    int p = (i == 0) ? Mp - 1 : (round + i) % (Mp - 1);
-                    int q = (i == 0) ? round : (round - i + Mp - 1) % (Mp - 1);
-                    if (p > q) { const int t = p; p = q; q = t; }
-                    const bool live = i < pairs && q < M;      // q == M: the padding index of an odd M
-                    pp[b] = live ? p : -1;
-                    qq[b] = q;
+            for (int r = 0; r < RG; ++r) t += part[r][j];
+            t *= bt;
+            int i = k + 1 + g;
+            for (; i + 7 * RG < M; i += 8 * RG) {
+                double x[8];
 #pragma unroll
-                    for (int t = 0; t < RR; ++t) {
-                        const int j = lane + 64 * t;
-                        x[b][t] = (live && j < M) ? bm[(size_t)p * M + j] : 0.0;
-                        y[b][t] = (live && j < M) ? bm[(size_t)q * M + j] : 0.0;
+                for (int u = 0; u < 8; ++u) x[u] = qm[(size_t)(i + u * RG) * M + j];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) qm[(size_t)(i + u * RG) * M + j] = x[u] - v[i + u * RG] * t;
+            }
+            for (; i < M; i += RG) qm[(size_t)i * M + j] -= v[i] * t;
+        }
+        __syncthreads();
+    }
+    if (col)
+        for (int i = g; i < M; i += RG) a[(size_t)j * M + i] = qm[(size_t)i * M + j];
+    __syncthreads();
+
+    // ---- 3. implicit QL; rotations act on rows i, i+1 of a = Q^T ----
+    // Thread 0 (wave 0) produces the rotations of iteration n+1 into one LDS buffer while threads 64 .. 64 + M - 1
+    // apply those of iteration n from the other: both between the same two barriers, no waiting on flags.
+    double anorm = 0.0;
+    for (int i = 0; i < M; ++i) anorm = fmax(anorm, fabs(d[i]) + fabs(e[i]));
+    const double floor_abs = 1e-22 * anorm;
+    int l = 0, iter = 0;             // producer state (the first wave, uniform over its lanes)
+    // One step of the producer: the next QL iteration (or the end), written into buffer `bf`.  Called by the whole
+    // first wave: its lanes look for the next negligible off-diagonal element 64 at a time; lane 0 alone runs
+    // the recurrence.
+    auto produce = [&](int bf) {
+        const int lane = tid;        // tid < 64 here
+        for (;;) {
+            if (l >= M) {
+                if (lane == 0) { ctl[bf][2] = 2; ctl[bf][3] = 0; }
+                return;
+            }
+            int m = l;
+            for (;;) {
+                const int idx = m + lane;
+                bool small = idx >= M - 1;
+                if (!small) small = fabs(e[idx]) <= 2.220446049250313e-16 * (fabs(d[idx]) + fabs(d[idx + 1])) + floor_abs;
+                const unsigned long long mask = __ballot(small);
+                if (mask != 0ull) { m += __ffsll((long long)mask) - 1; break; }
+                m += 64;
+            }
+            if (m == l) { ++l; iter = 0; continue; }             // eigenvalue l has converged
+            if (iter == 60) {
+                if (lane == 0) { ctl[bf][2] = 2; ctl[bf][3] = 1; }
+                return;
+            }
+            ++iter;
+            if (lane == 0) {
+                double gg = (d[l + 1] - d[l]) / (2.0 * e[l]);
+                double r = sqrt(gg * gg + 1.0);
+                gg = d[m] - d[l] + e[l] / (gg + (gg >= 0.0 ? r : -r));
+                double s = 1.0, c = 1.0, p = 0.0;
+                int i = m - 1;
+                bool under = false;
+                double ei = e[i], di = d[i], di1 = d[i + 1];
+                for (; i >= l; --i) {
+                    // the next step's elements are requested now and only looked at when this step is done
+                    const int ip = i > 0 ? i - 1 : 0;
+                    const double en = e[ip], dn = d[ip];
+                    const double f = s * ei, b = c * ei;
+                    const double h = fma(f, f, gg * gg);
+                    if (!(h > 1e-290)) {             // the rotation is undefined: deflate here and start over
+                        e[i + 1] = 0.0;
+                        d[i + 1] = di1 - p;
+                        e[m] = 0.0;
+                        under = true;
+                        break;
                     }
+                    // s = f / r0, c = g / r0 with r0 = sqrt(h); everything that does not need 1 / r0 is formed
+                    // while it is computed, so that two operations separate it from the next step's g
+                    const double g1 = di1 - p;
+                    const double wr = fma(di - g1, f, 2.0 * gg * b);     // = r0 ((d_i - g1) s + 2 c b)
+                    const double ri = rsqrt_full(h);
+                    e[i + 1] = h * ri;
+                    s = f * ri;
+                    c = gg * ri;
+                    r = wr * ri;
+                    p = s * r;
+                    d[i + 1] = g1 + p;
+                    gg = fma(c, r, -b);
+                    cc[bf][i] = c;
+                    ss[bf][i] = s;
+                    di1 = di;
+                    di = dn;
+                    ei = en;
                 }
+                if (!under) {
+                    d[l] -= p;
+                    e[l] = gg;
+                    e[m] = 0.0;
+                }
+                ctl[bf][0] = m;                      // rotations exist for rows m-1 down to the bottom row
+                ctl[bf][1] = under ? i + 1 : l;
+                ctl[bf][2] = 0;
+                ctl[bf][3] = 0;
+            }
+            return;
+        }
+    };
+    if (tid < 64) produce(0);
+    __syncthreads();
+    bool failed = false;
+    for (int n = 0;; ++n) {
+        const int bf = n & 1;
+        const int top = ctl[bf][0], bot = ctl[bf][1], kind = ctl[bf][2];
+        if (kind == 2) { failed = ctl[bf][3] != 0; break; }
+        if (tid < 64) {
+            produce(bf ^ 1);
+        } else if (tid < 64 + M && top > bot) {
+            const int jc = tid - 64;
+            // rows top-1 .. bot, each rotated against the row above it; row top's value is carried down.  Eight
+            // rows and their rotations are in flight at any time; the loop body has no branches (a request past
+            // the bottom row is clamped to it and its result ignored), so that nothing waits for a request it
+            // does not need yet.
+            double hi = a[(size_t)top * M + jc];
+            double buf[8], cb[8], sb[8];
+            int i = top - 1;
 #pragma unroll
-                for (int b = 0; b < PB; ++b) {
-                    if (pp[b] < 0) continue;
-                    double al = 0.0, be = 0.0, ga = 0.0;
+            for (int u = 0; u < 8; ++u) {
+                const int r = max(i - u, bot);
+                buf[u] = a[(size_t)r * M + jc];
+                cb[u] = cc[bf][r];
+                sb[u] = ss[bf][r];
+            }
+            while (i - 7 >= bot) {
 #pragma unroll
-                    for (int t = 0; t < RR; ++t) {
-                        al = fma(x[b][t], x[b][t], al);
-                        be = fma(y[b][t], y[b][t], be);
-                        ga = fma(x[b][t], y[b][t], ga);
-                    }
+                for (int u = 0; u < 8; ++u) {
+                    const int r = i - u, rn = max(r - 8, bot);
+                    const double lo = buf[u], c = cb[u], s = sb[u];
+                    buf[u] = a[(size_t)rn * M + jc];
+                    cb[u] = cc[bf][rn];
+                    sb[u] = ss[bf][rn];
+                    a[(size_t)(r + 1) * M + jc] = fma(s, lo, c * hi);
+                    hi = fma(c, lo, -s * hi);
+                }
+                i -= 8;
+            }
 #pragma unroll
-                    for (int o = 32; o > 0; o >>= 1) {
-                        al += __shfl_xor(al, o);
-                        be += __shfl_xor(be, o);
-                        ga += __shfl_xor(ga, o);
-                    }
-                    const double den = sqrt(al * be);
-                    if (!(fabs(ga) > tiny) || !(fabs(ga) > 1e-15 * den)) continue;   // orthogonal already
-                    if (lane == 0) atomicMax(&worst, (unsigned long long)__double_as_longlong(fabs(ga)));
-                    const double zeta = (be - al) / (2.0 * ga);
-                    const double t = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
-                    const double c = 1.0 / sqrt(1.0 + t * t), sn = c * t;
-#pragma unroll
-                    for (int r = 0; r < RR; ++r) {
-                        const int j = lane + 64 * r;
-                        if (j < M) {
-                            bm[(size_t)pp[b] * M + j] = c * x[b][r] - sn * y[b][r];
-                            bm[(size_t)qq[b] * M + j] = sn * x[b][r] + c * y[b][r];
-                        }
-                    }
+            for (int u = 0; u < 7; ++u) {      // the last rows, fewer than eight
+                const int r = i - u;
+                if (r >= bot) {
+                    a[(size_t)(r + 1) * M + jc] = fma(sb[u], buf[u], cb[u] * hi);
+                    hi = fma(cb[u], buf[u], -sb[u] * hi);
                 }
             }
-            __syncthreads();
+            a[(size_t)bot * M + jc] = hi;
         }
-        const double w = __longlong_as_double((long long)worst);
         __syncthreads();
-        if (!(w > 1e-18 * f2)) break;
     }
+    if (tid < M) lam_all[(size_t)blockIdx.x * M + tid] = d[tid];
+    if (tid == 0) status_all[blockIdx.x] = failed ? 1 : 0;
 }
 
 // ---- eigenvalues in descending order, and the decode-ready block of d eigenvectors -------------------
-// Row j of B is lambda_j q_j.  rank of eigenvalue j = how many are larger (ties broken by index): a
-// stable order without a sort.
+// Row j of the matrix buffer is the unit eigenvector q_j, lam_in[j] its eigenvalue (clamped at zero: G is
+// positive semi-definite).  rank of eigenvalue j = how many are larger (ties broken by index): a stable order
+// without a sort.
 // zvec[b*h][m][c] = exp(-lse_enc[m] / 2) * q_j[m] / sqrt(lambda_j),  j = the (first + c)-th largest;
 // zero where that index is beyond M or the eigenvalue is below 1e-12 of the largest.
+// A solver that did not converge (status != 0) gives NaN eigenvalues and a zero block.
 __global__ __launch_bounds__(256) void spectral_post_kernel(const double *__restrict__ b_all,
+                                                            const double *__restrict__ lam_in,
+                                                            const int *__restrict__ status,
                                                             const float *__restrict__ lse_enc,
                                                             float *__restrict__ evals, float *__restrict__ zvec, int M,
                                                             int d, int first)
@@ -195,28 +417,24 @@ __global__ __launch_bounds__(256) void spectral_post_kernel(const double *__rest
     int *row_of = reinterpret_cast<int *>(lam + M);
     const int bh = blockIdx.x, tid = threadIdx.x;
     const double *bm = b_all + (size_t)bh * M * M;
-    for (int j = tid; j < M; j += 256) {
-        double s = 0.0;
-        for (int i = 0; i < M; ++i) s = fma(bm[(size_t)j * M + i], bm[(size_t)j * M + i], s);
-        lam[j] = sqrt(s);
-    }
+    const bool bad = status[bh] != 0;
+    for (int j = tid; j < M; j += 256) lam[j] = fmax(lam_in[(size_t)bh * M + j], 0.0);
     __syncthreads();
     for (int j = tid; j < M; j += 256) {
         int rank = 0;
         for (int i = 0; i < M; ++i) rank += (lam[i] > lam[j] || (lam[i] == lam[j] && i < j)) ? 1 : 0;
         row_of[rank] = j;
-        evals[(size_t)bh * M + rank] = (float)lam[j];
+        evals[(size_t)bh * M + rank] = bad ? __builtin_nanf("") : (float)lam[j];
     }
     __syncthreads();
     const double top = lam[row_of[0]];
     for (int w = tid; w < M * d; w += 256) {
         const int m = w / d, c = w % d, rk = first + c;
         float out = 0.f;
-        if (rk < M) {
+        if (rk < M && !bad) {
             const int j = row_of[rk];
             if (lam[j] > 1e-12 * top && lam[j] > 1e-300)
-                out = (float)(exp(-0.5 * (double)lse_enc[(size_t)bh * M + m]) * bm[(size_t)j * M + m] /
-                              (lam[j] * sqrt(lam[j])));
+                out = (float)(exp(-0.5 * (double)lse_enc[(size_t)bh * M + m]) * bm[(size_t)j * M + m] / sqrt(lam[j]));
         }
         zvec[((size_t)bh * M + m) * d + c] = out;
     }
@@ -235,7 +453,8 @@ size_t spectral_bytes(const flare_shape &s)
 {
     const size_t BH = (size_t)s.B * s.H, mm = (size_t)s.M * s.M;
     const Split sp = spectral_split(s);
-    return align256(BH * sp.chunks * mm * 4) + align256(BH * mm * 8);
+    // partial G's; two fp64 matrices per (b,h) (G, then Q^T; Q); eigenvalues; solver status
+    return align256(BH * sp.chunks * mm * 4) + 2 * align256(BH * mm * 8) + align256(BH * s.M * 8) + align256(BH * 4);
 }
 
 int spectral_run(const flare_shape &s, const void *q, const void *k, const float *lse_enc, const float *lse_dec,
@@ -246,6 +465,9 @@ int spectral_run(const flare_shape &s, const void *q, const void *k, const float
     char *base = static_cast<char *>(ws);
     float *g_part = reinterpret_cast<float *>(base);
     double *a = reinterpret_cast<double *>(base + align256(BH * sp.chunks * mm * 4));
+    double *qbuf = reinterpret_cast<double *>(reinterpret_cast<char *>(a) + align256(BH * mm * 8));
+    double *lam = reinterpret_cast<double *>(reinterpret_cast<char *>(qbuf) + align256(BH * mm * 8));
+    int *status = reinterpret_cast<int *>(reinterpret_cast<char *>(lam) + align256(BH * s.M * 8));
     if (mfma_gram_supported(s)) {
         const int rc = mfma_gram_partial(s, sp, q, k, lse_enc, lse_dec, g_part, scale, stream);
         if (rc != FLARE_OK) return rc;
@@ -275,15 +497,14 @@ int spectral_run(const flare_shape &s, const void *q, const void *k, const float
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     {
         LaunchTimer t(KID_SPECTRAL_EIGEN, stream);
-        if (s.M <= 64) jacobi_kernel<1><<<(unsigned)BH, kJacobiThreads, 0, stream>>>(a, s.M);
-        else if (s.M <= 128) jacobi_kernel<2><<<(unsigned)BH, kJacobiThreads, 0, stream>>>(a, s.M);
-        else if (s.M <= 256) jacobi_kernel<4><<<(unsigned)BH, kJacobiThreads, 0, stream>>>(a, s.M);
-        else jacobi_kernel<8><<<(unsigned)BH, kJacobiThreads, 0, stream>>>(a, s.M);
+        if (s.M <= 256) eigen_kernel<256><<<(unsigned)BH, kEigThreads, 0, stream>>>(a, qbuf, lam, status, s.M);
+        else eigen_kernel<512><<<(unsigned)BH, kEigThreads, 0, stream>>>(a, qbuf, lam, status, s.M);
     }
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     {
         LaunchTimer t(KID_SPECTRAL_POST, stream);
-        spectral_post_kernel<<<(unsigned)BH, 256, s.M * 12, stream>>>(a, lse_enc, evals, zvec, s.M, s.d, first);
+        spectral_post_kernel<<<(unsigned)BH, 256, s.M * 12, stream>>>(a, lam, status, lse_enc, evals, zvec, s.M, s.d,
+                                                                      first);
     }
     return check_launch();
 }
