@@ -22,6 +22,7 @@ enum Experiment {
     E_SAME32_EXP, E_SAME32_FMA, E_SAME16_EXP, E_EXP_FMA,
     E_OTHER32, E_OTHER16,
     E_TILE,
+    E_F64,
     E_COUNT
 };
 const char *const kNames[E_COUNT] = {
@@ -32,7 +33,10 @@ const char *const kNames[E_COUNT] = {
     "same wave: 1 mfma 16x16x32 + k v_exp_f32", "same wave: 1 v_exp_f32 + k v_fma_f32",
     "other wave: mfma 32x32x16 wave beside exp+pack waves (param 0 both, 1 matrix only, 2 vector only)",
     "other wave: mfma 16x16x32 wave beside exp+pack waves (param 0 both, 1 matrix only, 2 vector only)",
-    "softmax tile: k score mfma -> 16 exp -> 8 pack -> 2 value mfma, next tile's scores issued first"};
+    "softmax tile: k score mfma -> 16 exp -> 8 pack -> 2 value mfma, next tile's scores issued first",
+    "fp64: param % 8 = 0 v_fma_f64, 1 v_mul_f64, 2 v_add_f64, 3 v_rsq_f64, 4 v_rcp_f64; param < 8 one dependent chain "
+    "per wave (latency), 8 <= param < 16 eight independent chains (issue rate), param >= 16 as param - 16 on eight "
+    "workgroups only"};
 
 constexpr size_t kScratch = (size_t)1 << 30;   // copy experiment: 512 MiB in, 512 MiB out
 constexpr int kClockSlots = 4;                 // uint64 per launch: shader and real-time ticks, start and end
@@ -302,6 +306,36 @@ __global__ __launch_bounds__(1024) void tile_kernel(float *__restrict__ sink, in
     if (s == 12345.678f) sink[0] = s;
 }
 
+// ---- fp64: NCH independent chains per wave of one instruction kind (NCH = 1: its dependent latency) ----
+template <int OP, int NCH>
+__global__ __launch_bounds__(1024) void f64_kernel(float *__restrict__ sink, int iters, uint64_t *clk)
+{
+    double x[NCH];
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) x[i] = 1.0 + 1e-3 * (double)(threadIdx.x % 17) + 0.01 * (double)i;
+    const double ya = 0.999 - 1e-6 * (double)threadIdx.x, yb = 1e-3;
+    {
+        Clocks c(clk);
+        for (int it = 0; it < iters; it += 8) {
+#pragma unroll
+            for (int rep = 0; rep < 8; ++rep)
+#pragma unroll
+                for (int i = 0; i < NCH; ++i) {
+                    if constexpr (OP == 0) x[i] = __builtin_fma(x[i], ya, yb);
+                    else if constexpr (OP == 1) x[i] = x[i] * ya;
+                    else if constexpr (OP == 2) x[i] = x[i] + yb;
+                    else if constexpr (OP == 3) x[i] = __builtin_amdgcn_rsq(x[i]);
+                    else x[i] = __builtin_amdgcn_rcp(x[i]);
+                }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    double s = 0.0;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) s += x[i];
+    if (s == 12345.678) sink[0] = (float)s;
+}
+
 int launch(int threads, int ex, int k, int iters, int cus, float *sink, uint64_t *clk, hipStream_t st, double *vec, double *mat)
 {
     const double w = threads / 256;   // waves per SIMD
@@ -359,6 +393,25 @@ int launch(int threads, int ex, int k, int iters, int cus, float *sink, uint64_t
             *vec = 24.0 * iters * w;
             *mat = (2.0 + k) * iters * w;
             return 0;
+        case E_F64: {
+            const int wgs = k >= 16 ? 8 : cus;     // param >= 16: eight workgroups only (a nearly idle chip)
+            k %= 16;
+#define F64(OP)                                                                              \
+    if (k >= 8) f64_kernel<OP, 8><<<wgs, threads, 0, st>>>(sink, iters, clk);              \
+    else f64_kernel<OP, 1><<<wgs, threads, 0, st>>>(sink, iters, clk);                     \
+    break
+            switch (k % 8) {
+                case 0: F64(0);
+                case 1: F64(1);
+                case 2: F64(2);
+                case 3: F64(3);
+                case 4: F64(4);
+                default: return -1;
+            }
+#undef F64
+            *vec = (k >= 8 ? 8.0 : 1.0) * ((iters + 7) / 8 * 8) * w;
+            return 0;
+        }
         default: return -1;
     }
 #undef VEC

@@ -92,6 +92,9 @@ def run_all(iters=20000):
             for w in (1, 2, 3):
                 for k in (1, 2, 3):
                     one(i, w, k, iters // 2)
+        elif n.startswith("fp64"):
+            for param in (0, 1, 2, 3, 4, 8, 9, 10, 11, 12, 16, 19, 24):
+                one(i, 1, param, iters)
     return rows
 
 
