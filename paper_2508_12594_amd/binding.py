@@ -327,6 +327,8 @@ def spectral(q_lat, k, lse_enc, lse_dec, scale, first=0, want_gram=False, stream
     need = ctypes.c_size_t(0)
     _check(load().flare_spectral_workspace_bytes(ctypes.byref(shp), ctypes.byref(need)), "flare_spectral_workspace_bytes")
     ws = torch.empty(max(int(need.value), 256), dtype=torch.uint8, device=k.device)
+    if stream is not None and stream != torch.cuda.current_stream():
+        ws.record_stream(stream)          # a temporary block used by kernels on another stream (see _workspace)
     ev = torch.empty((shp.B, shp.H, shp.M), dtype=torch.float32, device=k.device)
     zv = torch.empty((shp.B, shp.H, shp.M, shp.d), dtype=torch.float32, device=k.device)
     gram = torch.empty((shp.B, shp.H, shp.M, shp.M), dtype=torch.float32, device=k.device) if want_gram else None

@@ -88,3 +88,37 @@ def test_spectral_later_eigenvectors_and_rejections(oracle):
     with pytest.raises(binding.FlareError):
         binding.spectral(devb["q"], devb["k"], torch.zeros((1, 1, 1024), device="cuda"),
                          torch.zeros((1, 1, 64), device="cuda"), 1.0)
+
+
+def test_spectral_million_tokens(oracle):
+    """Workload 4 at full size (8 heads, 256 latents, 10^6 tokens), as bench.py --spectral runs it.  The oracle's
+    Algorithm 1 on two heads: the companion matrix and all 256 eigenvalues element by element; the first 16
+    eigenvectors by what is unique about them, W x = lambda x, with W x = decode(encode(x)) from the oracle's
+    forward (a dense W has 10^12 entries), and the first one constant."""
+    import torch
+    inp = synth.make_inputs(4, with_dy=False)
+    B, H, N, M, d = (inp[x] for x in "BHNMd")
+    scale = inp["scale"]
+    _say("spectral at full size: %s" % synth.describe(4))
+    dev = to_device(inp)
+    lse_dec = torch.empty((B, H, N), dtype=torch.float32, device="cuda")
+    _, _, lse_enc = binding.forward(dev["q"], dev["k"], dev["v"], scale, lse_dec=lse_dec)
+    ev, zv, gram = binding.spectral(dev["q"], dev["k"], lse_enc, lse_dec, scale, want_gram=True)
+    y32 = binding.decode(dev["q"], dev["k"], zv, scale)
+    torch.cuda.synchronize()
+    ev_h, gram_h = to_host(ev), to_host(gram)
+    assert np.all(np.isfinite(ev_h)) and np.all(np.diff(ev_h, axis=-1) <= 0)
+    assert np.abs(ev_h[..., 0] - 1.0).max() <= 3e-3
+    for h in (0, 5):
+        _say("   oracle on head %d" % h)
+        lam, g_ref, _ = oracle.spectral(inp["q"][h], inp["k"][0, h], scale)
+        e_g = np.linalg.norm(gram_h[0, h] - g_ref) / np.linalg.norm(g_ref)
+        e_l = np.abs(ev_h[0, h] - lam).max()
+        x = to_host(y32[0, h]).astype(np.float64)                         # [N, d]: eigenvectors 0 .. d-1
+        wx, _, _ = oracle.forward(inp["q"][h:h + 1], inp["k"][:, h:h + 1], x[None, None], scale)
+        res = np.linalg.norm(wx[0, 0] - x * lam[None, :d], axis=0) / np.linalg.norm(x, axis=0)
+        flat = np.ptp(x[:, 0]) / abs(x[:, 0]).max()
+        _say("   head %d: G %.2e  eigenvalues %.2e  residuals max %.2e  first vector spread %.2e  (lambda_16 %.2e)"
+             % (h, e_g, e_l, res.max(), flat, lam[d - 1]))
+        assert e_g <= 3e-3 and e_l <= 3e-3
+        assert res.max() <= 1e-2 and flat <= 1e-2
