@@ -638,14 +638,27 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
 #pragma unroll
         for (int s = 0; s < KS; ++s) { vt[s] = v_operand(vt[s]); gt[s] = to_bf16(gt[s]); }
     }
+    // The token statistics (lse_dec2, delta) are requested one tile ahead like the rows: a request made where its
+    // value is needed would also wait for the rows requested just before it (loads complete in order), and every
+    // token tile would begin with a full memory latency.
+    float lse_next = 0.f, delta_next = 0.f;
+    if (tile < tiles) {
+        const size_t row0 = (size_t)min(tile * 32 + l32, N - 1);
+        lse_next = lb[row0];
+        delta_next = db[row0];
+    }
     for (; tile < tiles; tile += stride) {
         const int n = tile * 32 + l32;
         const int tn = (tile + stride < tiles) ? tile + stride : tile;
         load_cols(kb, tn, ktn, true);
         load_cols(vb, tn, vtn, false);
         load_cols(gb, tn, gtn, ZPACK);
-        const size_t row = (size_t)min(n, N - 1);
-        const float nld = -lb[row] * ld_mul, dl = db[row];
+        const float nld = -lse_next * ld_mul, dl = delta_next;
+        {
+            const size_t rown = (size_t)min(tn * 32 + l32, N - 1);
+            lse_next = lb[rown];
+            delta_next = db[rown];
+        }
         const float wn = ONE ? fast_exp2(kap + nld) : 0.f;
 
         u32x4 wb;

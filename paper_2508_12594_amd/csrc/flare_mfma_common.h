@@ -37,6 +37,10 @@
 namespace flare {
 namespace {
 
+// a compile-time flag passed to a generic lambda (decltype(tag)::value)
+template <bool B>
+struct PlainTag { static constexpr bool value = B; };
+
 typedef uint16_t bf16_t;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));

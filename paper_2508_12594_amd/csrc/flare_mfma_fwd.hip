@@ -6,9 +6,6 @@
 namespace flare {
 namespace {
 
-template <bool B>
-struct PlainTag { static constexpr bool value = B; };
-
 // ============================================================================================
 // Decode.  One wave owns 32 tokens at a time and all M latents.  One pass over the latent tiles:
 //   the stabiliser b of a token is its largest score (hi terms only) among the FIRST 32 latents: a
@@ -118,11 +115,42 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
     const int stride = gridDim.x * 4;
     int tile = gp.x * 4 + wave;
     bf16x8 kt[KS], ktn[KS];
+    // hi part of the scores of latent tile t against the keys kk, without a stabiliser
+    auto qk_hi = [&](int t, const bf16x8 (&kk)[KS]) {
+        f32x16 r = splat16(0.f);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) r = mfma_s<F>(qh[t][ks], kk[ks], r);
+        return r;
+    };
+    // The stabiliser of a token tile is the maximum of the hi product of its FIRST latent tile (any value is exact
+    // as long as no weight overflows and the largest does not underflow; this one is <= the true maximum).  The
+    // scores of that latent tile are the same product minus the stabiliser, plus the lo product.
+    auto tile_max = [&](const f32x16 &hi) {
+        const float m = max16(hi, -INFINITY);
+        return fmaxf(m, __shfl_xor(m, 32));
+    };
+    auto first_scores = [&](f32x16 hi, float m, const bf16x8 (&kk)[KS]) {
+        if constexpr (PRE) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) hi[i] -= m;
+            if constexpr (!PACK) {
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) hi = mfma_s<F>(ql[0][ks], kk[ks], hi);
+            }
+        }
+        return hi;
+    };
+    // carried from one token tile of the wave to its next: the keys, the stabiliser, the scores of latent tile 0
+    float mx = 0.f;
+    f32x16 s_cur0 = splat16(0.f);
     if (tile < tiles) {
         const int nld = min(tile * 32 + l32, N - 1);
 #pragma unroll
         for (int s = 0; s < KS; ++s)
             kt[s] = as_bf16x8(row8_bf16<DR>(kb + tok_off(ts, nld), PACK ? 0 : (D / 2) * hh + 8 * s));
+        const f32x16 hi = qk_hi(0, kt);
+        mx = tile_max(hi);
+        s_cur0 = first_scores(hi, mx, kt);
     }
     for (; tile < tiles; tile += stride) {
         const int n = tile * 32 + l32;
@@ -133,15 +161,7 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
             for (int s = 0; s < KS; ++s)
                 ktn[s] = as_bf16x8(row8_bf16<DR>(kb + tok_off(ts, nld), PACK ? 0 : (D / 2) * hh + 8 * s));
         }
-        auto qk_hi = [&](int t) {
-            f32x16 r = splat16(0.f);
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) r = mfma_s<F>(qh[t][ks], kt[ks], r);
-            return r;
-        };
-
-        // The hi products behind the stabiliser are recomputed in the main sweep rather than kept; an
-        // opaque copy of the keys stops the compiler from merging the two.
+        // An opaque copy of the keys for the hi products, so that the compiler keeps them apart from the lo ones.
         bf16x8 kt2[KS];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
@@ -150,26 +170,14 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
             kt2[ks] = as_bf16x8(w);
         }
         f32x16 acc[HV];
-        float mx, b2;
-        for (bool exact = false;; exact = true) {
-            // stabiliser: the maximum over the first latent tile, or (second attempt) over all of them
-            mx = -INFINITY;
-            f32x16 s_cur = qk_hi(0), s_next;
-            if (!exact) {
-                mx = max16(s_cur, mx);
-            } else {
-#pragma unroll
-                for (int t = 0; t < MT; ++t) {
-                    if (t + 1 < MT) s_next = qk_hi(t + 1);
-                    sched_fence();
-                    mx = max16(s_cur, mx);
-                    s_cur = s_next;
-                }
-            }
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            // -b as the starting value of the score accumulators (PRE), or folded into the fma
-            const f32x16 cinit = splat16(PRE ? -mx : 0.f);
-            b2 = mx * ac2;
+        f32x16 s_ahead = splat16(0.f);   // hi product of the NEXT token tile's first latent tile
+        float b2 = mx * ac2;
+        // One sweep over the latent tiles: 2^x, pack, value product per tile.  s_cur: the scores of latent tile 0;
+        // cinit: -b as the starting value of the other tiles' score accumulators (PRE), or folded into the fma.
+        // AHEAD: the last latent tile, which has no next scores to request, requests the first hi product of
+        // the wave's next token tile instead, so that its stabiliser is known when this tile's output is stored.
+        auto sweep = [&](f32x16 s_cur, const f32x16 cinit, auto ahead_tag) {
+            constexpr bool AHEAD = decltype(ahead_tag)::value;
             auto qk_full = [&](int t) {
                 f32x16 r = cinit;
 #pragma unroll
@@ -180,11 +188,9 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
                 }
                 return r;
             };
-
-            // per latent tile 2^x, pack, and the value product
+            f32x16 s_next = s_cur;
 #pragma unroll
             for (int hv = 0; hv < HV; ++hv) acc[hv] = splat16(0.f);
-            s_cur = qk_full(0);
             sched_fence();
 #pragma unroll
             for (int t = 0; t < MT; ++t) {
@@ -192,10 +198,11 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
                 // dependent value products of tile t alternate (hi, value, lo, value), so that each finds its
                 // predecessor's result ready instead of waiting for the matrix pipe to drain
                 constexpr bool SPLIT = PRE && D == 16 && !PACK;
-                if constexpr (SPLIT) {
-                    if (t + 1 < MT) s_next = mfma_s<F>(qh[t + 1][0], kt2[0], cinit);
-                } else {
-                    if (t + 1 < MT) s_next = qk_full(t + 1);
+                if (t + 1 < MT) {
+                    if constexpr (SPLIT) s_next = mfma_s<F>(qh[t + 1][0], kt2[0], cinit);
+                    else s_next = qk_full(t + 1);
+                } else if constexpr (AHEAD) {
+                    s_next = qk_hi(0, ktn);
                 }
                 if constexpr (!(PRE && D == 16)) sched_fence();
                 if constexpr (!PRE) {
@@ -239,6 +246,15 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
                         FLARE_GROUP_TRANS(4);
                         FLARE_GROUP_VALU(4);
                         FLARE_GROUP_MFMA(1);      // second value product
+                    } else if (AHEAD) {
+                        FLARE_GROUP_TRANS(4);
+                        FLARE_GROUP_MFMA(1);      // hi product of the next token tile
+                        FLARE_GROUP_TRANS(4);
+                        FLARE_GROUP_VALU(4);
+                        FLARE_GROUP_MFMA(1);
+                        FLARE_GROUP_TRANS(8);
+                        FLARE_GROUP_VALU(4);
+                        FLARE_GROUP_MFMA(1);
                     } else {
                         FLARE_GROUP_TRANS(8);
                         FLARE_GROUP_VALU(4);
@@ -251,11 +267,30 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
                 sched_fence();
                 s_cur = s_next;
             }
-            // A later latent tile beat the first one by more than 2^64 for some token (its denominator, row 16,
-            // is huge or not finite): once more with the exact maximum.  Exponent field >= 127 + 64.
-            const bool over = (__float_as_uint(acc[0][8]) & 0x7f800000u) >= ((127u + 64u) << 23);
-            if (exact || !__any(over)) break;
+            return s_cur;
+        };
+        s_ahead = sweep(s_cur0, splat16(PRE ? -mx : 0.f), PlainTag<true>{});
+        // A later latent tile beat the first one by more than 2^64 for some token (its denominator, row 16,
+        // is huge or not finite): once more with the exact maximum.  Exponent field >= 127 + 64.
+        if (__any((__float_as_uint(acc[0][8]) & 0x7f800000u) >= ((127u + 64u) << 23))) {
+            float m = -INFINITY;
+            f32x16 hi0 = qk_hi(0, kt), s_cur = hi0, s_next = hi0;
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+                if (t + 1 < MT) s_next = qk_hi(t + 1, kt);
+                sched_fence();
+                m = max16(s_cur, m);
+                s_cur = s_next;
+            }
+            mx = fmaxf(m, __shfl_xor(m, 32));
+            b2 = mx * ac2;
+            (void)sweep(first_scores(hi0, mx, kt), splat16(PRE ? -mx : 0.f), PlainTag<false>{});
+            s_ahead = qk_hi(0, ktn);
         }
+        // The next tile's stabiliser and first scores, before this tile's output: their latencies (a cross-lane
+        // exchange, a matrix product) pass while the output below is normalised, packed and stored.
+        const float mx_next = tile_max(s_ahead);
+        s_cur0 = first_scores(s_ahead, mx_next, ktn);
         // row 16 (register 8 of the lower lane half) is the softmax denominator
         const float den = __shfl(acc[0][8], l32);
         const float inv = 1.f / den;
@@ -323,6 +358,7 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
         }
 #pragma unroll
         for (int s = 0; s < KS; ++s) kt[s] = ktn[s];
+        mx = mx_next;
     }
 }
 

@@ -34,8 +34,10 @@ __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c)
 }
 
 // MT: 32-latent tiles per head (padded geometry); HW: waves = heads; F: fp16 storage.
+// (Launch bounds: two waves per SIMD need at most 256 registers; with two waves per workgroup a minimum of four
+// workgroups per CU made the compiler keep to 128 registers and spill at four and more latent tiles.)
 template <int MT, int HW, bool F>
-__global__ __launch_bounds__(64 * HW, 8 / HW) void decode_project_kernel(
+__global__ __launch_bounds__(64 * HW, HW == 8 ? 1 : 2) void decode_project_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const float *__restrict__ z,
     const bf16_t *__restrict__ w_out, const float *__restrict__ bias, bf16_t *__restrict__ out,
     bf16_t *__restrict__ y, float *__restrict__ lse_dec, long long sq, int N, int Mtot, float c2)
@@ -98,49 +100,51 @@ __global__ __launch_bounds__(64 * HW, 8 / HW) void decode_project_kernel(
     const int tiles = (N + 31) / 32;
     bf16x8 kt, ktn;
     int tile = blockIdx.x;
-    if (tile < tiles) kt = as_bf16x8(*reinterpret_cast<const u32x4 *>(kb + (size_t)min(tile * 32 + l32, N - 1) * row_stride + 8 * hh));
+    // The decode of one head, as in decode_mfma_kernel, operation for operation (y is bit-identical): the stabiliser
+    // of a token tile is the maximum of the hi product of its first latent tile; the scores of that latent tile are
+    // the same product minus the stabiliser plus the lo product; the last latent tile requests the first hi
+    // product of the wave's next token tile.
+    auto qk_hi = [&](int t, bf16x8 kk) { return mfma_s<F>(qh[t][0], kk, splat16(0.f)); };
+    auto tile_max = [&](const f32x16 &hi) {
+        const float m = max16(hi, -INFINITY);
+        return fmaxf(m, __shfl_xor(m, 32));
+    };
+    auto first_scores = [&](f32x16 hi, float m, bf16x8 kk) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) hi[i] -= m;
+        return mfma_s<F>(ql[0][0], kk, hi);
+    };
+    float mx = 0.f;
+    f32x16 s_cur0 = splat16(0.f);
+    if (tile < tiles) {
+        kt = as_bf16x8(*reinterpret_cast<const u32x4 *>(kb + (size_t)min(tile * 32 + l32, N - 1) * row_stride + 8 * hh));
+        const f32x16 hi = qk_hi(0, kt);
+        mx = tile_max(hi);
+        s_cur0 = first_scores(hi, mx, kt);
+    }
     for (int it = 0; tile < tiles; tile += gridDim.x, ++it) {
         const int n = tile * 32 + l32;
         {   // keys of the workgroup's next tile (the last one is simply loaded again)
             const int tn = (tile + (int)gridDim.x < tiles) ? tile + (int)gridDim.x : tile;
             ktn = as_bf16x8(*reinterpret_cast<const u32x4 *>(kb + (size_t)min(tn * 32 + l32, N - 1) * row_stride + 8 * hh));
         }
-        auto qk_hi = [&](int t) { return mfma_s<F>(qh[t][0], kt, splat16(0.f)); };
         bf16x8 kt2;
         {
             u32x4 w = __builtin_bit_cast(u32x4, kt);
-            asm volatile("" : "+v"(w));                        // keeps the stabiliser's product apart from the sweep's
+            asm volatile("" : "+v"(w));                        // keeps the hi products apart from the lo ones
             kt2 = as_bf16x8(w);
         }
         f32x16 acc;
-        float mx;
-        for (bool exact = false;; exact = true) {
-            mx = -INFINITY;
-            f32x16 s_cur = qk_hi(0), s_next;
-            if (!exact) {
-                mx = max16(s_cur, mx);
-            } else {
-#pragma unroll
-                for (int t = 0; t < MT; ++t) {
-                    if (t + 1 < MT) s_next = qk_hi(t + 1);
-                    sched_fence();
-                    mx = max16(s_cur, mx);
-                    s_cur = s_next;
-                }
-            }
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const f32x16 cinit = splat16(-mx);
-            auto qk_full = [&](int t) {
-                f32x16 r = mfma_s<F>(qh[t][0], kt2, cinit);
-                return mfma_s<F>(ql[t][0], kt, r);
-            };
+        auto sweep = [&](f32x16 s_cur, const f32x16 cinit, auto ahead_tag) {
+            constexpr bool AHEAD = decltype(ahead_tag)::value;
+            f32x16 s_next = s_cur;
             acc = splat16(0.f);
-            s_cur = qk_full(0);
             sched_fence();
 #pragma unroll
             for (int t = 0; t < MT; ++t) {
                 // dependent pairs alternate (hi, value, lo, value), as in decode_mfma_kernel
                 if (t + 1 < MT) s_next = mfma_s<F>(qh[t + 1][0], kt2, cinit);
+                else if constexpr (AHEAD) s_next = qk_hi(0, ktn);
                 bf16x8 p0, p1;
                 exp_pack(s_cur, p0, p1);
                 acc = mfma(zt[2 * t], p0, acc);
@@ -157,6 +161,15 @@ __global__ __launch_bounds__(64 * HW, 8 / HW) void decode_project_kernel(
                     FLARE_GROUP_TRANS(4);
                     FLARE_GROUP_VALU(4);
                     FLARE_GROUP_MFMA(1);
+                } else if (AHEAD) {
+                    FLARE_GROUP_TRANS(4);
+                    FLARE_GROUP_MFMA(1);
+                    FLARE_GROUP_TRANS(4);
+                    FLARE_GROUP_VALU(4);
+                    FLARE_GROUP_MFMA(1);
+                    FLARE_GROUP_TRANS(8);
+                    FLARE_GROUP_VALU(4);
+                    FLARE_GROUP_MFMA(1);
                 } else {
                     FLARE_GROUP_TRANS(8);
                     FLARE_GROUP_VALU(4);
@@ -168,9 +181,26 @@ __global__ __launch_bounds__(64 * HW, 8 / HW) void decode_project_kernel(
                 sched_fence();
                 s_cur = s_next;
             }
-            const bool over = (__float_as_uint(acc[8]) & 0x7f800000u) >= ((127u + 64u) << 23);
-            if (exact || !__any(over)) break;
+            return s_cur;
+        };
+        f32x16 s_ahead = sweep(s_cur0, splat16(-mx), PlainTag<true>{});
+        // a denominator at or beyond 2^64 (or not finite): once more with the exact maximum over all latent tiles
+        if (__any((__float_as_uint(acc[8]) & 0x7f800000u) >= ((127u + 64u) << 23))) {
+            float m = -INFINITY;
+            f32x16 hi0 = qk_hi(0, kt), s_cur = hi0, s_next = hi0;
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+                if (t + 1 < MT) s_next = qk_hi(t + 1, kt);
+                sched_fence();
+                m = max16(s_cur, m);
+                s_cur = s_next;
+            }
+            mx = fmaxf(m, __shfl_xor(m, 32));
+            (void)sweep(first_scores(hi0, mx, kt), splat16(-mx), PlainTag<false>{});
+            s_ahead = qk_hi(0, ktn);
         }
+        const float mx_next = tile_max(s_ahead);
+        s_cur0 = first_scores(s_ahead, mx_next, ktn);
         const float den = __shfl(acc[8], l32);
         const float inv = 1.f / den;
         // this lane: token l32, columns 4 hh .. 4 hh + 3 (registers 0-3) and 8 + 4 hh .. (registers 4-7) of Y_h
@@ -213,6 +243,7 @@ __global__ __launch_bounds__(64 * HW, 8 / HW) void decode_project_kernel(
             }
         }
         kt = ktn;
+        mx = mx_next;
     }
 }
 
