@@ -524,6 +524,12 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         return mfma_s<F>(kk[0], qh[b][0], r);
     };
     auto qk_second = [&](int b, const bf16x8 (&kk)[KS], f32x16 r) { return mfma_s<F>(kk[0], ql[b][0], r); };
+    // The same at d = 32 in four parts: part 0 the correction k-step (unless plain) and the hi product's k-step 0,
+    // part 1 its k-step 1, parts 2 and 3 the lo product's k-steps.
+    auto qk_part = [&](int b, const bf16x8 (&kk)[KS], bf16x8 kk0a, bool plain, int part, f32x16 r) {
+        if (part == 0 && !plain) r = mfma_s<F>(kk0a, MODE == 0 ? caug[MODE == 0 ? b : 0] : ones23, r);
+        return mfma_s<F>(kk[part % KS], part < 2 ? qh[b][part % KS] : ql[b][part % KS], r);
+    };
     const uint32_t one0 = hh == 0 ? kOne<F> : 0u;
     const float *lb = (MODE == 1) ? lse_dec2 + (size_t)bh * N : nullptr;
     // Key operand of the correction k-step.  MODE 0: slot 0 := 1, else zero.  MODE 1: zero except
@@ -638,6 +644,9 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
             // SPREAD: the score products of the next latent tile and the value products of this one are issued
             // between the exponentials and packs of this tile instead of in one burst before and after them
             constexpr bool SPREAD = !TAIL && D == 16 && !PACK && (PLAIN || MODE == 1);
+            // the same at d = 32 (two k-steps per score product, two column groups of values: eight products a tile),
+            // in the dZ kernel only: there it gains 3 % (192 -> 186 us at 262144 tokens), the encode loses 1 % with it
+            constexpr bool SPREAD32 = !TAIL && D == 32 && MODE == 1;
             const int tok0 = tile_tok0(j);
             uint16_t *buf_next = vt + ((j + 1) & 1) * BUF;
             nln = load_lse(j + 1);
@@ -663,6 +672,9 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
                 if constexpr (SPREAD) {
                     if (b + 1 < NB) nxt = qk_first(b + 1, kt, kt0a, PLAIN);
                     else nxt = qk_first(0, ktn, k_aug(ktn[0], nln), PLAIN);
+                } else if constexpr (SPREAD32) {
+                    if (b + 1 < NB) nxt = qk_part(b + 1, kt, kt0a, PLAIN, 0, splat16(0.f));
+                    else nxt = qk_part(0, ktn, k_aug(ktn[0], nln), PLAIN, 0, splat16(0.f));
                 } else {
                     if (b + 1 < NB) nxt = qk(b + 1, kt, kt0a, PLAIN);
                     else nxt = qk(0, ktn, k_aug(ktn[0], nln), PLAIN);
@@ -714,6 +726,33 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
                     FLARE_GROUP_TRANS(4);
                     FLARE_GROUP_VALU(4);
                     FLARE_GROUP_MFMA(1);      // second value product
+                } else if constexpr (SPREAD32) {
+                    // eight products, each dependent pair apart: (hi k-step 0 above), value (0, p0), hi k-step 1,
+                    // value (1, p0), lo k-step 0, value (0, p1), lo k-step 1, value (1, p1)
+                    o[b][0] = mfma(va[0][0], p0, o[b][0]);
+                    nxt = (b + 1 < NB) ? qk_part(b + 1, kt, kt0a, PLAIN, 1, nxt) : qk_part(0, ktn, kt0a, PLAIN, 1, nxt);
+                    o[b][HV - 1] = mfma(va[HV - 1][0], p0, o[b][HV - 1]);
+                    nxt = (b + 1 < NB) ? qk_part(b + 1, kt, kt0a, PLAIN, 2, nxt) : qk_part(0, ktn, kt0a, PLAIN, 2, nxt);
+                    o[b][0] = mfma(va[0][1], p1, o[b][0]);
+                    nxt = (b + 1 < NB) ? qk_part(b + 1, kt, kt0a, PLAIN, 3, nxt) : qk_part(0, ktn, kt0a, PLAIN, 3, nxt);
+                    o[b][HV - 1] = mfma(va[HV - 1][1], p1, o[b][HV - 1]);
+                    if constexpr (MODE == 1) FLARE_GROUP_MFMA(1);   // the correction k-step of the next scores
+                    FLARE_GROUP_TRANS(4);
+                    FLARE_GROUP_MFMA(1);      // hi, k-step 0
+                    FLARE_GROUP_TRANS(4);
+                    FLARE_GROUP_VALU(4);
+                    FLARE_GROUP_MFMA(1);      // value (0, p0)
+                    FLARE_GROUP_TRANS(2);
+                    FLARE_GROUP_MFMA(1);      // hi, k-step 1
+                    FLARE_GROUP_TRANS(2);
+                    FLARE_GROUP_MFMA(1);      // value (1, p0)
+                    FLARE_GROUP_TRANS(2);
+                    FLARE_GROUP_MFMA(1);      // lo, k-step 0
+                    FLARE_GROUP_TRANS(2);
+                    FLARE_GROUP_VALU(4);
+                    FLARE_GROUP_MFMA(1);      // value (0, p1)
+                    FLARE_GROUP_MFMA(1);      // lo, k-step 1
+                    FLARE_GROUP_MFMA(1);      // value (1, p1)
                 } else {
 #pragma unroll
                     for (int hv = 0; hv < HV; ++hv) {
