@@ -7,9 +7,9 @@
 //
 // Steps here:  G as a streaming reduction over the tokens (matrix-core kernel in flare_mfma_fwd.hip,
 // or the fp32 kernel below), a fixed-order sum of the per-chunk partials, a symmetric eigensolver in fp64
-// (one workgroup per (b,h): Householder tridiagonalisation, then the implicit QL iteration with its
-// rotations applied to the rows of Q^T), and a last kernel that orders the eigenvalues and forms the decode-ready block
-// L_M^(1/2) U Sigma^(-1) of d consecutive eigenvectors.
+// (one workgroup per (b,h): Householder tridiagonalisation, the implicit QL iteration with its rotations
+// accumulated from the identity, and the reflectors applied to the d eigenvectors that were asked for), and a last
+// kernel that orders the eigenvalues and forms the decode-ready block L_M^(1/2) U Sigma^(-1) of those eigenvectors.
 #include <stdlib.h>
 
 #include "flare_internal.h"
@@ -84,21 +84,23 @@ __global__ __launch_bounds__(256) void gram_reduce_kernel(const float *__restric
 
 // ---- symmetric eigensolver, fp64, one workgroup per matrix ------------------------------------------------
 // G = Q T Q^T by Householder reflections (T tridiagonal), then the implicit-shift QL iteration on T with its
-// plane rotations applied to the rows of Q^T; at the end row j of the matrix buffer is the j-th eigenvector and
-// lam[j] its eigenvalue (unordered).  Thread j owns column j throughout, so every pass over a matrix reads and
-// writes whole rows side by side; all sums run in a fixed order (bit-reproducible).
+// plane rotations applied to the rows of a second matrix that starts as the identity; at the end row j of that
+// matrix is the j-th eigenvector of T and lam[j] its eigenvalue (unordered), and the dvec eigenvectors of G that
+// the caller asked for (ranks first .. first + dvec - 1) are those rows multiplied by Q, reflector by reflector.
+// Thread j owns column j throughout, so every pass over a matrix reads and writes whole rows side by side; all
+// sums run in a fixed order (bit-reproducible).
 //   1. for k = 0 .. M-3:  x = G[k][k+1..] (= the column below the diagonal, G is kept symmetric in full),
 //      sigma = |x|, alpha = -sign(x_0) sigma, v = x - alpha e_0, beta = 1 / (sigma (sigma + |x_0|)), so that
 //      H = I - beta v v^T maps x to alpha e_0;  p = beta G22 v,  w = p - (beta p.v / 2) v,
 //      G22 -= v w^T + w v^T  (= H G22 H);  v stays in row k for step 2, d[k] = G[k][k], e[k] = alpha.
-//   2. Q = H_0 ... H_{M-3} accumulated from the last reflector to the first (each touches only the trailing
-//      block), then transposed into the first buffer.
+//   2. the second buffer := I.  (Q itself is never formed: forming it costs as much as step 1, and only dvec of
+//      its M columns' worth of work is wanted.)
 //   3. QL with Wilkinson shifts on (d, e): thread 0 runs the scalar recurrence of one iteration and leaves the
 //      rotations (c_i, s_i) in LDS (1 / r from the hardware reciprocal square root and one third-order step: no
 //      division, no square root in the chain; a loop body without branches: a lone wave issues about one
 //      instruction per 10 clocks, so the step costs its ~40 instructions, not its dependent chain of ~120
 //      clocks); meanwhile one thread per column applies the rotations of the
-//      previous iteration to its column of Q^T, rows m .. l, with the rows and rotations it will need requested
+//      previous iteration to its column of the second buffer, rows m .. l, with the rows and rotations it will need requested
 //      eight steps ahead.  The two sides swap LDS buffers at one barrier per iteration.  An off-diagonal element
 //      counts as zero at 2^-52 (|d_m| + |d_m+1|) + 1e-10 |T|: the result is the exact eigensystem of a matrix
 //      within 1e-10 |G| of G, while G itself (sums of 10^6 products in fp32, bf16 weights on the matrix-core
@@ -155,7 +157,7 @@ __device__ __forceinline__ double column_dot(const double *__restrict__ mat, con
 template <int CP>
 __global__ __launch_bounds__(kEigThreads) void eigen_kernel(double *__restrict__ a_all, double *__restrict__ q_all,
                                                             double *__restrict__ lam_all, int *__restrict__ status_all,
-                                                            int M)
+                                                            double *__restrict__ vec_all, int M, int first, int dvec)
 {
     constexpr int RG = kEigThreads / CP;
     __shared__ double d[CP], e[CP], v[CP], w[CP], beta[CP], part[RG][CP], red[kEigThreads / 64];
@@ -230,43 +232,13 @@ __global__ __launch_bounds__(kEigThreads) void eigen_kernel(double *__restrict__
         d[M - 1] = a[(size_t)(M - 1) * M + M - 1];
         e[M - 1] = 0.0;
     }
-    // ---- 2. Q = H_0 ... H_{M-3}, then its transpose into the first buffer ----
+    // ---- 2. the second buffer := identity: QL rotates its rows into the eigenvectors of T ----
+    // (The product of the reflectors is not formed: only the requested eigenvectors are transformed back, at the end.)
     if (col)
         for (int i = g; i < M; i += RG) qm[(size_t)i * M + j] = (i == j) ? 1.0 : 0.0;
     __syncthreads();
-    for (int k = M - 3; k >= 0; --k) {
-        const double bt = beta[k];
-        if (bt == 0.0) continue;     // uniform: beta is in LDS
-        if (g == 0) v[j] = (col && j > k) ? a[(size_t)k * M + j] : 0.0;
-        __syncthreads();
-        {
-            double t = 0.0;
-            if (col && j > k) t = column_dot<RG>(qm, v, k + 1 + g, M, j);
-            part[g][j] = t;
-        }
-        __syncthreads();
-        if (col && j > k) {
-            double t = 0.0;
-#pragma unroll
-            for (int r = 0; r < RG; ++r) t += part[r][j];
-            t *= bt;
-            int i = k + 1 + g;
-            for (; i + 7 * RG < M; i += 8 * RG) {
-                double x[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) x[u] = qm[(size_t)(i + u * RG) * M + j];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) qm[(size_t)(i + u * RG) * M + j] = x[u] - v[i + u * RG] * t;
-            }
-            for (; i < M; i += RG) qm[(size_t)i * M + j] -= v[i] * t;
-        }
-        __syncthreads();
-    }
-    if (col)
-        for (int i = g; i < M; i += RG) a[(size_t)j * M + i] = qm[(size_t)i * M + j];
-    __syncthreads();
 
-    // ---- 3. implicit QL; rotations act on rows i, i+1 of a = Q^T ----
+    // ---- 3. implicit QL; rotations act on rows i, i+1 of the second buffer ----
     // Thread 0 (wave 0) produces the rotations of iteration n+1 into one LDS buffer while threads 64 .. 64 + M - 1
     // apply those of iteration n from the other: both between the same two barriers, no waiting on flags.
     double anorm = 0.0;
@@ -370,13 +342,13 @@ __global__ __launch_bounds__(kEigThreads) void eigen_kernel(double *__restrict__
             // rows and their rotations are in flight at any time; the loop body has no branches (a request past
             // the bottom row is clamped to it and its result ignored), so that nothing waits for a request it
             // does not need yet.
-            double hi = a[(size_t)top * M + jc];
+            double hi = qm[(size_t)top * M + jc];
             double buf[8], cb[8], sb[8];
             int i = top - 1;
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const int r = max(i - u, bot);
-                buf[u] = a[(size_t)r * M + jc];
+                buf[u] = qm[(size_t)r * M + jc];
                 cb[u] = cc[bf][r];
                 sb[u] = ss[bf][r];
             }
@@ -385,10 +357,10 @@ __global__ __launch_bounds__(kEigThreads) void eigen_kernel(double *__restrict__
                 for (int u = 0; u < 8; ++u) {
                     const int r = i - u, rn = max(r - 8, bot);
                     const double lo = buf[u], c = cb[u], s = sb[u];
-                    buf[u] = a[(size_t)rn * M + jc];
+                    buf[u] = qm[(size_t)rn * M + jc];
                     cb[u] = cc[bf][rn];
                     sb[u] = ss[bf][rn];
-                    a[(size_t)(r + 1) * M + jc] = fma(s, lo, c * hi);
+                    qm[(size_t)(r + 1) * M + jc] = fma(s, lo, c * hi);
                     hi = fma(c, lo, -s * hi);
                 }
                 i -= 8;
@@ -397,16 +369,77 @@ __global__ __launch_bounds__(kEigThreads) void eigen_kernel(double *__restrict__
             for (int u = 0; u < 7; ++u) {      // the last rows, fewer than eight
                 const int r = i - u;
                 if (r >= bot) {
-                    a[(size_t)(r + 1) * M + jc] = fma(sb[u], buf[u], cb[u] * hi);
+                    qm[(size_t)(r + 1) * M + jc] = fma(sb[u], buf[u], cb[u] * hi);
                     hi = fma(cb[u], buf[u], -sb[u] * hi);
                 }
             }
-            a[(size_t)bot * M + jc] = hi;
+            qm[(size_t)bot * M + jc] = hi;
         }
         __syncthreads();
     }
     if (tid < M) lam_all[(size_t)blockIdx.x * M + tid] = d[tid];
     if (tid == 0) status_all[blockIdx.x] = failed ? 1 : 0;
+
+    // ---- 4. the requested eigenvectors of G: x = H_0 ... H_{M-3} z for the rows z of ranks first .. first + dvec - 1 ----
+    // rank of eigenvalue j = how many are larger (ties broken by index; negative rounding noise counts as zero): the
+    // order the caller's post-processing uses.  One wave per vector, the vector in registers (lane l holds the
+    // elements l, l + 64, ...), the reflector's row requested one step ahead.
+    int *row_of = reinterpret_cast<int *>(&part[0][0]);
+    if (tid < M) {
+        const double lj = fmax(d[tid], 0.0);
+        int rank = 0;
+        for (int i = 0; i < M; ++i) {
+            const double li = fmax(d[i], 0.0);
+            rank += (li > lj || (li == lj && i < tid)) ? 1 : 0;
+        }
+        row_of[rank] = tid;
+    }
+    __syncthreads();
+    constexpr int NE = CP / 64;
+    const int lane = tid & 63, wave = tid >> 6;
+    for (int c = wave; c < dvec; c += kEigThreads / 64) {
+        double *out = vec_all + ((size_t)blockIdx.x * dvec + c) * M;
+        const int rk = first + c;
+        if (rk >= M) {
+            for (int i = 0; i < NE; ++i)
+                if (lane + 64 * i < M) out[lane + 64 * i] = 0.0;
+            continue;
+        }
+        const double *z = qm + (size_t)row_of[rk] * M;
+        double y[NE], v[NE], vn[NE];
+#pragma unroll
+        for (int i = 0; i < NE; ++i) {
+            const int m = lane + 64 * i;
+            y[i] = m < M ? z[m] : 0.0;
+            vn[i] = 0.0;
+        }
+        auto load_reflector = [&](int k, double (&t)[NE]) {
+#pragma unroll
+            for (int i = 0; i < NE; ++i) {
+                const int m = lane + 64 * i;
+                t[i] = (m > k && m < M) ? a[(size_t)k * M + m] : 0.0;
+            }
+        };
+        if (M >= 3) load_reflector(M - 3, vn);
+        for (int k = M - 3; k >= 0; --k) {
+#pragma unroll
+            for (int i = 0; i < NE; ++i) v[i] = vn[i];
+            if (k > 0) load_reflector(k - 1, vn);
+            const double bt = beta[k];
+            if (bt == 0.0) continue;
+            double dot = 0.0;
+#pragma unroll
+            for (int i = 0; i < NE; ++i) dot = fma(v[i], y[i], dot);
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) dot += __shfl_xor(dot, o);
+            const double t = bt * dot;
+#pragma unroll
+            for (int i = 0; i < NE; ++i) y[i] = fma(-t, v[i], y[i]);
+        }
+#pragma unroll
+        for (int i = 0; i < NE; ++i)
+            if (lane + 64 * i < M) out[lane + 64 * i] = y[i];
+    }
 }
 
 // ---- eigenvalues in descending order, and the decode-ready block of d eigenvectors -------------------
@@ -426,7 +459,7 @@ __global__ __launch_bounds__(256) void spectral_post_kernel(const double *__rest
     extern __shared__ double lam[];   // lam[M], then int row_of[M]
     int *row_of = reinterpret_cast<int *>(lam + M);
     const int bh = blockIdx.x, tid = threadIdx.x;
-    const double *bm = b_all + (size_t)bh * M * M;
+    const double *bm = b_all + (size_t)bh * d * M;       // row c: the unit eigenvector of rank first + c
     const bool bad = status[bh] != 0;
     for (int j = tid; j < M; j += 256) lam[j] = fmax(lam_in[(size_t)bh * M + j], 0.0);
     __syncthreads();
@@ -444,7 +477,7 @@ __global__ __launch_bounds__(256) void spectral_post_kernel(const double *__rest
         if (rk < M && !bad) {
             const int j = row_of[rk];
             if (lam[j] > 1e-12 * top && lam[j] > 1e-300)
-                out = (float)(exp(-0.5 * (double)lse_enc[(size_t)bh * M + m]) * bm[(size_t)j * M + m] / sqrt(lam[j]));
+                out = (float)(exp(-0.5 * (double)lse_enc[(size_t)bh * M + m]) * bm[(size_t)c * M + m] / sqrt(lam[j]));
         }
         zvec[((size_t)bh * M + m) * d + c] = out;
     }
@@ -463,8 +496,10 @@ size_t spectral_bytes(const flare_shape &s)
 {
     const size_t BH = (size_t)s.B * s.H, mm = (size_t)s.M * s.M;
     const Split sp = spectral_split(s);
-    // partial G's; two fp64 matrices per (b,h) (G, then Q^T; Q); eigenvalues; solver status
-    return align256(BH * sp.chunks * mm * 4) + 2 * align256(BH * mm * 8) + align256(BH * s.M * 8) + align256(BH * 4);
+    // partial G's; two fp64 matrices per (b,h) (G, then its reflectors; the rotated identity); eigenvalues; solver
+    // status; the d requested eigenvectors
+    return align256(BH * sp.chunks * mm * 4) + 2 * align256(BH * mm * 8) + align256(BH * s.M * 8) + align256(BH * 4) +
+           align256(BH * s.d * s.M * 8);
 }
 
 int spectral_run(const flare_shape &s, const void *q, const void *k, const float *lse_enc, const float *lse_dec,
@@ -478,6 +513,7 @@ int spectral_run(const flare_shape &s, const void *q, const void *k, const float
     double *qbuf = reinterpret_cast<double *>(reinterpret_cast<char *>(a) + align256(BH * mm * 8));
     double *lam = reinterpret_cast<double *>(reinterpret_cast<char *>(qbuf) + align256(BH * mm * 8));
     int *status = reinterpret_cast<int *>(reinterpret_cast<char *>(lam) + align256(BH * s.M * 8));
+    double *vec = reinterpret_cast<double *>(reinterpret_cast<char *>(status) + align256(BH * 4));
     if (mfma_gram_supported(s)) {
         const int rc = mfma_gram_partial(s, sp, q, k, lse_enc, lse_dec, g_part, scale, stream);
         if (rc != FLARE_OK) return rc;
@@ -507,13 +543,13 @@ int spectral_run(const flare_shape &s, const void *q, const void *k, const float
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     {
         LaunchTimer t(KID_SPECTRAL_EIGEN, stream);
-        if (s.M <= 256) eigen_kernel<256><<<(unsigned)BH, kEigThreads, 0, stream>>>(a, qbuf, lam, status, s.M);
-        else eigen_kernel<512><<<(unsigned)BH, kEigThreads, 0, stream>>>(a, qbuf, lam, status, s.M);
+        if (s.M <= 256) eigen_kernel<256><<<(unsigned)BH, kEigThreads, 0, stream>>>(a, qbuf, lam, status, vec, s.M, first, s.d);
+        else eigen_kernel<512><<<(unsigned)BH, kEigThreads, 0, stream>>>(a, qbuf, lam, status, vec, s.M, first, s.d);
     }
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     {
         LaunchTimer t(KID_SPECTRAL_POST, stream);
-        spectral_post_kernel<<<(unsigned)BH, 256, s.M * 12, stream>>>(a, lam, status, lse_enc, evals, zvec, s.M, s.d,
+        spectral_post_kernel<<<(unsigned)BH, 256, s.M * 12, stream>>>(vec, lam, status, lse_enc, evals, zvec, s.M, s.d,
                                                                       first);
     }
     return check_launch();
