@@ -391,8 +391,8 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
 // per-lane scalar here, and dS' = P (a + w c).  Runs only where plan[bh] = 1.
 // ============================================================================================
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-constexpr int kDsStride = 40;   // uint16 per row of the transposed dS tile (80 B: 16-byte aligned, conflict-free b128 reads)
-constexpr int kFusedWaveLds = 32 * kDsStride + 16 * kVtStride;   // uint16 per wave: dS^T tile, then K^T tile
+constexpr int kDsStride = 36;   // uint16 per row of the dS tile [token][latent] (72 B: conflict-free 8-byte stores)
+constexpr int kFusedWaveLds = 32 * kDsStride + 16 * kVtStride;   // uint16 per wave: dS tile, then K^T tile
 
 template <int DR, int MT, bool DQ, bool ONE, bool F>
 __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
@@ -780,19 +780,21 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                 acc2[hv] = mfma(rw[(1 * HV + hv) * 2 + 1], as_bf16x8(d1), acc2[hv]);
             }
             if constexpr (DQ) {
-                // dS (this lane: token l32, latents 8 (r/4) + 4 hh + r%4 for r = 0..15) -> LDS [latent][token]
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int ma = 8 * (i / 2) + 4 * hh + 2 * (i % 2);          // latent of the low half of d0[i]
-                    ds_t[ma * kDsStride + l32] = (uint16_t)(d0[i] & 0xffffu);
-                    ds_t[(ma + 1) * kDsStride + l32] = (uint16_t)(d0[i] >> 16);
-                    ds_t[(16 + ma) * kDsStride + l32] = (uint16_t)(d1[i] & 0xffffu);
-                    ds_t[(16 + ma + 1) * kDsStride + l32] = (uint16_t)(d1[i] >> 16);
-                }
+                // dS (this lane: token l32, latents 8 (r/4) + 4 hh + r%4 for r = 0..15) -> LDS as it is, row = token:
+                // four 8-byte stores of four latents each.  The product wants it the other way round (column =
+                // latent, 8 consecutive tokens per lane): four transposing reads, each four tokens of one latent.
+                uint16_t *drow = ds_t + l32 * kDsStride + 4 * hh;
+                *reinterpret_cast<u32x2 *>(drow) = u32x2{d0[0], d0[1]};
+                *reinterpret_cast<u32x2 *>(drow + 8) = u32x2{d0[2], d0[3]};
+                *reinterpret_cast<u32x2 *>(drow + 16) = u32x2{d1[0], d1[1]};
+                *reinterpret_cast<u32x2 *>(drow + 24) = u32x2{d1[2], d1[3]};
                 compiler_fence();
 #pragma unroll
                 for (int jb = 0; jb < 2; ++jb) {
-                    const u32x4 bop = *reinterpret_cast<const u32x4 *>(ds_t + (16 * jb + c16) * kDsStride + 8 * g16);
+                    // lane c16 of block g16: chunk row = token 8 g16 (+ 4) + c16 / 4, piece = latents 16 jb + 4 (c16 % 4)
+                    const uint16_t *src = ds_t + (8 * g16 + c16 / 4) * kDsStride + 16 * jb + 4 * (c16 % 4);
+                    const u32x2 b_lo = lds_read_tr16(src), b_hi = lds_read_tr16(src + 4 * kDsStride);
+                    const u32x4 bop = u32x4{b_lo[0], b_lo[1], b_hi[0], b_hi[1]};
                     dqa[t][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k_op, as_bf16x8(bop), dqa[t][jb], 0, 0, 0);
                 }
                 compiler_fence();

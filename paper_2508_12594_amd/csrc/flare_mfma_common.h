@@ -188,6 +188,21 @@ __device__ __forceinline__ void sched_fence() { __builtin_amdgcn_sched_barrier(0
 // written (classes: matrix, transcendental, other vector ALU).  Used to spread the matrix
 // instructions of a tile between its vector instructions, so that the matrix pipe (32 clocks per
 // instruction) never blocks the wave's issue.
+// The LDS transpose read of gfx950 (ds_read_b64_tr_b16), 16-bit elements.  Within each block of 16 lanes, lane p
+// addresses a chunk of four consecutive elements E[p][0..3]; lane i of the block receives the four elements
+// E[i/4][i%4], E[i/4 + 4][i%4], E[i/4 + 8][i%4], E[i/4 + 12][i%4]: with the 16 chunks laid over four rows of a
+// row-major tile (chunk p = 4 (row) + (piece of four columns), row = p / 4, piece = p % 4), lane i gets column i of
+// those four rows -- a column segment of a row-major tile, which is what a matrix-instruction operand wants of a
+// tile that was written the other way round.  (The lane mapping was read off the instruction's output on a
+// tile of distinct values.)  Returns two dwords (four elements); p must be 8-byte aligned.
+__device__ __forceinline__ u32x2 lds_read_tr16(const uint16_t *p)
+{
+    typedef short s16x4_t __attribute__((ext_vector_type(4)));
+    const s16x4_t v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (s16x4_t __attribute__((address_space(3))) *)(const_cast<uint16_t *>(p)));
+    return __builtin_bit_cast(u32x2, v);
+}
+
 #define FLARE_GROUP_MFMA(n) __builtin_amdgcn_sched_group_barrier(0x008, n, 0)
 #define FLARE_GROUP_TRANS(n) __builtin_amdgcn_sched_group_barrier(0x400, n, 0)
 #define FLARE_GROUP_VALU(n) __builtin_amdgcn_sched_group_barrier(0x002, n, 0)

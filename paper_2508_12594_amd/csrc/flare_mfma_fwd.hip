@@ -429,9 +429,13 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     constexpr int D = padded_dim(DR);
     constexpr int KS = D / 16;
     constexpr int HV = D / 16;
-    constexpr int ROWS = D + 2;                 // V^T rows, then a row of ones, then a row of zeros
+    // The value tile of a token tile lives in LDS as it is loaded, row = token: D columns of values, then a column
+    // of ones (the softmax denominator's row of the operand), then 15 columns of zeros; 8 more pad the row to a
+    // stride that keeps the 16-byte stores aligned.  The operand wants it transposed (row = column of V, eight
+    // tokens per lane): that is what the transposing LDS read delivers.
+    constexpr int RS = D + 16 + 8;              // uint16 per row
     constexpr bool PACK = pack_dim(DR);         // q' hi | lo in one operand, keys repeated in both lane halves
-    constexpr int BUF = ROWS * kVtStride;       // uint16 per buffer
+    constexpr int BUF = 32 * RS;                // uint16 per buffer
     __shared__ __attribute__((aligned(16))) uint16_t vt_all[4][2 * BUF];
 
     const int lane = threadIdx.x & 63, l32 = lane & 31, hh = lane >> 5;
@@ -442,12 +446,13 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     const uint32_t keep0 = hh == 0 ? 0xffff0000u : 0xffffffffu;
     uint16_t *vt = vt_all[wave];
 
-    // constant rows of the value operand, in both buffers
-    if (lane < kVtStride) {
-        vt[D * kVtStride + lane] = 0x3f80;
-        vt[(D + 1) * kVtStride + lane] = 0;
-        vt[BUF + D * kVtStride + lane] = 0x3f80;
-        vt[BUF + (D + 1) * kVtStride + lane] = 0;
+    // constant columns of the value tile, in both buffers: two lanes per row, eight columns each
+    {
+        u32x4 w;
+        w[0] = (lane & 1) == 0 ? 0x3f80u : 0u; w[1] = 0u; w[2] = 0u; w[3] = 0u;
+        uint16_t *c = vt + (lane >> 1) * RS + D + 8 * (lane & 1);
+        *reinterpret_cast<u32x4 *>(c) = w;
+        *reinterpret_cast<u32x4 *>(c + BUF) = w;
     }
 
     const int lat0 = 32 * NB * (G * (int)blockIdx.z + g);   // a workgroup owns NB*G tiles of latents
@@ -484,10 +489,12 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         for (int hv = 0; hv < HV; ++hv) o[b][hv] = splat16(0.f);
     }
 
-    // row of the value operand this lane supplies for column group hv
-    int vrow[HV];
-#pragma unroll
-    for (int hv = 0; hv < HV; ++hv) vrow[hv] = (l32 < 16) ? 16 * hv + l32 : (l32 == 16 ? D : D + 1);
+    // Transposing read of the value operand: this lane's chunk of the tile.  Lanes 16-31 and 48-63 supply rows
+    // 16-31 of the operand (the ones, then zeros); the others rows 0-15 (columns 16 hv ... of V).  Row within a group of
+    // four tokens: (lane % 16) / 4; the lane half takes tokens 4-7 of every eight.
+    const int tr_row = 4 * hh + (lane & 15) / 4;
+    const bool tr_upper = (lane & 16) != 0;
+    const int tr_piece = 4 * (lane & 3);
 
     // keys: A operand, row = token.  values: 32 tokens x D in 16-byte pieces, two lanes per token.
     constexpr int PIECES = D / 8;          // 16-byte pieces per token row
@@ -506,16 +513,12 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         for (int i = 0; i < LOADS; ++i)
             vv[i] = row8_bf16<DR>(vb + tok_off(ts, nv), 8 * ((lane & 1) * LOADS + i));
     };
-    auto write_vt = [&](const u32x4 (&vv)[LOADS], uint16_t *buf) {   // transposed: row = column of V
+    auto write_vt = [&](const u32x4 (&vv)[LOADS], uint16_t *buf) {   // as loaded: row = token, one 16-byte store a piece
 #pragma unroll
         for (int i = 0; i < LOADS; ++i) {
             const int d0 = 8 * ((lane & 1) * LOADS + i);
-            const u32x4 wv = to_bf16_row<F>(vv[i]);   // the value side of the second product is bf16
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                buf[(d0 + 2 * e) * kVtStride + vtok] = (uint16_t)(wv[e] & 0xffffu);
-                buf[(d0 + 2 * e + 1) * kVtStride + vtok] = (uint16_t)(wv[e] >> 16);
-            }
+            // the value side of the second product is bf16
+            *reinterpret_cast<u32x4 *>(buf + vtok * RS + d0) = to_bf16_row<F>(vv[i]);
         }
     };
     auto read_va = [&](const uint16_t *buf, bf16x8 (&va)[HV][2]) {
@@ -523,9 +526,10 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         for (int hv = 0; hv < HV; ++hv)
 #pragma unroll
             for (int s2 = 0; s2 < 2; ++s2) {
-                const uint16_t *row = buf + vrow[hv] * kVtStride + 16 * s2 + 4 * hh;
-                const u32x2 a = *reinterpret_cast<const u32x2 *>(row);
-                const u32x2 b = *reinterpret_cast<const u32x2 *>(row + 8);
+                // k-step s2 of the operand: tokens 16 s2 + 4 hh + (0..3) and + 8 of them, column = this lane's row
+                const uint16_t *src = buf + (16 * s2 + tr_row) * RS + (tr_upper ? D : 16 * hv) + tr_piece;
+                const u32x2 a = lds_read_tr16(src);
+                const u32x2 b = lds_read_tr16(src + 8 * RS);
                 u32x4 w;
                 w[0] = a[0]; w[1] = a[1]; w[2] = b[0]; w[3] = b[1];
                 va[hv][s2] = as_bf16x8(w);
