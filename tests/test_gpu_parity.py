@@ -1,6 +1,6 @@
 """GPU parity: libflare.so (through its C ABI) against the fp64 CPU oracle, element by element,
 on the same seeded inputs.  Sizes here finish in seconds on the oracle yet span several
-tiles, several token chunks and ragged tails.  Full BASELINE sizes are in
+tiles, several token chunks and ragged tails.  The full sizes of the reference workloads are in
 test_gpu_fullsize.py.
 
 Metric: max over (b,h) slices of ||T_gpu - T_ref||_F / ||T_ref||_F.  Bar: 1e-5 for the
