@@ -223,9 +223,8 @@ int flare_backward(const flare_shape *shape, const void *q_lat, const void *k, c
  * of W are those of the M x M matrix J J^T = U Sigma^2 U^T and its eigenvectors are
  * L_N^(1/2) J^T U Sigma^(-1) = W_decode (L_M^(1/2) U Sigma^(-1)).  The library forms J J^T in one
  * pass over the tokens, diagonalises it on the device in fp64 (Householder reduction to
- * tridiagonal form, implicit-shift QL, the reflectors applied to the requested eigenvectors
- * only; one workgroup per (b,h); an off-diagonal element below 1e-10 |G| counts as zero, so the
- * result is the exact eigensystem of a matrix that close to J J^T) and returns
+ * tridiagonal form, bisection for all eigenvalues, a twisted factorisation and the reflectors
+ * for the requested eigenvectors only; one workgroup per (b,h)) and returns
  *   eigenvalues [B][H][M] fp32, in descending order                                   (out)
  *   z_vec [B][H][M][d] fp32 = L_M^(1/2) U Sigma^(-1) restricted to the eigenvectors number
  *         first .. first + d - 1 (zero beyond M or where the eigenvalue is not positive): passed
@@ -233,10 +232,11 @@ int flare_backward(const flare_shape *shape, const void *q_lat, const void *k, c
  *   gram [B][H][M][M] fp32 = J J^T; may be NULL                                       (out, optional)
  *   q_lat, k as in the forward; lse_enc, lse_dec: what flare_forward wrote             (in)
  * Supported for M <= 512.  flare_spectral_workspace_bytes gives the scratch size (partial sums of
- * J J^T plus two fp64 M x M matrices and d vectors per (b,h)).  Eigenvectors are defined up to sign (and up to
- * rotation within a repeated eigenvalue).  A (b,h) whose QL iteration does not converge within 60
- * sweeps per eigenvalue (not observed; non-finite inputs do it) gets NaN eigenvalues and a zero
- * z_vec; the call still returns FLARE_OK, as the forward does for non-finite inputs.
+ * J J^T plus one fp64 M x M matrix and 3 d vectors per (b,h)).  Eigenvectors are defined up to
+ * sign; those of a repeated eigenvalue span its eigenspace.  z_vec is fp32 and carries the
+ * factor exp(-lse_enc[m] / 2): scores whose log-sum-exp exceeds ~170 underflow it.  A (b,h)
+ * with non-finite input gets NaN eigenvalues and a zero z_vec; the call still returns
+ * FLARE_OK, as the forward does for non-finite inputs.
  */
 int flare_spectral_workspace_bytes(const flare_shape *shape, size_t *bytes);
 int flare_spectral(const flare_shape *shape, const void *q_lat, const void *k, const float *lse_enc,

@@ -7,9 +7,9 @@
 //
 // Steps here:  G as a streaming reduction over the tokens (matrix-core kernel in flare_mfma_fwd.hip,
 // or the fp32 kernel below), a fixed-order sum of the per-chunk partials, a symmetric eigensolver in fp64
-// (one workgroup per (b,h): Householder tridiagonalisation, the implicit QL iteration with its rotations
-// accumulated from the identity, and the reflectors applied to the d eigenvectors that were asked for), and a last
-// kernel that orders the eigenvalues and forms the decode-ready block L_M^(1/2) U Sigma^(-1) of those eigenvectors.
+// (one workgroup per (b,h): Householder tridiagonalisation, bisection for the eigenvalues, a twisted factorisation
+// for each of the d eigenvectors that were asked for, and the reflectors applied to those), and a last kernel that
+// forms the decode-ready block L_M^(1/2) U Sigma^(-1) of those eigenvectors.
 #include <stdlib.h>
 
 #include "flare_internal.h"
@@ -83,32 +83,19 @@ __global__ __launch_bounds__(256) void gram_reduce_kernel(const float *__restric
 }
 
 // ---- symmetric eigensolver, fp64, one workgroup per matrix ------------------------------------------------
-// G = Q T Q^T by Householder reflections (T tridiagonal), then the implicit-shift QL iteration on T with its
-// plane rotations applied to the rows of a second matrix that starts as the identity; at the end row j of that
-// matrix is the j-th eigenvector of T and lam[j] its eigenvalue (unordered), and the dvec eigenvectors of G that
-// the caller asked for (ranks first .. first + dvec - 1) are those rows multiplied by Q, reflector by reflector.
-// Thread j owns column j throughout, so every pass over a matrix reads and writes whole rows side by side; all
-// sums run in a fixed order (bit-reproducible).
+// G = Q T Q^T by Householder reflections (T tridiagonal); all eigenvalues of T by bisection, one thread each;
+// the dvec eigenvectors the caller asked for (ranks first .. first + dvec - 1) by a twisted factorisation of
+// T - lambda I, one thread each; those vectors multiplied by Q, reflector by reflector, one wave each.  Everything
+// after the reduction is parallel over eigenvalues or vectors: a QL iteration, whose scalar recurrence is one serial
+// chain of ~M^2 rotations, took three times as long as the reduction (and a Jacobi method on the rows of G, the
+// first solver here, 25 times).  All sums run in a fixed order (bit-reproducible).
 //   1. for k = 0 .. M-3:  x = G[k][k+1..] (= the column below the diagonal, G is kept symmetric in full),
 //      sigma = |x|, alpha = -sign(x_0) sigma, v = x - alpha e_0, beta = 1 / (sigma (sigma + |x_0|)), so that
 //      H = I - beta v v^T maps x to alpha e_0;  p = beta G22 v,  w = p - (beta p.v / 2) v,
-//      G22 -= v w^T + w v^T  (= H G22 H);  v stays in row k for step 2, d[k] = G[k][k], e[k] = alpha.
-//   2. the second buffer := I.  (Q itself is never formed: forming it costs as much as step 1, and only dvec of
-//      its M columns' worth of work is wanted.)
-//   3. QL with Wilkinson shifts on (d, e): thread 0 runs the scalar recurrence of one iteration and leaves the
-//      rotations (c_i, s_i) in LDS (1 / r from the hardware reciprocal square root and one third-order step: no
-//      division, no square root in the chain; a loop body without branches: a lone wave issues about one
-//      instruction per 10 clocks, so the step costs its ~40 instructions, not its dependent chain of ~120
-//      clocks); meanwhile one thread per column applies the rotations of the
-//      previous iteration to its column of the second buffer, rows m .. l, with the rows and rotations it will need requested
-//      eight steps ahead.  The two sides swap LDS buffers at one barrier per iteration.  An off-diagonal element
-//      counts as zero at 2^-52 (|d_m| + |d_m+1|) + 1e-10 |T|: the result is the exact eigensystem of a matrix
-//      within 1e-10 |G| of G, while G itself (sums of 10^6 products in fp32, bf16 weights on the matrix-core
-//      path) is no more accurate than 4e-7 |G|; the eigenvalues are delivered in fp32.  (A floor of 1e-22 |T|
-//      costs a fifth more sweeps and changes no printed digit of the test results.)
-// 60 iterations without convergence for one eigenvalue: the solver stops and reports it (status != 0; the caller
-// then returns NaN eigenvalues).  The previous solver here, a one-sided Jacobi method on the rows of G, needed
-// ~2500 rounds of row-pair rotations through global memory (102 ms for eight 256 x 256 matrices).
+//      G22 -= v w^T + w v^T  (= H G22 H);  v stays in row k for step 4, d[k] = G[k][k], e[k] = alpha.
+//      Thread (j, g) owns column j and the rows g (mod RG), so every pass reads and writes whole rows side by side.
+//   2. - 4. are described where they stand.  Q itself is never formed: forming it costs as much as step 1.
+// Non-finite input gives non-finite eigenvalues: status != 0, and the caller returns NaN eigenvalues and a zero block.
 constexpr int kEigThreads = 1024;
 
 __device__ __forceinline__ double block_sum(double x, double *red)
@@ -123,16 +110,6 @@ __device__ __forceinline__ double block_sum(double x, double *red)
 #pragma unroll
     for (int w = 0; w < kEigThreads / 64; ++w) s += red[w];
     return s;
-}
-
-// 1 / sqrt(h) to full fp64 accuracy from the hardware estimate y (relative error e0 <= 2^-20, far more than it
-// needs) and one third-order step: with e = 1 - h y^2,  1/sqrt(h) = y (1 - e)^(-1/2) = y (1 + e/2 + 3 e^2/8 + O(e^3)).
-// (h > 0, normal.)
-__device__ __forceinline__ double rsqrt_full(double h)
-{
-    const double y = __builtin_amdgcn_rsq(h);
-    const double e = fma(-h * y, y, 1.0);
-    return fma(y * e, fma(0.375, e, 0.5), y);
 }
 
 // sum over rows i = first, first + RG, ... < M of mat[i][j] * vec[i], eight rows requested at a time; one fixed order
@@ -161,13 +138,11 @@ __global__ __launch_bounds__(kEigThreads) void eigen_kernel(double *__restrict__
 {
     constexpr int RG = kEigThreads / CP;
     __shared__ double d[CP], e[CP], v[CP], w[CP], beta[CP], part[RG][CP], red[kEigThreads / 64];
-    __shared__ double cc[2][CP], ss[2][CP];
-    __shared__ int ctl[2][4];        // per buffer: top row, bottom row, kind (0 rotate, 2 finished), failed
     __shared__ double x_first;
     const int tid = threadIdx.x, j = tid % CP, g = tid / CP;
     const bool col = j < M;
     double *a = a_all + (size_t)blockIdx.x * M * M;
-    double *qm = q_all + (size_t)blockIdx.x * M * M;
+    double *qm = q_all + (size_t)blockIdx.x * 2 * M * dvec;   // pivots of the twisted factorisations (step 3)
 
     // ---- 1. tridiagonalisation ----
     for (int k = 0; k + 2 < M; ++k) {
@@ -232,169 +207,157 @@ __global__ __launch_bounds__(kEigThreads) void eigen_kernel(double *__restrict__
         d[M - 1] = a[(size_t)(M - 1) * M + M - 1];
         e[M - 1] = 0.0;
     }
-    // ---- 2. the second buffer := identity: QL rotates its rows into the eigenvectors of T ----
-    // (The product of the reflectors is not formed: only the requested eigenvectors are transformed back, at the end.)
-    if (col)
-        for (int i = g; i < M; i += RG) qm[(size_t)i * M + j] = (i == j) ? 1.0 : 0.0;
     __syncthreads();
-
-    // ---- 3. implicit QL; rotations act on rows i, i+1 of the second buffer ----
-    // Thread 0 (wave 0) produces the rotations of iteration n+1 into one LDS buffer while threads 64 .. 64 + M - 1
-    // apply those of iteration n from the other: both between the same two barriers, no waiting on flags.
-    double anorm = 0.0;
-    for (int i = 0; i < M; ++i) anorm = fmax(anorm, fabs(d[i]) + fabs(e[i]));
-    const double floor_abs = 1e-10 * anorm;
-    int l = 0, iter = 0;             // producer state (the first wave, uniform over its lanes)
-    // One step of the producer: the next QL iteration (or the end), written into buffer `bf`.  Called by the whole
-    // first wave: its lanes look for the next negligible off-diagonal element 64 at a time; lane 0 alone runs
-    // the recurrence.
-    auto produce = [&](int bf) {
-        const int lane = tid;        // tid < 64 here
-        for (;;) {
-            if (l >= M) {
-                if (lane == 0) { ctl[bf][2] = 2; ctl[bf][3] = 0; }
-                return;
-            }
-            int m = l;
-            for (;;) {
-                const int idx = m + lane;
-                bool small = idx >= M - 1;
-                if (!small) small = fabs(e[idx]) <= 2.220446049250313e-16 * (fabs(d[idx]) + fabs(d[idx + 1])) + floor_abs;
-                const unsigned long long mask = __ballot(small);
-                if (mask != 0ull) { m += __ffsll((long long)mask) - 1; break; }
-                m += 64;
-            }
-            if (m == l) { ++l; iter = 0; continue; }             // eigenvalue l has converged
-            if (iter == 60) {
-                if (lane == 0) { ctl[bf][2] = 2; ctl[bf][3] = 1; }
-                return;
-            }
-            ++iter;
-            if (lane == 0) {
-                double gg = (d[l + 1] - d[l]) / (2.0 * e[l]);
-                double r = sqrt(gg * gg + 1.0);
-                gg = d[m] - d[l] + e[l] / (gg + (gg >= 0.0 ? r : -r));
-                double s = 1.0, c = 1.0, p = 0.0;
-                int i = m - 1;
-                double ei = e[i], di = d[i], di1 = d[i + 1];
-                double g1 = 0.0;
-                bool ok = true;
-                // The loop body has no branch of its own (a taken branch costs a single wave more than the whole
-                // dependent chain of the step): a rotation that is undefined (h underflows) is computed like any
-                // other, ends the loop, and what it stored is put right afterwards.
-                do {
-                    // the next step's elements are requested now and only looked at when this step is done
-                    const int ip = i > 0 ? i - 1 : 0;
-                    const double en = e[ip], dn = d[ip];
-                    const double f = s * ei, b = c * ei;
-                    const double h = fma(f, f, gg * gg);
-                    // s = f / r0, c = g / r0 with r0 = sqrt(h); everything that does not need 1 / r0 is formed
-                    // while it is computed, so that two operations separate it from the next step's g
-                    g1 = di1 - p;
-                    const double wr = fma(di - g1, f, 2.0 * gg * b);     // = r0 ((d_i - g1) s + 2 c b)
-                    const double ri = rsqrt_full(h);
-                    e[i + 1] = h * ri;
-                    s = f * ri;
-                    c = gg * ri;
-                    r = wr * ri;
-                    p = s * r;
-                    d[i + 1] = g1 + p;
-                    gg = fma(c, r, -b);
-                    cc[bf][i] = c;
-                    ss[bf][i] = s;
-                    di1 = di;
-                    di = dn;
-                    ei = en;
-                    ok = h > 1e-290;
-                    --i;
-                } while (ok && i >= l);
-                const bool under = !ok;
-                if (under) {                         // step i + 1 was undefined: deflate there and start over
-                    ++i;
-                    e[i + 1] = 0.0;
-                    d[i + 1] = g1;
-                    e[m] = 0.0;
-                } else {
-                    d[l] -= p;
-                    e[l] = gg;
-                    e[m] = 0.0;
-                }
-                ctl[bf][0] = m;                      // rotations exist for rows m-1 down to the bottom row
-                ctl[bf][1] = under ? i + 1 : l;
-                ctl[bf][2] = 0;
-                ctl[bf][3] = 0;
-            }
-            return;
-        }
-    };
-    if (tid < 64) produce(0);
+    // ---- 2. all eigenvalues of T by bisection, one thread per eigenvalue ----
+    // Sturm count: the number of negative pivots q_i of T - x I (q_0 = d_0 - x, q_i = d_i - x - e_{i-1}^2 / q_{i-1})
+    // is the number of eigenvalues below x; thread t halves the Gershgorin interval until it holds only the
+    // eigenvalue of rank t (descending).  A pivot below pivmin in size is replaced by -pivmin (a change of T far
+    // below its rounding).  The eigenvalues come out ordered and to the absolute accuracy of T's entries.
+    double *e2 = w, *lam_s = v;                     // LDS: squares of the off-diagonal, the ordered eigenvalues
+    if (tid < M) e2[tid] = e[tid] * e[tid];
     __syncthreads();
-    bool failed = false;
-    for (int n = 0;; ++n) {
-        const int bf = n & 1;
-        const int top = ctl[bf][0], bot = ctl[bf][1], kind = ctl[bf][2];
-        if (kind == 2) { failed = ctl[bf][3] != 0; break; }
-        if (tid < 64) {
-            produce(bf ^ 1);
-        } else if (tid < 64 + M && top > bot) {
-            const int jc = tid - 64;
-            // rows top-1 .. bot, each rotated against the row above it; row top's value is carried down.  Eight
-            // rows and their rotations are in flight at any time; the loop body has no branches (a request past
-            // the bottom row is clamped to it and its result ignored), so that nothing waits for a request it
-            // does not need yet.
-            double hi = qm[(size_t)top * M + jc];
-            double buf[8], cb[8], sb[8];
-            int i = top - 1;
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int r = max(i - u, bot);
-                buf[u] = qm[(size_t)r * M + jc];
-                cb[u] = cc[bf][r];
-                sb[u] = ss[bf][r];
-            }
-            while (i - 7 >= bot) {
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int r = i - u, rn = max(r - 8, bot);
-                    const double lo = buf[u], c = cb[u], s = sb[u];
-                    buf[u] = qm[(size_t)rn * M + jc];
-                    cb[u] = cc[bf][rn];
-                    sb[u] = ss[bf][rn];
-                    qm[(size_t)(r + 1) * M + jc] = fma(s, lo, c * hi);
-                    hi = fma(c, lo, -s * hi);
-                }
-                i -= 8;
-            }
-#pragma unroll
-            for (int u = 0; u < 7; ++u) {      // the last rows, fewer than eight
-                const int r = i - u;
-                if (r >= bot) {
-                    qm[(size_t)(r + 1) * M + jc] = fma(sb[u], buf[u], cb[u] * hi);
-                    hi = fma(cb[u], buf[u], -sb[u] * hi);
-                }
-            }
-            qm[(size_t)bot * M + jc] = hi;
-        }
-        __syncthreads();
+    double gl = INFINITY, gu = -INFINITY, emax2 = 0.0;
+    for (int i = 0; i < M; ++i) {
+        const double rad = fabs(e[i]) + (i > 0 ? fabs(e[i - 1]) : 0.0);
+        gl = fmin(gl, d[i] - rad);
+        gu = fmax(gu, d[i] + rad);
+        emax2 = fmax(emax2, e2[i]);
     }
-    if (tid < M) lam_all[(size_t)blockIdx.x * M + tid] = d[tid];
-    if (tid == 0) status_all[blockIdx.x] = failed ? 1 : 0;
-
-    // ---- 4. the requested eigenvectors of G: x = H_0 ... H_{M-3} z for the rows z of ranks first .. first + dvec - 1 ----
-    // rank of eigenvalue j = how many are larger (ties broken by index; negative rounding noise counts as zero): the
-    // order the caller's post-processing uses.  One wave per vector, the vector in registers (lane l holds the
-    // elements l, l + 64, ...), the reflector's row requested one step ahead.
-    int *row_of = reinterpret_cast<int *>(&part[0][0]);
+    const double tnorm = fmax(fabs(gl), fabs(gu));
+    const double pivmin = fmax(4.9e-32 * emax2, 1e-290);
     if (tid < M) {
-        const double lj = fmax(d[tid], 0.0);
-        int rank = 0;
-        for (int i = 0; i < M; ++i) {
-            const double li = fmax(d[i], 0.0);
-            rank += (li > lj || (li == lj && i < tid)) ? 1 : 0;
+        const int idx = M - 1 - tid;                // rank from below
+        double lo = gl - 1e-15 * tnorm - pivmin, hi = gu + 1e-15 * tnorm + pivmin;
+        for (int it = 0; it < 60; ++it) {
+            const double x = 0.5 * (lo + hi);
+            double q = d[0] - x;
+            int cnt = q < 0.0 ? 1 : 0;
+#pragma unroll 4
+            for (int i = 1; i < M; ++i) {
+                if (fabs(q) < pivmin) q = -pivmin;
+                double r = __builtin_amdgcn_rcp(q);
+                r = r * fma(-q, r, 2.0);            // one Newton step: 1 / q to fp64
+                q = fma(-e2[i - 1], r, d[i] - x);
+                cnt += q < 0.0 ? 1 : 0;
+            }
+            if (cnt > idx) hi = x; else lo = x;
         }
-        row_of[rank] = tid;
+        const double lam = 0.5 * (lo + hi);
+        lam_s[tid] = lam;
+        lam_all[(size_t)blockIdx.x * M + tid] = lam;
     }
     __syncthreads();
+    if (tid == 0) {
+        bool bad = false;
+        for (int i = 0; i < M; ++i) bad |= !(fabs(lam_s[i]) <= 1e300);
+        status_all[blockIdx.x] = bad ? 1 : 0;
+    }
+
+    // ---- 3. the requested eigenvectors of T, one thread per vector: twisted factorisation ----
+    // For the eigenvalue lambda: the pivots q+ of T - lambda I from the top (as above) and q- from the bottom;
+    // gamma_k = q+_k + q-_k - (d_k - lambda) is what is left of row k when everything above is eliminated from the
+    // top and everything below from the bottom, and z with z_k = 1, z_{i-1} = -e_{i-1} z_i / q+_{i-1} above k,
+    // z_{i+1} = -e_i z_i / q-_{i+1} below k solves every row of (T - lambda I) z = 0 but row k, whose residual
+    // is gamma_k: with k at the smallest |gamma| the residual is of the size of lambda's error.
+    double *qp_all = qm, *qn_all = qm + (size_t)M * dvec;     // [i][c]: neighbouring threads, neighbouring addresses
+    double *z_all = vec_all + (size_t)blockIdx.x * dvec * M;   // [c][i]
+    auto guard = [&](double q) { return fabs(q) < pivmin ? -pivmin : q; };
+    // the vector of eigenvalue lam from the stored pivots of thread c, twisted at k; returns its norm
+    auto build_vector = [&](int c, int k) {
+        double *z = z_all + (size_t)c * M;
+        z[k] = 1.0;
+        double n2 = 1.0, zi = 1.0;
+        for (int i = k - 1; i >= 0; --i) {
+            zi = -e[i] * zi / guard(qp_all[(size_t)i * dvec + c]);
+            if (fabs(zi) > 1e150) {              // rescale what is there (rare: a run of tiny pivots)
+                for (int j = i + 1; j <= k; ++j) z[j] *= 1e-150;
+                zi *= 1e-150;
+                n2 *= 1e-300;
+            }
+            z[i] = zi;
+            n2 = fma(zi, zi, n2);
+        }
+        zi = z[k];
+        for (int i = k + 1; i < M; ++i) {
+            zi = -e[i - 1] * zi / guard(qn_all[(size_t)i * dvec + c]);
+            if (fabs(zi) > 1e150) {
+                for (int j = 0; j < i; ++j) z[j] *= 1e-150;
+                zi *= 1e-150;
+                n2 *= 1e-300;
+            }
+            z[i] = zi;
+            n2 = fma(zi, zi, n2);
+        }
+        const double inv = 1.0 / sqrt(n2);
+        for (int i = 0; i < M; ++i) z[i] *= inv;
+    };
+    auto gamma_at = [&](int c, int i, double lam) {
+        return qp_all[(size_t)i * dvec + c] + qn_all[(size_t)i * dvec + c] - (d[i] - lam);
+    };
+    if (tid < dvec && first + tid < M) {
+        const int c = tid;
+        const double lam = lam_s[first + c];
+        double q = d[0] - lam;
+        for (int i = 1; i < M; ++i) {
+            q = guard(q);
+            qp_all[(size_t)(i - 1) * dvec + c] = q;
+            q = (d[i] - lam) - e2[i - 1] / q;
+        }
+        qp_all[(size_t)(M - 1) * dvec + c] = q;
+        q = d[M - 1] - lam;
+        for (int i = M - 2; i >= 0; --i) {
+            q = guard(q);
+            qn_all[(size_t)(i + 1) * dvec + c] = q;
+            q = (d[i] - lam) - e2[i] / q;
+        }
+        qn_all[(size_t)0 * dvec + c] = q;
+        int k = 0;
+        double best = INFINITY;
+        for (int i = 0; i < M; ++i) {
+            const double gmm = fabs(gamma_at(c, i, lam));
+            if (gmm < best) { best = gmm; k = i; }
+        }
+        build_vector(c, k);
+    }
+    __syncthreads();
+    // Eigenvalues that agree to 1e-12 |T| (T splits, or nearly: only then can eigenvalues of a tridiagonal matrix
+    // coincide): the recipe above may give them the same vector.  One thread goes over such runs in order: a later
+    // vector of a run is twisted at the smallest |gamma| among the rows where the earlier ones are small, and made
+    // orthogonal to them.
+    if (tid == 0) {
+        for (int c = 1; c < dvec && first + c < M; ++c) {
+            int c0 = c;
+            while (c0 > 0 && fabs(lam_s[first + c0 - 1] - lam_s[first + c]) <= 1e-12 * tnorm) --c0;
+            if (c0 == c) continue;
+            const double lam = lam_s[first + c];
+            int k = -1;
+            double best = INFINITY;
+            for (int i = 0; i < M; ++i) {
+                double seen = 0.0;
+                for (int p = c0; p < c; ++p) seen = fmax(seen, fabs(z_all[(size_t)p * M + i]));
+                const double gmm = fabs(gamma_at(c, i, lam));
+                if (seen < 1e-3 && gmm < best) { best = gmm; k = i; }
+            }
+            if (k >= 0) build_vector(c, k);
+            double *z = z_all + (size_t)c * M;
+            for (int p = c0; p < c; ++p) {
+                const double *zp = z_all + (size_t)p * M;
+                double dot = 0.0;
+                for (int i = 0; i < M; ++i) dot = fma(zp[i], z[i], dot);
+                for (int i = 0; i < M; ++i) z[i] = fma(-dot, zp[i], z[i]);
+            }
+            double n2 = 0.0;
+            for (int i = 0; i < M; ++i) n2 = fma(z[i], z[i], n2);
+            if (n2 > 1e-16) {
+                const double inv = 1.0 / sqrt(n2);
+                for (int i = 0; i < M; ++i) z[i] *= inv;
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- 4. the eigenvectors of G: x = H_0 ... H_{M-3} z, one wave per vector ----
+    // The vector in registers (lane l holds the elements l, l + 64, ...), the reflector's row requested one step ahead.
     constexpr int NE = CP / 64;
     const int lane = tid & 63, wave = tid >> 6;
     for (int c = wave; c < dvec; c += kEigThreads / 64) {
@@ -405,7 +368,7 @@ __global__ __launch_bounds__(kEigThreads) void eigen_kernel(double *__restrict__
                 if (lane + 64 * i < M) out[lane + 64 * i] = 0.0;
             continue;
         }
-        const double *z = qm + (size_t)row_of[rk] * M;
+        const double *z = out;                        // step 3 left the eigenvector of T there
         double y[NE], v[NE], vn[NE];
 #pragma unroll
         for (int i = 0; i < NE; ++i) {
@@ -492,14 +455,17 @@ Split spectral_split(const flare_shape &s)
     return plan_split(s.N, s.B * s.H, 256, mfma_gram_supported(s) ? 512 : 1024);
 }
 
+// doubles per (b,h) for the pivots of the twisted factorisations: two arrays of M per requested vector
+static size_t pivot_elems(const flare_shape &s) { return 2 * (size_t)s.M * s.d; }
+
 size_t spectral_bytes(const flare_shape &s)
 {
     const size_t BH = (size_t)s.B * s.H, mm = (size_t)s.M * s.M;
     const Split sp = spectral_split(s);
-    // partial G's; two fp64 matrices per (b,h) (G, then its reflectors; the rotated identity); eigenvalues; solver
-    // status; the d requested eigenvectors
-    return align256(BH * sp.chunks * mm * 4) + 2 * align256(BH * mm * 8) + align256(BH * s.M * 8) + align256(BH * 4) +
-           align256(BH * s.d * s.M * 8);
+    // partial G's; one fp64 matrix per (b,h) (G, then its reflectors); the pivots of the requested vectors;
+    // eigenvalues; solver status; the d requested eigenvectors
+    return align256(BH * sp.chunks * mm * 4) + align256(BH * mm * 8) + align256(BH * pivot_elems(s) * 8) +
+           align256(BH * s.M * 8) + align256(BH * 4) + align256(BH * s.d * s.M * 8);
 }
 
 int spectral_run(const flare_shape &s, const void *q, const void *k, const float *lse_enc, const float *lse_dec,
@@ -511,7 +477,7 @@ int spectral_run(const flare_shape &s, const void *q, const void *k, const float
     float *g_part = reinterpret_cast<float *>(base);
     double *a = reinterpret_cast<double *>(base + align256(BH * sp.chunks * mm * 4));
     double *qbuf = reinterpret_cast<double *>(reinterpret_cast<char *>(a) + align256(BH * mm * 8));
-    double *lam = reinterpret_cast<double *>(reinterpret_cast<char *>(qbuf) + align256(BH * mm * 8));
+    double *lam = reinterpret_cast<double *>(reinterpret_cast<char *>(qbuf) + align256(BH * pivot_elems(s) * 8));
     int *status = reinterpret_cast<int *>(reinterpret_cast<char *>(lam) + align256(BH * s.M * 8));
     double *vec = reinterpret_cast<double *>(reinterpret_cast<char *>(status) + align256(BH * 4));
     if (mfma_gram_supported(s)) {

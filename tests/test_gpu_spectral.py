@@ -122,3 +122,44 @@ def test_spectral_million_tokens(oracle):
              % (h, e_g, e_l, res.max(), flat, lam[d - 1]))
         assert e_g <= 3e-3 and e_l <= 3e-3
         assert res.max() <= 1e-2 and flat <= 1e-2
+
+
+def test_spectral_repeated_eigenvalues(oracle):
+    """Two groups of latents and tokens that do not see each other (their scores differ by 162: the weights
+    between the groups are 1e-70 of the others, zero in fp32) and are copies of one another: W is block diagonal
+    with two equal blocks, every eigenvalue is double.  Each returned vector must still satisfy W x = lambda x, and the vectors of a
+    pair must span the pair's eigenspace (here: be orthogonal), not coincide."""
+    import torch
+    rng = np.random.default_rng(77)
+    M, N, d = 16, 200, 4
+    q0 = rng.standard_normal((M // 2, d - 1)).astype(np.float32)
+    k0 = rng.standard_normal((N // 2, d - 1)).astype(np.float32)
+    off = 9.0      # (much larger and exp(-lse_enc / 2), a factor of the fp32 block z_vec, would underflow)
+    q = np.concatenate([np.concatenate([q0, np.full((M // 2, 1), off, np.float32)], 1),
+                        np.concatenate([q0, np.full((M // 2, 1), -off, np.float32)], 1)], 0)[None]      # [1, M, d]
+    k = np.concatenate([np.concatenate([k0, np.full((N // 2, 1), off, np.float32)], 1),
+                        np.concatenate([k0, np.full((N // 2, 1), -off, np.float32)], 1)], 0)[None, None]  # [1, 1, N, d]
+    v = rng.standard_normal((1, 1, N, d)).astype(np.float32)
+    scale = 1.0
+    _say("spectral with every eigenvalue double: M=%d N=%d d=%d, groups %g apart in the last coordinate" % (M, N, d, off))
+    dev = {n: torch.from_numpy(x).cuda() for n, x in (("q", q), ("k", k), ("v", v))}
+    lse_dec = torch.empty((1, 1, N), dtype=torch.float32, device="cuda")
+    _, _, lse_enc = binding.forward(dev["q"], dev["k"], dev["v"], scale, lse_dec=lse_dec)
+    lam, _, _ = oracle.spectral(q[0], k[0, 0], scale)
+    _, _, w = oracle.explicit_w(q[0], k[0, 0], scale)
+    assert np.abs(lam[0::2] - lam[1::2]).max() <= 1e-12          # the oracle's eigenvalues come in pairs
+    for first in (0, 4):
+        ev, zv, _ = binding.spectral(dev["q"], dev["k"], lse_enc, lse_dec, scale, first=first)
+        x = to_host(binding.decode(dev["q"], dev["k"], zv, scale))[0, 0].astype(np.float64)   # [N, d]
+        torch.cuda.synchronize()
+        assert np.abs(to_host(ev)[0, 0] - lam).max() <= 2e-5
+        x = x / np.linalg.norm(x, axis=0, keepdims=True)
+        res = np.linalg.norm(w @ x - x * lam[None, first:first + d], axis=0)
+        gram = x.T @ x
+        _say("   first %d: residuals max %.2e  smallest singular value of the block %.3f" %
+             (first, res.max(), np.linalg.svd(x, compute_uv=False).min()))
+        assert res.max() <= 2e-4
+        # the two vectors of a pair live on different groups of tokens (eigenvectors of different eigenvalues of
+        # the non-symmetric W need not be orthogonal); all four are linearly independent
+        assert abs(gram[0, 1]) <= 1e-3 and abs(gram[2, 3]) <= 1e-3
+        assert np.linalg.svd(x, compute_uv=False).min() >= 0.5
