@@ -25,13 +25,17 @@ def _say(msg):
 CASES = [
     # dtype, B, H, N, M, d, tolerance on eigenvalues and G (absolute / relative), on the residual
     ("f32", 1, 2, 300, 24, 8, 2e-5, 2e-4),
-    ("f32", 2, 1, 257, 7, 4, 2e-5, 2e-4),       # odd M: one idle pair per Jacobi round
+    ("f32", 2, 1, 257, 7, 4, 2e-5, 2e-4),       # odd M, fewer latents than a wave has lanes
     ("bf16", 1, 2, 700, 64, 16, 3e-3, 1e-2),    # matrix-core Gram kernel
     ("bf16", 1, 1, 1500, 256, 16, 3e-3, 1e-2),
     ("bf16", 1, 2, 515, 128, 32, 3e-3, 1e-2),
     ("bf16", 1, 1, 333, 32, 8, 3e-3, 1e-2),
     ("bf16", 1, 1, 400, 96, 16, 3e-3, 1e-2),    # bf16 storage on the vector-ALU Gram kernel
     ("f16", 1, 2, 500, 64, 16, 3e-3, 1e-2),     # fp16 storage: matrix-core forward, vector-ALU Gram kernel
+    ("f32", 1, 1, 50, 1, 4, 2e-5, 2e-4),        # fewer latents than the solver has phases for: 1, 2, 3
+    ("f32", 1, 2, 61, 2, 4, 2e-5, 2e-4),
+    ("f32", 2, 1, 77, 3, 8, 2e-5, 2e-4),
+    ("f32", 1, 1, 900, 300, 8, 5e-5, 5e-4),     # more than 256 latents: the solver's 512-column instance
 ]
 
 
