@@ -149,14 +149,20 @@ int mfma_dz_partial(const flare_shape &s, const void *q, const void *k, const vo
 // The dQ and dK/dV kernels exist in two variants, one and two exponentials per score.  Both are
 // launched; each leaves at once the (b,h) slices that plan[b*h] (1 = one exponential) gives to the
 // other.  ld_range[b*h][part] = (min, max) of lse_dec2 as mfma_dz_partial recorded it.
-// plan[bh] = 1 iff, with kappa = max_m lse_enc2[m], every u[m] = 2^(lse_enc2[m] - kappa) >= 2^-kPlanSpan and
-// every w[n] = 2^(kappa - lse_dec2[n]) lies in [2^-kPlanSpan, 2^kPlanSpan].  Then wherever
-// R = P u w is above 2^-(126 - 2 kPlanSpan), P is a normal fp32 number and nothing is lost; anything
-// else (wide score ranges, non-finite statistics) takes the two-exponential kernels.
-// Called by one whole wave (of the kernel that merges the dZ partials: everything it reads is complete by then).
-constexpr float kPlanSpan = 50.f;
-__device__ __forceinline__ void bwd_plan_wave(const float *__restrict__ ld_range, const float *__restrict__ lse_enc,
-                                              int *__restrict__ plan, int bh, int parts, int M, int force_two)
+// One exponential: P~ = 2^S2 as it comes, without a normaliser (S2 <= lse_enc2[m] and S2 <= lse_dec2[n], so with
+// both log-sum-exps of a (b,h) within +-kPlanSpan nothing overflows and every weight that matters is a normal
+// number), P = P~ e_m with e_m = 2^-lse_enc2[m] and R = P~ w_n with w_n = 2^-lse_dec2[n]:
+//   dS = P (a - eps) + R (c - delta) = P~ (e_m (a - eps_m) + w_n (c - delta_n)),   dV += (e_m dZ_m) P~.
+// e_m is folded into dZ where its partials are merged, BEFORE dZ is rounded to bf16 and eps = <dZ, Z> is formed
+// (bwd_one_exp_ok decides there, and the kernels that follow take dZ and eps as they find them), so that a and
+// eps still see the same rounded values and the score products need no correction k-step; w_n is a per-token
+// scalar.  Anything else (log-sum-exps beyond +-kPlanSpan, non-finite statistics) takes the two-exponential
+// kernels with dZ as it is.
+// Called by one whole wave (of the kernel that merges the dZ partials: everything it reads is complete by
+// then); every lane returns the same answer.
+constexpr float kPlanSpan = 60.f;
+__device__ __forceinline__ bool bwd_one_exp_ok(const float *__restrict__ ld_range, const float *__restrict__ lse_enc,
+                                               int bh, int parts, int M, int force_two)
 {
     const int lane = threadIdx.x & 63;
     float le_min = INFINITY, le_max = -INFINITY, ld_min = INFINITY, ld_max = -INFINITY;
@@ -176,12 +182,9 @@ __device__ __forceinline__ void bwd_plan_wave(const float *__restrict__ ld_range
         ld_min = fminf(ld_min, __shfl_xor(ld_min, off));
         ld_max = fmaxf(ld_max, __shfl_xor(ld_max, off));
     }
-    if (lane == 0) {
-        // written so that a NaN anywhere makes the test fail
-        const bool ok = (le_max - le_min <= kPlanSpan) && (le_max - ld_min <= kPlanSpan) &&
-                        (ld_max - le_max <= kPlanSpan) && fabsf(le_max) < 1e30f;
-        plan[bh] = (ok && !force_two) ? 1 : 0;
-    }
+    // written so that a NaN anywhere makes the test fail
+    const bool ok = (le_max <= kPlanSpan) && (le_min >= -kPlanSpan) && (ld_max <= kPlanSpan) && (ld_min >= -kPlanSpan);
+    return ok && !force_two;
 }
 
 // ---- spectral analysis (Appendix C.1, Algorithm 1) ---------------------------------------------

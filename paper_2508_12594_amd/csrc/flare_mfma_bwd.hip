@@ -20,12 +20,13 @@ namespace {
 // with K^T read back from a wave-private, double-buffered LDS tile.  Masked tokens have both
 // exponents at -inf, so their dS is exactly zero.
 //
-// ONE = true is the variant with one exponential per score.  With kappa = max_m lse_enc2[m],
-//     R[n][m] = P[m][n] * u[m] * w[n],   u[m] = 2^(lse_enc2[m] - kappa),  w[n] = 2^(kappa - lse_dec2[n]),
-// so dS^T = P * (a + w[n] * u[m] c): u is folded into the Z operand (and multiplies delta in the
-// correction k-step), w[n] is a per-row factor that goes from the token's lane to the rows of
-// the accumulator layout through 128 bytes of LDS.  It is exact as long as u, w and P stay in
-// fp32 range wherever R matters, which bwd_plan_wave guarantees per (b,h) (plan[bh] = 1);
+// ONE = true is the variant with one exponential per score, P~ = 2^S2 without a normaliser:
+//     P = P~ e[m],  R = P~ w[n],   e[m] = 2^-lse_enc2[m],  w[n] = 2^-lse_dec2[n],
+// so dS^T = P~ (e[m] (a - eps) + w[n] (c - delta)).  e[m] arrives folded into dZ and eps (the kernel that merges
+// the dZ partials scales dZ before it rounds it and forms eps), so the a chain needs nothing new and the score
+// products need no correction k-step; w[n] is a per-row factor that goes from the token's lane to the rows of
+// the accumulator layout through 128 bytes of LDS (and multiplies delta in the correction k-step).  It is exact
+// as long as both log-sum-exps stay within +-60, which bwd_one_exp_ok checks per (b,h) (plan[bh] = 1);
 // otherwise the ONE = false variant runs.  Each variant returns at once when the plan names the other.
 // ============================================================================================
 template <int DR, int NB, int MINB, bool ONE, bool F>
@@ -60,13 +61,7 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
     const bool lower = hh == 0;
     uint16_t *lds = kt_all[wave];
     float (*wl)[32] = wl_all[ONE ? wave : 0];
-    float kap = 0.f;
-    if constexpr (ONE) {
-        kap = -INFINITY;
-        for (int m = lane; m < M; m += 64) kap = fmaxf(kap, lse_enc[(size_t)bh * M + m] * kLog2e);
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) kap = fmaxf(kap, __shfl_xor(kap, off));
-    }
+    constexpr float kap = 0.f;                  // w[n] = 2^(kap - lse_dec2[n])
     if (lane < kVtStride) {
         lds[D * kVtStride + lane] = 0;
         lds[BUF + D * kVtStride + lane] = 0;
@@ -95,7 +90,7 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
             for (int ks = 0; ks < KS; ++ks) { qh[b][ks] = zero_operand(); ql[b][ks] = zero_operand(); }
         }
         const float le2 = real ? lse_enc[(size_t)bh * M + m] * kLog2e : 0.f;
-        const float um = ONE ? fast_exp2(le2 - kap) : 1.f;   // folded into Z
+        const float um = 1.f;                       // (a per-latent factor of the c chain: none in either variant)
         if constexpr (ONE) {
             const uint32_t us = split_bf16_pair(um);          // slots 0,1,2 := u hi, u hi, u lo
             u32x4 wu;
@@ -292,7 +287,8 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
 #pragma unroll
                     for (int ks = 0; ks < KS; ++ks) x = mfma_s<F>(kt[ks], ql[b][ks], x);
                 }
-                f32x16 s1 = mfma_s<F>(kt_a, q_aug[b], x);
+                f32x16 s1 = x;                  // one exponential: the scores as they are
+                if constexpr (!ONE) s1 = mfma_s<F>(kt_a, q_aug[b], x);
                 f32x16 s2 = s1;
                 if constexpr (!ONE) s2 = mfma_s<F>(kt_b, q_aug[b], x);
                 f32x16 av = splat16(0.f), cv = splat16(0.f);
@@ -450,13 +446,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     const int bh = gp.y, h = bh % H;
     const bool lower = hh == 0;
     if ((plan[bh] != 0) != ONE) return;         // the other variant owns this (b,h); uniform over the workgroup
-    float kap = 0.f;
-    if constexpr (ONE) {
-        kap = -INFINITY;
-        for (int m = lane; m < Mtot; m += 64) kap = fmaxf(kap, lse_enc[(size_t)bh * Mtot + m] * kLog2e);
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) kap = fmaxf(kap, __shfl_xor(kap, off));
-    }
+    constexpr float kap = 0.f;                  // w[n] = 2^(kap - lse_dec2[n])
 
     // ---- build the operand images ----
     {
@@ -486,7 +476,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                 // (and the a and c products meet slots 0-3 with zeros).  u <= 1 and finite 16-bit patterns of either type read as finite values
                 // of the other, so the foreign slots contribute exact zeros.
                 if constexpr (ONE) {   // slots 4,5,6 := u hi, u hi, u lo
-                    const uint32_t us = split_bf16_pair(real ? fast_exp2(le2 - kap) : 0.f);
+                    const uint32_t us = split_bf16_pair(real ? 1.f : 0.f);   // (the latent's factor of the c chain: 1)
                     w[2] = hf == 0 ? ((us & 0xffffu) | (us << 16)) : 0u;
                     w[3] = hf == 0 ? (us >> 16) : 0u;
                 }
@@ -507,9 +497,6 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                 } else {
                     const bool is_z = kind >= 3;
                     row8_f32<DR>((is_z ? zb : dzb) + (size_t)m * DR, (ZPACK && is_z) ? 0 : d0, x);
-                    const float um = (ONE && is_z) ? fast_exp2(leb[m] * kLog2e - kap) : 1.f;
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) x[i] *= um;
                 }
                 if (!real) {
 #pragma unroll
@@ -548,7 +535,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                 if (PACK && hf == 1 && kind == 2 && real) w[0] = split_bf16_pair(-eb[m]);   // slots 8,9 := -eps
                 if (PACK && !ZPACK && hf == 1 && kind == 3 && real) {                // slots 8,9,10 := u, u, u lo / 1, 1
                     if constexpr (ONE) {
-                        const uint32_t us = split_bf16_pair(fast_exp2(leb[m] * kLog2e - kap));
+                        const uint32_t us = split_bf16_pair(1.f);
                         w[0] = (us & 0xffffu) | (us << 16);
                         w[1] = us >> 16;
                     } else {
@@ -722,9 +709,13 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) x = mfma_s<F>(image(t, 1 * KS + ks), kt[ks], x);
             }
-            const bf16x8 qa = image(t, NA - 1);
-            s1 = mfma_s<F>(qa, kt_a, x);
-            if constexpr (!ONE) s2 = mfma_s<F>(qa, kt_b, x);
+            if constexpr (ONE) {
+                s1 = x;                         // one exponential: the scores as they are
+            } else {
+                const bf16x8 qa = image(t, NA - 1);
+                s1 = mfma_s<F>(qa, kt_a, x);
+                s2 = mfma_s<F>(qa, kt_b, x);
+            }
         };
         // One latent tile, software-pipelined: the a and c products of tile t and the score products
         // of tile t+1 are issued first and run on the matrix cores while the vector ALUs

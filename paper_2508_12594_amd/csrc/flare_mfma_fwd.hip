@@ -415,7 +415,7 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
 // every wave also forms delta[n] = <dY_n, Y_n> from the rows it streams anyway (no branch in the
 // loop), and the waves of latent group 0 store it to delta_out for the two kernels that follow.
 // Those waves also record the smallest and largest lse_dec2 they met, ld_range[part] = (min, max),
-// from which bwd_plan_wave decides which variant of the next two kernels may run.
+// from which bwd_one_exp_ok decides which variant of the next two kernels may run.
 template <int DR, int NB, int MINB, int MODE, bool F, bool Y32 = false>
 __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,

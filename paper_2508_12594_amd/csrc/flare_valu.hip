@@ -492,9 +492,17 @@ __global__ __launch_bounds__(256) void dz_merge_kernel(
     const int j = threadIdx.x & 15;
     const int m = blockIdx.x * 16 + (threadIdx.x >> 4);
     const int bh = blockIdx.y;
-    // matrix-core path: one more workgroup per (b,h) decides which variant of the next kernels runs
+    // matrix-core path: which variant of the next kernels runs for this (b,h) (every workgroup works it out for
+    // itself: the one-exponential variant wants dZ scaled, see bwd_one_exp_ok); one more workgroup records it
+    __shared__ int one_exp_s;
+    if (threadIdx.x < 64) {
+        const bool ok = plan != nullptr && bwd_one_exp_ok(ld_range, lse_enc, bh, parts, M, force_two);
+        if (threadIdx.x == 0) one_exp_s = ok ? 1 : 0;
+    }
+    __syncthreads();
+    const bool one_exp = one_exp_s != 0;
     if (plan != nullptr && blockIdx.x == gridDim.x - 1) {
-        if (threadIdx.x < 64) bwd_plan_wave(ld_range, lse_enc, plan, bh, parts, M, force_two);
+        if (threadIdx.x == 0) plan[bh] = one_exp ? 1 : 0;
         return;
     }
     const bool live = m < M;
@@ -502,6 +510,11 @@ __global__ __launch_bounds__(256) void dz_merge_kernel(
     sum_slots<D>(dz_part, bh, BH, 1, parts, M, live ? m : M - 1, j, acc);
     if (!live || j != 0) return;
     const size_t idx = (size_t)bh * M + m;
+    if (one_exp) {
+        const float em = exp2f(-lse_enc[idx] * 1.4426950408889634f);
+#pragma unroll
+        for (int i = 0; i < D; ++i) acc[i] *= em;
+    }
     if (round_bf16) {
         // The matrix-core kernels take dZ as a bf16 operand.  Rounding it here, before eps is formed,
         // keeps a[m][n] = <dZ_m, V_n - Z_m> an exact expression in the rounded dZ (eps and the products
@@ -545,12 +558,24 @@ __global__ __launch_bounds__(256) void dz_merge_few_kernel(
     const int j = threadIdx.x % L;
     const int m = blockIdx.x * ROWS + threadIdx.x / L;
     const int bh = blockIdx.y;
+    __shared__ int one_exp_s;                        // as in dz_merge_kernel
+    if (threadIdx.x < 64) {
+        const bool ok = plan != nullptr && bwd_one_exp_ok(ld_range, lse_enc, bh, parts, M, force_two);
+        if (threadIdx.x == 0) one_exp_s = ok ? 1 : 0;
+    }
+    __syncthreads();
+    const bool one_exp = one_exp_s != 0;
     if (plan != nullptr && blockIdx.x == gridDim.x - 1) {
-        if (threadIdx.x < 64) bwd_plan_wave(ld_range, lse_enc, plan, bh, parts, M, force_two);
+        if (threadIdx.x == 0) plan[bh] = one_exp ? 1 : 0;
         return;
     }
     const bool live = m < M;                         // no early exit: the row's lanes meet in the shuffles below
     float2 a = sum_slots_few<D>(dz_part, bh, BH, 1, parts, M, live ? m : M - 1, j);
+    if (one_exp) {                                   // the one-exponential kernels take dZ scaled by 2^-lse_enc2[m]
+        const float em = exp2f(-lse_enc[(size_t)bh * M + (live ? m : M - 1)] * 1.4426950408889634f);
+        a.x *= em;
+        a.y *= em;
+    }
     if (round_bf16) {                                // as in dz_merge_kernel: round before eps is formed
         uint32_t u = __float_as_uint(a.x);
         u += 0x7fffu + ((u >> 16) & 1u);
