@@ -437,6 +437,26 @@ def test_backward_wide_score_range_picks_variant_per_head(oracle):
             assert e["dk"] <= (TOL["bf16"] if h == 0 else 1e-1)
 
 
+@pytest.mark.parametrize("key0", [15.0, 21.0])
+def test_backward_with_every_score_shifted(oracle, key0):
+    """All scores of head 1 are shifted by one large constant (first query coordinate 8, first key coordinate
+    key0): both log-sum-exps sit at about 55 (key0 = 15) or 72 (key0 = 21) log2 units, either side of the limit
+    up to which the one-exponential kernels work with weights 2^S that carry no normaliser.  Head 0 is ordinary.
+    Gradients within tolerance on both sides of the limit, with saved and with recomputed statistics."""
+    _say("backward, scores of one head shifted: first key coordinate %g" % key0)
+    inp = synth.make_inputs(2, B=1, H=2, N=1500, M=64, d=16, with_dy=True)
+    q, k = inp["q"].copy(), inp["k"].copy()
+    q[1, :, 0] = 8.0
+    k[:, 1, :, 0] = key0
+    inp["q"], inp["k"] = synth.bf16_round(q), synth.bf16_round(k)
+    _, _, lse = oracle.forward(inp["q"], inp["k"], inp["v"], inp["scale"])
+    level = lse[0].mean(axis=1) * np.log2(np.e)
+    _say("   lse_enc (log2 units) per head: %s" % np.round(level, 1))
+    assert abs(level[0]) < 30 and ((50 < level[1] < 60) if key0 == 15.0 else (65 < level[1] < 80))
+    _backward_case(oracle, inp, saved=True)
+    _backward_case(oracle, inp, saved=False)
+
+
 @pytest.mark.parametrize("M,d", [(64, 16), (256, 16), (128, 32), (256, 32), (64, 8)])
 def test_keys_huge_where_every_latent_is_zero(oracle, M, d):
     """Every other token has a key that is huge in the dimensions where all latent queries are zero: the
