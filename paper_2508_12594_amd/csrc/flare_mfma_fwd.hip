@@ -434,6 +434,9 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     // stride that keeps the 16-byte stores aligned.  The operand wants it transposed (row = column of V, eight
     // tokens per lane): that is what the transposing LDS read delivers.
     constexpr int RS = D + 16 + 8;              // uint16 per row
+    // dZ kernel, d <= 16 (four latent tiles per token tile): -lse_dec2 of the tokens is what the score accumulators
+    // start from; at d = 32 (two latent tiles, 250 registers) it rides in a correction k-step, which is faster there
+    constexpr bool CINIT = MODE == 1 && D == 16;
     constexpr bool PACK = pack_dim(DR);         // q' hi | lo in one operand, keys repeated in both lane halves
     constexpr int BUF = 32 * RS;                // uint16 per buffer
     __shared__ __attribute__((aligned(16))) uint16_t vt_all[4][2 * BUF];
@@ -535,40 +538,42 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
                 va[hv][s2] = as_bf16x8(w);
             }
     };
-    u32x4 w23;
-    w23[0] = 0u; w23[1] = hh == 0 ? kOnePair<F> : 0u; w23[2] = 0u; w23[3] = 0u;
-    const bf16x8 ones23 = as_bf16x8(w23);      // query side of the correction k-step: slots 2,3 = 1
     // scores minus the stabiliser of latent tile b against the token tile (kk; kk0a = key side of the correction k-step)
     // (plain: without the correction k-step -- the encode's sweep that needs no stabiliser)
-    auto qk = [&](int b, const bf16x8 (&kk)[KS], bf16x8 kk0a, bool plain) {
-        f32x16 r = splat16(0.f);
+    u32x4 w23;
+    w23[0] = 0u; w23[1] = hh == 0 ? kOnePair<F> : 0u; w23[2] = 0u; w23[3] = 0u;
+    const bf16x8 ones23 = as_bf16x8(w23);      // query side of the dZ kernel's correction k-step (d = 32): slots 2,3 = 1
+    // c0: what the score accumulators start from -- zero, or (CINIT) minus lse_dec2 of the register's token, which
+    // then needs no correction k-step
+    auto qk = [&](int b, const bf16x8 (&kk)[KS], bf16x8 kk0a, bool plain, const f32x16 &c0) {
+        f32x16 r = c0;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) r = mfma_s<F>(kk[ks], qh[b][ks], r);
         if constexpr (!PACK) {
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) r = mfma_s<F>(kk[ks], ql[b][ks], r);
         }
-        if (!plain) r = mfma_s<F>(kk0a, MODE == 0 ? caug[MODE == 0 ? b : 0] : ones23, r);
+        if (!CINIT && !plain) r = mfma_s<F>(kk0a, MODE == 0 ? caug[MODE == 0 ? b : 0] : ones23, r);
         return r;
     };
     // The same in two parts (d = 16, q' as a hi + lo pair), for the tiles that spread their matrix instructions:
     // the correction k-step and the hi product first, the lo product on top of them later.
-    auto qk_first = [&](int b, const bf16x8 (&kk)[KS], bf16x8 kk0a, bool plain) {
-        f32x16 r = splat16(0.f);
-        if (!plain) r = mfma_s<F>(kk0a, MODE == 0 ? caug[MODE == 0 ? b : 0] : ones23, r);
+    auto qk_first = [&](int b, const bf16x8 (&kk)[KS], bf16x8 kk0a, bool plain, const f32x16 &c0) {
+        f32x16 r = c0;
+        if (!CINIT && !plain) r = mfma_s<F>(kk0a, MODE == 0 ? caug[MODE == 0 ? b : 0] : ones23, r);
         return mfma_s<F>(kk[0], qh[b][0], r);
     };
     auto qk_second = [&](int b, const bf16x8 (&kk)[KS], f32x16 r) { return mfma_s<F>(kk[0], ql[b][0], r); };
     // The same at d = 32 in four parts: part 0 the correction k-step (unless plain) and the hi product's k-step 0,
     // part 1 its k-step 1, parts 2 and 3 the lo product's k-steps.
     auto qk_part = [&](int b, const bf16x8 (&kk)[KS], bf16x8 kk0a, bool plain, int part, f32x16 r) {
-        if (part == 0 && !plain) r = mfma_s<F>(kk0a, MODE == 0 ? caug[MODE == 0 ? b : 0] : ones23, r);
+        if (!CINIT && part == 0 && !plain) r = mfma_s<F>(kk0a, MODE == 0 ? caug[MODE == 0 ? b : 0] : ones23, r);
         return mfma_s<F>(kk[part % KS], part < 2 ? qh[b][part % KS] : ql[b][part % KS], r);
     };
     const uint32_t one0 = hh == 0 ? kOne<F> : 0u;
     const float *lb = (MODE == 1) ? lse_dec2 + (size_t)bh * N : nullptr;
-    // Key operand of the correction k-step.  MODE 0: slot 0 := 1, else zero.  MODE 1: zero except
-    // slots 2,3 := -lse_dec2 of this lane's token (hi + lo pair).
+    // Key operand of the correction k-step.  MODE 0: slot 0 := 1, else zero.  MODE 1 (where it is used: d = 32): zero
+    // except slots 2,3 := -lse_dec2 of this lane's token (hi + lo pair).
     auto k_aug = [&](bf16x8 k0, float neg_lse) {
         if constexpr (MODE == 0) return with_slot0(as_bf16x8(wzero), keep0, one0);
         else {
@@ -578,9 +583,33 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
             return as_bf16x8(w);
         }
     };
-    auto load_lse = [&](int j) {
+    auto load_lse = [&](int j) {   // -lse_dec2 of this lane's token (MODE 1: for the range the wave records)
         if constexpr (MODE == 1) return -lb[min(tile_tok0(j) + l32, N - 1)] * ld_mul;
         else return 0.f;
+    };
+    // MODE 1: lse_dec2 of the 16 tokens whose scores this lane's accumulator registers hold (register r: token
+    // 8 (r / 4) + 4 hh + r % 4 of the tile), as stored; negated and scaled where it becomes the accumulators' start.
+    // Four 16-byte loads, each the same address for a whole lane half.  Only a wave's last tile can reach past the
+    // end of the array: there (a wave-uniform case) the elements are loaded one by one with clamped indices.
+    auto load_ld16 = [&](int j, f32x16 &t) {
+        if constexpr (CINIT) {
+            const int t0 = tile_tok0(j) + 4 * hh;
+            if (__builtin_amdgcn_readfirstlane((int)(j < cnt - 1)) != 0) {
+                typedef float f32x4_dword_aligned __attribute__((ext_vector_type(4), aligned(4)));
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {          // (the array starts at any (b,h) * N: only 4-byte aligned)
+                    const f32x4_dword_aligned x = *reinterpret_cast<const f32x4_dword_aligned *>(lb + t0 + 8 * i);
+                    t[4 * i] = x[0]; t[4 * i + 1] = x[1]; t[4 * i + 2] = x[2]; t[4 * i + 3] = x[3];
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) t[r] = lb[min(t0 + 8 * (r / 4) + r % 4, N - 1)];
+            }
+        }
+    };
+    auto start_from = [&](f32x16 &t) {   // the accumulators' start: -ld_mul * lse_dec2
+#pragma unroll
+        for (int i = 0; i < 16; ++i) t[i] *= -ld_mul;
     };
     // delta of the wave's j-th tile (j < cnt) from its dY and Y rows: two lanes per token
     const bool do_delta = (MODE == 1) && y_tok != nullptr && blockIdx.z == 0;
@@ -669,12 +698,17 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         load_v(1, vr1);
 #pragma unroll
         for (int b = 0; b < NB; ++b) S[b] = splat16(0.f);
-        S[0] = qk(0, kt, k_aug(kt[0], nl), PLAIN);
+        // MODE 1: the score accumulators' starting values of the current and of the next token tile; the tiles
+        // alternate between the two (no copy at the end of a tile)
+        f32x16 c_a = splat16(0.f), c_b = splat16(0.f);
+        load_ld16(0, c_a);
+        if constexpr (CINIT) start_from(c_a);
+        S[0] = qk(0, kt, k_aug(kt[0], nl), PLAIN, c_a);
 
         // One token tile.  TAIL: the wave's last tile, the only one that can reach past the chunk's end (its rows
         // beyond n1 are masked); the tiles before it carry no mask code, so that their matrix and vector
         // instructions form one scheduling region.
-        auto tile = [&](int j, auto tail_tag) {
+        auto tile = [&](int j, auto tail_tag, const f32x16 &c_cur, f32x16 &c_nxt) {
             constexpr bool TAIL = decltype(tail_tag)::value;
             // SPREAD: the score products of the next latent tile and the value products of this one are issued
             // between the exponentials and packs of this tile instead of in one burst before and after them
@@ -685,6 +719,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
             const int tok0 = tile_tok0(j);
             uint16_t *buf_next = vt + ((j + 1) & 1) * BUF;
             nln = load_lse(j + 1);
+            load_ld16(j + 1, c_nxt);
             load_k(j + 1, ktn);
             load_v(j + 2, vr2);
             if constexpr (MODE == 1) {
@@ -704,15 +739,18 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
             for (int b = 0; b < NB; ++b) {
                 // issue the next score product first: the next latent tile, or tile 0 of the next tokens
                 f32x16 nxt;
+                if constexpr (CINIT) {
+                    if (b + 1 == NB) start_from(c_nxt);   // requested at the top of the tile, needed only now
+                }
                 if constexpr (SPREAD) {
-                    if (b + 1 < NB) nxt = qk_first(b + 1, kt, kt0a, PLAIN);
-                    else nxt = qk_first(0, ktn, k_aug(ktn[0], nln), PLAIN);
+                    if (b + 1 < NB) nxt = qk_first(b + 1, kt, kt0a, PLAIN, c_cur);
+                    else nxt = qk_first(0, ktn, k_aug(ktn[0], nln), PLAIN, c_nxt);
                 } else if constexpr (SPREAD32) {
-                    if (b + 1 < NB) nxt = qk_part(b + 1, kt, kt0a, PLAIN, 0, splat16(0.f));
-                    else nxt = qk_part(0, ktn, k_aug(ktn[0], nln), PLAIN, 0, splat16(0.f));
+                    if (b + 1 < NB) nxt = qk_part(b + 1, kt, kt0a, PLAIN, 0, c_cur);
+                    else nxt = qk_part(0, ktn, k_aug(ktn[0], nln), PLAIN, 0, c_nxt);
                 } else {
-                    if (b + 1 < NB) nxt = qk(b + 1, kt, kt0a, PLAIN);
-                    else nxt = qk(0, ktn, k_aug(ktn[0], nln), PLAIN);
+                    if (b + 1 < NB) nxt = qk(b + 1, kt, kt0a, PLAIN, c_cur);
+                    else nxt = qk(0, ktn, k_aug(ktn[0], nln), PLAIN, c_nxt);
                     sched_fence();
                 }
                 f32x16 sc = S[b];
@@ -750,7 +788,6 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
                     if (b + 1 < NB) nxt = qk_second(b + 1, kt, nxt);
                     else nxt = qk_second(0, ktn, nxt);
                     o[b][0] = mfma(va[0][1], p1, o[b][0]);
-                    if constexpr (MODE == 1) FLARE_GROUP_MFMA(1);   // the correction k-step of the next scores
                     FLARE_GROUP_TRANS(4);
                     FLARE_GROUP_MFMA(1);      // hi product of the next scores
                     FLARE_GROUP_TRANS(4);
@@ -771,7 +808,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
                     o[b][0] = mfma(va[0][1], p1, o[b][0]);
                     nxt = (b + 1 < NB) ? qk_part(b + 1, kt, kt0a, PLAIN, 3, nxt) : qk_part(0, ktn, kt0a, PLAIN, 3, nxt);
                     o[b][HV - 1] = mfma(va[HV - 1][1], p1, o[b][HV - 1]);
-                    if constexpr (MODE == 1) FLARE_GROUP_MFMA(1);   // the correction k-step of the next scores
+                    if constexpr (MODE == 1 && !CINIT) FLARE_GROUP_MFMA(1);   // the correction k-step of the next scores
                     FLARE_GROUP_TRANS(4);
                     FLARE_GROUP_MFMA(1);      // hi, k-step 0
                     FLARE_GROUP_TRANS(4);
@@ -812,8 +849,22 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
                 for (int i = 0; i < LOADS; ++i) yr1[i] = yr2[i];
             }
         };
-        for (int j = 0; j + 1 < cnt; ++j) tile(j, PlainTag<false>{});
-        tile(cnt - 1, PlainTag<true>{});
+        if constexpr (CINIT) {
+            int j = 0;
+            for (; j + 2 < cnt; j += 2) {
+                tile(j, PlainTag<false>{}, c_a, c_b);
+                tile(j + 1, PlainTag<false>{}, c_b, c_a);
+            }
+            if (j + 1 < cnt) {
+                tile(j, PlainTag<false>{}, c_a, c_b);
+                tile(j + 1, PlainTag<true>{}, c_b, c_a);
+            } else {
+                tile(j, PlainTag<true>{}, c_a, c_b);
+            }
+        } else {
+            for (int j = 0; j + 1 < cnt; ++j) tile(j, PlainTag<false>{}, c_a, c_b);
+            tile(cnt - 1, PlainTag<true>{}, c_a, c_b);
+        }
     };
     if (cnt > 0) {
         if constexpr (MODE == 0) {
