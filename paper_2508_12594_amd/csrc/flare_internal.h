@@ -158,33 +158,43 @@ int mfma_dz_partial(const flare_shape &s, const void *q, const void *k, const vo
 // eps still see the same rounded values and the score products need no correction k-step; w_n is a per-token
 // scalar.  Anything else (log-sum-exps beyond +-kPlanSpan, non-finite statistics) takes the two-exponential
 // kernels with dZ as it is.
-// Called by one whole wave (of the kernel that merges the dZ partials: everything it reads is complete by
-// then); every lane returns the same answer.
+// Called by a whole workgroup of 256 threads (of the kernel that merges the dZ partials: everything it reads is
+// complete by then), all of whose threads take part in the reads (one memory latency, not one per 64 values);
+// one barrier inside; every thread returns the same answer.  red: 16 floats of LDS.
 constexpr float kPlanSpan = 60.f;
 __device__ __forceinline__ bool bwd_one_exp_ok(const float *__restrict__ ld_range, const float *__restrict__ lse_enc,
-                                               int bh, int parts, int M, int force_two)
+                                               int bh, int parts, int M, int force_two, float *red)
 {
-    const int lane = threadIdx.x & 63;
-    float le_min = INFINITY, le_max = -INFINITY, ld_min = INFINITY, ld_max = -INFINITY;
-    for (int m = lane; m < M; m += 64) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // extremes of lse_enc2, as (max, -min), and of lse_dec2 likewise: one maximum each
+    float le_hi = -INFINITY, le_lo = -INFINITY, ld_hi = -INFINITY, ld_lo = -INFINITY;
+    bool nan = false;
+    for (int m = tid; m < M; m += 256) {
         const float v = lse_enc[(size_t)bh * M + m] * 1.4426950408889634f;
-        le_min = fminf(le_min, v);
-        le_max = fmaxf(le_max, v);
+        nan |= v != v;
+        le_hi = fmaxf(le_hi, v);
+        le_lo = fmaxf(le_lo, -v);
     }
-    for (int p = lane; p < parts; p += 64) {
-        ld_min = fminf(ld_min, ld_range[2 * ((size_t)bh * parts + p)]);
-        ld_max = fmaxf(ld_max, ld_range[2 * ((size_t)bh * parts + p) + 1]);
+    for (int p = tid; p < parts; p += 256) {
+        const float a = ld_range[2 * ((size_t)bh * parts + p)], b = ld_range[2 * ((size_t)bh * parts + p) + 1];
+        nan |= a != a || b != b;
+        ld_lo = fmaxf(ld_lo, -a);
+        ld_hi = fmaxf(ld_hi, b);
     }
+    if (nan) le_hi = INFINITY;                       // a NaN anywhere makes the test fail
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
-        le_min = fminf(le_min, __shfl_xor(le_min, off));
-        le_max = fmaxf(le_max, __shfl_xor(le_max, off));
-        ld_min = fminf(ld_min, __shfl_xor(ld_min, off));
-        ld_max = fmaxf(ld_max, __shfl_xor(ld_max, off));
+        le_hi = fmaxf(le_hi, __shfl_xor(le_hi, off));
+        le_lo = fmaxf(le_lo, __shfl_xor(le_lo, off));
+        ld_hi = fmaxf(ld_hi, __shfl_xor(ld_hi, off));
+        ld_lo = fmaxf(ld_lo, __shfl_xor(ld_lo, off));
     }
-    // written so that a NaN anywhere makes the test fail
-    const bool ok = (le_max <= kPlanSpan) && (le_min >= -kPlanSpan) && (ld_max <= kPlanSpan) && (ld_min >= -kPlanSpan);
-    return ok && !force_two;
+    if (lane == 0) { red[4 * wave] = le_hi; red[4 * wave + 1] = le_lo; red[4 * wave + 2] = ld_hi; red[4 * wave + 3] = ld_lo; }
+    __syncthreads();
+    float worst = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) worst = fmaxf(worst, red[i]);
+    return worst <= kPlanSpan && !force_two;
 }
 
 // ---- spectral analysis (Appendix C.1, Algorithm 1) ---------------------------------------------

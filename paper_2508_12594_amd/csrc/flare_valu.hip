@@ -494,13 +494,8 @@ __global__ __launch_bounds__(256) void dz_merge_kernel(
     const int bh = blockIdx.y;
     // matrix-core path: which variant of the next kernels runs for this (b,h) (every workgroup works it out for
     // itself: the one-exponential variant wants dZ scaled, see bwd_one_exp_ok); one more workgroup records it
-    __shared__ int one_exp_s;
-    if (threadIdx.x < 64) {
-        const bool ok = plan != nullptr && bwd_one_exp_ok(ld_range, lse_enc, bh, parts, M, force_two);
-        if (threadIdx.x == 0) one_exp_s = ok ? 1 : 0;
-    }
-    __syncthreads();
-    const bool one_exp = one_exp_s != 0;
+    __shared__ float plan_red[16];
+    const bool one_exp = plan != nullptr && bwd_one_exp_ok(ld_range, lse_enc, bh, parts, M, force_two, plan_red);
     if (plan != nullptr && blockIdx.x == gridDim.x - 1) {
         if (threadIdx.x == 0) plan[bh] = one_exp ? 1 : 0;
         return;
@@ -558,13 +553,8 @@ __global__ __launch_bounds__(256) void dz_merge_few_kernel(
     const int j = threadIdx.x % L;
     const int m = blockIdx.x * ROWS + threadIdx.x / L;
     const int bh = blockIdx.y;
-    __shared__ int one_exp_s;                        // as in dz_merge_kernel
-    if (threadIdx.x < 64) {
-        const bool ok = plan != nullptr && bwd_one_exp_ok(ld_range, lse_enc, bh, parts, M, force_two);
-        if (threadIdx.x == 0) one_exp_s = ok ? 1 : 0;
-    }
-    __syncthreads();
-    const bool one_exp = one_exp_s != 0;
+    __shared__ float plan_red[16];                   // as in dz_merge_kernel
+    const bool one_exp = plan != nullptr && bwd_one_exp_ok(ld_range, lse_enc, bh, parts, M, force_two, plan_red);
     if (plan != nullptr && blockIdx.x == gridDim.x - 1) {
         if (threadIdx.x == 0) plan[bh] = one_exp ? 1 : 0;
         return;
