@@ -587,29 +587,24 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         if constexpr (MODE == 1) return -lb[min(tile_tok0(j) + l32, N - 1)] * ld_mul;
         else return 0.f;
     };
-    // MODE 1: lse_dec2 of the 16 tokens whose scores this lane's accumulator registers hold (register r: token
-    // 8 (r / 4) + 4 hh + r % 4 of the tile), as stored; negated and scaled where it becomes the accumulators' start.
-    // Four 16-byte loads, each the same address for a whole lane half.  Only a wave's last tile can reach past the
-    // end of the array: there (a wave-uniform case) the elements are loaded one by one with clamped indices.
-    auto load_ld16 = [&](int j, f32x16 &t) {
+    // CINIT: the accumulators of a score tile start from -lse_dec2 (scaled) of their tokens: register r of a lane
+    // holds token 8 (r / 4) + 4 hh + r % 4 of the tile.  Every lane has its own token's value (load_lse); the 32
+    // values of a tile go through 128 bytes of wave-private LDS and come back as four 16-byte reads per lane.
+    __shared__ __attribute__((aligned(16))) float ld_all[CINIT ? 4 : 1][32];
+    float *ldw = ld_all[CINIT ? wave : 0];
+    auto put_ld = [&](float neg_lse) {
         if constexpr (CINIT) {
-            const int t0 = tile_tok0(j) + 4 * hh;
-            if (__builtin_amdgcn_readfirstlane((int)(j < cnt - 1)) != 0) {
-                typedef float f32x4_dword_aligned __attribute__((ext_vector_type(4), aligned(4)));
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {          // (the array starts at any (b,h) * N: only 4-byte aligned)
-                    const f32x4_dword_aligned x = *reinterpret_cast<const f32x4_dword_aligned *>(lb + t0 + 8 * i);
-                    t[4 * i] = x[0]; t[4 * i + 1] = x[1]; t[4 * i + 2] = x[2]; t[4 * i + 3] = x[3];
-                }
-            } else {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) t[r] = lb[min(t0 + 8 * (r / 4) + r % 4, N - 1)];
-            }
+            if (hh == 0) ldw[l32] = neg_lse;
         }
     };
-    auto start_from = [&](f32x16 &t) {   // the accumulators' start: -ld_mul * lse_dec2
+    auto get_ld = [&](f32x16 &t) {
+        if constexpr (CINIT) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) t[i] *= -ld_mul;
+            for (int i = 0; i < 4; ++i) {
+                const float4 x = *reinterpret_cast<const float4 *>(ldw + 4 * hh + 8 * i);
+                t[4 * i] = x.x; t[4 * i + 1] = x.y; t[4 * i + 2] = x.z; t[4 * i + 3] = x.w;
+            }
+        }
     };
     // delta of the wave's j-th tile (j < cnt) from its dY and Y rows: two lanes per token
     const bool do_delta = (MODE == 1) && y_tok != nullptr && blockIdx.z == 0;
@@ -701,8 +696,9 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         // MODE 1: the score accumulators' starting values of the current and of the next token tile; the tiles
         // alternate between the two (no copy at the end of a tile)
         f32x16 c_a = splat16(0.f), c_b = splat16(0.f);
-        load_ld16(0, c_a);
-        if constexpr (CINIT) start_from(c_a);
+        put_ld(nl);
+        compiler_fence();
+        get_ld(c_a);
         S[0] = qk(0, kt, k_aug(kt[0], nl), PLAIN, c_a);
 
         // One token tile.  TAIL: the wave's last tile, the only one that can reach past the chunk's end (its rows
@@ -719,7 +715,6 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
             const int tok0 = tile_tok0(j);
             uint16_t *buf_next = vt + ((j + 1) & 1) * BUF;
             nln = load_lse(j + 1);
-            load_ld16(j + 1, c_nxt);
             load_k(j + 1, ktn);
             load_v(j + 2, vr2);
             if constexpr (MODE == 1) {
@@ -740,7 +735,13 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
                 // issue the next score product first: the next latent tile, or tile 0 of the next tokens
                 f32x16 nxt;
                 if constexpr (CINIT) {
-                    if (b + 1 == NB) start_from(c_nxt);   // requested at the top of the tile, needed only now
+                    // the next tile's values were requested at the top of this tile: into LDS one latent tile
+                    // before they are needed as the next tile's starting values (with one latent tile: at once)
+                    if (b == (NB >= 2 ? NB - 2 : 0)) put_ld(nln);
+                    if (b + 1 == NB) {
+                        compiler_fence();
+                        get_ld(c_nxt);
+                    }
                 }
                 if constexpr (SPREAD) {
                     if (b + 1 < NB) nxt = qk_first(b + 1, kt, kt0a, PLAIN, c_cur);
