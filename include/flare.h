@@ -203,7 +203,7 @@ int flare_forward_static(const flare_shape *shape, const void *q_lat, const void
  *   y, lse_dec: what flare_forward wrote, or NULL.  When both are given, delta_n is taken from
  *     the stored y and the decode normaliser from lse_dec; when either is NULL both are
  *     recomputed from z (one more pass over the scores, Y in fp32).  With bf16 storage (or f16
- *     storage on the matrix-core kernels) and d < 16, or at most 32 tokens, they are recomputed in
+ *     storage on the matrix-core kernels) and d < 16, or at most 32 tokens, or fewer tokens than latents, they are recomputed in
  *     either case: delta from a y of bf16 accuracy and so few terms would not meet the accuracy of
  *     the rest -- unless shape->y_f32 is set and y is the forward's fp32 output.  (16-bit shapes of
  *     fewer than 8 tokens run on the fp32 kernels throughout, forward and backward: with so few tokens

@@ -408,8 +408,8 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
 // Output per wave: (c, row sums, unnormalised O) for its latents = one partial slot.
 // ============================================================================================
 // MODE 1 (second step of the backward) reuses the same machinery for dZ = R^T dY: the values are
-// dY, the weights are R^T[n][m] = 2^(S2 - lse_dec2[n]) with the per-token -lse_dec2 carried as a
-// hi + lo bf16 pair in one more k-step (token side: slots 2,3; query side: 1,1), and there is no
+// dY, the weights are R^T[n][m] = 2^(S2 - lse_dec2[n]) with the per-token -lse_dec2 as the value the score
+// accumulators start from (exact in fp32; no k-step of its own), and there is no
 // softmax state: only the unnormalised sums are written.  lse_dec2 is read as ld_mul * lse_dec2[n]
 // (ld_mul = log2 e when the array holds the forward's natural-log statistic).  When y_tok is given,
 // every wave also forms delta[n] = <dY_n, Y_n> from the rows it streams anyway (no branch in the
@@ -434,9 +434,8 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     // stride that keeps the 16-byte stores aligned.  The operand wants it transposed (row = column of V, eight
     // tokens per lane): that is what the transposing LDS read delivers.
     constexpr int RS = D + 16 + 8;              // uint16 per row
-    // dZ kernel, d <= 16 (four latent tiles per token tile): -lse_dec2 of the tokens is what the score accumulators
-    // start from; at d = 32 (two latent tiles, 250 registers) it rides in a correction k-step, which is faster there
-    constexpr bool CINIT = MODE == 1 && D == 16;
+    // dZ kernel: -lse_dec2 of the tokens is what the score accumulators start from (no correction k-step)
+    constexpr bool CINIT = MODE == 1;
     constexpr bool PACK = pack_dim(DR);         // q' hi | lo in one operand, keys repeated in both lane halves
     constexpr int BUF = 32 * RS;                // uint16 per buffer
     __shared__ __attribute__((aligned(16))) uint16_t vt_all[4][2 * BUF];
@@ -540,9 +539,6 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     };
     // scores minus the stabiliser of latent tile b against the token tile (kk; kk0a = key side of the correction k-step)
     // (plain: without the correction k-step -- the encode's sweep that needs no stabiliser)
-    u32x4 w23;
-    w23[0] = 0u; w23[1] = hh == 0 ? kOnePair<F> : 0u; w23[2] = 0u; w23[3] = 0u;
-    const bf16x8 ones23 = as_bf16x8(w23);      // query side of the dZ kernel's correction k-step (d = 32): slots 2,3 = 1
     // c0: what the score accumulators start from -- zero, or (CINIT) minus lse_dec2 of the register's token, which
     // then needs no correction k-step
     auto qk = [&](int b, const bf16x8 (&kk)[KS], bf16x8 kk0a, bool plain, const f32x16 &c0) {
@@ -553,36 +549,27 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) r = mfma_s<F>(kk[ks], ql[b][ks], r);
         }
-        if (!CINIT && !plain) r = mfma_s<F>(kk0a, MODE == 0 ? caug[MODE == 0 ? b : 0] : ones23, r);
+        if (!CINIT && !plain) r = mfma_s<F>(kk0a, caug[MODE == 0 ? b : 0], r);
         return r;
     };
     // The same in two parts (d = 16, q' as a hi + lo pair), for the tiles that spread their matrix instructions:
     // the correction k-step and the hi product first, the lo product on top of them later.
     auto qk_first = [&](int b, const bf16x8 (&kk)[KS], bf16x8 kk0a, bool plain, const f32x16 &c0) {
         f32x16 r = c0;
-        if (!CINIT && !plain) r = mfma_s<F>(kk0a, MODE == 0 ? caug[MODE == 0 ? b : 0] : ones23, r);
+        if (!CINIT && !plain) r = mfma_s<F>(kk0a, caug[MODE == 0 ? b : 0], r);
         return mfma_s<F>(kk[0], qh[b][0], r);
     };
     auto qk_second = [&](int b, const bf16x8 (&kk)[KS], f32x16 r) { return mfma_s<F>(kk[0], ql[b][0], r); };
     // The same at d = 32 in four parts: part 0 the correction k-step (unless plain) and the hi product's k-step 0,
     // part 1 its k-step 1, parts 2 and 3 the lo product's k-steps.
     auto qk_part = [&](int b, const bf16x8 (&kk)[KS], bf16x8 kk0a, bool plain, int part, f32x16 r) {
-        if (!CINIT && part == 0 && !plain) r = mfma_s<F>(kk0a, MODE == 0 ? caug[MODE == 0 ? b : 0] : ones23, r);
+        if (!CINIT && part == 0 && !plain) r = mfma_s<F>(kk0a, caug[MODE == 0 ? b : 0], r);
         return mfma_s<F>(kk[part % KS], part < 2 ? qh[b][part % KS] : ql[b][part % KS], r);
     };
     const uint32_t one0 = hh == 0 ? kOne<F> : 0u;
     const float *lb = (MODE == 1) ? lse_dec2 + (size_t)bh * N : nullptr;
-    // Key operand of the correction k-step.  MODE 0: slot 0 := 1, else zero.  MODE 1 (where it is used: d = 32): zero
-    // except slots 2,3 := -lse_dec2 of this lane's token (hi + lo pair).
-    auto k_aug = [&](bf16x8 k0, float neg_lse) {
-        if constexpr (MODE == 0) return with_slot0(as_bf16x8(wzero), keep0, one0);
-        else {
-            u32x4 w;
-            w[0] = 0u; w[2] = 0u; w[3] = 0u;
-            w[1] = hh == 0 ? split_pair<F>(neg_lse) : 0u;
-            return as_bf16x8(w);
-        }
-    };
+    // Key operand of the encode's stabiliser k-step: slot 0 := 1, else zero.
+    auto k_aug = [&](bf16x8 k0, float neg_lse) { return with_slot0(as_bf16x8(wzero), keep0, one0); };
     auto load_lse = [&](int j) {   // -lse_dec2 of this lane's token (MODE 1: for the range the wave records)
         if constexpr (MODE == 1) return -lb[min(tile_tok0(j) + l32, N - 1)] * ld_mul;
         else return 0.f;
@@ -809,7 +796,6 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
                     o[b][0] = mfma(va[0][1], p1, o[b][0]);
                     nxt = (b + 1 < NB) ? qk_part(b + 1, kt, kt0a, PLAIN, 3, nxt) : qk_part(0, ktn, kt0a, PLAIN, 3, nxt);
                     o[b][HV - 1] = mfma(va[HV - 1][1], p1, o[b][HV - 1]);
-                    if constexpr (MODE == 1 && !CINIT) FLARE_GROUP_MFMA(1);   // the correction k-step of the next scores
                     FLARE_GROUP_TRANS(4);
                     FLARE_GROUP_MFMA(1);      // hi, k-step 0
                     FLARE_GROUP_TRANS(4);

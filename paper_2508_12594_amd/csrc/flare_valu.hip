@@ -816,8 +816,10 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     // rounding of y out (dq_lat, dK 2.1-2.4e-2 from the saved y, 8e-3 recomputed), and the recomputation costs
     // nothing at that size.
     // (at most one tile of tokens: any 16-bit y, also fp16 on the fp32 kernels)
+    // Likewise with fewer tokens than latents: a latent's gradient is then a sum over few tokens (300 tokens, 1000
+    // latents, d = 32: dq_lat 1.9e-2 ... 2.1e-2 from the saved y, 9e-3 recomputed).
     const bool bf16_weights = s.dtype == FLARE_BF16 || (s.dtype == FLARE_F16 && mf);
-    const bool coarse_y = s.dtype != FLARE_F32 && ((bf16_weights && s.d < 16) || s.N <= 32) &&
+    const bool coarse_y = s.dtype != FLARE_F32 && ((bf16_weights && s.d < 16) || s.N <= 32 || s.N < s.M) &&
                           !(s.y_f32 && mf);   // an fp32 y is not coarse (the fp32 kernels, which take the
                                               // 16-bit shapes of fewer than 8 tokens, never read it: they recompute)
     const bool saved = y && lse_dec && !coarse_y;
