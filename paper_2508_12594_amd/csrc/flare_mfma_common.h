@@ -181,6 +181,31 @@ __device__ __forceinline__ void exp_pack(const f32x16 &dlt, bf16x8 &p0, bf16x8 &
     p0 = as_bf16x8(w0);
     p1 = as_bf16x8(w1);
 }
+// The same, and the sum of the 16 rounded weights added to `sum` (v_dot2c_f32_bf16 against a pair of ones: the
+// products are exact and the sums fp32, so this is the sum of exactly the weights the matrix product sees).
+// The dot products take the packed words as they leave the conversion, before they become vector elements.
+__device__ __forceinline__ void exp_pack_sum(const f32x16 &dlt, bf16x8 &p0, bf16x8 &p1, float &sum)
+{
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    const bf16x2_t ones = __builtin_bit_cast(bf16x2_t, 0x3f803f80u);
+    u32x4 w0, w1;
+    float acc = sum;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t w = cvt_pk_bf16(fast_exp2(dlt[2 * i]), fast_exp2(dlt[2 * i + 1]));
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w), ones, acc, false);
+        w0[i] = w;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t w = cvt_pk_bf16(fast_exp2(dlt[8 + 2 * i]), fast_exp2(dlt[8 + 2 * i + 1]));
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w), ones, acc, false);
+        w1[i] = w;
+    }
+    sum = acc;
+    p0 = as_bf16x8(w0);
+    p1 = as_bf16x8(w1);
+}
 // Nothing may be scheduled across this point: keeps the matrix-core work of the next tile issued
 // ahead of the vector work of the current one.
 __device__ __forceinline__ void sched_fence() { __builtin_amdgcn_sched_barrier(0); }

@@ -428,7 +428,13 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     static_assert(!Y32 || (MODE == 1 && DR <= 8), "fp32 rows of y: written for the statistics of d <= 8");
     constexpr int D = padded_dim(DR);
     constexpr int KS = D / 16;
-    constexpr int HV = D / 16;
+    // d = 32: the value operand's 32 rows are the 32 columns of V, so there is no free row for the ones that sum
+    // the weights at d <= 16.  The encode's denominators then come from the vector ALU instead: one v_dot2c per
+    // packed pair of weights adds the same rounded weights that enter the matrix product (eight instructions a
+    // tile instead of the two extra matrix products of a second column group with its own ones row).
+    constexpr bool WIDE = D == 32;
+    constexpr bool ROWSUM = WIDE && MODE == 0;
+    constexpr int HV = 1;
     // The value tile of a token tile lives in LDS as it is loaded, row = token: D columns of values, then a column
     // of ones (the softmax denominator's row of the operand), then 15 columns of zeros; 8 more pad the row to a
     // stride that keeps the 16-byte stores aligned.  The operand wants it transposed (row = column of V, eight
@@ -482,18 +488,21 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     const int cnt = (tiles > tg) ? (tiles - tg + TG - 1) / TG : 0;   // tiles of this wave
 
     float c[NB];
+    float l[NB];                                   // ROWSUM: this lane's share of the denominators
     float nl_min = INFINITY, nl_max = -INFINITY;   // range of -lse_dec2 over this wave's tokens (MODE 1)
     f32x16 o[NB][HV];
 #pragma unroll
     for (int b = 0; b < NB; ++b) {   // what a wave without tiles stores
         c[b] = 0.f;
+        l[b] = 0.f;
 #pragma unroll
         for (int hv = 0; hv < HV; ++hv) o[b][hv] = splat16(0.f);
     }
 
     // Transposing read of the value operand: this lane's chunk of the tile.  Lanes 16-31 and 48-63 supply rows
-    // 16-31 of the operand (the ones, then zeros); the others rows 0-15 (columns 16 hv ... of V).  Row within a group of
-    // four tokens: (lane % 16) / 4; the lane half takes tokens 4-7 of every eight.
+    // 16-31 of the operand (d <= 16: the ones, then zeros; d = 32: columns 16-31 of V); the others rows 0-15
+    // (columns 0-15 of V).  Row within a group of four tokens: (lane % 16) / 4; the lane half takes tokens 4-7 of
+    // every eight.
     const int tr_row = 4 * hh + (lane & 15) / 4;
     const bool tr_upper = (lane & 16) != 0;
     const int tr_piece = 4 * (lane & 3);
@@ -529,7 +538,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
 #pragma unroll
             for (int s2 = 0; s2 < 2; ++s2) {
                 // k-step s2 of the operand: tokens 16 s2 + 4 hh + (0..3) and + 8 of them, column = this lane's row
-                const uint16_t *src = buf + (16 * s2 + tr_row) * RS + (tr_upper ? D : 16 * hv) + tr_piece;
+                const uint16_t *src = buf + (16 * s2 + tr_row) * RS + (tr_upper ? (WIDE ? 16 : D) : 16 * hv) + tr_piece;
                 const u32x2 a = lds_read_tr16(src);
                 const u32x2 b = lds_read_tr16(src + 8 * RS);
                 u32x4 w;
@@ -655,11 +664,15 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
             c[b] = 0.f;
+            l[b] = 0.f;
 #pragma unroll
             for (int hv = 0; hv < HV; ++hv) o[b][hv] = splat16(0.f);
             if constexpr (MODE == 0) caug[b] = as_bf16x8(wzero);
         }
-        bf16x8 kt[KS], ktn[KS], va[HV][2];
+        // keys: requested one token tile ahead; at d = 32, where a token tile is only two latent tiles long and the
+        // next keys are needed after the first of them, two tiles ahead (ktf)
+        constexpr bool KFAR = D == 32;
+        bf16x8 kt[KS], ktn[KS], ktf[KFAR ? KS : 1], va[HV][2];
         u32x4 vr1[LOADS], vr2[LOADS], yr1[LOADS], yr2[LOADS];
         f32x16 S[NB];
         bool first = true;
@@ -667,6 +680,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         // prologue: tile 0 fully staged, tile 1's values in flight
         float nl = load_lse(0), nln = 0.f;
         load_k(0, kt);
+        if constexpr (KFAR) load_k(1, ktn);
         load_v(0, vr1);
         if (do_delta) {
             load_y(0, yr1);
@@ -691,7 +705,11 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         // One token tile.  TAIL: the wave's last tile, the only one that can reach past the chunk's end (its rows
         // beyond n1 are masked); the tiles before it carry no mask code, so that their matrix and vector
         // instructions form one scheduling region.
-        auto tile = [&](int j, auto tail_tag, const f32x16 &c_cur, f32x16 &c_nxt) {
+        // vn, yn: the rows of token tile j+1 (requested a tile ago); vf, yf: receive those of tile j+2.  Consecutive
+        // tiles swap the two sets, so that no register of a load in flight is ever copied (a copy would make the
+        // wave wait for the load in the tile that issued it).
+        auto tile = [&](int j, auto tail_tag, const f32x16 &c_cur, f32x16 &c_nxt, u32x4 (&vn)[LOADS],
+                        u32x4 (&vf)[LOADS], u32x4 (&yn)[LOADS], u32x4 (&yf)[LOADS]) {
             constexpr bool TAIL = decltype(tail_tag)::value;
             // SPREAD: the score products of the next latent tile and the value products of this one are issued
             // between the exponentials and packs of this tile instead of in one burst before and after them
@@ -702,15 +720,16 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
             const int tok0 = tile_tok0(j);
             uint16_t *buf_next = vt + ((j + 1) & 1) * BUF;
             nln = load_lse(j + 1);
-            load_k(j + 1, ktn);
-            load_v(j + 2, vr2);
+            if constexpr (KFAR) load_k(j + 2, ktf);
+            else load_k(j + 1, ktn);
+            load_v(j + 2, vf);
             if constexpr (MODE == 1) {
                 // (when y_tok is NULL, yb aliases the dY rows: the loads stay in bounds, nothing is stored)
-                load_y(j + 2, yr2);
-                put_delta(j + 1, vr1, yr1);   // vr1, yr1: rows of tile j+1 (nothing stored past the last tile)
+                load_y(j + 2, yf);
+                put_delta(j + 1, vn, yn);     // rows of tile j+1 (nothing stored past the last tile)
             }
             compiler_fence();
-            write_vt(vr1, buf_next);          // values of tile j+1
+            write_vt(vn, buf_next);           // values of tile j+1
             compiler_fence();
             const bf16x8 kt0a = k_aug(kt[0], nl);
 
@@ -758,6 +777,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
                         for (int hv = 0; hv < HV; ++hv)
 #pragma unroll
                             for (int i = 0; i < 16; ++i) o[b][hv][i] *= f;
+                        l[b] *= f;
                     }
                     c[b] = cn;
                     caug[b] = with_slot0(caug[b], keep0, hh == 0 ? rne_elem<F>(-cn) : 0u);
@@ -769,7 +789,8 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
                     }
                 }
                 bf16x8 p0, p1;
-                exp_pack(sc, p0, p1);
+                if constexpr (ROWSUM) exp_pack_sum(sc, p0, p1, l[b]);
+                else exp_pack(sc, p0, p1);
                 if constexpr (SPREAD) {
                     // dependent pairs alternate (hi, value, lo, value): each finds its predecessor's result ready
                     o[b][0] = mfma(va[0][0], p0, o[b][0]);
@@ -787,31 +808,25 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
                     FLARE_GROUP_VALU(4);
                     FLARE_GROUP_MFMA(1);      // second value product
                 } else if constexpr (SPREAD32) {
-                    // eight products, each dependent pair apart: (hi k-step 0 above), value (0, p0), hi k-step 1,
-                    // value (1, p0), lo k-step 0, value (0, p1), lo k-step 1, value (1, p1)
-                    o[b][0] = mfma(va[0][0], p0, o[b][0]);
+                    // six products, each dependent pair apart: (hi k-step 0 above), hi k-step 1, value (p0),
+                    // lo k-step 0, lo k-step 1, value (p1)
                     nxt = (b + 1 < NB) ? qk_part(b + 1, kt, kt0a, PLAIN, 1, nxt) : qk_part(0, ktn, kt0a, PLAIN, 1, nxt);
-                    o[b][HV - 1] = mfma(va[HV - 1][0], p0, o[b][HV - 1]);
+                    o[b][0] = mfma(va[0][0], p0, o[b][0]);
                     nxt = (b + 1 < NB) ? qk_part(b + 1, kt, kt0a, PLAIN, 2, nxt) : qk_part(0, ktn, kt0a, PLAIN, 2, nxt);
-                    o[b][0] = mfma(va[0][1], p1, o[b][0]);
                     nxt = (b + 1 < NB) ? qk_part(b + 1, kt, kt0a, PLAIN, 3, nxt) : qk_part(0, ktn, kt0a, PLAIN, 3, nxt);
-                    o[b][HV - 1] = mfma(va[HV - 1][1], p1, o[b][HV - 1]);
+                    o[b][0] = mfma(va[0][1], p1, o[b][0]);
                     FLARE_GROUP_TRANS(4);
                     FLARE_GROUP_MFMA(1);      // hi, k-step 0
                     FLARE_GROUP_TRANS(4);
                     FLARE_GROUP_VALU(4);
-                    FLARE_GROUP_MFMA(1);      // value (0, p0)
-                    FLARE_GROUP_TRANS(2);
                     FLARE_GROUP_MFMA(1);      // hi, k-step 1
-                    FLARE_GROUP_TRANS(2);
-                    FLARE_GROUP_MFMA(1);      // value (1, p0)
-                    FLARE_GROUP_TRANS(2);
-                    FLARE_GROUP_MFMA(1);      // lo, k-step 0
-                    FLARE_GROUP_TRANS(2);
+                    FLARE_GROUP_TRANS(4);
+                    FLARE_GROUP_MFMA(1);      // value (p0)
+                    FLARE_GROUP_TRANS(4);
                     FLARE_GROUP_VALU(4);
-                    FLARE_GROUP_MFMA(1);      // value (0, p1)
+                    FLARE_GROUP_MFMA(1);      // lo, k-step 0
                     FLARE_GROUP_MFMA(1);      // lo, k-step 1
-                    FLARE_GROUP_MFMA(1);      // value (1, p1)
+                    FLARE_GROUP_MFMA(1);      // value (p1)
                 } else {
 #pragma unroll
                     for (int hv = 0; hv < HV; ++hv) {
@@ -828,29 +843,21 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
             compiler_fence();
             read_va(buf_next, va);            // value operand of tile j+1 (written at the top of this iteration)
 #pragma unroll
-            for (int s = 0; s < KS; ++s) kt[s] = ktn[s];
-#pragma unroll
-            for (int i = 0; i < LOADS; ++i) vr1[i] = vr2[i];
-            if (do_delta) {
-#pragma unroll
-                for (int i = 0; i < LOADS; ++i) yr1[i] = yr2[i];
+            for (int s = 0; s < KS; ++s) {
+                kt[s] = ktn[s];
+                if constexpr (KFAR) ktn[s] = ktf[s];
             }
         };
-        if constexpr (CINIT) {
-            int j = 0;
-            for (; j + 2 < cnt; j += 2) {
-                tile(j, PlainTag<false>{}, c_a, c_b);
-                tile(j + 1, PlainTag<false>{}, c_b, c_a);
-            }
-            if (j + 1 < cnt) {
-                tile(j, PlainTag<false>{}, c_a, c_b);
-                tile(j + 1, PlainTag<true>{}, c_b, c_a);
-            } else {
-                tile(j, PlainTag<true>{}, c_a, c_b);
-            }
+        int j = 0;
+        for (; j + 2 < cnt; j += 2) {
+            tile(j, PlainTag<false>{}, c_a, c_b, vr1, vr2, yr1, yr2);
+            tile(j + 1, PlainTag<false>{}, c_b, c_a, vr2, vr1, yr2, yr1);
+        }
+        if (j + 1 < cnt) {
+            tile(j, PlainTag<false>{}, c_a, c_b, vr1, vr2, yr1, yr2);
+            tile(j + 1, PlainTag<true>{}, c_b, c_a, vr2, vr1, yr2, yr1);
         } else {
-            for (int j = 0; j + 1 < cnt; ++j) tile(j, PlainTag<false>{}, c_a, c_b);
-            tile(cnt - 1, PlainTag<true>{}, c_a, c_b);
+            tile(j, PlainTag<true>{}, c_a, c_b, vr1, vr2, yr1, yr2);
         }
     };
     if (cnt > 0) {
@@ -862,7 +869,8 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
             bool redo = false;
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
-                const uint32_t e = (__float_as_uint(o[b][0][8]) >> 23) & 0xffu;
+                const float den = ROWSUM ? l[b] + __shfl_xor(l[b], 32) : o[b][0][8];
+                const uint32_t e = (__float_as_uint(den) >> 23) & 0xffu;
                 redo |= hh == 0 && lat0 + 32 * b + l32 < M && (e < 127u - 80u || e > 127u + 100u);
             }
             if (__any(redo)) sweep(PlainTag<false>{});
@@ -871,6 +879,10 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         }
     }
 
+    if constexpr (ROWSUM) {   // the two lane halves hold the sums over different tokens of the same latent
+#pragma unroll
+        for (int b = 0; b < NB; ++b) l[b] += __shfl_xor(l[b], 32);
+    }
     // partial slot of this wave: (bh, chunk*TG + tg), latents lat0 .. lat0 + 32*NB
     if (tg >= TG) return;
     const size_t part = (size_t)bh * parts + (size_t)chunk * TG + tg;
@@ -891,7 +903,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         const size_t slot = part * M + lat0 + 32 * b + l32;
         if (MODE == 0 && hh == 0) {
             m_part[slot] = (cnt > 0) ? c[b] : -INFINITY;
-            l_part[slot] = o[b][0][8];
+            l_part[slot] = ROWSUM ? l[b] : o[b][0][8];
         }
 #pragma unroll
         for (int hv = 0; hv < HV; ++hv) {
@@ -899,6 +911,11 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
             float4 hi4 = make_float4(o[b][hv][4], o[b][hv][5], o[b][hv][6], o[b][hv][7]);
             if (quartet_inside<DR>(hv, hh, 0)) *reinterpret_cast<float4 *>(o_part + slot * DR + 16 * hv + 4 * hh) = lo4;
             if (quartet_inside<DR>(hv, hh, 1)) *reinterpret_cast<float4 *>(o_part + slot * DR + 16 * hv + 8 + 4 * hh) = hi4;
+            if constexpr (WIDE) {   // registers 8-15: columns 16-31 of the same layout
+                float *dst = o_part + slot * DR + 16 + 4 * hh;
+                *reinterpret_cast<float4 *>(dst) = make_float4(o[b][0][8], o[b][0][9], o[b][0][10], o[b][0][11]);
+                *reinterpret_cast<float4 *>(dst + 8) = make_float4(o[b][0][12], o[b][0][13], o[b][0][14], o[b][0][15]);
+            }
         }
     }
 }
