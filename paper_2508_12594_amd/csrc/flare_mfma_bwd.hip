@@ -634,13 +634,18 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
         lse_next = lb[row0];
         delta_next = db[row0];
     }
+    // (the first tile's rows and statistics have arrived before the loop starts: inside it, nothing waits for
+    // anything but what the loop itself requested a tile earlier)
+    float nld_cur = pinned(-lse_next * ld_mul), dl_cur = pinned(delta_next);
+#pragma unroll
+    for (int s = 0; s < KS; ++s) { kt[s] = pinned(kt[s]); vt[s] = pinned(vt[s]); gt[s] = pinned(gt[s]); }
     for (; tile < tiles; tile += stride) {
         const int n = tile * 32 + l32;
         const int tn = (tile + stride < tiles) ? tile + stride : tile;
         load_cols(kb, tn, ktn, true);
         load_cols(vb, tn, vtn, false);
         load_cols(gb, tn, gtn, ZPACK);
-        const float nld = -lse_next * ld_mul, dl = delta_next;
+        const float nld = nld_cur, dl = dl_cur;
         {
             const size_t rown = (size_t)min(tn * 32 + l32, N - 1);
             lse_next = lb[rown];
@@ -811,6 +816,18 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                 }
             }
         }
+        // What was requested at the top of this tile is taken over here, ahead of the tile's stores: memory
+        // operations complete in order, so taking it over after them (at the top of the next tile) would make the
+        // wave wait for its own stores once per tile.
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            kt[s] = pinned(ktn[s]);
+            vt[s] = pinned(v_operand(vtn[s]));
+            gt[s] = pinned(to_bf16(gtn[s]));
+        }
+        nld_cur = pinned(-lse_next * ld_mul);
+        dl_cur = pinned(delta_next);
+        compiler_fence();
         // registers 4 q .. 4 q + 3 of an accumulator: columns (16 hv +) 8 q + 4 hh .. + 3 of this lane's token
         if (n < N) {
 #pragma unroll
@@ -846,8 +863,6 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                     }
                 }
         }
-#pragma unroll
-        for (int s = 0; s < KS; ++s) { kt[s] = ktn[s]; vt[s] = v_operand(vtn[s]); gt[s] = to_bf16(gtn[s]); }
     }
 
     if constexpr (DQ) {

@@ -351,6 +351,19 @@ __device__ __forceinline__ bf16x8 with_slot0(bf16x8 x, uint32_t keep, uint32_t b
     return as_bf16x8(w);
 }
 __device__ __forceinline__ void compiler_fence() { asm volatile("" ::: "memory"); }
+// The value as of this point of the program: an opaque statement takes and returns it, so that whatever produces
+// it (a load's arrival, a conversion) is complete here and not wherever its first real use ends up.
+__device__ __forceinline__ bf16x8 pinned(bf16x8 x)
+{
+    u32x4 w = __builtin_bit_cast(u32x4, x);
+    asm volatile("" : "+v"(w));
+    return __builtin_bit_cast(bf16x8, w);
+}
+__device__ __forceinline__ float pinned(float x)
+{
+    asm volatile("" : "+v"(x));
+    return x;
+}
 
 // More than 256 latents per head are taken 256 at a time: the latent-major kernels get one more grid
 // dimension (each workgroup owns one such chunk and streams the tokens again), the token-major ones
