@@ -579,8 +579,8 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     const float *lb = (MODE == 1) ? lse_dec2 + (size_t)bh * N : nullptr;
     // Key operand of the encode's stabiliser k-step: slot 0 := 1, else zero.
     auto k_aug = [&](bf16x8 k0, float neg_lse) { return with_slot0(as_bf16x8(wzero), keep0, one0); };
-    auto load_lse = [&](int j) {   // -lse_dec2 of this lane's token (MODE 1: for the range the wave records)
-        if constexpr (MODE == 1) return -lb[min(tile_tok0(j) + l32, N - 1)] * ld_mul;
+    auto load_lse = [&](int j) {   // lse_dec2 (as stored) of this lane's token in the wave's j-th tile (MODE 1)
+        if constexpr (MODE == 1) return lb[min(tile_tok0(j) + l32, N - 1)];
         else return 0.f;
     };
     // CINIT: the accumulators of a score tile start from -lse_dec2 (scaled) of their tokens: register r of a lane
@@ -678,7 +678,10 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         bool first = true;
 
         // prologue: tile 0 fully staged, tile 1's values in flight
-        float nl = load_lse(0), nln = 0.f;
+        // -lse_dec2 of the current tile's token and of the next tile's; the values are requested two tiles ahead
+        // (la, lb2 alternate like the row registers), so that nothing waits for a request of the same tile
+        float nl = -load_lse(0) * ld_mul, nln = 0.f;
+        float la = load_lse(1), lb2 = 0.f;
         load_k(0, kt);
         if constexpr (KFAR) load_k(1, ktn);
         load_v(0, vr1);
@@ -709,7 +712,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         // tiles swap the two sets, so that no register of a load in flight is ever copied (a copy would make the
         // wave wait for the load in the tile that issued it).
         auto tile = [&](int j, auto tail_tag, const f32x16 &c_cur, f32x16 &c_nxt, u32x4 (&vn)[LOADS],
-                        u32x4 (&vf)[LOADS], u32x4 (&yn)[LOADS], u32x4 (&yf)[LOADS]) {
+                        u32x4 (&vf)[LOADS], u32x4 (&yn)[LOADS], u32x4 (&yf)[LOADS], const float &ln, float &lf) {
             constexpr bool TAIL = decltype(tail_tag)::value;
             // SPREAD: the score products of the next latent tile and the value products of this one are issued
             // between the exponentials and packs of this tile instead of in one burst before and after them
@@ -719,7 +722,8 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
             constexpr bool SPREAD32 = !TAIL && D == 32 && MODE == 1;
             const int tok0 = tile_tok0(j);
             uint16_t *buf_next = vt + ((j + 1) & 1) * BUF;
-            nln = load_lse(j + 1);
+            lf = load_lse(j + 2);
+            nln = -ln * ld_mul;
             if constexpr (KFAR) load_k(j + 2, ktf);
             else load_k(j + 1, ktn);
             load_v(j + 2, vf);
@@ -850,14 +854,14 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         };
         int j = 0;
         for (; j + 2 < cnt; j += 2) {
-            tile(j, PlainTag<false>{}, c_a, c_b, vr1, vr2, yr1, yr2);
-            tile(j + 1, PlainTag<false>{}, c_b, c_a, vr2, vr1, yr2, yr1);
+            tile(j, PlainTag<false>{}, c_a, c_b, vr1, vr2, yr1, yr2, la, lb2);
+            tile(j + 1, PlainTag<false>{}, c_b, c_a, vr2, vr1, yr2, yr1, lb2, la);
         }
         if (j + 1 < cnt) {
-            tile(j, PlainTag<false>{}, c_a, c_b, vr1, vr2, yr1, yr2);
-            tile(j + 1, PlainTag<true>{}, c_b, c_a, vr2, vr1, yr2, yr1);
+            tile(j, PlainTag<false>{}, c_a, c_b, vr1, vr2, yr1, yr2, la, lb2);
+            tile(j + 1, PlainTag<true>{}, c_b, c_a, vr2, vr1, yr2, yr1, lb2, la);
         } else {
-            tile(j, PlainTag<true>{}, c_a, c_b, vr1, vr2, yr1, yr2);
+            tile(j, PlainTag<true>{}, c_a, c_b, vr1, vr2, yr1, yr2, la, lb2);
         }
     };
     if (cnt > 0) {
