@@ -669,10 +669,10 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
             for (int hv = 0; hv < HV; ++hv) o[b][hv] = splat16(0.f);
             if constexpr (MODE == 0) caug[b] = as_bf16x8(wzero);
         }
-        // keys: requested one token tile ahead; at d = 32, where a token tile is only two latent tiles long and the
-        // next keys are needed after the first of them, two tiles ahead (ktf)
-        constexpr bool KFAR = D == 32;
-        bf16x8 kt[KS], ktn[KS], ktf[KFAR ? KS : 1], va[HV][2];
+        // keys: requested two token tiles ahead (ktf), like the values: the next tile's keys are needed before the
+        // current tile ends (by the first score product of the next one), a request made at the top of the same
+        // tile would have three quarters of a tile, or half of one at d = 32, to arrive
+        bf16x8 kt[KS], ktn[KS], ktf[KS], va[HV][2];
         u32x4 vr1[LOADS], vr2[LOADS], yr1[LOADS], yr2[LOADS];
         f32x16 S[NB];
         bool first = true;
@@ -683,7 +683,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         float nl = -load_lse(0) * ld_mul, nln = 0.f;
         float la = load_lse(1), lb2 = 0.f;
         load_k(0, kt);
-        if constexpr (KFAR) load_k(1, ktn);
+        load_k(1, ktn);
         load_v(0, vr1);
         if (do_delta) {
             load_y(0, yr1);
@@ -724,8 +724,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
             uint16_t *buf_next = vt + ((j + 1) & 1) * BUF;
             lf = load_lse(j + 2);
             nln = -ln * ld_mul;
-            if constexpr (KFAR) load_k(j + 2, ktf);
-            else load_k(j + 1, ktn);
+            load_k(j + 2, ktf);
             load_v(j + 2, vf);
             if constexpr (MODE == 1) {
                 // (when y_tok is NULL, yb aliases the dY rows: the loads stay in bounds, nothing is stored)
@@ -849,7 +848,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
                 kt[s] = ktn[s];
-                if constexpr (KFAR) ktn[s] = ktf[s];
+                ktn[s] = ktf[s];
             }
         };
         int j = 0;
