@@ -220,44 +220,44 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
     };
 
     if (cnt > 0) {
-        // keys are requested two tiles ahead; so are the other operands where registers allow (d <= 16)
-        constexpr bool DEEP = (D == 16);
-        bf16x8 kt[KS], ktn[KS], ktnn[KS], vt[KS], vtn[KS], vtnn[KS], gt[KS], gtn[KS], gtnn[KS], kT[HV][2];
-        float nld, nldn, nldnn, dl, dln, dlnn;
+        // The rows of a token tile (keys, values, dY, as loaded) and its two statistics are requested as soon as
+        // the tile three places earlier is done with its registers: a tile of this kernel is short (one or two
+        // latent tiles), and a request has to be older than the memory latency when its rows are needed (the keys
+        // two tiles later, the rest three).  Three sets of registers take turns as current tile, next tile and in
+        // flight, so that no register of a load in flight is ever copied.
+        struct Rows {
+            bf16x8 k[KS], v[KS], g[KS];
+            float l, d;   // lse_dec2 as stored, delta
+        };
+        auto request = [&](int j, Rows &r) {
+            load_rows(kb, j, r.k, true);
+            load_rows(vb, j, r.v, false);
+            load_rows(gb, j, r.g, true);
+            const int n = min(tile_tok0(j) + l32, N - 1);
+            r.l = lb[n];
+            r.d = db[n];
+        };
+        Rows ra, rb, rc;
+        bf16x8 kT[HV][2];
         float wrow[ONE ? 16 : 1];
-        load_rows(kb, 0, kt, true);
-        load_rows(kb, 1, ktn, true);
-        load_rows(vb, 0, vt, false);
-        load_rows(vb, 1, vtn, false);
-        load_rows(gb, 0, gt, true);
-        load_rows(gb, 1, gtn, true);
-        if constexpr (F || PACK) {   // V and dY meet bf16 operands: converted once, when they become current
-#pragma unroll
-            for (int s = 0; s < KS; ++s) { vt[s] = v_operand(vt[s]); gt[s] = to_bf16(gt[s]); }
-        }
-        nld = -lb[min(tile_tok0(0) + l32, N - 1)] * ld_mul;
-        dl = db[min(tile_tok0(0) + l32, N - 1)];
-        nldn = -lb[min(tile_tok0(1) + l32, N - 1)] * ld_mul;
-        dln = db[min(tile_tok0(1) + l32, N - 1)];
+        request(0, ra);
+        request(1, rb);
+        request(2, rc);
         compiler_fence();
-        write_kt(kt, lds);
-        if constexpr (ONE) wl[0][l32] = fast_exp2(kap + nld);
+        write_kt(ra.k, lds);
+        if constexpr (ONE) wl[0][l32] = fast_exp2(kap - ra.l * ld_mul);
         compiler_fence();
         read_kT(lds, kT);
         if constexpr (ONE) read_w(wl[0], wrow);
 
-        for (int j = 0; j < cnt; ++j) {
+        // tile j: cur holds its rows (and receives those of tile j+3 at the end), nxt those of tile j+1
+        auto tile = [&](int j, Rows &cur, const Rows &nxt) {
             const int tok0 = tile_tok0(j);
             uint16_t *buf_next = lds + ((j + 1) & 1) * BUF;
-            load_rows(kb, j + 2, ktnn, true);
-            load_rows(vb, j + (DEEP ? 2 : 1), vtnn, false);
-            load_rows(gb, j + (DEEP ? 2 : 1), gtnn, true);
-            nldnn = -lb[min(tile_tok0(j + (DEEP ? 2 : 1)) + l32, N - 1)] * ld_mul;
-            dlnn = db[min(tile_tok0(j + (DEEP ? 2 : 1)) + l32, N - 1)];
-            compiler_fence();
-            write_kt(ktn, buf_next);
-            if constexpr (ONE) wl[(j + 1) & 1][l32] = fast_exp2(kap + (DEEP ? nldn : nldnn));
-            compiler_fence();
+            const float nld = -cur.l * ld_mul, dl = cur.d;
+            bf16x8 vt[KS], gt[KS];   // V and dY meet bf16 operands
+#pragma unroll
+            for (int s = 0; s < KS; ++s) { vt[s] = v_operand(cur.v[s]); gt[s] = to_bf16(cur.g[s]); }
 
             // token-side operands of the correction k-steps (zero outside the named slots)
             u32x4 wb;
@@ -282,10 +282,10 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
             for (int b = 0; b < NB; ++b) {
                 f32x16 x = splat16(0.f);
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) x = mfma_s<F>(kt[ks], qh[b][ks], x);
+                for (int ks = 0; ks < KS; ++ks) x = mfma_s<F>(cur.k[ks], qh[b][ks], x);
                 if constexpr (!PACK) {
 #pragma unroll
-                    for (int ks = 0; ks < KS; ++ks) x = mfma_s<F>(kt[ks], ql[b][ks], x);
+                    for (int ks = 0; ks < KS; ++ks) x = mfma_s<F>(cur.k[ks], ql[b][ks], x);
                 }
                 f32x16 s1 = x;                  // one exponential: the scores as they are
                 if constexpr (!ONE) s1 = mfma_s<F>(kt_a, q_aug[b], x);
@@ -329,17 +329,26 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
                     acc[b][hv] = mfma(kT[hv][1], as_bf16x8(w1), acc[b][hv]);
                 }
             }
+            // The next tile's K^T and w go through LDS here, at the end of the tile: its rows were requested two
+            // tiles ago, and what is read back is first needed by the last products of the next tile.
             compiler_fence();
+            write_kt(nxt.k, buf_next);
+            if constexpr (ONE) wl[(j + 1) & 1][l32] = fast_exp2(kap - nxt.l * ld_mul);
+            compiler_fence();
+            request(j + 3, cur);
             read_kT(buf_next, kT);
             if constexpr (ONE) read_w(wl[(j + 1) & 1], wrow);
-#pragma unroll
-            for (int s = 0; s < KS; ++s) {
-                kt[s] = ktn[s]; ktn[s] = ktnn[s];
-                vt[s] = v_operand(DEEP ? vtn[s] : vtnn[s]); vtn[s] = vtnn[s];
-                gt[s] = to_bf16(DEEP ? gtn[s] : gtnn[s]); gtn[s] = gtnn[s];
-            }
-            nld = DEEP ? nldn : nldnn; nldn = nldnn;
-            dl = DEEP ? dln : dlnn; dln = dlnn;
+            sched_fence();   // consecutive tiles are not interleaved (their temporaries would not fit the registers)
+        };
+        int j = 0;
+        for (; j + 3 <= cnt; j += 3) {
+            tile(j, ra, rb);
+            tile(j + 1, rb, rc);
+            tile(j + 2, rc, ra);
+        }
+        if (j < cnt) {
+            tile(j, ra, rb);
+            if (j + 1 < cnt) tile(j + 1, rb, rc);
         }
     }
 
