@@ -744,10 +744,10 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
                 // issue the next score product first: the next latent tile, or tile 0 of the next tokens
                 f32x16 nxt;
                 if constexpr (CINIT) {
-                    // the next tile's values were requested at the top of this tile: into LDS one latent tile
-                    // before they are needed as the next tile's starting values (with one latent tile: at once)
-                    if (b == (NB >= 2 ? NB - 2 : 0)) put_ld(nln);
-                    if (b + 1 == NB) {
+                    // the next tile's values (requested two tiles ago) go into LDS at the top of the tile and are
+                    // read back one latent tile before the next tile's first score product starts from them
+                    if (b == 0) put_ld(nln);
+                    if (b == (NB >= 2 ? NB - 2 : 0)) {
                         compiler_fence();
                         get_ld(c_nxt);
                     }
