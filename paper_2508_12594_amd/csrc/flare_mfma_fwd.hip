@@ -654,6 +654,12 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         if (do_delta && j < cnt && g == 0 && (lane & 1) == 0 && n < n1) delta_out[(size_t)bh * N + n] = part;
     };
 
+    // The waves of a workgroup that share token tiles (one per latent group) read the same rows; nothing else keeps
+    // them together, and once they are more tiles apart than the L2 holds, the later one fetches its rows a second
+    // time.  The dZ kernel therefore lines its waves up every kSyncTiles tiles (a wave passes the same number of
+    // barriers whatever its number of tiles: those its sweep does not reach follow after it).
+    constexpr bool SYNC = MODE == 1;
+    constexpr int kSyncTiles = 32;
     // One sweep over this wave's token tiles.  PLAIN (encode only): the weights are 2^S2 as they come, with no
     // stabiliser (c = 0: no running maximum, no correction k-step, no rescaling) -- right whenever the row sums
     // end up in a range that shows that nothing overflowed and nothing that matters was flushed to zero, which
@@ -853,6 +859,7 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
         };
         int j = 0;
         for (; j + 2 < cnt; j += 2) {
+            if (SYNC && j > 0 && (j & (kSyncTiles - 1)) == 0) __syncthreads();
             tile(j, PlainTag<false>{}, c_a, c_b, vr1, vr2, yr1, yr2, la, lb2);
             tile(j + 1, PlainTag<false>{}, c_b, c_a, vr2, vr1, yr2, yr1, lb2, la);
         }
@@ -863,7 +870,13 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
             tile(j, PlainTag<true>{}, c_a, c_b, vr1, vr2, yr1, yr2, la, lb2);
         }
     };
-    if (cnt > 0) {
+    if constexpr (SYNC) {
+        // the barriers this wave's sweep does not reach (it has one tile fewer than the longest, or none at all)
+        const int cnt_max = (tiles + TG - 1) / TG;
+        const int mine = cnt >= 3 ? (cnt - 3) / kSyncTiles : 0, all = cnt_max >= 3 ? (cnt_max - 3) / kSyncTiles : 0;
+        if (cnt > 0) sweep(PlainTag<false>{});
+        for (int i = mine; i < all; ++i) __syncthreads();
+    } else if (cnt > 0) {
         if constexpr (MODE == 0) {
             sweep(PlainTag<true>{});
             // Row sums (register 8 of the lower lane half) between 2^-80 and 2^100: no weight overflowed, and the
