@@ -206,6 +206,21 @@ __device__ __forceinline__ void exp_pack_sum(const f32x16 &dlt, bf16x8 &p0, bf16
     p0 = as_bf16x8(w0);
     p1 = as_bf16x8(w1);
 }
+// acc + <a, b> for eight bf16 elements a side (four packed pairs): v_dot2c_f32_bf16, exact products, fp32 sums.
+// Written as one opaque block because the compiler's own form of the instruction mixes up its operands when
+// they are elements of loaded vectors (hipcc 7.2), and closed by the wait states that a reader of the result
+// (also a DPP move) needs after a dot instruction: inside the block the compiler inserts none.
+__device__ __forceinline__ float dot8_bf16(const u32x4 &a, const u32x4 &b, float acc)
+{
+    asm volatile("v_dot2c_f32_bf16 %0, %1, %2\n\t"
+                 "v_dot2c_f32_bf16 %0, %3, %4\n\t"
+                 "v_dot2c_f32_bf16 %0, %5, %6\n\t"
+                 "v_dot2c_f32_bf16 %0, %7, %8\n\t"
+                 "s_nop 3"
+                 : "+v"(acc)
+                 : "v"(a[0]), "v"(b[0]), "v"(a[1]), "v"(b[1]), "v"(a[2]), "v"(b[2]), "v"(a[3]), "v"(b[3]));
+    return acc;
+}
 // Nothing may be scheduled across this point: keeps the matrix-core work of the next tile issued
 // ahead of the vector work of the current one.
 __device__ __forceinline__ void sched_fence() { __builtin_amdgcn_sched_barrier(0); }

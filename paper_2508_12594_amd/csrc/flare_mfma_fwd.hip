@@ -639,6 +639,11 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
                 done = true;
             }
         }
+        if constexpr (!F && !Y32) {   // bf16 rows on both sides: one dot instruction per pair of elements
+#pragma unroll
+            for (int i = 0; i < LOADS; ++i) part = dot8_bf16(gv[i], yy[i], part);
+            done = true;
+        }
         if (!done) {
 #pragma unroll
         for (int i = 0; i < LOADS; ++i)
