@@ -375,6 +375,53 @@ def test_large_score_offsets(oracle, dtype):
     _forward_case(oracle, inp, tol=1e-4 if dtype == "f32" else None)
 
 
+@pytest.mark.parametrize("dtype,M,d", [("bf16", 256, 16), ("bf16", 64, 8), ("f16", 128, 32), ("bf16", 256, 32),
+                                       ("f32", 64, 16)])
+def test_decode_with_every_token_shifted_differently(dtype, M, d):
+    """The decode's softmax runs over the latents of one token, so adding the same amount to all scores of a token
+    leaves y unchanged and moves lse_dec by that amount.  Here token n's scores are shifted by a ramp from -138 to
+    +138 log2 units: the kernel's first sweep of a token tile has no stabiliser and must notice, from the
+    denominators alone, every tile that left its range (below 2^-80, from 2^64 on) -- tiles on both sides of both
+    limits, and tiles that straddle them.  Reference: the definition, in fp64 (Eq. flare_decode)."""
+    import torch
+    _say("decode, per-token score shifts, %s M=%d d=%d" % (dtype, M, d))
+    N = 4000
+    inp = synth.make_inputs(1, B=1, H=2, N=N, M=M, d=d, dtype=dtype, with_dy=False)
+    scale = 1.0 / np.sqrt(d)
+    q, k = inp["q"].copy(), inp["k"].copy()
+    q[..., 0] = 16.0                                   # token n's scores get + scale * 16 * k[n][0]
+    ramp = np.linspace(-1.0, 1.0, N, dtype=np.float32) * np.float32(138.0 / (scale * 16.0 * 1.4426950408889634))
+    k[..., 0] = ramp[None, None, :]
+    if dtype == "bf16":
+        q, k = synth.bf16_round(q), synth.bf16_round(k)
+    elif dtype == "f16":
+        q, k = q.astype(np.float16).astype(np.float32), k.astype(np.float16).astype(np.float32)
+    rng = np.random.Generator(np.random.PCG64(20250812))
+    z = rng.standard_normal((1, 2, M, d)).astype(np.float32)
+    dev = to_device(dict(inp, q=q, k=k))
+    zt = torch.from_numpy(z).cuda()
+    lse_dec = torch.empty((1, 2, N), dtype=torch.float32, device="cuda")
+    y = binding.decode(dev["q"], dev["k"], zt, scale, lse_dec=lse_dec)
+    torch.cuda.synchronize()
+    s = scale * np.einsum("hmj,bhnj->bhnm", q.astype(np.float64), k.astype(np.float64))      # [B, H, N, M]
+    top = s.max(axis=-1, keepdims=True)
+    w = np.exp(s - top)
+    den = w.sum(axis=-1, keepdims=True)
+    y_ref = (w / den) @ z.astype(np.float64)
+    lse_ref = (top + np.log(den))[..., 0]
+    shift = lse_ref / np.log(2.0)
+    assert shift.min() < -100.0 and shift.max() > 100.0   # the ramp does cross both limits
+    tol = TOL["bf16"] if dtype == "f16" else TOL[dtype]   # 16-bit storage: the matrix-core kernels (bf16 weights)
+    e_y = slice_relerr(to_host(y), y_ref)
+    r_y = row_relerr(to_host(y), y_ref)
+    e_l = float(np.max(np.abs(to_host(lse_dec) - lse_ref)))
+    _say("   err y %.3e (worst row %.3e)  lse_dec(abs) %.3e  (tol %.0e)" % (e_y, r_y, e_l, tol))
+    assert e_y <= tol and r_y <= ROW_FACTOR * tol
+    # a score of magnitude |S| carries |S| * 2^-23 of fp32 rounding (2^-9 of it through bf16 keys: exact here,
+    # the ramp is rounded before both sides see it)
+    assert e_l <= (5e-3 if dtype != "f32" else 2e-5) + 1e-5 * float(np.max(np.abs(lse_ref)))
+
+
 @pytest.mark.parametrize("cfg,over", [(2, dict(B=2, N=2050)), (4, dict(N=3001)), (5, dict(N=1999)), (3, dict(B=1, N=700))])
 def test_backward_two_exponential_kernels(oracle, cfg, over):
     """The matrix-core backward has a one-exponential and a two-exponential variant of its last
