@@ -115,6 +115,37 @@ __device__ __forceinline__ float dot(const float (&a)[D], const float (&b)[D])
     return s;
 }
 
+// The thread-per-latent kernels read the token rows through the scalar data path (the address is the same for the
+// whole wave), a handful of rows per request, and a wave can use none of them before all have arrived: with the
+// rows coming from HBM every group of tokens costs several full memory latencies.  So each group first touches
+// the rows of a later group with one vector load that needs no register: its data goes to a few bytes of LDS
+// that nobody reads (global_load_lds_dword), and the rows are in the L2 when the scalar requests come.
+// Lanes 8 i + t of every 32 touch row t of the group kPrefetchTokens on in tensor i (a, b, c; i = 3: a again).
+// The tensors' addresses come in a second time as plain integers (RowTouch): a pointer derived from the kernel's
+// own tensor arguments would make the compiler treat the rows as possibly overwritten by this load and take
+// them off the scalar data path.
+constexpr int kPrefetchTokens = 16;   // two groups of kGroup ahead
+struct RowTouch {
+    unsigned long long a, b, c;   // addresses of up to three token tensors (element (0,0,0,0)); unused: a again
+    unsigned long long f, g;      // addresses of up to two per-token fp32 arrays [b*h][N] (lanes 24-27); or 0
+};
+template <typename T>
+__device__ __forceinline__ void touch_rows(const RowTouch &rt, size_t base, const TokStride &ts, int n, int N,
+                                           float *sink)
+{
+    const int lane = threadIdx.x & 31;
+    const int tok = min(n + kPrefetchTokens + (lane & 7), N - 1);
+    const unsigned long long which = (lane & 16) ? ((lane & 8) ? rt.a : rt.c) : ((lane & 8) ? rt.b : rt.a);
+    const void *src = reinterpret_cast<const T *>(which) + base + tok_off(ts, tok);
+    if (lane >= 24 && lane < 28 && rt.f != 0) {   // the statistics of tokens n + kPrefetchTokens and 32 further on
+        const unsigned long long arr = (lane & 2) ? rt.g : rt.f;
+        src = reinterpret_cast<const float *>(arr) + (size_t)blockIdx.y * N + min(n + kPrefetchTokens + 32 * (lane & 1), N - 1);
+    }
+    __builtin_amdgcn_global_load_lds(src, sink, 4, 0, 0);
+}
+
+inline unsigned long long addr(const void *p) { return (unsigned long long)(uintptr_t)p; }
+
 constexpr int kLatentBlock = 256;  // threads per block in the thread-per-latent kernels
 constexpr int kTokenBlock = 256;   // threads per block in the thread-per-token kernels
 constexpr int kGroup = 8;          // scores handled between two running-max updates
@@ -127,7 +158,7 @@ template <typename T, int D>
 __global__ __launch_bounds__(kLatentBlock) void encode_partial_kernel(
     const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v,
     float *__restrict__ m_part, float *__restrict__ l_part, float *__restrict__ o_part,
-    TokStride ts, int H, int N, int M, int chunk_len, int chunks, float c2)
+    TokStride ts, int H, int N, int M, int chunk_len, int chunks, float c2, RowTouch touch)
 {
     const int m = blockIdx.z * kLatentBlock + threadIdx.x;
     if (m >= M) return;
@@ -145,8 +176,10 @@ __global__ __launch_bounds__(kLatentBlock) void encode_partial_kernel(
 #pragma unroll
     for (int j = 0; j < D; ++j) o[j] = 0.f;
 
+    __shared__ float sink[kLatentBlock];
     int n = n0;
     for (; n + kGroup <= n1; n += kGroup) {
+        touch_rows<T>(touch, tok_base(ts, bh, H), ts, n, N, sink);
         float s[kGroup];
         float gm = mr;
 #pragma unroll
@@ -423,7 +456,7 @@ template <typename T, int D>
 __global__ __launch_bounds__(kLatentBlock) void dz_partial_kernel(
     const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ dy,
     const float *__restrict__ lse_dec2, float *__restrict__ dz_part,
-    TokStride ts, int H, int N, int M, int chunk_len, int chunks, float c2)
+    TokStride ts, int H, int N, int M, int chunk_len, int chunks, float c2, RowTouch touch)
 {
     const int m = blockIdx.z * kLatentBlock + threadIdx.x;
     if (m >= M) return;
@@ -440,7 +473,9 @@ __global__ __launch_bounds__(kLatentBlock) void dz_partial_kernel(
     float acc[D];
 #pragma unroll
     for (int j = 0; j < D; ++j) acc[j] = 0.f;
+    __shared__ float sink[kLatentBlock];
     for (int n = n0; n < n1; ++n) {
+        if (((n - n0) & 7) == 0) touch_rows<T>(touch, tok_base(ts, bh, H), ts, n, N, sink);
         float kr[D], g[D];
         load_row<D>(kb + tok_off(ts, n), kr);
         const float r = fast_exp2(dot<D>(qm, kr) - lb[n]);
@@ -609,7 +644,8 @@ __global__ __launch_bounds__(kLatentBlock) void dq_partial_kernel(
     const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v, const T *__restrict__ dy,
     const float *__restrict__ z, const float *__restrict__ lse_enc, const float *__restrict__ dz,
     const float *__restrict__ eps, const float *__restrict__ lse_dec2, const float *__restrict__ delta,
-    float *__restrict__ dq_part, TokStride ts, int H, int N, int M, int chunk_len, int chunks, float c2)
+    float *__restrict__ dq_part, TokStride ts, int H, int N, int M, int chunk_len, int chunks, float c2,
+    RowTouch touch)
 {
     const int m = blockIdx.z * kLatentBlock + threadIdx.x;
     if (m >= M) return;
@@ -629,7 +665,9 @@ __global__ __launch_bounds__(kLatentBlock) void dq_partial_kernel(
     const float *db = delta + (size_t)bh * N;
     const int n0 = chunk * chunk_len;
     const int n1 = min(N, n0 + chunk_len);
+    __shared__ float sink[kLatentBlock];
     for (int n = n0; n < n1; ++n) {
+        if (((n - n0) & 7) == 0) touch_rows<T>(touch, tok_base(ts, bh, H), ts, n, N, sink);
         float kr[D], vr[D], g[D];
         load_row<D>(kb + tok_off(ts, n), kr);
         load_row<D>(vb + tok_off(ts, n), vr);
@@ -774,7 +812,8 @@ int encode_impl(const flare_shape &s, const T *q, const T *k, const T *v, float 
     {
         LaunchTimer t(KID_ENCODE_PARTIAL, stream);
         encode_partial_kernel<T, D><<<dim3(plan.enc.chunks, BH, lat_blocks), kLatentBlock, 0, stream>>>(
-            q, k, v, m_part, l_part, o_part, tok_stride(s), s.H, s.N, s.M, plan.enc.chunk_len, plan.enc.chunks, scale * kLog2e);
+            q, k, v, m_part, l_part, o_part, tok_stride(s), s.H, s.N, s.M, plan.enc.chunk_len, plan.enc.chunks, scale * kLog2e,
+            RowTouch{addr(k), addr(v), addr(k), 0, 0});
     }
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     return launch_encode_merge(s, m_part, l_part, o_part, z, lse_enc, plan.enc.chunks, stream);
@@ -857,7 +896,7 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
             LaunchTimer t(KID_BWD_DZ_PARTIAL, stream);
             dz_partial_kernel<T, D><<<lat_grid, kLatentBlock, 0, stream>>>(q, k, dy, w.lse_dec2, w.part, ts, s.H,
                                                                            s.N, s.M, plan.bwd.chunk_len, plan.bwd.chunks,
-                                                                           c2);
+                                                                           c2, RowTouch{addr(k), addr(dy), addr(k), addr(w.lse_dec2), addr(w.lse_dec2)});
         }
         if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     }
@@ -889,7 +928,8 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
         LaunchTimer t(KID_BWD_DQ_PARTIAL, stream);
         dq_partial_kernel<T, D><<<lat_grid, kLatentBlock, 0, stream>>>(q, k, v, dy, z, lse_enc, w.dz, w.eps,
                                                                        w.lse_dec2, w.delta, w.part, ts, s.H, s.N, s.M,
-                                                                       plan.bwd.chunk_len, plan.bwd.chunks, c2);
+                                                                       plan.bwd.chunk_len, plan.bwd.chunks, c2,
+                                                                       RowTouch{addr(k), addr(v), addr(dy), addr(w.lse_dec2), addr(w.delta)});
     }
     if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
     auto reduce_dq = [&]() -> int {
