@@ -122,25 +122,17 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
         for (int ks = 0; ks < KS; ++ks) r = mfma_s<F>(qh[t][ks], kk[ks], r);
         return r;
     };
-    // Stabiliser.  FREE (q pre-scaled): a token tile is first swept with none at all -- the weights are 2^S2 as they
-    // come, no maximum, no subtraction, the score accumulators start from the constant zero -- which is exact
-    // whenever nothing left fp32's range; the denominators show afterwards whether that held (see below), and
-    // only then the tile is swept again with the exact maximum over all latent tiles.  Otherwise (raw q): the
-    // maximum of the hi product of the tile's FIRST latent tile (any value is exact as long as no weight overflows
-    // and the largest does not underflow; this one is <= the true maximum), with the same second sweep behind it.
-    // The scores of latent tile 0 are the hi product minus the stabiliser, plus the lo product.
-    constexpr bool FREE = PRE;
+    // The stabiliser of a token tile is the maximum of the hi product of its FIRST latent tile (any value is exact
+    // as long as no weight overflows and the largest does not underflow; this one is <= the true maximum).  The
+    // scores of that latent tile are the same product minus the stabiliser, plus the lo product.
     auto tile_max = [&](const f32x16 &hi) {
-        if constexpr (FREE) return 0.f;
         const float m = max16(hi, -INFINITY);
         return fmaxf(m, __shfl_xor(m, 32));
     };
-    auto first_scores = [&](f32x16 hi, float m, const bf16x8 (&kk)[KS], bool subtract) {
+    auto first_scores = [&](f32x16 hi, float m, const bf16x8 (&kk)[KS]) {
         if constexpr (PRE) {
-            if (subtract) {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) hi[i] -= m;
-            }
+            for (int i = 0; i < 16; ++i) hi[i] -= m;
             if constexpr (!PACK) {
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) hi = mfma_s<F>(ql[0][ks], kk[ks], hi);
@@ -158,7 +150,7 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
             kt[s] = as_bf16x8(row8_bf16<DR>(kb + tok_off(ts, nld), PACK ? 0 : (D / 2) * hh + 8 * s));
         const f32x16 hi = qk_hi(0, kt);
         mx = tile_max(hi);
-        s_cur0 = first_scores(hi, mx, kt, !FREE);
+        s_cur0 = first_scores(hi, mx, kt);
     }
     for (; tile < tiles; tile += stride) {
         const int n = tile * 32 + l32;
@@ -308,14 +300,10 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
             }
             return s_cur;
         };
-        s_ahead = sweep(s_cur0, splat16((PRE && !FREE) ? -mx : 0.f), PlainTag<true>{});
-        // The denominators (row 16: register 8 of the lower lane half) tell whether the sweep was exact.  At or
-        // above 2^64 (or not finite): a weight may have overflowed -- a later latent tile beat the stabiliser by
-        // that much.  FREE also: below 2^-80, the largest score of the token is under -80 and weights that
-        // matter may have been flushed to zero (with a denominator of at least 2^-80, whatever was flushed, at
-        // most 2^-126 a latent, is below 2^-35 of it).  Then once more with the exact maximum.
-        const uint32_t den_exp = (__float_as_uint(acc[0][8]) >> 23) & 0xffu;
-        if (__any(hh == 0 && (den_exp >= 127u + 64u || (FREE && den_exp < 127u - 80u)))) {
+        s_ahead = sweep(s_cur0, splat16(PRE ? -mx : 0.f), PlainTag<true>{});
+        // A later latent tile beat the first one by more than 2^64 for some token (its denominator, row 16,
+        // is huge or not finite): once more with the exact maximum.  Exponent field >= 127 + 64.
+        if (__any((__float_as_uint(acc[0][8]) & 0x7f800000u) >= ((127u + 64u) << 23))) {
             float m = -INFINITY;
             f32x16 hi0 = qk_hi(0, kt), s_cur = hi0, s_next = hi0;
 #pragma unroll
@@ -327,13 +315,13 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
             }
             mx = fmaxf(m, __shfl_xor(m, 32));
             b2 = mx * ac2;
-            (void)sweep(first_scores(hi0, mx, kt, true), splat16(PRE ? -mx : 0.f), PlainTag<false>{});
+            (void)sweep(first_scores(hi0, mx, kt), splat16(PRE ? -mx : 0.f), PlainTag<false>{});
             s_ahead = qk_hi(0, ktn);
         }
         // The next tile's stabiliser and first scores, before this tile's output: their latencies (a cross-lane
         // exchange, a matrix product) pass while the output below is normalised, packed and stored.
         const float mx_next = tile_max(s_ahead);
-        s_cur0 = first_scores(s_ahead, mx_next, ktn, !FREE);
+        s_cur0 = first_scores(s_ahead, mx_next, ktn);
         // row 16 (register 8 of the lower lane half) is the softmax denominator
         const float den = __shfl(acc[0][8], l32);
         const float inv = 1.f / den;

@@ -100,24 +100,27 @@ __global__ __launch_bounds__(64 * HW, HW == 8 ? 1 : 2) void decode_project_kerne
     const int tiles = (N + 31) / 32;
     bf16x8 kt, ktn;
     int tile = blockIdx.x;
-    // The decode of one head, as in decode_mfma_kernel, operation for operation (y is bit-identical): a token tile
-    // is first swept without a stabiliser (weights 2^S2 as they come, score accumulators starting from zero); if
-    // its denominators show that something may have left fp32's range, it is swept again with the exact maximum
-    // over all latent tiles.  The scores of latent tile 0 are the hi product (minus the stabiliser in the second
-    // sweep) plus the lo product; the last latent tile requests the first hi product of the wave's next token tile.
+    // The decode of one head, as in decode_mfma_kernel, operation for operation (y is bit-identical): the stabiliser
+    // of a token tile is the maximum of the hi product of its first latent tile; the scores of that latent tile are
+    // the same product minus the stabiliser plus the lo product; the last latent tile requests the first hi
+    // product of the wave's next token tile.
     auto qk_hi = [&](int t, bf16x8 kk) { return mfma_s<F>(qh[t][0], kk, splat16(0.f)); };
-    auto first_scores = [&](f32x16 hi, float m, bf16x8 kk, bool subtract) {
-        if (subtract) {
+    auto tile_max = [&](const f32x16 &hi) {
+        const float m = max16(hi, -INFINITY);
+        return fmaxf(m, __shfl_xor(m, 32));
+    };
+    auto first_scores = [&](f32x16 hi, float m, bf16x8 kk) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) hi[i] -= m;
-        }
+        for (int i = 0; i < 16; ++i) hi[i] -= m;
         return mfma_s<F>(ql[0][0], kk, hi);
     };
     float mx = 0.f;
     f32x16 s_cur0 = splat16(0.f);
     if (tile < tiles) {
         kt = as_bf16x8(*reinterpret_cast<const u32x4 *>(kb + (size_t)min(tile * 32 + l32, N - 1) * row_stride + 8 * hh));
-        s_cur0 = first_scores(qk_hi(0, kt), 0.f, kt, false);
+        const f32x16 hi = qk_hi(0, kt);
+        mx = tile_max(hi);
+        s_cur0 = first_scores(hi, mx, kt);
     }
     for (int it = 0; tile < tiles; tile += gridDim.x, ++it) {
         const int n = tile * 32 + l32;
@@ -180,12 +183,9 @@ __global__ __launch_bounds__(64 * HW, HW == 8 ? 1 : 2) void decode_project_kerne
             }
             return s_cur;
         };
-        mx = 0.f;
-        f32x16 s_ahead = sweep(s_cur0, splat16(0.f), PlainTag<true>{});
-        // a denominator at or beyond 2^64 (or not finite), or below 2^-80: once more with the exact maximum over all
-        // latent tiles
-        const uint32_t den_exp = (__float_as_uint(acc[8]) >> 23) & 0xffu;
-        if (__any(hh == 0 && (den_exp >= 127u + 64u || den_exp < 127u - 80u))) {
+        f32x16 s_ahead = sweep(s_cur0, splat16(-mx), PlainTag<true>{});
+        // a denominator at or beyond 2^64 (or not finite): once more with the exact maximum over all latent tiles
+        if (__any((__float_as_uint(acc[8]) & 0x7f800000u) >= ((127u + 64u) << 23))) {
             float m = -INFINITY;
             f32x16 hi0 = qk_hi(0, kt), s_cur = hi0, s_next = hi0;
 #pragma unroll
@@ -196,10 +196,11 @@ __global__ __launch_bounds__(64 * HW, HW == 8 ? 1 : 2) void decode_project_kerne
                 s_cur = s_next;
             }
             mx = fmaxf(m, __shfl_xor(m, 32));
-            (void)sweep(first_scores(hi0, mx, kt, true), splat16(-mx), PlainTag<false>{});
+            (void)sweep(first_scores(hi0, mx, kt), splat16(-mx), PlainTag<false>{});
             s_ahead = qk_hi(0, ktn);
         }
-        s_cur0 = first_scores(s_ahead, 0.f, ktn, false);
+        const float mx_next = tile_max(s_ahead);
+        s_cur0 = first_scores(s_ahead, mx_next, ktn);
         const float den = __shfl(acc[8], l32);
         const float inv = 1.f / den;
         // this lane: token l32, columns 4 hh .. 4 hh + 3 (registers 0-3) and 8 + 4 hh .. (registers 4-7) of Y_h
@@ -242,6 +243,7 @@ __global__ __launch_bounds__(64 * HW, HW == 8 ? 1 : 2) void decode_project_kerne
             }
         }
         kt = ktn;
+        mx = mx_next;
     }
 }
 

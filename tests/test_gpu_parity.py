@@ -380,9 +380,9 @@ def test_large_score_offsets(oracle, dtype):
 def test_decode_with_every_token_shifted_differently(dtype, M, d):
     """The decode's softmax runs over the latents of one token, so adding the same amount to all scores of a token
     leaves y unchanged and moves lse_dec by that amount.  Here token n's scores are shifted by a ramp from -138 to
-    +138 log2 units: the kernel's first sweep of a token tile has no stabiliser and must notice, from the
-    denominators alone, every tile that left its range (below 2^-80, from 2^64 on) -- tiles on both sides of both
-    limits, and tiles that straddle them.  Reference: the definition, in fp64 (Eq. flare_decode)."""
+    +138 log2 units, so the tokens of one 32-token tile differ by about 2 units and the tiles span the whole range
+    of fp32 exponents that a stabiliser has to absorb, per token.  Reference: the definition, in fp64
+    (Eq. flare_decode)."""
     import torch
     _say("decode, per-token score shifts, %s M=%d d=%d" % (dtype, M, d))
     N = 4000
