@@ -401,10 +401,12 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
 //   key side 1 in slot 0, query side -c in slot 0, so that every lo term of q' stays in),
 //   lazy online softmax: c moves only when a score exceeds it by more than kLazy (or on the
 //   first tile), then O is rescaled; 2^x, pack; O^T += Vaug^T . P^T, Vaug = [V | 1].
-// V^T is formed through a wave-private, double-buffered LDS tile (no workgroup barrier
-// anywhere): the values of tile j+1 are written while tile j is computed and read back at its
-// end.  Keys are prefetched one tile ahead, values two.  The MFMAs of the next latent tile (or
-// of the next token tile) are issued before the vector work on the current one.
+// V^T is formed through a wave-private, double-buffered LDS tile (no workgroup barrier in the
+// encode; the dZ kernel lines its waves up every 32 tiles): the values of tile j+1 are written
+// while tile j is computed and read back at its end.  Keys and values are requested two tiles
+// ahead; the value rows of consecutive tiles alternate between two sets of registers (a copy of
+// a load in flight would be waited for in the tile that issued it).  The MFMAs of the next
+// latent tile (or of the next token tile) are issued before the vector work on the current one.
 // Output per wave: (c, row sums, unnormalised O) for its latents = one partial slot.
 // ============================================================================================
 // MODE 1 (second step of the backward) reuses the same machinery for dZ = R^T dY: the values are
