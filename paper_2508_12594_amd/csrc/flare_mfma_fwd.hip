@@ -449,7 +449,9 @@ __global__ __launch_bounds__(256, MINB) void encode_mfma_kernel(
     __shared__ __attribute__((aligned(16))) uint16_t vt_all[4][2 * BUF];
 
     const int lane = threadIdx.x & 63, l32 = lane & 31, hh = lane >> 5;
-    const int wave = threadIdx.x >> 6;
+    // (read from the first lane: the compiler then knows it is the same for the whole wave and keeps everything derived
+    // from it -- token groups, tile indices, loop bounds -- on the scalar unit)
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int g = wave % G, tg = wave / G;
     const GridPos gp = grid_pos(ts, H, DR * 2);
     const int bh = gp.y, h = bh % H, chunk = gp.x;
