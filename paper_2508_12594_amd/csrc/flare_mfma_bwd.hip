@@ -53,7 +53,7 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
     __shared__ __attribute__((aligned(16))) float wl_all[ONE ? 4 : 1][2][32];   // w[n] of a token tile
 
     const int lane = threadIdx.x & 63, l32 = lane & 31, hh = lane >> 5;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // known to be wave-uniform: scalar unit
     const int g = wave % G, tg = wave / G;
     const GridPos gp = grid_pos(ts, H, DR * 2);
     const int bh = gp.y, h = bh % H, chunk = gp.x;
@@ -450,7 +450,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // known to be wave-uniform: scalar unit
     const GridPos gp = grid_pos(ts, H, DR * 2);
     const int bh = gp.y, h = bh % H;
     const bool lower = hh == 0;

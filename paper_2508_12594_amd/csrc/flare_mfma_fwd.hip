@@ -47,7 +47,7 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
     constexpr int HV = D / 16;   // 16-wide column groups of Z, each with its own ones row
     constexpr bool PACK = PRE && pack_dim(DR);   // q' hi | lo in one operand, keys repeated in both lane halves
     const int lane = threadIdx.x & 63, l32 = lane & 31, hh = lane >> 5;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // known to be wave-uniform: scalar unit
     const GridPos gp = grid_pos(ts, H, DR * 2);
     const int bh = gp.y, h = bh % H;
     const bool flip = c2 < 0.f;
