@@ -989,15 +989,22 @@ __global__ __launch_bounds__(64 * MT) void gram_mfma_kernel(
 #pragma unroll
     for (int t = 0; t < MT; ++t) acc[t] = splat16(0.f);
 
+    // keys and lse_dec of a tile are requested one tile ahead (the last tile requests itself again: in bounds, unused)
+    bf16x8 kt[KS], ktn[KS];
+    float ld = 0.f, ldn = 0.f;
+    auto request = [&](int j, bf16x8 (&kk)[KS], float &l) {
+        const int n = min(n0 + 32 * min(j, tiles - 1) + l32, N - 1);
+#pragma unroll
+        for (int s = 0; s < KS; ++s) kk[s] = as_bf16x8(row8_bf16<DR>(kb + tok_off(ts, n), (D / 2) * hh + 8 * s));
+        l = lb[n];
+    };
+    if (tiles > 0) request(0, kt, ld);
     for (int j = 0; j < tiles; ++j) {
         const int tok0 = n0 + 32 * j;
-        const int n = min(tok0 + l32, N - 1);
-        bf16x8 kt[KS];
-#pragma unroll
-        for (int s = 0; s < KS; ++s) kt[s] = as_bf16x8(row8_bf16<DR>(kb + tok_off(ts, n), (D / 2) * hh + 8 * s));
+        request(j + 1, ktn, ldn);
         u32x4 wk;
         wk[0] = lower ? 0x3f803f80u : 0u;                                      // slots 0,1 := 1
-        wk[1] = lower ? split_bf16_pair(-0.5f * kLog2e * lb[n]) : 0u;          // slots 2,3 := -lse_dec2[n] / 2
+        wk[1] = lower ? split_bf16_pair(-0.5f * kLog2e * ld) : 0u;             // slots 2,3 := -lse_dec2[n] / 2
         wk[2] = 0u; wk[3] = 0u;
         f32x16 x = splat16(0.f);
 #pragma unroll
@@ -1022,6 +1029,9 @@ __global__ __launch_bounds__(64 * MT) void gram_mfma_kernel(
             acc[t] = mfma(p0, as_bf16x8(buf[t][0][lane]), acc[t]);
             acc[t] = mfma(p1, as_bf16x8(buf[t][1][lane]), acc[t]);
         }
+#pragma unroll
+        for (int s = 0; s < KS; ++s) kt[s] = ktn[s];
+        ld = ldn;
     }
     float *out = g_part + ((size_t)bh * chunks + chunk) * M * M;
 #pragma unroll
