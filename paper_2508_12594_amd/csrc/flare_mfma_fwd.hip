@@ -161,6 +161,22 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
             for (int s = 0; s < KS; ++s)
                 ktn[s] = as_bf16x8(row8_bf16<DR>(kb + tok_off(ts, nld), PACK ? 0 : (D / 2) * hh + 8 * s));
         }
+        // MODE 1: this lane's quartets of the tile's dY rows, used after the sweep (for delta).  Requested here, a
+        // whole tile before their use -- except at d = 32, where their eight registers would cost the kernel its
+        // third wave per SIMD: there they are requested where they are used.
+        constexpr bool EARLY_G = D <= 16;
+        u32x2 gq[MODE == 1 ? HV : 1][2];
+        auto request_g = [&]() {
+            const bf16_t *gr = dy + tok_base(ts, bh, H) + tok_off(ts, min(n, N - 1));
+#pragma unroll
+            for (int hv = 0; hv < HV; ++hv) {
+                gq[hv][0] = u32x2{0u, 0u};
+                gq[hv][1] = u32x2{0u, 0u};
+                if (quartet_inside<DR>(hv, hh, 0)) gq[hv][0] = *reinterpret_cast<const u32x2 *>(gr + 16 * hv + 4 * hh);
+                if (quartet_inside<DR>(hv, hh, 1)) gq[hv][1] = *reinterpret_cast<const u32x2 *>(gr + 16 * hv + 8 + 4 * hh);
+            }
+        };
+        if constexpr (MODE == 1 && EARLY_G) request_g();
         // An opaque copy of the keys for the hi products, so that the compiler keeps them apart from the lo ones.
         bf16x8 kt2[KS];
 #pragma unroll
@@ -327,14 +343,11 @@ __global__ __launch_bounds__(256, MINB) void decode_mfma_kernel(
         const float inv = 1.f / den;
         if constexpr (MODE == 1) {
             const size_t row = (size_t)bh * N + min(n, N - 1);
-            const bf16_t *gr = dy + tok_base(ts, bh, H) + tok_off(ts, min(n, N - 1));
+            if constexpr (!EARLY_G) request_g();
             float part = 0.f;
 #pragma unroll
             for (int hv = 0; hv < HV; ++hv) {
-                u32x2 g0, g1;
-                g0[0] = 0u; g0[1] = 0u; g1[0] = 0u; g1[1] = 0u;
-                if (quartet_inside<DR>(hv, hh, 0)) g0 = *reinterpret_cast<const u32x2 *>(gr + 16 * hv + 4 * hh);
-                if (quartet_inside<DR>(hv, hh, 1)) g1 = *reinterpret_cast<const u32x2 *>(gr + 16 * hv + 8 + 4 * hh);
+                const u32x2 g0 = gq[hv][0], g1 = gq[hv][1];
                 if constexpr (DR <= 8) {   // rows 8 + j: the lo part of column j (zero unless z_lo), same lane
 #pragma unroll
                     for (int i = 0; i < 4; ++i) acc[hv][i] += acc[hv][4 + i];
