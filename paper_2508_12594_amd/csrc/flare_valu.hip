@@ -474,15 +474,21 @@ __global__ __launch_bounds__(kLatentBlock) void dz_partial_kernel(
 #pragma unroll
     for (int j = 0; j < D; ++j) acc[j] = 0.f;
     __shared__ float sink[kLatentBlock];
-    for (int n = n0; n < n1; ++n) {
-        if (((n - n0) & 7) == 0) touch_rows<T>(touch, tok_base(ts, bh, H), ts, n, N, sink);
+    auto token = [&](int n) {
         float kr[D], g[D];
         load_row<D>(kb + tok_off(ts, n), kr);
         const float r = fast_exp2(dot<D>(qm, kr) - lb[n]);
         load_row<D>(gb + tok_off(ts, n), g);
 #pragma unroll
         for (int j = 0; j < D; ++j) acc[j] = fmaf(r, g[j], acc[j]);
+    };
+    int n = n0;
+    for (; n + kGroup <= n1; n += kGroup) {   // whole groups: the touch is unconditional, no branch inside the group
+        touch_rows<T>(touch, tok_base(ts, bh, H), ts, n, N, sink);
+#pragma unroll
+        for (int t = 0; t < kGroup; ++t) token(n + t);
     }
+    for (; n < n1; ++n) token(n);
     store_row<D>(dz_part + (((size_t)bh * chunks + chunk) * M + m) * D, acc);
 }
 
@@ -666,8 +672,7 @@ __global__ __launch_bounds__(kLatentBlock) void dq_partial_kernel(
     const int n0 = chunk * chunk_len;
     const int n1 = min(N, n0 + chunk_len);
     __shared__ float sink[kLatentBlock];
-    for (int n = n0; n < n1; ++n) {
-        if (((n - n0) & 7) == 0) touch_rows<T>(touch, tok_base(ts, bh, H), ts, n, N, sink);
+    auto token = [&](int n) {
         float kr[D], vr[D], g[D];
         load_row<D>(kb + tok_off(ts, n), kr);
         load_row<D>(vb + tok_off(ts, n), vr);
@@ -678,7 +683,14 @@ __global__ __launch_bounds__(kLatentBlock) void dq_partial_kernel(
         const float ds = p * (dot<D>(dzm, vr) - ep) + r * (dot<D>(zm, g) - db[n]);
 #pragma unroll
         for (int j = 0; j < D; ++j) acc[j] = fmaf(ds, kr[j], acc[j]);
+    };
+    int n = n0;
+    for (; n + kGroup <= n1; n += kGroup) {   // whole groups: the touch is unconditional, no branch inside the group
+        touch_rows<T>(touch, tok_base(ts, bh, H), ts, n, N, sink);
+#pragma unroll
+        for (int t = 0; t < kGroup; ++t) token(n + t);
     }
+    for (; n < n1; ++n) token(n);
     store_row<D>(dq_part + (((size_t)bh * chunks + chunk) * M + m) * D, acc);
 }
 
