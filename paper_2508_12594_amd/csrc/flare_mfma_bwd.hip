@@ -804,7 +804,8 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
                 }
                 compiler_fence();
             }
-            sched_fence();
+            // (the fused one-exponential kernel of d = 16 is 0.6 % faster without this fence between its latent tiles)
+            if constexpr (!(DQ && ONE && D == 16)) sched_fence();
         };
         {
             f32x16 sa1 = splat16(0.f), sa2 = splat16(0.f), sb1 = splat16(0.f), sb2 = splat16(0.f);
