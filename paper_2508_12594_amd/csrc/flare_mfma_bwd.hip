@@ -399,8 +399,10 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kDsStride = 36;   // uint16 per row of the dS tile [token][latent] (72 B: conflict-free 8-byte stores)
 constexpr int kFusedWaveLds = 32 * kDsStride + 16 * kVtStride;   // uint16 per wave: dS tile, then K^T tile
 
-template <int DR, int MT, bool DQ, bool ONE, bool F>
-__global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
+// WV: waves per workgroup (one workgroup per CU).  Eight, or twelve where the kernel fits 168 registers (three waves
+// per SIMD): d = 32 with one exponential.
+template <int DR, int MT, bool DQ, bool ONE, bool F, int WV = 8>
+__global__ __launch_bounds__(64 * WV, 1) void bwd_dkdv_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const bf16_t *__restrict__ dy, const float *__restrict__ z, const float *__restrict__ lse_enc,
     const float *__restrict__ dz, const float *__restrict__ eps, const float *__restrict__ lse_dec2,
@@ -468,7 +470,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
         // real latent and every value that could reach dK or dV is zero -- q, Z, dZ, eps, u and the ones
         // that pick -delta -- so that a = c = 0 and dS = 0 whatever P and R come out as.
         const int mleft = Mtot - m0;
-        for (int idx = tid; idx < MT * PER_TILE * 64; idx += 512) {
+        for (int idx = tid; idx < MT * PER_TILE * 64; idx += 64 * WV) {
             const int ln = idx & 63, sid = (idx >> 6) % PER_TILE, t = (idx >> 6) / PER_TILE;
             const int r32 = ln & 31, hf = ln >> 5;
             u32x4 w;
@@ -593,7 +595,8 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
     const float *lb = lse_dec2 + (size_t)bh * N;
     const float *db = delta + (size_t)bh * N;
     const int tiles = (N + 31) / 32;
-    const int stride = gridDim.x * 8;
+    static_assert(!DQ || WV == 8, "the fused dQ reduction is written for eight waves");
+    const int stride = gridDim.x * WV;
     // B operand: column = token.  rep (PACK only): both lane halves get elements 0-7 of the row.
     auto load_cols = [&](const bf16_t *base, int tile, bf16x8 (&t)[KS], bool rep) {
         const int n = min(tile * 32 + l32, N - 1);
@@ -625,7 +628,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkdv_mfma_kernel(
         for (int jb = 0; jb < 2; ++jb) dqa[t][jb] = f32x4{0.f, 0.f, 0.f, 0.f};
     const int c16 = lane & 15, g16 = lane >> 4;
 
-    int tile = gp.x * 8 + wave;
+    int tile = gp.x * WV + wave;
     bf16x8 kt[KS], vt[KS], gt[KS], ktn[KS], vtn[KS], gtn[KS];
     if (tile < tiles) {
         load_cols(kb, tile, kt, true);
@@ -1007,6 +1010,7 @@ int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v,
     const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *vv = (const bf16_t *)v, *gg = (const bf16_t *)dy;
     const bool f16 = s.dtype == FLARE_F16;
     LaunchTimer t(one_exp ? KID_BWD_DKDV : KID_BWD_DKDV_2EXP, stream);
+    int threads = 512;
 #define FLARE_DKDV(DD, MTT, LO)                                                                                  \
     do {                                                                                                         \
         auto kern = f16 ? (one_exp ? bwd_dkdv_mfma_kernel<DD, MTT, LO, true, true>                               \
@@ -1016,7 +1020,7 @@ int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v,
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
                                 (int)lds) != hipSuccess)                                                         \
             return FLARE_ELAUNCH;                                                                                \
-        kern<<<grid, 512, lds, stream>>>(qq, kk, vv, gg, z, lse_enc, dz, eps, lse_dec2, delta, ld_mul, plan,     \
+        kern<<<grid, threads, lds, stream>>>(qq, kk, vv, gg, z, lse_enc, dz, eps, lse_dec2, delta, ld_mul, plan, \
                                          (bf16_t *)dk, (bf16_t *)dv, acc32, dq_part, tok_stride(s), s.H, s.N,    \
                                          s.M, m0, c2, scale);                                                    \
     } while (0)
@@ -1048,6 +1052,17 @@ int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v,
         FLARE_DKDV_MT(8)
     } else if (s.d == 16) {
         FLARE_DKDV_MT(16)
+    } else if (one_exp && MT == 8) {
+        // d = 32, 256 latents, one exponential: 168 registers, so twelve waves (three per SIMD) share the images
+        threads = 768;
+        auto kern = f16 ? bwd_dkdv_mfma_kernel<32, 8, false, true, true, 12>
+                        : bwd_dkdv_mfma_kernel<32, 8, false, true, false, 12>;
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds) != hipSuccess)
+            return FLARE_ELAUNCH;
+        kern<<<grid, threads, lds, stream>>>(qq, kk, vv, gg, z, lse_enc, dz, eps, lse_dec2, delta, ld_mul, plan,
+                                             (bf16_t *)dk, (bf16_t *)dv, acc32, dq_part, tok_stride(s), s.H, s.N,
+                                             s.M, m0, c2, scale);
     } else {
         switch (MT) {
             case 1: FLARE_DKDV(32, 1, false); break;
