@@ -1199,7 +1199,9 @@ static int launch_decode_family(const flare_shape &s, const void *q, const void 
 {
     const int BH = s.B * s.H;
     const int tiles = (s.N + 31) / 32;
-    int blocks = (kDecodeTargetBlocks + BH - 1) / BH;
+    // d = 32 with 192 or 256 latents (Z in LDS, 168 registers): three workgroups fit a CU
+    const bool three = padded_dim(s.d) == 32 && Mc > 128;
+    int blocks = ((three ? 768 : kDecodeTargetBlocks) + BH - 1) / BH;
     if (blocks > (tiles + 3) / 4) blocks = (tiles + 3) / 4;
     const dim3 grid(blocks, BH);
     const float c2 = scale * kLog2e;
