@@ -40,7 +40,7 @@ ProfileState g_prof;
 const char *const kKernelNames[KID_COUNT] = {
     "encode_partial", "encode_merge", "decode", "bwd_token_stats", "bwd_prep", "bwd_dz_partial",
     "bwd_dz_merge", "bwd_dq_partial", "bwd_dq_reduce", "bwd_dkdv", "bwd_dq_partial_2exp",
-    "bwd_dkdv_2exp", "decode_merge", "bwd_dkdv_finish", "spectral_gram", "spectral_reduce", "spectral_eigen",
+    "bwd_dkdv_2exp", "decode_merge", "spectral_gram", "spectral_reduce", "spectral_eigen",
     "spectral_post", "decode_project"};
 }  // namespace
 

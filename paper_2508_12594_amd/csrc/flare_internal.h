@@ -24,7 +24,6 @@ enum KernelId {
     KID_BWD_DQ_PARTIAL_2EXP,
     KID_BWD_DKDV_2EXP,
     KID_DECODE_MERGE,
-    KID_BWD_DKDV_FINISH,
     KID_SPECTRAL_GRAM,
     KID_SPECTRAL_REDUCE,
     KID_SPECTRAL_EIGEN,
@@ -136,7 +135,6 @@ int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v,
               float scale, hipStream_t stream);
 int mfma_dkdv_blocks(const flare_shape &s);
 bool mfma_dq_fused(const flare_shape &s);
-int mfma_dkdv_finish(const flare_shape &s, const float *acc32, void *dk, void *dv, hipStream_t stream);
 int mfma_dq_parts(const flare_shape &s);
 int mfma_dq_partial(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy,
                     const float *z, const float *lse_enc, const float *dz, const float *eps,

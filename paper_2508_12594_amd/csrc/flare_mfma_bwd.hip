@@ -422,7 +422,8 @@ __global__ __launch_bounds__(64 * WV, 1) void bwd_dkdv_mfma_kernel(
     // rounding coherently, see the dQ kernel).
     // The kernel works on the latents m0 .. m0 + M of the head's Mtot.  With acc32 given (more than one
     // latent chunk) it adds its dV and dK rows in fp32 to acc32[0][b*h][n][DR] and acc32[1][...] (the
-    // chunk with m0 = 0 stores instead) and dkdv_finish_kernel rounds the sums to dk and dv.
+    // chunk with m0 = 0 stores instead); the last chunk adds what is there to its own rows and rounds the
+    // sums to dk and dv.  The chunks run as launches in a row on one stream, so the order of the sum is fixed.
     constexpr int D = padded_dim(DR);
     constexpr int KS = D / 16;
     // Row blocks of the two accumulations.  d <= 16: one 32x32 product per 16 columns (rows 16-31 of its
@@ -842,6 +843,10 @@ __global__ __launch_bounds__(64 * WV, 1) void bwd_dkdv_mfma_kernel(
         dl_cur = pinned(delta_next);
         compiler_fence();
         // registers 4 q .. 4 q + 3 of an accumulator: columns (16 hv +) 8 q + 4 hh .. + 3 of this lane's token
+        // More than one latent chunk: all but the first add what the chunks before them left in acc32, and all but
+        // the head's last one leave their sums there; the last one rounds and stores them like a single chunk.
+        const bool from_acc = acc32 != nullptr && m0 != 0;
+        const bool to_acc = acc32 != nullptr && m0 + 32 * MT < Mtot;
         if (n < N) {
 #pragma unroll
             for (int hv = 0; hv < HV; ++hv)
@@ -853,18 +858,21 @@ __global__ __launch_bounds__(64 * WV, 1) void bwd_dkdv_mfma_kernel(
                                            acc1[hv][4 * qd + 3]);
                     float4 b = make_float4(scale * acc2[hv][4 * qd], scale * acc2[hv][4 * qd + 1],
                                            scale * acc2[hv][4 * qd + 2], scale * acc2[hv][4 * qd + 3]);
-                    if (acc32 != nullptr) {
+                    if (from_acc || to_acc) {
                         float *dvr = acc32 + ((size_t)bh * N + n) * DR + o;
                         float *dkr = dvr + (size_t)gridDim.y * N * DR;
-                        if (m0 != 0) {
+                        if (from_acc) {
                             const float4 pa = *reinterpret_cast<const float4 *>(dvr);
                             const float4 pb = *reinterpret_cast<const float4 *>(dkr);
                             a.x += pa.x; a.y += pa.y; a.z += pa.z; a.w += pa.w;
                             b.x += pb.x; b.y += pb.y; b.z += pb.z; b.w += pb.w;
                         }
-                        *reinterpret_cast<float4 *>(dvr) = a;
-                        *reinterpret_cast<float4 *>(dkr) = b;
-                    } else {
+                        if (to_acc) {
+                            *reinterpret_cast<float4 *>(dvr) = a;
+                            *reinterpret_cast<float4 *>(dkr) = b;
+                        }
+                    }
+                    if (!to_acc) {
                         const size_t at = tok_base(ts, bh, H) + tok_off(ts, n) + o;
                         u32x2 w;
                         w[0] = pack_elems<F>(a.x, a.y);
@@ -1078,59 +1086,10 @@ int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v,
     return check_launch();
 }
 
-// fp32 sums of the per-chunk dV and dK rows (M > 256) -> dk, dv in the caller's layout
-namespace {
-template <int DR, bool F>
-__global__ __launch_bounds__(256) void dkdv_finish_kernel(const float *__restrict__ acc32, bf16_t *__restrict__ dk,
-                                                          bf16_t *__restrict__ dv, TokStride ts, int H, int N)
-{
-    const int n = blockIdx.x * 256 + threadIdx.x;
-    if (n >= N) return;
-    const int bh = blockIdx.y;
-    const float *sv = acc32 + ((size_t)bh * N + n) * DR;
-    const float *sk = sv + (size_t)gridDim.y * N * DR;
-    const size_t trow = tok_base(ts, bh, H) + tok_off(ts, n);
-#pragma unroll
-    for (int j = 0; j < DR; j += 4) {
-        const float4 a = *reinterpret_cast<const float4 *>(sv + j);
-        const float4 b = *reinterpret_cast<const float4 *>(sk + j);
-        u32x2 wa, wb;
-        wa[0] = pack_elems<F>(a.x, a.y); wa[1] = pack_elems<F>(a.z, a.w);
-        wb[0] = pack_elems<F>(b.x, b.y); wb[1] = pack_elems<F>(b.z, b.w);
-        *reinterpret_cast<u32x2 *>(dv + trow + j) = wa;
-        *reinterpret_cast<u32x2 *>(dk + trow + j) = wb;
-    }
-}
-}  // namespace
-
 size_t mfma_dkdv_acc_bytes(const flare_shape &s)
 {
     if (s.M <= kLatChunk) return 0;
     return ((size_t)s.B * s.H * s.N * s.d * 4 * 2 + 255) & ~(size_t)255;
-}
-
-int mfma_dkdv_finish(const flare_shape &s, const float *acc32, void *dk, void *dv, hipStream_t stream)
-{
-    const dim3 grid((s.N + 255) / 256, s.B * s.H);
-    LaunchTimer t(KID_BWD_DKDV_FINISH, stream);
-    const bool f16 = s.dtype == FLARE_F16;
-#define FLARE_FIN(DD)                                                                                          \
-    do {                                                                                                       \
-        if (f16)                                                                                               \
-            dkdv_finish_kernel<DD, true><<<grid, 256, 0, stream>>>(acc32, (bf16_t *)dk, (bf16_t *)dv,          \
-                                                                   tok_stride(s), s.H, s.N);                   \
-        else                                                                                                   \
-            dkdv_finish_kernel<DD, false><<<grid, 256, 0, stream>>>(acc32, (bf16_t *)dk, (bf16_t *)dv,         \
-                                                                    tok_stride(s), s.H, s.N);                  \
-    } while (0)
-    switch (s.d) {
-        case 4: FLARE_FIN(4); break;
-        case 8: FLARE_FIN(8); break;
-        case 16: FLARE_FIN(16); break;
-        default: FLARE_FIN(32); break;
-    }
-#undef FLARE_FIN
-    return check_launch();
 }
 
 // partial slots per (b,h) that mfma_dq_partial writes

@@ -969,10 +969,6 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
                                          m0, scale, stream);
                 if (rc != FLARE_OK) return rc;
             }
-        if (chunked) {
-            const int rc = mfma_dkdv_finish(s, w.acc32, dk, dv, stream);
-            if (rc != FLARE_OK) return rc;
-        }
         return dq_fused ? reduce_dq() : FLARE_OK;
     }
     {
