@@ -397,7 +397,8 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
 // ============================================================================================
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kDsStride = 36;   // uint16 per row of the dS tile [token][latent] (72 B: conflict-free 8-byte stores)
-constexpr int kFusedWaveLds = 32 * kDsStride + 16 * kVtStride;   // uint16 per wave: dS tile, then K^T tile
+constexpr int kKtStride = 16;   // uint16 per row of the key tile [token][d] of the fused dQ product (rows as loaded)
+constexpr int kFusedWaveLds = 32 * kDsStride + 32 * kKtStride;   // uint16 per wave: dS tile, then the key tile
 
 // WV: waves per workgroup (one workgroup per CU).  Eight, or twelve where the kernel fits 168 registers (three waves
 // per SIMD): d = 32 with one exponential.
@@ -616,11 +617,8 @@ __global__ __launch_bounds__(64 * WV, 1) void bwd_dkdv_mfma_kernel(
     // fused dQ: wave-private LDS tiles and the accumulators dQ^T[dd = 4 (lane / 16) + r][m = 32 t + 16 jb + lane % 16]
     uint16_t *ds_t = reinterpret_cast<uint16_t *>(img + MT * PER_TILE * 64) + (DQ ? wave * kFusedWaveLds : 0);
     uint16_t *k_t = ds_t + 32 * kDsStride;
-    if constexpr (DQ && PACK) {   // K^T rows 8-15 are never written at d <= 8: zero (the output rows 8-15 are dropped)
-        if (lane < kVtStride) {
-#pragma unroll
-            for (int r = 8; r < 16; ++r) k_t[r * kVtStride + lane] = 0;
-        }
+    if constexpr (DQ && PACK) {   // columns 8-15 of the key tile are never written at d <= 8: zero (the output rows 8-15 are dropped)
+        if (lane < 32) *reinterpret_cast<u32x4 *>(k_t + lane * kKtStride + 8) = u32x4{0u, 0u, 0u, 0u};
     }
     f32x4 dqa[DQ ? MT : 1][2];
 #pragma unroll
@@ -702,17 +700,13 @@ __global__ __launch_bounds__(64 * WV, 1) void bwd_dkdv_mfma_kernel(
         bf16x8 k_op = zero_operand();
         if constexpr (DQ) {
             const u32x4 w = (n < N) ? to_bf16_row<F>(__builtin_bit_cast(u32x4, kt[0])) : __builtin_bit_cast(u32x4, zero_operand());
-            if (!(PACK && hh)) {   // d <= 8: the upper lane half holds a copy of the same elements
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    k_t[(8 * hh + 2 * e) * kVtStride + l32] = (uint16_t)(w[e] & 0xffffu);
-                    k_t[(8 * hh + 2 * e + 1) * kVtStride + l32] = (uint16_t)(w[e] >> 16);
-                }
-            }
+            // the tile as loaded, row = token (one 16-byte store per lane); the transposing read hands lane c16 of block
+            // g16 column c16 of the rows 8 g16 .. + 3 (second read: + 4 .. + 7), as for the dS tile below
+            if (!(PACK && hh))     // d <= 8: the upper lane half holds a copy of the same elements
+                *reinterpret_cast<u32x4 *>(k_t + l32 * kKtStride + 8 * hh) = w;
             compiler_fence();
-            const uint16_t *rowp = k_t + c16 * kVtStride + 8 * g16;
-            const u32x2 lo2 = *reinterpret_cast<const u32x2 *>(rowp);
-            const u32x2 hi2 = *reinterpret_cast<const u32x2 *>(rowp + 4);
+            const uint16_t *src = k_t + (8 * g16 + c16 / 4) * kKtStride + 4 * (c16 % 4);
+            const u32x2 lo2 = lds_read_tr16(src), hi2 = lds_read_tr16(src + 4 * kKtStride);
             u32x4 ka;
             ka[0] = lo2[0]; ka[1] = lo2[1]; ka[2] = hi2[0]; ka[3] = hi2[1];
             k_op = as_bf16x8(ka);
