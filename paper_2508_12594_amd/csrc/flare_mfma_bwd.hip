@@ -48,7 +48,10 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
     // d <= 8: the upper half of the padded contraction carries what otherwise needs products of its own:
     // q' lo and Z lo (K and dY rows repeated in both lane halves) and -eps (against ones in the V operand).
     constexpr bool PACK = pack_dim(DR);
-    constexpr int BUF = ROWS * kVtStride;
+    // d = 32: the key tile goes to LDS as loaded, row = token (kKwStride uint16 a row: 80 B, two 16-byte stores per
+    // lane), and the transposing read forms the K^T operand; d <= 16: transposed on the way in, two bytes a store.
+    constexpr int kKwStride = 40;
+    constexpr int BUF = WIDE ? 32 * kKwStride : ROWS * kVtStride;
     __shared__ __attribute__((aligned(16))) uint16_t kt_all[4][2 * BUF];
     __shared__ __attribute__((aligned(16))) float wl_all[ONE ? 4 : 1][2][32];   // w[n] of a token tile
 
@@ -62,7 +65,7 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
     uint16_t *lds = kt_all[wave];
     float (*wl)[32] = wl_all[ONE ? wave : 0];
     constexpr float kap = 0.f;                  // w[n] = 2^(kap - lse_dec2[n])
-    if (lane < kVtStride) {
+    if (!WIDE && lane < kVtStride) {
         lds[D * kVtStride + lane] = 0;
         lds[BUF + D * kVtStride + lane] = 0;
         if constexpr (PACK) {   // K^T rows 8-15 are never written: zero, so that the unused output rows stay finite
@@ -185,6 +188,13 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
     };
     auto write_kt = [&](const bf16x8 (&t)[KS], uint16_t *buf) {   // transposed: row = d-index, column = token
         if (PACK && !lower) return;   // the upper lane half holds a copy of the same elements
+        if constexpr (WIDE) {
+#pragma unroll
+            for (int s = 0; s < KS; ++s)
+                *reinterpret_cast<u32x4 *>(buf + l32 * kKwStride + (D / 2) * hh + 8 * s) =
+                    to_bf16_row<F>(__builtin_bit_cast(u32x4, t[s]));
+            return;
+        }
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             const u32x4 w = to_bf16_row<F>(__builtin_bit_cast(u32x4, t[s]));   // K as a value: bf16
@@ -201,6 +211,16 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
         for (int hv = 0; hv < HV; ++hv)
 #pragma unroll
             for (int s2 = 0; s2 < 2; ++s2) {
+                if constexpr (WIDE) {
+                    // lanes 16 i .. 16 i + 15 hand in four rows (tokens) of 16 columns (d-indices 16 (i & 1) ..) and
+                    // lane c of them receives column c of the four: tokens 16 s2 + 4 hh + 0..3, then + 8..11
+                    const int c16 = lane & 15;
+                    const uint16_t *src =
+                        buf + (16 * s2 + 4 * hh + (c16 >> 2)) * kKwStride + 16 * (l32 >> 4) + 4 * (c16 & 3);
+                    const u32x2 a = lds_read_tr16(src), b = lds_read_tr16(src + 8 * kKwStride);
+                    kT[hv][s2] = as_bf16x8(u32x4{a[0], a[1], b[0], b[1]});
+                    continue;
+                }
                 const uint16_t *row = buf + krow[hv] * kVtStride + 16 * s2 + 4 * hh;
                 const u32x2 a = *reinterpret_cast<const u32x2 *>(row);
                 const u32x2 b = *reinterpret_cast<const u32x2 *>(row + 8);
