@@ -63,7 +63,6 @@ def algorithmic_bytes(kernel, B, H, N, M, d, elem):
         "bwd_dz_partial": 3 * row + 8,          # k, dy, y, lse_dec in; delta out (saved-statistics path)
         "bwd_dq_partial": 3 * row + 8,          # k, v, dy, lse_dec, delta in
         "bwd_dkdv": 5 * row + 8,                # k, v, dy in; dk, dv out
-        "bwd_dq_partial_2exp": 3 * row + 8,
         "bwd_dkdv_2exp": 5 * row + 8,
     }
     if kernel in per_token:
@@ -77,7 +76,7 @@ def exponentials(kernel, B, H, N, M):
     a multiplication, R = P * 2^(lse_enc2[m] - lse_dec2[n]); their two-exponential fall-backs are
     priced at two.)"""
     per_pair = {"encode_partial": 1, "decode": 1, "bwd_token_stats": 1, "bwd_dz_partial": 1,
-                "bwd_dq_partial": 1, "bwd_dkdv": 1, "bwd_dq_partial_2exp": 2, "bwd_dkdv_2exp": 2}
+                "bwd_dq_partial": 1, "bwd_dkdv": 1, "bwd_dkdv_2exp": 2}
     return per_pair.get(kernel, 0) * B * H * N * M
 
 
@@ -99,7 +98,6 @@ def issue_clocks_per_tile(kernel, d, fused_dq):
         "bwd_dq_partial": (16, 16, 32, score + 2 * ks + value),                       # scores, a, c, dS.K
         "bwd_dkdv": (16, 16, 32, score + 2 * ks + 2 * value + (1 if fused_dq else 0)),  # + dV, dK (, dQ: 16-row products)
     }
-    mix["bwd_dq_partial_2exp"] = (32,) + mix["bwd_dq_partial"][1:]
     mix["bwd_dkdv_2exp"] = (32,) + mix["bwd_dkdv"][1:]
     if kernel not in mix:
         return None
@@ -225,7 +223,7 @@ def run_workload(cfg, args, steps, warmup, primary):
     prof = binding.profile_read()
     binding.profile_enable(False)
 
-    fused_dq = "bwd_dq_partial" not in prof and "bwd_dq_partial_2exp" not in prof
+    fused_dq = "bwd_dq_partial" not in prof
     tiles_per_simd = B * H * ((N + 31) // 32) * ((M + 31) // 32) / SIMDS
     kernels = {}
     for name, (ms, cnt) in prof.items():

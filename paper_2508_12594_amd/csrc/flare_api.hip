@@ -39,7 +39,7 @@ struct ProfileState {
 ProfileState g_prof;
 const char *const kKernelNames[KID_COUNT] = {
     "encode_partial", "encode_merge", "decode", "bwd_token_stats", "bwd_prep", "bwd_dz_partial",
-    "bwd_dz_merge", "bwd_dq_partial", "bwd_dq_reduce", "bwd_dkdv", "bwd_dq_partial_2exp",
+    "bwd_dz_merge", "bwd_dq_partial", "bwd_dq_reduce", "bwd_dkdv",
     "bwd_dkdv_2exp", "decode_merge", "spectral_gram", "spectral_reduce", "spectral_eigen",
     "spectral_post", "decode_project"};
 }  // namespace

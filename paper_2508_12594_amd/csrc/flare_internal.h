@@ -21,7 +21,6 @@ enum KernelId {
     KID_BWD_DQ_PARTIAL,
     KID_BWD_DQ_REDUCE,
     KID_BWD_DKDV,
-    KID_BWD_DQ_PARTIAL_2EXP,
     KID_BWD_DKDV_2EXP,
     KID_DECODE_MERGE,
     KID_SPECTRAL_GRAM,
@@ -131,15 +130,15 @@ bool mfma_dkdv_supported(const flare_shape &s);
 // lse_dec with ld_mul = log2(e).
 int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy, const float *z,
               const float *lse_enc, const float *dz, const float *eps, const float *lse_dec2, const float *delta,
-              float ld_mul, const int *plan, bool one_exp, void *dk, void *dv, float *acc32, float *dq_part, int m0,
-              float scale, hipStream_t stream);
+              float ld_mul, const int *plan, void *dk, void *dv, float *acc32, float *dq_part, int m0, float scale,
+              hipStream_t stream);
 int mfma_dkdv_blocks(const flare_shape &s);
 bool mfma_dq_fused(const flare_shape &s);
 int mfma_dq_parts(const flare_shape &s);
 int mfma_dq_partial(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy,
                     const float *z, const float *lse_enc, const float *dz, const float *eps,
-                    const float *lse_dec2, const float *delta, float ld_mul, const int *plan, bool one_exp,
-                    float *dq_part, float scale, hipStream_t stream);
+                    const float *lse_dec2, const float *delta, float ld_mul, const int *plan, float *dq_part,
+                    float scale, hipStream_t stream);
 // y and delta_out may be NULL; when given, delta_out[b][h][n] = <dY_n, Y_n> is written as a by-product.
 int mfma_dz_partial(const flare_shape &s, const void *q, const void *k, const void *dy, const float *lse_dec2,
                     float ld_mul, const void *y, float *delta_out, float *ld_range, float *dz_part, float scale,

@@ -30,7 +30,7 @@ namespace {
 // otherwise the ONE = false variant runs.  Each variant returns at once when the plan names the other.
 // ============================================================================================
 template <int DR, int NB, int MINB, bool ONE, bool F>
-__global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
+__device__ __forceinline__ void dq_body(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const bf16_t *__restrict__ dy, const float *__restrict__ z, const float *__restrict__ lse_enc,
     const float *__restrict__ dz, const float *__restrict__ eps, const float *__restrict__ lse_dec2,
@@ -389,6 +389,25 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
     }
 }
 
+// Both variants in one launch: each workgroup takes the one that the plan names for its (b,h) (a second launch whose
+// workgroups all leave at once would still cost 4-6 us).  The two bodies share the kernel's registers; their LDS adds up.
+template <int DR, int NB, int MINB, bool F>
+__global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
+    const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
+    const bf16_t *__restrict__ dy, const float *__restrict__ z, const float *__restrict__ lse_enc,
+    const float *__restrict__ dz, const float *__restrict__ eps, const float *__restrict__ lse_dec2,
+    const float *__restrict__ delta, float ld_mul, const int *__restrict__ plan, float *__restrict__ dq_part,
+    TokStride ts, int H, int N, int M, int chunk_len, int parts, int G, int TG, float c2)
+{
+    const int bh = grid_pos(ts, H, DR * 2).y;
+    if (plan[bh] != 0)
+        dq_body<DR, NB, MINB, true, F>(q, k, v, dy, z, lse_enc, dz, eps, lse_dec2, delta, ld_mul, plan, dq_part, ts, H, N,
+                                       M, chunk_len, parts, G, TG, c2);
+    else
+        dq_body<DR, NB, MINB, false, F>(q, k, v, dy, z, lse_enc, dz, eps, lse_dec2, delta, ld_mul, plan, dq_part, ts, H, N,
+                                        M, chunk_len, parts, G, TG, c2);
+}
+
 // ============================================================================================
 // Backward, dK and dV (token-major, like the decode: one wave owns 32 tokens at a time and walks
 // over all latent tiles).  Everything that depends on the latents only is prepared once per
@@ -423,7 +442,7 @@ constexpr int kFusedWaveLds = 32 * kDsStride + 32 * kKtStride;   // uint16 per w
 // WV: waves per workgroup (one workgroup per CU).  Eight, or twelve where the kernel fits 168 registers (three waves
 // per SIMD): d = 32 with one exponential.
 template <int DR, int MT, bool DQ, bool ONE, bool F, int WV = 8>
-__global__ __launch_bounds__(64 * WV, 1) void bwd_dkdv_mfma_kernel(
+__device__ __forceinline__ void dkdv_body(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const bf16_t *__restrict__ dy, const float *__restrict__ z, const float *__restrict__ lse_enc,
     const float *__restrict__ dz, const float *__restrict__ eps, const float *__restrict__ lse_dec2,
@@ -934,13 +953,43 @@ __global__ __launch_bounds__(64 * WV, 1) void bwd_dkdv_mfma_kernel(
     }
 }
 
+#define FLARE_DKDV_PARAMS                                                                                        \
+    const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,                    \
+        const bf16_t *__restrict__ dy, const float *__restrict__ z, const float *__restrict__ lse_enc,           \
+        const float *__restrict__ dz, const float *__restrict__ eps, const float *__restrict__ lse_dec2,         \
+        const float *__restrict__ delta, float ld_mul, const int *__restrict__ plan, bf16_t *__restrict__ dk,    \
+        bf16_t *__restrict__ dv, float *__restrict__ acc32, float *__restrict__ dq_part, TokStride ts, int H,    \
+        int N, int Mtot, int m0, float c2, float scale
+#define FLARE_DKDV_PASS \
+    q, k, v, dy, z, lse_enc, dz, eps, lse_dec2, delta, ld_mul, plan, dk, dv, acc32, dq_part, ts, H, N, Mtot, m0, c2, scale
+
+// One variant per launch (the workgroups of a (b,h) that the plan gives to the other variant leave at once) ...
+template <int DR, int MT, bool DQ, bool ONE, bool F, int WV = 8>
+__global__ __launch_bounds__(64 * WV, 1) void bwd_dkdv_mfma_kernel(FLARE_DKDV_PARAMS)
+{
+    dkdv_body<DR, MT, DQ, ONE, F, WV>(FLARE_DKDV_PASS);
+}
+
+// ... or both in one launch, each workgroup taking the variant that the plan names for its (b,h): one launch less per
+// step (a launch whose workgroups all leave at once still costs 4-6 us).  Both bodies share the kernel's registers,
+// which at one workgroup per CU costs nothing.
+template <int DR, int MT, bool DQ, bool F>
+__global__ __launch_bounds__(512, 1) void bwd_dkdv_planned_kernel(FLARE_DKDV_PARAMS)
+{
+    const int bh = grid_pos(ts, H, DR * 2).y;
+    if (plan[bh] != 0) dkdv_body<DR, MT, DQ, true, F, 8>(FLARE_DKDV_PASS);
+    else dkdv_body<DR, MT, DQ, false, F, 8>(FLARE_DKDV_PASS);
+}
+#undef FLARE_DKDV_PASS
+#undef FLARE_DKDV_PARAMS
+
 }  // namespace
 
 // dQ partials of the backward; slot layout as the encode partials: [(b*h) * parts + part][M][d]
 int mfma_dq_partial(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy,
                     const float *z, const float *lse_enc, const float *dz, const float *eps,
-                    const float *lse_dec2, const float *delta, float ld_mul, const int *plan, bool one_exp,
-                    float *dq_part, float scale, hipStream_t stream)
+                    const float *lse_dec2, const float *delta, float ld_mul, const int *plan, float *dq_part,
+                    float scale, hipStream_t stream)
 {
     const MfmaPlan p = mfma_plan(s);
     int zdim;
@@ -950,21 +999,15 @@ int mfma_dq_partial(const flare_shape &s, const void *q, const void *k, const vo
     const int parts = p.enc.chunks * e.TG;
     const dim3 grid(p.enc.chunks, BH, zdim);
     const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *vv = (const bf16_t *)v, *gg = (const bf16_t *)dy;
-    LaunchTimer t(one_exp ? KID_BWD_DQ_PARTIAL : KID_BWD_DQ_PARTIAL_2EXP, stream);
+    LaunchTimer t(KID_BWD_DQ_PARTIAL, stream);
     const bool f16 = s.dtype == FLARE_F16;
 #define FLARE_DQ_ARGS                                                                                            \
     qq, kk, vv, gg, z, lse_enc, dz, eps, lse_dec2, delta, ld_mul, plan, dq_part, tok_stride(s), s.H, s.N, s.M,   \
         p.enc.chunk_len, parts, e.G, e.TG, c2
 #define FLARE_DQ(DD, NBB, MINB)                                                                                  \
     do {                                                                                                         \
-        if (one_exp && f16)                                                                                      \
-            bwd_dq_mfma_kernel<DD, NBB, MINB, true, true><<<grid, e.threads, 0, stream>>>(FLARE_DQ_ARGS);        \
-        else if (one_exp)                                                                                        \
-            bwd_dq_mfma_kernel<DD, NBB, MINB, true, false><<<grid, e.threads, 0, stream>>>(FLARE_DQ_ARGS);       \
-        else if (f16)                                                                                            \
-            bwd_dq_mfma_kernel<DD, NBB, MINB, false, true><<<grid, e.threads, 0, stream>>>(FLARE_DQ_ARGS);       \
-        else                                                                                                     \
-            bwd_dq_mfma_kernel<DD, NBB, MINB, false, false><<<grid, e.threads, 0, stream>>>(FLARE_DQ_ARGS);      \
+        if (f16) bwd_dq_mfma_kernel<DD, NBB, MINB, true><<<grid, e.threads, 0, stream>>>(FLARE_DQ_ARGS);         \
+        else bwd_dq_mfma_kernel<DD, NBB, MINB, false><<<grid, e.threads, 0, stream>>>(FLARE_DQ_ARGS);            \
     } while (0)
 #define FLARE_DQ_NB(DD)                      \
     do {                                     \
@@ -1015,10 +1058,11 @@ bool mfma_dq_fused(const flare_shape &s)
 
 int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v, const void *dy, const float *z,
               const float *lse_enc, const float *dz, const float *eps, const float *lse_dec2, const float *delta,
-              float ld_mul, const int *plan, bool one_exp, void *dk, void *dv, float *acc32, float *dq_part, int m0,
-              float scale, hipStream_t stream)
+              float ld_mul, const int *plan, void *dk, void *dv, float *acc32, float *dq_part, int m0, float scale,
+              hipStream_t stream)
 {
-    // dq_part != NULL: also write the dQ partials (mfma_dq_fused(s) must hold), slot layout
+    // Both variants (one or two exponentials per score, whichever the plan names for a (b,h)) for the latent chunk
+    // that starts at m0.  dq_part != NULL: also write the dQ partials (mfma_dq_fused(s) must hold), slot layout
     // [(b*h) * mfma_dkdv_blocks(s) + block][M][d]
     const int BH = s.B * s.H;
     const dim3 grid(mfma_dkdv_blocks(s), BH);
@@ -1031,72 +1075,67 @@ int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v,
     const size_t lds = (size_t)MT * (4 * KS + 1 + 4 * HV) * 1024 + (fuse ? 8 * kFusedWaveLds * 2 : 0);
     const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *vv = (const bf16_t *)v, *gg = (const bf16_t *)dy;
     const bool f16 = s.dtype == FLARE_F16;
-    LaunchTimer t(one_exp ? KID_BWD_DKDV : KID_BWD_DKDV_2EXP, stream);
-    int threads = 512;
-#define FLARE_DKDV(DD, MTT, LO)                                                                                  \
+#define FLARE_DKDV_LAUNCH(KERN, THREADS)                                                                         \
     do {                                                                                                         \
-        auto kern = f16 ? (one_exp ? bwd_dkdv_mfma_kernel<DD, MTT, LO, true, true>                               \
-                                   : bwd_dkdv_mfma_kernel<DD, MTT, LO, false, true>)                             \
-                        : (one_exp ? bwd_dkdv_mfma_kernel<DD, MTT, LO, true, false>                              \
-                                   : bwd_dkdv_mfma_kernel<DD, MTT, LO, false, false>);                           \
+        auto kern = KERN;                                                                                        \
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
                                 (int)lds) != hipSuccess)                                                         \
             return FLARE_ELAUNCH;                                                                                \
-        kern<<<grid, threads, lds, stream>>>(qq, kk, vv, gg, z, lse_enc, dz, eps, lse_dec2, delta, ld_mul, plan, \
-                                         (bf16_t *)dk, (bf16_t *)dv, acc32, dq_part, tok_stride(s), s.H, s.N,    \
-                                         s.M, m0, c2, scale);                                                    \
+        kern<<<grid, THREADS, lds, stream>>>(qq, kk, vv, gg, z, lse_enc, dz, eps, lse_dec2, delta, ld_mul, plan, \
+                                             (bf16_t *)dk, (bf16_t *)dv, acc32, dq_part, tok_stride(s), s.H,     \
+                                             s.N, s.M, m0, c2, scale);                                           \
     } while (0)
-#define FLARE_DKDV_MT(DD)                              \
-    switch (MT) {                                      \
-        case 1: FLARE_DKDV(DD, 1, false); break;       \
-        case 2: FLARE_DKDV(DD, 2, false); break;       \
-        case 4: FLARE_DKDV(DD, 4, false); break;       \
-        case 8: FLARE_DKDV(DD, 8, false); break;       \
-        default: return FLARE_EUNSUPPORTED;            \
+    if (s.d == 32 && MT == 8) {
+        // d = 32, 256 latents: the one-exponential variant fits 168 registers, so twelve waves (three per SIMD) share
+        // its images; the two-exponential variant keeps eight.  One launch each.
+        {
+            LaunchTimer t(KID_BWD_DKDV, stream);
+            if (f16) FLARE_DKDV_LAUNCH((bwd_dkdv_mfma_kernel<32, 8, false, true, true, 12>), 768);
+            else FLARE_DKDV_LAUNCH((bwd_dkdv_mfma_kernel<32, 8, false, true, false, 12>), 768);
+        }
+        if (check_launch() != FLARE_OK) return FLARE_ELAUNCH;
+        LaunchTimer t(KID_BWD_DKDV_2EXP, stream);
+        if (f16) FLARE_DKDV_LAUNCH((bwd_dkdv_mfma_kernel<32, 8, false, false, true, 8>), 512);
+        else FLARE_DKDV_LAUNCH((bwd_dkdv_mfma_kernel<32, 8, false, false, false, 8>), 512);
+        return check_launch();
     }
-#define FLARE_DKDV_MT_DQ(DD)                           \
-    switch (MT) {                                      \
-        case 1: FLARE_DKDV(DD, 1, true); break;        \
-        case 2: FLARE_DKDV(DD, 2, true); break;        \
-        case 4: FLARE_DKDV(DD, 4, true); break;        \
-        case 8: FLARE_DKDV(DD, 8, true); break;        \
-        default: return FLARE_EUNSUPPORTED;            \
+    LaunchTimer t(KID_BWD_DKDV, stream);
+#define FLARE_DKDV(DD, MTT, LO)                                                                 \
+    do {                                                                                        \
+        if (f16) FLARE_DKDV_LAUNCH((bwd_dkdv_planned_kernel<DD, MTT, LO, true>), 512);          \
+        else FLARE_DKDV_LAUNCH((bwd_dkdv_planned_kernel<DD, MTT, LO, false>), 512);             \
+    } while (0)
+#define FLARE_DKDV_MT(DD, LO)                       \
+    switch (MT) {                                   \
+        case 1: FLARE_DKDV(DD, 1, LO); break;       \
+        case 2: FLARE_DKDV(DD, 2, LO); break;       \
+        case 4: FLARE_DKDV(DD, 4, LO); break;       \
+        case 8: FLARE_DKDV(DD, 8, LO); break;       \
+        default: return FLARE_EUNSUPPORTED;         \
     }
     if (s.d == 4 && fuse) {
-        FLARE_DKDV_MT_DQ(4)
+        FLARE_DKDV_MT(4, true)
     } else if (s.d == 8 && fuse) {
-        FLARE_DKDV_MT_DQ(8)
+        FLARE_DKDV_MT(8, true)
     } else if (s.d == 16 && fuse) {
-        FLARE_DKDV_MT_DQ(16)
+        FLARE_DKDV_MT(16, true)
     } else if (s.d == 4) {
-        FLARE_DKDV_MT(4)
+        FLARE_DKDV_MT(4, false)
     } else if (s.d == 8) {
-        FLARE_DKDV_MT(8)
+        FLARE_DKDV_MT(8, false)
     } else if (s.d == 16) {
-        FLARE_DKDV_MT(16)
-    } else if (one_exp && MT == 8) {
-        // d = 32, 256 latents, one exponential: 168 registers, so twelve waves (three per SIMD) share the images
-        threads = 768;
-        auto kern = f16 ? bwd_dkdv_mfma_kernel<32, 8, false, true, true, 12>
-                        : bwd_dkdv_mfma_kernel<32, 8, false, true, false, 12>;
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)lds) != hipSuccess)
-            return FLARE_ELAUNCH;
-        kern<<<grid, threads, lds, stream>>>(qq, kk, vv, gg, z, lse_enc, dz, eps, lse_dec2, delta, ld_mul, plan,
-                                             (bf16_t *)dk, (bf16_t *)dv, acc32, dq_part, tok_stride(s), s.H, s.N,
-                                             s.M, m0, c2, scale);
+        FLARE_DKDV_MT(16, false)
     } else {
-        switch (MT) {
+        switch (MT) {   // d = 32 (with 256 latents: above)
             case 1: FLARE_DKDV(32, 1, false); break;
             case 2: FLARE_DKDV(32, 2, false); break;
             case 4: FLARE_DKDV(32, 4, false); break;
-            case 8: FLARE_DKDV(32, 8, false); break;
             default: return FLARE_EUNSUPPORTED;
         }
     }
-#undef FLARE_DKDV_MT_DQ
 #undef FLARE_DKDV_MT
 #undef FLARE_DKDV
+#undef FLARE_DKDV_LAUNCH
     return check_launch();
 }
 

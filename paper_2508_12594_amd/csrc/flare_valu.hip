@@ -931,11 +931,9 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
         dq_parts = mfma_dkdv_blocks(s);
     } else if (mf) {
         dq_parts = mfma_dq_parts(s);
-        for (int one = 1; one >= 0; --one) {   // each (b,h) slice is computed by exactly one of the two
-            const int rc = mfma_dq_partial(s, q, k, v, dy, z, lse_enc, w.dz, w.eps, ld, w.delta, ld_mul, w.plan,
-                                           one != 0, w.part, scale, stream);
-            if (rc != FLARE_OK) return rc;
-        }
+        const int rc = mfma_dq_partial(s, q, k, v, dy, z, lse_enc, w.dz, w.eps, ld, w.delta, ld_mul, w.plan, w.part,
+                                       scale, stream);   // each (b,h) slice by the variant its plan names
+        if (rc != FLARE_OK) return rc;
     } else {
         LaunchTimer t(KID_BWD_DQ_PARTIAL, stream);
         dq_partial_kernel<T, D><<<lat_grid, kLatentBlock, 0, stream>>>(q, k, v, dy, z, lse_enc, w.dz, w.eps,
@@ -962,13 +960,11 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     }
     if (mf && mfma_dkdv_supported(s)) {
         const bool chunked = mfma_dkdv_acc_bytes(s) != 0;   // more than 256 latents: one pass per chunk
-        for (int m0 = 0; m0 < s.M; m0 += 256)
-            for (int one = 1; one >= 0; --one) {
-                const int rc = mfma_dkdv(s, q, k, v, dy, z, lse_enc, w.dz, w.eps, ld, w.delta, ld_mul, w.plan,
-                                         one != 0, dk, dv, chunked ? w.acc32 : nullptr, dq_fused ? w.part : nullptr,
-                                         m0, scale, stream);
-                if (rc != FLARE_OK) return rc;
-            }
+        for (int m0 = 0; m0 < s.M; m0 += 256) {   // each (b,h) slice by the variant its plan names
+            const int rc = mfma_dkdv(s, q, k, v, dy, z, lse_enc, w.dz, w.eps, ld, w.delta, ld_mul, w.plan, dk, dv,
+                                     chunked ? w.acc32 : nullptr, dq_fused ? w.part : nullptr, m0, scale, stream);
+            if (rc != FLARE_OK) return rc;
+        }
         return dq_fused ? reduce_dq() : FLARE_OK;
     }
     {
