@@ -450,12 +450,14 @@ def test_backward_separate_dq_kernel(oracle, cfg, over):
     assert slice_relerr(to_host(dq2), to_host(dq1)) <= tol and slice_relerr(to_host(dk2), to_host(dk1)) <= tol
 
 
-def test_backward_wide_score_range_picks_variant_per_head(oracle):
+@pytest.mark.parametrize("M,d", [(64, 16), (128, 32), (256, 32)])
+def test_backward_wide_score_range_picks_variant_per_head(oracle, M, d):
     """Head 0 has ordinary scores; head 1 has per-latent score offsets hundreds of log2 units apart,
     where one exponential per score would underflow: the library must take the two-exponential
-    kernels for that head alone and stay within tolerance on both."""
-    _say("backward wide score range, mixed heads")
-    inp = synth.make_inputs(2, B=1, H=2, N=1500, M=64, d=16, with_dy=True)
+    kernels for that head alone and stay within tolerance on both.  (d = 16: dQ, dK and dV from one kernel that
+    holds both variants; d = 32: a dQ kernel of that kind and, at 256 latents, one dK/dV launch per variant.)"""
+    _say("backward wide score range, mixed heads, M = %d, d = %d" % (M, d))
+    inp = synth.make_inputs(2, B=1, H=2, N=1500, M=M, d=d, with_dy=True)
     q, k = inp["q"].copy(), inp["k"].copy()
     k[:, 1, :, 0] = 4.0
     q[1, :, 0] = np.linspace(-120.0, 120.0, q.shape[1], dtype=np.float32)
