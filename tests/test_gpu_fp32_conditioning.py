@@ -50,6 +50,7 @@ CASES = [
     # and two from a third sweep (fewer tokens than latents at d = 4)
     dict(kind=2, B=3, H=1, N=217, M=296, d=4, seed=777 + 21402, layout="bhnd", saved=True, shared=False),
     dict(kind=2, B=1, H=2, N=59, M=176, d=4, seed=777 + 22884, layout="bnhd", saved=False, shared=False),
+    dict(kind=2, B=2, H=3, N=436, M=257, d=4, seed=777 + 25080, layout="bhnd", saved=False, shared=False),
     # a well-conditioned shape for comparison (first reference workload: normal inputs): plain bar
     dict(kind=1, B=1, H=4, N=1024, M=64, d=32, seed=250812595, layout="bhnd", saved=False, shared=False),
 ]
