@@ -24,6 +24,9 @@ and the same bound with K_dK = scale * (||sum_m P_mn eps_m q_m||_F + ||delta_n q
 slice.  It stays near 10 on the shapes above; the fourth case (two tokens, 252 latents, scores doubled, found
 by a random sweep at dk = 1.4e-4) has K_dK = 384: with two tokens every latent's encode weights are almost
 one-hot, dK is a small remainder of terms 384 times its size, and 1e-5 + 8 * 2^-24 * 384 = 1.9e-4.
+
+The last test of the file pins the one 16-bit case of the same kind that the sweeps found (bf16, 692 latents over 242
+tokens), with the rounding of the bf16 weights in place of the fp32 one.
 """
 import sys
 
