@@ -25,7 +25,7 @@ slice.  It stays near 10 on the shapes above; the fourth case (two tokens, 252 l
 by a random sweep at dk = 1.4e-4) has K_dK = 384: with two tokens every latent's encode weights are almost
 one-hot, dK is a small remainder of terms 384 times its size, and 1e-5 + 8 * 2^-24 * 384 = 1.9e-4.
 
-The last test of the file pins the one 16-bit case of the same kind that the sweeps found (bf16, 692 latents over 242
+The last test of the file pins the three 16-bit cases of the same kind that the sweeps found (many more latents than
 tokens), with the rounding of the bf16 weights in place of the fp32 one.
 """
 import sys
@@ -136,32 +136,43 @@ def test_fp32_gradients_meet_the_bar_up_to_their_conditioning(oracle, case):
         assert max(K, K_dk) <= 20.0 and max(errs["dq"], errs["dk"]) <= 1e-5      # well-conditioned: the plain bar
 
 
-def test_bf16_gradient_of_a_dominating_latent_within_its_conditioning(oracle):
-    """The same conditioning on the matrix cores (bf16 storage, 692 latents over 242 tokens, d = 16, mesh-like inputs;
-    one case in 8300 of a random sweep over 257 ... 2048 latents): dq_lat reads 2.4e-2 against the bar of 2e-2, more
-    than half of the squared error in ONE latent row, 87 % in five -- rows whose two halves are each K times their
-    difference (K = 14 over the head).  The weights P and dS enter the matrix products rounded to bf16 (2^-9
-    relative), so the bound the arithmetic meets is 2e-2 + 2^-9 K; every other output is at the plain bar."""
+SIXTEEN_BIT_CASES = [
+    dict(dtype="bf16", N=242, M=692, d=16, seed=777 + 7966, layout="bhnd"),     # measured dq_lat 2.39e-2
+    dict(dtype="bf16", N=427, M=1539, d=16, seed=777 + 17910, layout="bnhd"),   # 2.49e-2
+    dict(dtype="f16", N=9, M=1157, d=16, seed=777 + 15775, layout="bhnd"),      # 3.08e-2 (nine tokens)
+]
+
+
+@pytest.mark.parametrize("case", SIXTEEN_BIT_CASES, ids=lambda c: "%(dtype)s-N%(N)d-M%(M)d" % c)
+def test_16bit_gradient_of_dominating_latents_within_its_conditioning(oracle, case):
+    """The same conditioning on the matrix cores (16-bit storage, mesh-like inputs, many more latents than tokens; the
+    three cases over the bar of 2e-2 in 20 000 shapes of a random sweep over 257 ... 2048 latents): dq_lat reads
+    2.4e-2 ... 3.1e-2, most of the squared error in a handful of latent rows -- rows whose two halves are each K times
+    their difference.  The weights P and dS enter the matrix products rounded to bf16 (2^-9 relative) whatever the
+    storage type, so the bound the arithmetic meets is 2e-2 + 2^-9 K; every other output is at the plain bar."""
     import torch
-    c = dict(kind=2, B=1, H=1, N=242, M=692, d=16, seed=777 + 7966)
-    print("[case] bf16 conditioning %s" % (c,), flush=True)
-    inp = synth.make_inputs(c["kind"], B=1, H=1, N=c["N"], M=c["M"], d=c["d"], dtype="bf16", with_dy=True, seed=c["seed"])
+    c = case
+    print("[case] 16-bit conditioning %s" % (c,), flush=True)
+    inp = synth.make_inputs(2, B=1, H=1, N=c["N"], M=c["M"], d=c["d"], dtype=c["dtype"], with_dy=True, seed=c["seed"])
     scale = 1.0 / np.sqrt(c["d"])
     dev = to_device(inp)
-    y, z, lse = binding.forward(dev["q"], dev["k"], dev["v"], scale)
-    dq, dk, dv = binding.backward(dev["q"], dev["k"], dev["v"], dev["dy"], z, lse, scale)
+    conv = (lambda t: t.permute(0, 2, 1, 3).contiguous()) if c["layout"] == "bnhd" else (lambda t: t)
+    back = (lambda t: t.permute(0, 2, 1, 3)) if c["layout"] == "bnhd" else (lambda t: t)
+    k, v, dy = conv(dev["k"]), conv(dev["v"]), conv(dev["dy"])
+    y, z, lse = binding.forward(dev["q"], k, v, scale, layout=c["layout"])
+    dq, dk, dv = binding.backward(dev["q"], k, v, dy, z, lse, scale, layout=c["layout"])
     torch.cuda.synchronize()
     y_ref, z_ref, _ = oracle.forward(inp["q"], inp["k"], inp["v"], scale)
     dq_ref, dk_ref, dv_ref = oracle.backward(inp["q"], inp["k"], inp["v"], inp["dy"], scale)
-    errs = dict(y=slice_relerr(to_host(y), y_ref), z=slice_relerr(to_host(z), z_ref),
-                dk=slice_relerr(to_host(dk), dk_ref), dv=slice_relerr(to_host(dv), dv_ref),
+    errs = dict(y=slice_relerr(to_host(back(y)), y_ref), z=slice_relerr(to_host(z), z_ref),
+                dk=slice_relerr(to_host(back(dk)), dk_ref), dv=slice_relerr(to_host(back(dv)), dv_ref),
                 dq=slice_relerr(to_host(dq), dq_ref))
     K, K_dk = _cancellation_factor(inp["q"], inp["k"], inp["v"], inp["dy"], scale, dq_ref, dk_ref)
     rows = np.sort(np.sum((to_host(dq)[0].astype(np.float64) - dq_ref[0]) ** 2, axis=1))[::-1]
-    share = float(rows[:5].sum() / rows.sum())
+    share = float(rows[:max(5, c["M"] // 50)].sum() / rows.sum())
     bound = 2e-2 + 2.0 ** -9 * K
     print("[case]    " + "  ".join("%s %.2e" % kv for kv in errs.items()) +
-          "  K %.1f (dQ) %.1f (dK) -> bound %.2e; five rows hold %.0f %% of the squared error" % (K, K_dk, bound, 100 * share),
+          "  K %.1f (dQ) %.1f (dK) -> bound %.2e; 2 %% of the rows hold %.0f %% of the squared error" % (K, K_dk, bound, 100 * share),
           flush=True)
     assert max(errs["y"], errs["z"], errs["dv"], errs["dk"]) <= 2e-2
     assert errs["dq"] <= bound
