@@ -441,7 +441,7 @@ constexpr int kFusedWaveLds = 32 * kDsStride + 32 * kKtStride;   // uint16 per w
 
 // WV: waves per workgroup (one workgroup per CU).  Eight, or twelve where the kernel fits 168 registers (three waves
 // per SIMD): d = 32 with one exponential.
-template <int DR, int MT, bool DQ, bool ONE, bool F, int WV = 8>
+template <int DR, int MT, bool DQ, bool ONE, bool F, int WV = 8, bool ZL = false>
 __device__ __forceinline__ void dkdv_body(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const bf16_t *__restrict__ dy, const float *__restrict__ z, const float *__restrict__ lse_enc,
@@ -473,7 +473,15 @@ __device__ __forceinline__ void dkdv_body(
     constexpr int HV = WIDE ? 1 : D / 16;
     constexpr int QUARTS = WIDE ? 4 : 2;        // 4-column pieces per lane and accumulator: columns 8 q + 4 hh (+ 16 hv)
     static_assert(!DQ || DR <= 16, "the fused dQ product is written for d <= 16 (16 output rows)");
-    constexpr int NA = 4 * KS + 1;              // A-type images per latent tile (the last one: corrections)
+    // ZL (DQ at d = 16, shapes with fewer tokens than latents): the c chain carries the lo term of Z as one more image
+    // and product (at d <= 8 it rides in the free upper half of the Z image, ZPACK below).  dQ sums dS over the tokens
+    // of one latent, so the rounding of Z_m adds up coherently there, and on rows whose halves cancel it shows:
+    // mesh-like inputs, 692 latents over 242 tokens, dq_lat 2.4e-2 without it, 1.1e-2 with it (1539 over 427: 2.5e-2
+    // and 7e-3).  It costs 5 % of the kernel's time; random shapes with at least as many tokens as latents stayed
+    // within the bar without it.
+    constexpr bool ZLO = DQ && !pack_dim(DR) && ZL;
+    static_assert(!ZL || (DQ && !pack_dim(DR)), "the extra image is for the fused dQ product at d = 16");
+    constexpr int NA = (ZLO ? 5 : 4) * KS + 1;  // A-type images per latent tile (the last one: corrections)
     constexpr int NR = 4 * HV;                  // row images per latent tile (RW1, RW2) x 2 k-steps
     constexpr int PER_TILE = NA + NR;
     constexpr bool PIPE = (D == 16);            // look one latent tile ahead where registers allow
@@ -790,6 +798,7 @@ __device__ __forceinline__ void dkdv_body(
             for (int ks = 0; ks < KS; ++ks) {
                 av = mfma(image(t, 2 * KS + ks), vt[ks], av);
                 cv = mfma(image(t, 3 * KS + ks), gc[ks], cv);
+                if constexpr (ZLO) cv = mfma(image(t, 4 * KS + ks), gc[ks], cv);
             }
             if constexpr (PIPE) {
                 if (t + 1 < MT) scores(t + 1, s1n, s2n);
@@ -973,12 +982,12 @@ __global__ __launch_bounds__(64 * WV, 1) void bwd_dkdv_mfma_kernel(FLARE_DKDV_PA
 // ... or both in one launch, each workgroup taking the variant that the plan names for its (b,h): one launch less per
 // step (a launch whose workgroups all leave at once still costs 4-6 us).  Both bodies share the kernel's registers,
 // which at one workgroup per CU costs nothing.
-template <int DR, int MT, bool DQ, bool F>
+template <int DR, int MT, bool DQ, bool F, bool ZL = false>
 __global__ __launch_bounds__(512, 1) void bwd_dkdv_planned_kernel(FLARE_DKDV_PARAMS)
 {
     const int bh = grid_pos(ts, H, DR * 2).y;
-    if (plan[bh] != 0) dkdv_body<DR, MT, DQ, true, F, 8>(FLARE_DKDV_PASS);
-    else dkdv_body<DR, MT, DQ, false, F, 8>(FLARE_DKDV_PASS);
+    if (plan[bh] != 0) dkdv_body<DR, MT, DQ, true, F, 8, ZL>(FLARE_DKDV_PASS);
+    else dkdv_body<DR, MT, DQ, false, F, 8, ZL>(FLARE_DKDV_PASS);
 }
 #undef FLARE_DKDV_PASS
 #undef FLARE_DKDV_PARAMS
@@ -1072,7 +1081,10 @@ int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v,
     const int MT = lat_eff(s.M) == 192 ? 8 : lat_eff(s.M) / 32;   // instantiated for 1, 2, 4, 8 tiles
     const int pd = padded_dim(s.d);
     const int KS = pd / 16, HV = (pd == 32) ? 1 : pd / 16;   // d = 32: one 32-row block of row images
-    const size_t lds = (size_t)MT * (4 * KS + 1 + 4 * HV) * 1024 + (fuse ? 8 * kFusedWaveLds * 2 : 0);
+    // dQ from this kernel at d = 16 with fewer tokens than latents: one more image, the lo term of Z (see the kernel)
+    const bool zlo = fuse && s.d == 16 && s.N < s.M;
+    const int na = (zlo ? 5 : 4) * KS + 1;
+    const size_t lds = (size_t)MT * (na + 4 * HV) * 1024 + (fuse ? 8 * kFusedWaveLds * 2 : 0);
     const bf16_t *qq = (const bf16_t *)q, *kk = (const bf16_t *)k, *vv = (const bf16_t *)v, *gg = (const bf16_t *)dy;
     const bool f16 = s.dtype == FLARE_F16;
 #define FLARE_DKDV_LAUNCH(KERN, THREADS)                                                                         \
@@ -1117,6 +1129,20 @@ int mfma_dkdv(const flare_shape &s, const void *q, const void *k, const void *v,
         FLARE_DKDV_MT(4, true)
     } else if (s.d == 8 && fuse) {
         FLARE_DKDV_MT(8, true)
+    } else if (s.d == 16 && fuse && zlo) {
+#define FLARE_DKDV_Z(MTT)                                                                          \
+    do {                                                                                           \
+        if (f16) FLARE_DKDV_LAUNCH((bwd_dkdv_planned_kernel<16, MTT, true, true, true>), 512);     \
+        else FLARE_DKDV_LAUNCH((bwd_dkdv_planned_kernel<16, MTT, true, false, true>), 512);        \
+    } while (0)
+        switch (MT) {
+            case 1: FLARE_DKDV_Z(1); break;
+            case 2: FLARE_DKDV_Z(2); break;
+            case 4: FLARE_DKDV_Z(4); break;
+            case 8: FLARE_DKDV_Z(8); break;
+            default: return FLARE_EUNSUPPORTED;
+        }
+#undef FLARE_DKDV_Z
     } else if (s.d == 16 && fuse) {
         FLARE_DKDV_MT(16, true)
     } else if (s.d == 4) {

@@ -137,23 +137,29 @@ def test_fp32_gradients_meet_the_bar_up_to_their_conditioning(oracle, case):
 
 
 SIXTEEN_BIT_CASES = [
-    dict(dtype="bf16", N=242, M=692, d=16, seed=777 + 7966, layout="bhnd"),     # measured dq_lat 2.39e-2
-    dict(dtype="bf16", N=427, M=1539, d=16, seed=777 + 17910, layout="bnhd"),   # 2.49e-2
-    dict(dtype="f16", N=9, M=1157, d=16, seed=777 + 15775, layout="bhnd"),      # 3.08e-2 (nine tokens)
+    # over the bar in the sweep: measured dq_lat 2.11e-2, 2.16e-2, 2.91e-2
+    dict(dtype="bf16", B=2, H=1, N=12, M=1489, d=16, seed=777 + 2880, layout="bhnd"),
+    dict(dtype="bf16", B=2, H=2, N=185, M=1536, d=16, seed=777 + 7074, layout="bhnd"),
+    dict(dtype="f16", B=1, H=1, N=9, M=1157, d=16, seed=777 + 15775, layout="bhnd"),
+    # 2.39e-2 and 2.49e-2 while the fused kernel carried Z as one bf16 term; with the lo term: 1.14e-2, 6.96e-3
+    dict(dtype="bf16", B=1, H=1, N=242, M=692, d=16, seed=777 + 7966, layout="bhnd"),
+    dict(dtype="bf16", B=1, H=1, N=427, M=1539, d=16, seed=777 + 17910, layout="bnhd"),
 ]
 
 
 @pytest.mark.parametrize("case", SIXTEEN_BIT_CASES, ids=lambda c: "%(dtype)s-N%(N)d-M%(M)d" % c)
 def test_16bit_gradient_of_dominating_latents_within_its_conditioning(oracle, case):
-    """The same conditioning on the matrix cores (16-bit storage, mesh-like inputs, many more latents than tokens; the
-    three cases over the bar of 2e-2 in 20 000 shapes of a random sweep over 257 ... 2048 latents): dq_lat reads
-    2.4e-2 ... 3.1e-2, most of the squared error in a handful of latent rows -- rows whose two halves are each K times
-    their difference.  The weights P and dS enter the matrix products rounded to bf16 (2^-9 relative) whatever the
-    storage type, so the bound the arithmetic meets is 2e-2 + 2^-9 K; every other output is at the plain bar."""
+    """The same conditioning on the matrix cores (16-bit storage, mesh-like inputs, many more latents than tokens: the
+    cases over the bar of 2e-2 in 21 000 shapes of a random sweep over 257 ... 2048 latents, before and after the fused
+    backward kernel got the lo term of Z for such shapes): dq_lat reads up to 2.9e-2, most of the squared error in a
+    handful of latent rows -- rows whose two halves are each K times their difference.  The weights P and dS enter
+    the matrix products rounded to bf16 (2^-9 relative) whatever the storage type, so the bound the arithmetic meets
+    is 2e-2 + 2^-9 K; every other output is at the plain bar."""
     import torch
     c = case
     print("[case] 16-bit conditioning %s" % (c,), flush=True)
-    inp = synth.make_inputs(2, B=1, H=1, N=c["N"], M=c["M"], d=c["d"], dtype=c["dtype"], with_dy=True, seed=c["seed"])
+    inp = synth.make_inputs(2, B=c["B"], H=c["H"], N=c["N"], M=c["M"], d=c["d"], dtype=c["dtype"], with_dy=True,
+                            seed=c["seed"])
     scale = 1.0 / np.sqrt(c["d"])
     dev = to_device(inp)
     conv = (lambda t: t.permute(0, 2, 1, 3).contiguous()) if c["layout"] == "bnhd" else (lambda t: t)
@@ -168,7 +174,10 @@ def test_16bit_gradient_of_dominating_latents_within_its_conditioning(oracle, ca
                 dk=slice_relerr(to_host(back(dk)), dk_ref), dv=slice_relerr(to_host(back(dv)), dv_ref),
                 dq=slice_relerr(to_host(dq), dq_ref))
     K, K_dk = _cancellation_factor(inp["q"], inp["k"], inp["v"], inp["dy"], scale, dq_ref, dk_ref)
-    rows = np.sort(np.sum((to_host(dq)[0].astype(np.float64) - dq_ref[0]) ** 2, axis=1))[::-1]
+    # in the head with the largest error: the part of the squared error that 2 % of the latent rows hold
+    diff = to_host(dq).astype(np.float64) - dq_ref
+    h = int(np.argmax([np.linalg.norm(diff[i]) / np.linalg.norm(dq_ref[i]) for i in range(c["H"])]))
+    rows = np.sort(np.sum(diff[h] ** 2, axis=1))[::-1]
     share = float(rows[:max(5, c["M"] // 50)].sum() / rows.sum())
     bound = 2e-2 + 2.0 ** -9 * K
     print("[case]    " + "  ".join("%s %.2e" % kv for kv in errs.items()) +
