@@ -429,7 +429,8 @@ __global__ __launch_bounds__(256, MINB) void bwd_dq_mfma_kernel(
 // No lo terms of dZ and Z for dK and dV: dZ arrives bf16-exact, and the rounding of Z_m is one error per
 // latent, which the sums of dK_n and dV_n over the latents average out (measured: dK error up by
 // 5-10 %, time down by 9 %) -- unlike in dQ, whose sums run over the tokens of one latent and add that
-// error up coherently (the DQ variant below therefore carries the lo term of Z).
+// error up coherently (the DQ variant below therefore carries the lo term of Z at d <= 8, and at d = 16 where the
+// shape calls for it: ZL).
 // ONE: one exponential per score, as in the dQ kernel: R = P u[m] w[n]; u is folded into the Z images
 // (and into slots 4-6 of the correction image, against -delta in the token operand), w[n] is a
 // per-lane scalar here, and dS' = P (a + w c).  Runs only where plan[bh] = 1.
@@ -458,8 +459,8 @@ __device__ __forceinline__ void dkdv_body(
     // dQ of all 32*MT latents in 8*MT registers.  At the end the eight waves add their partials in a
     // fixed order through LDS and the workgroup writes slot x (its grid position) of dq_part
     // ([(b*h) * gridDim.x + x][Mtot][d], summed and scaled by dq_reduce_kernel).  The c chain
-    // then carries the lo term of Z (dQ sums dS over the tokens of one latent and would add up its
-    // rounding coherently, see the dQ kernel).
+    // then carries the lo term of Z at d <= 8 (ZPACK below) and, with ZL, at d = 16 (dQ sums dS over the tokens of
+    // one latent and adds up its rounding coherently, see the dQ kernel).
     // The kernel works on the latents m0 .. m0 + M of the head's Mtot.  With acc32 given (more than one
     // latent chunk) it adds its dV and dK rows in fp32 to acc32[0][b*h][n][DR] and acc32[1][...] (the
     // chunk with m0 = 0 stores instead); the last chunk adds what is there to its own rows and rounds the
