@@ -29,7 +29,7 @@
  *     elements (d, or H*d for FLARE_BNHD) below 2^32; d in {4, 8, 16, 32}; dtype f32, bf16 or f16;
  *     either flare_layout for the token tensors (every "[B][H][N][d]" below reads [B][N][H][d]
  *     when shape->layout is FLARE_BNHD; the per-token statistic lse_dec is [B][H][N] always).
- *     Shapes with dtype bf16 or f16, M <= 2048 and N >= 8 run on the matrix-core kernels (d < 16 with the
+ *     Shapes with dtype bf16 or f16, M <= 2048 and N >= 16 run on the matrix-core kernels (d < 16 with the
  *     contraction padded to 16; M in tiles of 32 on the geometry of the next of 32, 64, 128, 256
  *     or a multiple of 256, the latents beyond M being padding that is masked; M > 256 in chunks
  *     of 256 latents); everything else runs on the fp32 vector kernels.  On the matrix
@@ -88,7 +88,7 @@ typedef struct {
     int y_f32;           /* 0: y has the element type dtype.  1 (16-bit dtypes with M <= 2048, else
                             FLARE_EUNSUPPORTED): flare_decode / flare_forward write y as fp32 (same layout),
                             and the y handed to flare_backward is that fp32 tensor.  The backward then takes
-                            delta_n = <dY_n, Y_n> from an unrounded Y, so that no shape of 8 tokens or more
+                            delta_n = <dY_n, Y_n> from an unrounded Y, so that no shape of 16 tokens or more
                             needs the recomputation described at flare_backward (at d < 16 that pass is a
                             sixth of the step), at the price of a y of twice the bytes */
     int variant;         /* 0: the library picks its kernels.  Otherwise a set of flare_variant bits that forces
@@ -161,7 +161,7 @@ int flare_forward(const flare_shape *shape, const void *q_lat, const void *k, co
  *   out   [B][N][C] of the storage dtype (rounded once from fp32)                                         (out)
  *   y     [B][N][H][d] dtype, lse_dec [B][H][N] fp32: as flare_decode writes them, or NULL              (out, optional)
  * Supported (else FLARE_EUNSUPPORTED, nothing launched): dtype bf16 or f16, layout FLARE_BNHD, d = 16,
- * H in {2, 4, 8}, M <= 256, N >= 8, y_f32 = 0.  The rows of Y enter the projection rounded to the storage
+ * H in {2, 4, 8}, M <= 256, N >= 16, y_f32 = 0.  The rows of Y enter the projection rounded to the storage
  * dtype, exactly the values a separate flare_decode would have stored.  Needs no workspace.
  * flare_forward_project = flare_encode followed by flare_decode_project on the same stream.
  */
@@ -206,7 +206,7 @@ int flare_forward_static(const flare_shape *shape, const void *q_lat, const void
  *     storage on the matrix-core kernels) and d < 16, or at most 32 tokens, or fewer tokens than latents, they are recomputed in
  *     either case: delta from a y of bf16 accuracy and so few terms would not meet the accuracy of
  *     the rest -- unless shape->y_f32 is set and y is the forward's fp32 output.  (16-bit shapes of
- *     fewer than 8 tokens run on the fp32 kernels throughout, forward and backward: with so few tokens
+ *     fewer than 16 tokens run on the fp32 kernels throughout, forward and backward: with so few tokens
  *     the gradients' differences cancel too far for bf16 operands.)
  *                                                                           (in, optional)
  *   dq_lat [H][M][d] fp32 (summed over the batch), dk, dv [B][H][N][d] dtype (out)

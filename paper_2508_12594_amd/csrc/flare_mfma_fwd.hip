@@ -1064,8 +1064,9 @@ bool mfma_supported(const flare_shape &s)
     if (s.d != 4 && s.d != 8 && s.d != 16 && s.d != 32) return false;   // d < 16 runs padded to 16
     // A handful of tokens: every Z_m lies in the span of those few value rows, so c - delta = <dY_n, Z_m - Y_n>
     // and a - eps cancel almost completely and the bf16 operands' rounding shows in dQ and dK (two tokens,
-    // fp16 storage, d = 16: up to 1.6e-1 measured).  The fp32 kernels take such shapes; they cost nothing there.
-    if (s.N < 8) return false;
+    // fp16 storage, d = 16: up to 1.6e-1 measured; 9 and 12 tokens under more than a thousand latents: 2.1e-2 and 2.9e-2).
+    // The fp32 kernels take such shapes; they cost nothing there.
+    if (s.N < 16) return false;
     return s.M <= 2048;   // any number of latents: tiles of 32, the last ones padded
 }
 

@@ -872,7 +872,7 @@ int backward_impl(const flare_shape &s, const T *q, const T *k, const T *v, cons
     const bool bf16_weights = s.dtype == FLARE_BF16 || (s.dtype == FLARE_F16 && mf);
     const bool coarse_y = s.dtype != FLARE_F32 && ((bf16_weights && s.d < 16) || s.N <= 32 || s.N < s.M) &&
                           !(s.y_f32 && mf);   // an fp32 y is not coarse (the fp32 kernels, which take the
-                                              // 16-bit shapes of fewer than 8 tokens, never read it: they recompute)
+                                              // 16-bit shapes of fewer than 16 tokens, never read it: they recompute)
     const bool saved = y && lse_dec && !coarse_y;
     const bool fused = saved && mf && mfma_dkdv_supported(s);   // every later kernel is a matrix-core one
     const float *ld = fused ? lse_dec : w.lse_dec2;

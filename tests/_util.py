@@ -9,9 +9,9 @@ TOL = {"f32": 1e-5, "bf16": 2e-2, "f16": 1e-3}
 
 
 def on_matrix_cores(dtype, M, N=None):
-    """The library's documented rule: 16-bit storage with at most 2048 latents per head and at least 8
+    """The library's documented rule: 16-bit storage with at most 2048 latents per head and at least 16
     tokens runs on the matrix-core kernels (tiles of 32 latents, the last ones padded)."""
-    return dtype != "f32" and M <= 2048 and (N is None or N >= 8)
+    return dtype != "f32" and M <= 2048 and (N is None or N >= 16)
 
 
 def tol_for(inp):

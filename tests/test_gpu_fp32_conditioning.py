@@ -137,9 +137,10 @@ def test_fp32_gradients_meet_the_bar_up_to_their_conditioning(oracle, case):
 
 
 SIXTEEN_BIT_CASES = [
-    # over the bar in the sweep: measured dq_lat 2.11e-2, 2.16e-2, 2.91e-2
-    dict(dtype="bf16", B=2, H=1, N=12, M=1489, d=16, seed=777 + 2880, layout="bhnd"),
+    # over the bar in the sweep: measured dq_lat 2.16e-2
     dict(dtype="bf16", B=2, H=2, N=185, M=1536, d=16, seed=777 + 7074, layout="bhnd"),
+    # 2.11e-2 and 2.91e-2 on the matrix cores; shapes of fewer than 16 tokens run on the fp32 kernels since: 5e-6, 6e-6
+    dict(dtype="bf16", B=2, H=1, N=12, M=1489, d=16, seed=777 + 2880, layout="bhnd"),
     dict(dtype="f16", B=1, H=1, N=9, M=1157, d=16, seed=777 + 15775, layout="bhnd"),
     # 2.39e-2 and 2.49e-2 while the fused kernel carried Z as one bf16 term; with the lo term: 1.14e-2, 6.96e-3
     dict(dtype="bf16", B=1, H=1, N=242, M=692, d=16, seed=777 + 7966, layout="bhnd"),
@@ -151,8 +152,9 @@ SIXTEEN_BIT_CASES = [
 def test_16bit_gradient_of_dominating_latents_within_its_conditioning(oracle, case):
     """The same conditioning on the matrix cores (16-bit storage, mesh-like inputs, many more latents than tokens: the
     cases over the bar of 2e-2 in 21 000 shapes of a random sweep over 257 ... 2048 latents, before and after the fused
-    backward kernel got the lo term of Z for such shapes): dq_lat reads up to 2.9e-2, most of the squared error in a
-    handful of latent rows -- rows whose two halves are each K times their difference.  The weights P and dS enter
+    backward kernel got the lo term of Z for such shapes and shapes of 8 ... 15 tokens went to the fp32 kernels):
+    dq_lat read up to 2.9e-2, now 2.2e-2 on one of them, most of the squared error in a handful of latent rows --
+    rows whose two halves are each K times their difference.  The weights P and dS enter
     the matrix products rounded to bf16 (2^-9 relative) whatever the storage type, so the bound the arithmetic meets
     is 2e-2 + 2^-9 K; every other output is at the plain bar."""
     import torch

@@ -24,7 +24,7 @@ CASES = [
     ("bf16", 3, 4, 777, 64, True),
     ("f16", 1, 8, 1500, 96, True),        # padded latent tiles, fp16 products
     ("bf16", 2, 2, 100, 32, False),
-    ("bf16", 1, 8, 9, 200, True),         # one ragged tile, 56 padding latents
+    ("bf16", 1, 8, 19, 200, True),        # one ragged tile, 56 padding latents
 ]
 
 

@@ -25,7 +25,7 @@ CASES = [
     ("f16", 1, 3, 900, 128, 8, "bhnd"),
     ("bf16", 1, 2, 600, 512, 16, "bhnd"),      # two latent chunks
     ("bf16", 3, 2, 333, 192, 4, "bnhd"),       # dK/dV on the vector kernels
-    ("bf16", 2, 3, 5, 96, 16, "bnhd"),         # fewer than 8 tokens: 16-bit storage on the fp32 kernels
+    ("bf16", 2, 3, 5, 96, 16, "bnhd"),         # fewer than 16 tokens: 16-bit storage on the fp32 kernels
     ("f16", 3, 2, 3, 40, 8, "bhnd"),
 ]
 

@@ -27,7 +27,7 @@ CASES = [
     # fp16 storage at d = 16: delta comes from a pass of its own, which must round dY to bf16 as the kernels do
     (2, dict(B=1, H=1, N=12, M=234, d=16, dtype="f16", seed=777 + 542), "bhnd"),
     (3, dict(B=1, N=333, M=234, d=16, dtype="f16"), "bnhd"),
-    # fewer than 8 tokens: the fp32 kernels write the fp32 y, the backward recomputes the statistics
+    # fewer than 16 tokens: the fp32 kernels write the fp32 y, the backward recomputes the statistics
     (2, dict(B=1, H=1, N=2, M=234, d=16, dtype="f16", seed=777 + 542), "bhnd"),
     (2, dict(B=2, H=3, N=5, M=96, d=8), "bnhd"),
     (1, dict(B=1, H=2, N=7, M=300, d=32, dtype="f16"), "bhnd"),
