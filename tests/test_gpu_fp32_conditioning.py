@@ -145,6 +145,9 @@ SIXTEEN_BIT_CASES = [
     # 2.39e-2 and 2.49e-2 while the fused kernel carried Z as one bf16 term; with the lo term: 1.14e-2, 6.96e-3
     dict(dtype="bf16", B=1, H=1, N=242, M=692, d=16, seed=777 + 7966, layout="bhnd"),
     dict(dtype="bf16", B=1, H=1, N=427, M=1539, d=16, seed=777 + 17910, layout="bnhd"),
+    # delta from the forward's saved bf16 y (1990 tokens, 192 latents; one case in 30 000 of the general sweep): 2.40e-2,
+    # five rows hold 91 % of the squared error; 3.9e-3 with the statistics recomputed (or with the fp32 y)
+    dict(dtype="bf16", B=1, H=1, N=1990, M=192, d=16, seed=777 + 50548, layout="bhnd", saved=True),
 ]
 
 
@@ -167,8 +170,11 @@ def test_16bit_gradient_of_dominating_latents_within_its_conditioning(oracle, ca
     conv = (lambda t: t.permute(0, 2, 1, 3).contiguous()) if c["layout"] == "bnhd" else (lambda t: t)
     back = (lambda t: t.permute(0, 2, 1, 3)) if c["layout"] == "bnhd" else (lambda t: t)
     k, v, dy = conv(dev["k"]), conv(dev["v"]), conv(dev["dy"])
-    y, z, lse = binding.forward(dev["q"], k, v, scale, layout=c["layout"])
-    dq, dk, dv = binding.backward(dev["q"], k, v, dy, z, lse, scale, layout=c["layout"])
+    saved = c.get("saved", False)
+    lse_dec = torch.empty((c["B"], c["H"], c["N"]), dtype=torch.float32, device="cuda") if saved else None
+    y, z, lse = binding.forward(dev["q"], k, v, scale, lse_dec=lse_dec, layout=c["layout"])
+    dq, dk, dv = binding.backward(dev["q"], k, v, dy, z, lse, scale, y=y if saved else None, lse_dec=lse_dec,
+                                  layout=c["layout"])
     torch.cuda.synchronize()
     y_ref, z_ref, _ = oracle.forward(inp["q"], inp["k"], inp["v"], scale)
     dq_ref, dk_ref, dv_ref = oracle.backward(inp["q"], inp["k"], inp["v"], inp["dy"], scale)
