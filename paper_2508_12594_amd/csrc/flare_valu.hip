@@ -240,19 +240,30 @@ __global__ __launch_bounds__(256) void encode_merge_kernel(
     float gm = -INFINITY, l = 0.f, o[D];
 #pragma unroll
     for (int i = 0; i < D; ++i) o[i] = 0.f;
-    for (int p = j; p < parts; p += 16) {
-        const size_t slot = ((size_t)bh * parts + p) * M + mm;
-        const float mp = m_part[slot];
-        if (mp == -INFINITY) continue;
-        const float ng = fmaxf(gm, mp);
-        const float wa = fast_exp2(gm - ng);          // gm = -inf on the first live slot: weight 0
-        const float wb = fast_exp2(mp - ng);
-        float oc[D];
-        load_row<D>(o_part + slot * D, oc);
-        l = l * wa + l_part[slot] * wb;
+    // four slots at a time: their loads are all issued before the first is folded (one memory latency per
+    // batch instead of two per slot); the folds keep the slot order
+    constexpr int kBatch = 4;
+    for (int p0 = j; p0 < parts; p0 += 16 * kBatch) {
+        float mp[kBatch], lp[kBatch], oc[kBatch][D];
 #pragma unroll
-        for (int i = 0; i < D; ++i) o[i] = o[i] * wa + oc[i] * wb;
-        gm = ng;
+        for (int b = 0; b < kBatch; ++b) {
+            const int p = p0 + 16 * b;
+            const size_t slot = ((size_t)bh * parts + min(p, parts - 1)) * M + mm;
+            mp[b] = p < parts ? m_part[slot] : -INFINITY;
+            lp[b] = l_part[slot];
+            load_row<D>(o_part + slot * D, oc[b]);
+        }
+#pragma unroll
+        for (int b = 0; b < kBatch; ++b) {
+            if (mp[b] == -INFINITY) continue;          // an empty slot (or none): contributes nothing
+            const float ng = fmaxf(gm, mp[b]);
+            const float wa = fast_exp2(gm - ng);          // gm = -inf on the first live slot: weight 0
+            const float wb = fast_exp2(mp[b] - ng);
+            l = l * wa + lp[b] * wb;
+#pragma unroll
+            for (int i = 0; i < D; ++i) o[i] = o[i] * wa + oc[b][i] * wb;
+            gm = ng;
+        }
     }
 #pragma unroll
     for (int off = 1; off < 16; off <<= 1) {
@@ -505,12 +516,23 @@ __device__ __forceinline__ void sum_slots(const float *__restrict__ part, int ou
 #pragma unroll
     for (int i = 0; i < D; ++i) acc[i] = 0.f;
     const int total = groups * inner;
-    for (int s = j; s < total; s += 16) {
-        const size_t slot = ((size_t)(s / inner) * n_outer + outer) * inner + (s % inner);
-        float t[D];
-        load_row<D>(part + (slot * M + m) * D, t);
+    // four slots at a time: their loads are all issued before the first is added; the sums keep the slot order
+    constexpr int kBatch = 4;
+    for (int s0 = j; s0 < total; s0 += 16 * kBatch) {
+        float t[kBatch][D];
 #pragma unroll
-        for (int i = 0; i < D; ++i) acc[i] += t[i];
+        for (int b = 0; b < kBatch; ++b) {
+            const int s = min(s0 + 16 * b, total - 1);
+            const size_t slot = ((size_t)(s / inner) * n_outer + outer) * inner + (s % inner);
+            load_row<D>(part + (slot * M + m) * D, t[b]);
+        }
+#pragma unroll
+        for (int b = 0; b < kBatch; ++b) {
+            if (s0 + 16 * b < total) {
+#pragma unroll
+                for (int i = 0; i < D; ++i) acc[i] += t[b][i];
+            }
+        }
     }
 #pragma unroll
     for (int off = 1; off < 16; off <<= 1) {
