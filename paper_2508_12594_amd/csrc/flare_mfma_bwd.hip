@@ -478,8 +478,8 @@ __device__ __forceinline__ void dkdv_body(
     // and product (at d <= 8 it rides in the free upper half of the Z image, ZPACK below).  dQ sums dS over the tokens
     // of one latent, so the rounding of Z_m adds up coherently there, and on rows whose halves cancel it shows:
     // mesh-like inputs, 692 latents over 242 tokens, dq_lat 2.4e-2 without it, 1.1e-2 with it (1539 over 427: 2.5e-2
-    // and 7e-3).  It costs 5 % of the kernel's time; random shapes with at least as many tokens as latents stayed
-    // within the bar without it.
+    // and 7e-3).  It costs 5 % of the kernel's time; of the random shapes with at least as many tokens as latents one
+    // in 30 000 left the bar, and that one for another reason (delta from the saved bf16 y), the lo term or not.
     constexpr bool ZLO = DQ && !pack_dim(DR) && ZL;
     static_assert(!ZL || (DQ && !pack_dim(DR)), "the extra image is for the fused dQ product at d = 16");
     constexpr int NA = (ZLO ? 5 : 4) * KS + 1;  // A-type images per latent tile (the last one: corrections)
